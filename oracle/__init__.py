@@ -1,0 +1,201 @@
+"""CPU oracle for xKV Selective-Reconstruction decode (test infrastructure).
+
+Thin ctypes wrapper around ``xkv_oracle.c`` (plain C, double precision).  Only
+``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg
+may import this package; the GPU library never does and shares no code with it.
+
+Inputs may be float64, float32 or bf16 (given as ``uint16`` bit patterns); they
+are widened to float64 exactly before the C code sees them.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "xkv_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  Returns the path of the shared library."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fvisibility=hidden", "-shared", "-fPIC",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        _lib.oracle_compression_ratio.restype = ctypes.c_double
+        _lib.oracle_compression_ratio.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                  ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    return _lib
+
+
+def widen(x) -> np.ndarray:
+    """Exact widening to float64: float arrays as they are, uint16 taken as bf16 bits."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        x = (x.astype(np.uint32) << 16).view(np.float32)
+    return np.ascontiguousarray(x, dtype=np.float64)
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _ip(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _fp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def default_scale(d_h: int) -> float:
+    return 1.0 / float(np.sqrt(np.float64(d_h)))
+
+
+def project(B_k, q, H_kv):
+    """p[H_q][r_k] = B^K_{l,rho(h)} q_h (step 1)."""
+    B_k, q = widen(B_k), widen(q)
+    r_k, d = B_k.shape
+    H_q, d_h = q.shape
+    assert d == H_kv * d_h and H_q % H_kv == 0
+    p = np.empty((H_q, r_k), np.float64)
+    _load().oracle_project(_dp(B_k), _dp(q), r_k, H_kv, H_q, d_h, _dp(p))
+    return p
+
+
+def scores(A_k, p, scale):
+    """s[H_q][L] = scale * A^K p_h (step 2)."""
+    A_k, p = widen(A_k), widen(p)
+    L, r_k = A_k.shape
+    H_q = p.shape[0]
+    assert p.shape[1] == r_k
+    s = np.empty((H_q, L), np.float64)
+    _load().oracle_scores(_dp(A_k), _dp(p), L, r_k, H_q, ctypes.c_double(scale), _dp(s))
+    return s
+
+
+def pool(s, H_kv):
+    """S[H_kv][L] = max over the query heads of each KV head (step 3)."""
+    s = widen(s)
+    H_q, L = s.shape
+    assert H_q % H_kv == 0
+    S = np.empty((H_kv, L), np.float64)
+    _load().oracle_pool(_dp(s), L, H_kv, H_q, _dp(S))
+    return S
+
+
+def pooled_scores(A_k, B_k, q, H_kv, scale=None):
+    """Steps 1-3: pooled fp64 scores S[H_kv][L]."""
+    q = widen(q)
+    scale = default_scale(q.shape[1]) if scale is None else scale
+    return pool(scores(A_k, project(B_k, q, H_kv), scale), H_kv)
+
+
+def select(S_row, k):
+    """Step 4 on one fp32 score row: the k selected indices, ascending."""
+    S_row = np.ascontiguousarray(S_row, dtype=np.float32)
+    assert S_row.ndim == 1
+    idx = np.empty((k,), np.int32)
+    rc = _load().oracle_select(_fp(S_row), S_row.shape[0], k, _ip(idx))
+    if rc != 0:
+        raise ValueError(f"oracle_select failed ({rc})")
+    return idx
+
+
+def reconstruct(A, B):
+    """Dense reconstruction X^ = A B."""
+    A, B = widen(A), widen(B)
+    L, r = A.shape
+    assert B.shape[0] == r
+    d = B.shape[1]
+    X = np.empty((L, d), np.float64)
+    _load().oracle_reconstruct(_dp(A), _dp(B), L, r, d, _dp(X))
+    return X
+
+
+def gather_attend(A_k, A_v, B_k, B_v, q, idx, scale=None):
+    """Steps 5-6 for given index sets idx[H_kv][k]: out[H_q][d_h]."""
+    A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    L, r_k = A_k.shape
+    r_v = A_v.shape[1]
+    H_q, d_h = q.shape
+    H_kv, k = idx.shape
+    assert B_k.shape == (r_k, H_kv * d_h) and B_v.shape == (r_v, H_kv * d_h) and A_v.shape[0] == L
+    scale = default_scale(d_h) if scale is None else scale
+    out = np.empty((H_q, d_h), np.float64)
+    rc = _load().oracle_gather_attend(_dp(A_k), _dp(A_v), _dp(B_k), _dp(B_v), _dp(q), _ip(idx),
+                                      L, r_k, r_v, H_kv, H_q, d_h, k, ctypes.c_double(scale), _dp(out))
+    if rc != 0:
+        raise ValueError(f"oracle_gather_attend failed ({rc})")
+    return out
+
+
+def dense(K, V, q, H_kv, scale=None):
+    """Textbook decode attention, K and V as [L][H_kv*d_h]: out[H_q][d_h]."""
+    K, V, q = widen(K), widen(V), widen(q)
+    L, d = K.shape
+    H_q, d_h = q.shape
+    assert d == H_kv * d_h and V.shape == K.shape
+    scale = default_scale(d_h) if scale is None else scale
+    out = np.empty((H_q, d_h), np.float64)
+    rc = _load().oracle_dense(_dp(K), _dp(V), _dp(q), L, H_kv, H_q, d_h, ctypes.c_double(scale), _dp(out))
+    if rc != 0:
+        raise ValueError(f"oracle_dense failed ({rc})")
+    return out
+
+
+def sr_decode(A_k, A_v, B_k, B_v, q, H_kv, k, scale=None):
+    """Whole SR step (steps 1-6).  Returns (out[H_q][d_h], idx[H_kv][k], S32[H_kv][L])."""
+    A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
+    L, r_k = A_k.shape
+    r_v = A_v.shape[1]
+    H_q, d_h = q.shape
+    scale = default_scale(d_h) if scale is None else scale
+    out = np.empty((H_q, d_h), np.float64)
+    idx = np.empty((H_kv, k), np.int32)
+    S32 = np.empty((H_kv, L), np.float32)
+    rc = _load().oracle_sr_decode(_dp(A_k), _dp(A_v), _dp(B_k), _dp(B_v), _dp(q), L, r_k, r_v, H_kv, H_q, d_h,
+                                  k, ctypes.c_double(scale), _dp(out), _ip(idx), _fp(S32))
+    if rc != 0:
+        raise ValueError(f"oracle_sr_decode failed ({rc})")
+    return out, idx, S32
+
+
+def factorize(X_cat, r):
+    """Eq. 1: (A[L][r], B[r][n], sigma[n]) with A = U Sigma, B = V_r^T."""
+    X = widen(X_cat)
+    L, n = X.shape
+    A = np.empty((L, r), np.float64)
+    B = np.empty((r, n), np.float64)
+    sigma = np.empty((n,), np.float64)
+    rc = _load().oracle_factorize(_dp(X), L, n, r, _dp(A), _dp(B), _dp(sigma))
+    if rc != 0:
+        raise ValueError(f"oracle_factorize failed ({rc})")
+    return A, B, sigma
+
+
+_RATIO = {"C_K": 0, "C_V": 1, "xKV": 2, "xK-SR-gpu": 3, "xK-SR-total": 4, "xKV-SR": 5}
+
+
+def compression_ratio(which, N, W, d, L, r_k, r_v=0, c=0):
+    """Closed-form compression ratios of App. C.6."""
+    return float(_load().oracle_compression_ratio(_RATIO[which], N, W, d, float(L), r_k, r_v, c))
