@@ -1,0 +1,133 @@
+/*
+ * xkv.h -- C ABI of libxkv: xKV Selective-Reconstruction (SR) decode attention over a
+ * cross-layer factorized KV cache, hand-written for AMD MI355X (gfx950), one GPU.
+ *
+ * Method (arXiv 2503.18893): a group of G adjacent layers stores its key cache as
+ * K_l ~= A^K B^K_l and its value cache as V_l ~= A^V B^V_l, with the token bases
+ * A^K [L][r_k], A^V [L][r_v] shared by the group and one small reconstruction matrix
+ * B_l [r][d] per layer, d = H_kv * d_h (Sec. 3.1, Eq. 1-2; App. C.6 "Setup").  A decode
+ * step of layer l scores every token from the factors, pools the scores of the query
+ * heads of each KV head, picks the k best tokens per KV head, reconstructs only those
+ * rows (Sec. 3.2, Eq. 3) and runs softmax attention over them.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller (row-major, contiguous,
+ *     16-byte aligned).  `shape` and `bytes` are HOST pointers.  `hip_stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls validate on the host, enqueue kernels on the stream and return; they do not
+ *     allocate, free or synchronise.  Inputs are read-only.  `workspace` is scratch of
+ *     at least xkv_workspace_bytes() bytes (256-byte aligned); no state is carried
+ *     between calls; two calls in flight at once need two workspaces.
+ *   - Errors are returned, never thrown: XKV_ERR_INVALID_ARG for a bad shape or a null
+ *     required pointer (nothing is launched), XKV_ERR_WORKSPACE for a workspace that is
+ *     too small, XKV_ERR_UNSUPPORTED for a shape no kernel handles, XKV_ERR_HIP when a
+ *     launch fails.
+ *   - GQA map: rho(h) = h / (H_q / H_kv) (contiguous groups of query heads).
+ *   - dtype is the element type of A, B, q, K, V and out; all accumulation is fp32;
+ *     scores are fp32 and indices int32.  Inputs must be finite.
+ *   - Layouts: A_k [batch][L][r_k], A_v [batch][L][r_v], B_k [batch][G][r_k][H_kv*d_h],
+ *     B_v [batch][G][r_v][H_kv*d_h] (KV head g = columns g*d_h .. g*d_h+d_h-1),
+ *     q/out [batch][H_q][d_h], pooled scores [batch][H_kv][L], idx [batch][H_kv][k],
+ *     dense K/V [batch][H_kv][L][d_h].
+ */
+#ifndef XKV_H
+#define XKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define XKV_API __attribute__((visibility("default")))
+
+typedef enum {
+    XKV_OK = 0,
+    XKV_ERR_INVALID_ARG = -1,
+    XKV_ERR_UNSUPPORTED = -2,
+    XKV_ERR_WORKSPACE = -3,
+    XKV_ERR_HIP = -4
+} xkv_status;
+
+typedef enum { XKV_F32 = 0, XKV_BF16 = 1 } xkv_dtype;
+
+typedef struct xkv_shape {
+    int32_t G;     /* layers per group (the paper's window size W, Sec. 3.1)          */
+    int32_t H_kv;  /* KV heads                                                        */
+    int32_t H_q;   /* query heads, a multiple of H_kv                                 */
+    int32_t d_h;   /* per-head width (<= 256)                                         */
+    int32_t r_k;   /* rank of the key token basis A^K                                 */
+    int32_t r_v;   /* rank of the value token basis A^V (App. C.6 allows r_k != r_v)  */
+    int32_t L;     /* tokens in the compressed context                                */
+    int32_t k;     /* tokens selected per KV head, 1 <= k <= L                        */
+    int32_t batch; /* independent sequences                                           */
+    int32_t dtype; /* xkv_dtype                                                       */
+    float scale;   /* logit scale, > 0; 0 means 1/sqrt(d_h) (App. B.1, Alg. 2)        */
+} xkv_shape;
+
+/* Bytes of scratch any entry point below needs for this shape (host call, no GPU work). */
+XKV_API xkv_status xkv_workspace_bytes(const xkv_shape *shape, size_t *bytes);
+
+/*
+ * One SR decode step of one layer for every sequence of the batch (Sec. 3.2, Eq. 3, with
+ * the scoring, GQA max-pooling and per-KV-head ArgTopK of App. B.1 Alg. 2 applied per
+ * token to scores computed from the factors):
+ *   p_h = B^K_{l,rho(h)} q_h;  s[h,t] = scale * A^K[t,:] . p_h;  S[g,t] = max_{rho(h)=g} s[h,t];
+ *   I_g = the k tokens with the largest S[g,.] (ties: smaller index first);
+ *   K^_g = A^K[I_g,:] B^K_{l,g},  V^_g = A^V[I_g,:] B^V_{l,g};
+ *   out_h = softmax(scale * K^_{rho(h)} q_h)^T V^_{rho(h)}.
+ * layer_in_group in [0, G) picks B_k[:, layer_in_group], B_v[:, layer_in_group].
+ * idx_out (nullable) receives the selected token ids, ascending per KV head;
+ * score_out (nullable) receives the pooled fp32 scores S.
+ */
+XKV_API xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer_in_group,
+                                 const void *A_k, const void *A_v, const void *B_k, const void *B_v,
+                                 const void *q, void *out, int32_t *idx_out, float *score_out,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Dense decode attention on an uncompressed cache, the speedup baseline (Sec. 5, "Full
+ * Attention"): out_h = softmax(scale * K_{rho(h)} q_h)^T V_{rho(h)} over all L tokens.
+ * K, V: [batch][H_kv][L][d_h].  shape->r_k, r_v, k, G are ignored.
+ */
+XKV_API xkv_status xkv_dense_decode(const xkv_shape *shape, const void *K, const void *V, const void *q,
+                                    void *out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Stage 1 of xkv_sr_decode on its own: pooled scores S [batch][H_kv][L] (fp32) from the
+ * key factors and the queries (query projection, low-rank score stream, GQA max-pool). */
+XKV_API xkv_status xkv_score(const xkv_shape *shape, int32_t layer_in_group, const void *A_k, const void *B_k,
+                             const void *q, float *score_out, void *workspace, size_t workspace_bytes,
+                             void *hip_stream);
+
+/* Stage 2 on its own: per-row ArgTopK (App. B.1 Alg. 2, top-k step) of ANY finite fp32 array
+ * score [batch][H_kv][L] -> idx_out [batch][H_kv][k].  Order: value descending under the
+ * IEEE bit-pattern order (-0.0 < +0.0), ties broken towards the smaller index; exactly k
+ * distinct ids per row, written in ascending id order; bit-exact and deterministic. */
+XKV_API xkv_status xkv_topk(const xkv_shape *shape, const float *score, int32_t *idx_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+/* Stages 3-4 on their own: reconstruct the rows idx [batch][H_kv][k] of K and V (Eq. 3)
+ * and attend over them.  Ids must lie in [0, L); they need not be sorted or distinct. */
+XKV_API xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                     const void *A_v, const void *B_k, const void *B_v, const void *q,
+                                     const int32_t *idx, void *out, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+
+/* Dense reconstruction X^_l = A B_l for all L tokens (Sec. 3.2), written head-major as
+ * X_out [batch][H_kv][L][d_h] in shape->dtype (accumulated in fp32, rounded once).  A is
+ * [batch][L][r], B is [batch][G][r][H_kv*d_h]; r is given explicitly so the same call serves
+ * keys and values.  Used to build the dense baseline's cache from the factors. */
+XKV_API xkv_status xkv_reconstruct(const xkv_shape *shape, int32_t layer_in_group, const void *A, const void *B,
+                                   int32_t r, void *X_out, void *hip_stream);
+
+/* Human-readable name of a status code (static storage). */
+XKV_API const char *xkv_status_string(xkv_status status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+XKV_API int32_t xkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XKV_H */

@@ -1,0 +1,157 @@
+"""Thin Python binding of libxkv's C ABI: argument marshalling only.
+
+Every function has the name and argument order of its C entry point (include/xkv.h) and takes
+torch tensors for device memory; the stream is torch's current stream unless one is given.
+There is no CPU fallback: if the HIP library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libxkv.so")
+
+XKV_OK, XKV_ERR_INVALID_ARG, XKV_ERR_UNSUPPORTED, XKV_ERR_WORKSPACE, XKV_ERR_HIP = 0, -1, -2, -3, -4
+XKV_F32, XKV_BF16 = 0, 1
+DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
+
+ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_dense_decode", "xkv_score", "xkv_topk",
+                "xkv_gather_attend", "xkv_reconstruct", "xkv_status_string", "xkv_version")
+
+
+class XkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where} failed: {status_string(status)} ({status})")
+
+
+class xkv_shape(ctypes.Structure):
+    _fields_ = [("G", ctypes.c_int32), ("H_kv", ctypes.c_int32), ("H_q", ctypes.c_int32), ("d_h", ctypes.c_int32),
+                ("r_k", ctypes.c_int32), ("r_v", ctypes.c_int32), ("L", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("batch", ctypes.c_int32), ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+@dataclass(frozen=True)
+class Shape:
+    G: int
+    H_kv: int
+    H_q: int
+    d_h: int
+    r_k: int
+    r_v: int
+    L: int
+    k: int
+    batch: int
+    dtype: str = "bf16"
+    scale: float = 0.0
+
+    def c(self) -> xkv_shape:
+        return xkv_shape(self.G, self.H_kv, self.H_q, self.d_h, self.r_k, self.r_v, self.L, self.k, self.batch,
+                         DTYPES[self.dtype], self.scale)
+
+    @staticmethod
+    def of(w, **kw) -> "Shape":
+        """From a synth.Workload (or anything with the same field names)."""
+        f = dict(G=w.G, H_kv=w.H_kv, H_q=w.H_q, d_h=w.d_h, r_k=w.r_k, r_v=w.r_v, L=w.L, k=w.k, batch=w.batch,
+                 dtype=w.dtype)
+        f.update(kw)
+        return Shape(**f)
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libxkv.so (built in-tree by build.build_library()).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2503_18893_amd.build` "
+                               "(or __graft_entry__.build()); there is no fallback path")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        sp = ctypes.POINTER(xkv_shape)
+        lib.xkv_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
+        lib.xkv_sr_decode.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_dense_decode.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_score.argtypes = [sp, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_topk.argtypes = [sp, vp, vp, vp, sz, vp]
+        lib.xkv_gather_attend.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_reconstruct.argtypes = [sp, i32, vp, vp, i32, vp, vp]
+        lib.xkv_status_string.argtypes = [ctypes.c_int]
+        lib.xkv_status_string.restype = ctypes.c_char_p
+        lib.xkv_version.restype = i32
+        for name in ENTRY_POINTS[:7]:
+            getattr(lib, name).restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().xkv_status_string(int(status)).decode()
+
+
+def xkv_version() -> int:
+    return int(load().xkv_version())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return ctypes.c_void_p(int(stream))
+
+
+def _check(status: int, where: str):
+    if status != XKV_OK:
+        raise XkvError(status, where)
+
+
+def xkv_workspace_bytes(shape: Shape) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().xkv_workspace_bytes(ctypes.byref(shape.c()), ctypes.byref(n)), "xkv_workspace_bytes")
+    return int(n.value)
+
+
+def alloc_workspace(shape: Shape, device="cuda"):
+    """A torch byte tensor large enough for any entry point at this shape (256-byte aligned by torch)."""
+    import torch
+    return torch.empty(max(xkv_workspace_bytes(shape), 256), dtype=torch.uint8, device=device)
+
+
+def xkv_sr_decode(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, idx_out, score_out, workspace, stream=None):
+    _check(load().xkv_sr_decode(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k), _ptr(B_v),
+                                _ptr(q), _ptr(out), _ptr(idx_out), _ptr(score_out), _ptr(workspace),
+                                workspace.numel(), _stream(stream)), "xkv_sr_decode")
+
+
+def xkv_dense_decode(shape, K, V, q, out, workspace, stream=None):
+    _check(load().xkv_dense_decode(ctypes.byref(shape.c()), _ptr(K), _ptr(V), _ptr(q), _ptr(out), _ptr(workspace),
+                                   workspace.numel(), _stream(stream)), "xkv_dense_decode")
+
+
+def xkv_score(shape, layer_in_group, A_k, B_k, q, score_out, workspace, stream=None):
+    _check(load().xkv_score(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(B_k), _ptr(q), _ptr(score_out),
+                            _ptr(workspace), workspace.numel(), _stream(stream)), "xkv_score")
+
+
+def xkv_topk(shape, score, idx_out, workspace, stream=None):
+    _check(load().xkv_topk(ctypes.byref(shape.c()), _ptr(score), _ptr(idx_out), _ptr(workspace), workspace.numel(),
+                           _stream(stream)), "xkv_topk")
+
+
+def xkv_gather_attend(shape, layer_in_group, A_k, A_v, B_k, B_v, q, idx, out, workspace, stream=None):
+    _check(load().xkv_gather_attend(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
+                                    _ptr(B_v), _ptr(q), _ptr(idx), _ptr(out), _ptr(workspace), workspace.numel(),
+                                    _stream(stream)), "xkv_gather_attend")
+
+
+def xkv_reconstruct(shape, layer_in_group, A, B, r, X_out, stream=None):
+    _check(load().xkv_reconstruct(ctypes.byref(shape.c()), layer_in_group, _ptr(A), _ptr(B), r, _ptr(X_out),
+                                  _stream(stream)), "xkv_reconstruct")

@@ -1,0 +1,215 @@
+// C ABI of libxkv: argument validation, workspace carving and launch sequencing.
+// Every step of the path runs in the HIP kernels of this library; nothing here computes.
+#include <cmath>
+#include <cstring>
+
+#include "xkv_common.h"
+
+namespace xkv {
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+static xkv_status validate(const xkv_shape *s)
+{
+    if (!s) return XKV_ERR_INVALID_ARG;
+    if (s->G < 1 || s->H_kv < 1 || s->H_q < 1 || s->d_h < 1 || s->r_k < 1 || s->r_v < 1 || s->L < 1 || s->batch < 0)
+        return XKV_ERR_INVALID_ARG;
+    if (s->H_q % s->H_kv != 0) return XKV_ERR_INVALID_ARG;
+    if (s->k < 1 || s->k > s->L) return XKV_ERR_INVALID_ARG;
+    if (s->dtype != XKV_F32 && s->dtype != XKV_BF16) return XKV_ERR_INVALID_ARG;
+    if (!(s->scale >= 0.0f) || !std::isfinite(s->scale)) return XKV_ERR_INVALID_ARG;
+    if (s->d_h > 256) return XKV_ERR_UNSUPPORTED;
+    if (s->H_q / s->H_kv > 16) return XKV_ERR_UNSUPPORTED;
+    if ((long long)s->batch * s->H_kv > 65535LL) return XKV_ERR_UNSUPPORTED;  // grid.y limit
+    return XKV_OK;
+}
+
+xkv_status make_plan(const xkv_shape &s, Plan &p)
+{
+    std::memset(&p, 0, sizeof p);
+    p.n_rep = s.H_q / s.H_kv;
+    p.rows = s.batch * s.H_kv;
+    p.scale = s.scale > 0.0f ? s.scale : 1.0f / std::sqrt((float)s.d_h);
+    const int rows = p.rows > 0 ? p.rows : 1;
+    const int want = ceil_div(1024, rows);  // aim at ~4 workgroups per compute unit
+
+    int chunks = clampi(want, 1, clampi(ceil_div(s.L, 2048), 1, 64));
+    p.topk_chunk = ceil_div(ceil_div(s.L, chunks), 256) * 256;
+    p.topk_chunks = ceil_div(s.L, p.topk_chunk);
+
+    int splits = clampi(want, 1, clampi(ceil_div(s.k, 64), 1, 64));
+    p.sr_chunk = ceil_div(ceil_div(s.k, splits), 64) * 64;
+    p.sr_splits = ceil_div(s.k, p.sr_chunk);
+
+    splits = clampi(want, 1, clampi(ceil_div(s.L, 256), 1, 128));
+    p.dense_chunk = ceil_div(ceil_div(s.L, splits), 64) * 64;
+    p.dense_splits = ceil_div(s.L, p.dense_chunk);
+
+    p.max_splits = 4 * (p.sr_splits > p.dense_splits ? p.sr_splits : p.dense_splits);  // one partial per wavefront
+
+    const size_t b = (size_t)(s.batch > 0 ? s.batch : 1);
+    size_t off = 0;
+    p.off_p = off;
+    off = align_up(off + b * (size_t)(s.H_q + 32) * s.r_k * sizeof(float), 256);
+    p.off_score = off;
+    off = align_up(off + b * s.H_kv * (size_t)s.L * sizeof(float), 256);
+    p.off_idx = off;
+    off = align_up(off + b * s.H_kv * (size_t)s.k * sizeof(int32_t), 256);
+    p.off_hist = off;
+    off = align_up(off + (size_t)rows * p.topk_chunks * kTopkLevels * kTopkBins * sizeof(uint32_t), 256);
+    p.off_state = off;
+    off = align_up(off + (size_t)rows * kStateWords * sizeof(uint32_t), 256);
+    p.off_part_o = off;
+    off = align_up(off + b * s.H_q * (size_t)p.max_splits * s.d_h * sizeof(float), 256);
+    p.off_part_ml = off;
+    off = align_up(off + b * s.H_q * (size_t)p.max_splits * 2 * sizeof(float), 256);
+    p.total = off;
+    return XKV_OK;
+}
+
+static inline xkv_status hip_status(hipError_t e) { return e == hipSuccess ? XKV_OK : XKV_ERR_HIP; }
+
+static xkv_status prepare(const xkv_shape *s, void *ws, size_t ws_bytes, Plan &p)
+{
+    xkv_status st = validate(s);
+    if (st != XKV_OK) return st;
+    make_plan(*s, p);
+    if (!ws) return XKV_ERR_INVALID_ARG;
+    if (ws_bytes < p.total) return XKV_ERR_WORKSPACE;
+    if (((uintptr_t)ws) & 255u) return XKV_ERR_INVALID_ARG;
+    return XKV_OK;
+}
+
+template <typename T> static inline T *at(void *ws, size_t off) { return reinterpret_cast<T *>((char *)ws + off); }
+
+}  // namespace xkv
+
+using namespace xkv;
+
+extern "C" {
+
+xkv_status xkv_workspace_bytes(const xkv_shape *shape, size_t *bytes)
+{
+    if (!bytes) return XKV_ERR_INVALID_ARG;
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    Plan p;
+    make_plan(*shape, p);
+    *bytes = p.total;
+    return XKV_OK;
+}
+
+xkv_status xkv_score(const xkv_shape *shape, int32_t layer, const void *A_k, const void *B_k, const void *q,
+                     float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    xkv_status st = prepare(shape, workspace, workspace_bytes, p);
+    if (st != XKV_OK) return st;
+    if (!A_k || !B_k || !q || !score_out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *P = at<float>(workspace, p.off_p);
+    hipError_t e = launch_project_q(*shape, p, layer, B_k, q, P, stream);
+    if (e == hipSuccess) e = launch_score(*shape, p, A_k, P, score_out, stream);
+    return hip_status(e);
+}
+
+xkv_status xkv_topk(const xkv_shape *shape, const float *score, int32_t *idx_out, void *workspace,
+                    size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    xkv_status st = prepare(shape, workspace, workspace_bytes, p);
+    if (st != XKV_OK) return st;
+    if (!score || !idx_out) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    return hip_status(launch_topk(*shape, p, score, idx_out, at<uint32_t>(workspace, p.off_hist),
+                                  at<uint32_t>(workspace, p.off_state), (hipStream_t)hip_stream));
+}
+
+xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                             const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *out,
+                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    xkv_status st = prepare(shape, workspace, workspace_bytes, p);
+    if (st != XKV_OK) return st;
+    if (!A_k || !A_v || !B_k || !B_v || !q || !idx || !out || layer < 0 || layer >= shape->G)
+        return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *part_o = at<float>(workspace, p.off_part_o);
+    float *part_ml = at<float>(workspace, p.off_part_ml);
+    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream);
+    return hip_status(e);
+}
+
+xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v, const void *B_k,
+                         const void *B_v, const void *q, void *out, int32_t *idx_out, float *score_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    xkv_status st = prepare(shape, workspace, workspace_bytes, p);
+    if (st != XKV_OK) return st;
+    if (!A_k || !A_v || !B_k || !B_v || !q || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *P = at<float>(workspace, p.off_p);
+    float *S = score_out ? score_out : at<float>(workspace, p.off_score);
+    int32_t *idx = idx_out ? idx_out : at<int32_t>(workspace, p.off_idx);
+    float *part_o = at<float>(workspace, p.off_part_o);
+    float *part_ml = at<float>(workspace, p.off_part_ml);
+    hipError_t e = launch_project_q(*shape, p, layer, B_k, q, P, stream);
+    if (e == hipSuccess) e = launch_score(*shape, p, A_k, P, S, stream);
+    if (e == hipSuccess)
+        e = launch_topk(*shape, p, S, idx, at<uint32_t>(workspace, p.off_hist), at<uint32_t>(workspace, p.off_state),
+                        stream);
+    if (e == hipSuccess)
+        e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream);
+    return hip_status(e);
+}
+
+xkv_status xkv_dense_decode(const xkv_shape *shape, const void *K, const void *V, const void *q, void *out,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    xkv_status st = prepare(shape, workspace, workspace_bytes, p);
+    if (st != XKV_OK) return st;
+    if (!K || !V || !q || !out) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *part_o = at<float>(workspace, p.off_part_o);
+    float *part_ml = at<float>(workspace, p.off_part_ml);
+    hipError_t e = launch_dense(*shape, p, K, V, q, part_o, part_ml, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, p.dense_splits, part_o, part_ml, out, stream);
+    return hip_status(e);
+}
+
+xkv_status xkv_reconstruct(const xkv_shape *shape, int32_t layer, const void *A, const void *B, int32_t r,
+                           void *X_out, void *hip_stream)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    if (!A || !B || !X_out || r < 1 || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    return hip_status(launch_reconstruct(*shape, layer, A, B, r, X_out, (hipStream_t)hip_stream));
+}
+
+const char *xkv_status_string(xkv_status status)
+{
+    switch (status) {
+    case XKV_OK: return "XKV_OK";
+    case XKV_ERR_INVALID_ARG: return "XKV_ERR_INVALID_ARG";
+    case XKV_ERR_UNSUPPORTED: return "XKV_ERR_UNSUPPORTED";
+    case XKV_ERR_WORKSPACE: return "XKV_ERR_WORKSPACE";
+    case XKV_ERR_HIP: return "XKV_ERR_HIP";
+    default: return "XKV_ERR_UNKNOWN";
+    }
+}
+
+int32_t xkv_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,96 @@
+// Shared device helpers and the internal launch interface of libxkv (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "xkv.h"
+
+namespace xkv {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+
+// round-to-nearest-even; inputs are finite by contract
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return f32_to_bf16(x); }
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+__device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+
+// monotone unsigned image of an fp32 bit pattern: a > b as floats (with -0 < +0) <=> key(a) > key(b)
+__device__ __forceinline__ uint32_t order_key(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host-side plan: how a shape is split over workgroups and where each scratch array lives.
+// ---------------------------------------------------------------------------------------------
+struct Plan {
+    int n_rep;         // query heads per KV head
+    int rows;          // batch * H_kv independent top-k problems
+    int topk_chunks;   // chunks each score row is split into
+    int topk_chunk;    // elements per chunk (multiple of 256)
+    int sr_splits;     // splits of the k selected tokens per (sequence, KV head)
+    int sr_chunk;      // selected tokens per split
+    int dense_splits;  // splits of the L tokens per (sequence, KV head)
+    int dense_chunk;   // tokens per split
+    int max_splits;
+    float scale;
+    // byte offsets into the workspace
+    size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, total;
+};
+
+constexpr int kTopkLevels = 4;   // 8-bit digits of the 32-bit order key
+constexpr int kTopkBins = 256;
+constexpr int kStateWords = 8;   // per row: (prefix, k_rem) for each resolved level
+
+xkv_status make_plan(const xkv_shape &s, Plan &p);
+
+// Kernel launchers (each enqueues on `st`; shapes were validated by the caller).
+hipError_t launch_project_q(const xkv_shape &s, const Plan &p, int layer, const void *B_k, const void *q, float *P,
+                            hipStream_t st);
+hipError_t launch_score(const xkv_shape &s, const Plan &p, const void *A_k, const float *P, float *S, hipStream_t st);
+hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
+                       uint32_t *state, hipStream_t st);
+hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
+                                const void *B_k, const void *B_v, const void *q, const int32_t *idx, float *part_o,
+                                float *part_ml, hipStream_t st);
+hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
+                        float *part_ml, hipStream_t st);
+hipError_t launch_combine(const xkv_shape &s, int n_splits, const float *part_o, const float *part_ml, void *out,
+                          hipStream_t st);
+hipError_t launch_reconstruct(const xkv_shape &s, int layer, const void *A, const void *B, int r, void *X,
+                              hipStream_t st);
+
+}  // namespace xkv

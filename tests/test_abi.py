@@ -1,0 +1,80 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_18893_amd import binding as xb
+from paper_2503_18893_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_entry_points():
+    text = open(os.path.join(ROOT, "include", "xkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"XKV_API[^;(]*?\b(xkv_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_calls():
+    names = declared_entry_points()
+    for must in ("xkv_sr_decode", "xkv_dense_decode", "xkv_score", "xkv_topk", "xkv_gather_attend",
+                 "xkv_workspace_bytes", "xkv_reconstruct"):
+        assert must in names
+    assert sorted(xb.ENTRY_POINTS) == names      # the binding wraps exactly what the header declares
+
+
+def test_library_exports_every_declared_symbol():
+    lib = xb.load()
+    for name in declared_entry_points():
+        assert getattr(lib, name) is not None, name
+
+
+def test_status_strings_and_version():
+    assert xb.status_string(0) == "XKV_OK"
+    assert xb.status_string(-1) == "XKV_ERR_INVALID_ARG"
+    assert xb.status_string(-2) == "XKV_ERR_UNSUPPORTED"
+    assert xb.status_string(-3) == "XKV_ERR_WORKSPACE"
+    assert xb.status_string(-4) == "XKV_ERR_HIP"
+    assert xb.xkv_version() >= 100
+
+
+def test_workspace_query_and_shape_validation():
+    good = xb.Shape.of(synth.LLAMA_GROUP)
+    assert xb.xkv_workspace_bytes(good) > 0
+    bad = [dict(k=0), dict(k=good.L + 1), dict(H_q=30), dict(L=0), dict(r_k=0), dict(batch=-1), dict(scale=-1.0),
+           dict(scale=float("nan")), dict(dtype_code=7), dict(G=0)]
+    for kw in bad:
+        c = good.c()
+        for name, val in kw.items():
+            setattr(c, "dtype" if name == "dtype_code" else name, val)
+        n = ctypes.c_size_t(0)
+        st = xb.load().xkv_workspace_bytes(ctypes.byref(c), ctypes.byref(n))
+        assert st == xb.XKV_ERR_INVALID_ARG, kw
+    for kw in (dict(d_h=512), dict(H_q=8 * 32)):       # shapes no kernel handles
+        c = good.c()
+        for name, val in kw.items():
+            setattr(c, name, val)
+        n = ctypes.c_size_t(0)
+        assert xb.load().xkv_workspace_bytes(ctypes.byref(c), ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED, kw
+    assert xb.load().xkv_workspace_bytes(None, ctypes.byref(ctypes.c_size_t(0))) == xb.XKV_ERR_INVALID_ARG
+    assert xb.load().xkv_workspace_bytes(ctypes.byref(good.c()), None) == xb.XKV_ERR_INVALID_ARG
+
+
+def test_calls_reject_null_pointers_before_touching_the_gpu():
+    lib = xb.load()
+    c = xb.Shape.of(synth.TINY).c()
+    null = ctypes.c_void_p(0)
+    assert lib.xkv_topk(ctypes.byref(c), null, null, null, 0, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_sr_decode(ctypes.byref(c), 0, null, null, null, null, null, null, null, null, null, 0,
+                             null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_reconstruct(ctypes.byref(c), 0, null, null, 4, null, null) == xb.XKV_ERR_INVALID_ARG
+
+
+def test_binding_has_no_cpu_fallback(monkeypatch):
+    monkeypatch.setattr(xb, "_lib", None)
+    monkeypatch.setattr(xb, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
+    with pytest.raises(RuntimeError):
+        xb.load()

@@ -1,0 +1,265 @@
+"""GPU parity: libxkv (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Selection is discontinuous, so parity is a chain of strict links (each stage is fed exactly
+what the GPU fed the next one):
+  (i)   xkv_score                      vs oracle steps 1-3            within tolerance
+  (ii)  xkv_topk(S_gpu)                vs oracle.select(S_gpu)        identical sets
+  (iii) xkv_gather_attend(idx_gpu)     vs oracle steps 5-6 on idx_gpu within tolerance
+  (iv)  xkv_sr_decode end to end       vs the whole oracle            within tolerance where the
+        score gap at the k-th place exceeds rounding (fp32 tiny case), else reported
+Tolerance: max|gpu - ref| / max|ref| per tensor, 1e-5 for fp32 and 2e-2 for bf16 storage with
+fp32 accumulation.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2503_18893_amd import synth
+from paper_2503_18893_amd import binding as xb
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def torch_mod():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch
+
+
+def max_rel(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+def run_stages(w, case, layer, scale=0.0):
+    """Run every stage entry point plus the fused call on the device; return host copies."""
+    torch = torch_mod()
+    shape = xb.Shape.of(w, scale=scale)
+    dev = synth.to_device(case, w.dtype)
+    ws = xb.alloc_workspace(shape)
+    dt = synth.torch_dtype(w.dtype)
+    q = dev["q"][layer].contiguous()
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
+    out_stage = torch.empty((w.batch, w.H_q, w.d_h), dtype=dt, device="cuda")
+    xb.xkv_score(shape, layer, dev["A_k"], dev["B_k"], q, S, ws)
+    xb.xkv_topk(shape, S, idx, ws)
+    xb.xkv_gather_attend(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, idx, out_stage, ws)
+    S2 = torch.empty_like(S)
+    idx2 = torch.empty_like(idx)
+    out_fused = torch.empty_like(out_stage)
+    xb.xkv_sr_decode(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, out_fused, idx2, S2, ws)
+    out_noaux = torch.empty_like(out_stage)
+    xb.xkv_sr_decode(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, out_noaux, None, None, ws)
+    torch.cuda.synchronize()
+    return dict(S=S.cpu().numpy(), idx=idx.cpu().numpy(), out_stage=synth.storage_to_f64(synth.to_host(out_stage)),
+                S_fused=S2.cpu().numpy(), idx_fused=idx2.cpu().numpy(),
+                out_fused=synth.storage_to_f64(synth.to_host(out_fused)),
+                out_noaux=synth.storage_to_f64(synth.to_host(out_noaux)))
+
+
+def check_chain(w, case, layer, scale=None, e2e_strict=False):
+    tol = TOL[w.dtype]
+    sc = oracle.default_scale(w.d_h) if scale is None else scale
+    got = run_stages(w, case, layer, 0.0 if scale is None else scale)
+    report = {}
+    for b in range(w.batch):
+        A_k, A_v = case["A_k"][b], case["A_v"][b]
+        B_k, B_v = case["B_k"][b, layer], case["B_v"][b, layer]
+        q = case["q"][layer, b]
+        # (i) scores
+        S_ref = oracle.pooled_scores(A_k, B_k, q, w.H_kv, sc)
+        err_s = max_rel(got["S"][b], S_ref)
+        assert err_s <= tol, f"score seq {b}: {err_s}"
+        # (ii) selection on the GPU's own scores: identical sets, k distinct ids, ascending order
+        for g in range(w.H_kv):
+            ref_idx = oracle.select(got["S"][b, g], w.k)
+            np.testing.assert_array_equal(np.sort(got["idx"][b, g]), ref_idx)
+            np.testing.assert_array_equal(got["idx"][b, g], ref_idx)  # library writes ascending ids
+        # (iii) reconstruct + attend on the GPU's index sets
+        out_ref = oracle.gather_attend(A_k, A_v, B_k, B_v, q, got["idx"][b], sc)
+        err_o = max_rel(got["out_stage"][b], out_ref)
+        assert err_o <= tol, f"gather_attend seq {b}: {err_o}"
+        # (iv) end to end
+        out_e2e, idx_e2e, _ = oracle.sr_decode(A_k, A_v, B_k, B_v, q, w.H_kv, w.k, sc)
+        jac = np.mean([len(set(got["idx_fused"][b, g]) & set(idx_e2e[g])) /
+                       len(set(got["idx_fused"][b, g]) | set(idx_e2e[g])) for g in range(w.H_kv)])
+        err_e = max_rel(got["out_fused"][b], out_e2e)
+        report[b] = dict(score=err_s, attend=err_o, e2e=err_e, jaccard=jac)
+        if e2e_strict:
+            assert jac == 1.0 and err_e <= tol, report[b]
+    # the fused call must reproduce the staged calls bit for bit (same kernels, same inputs)
+    np.testing.assert_array_equal(got["S_fused"], got["S"])
+    np.testing.assert_array_equal(got["idx_fused"], got["idx"])
+    np.testing.assert_array_equal(got["out_fused"], got["out_stage"])
+    np.testing.assert_array_equal(got["out_noaux"], got["out_stage"])
+    return report
+
+
+# ------------------------------------------------------------------------------ SR chain
+def test_tiny_fp32_config_end_to_end():
+    """Benchmark configuration 1 (fp32): every link strict, end to end included.
+
+    The seed is one where the gap between the k-th and (k+1)-th pooled score is far above fp32
+    rounding, so the GPU and the oracle must pick the same tokens."""
+    w = synth.TINY
+    case = synth.make_case(w, seed=0)
+    for layer in range(w.G):
+        _, _, S32 = oracle.sr_decode(case["A_k"][0], case["A_v"][0], case["B_k"][0, layer], case["B_v"][0, layer],
+                                     case["q"][layer, 0], w.H_kv, w.k)
+        srt = np.sort(S32[0])[::-1]
+        assert (srt[w.k - 1] - srt[w.k]) > 1e-4 * np.abs(srt).max(), "pick a seed with a clear gap"
+        rep = check_chain(w, case, layer, e2e_strict=True)
+        print("tiny", layer, rep)
+
+
+SMALL = [
+    # name, workload: sizes span several tiles with ragged tails
+    ("llama_small_bf16", synth.LLAMA_GROUP.with_(L=3000, k=200, r_k=128, r_v=192, batch=2, G=2)),
+    ("qwen_small_bf16", synth.QWEN.with_(L=5001, k=257, r_k=128, r_v=64, batch=1, G=1)),
+    ("odd_f32", synth.Workload("odd_f32", G=3, H_kv=3, H_q=6, d_h=64, r_k=40, r_v=24, L=777, k=33, batch=2,
+                               dtype="f32", a_scale=1.0, sigma_decay=0.5, q_scale=1.0)),
+    ("odd_bf16_dh96", synth.Workload("odd_bf16", G=1, H_kv=2, H_q=10, d_h=96, r_k=72, r_v=56, L=1300, k=64, batch=1,
+                                     dtype="bf16", a_scale=0.2, sigma_decay=0.8, q_scale=0.3)),
+    ("mha_f32", synth.Workload("mha_f32", G=1, H_kv=4, H_q=4, d_h=32, r_k=16, r_v=16, L=300, k=7, batch=3,
+                               dtype="f32", a_scale=1.0, sigma_decay=1.0, q_scale=1.0)),
+]
+
+
+@pytest.mark.parametrize("name,w", SMALL, ids=[n for n, _ in SMALL])
+def test_small_shapes_chain(name, w):
+    case = synth.make_case(w, seed=11)
+    rep = check_chain(w, case, layer=w.G - 1)
+    print(name, rep)
+
+
+def test_peaked_softmax_case():
+    """Same data with the logit scale raised so that softmax is dominated by a few tokens and
+    selection matters for the output."""
+    w = synth.LLAMA_GROUP.with_(L=2048, k=128, r_k=64, r_v=64, batch=1, G=1, q_scale=1.0, a_scale=1.0)
+    case = synth.make_case(w, seed=5)
+    rep = check_chain(w, case, layer=0, scale=4.0)
+    print("peaked", rep)
+
+
+@pytest.mark.parametrize("k_kind", ["k1", "kL"])
+def test_degenerate_k(k_kind):
+    w = synth.TINY.with_(L=200, k=1 if k_kind == "k1" else 200, G=1)
+    case = synth.make_case(w, seed=2)
+    rep = check_chain(w, case, layer=0)
+    if k_kind == "kL":  # selecting everything: SR equals dense attention on the reconstruction
+        got = run_stages(w, case, 0)
+        K = oracle.reconstruct(case["A_k"][0], case["B_k"][0, 0])
+        V = oracle.reconstruct(case["A_v"][0], case["B_v"][0, 0])
+        ref = oracle.dense(K, V, case["q"][0, 0], w.H_kv)
+        assert max_rel(got["out_fused"][0], ref) <= TOL["f32"]
+    print(k_kind, rep)
+
+
+# ------------------------------------------------------------------------------ top-k on arbitrary arrays
+def topk_gpu(rows_np, k):
+    torch = torch_mod()
+    n_rows, L = rows_np.shape
+    shape = xb.Shape(G=1, H_kv=n_rows, H_q=n_rows, d_h=64, r_k=8, r_v=8, L=L, k=k, batch=1, dtype="f32")
+    ws = xb.alloc_workspace(shape)
+    S = torch.from_numpy(np.ascontiguousarray(rows_np, np.float32)).cuda().view(1, n_rows, L)
+    idx = torch.full((1, n_rows, k), -1, dtype=torch.int32, device="cuda")
+    xb.xkv_topk(shape, S, idx, ws)
+    first = idx.cpu().numpy()[0]
+    idx.fill_(-1)
+    xb.xkv_topk(shape, S, idx, ws)   # determinism run to run
+    np.testing.assert_array_equal(idx.cpu().numpy()[0], first)
+    return first
+
+
+@pytest.mark.parametrize("L", [1, 63, 64, 255, 256, 257, 1000, 4096, 10007, 70001])
+def test_topk_adversarial_arrays(L):
+    rng = np.random.default_rng(L)
+    rows = [
+        rng.standard_normal(L),                                   # generic
+        np.full(L, 0.75),                                         # all equal: smallest ids win
+        rng.integers(0, 4, L).astype(np.float64),                 # many duplicates
+        np.where(rng.random(L) < 0.5, 0.0, -0.0),                 # signed zeros
+        rng.standard_normal(L) * 1e-42,                           # denormals
+        np.arange(L, dtype=np.float64),                           # sorted
+        -np.arange(L, dtype=np.float64),                          # reverse sorted
+        np.abs(rng.standard_normal(L)) * 1e-3 + 1.0,              # values sharing the high key bytes
+        -np.abs(rng.standard_normal(L)) - 5.0,                    # all negative
+    ]
+    rows = np.stack(rows).astype(np.float32)
+    for k in sorted({1, min(2, L), max(1, L // 16), max(1, L // 2), max(1, L - 1), L}):
+        got = topk_gpu(rows, k)
+        for r in range(rows.shape[0]):
+            np.testing.assert_array_equal(got[r], oracle.select(rows[r], k), err_msg=f"L={L} k={k} row={r}")
+
+
+# ------------------------------------------------------------------------------ dense baseline and reconstruction
+DENSE = [
+    ("tiny_f32", synth.TINY.with_(L=700)),
+    ("llama_bf16", synth.LLAMA_GROUP.with_(L=4100, batch=2, r_k=64, r_v=64, G=1)),
+    ("qwen_bf16", synth.QWEN.with_(L=2500, k=100, batch=1, r_k=64, r_v=64, G=1)),
+]
+
+
+@pytest.mark.parametrize("name,w", DENSE, ids=[n for n, _ in DENSE])
+def test_reconstruct_and_dense_decode(name, w):
+    torch = torch_mod()
+    case = synth.make_case(w, seed=21)
+    dev = synth.to_device(case, w.dtype)
+    shape = xb.Shape.of(w)
+    ws = xb.alloc_workspace(shape)
+    dt = synth.torch_dtype(w.dtype)
+    K = torch.empty((w.batch, w.H_kv, w.L, w.d_h), dtype=dt, device="cuda")
+    V = torch.empty_like(K)
+    xb.xkv_reconstruct(shape, 0, dev["A_k"], dev["B_k"], w.r_k, K)
+    xb.xkv_reconstruct(shape, 0, dev["A_v"], dev["B_v"], w.r_v, V)
+    out = torch.empty((w.batch, w.H_q, w.d_h), dtype=dt, device="cuda")
+    xb.xkv_dense_decode(shape, K, V, dev["q"][0].contiguous(), out, ws)
+    torch.cuda.synchronize()
+    Kh, Vh = synth.storage_to_f64(synth.to_host(K)), synth.storage_to_f64(synth.to_host(V))
+    outh = synth.storage_to_f64(synth.to_host(out))
+    for b in range(w.batch):
+        K_ref = oracle.reconstruct(case["A_k"][b], case["B_k"][b, 0])      # [L][d]
+        V_ref = oracle.reconstruct(case["A_v"][b], case["B_v"][b, 0])
+        K_lm = Kh[b].transpose(1, 0, 2).reshape(w.L, w.d)                   # head-major -> [L][d]
+        V_lm = Vh[b].transpose(1, 0, 2).reshape(w.L, w.d)
+        assert max_rel(K_lm, K_ref) <= (2.0 ** -8 if w.dtype == "bf16" else 1e-5)
+        assert max_rel(V_lm, V_ref) <= (2.0 ** -8 if w.dtype == "bf16" else 1e-5)
+        # the dense kernel is checked on exactly the cache it read
+        ref = oracle.dense(K_lm, V_lm, case["q"][0, b], w.H_kv)
+        assert max_rel(outh[b], ref) <= TOL[w.dtype], name
+
+
+# ------------------------------------------------------------------------------ full benchmark shapes
+def test_llama_group_full_size():
+    """Benchmark configuration 2 at full size (L=32768, r=512, k=2048, bf16), whole oracle."""
+    w = synth.LLAMA_GROUP.with_(G=1)
+    case = synth.make_case(w, seed=7)
+    rep = check_chain(w, case, layer=0)
+    print("llama_group_full", rep)
+
+
+# ------------------------------------------------------------------------------ error paths (host side, no launch)
+def test_error_codes():
+    torch = torch_mod()
+    w = synth.TINY
+    shape = xb.Shape.of(w)
+    ws = xb.alloc_workspace(shape)
+    t = torch.zeros(16, device="cuda")
+    with pytest.raises(xb.XkvError) as e:
+        xb.xkv_topk(xb.Shape.of(w, k=w.L + 1), t, t, ws)
+    assert e.value.status == xb.XKV_ERR_INVALID_ARG
+    with pytest.raises(xb.XkvError) as e:
+        xb.xkv_topk(shape, t, t, torch.empty(256, dtype=torch.uint8, device="cuda")[:16])
+    assert e.value.status == xb.XKV_ERR_WORKSPACE
+    with pytest.raises(xb.XkvError) as e:
+        xb.xkv_topk(shape, None, t, ws)
+    assert e.value.status == xb.XKV_ERR_INVALID_ARG
+    with pytest.raises(xb.XkvError) as e:
+        xb.xkv_sr_decode(shape, w.G, t, t, t, t, t, t, None, None, ws)   # layer out of range
+    assert e.value.status == xb.XKV_ERR_INVALID_ARG
+    xb.xkv_topk(xb.Shape.of(w, batch=0), t, t, ws)                         # empty batch: no-op
+    torch.cuda.synchronize()
