@@ -80,30 +80,220 @@ __global__ __launch_bounds__(256) void score_generic_kernel(const T *__restrict_
     }
 }
 
-hipError_t launch_project_q(const xkv_shape &s, const Plan &p, int layer, const void *B_k, const void *q, float *P,
-                            hipStream_t st)
+// ==========================================================================================
+// bf16 MFMA path.  The contraction S^T = P_slots (32 x r) . A^T (r x tokens) runs on
+// v_mfma_f32_32x32x16_bf16: the MFMA "A" operand is a fragment of P (32 head slots x 16 ranks)
+// read from LDS, the "B" operand is 16 B of a token's row of A^K loaded straight from global
+// memory (lane (n, hf) holds ranks 16f + 8hf .. +7 of token n for fragment f), so A^K is
+// streamed exactly once and never staged.  In the 32x32 result lane (n, hf) holds, for token n,
+// the 16 head slots 8(v/4) + 4hf + v%4, v = 0..15.  Query heads are placed in slots so that all
+// heads of a KV head sit in one lane's registers: the GQA max-pool needs no cross-lane traffic.
+//
+// Slot map: half hf holds gph = 16 / n_rep KV heads; KV head g sits in block g / (2 gph), half
+// (g % (2 gph)) / gph, position u = g % gph, and its query head hh in register v = u n_rep + hh.
+// P is kept as a sum of two bf16 values (high part and remainder) so that the scores carry
+// fp32-accumulation accuracy even though the MFMA operands are bf16.
+// ==========================================================================================
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+__host__ __device__ inline int mfma_gph(int n_rep) { return 16 / n_rep; }
+__host__ __device__ inline int mfma_blocks(int H_kv, int n_rep) { return (H_kv + 2 * mfma_gph(n_rep) - 1) / (2 * mfma_gph(n_rep)); }
+
+// One wavefront per (rank index i, half hf, position u, block): writes the bf16 hi/lo fragments.
+// Pfrag layout: [batch][block][part(hi,lo)][F8 fragments][64 lanes][8 bf16], F8 = roundup(r_k/16, 8).
+__global__ __launch_bounds__(256) void project_q_frag_kernel(const bf16_t *__restrict__ B_k,
+                                                             const bf16_t *__restrict__ q,
+                                                             bf16_t *__restrict__ Pfrag, int G, int layer, int r_k,
+                                                             int H_kv, int H_q, int d_h, int F8)
 {
-    (void)p;
-    dim3 grid((s.r_k * s.H_kv + 3) / 4, s.batch), block(256);
-    if (s.dtype == XKV_F32)
-        hipLaunchKernelGGL(project_q_kernel<float>, grid, block, 0, st, (const float *)B_k, (const float *)q, P, s.G,
+    const int n_rep = H_q / H_kv, d = H_kv * d_h;
+    const int gph = mfma_gph(n_rep), nblk = mfma_blocks(H_kv, n_rep);
+    const int r_pad = F8 * 16;
+    const int b = blockIdx.y;
+    const int item = blockIdx.x * 4 + wave_id();
+    if (item >= r_pad * 2 * gph * nblk) return;
+    const int i = item % r_pad;
+    const int pos = item / r_pad;  // (block, half, u)
+    const int u = pos % gph, hf = (pos / gph) % 2, blk = pos / (2 * gph);
+    const int g = blk * 2 * gph + hf * gph + u;
+    const int lane = lane_id();
+    const bool real = (g < H_kv) && (i < r_k);
+    float acc[16];
+#pragma unroll
+    for (int hh = 0; hh < 16; ++hh) acc[hh] = 0.0f;
+    if (real) {
+        const bf16_t *Brow = B_k + (((size_t)b * G + layer) * r_k + i) * d + (size_t)g * d_h;
+        const bf16_t *qg = q + ((size_t)b * H_q + (size_t)g * n_rep) * d_h;
+        for (int j = lane; j < d_h; j += kWave) {
+            const float bv = bf16_to_f32(Brow[j]);
+#pragma unroll
+            for (int hh = 0; hh < 16; ++hh)
+                if (hh < n_rep) acc[hh] = fmaf(bv, bf16_to_f32(qg[(size_t)hh * d_h + j]), acc[hh]);
+        }
+    }
+    // registers of this position: v in [u n_rep, (u+1) n_rep); the last position also clears the unused tail
+    const int v_end = (u == gph - 1) ? 16 : (u + 1) * n_rep;
+    const int f = i / 16, khf = (i % 16) / 8, e = i % 8;
+    const size_t part_stride = (size_t)F8 * 64 * 8;
+    bf16_t *base = Pfrag + ((size_t)b * nblk + blk) * 2 * part_stride + ((size_t)f * 64) * 8 + e;
+#pragma unroll
+    for (int hh = 0; hh < 16; ++hh) {
+        const int v = u * n_rep + hh;
+        if (v < v_end) {
+            const float val = (hh < n_rep) ? wave_sum(acc[hh]) : 0.0f;
+            if (lane == 0) {
+                const int m = 8 * (v / 4) + 4 * hf + (v % 4);  // head slot = MFMA row
+                const bf16_t hi = f32_to_bf16(val);
+                const bf16_t lo = f32_to_bf16(val - bf16_to_f32(hi));
+                base[(size_t)(khf * 32 + m) * 8] = hi;
+                base[part_stride + (size_t)(khf * 32 + m) * 8] = lo;
+            }
+        }
+    }
+}
+
+template <int N_REP>
+__global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restrict__ A_k,    // [batch][L][r_k]
+                                                         const bf16_t *__restrict__ Pfrag,  // see above
+                                                         float *__restrict__ S,             // [batch][H_kv][L]
+                                                         int L, int r_k, int H_kv, int F8, int tiles_per_wg,
+                                                         float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);  // [2][F8][64] fragments of 16 B per lane
+    constexpr int GPH = 16 / N_REP;
+    const int b = blockIdx.z, blk = blockIdx.y, nblk = gridDim.y;
+    const int lane = lane_id(), w = wave_id();
+    const int n = lane & 31, hf = lane >> 5;
+    const int F = r_k / 16;
+
+    // stage this block's P fragments (hi and lo parts) in LDS
+    {
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
+        for (int e = threadIdx.x; e < 2 * F8 * 64; e += 256) Pl[e] = src[e];
+    }
+    __syncthreads();
+
+    const bf16_t *Ab = A_k + (size_t)b * L * r_k;
+    const int n_tiles = (L + 31) / 32;
+    const int tile_begin = blockIdx.x * tiles_per_wg;
+    const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
+    for (int tile = tile_begin + w; tile < tile_end; tile += 4) {
+        const int t = tile * 32 + n;
+        const int t_ld = t < L ? t : L - 1;
+        const u32x4_t *row = reinterpret_cast<const u32x4_t *>(Ab + (size_t)t_ld * r_k) + hf;  // 16 B units
+        f32x16_t acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        for (int f0 = 0; f0 < F8; f0 += 8) {
+            u32x4_t a[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (f0 + j < F)
+                    a[j] = row[2 * (f0 + j)];
+                else
+                    a[j] = u32x4_t{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u32x4_t ph = Pl[(f0 + j) * 64 + lane];
+                const u32x4_t pl = Pl[(F8 + f0 + j) * 64 + lane];
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph),
+                                                              __builtin_bit_cast(bf16x8_t, a[j]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl),
+                                                              __builtin_bit_cast(bf16x8_t, a[j]), acc, 0, 0, 0);
+            }
+        }
+        if (t < L) {
+#pragma unroll
+            for (int u = 0; u < GPH; ++u) {
+                float best = acc[u * N_REP];
+#pragma unroll
+                for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc[u * N_REP + hh]);
+                const int g = blk * 2 * GPH + hf * GPH + u;
+                if (g < H_kv) S[((size_t)b * H_kv + g) * L + t] = scale * best;
+            }
+        }
+    }
+}
+
+static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
+{
+    const int n_rep = s.H_q / s.H_kv;
+    const bool rep_ok = (n_rep >= 1 && n_rep <= 8) || n_rep == 16;
+    return s.dtype == XKV_BF16 && rep_ok && s.r_k % 16 == 0 && (((uintptr_t)A_k) & 15u) == 0 && s.r_k <= 2048;
+}
+
+static hipError_t launch_score_generic(const xkv_shape &s, const Plan &p, int layer, const void *A_k,
+                                       const void *B_k, const void *q, float *P, float *S, hipStream_t st)
+{
+    dim3 pgrid((s.r_k * s.H_kv + 3) / 4, s.batch), grid((s.L + 255) / 256, s.batch), block(256);
+    if (s.dtype == XKV_F32) {
+        hipLaunchKernelGGL(project_q_kernel<float>, pgrid, block, 0, st, (const float *)B_k, (const float *)q, P, s.G,
                            layer, s.r_k, s.H_kv, s.H_q, s.d_h);
-    else
-        hipLaunchKernelGGL(project_q_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q, P,
+        hipLaunchKernelGGL(score_generic_kernel<float>, grid, block, 0, st, (const float *)A_k, P, S, s.L, s.r_k,
+                           s.H_kv, s.H_q, p.scale);
+    } else {
+        hipLaunchKernelGGL(project_q_kernel<bf16_t>, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q, P,
                            s.G, layer, s.r_k, s.H_kv, s.H_q, s.d_h);
+        hipLaunchKernelGGL(score_generic_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)A_k, P, S, s.L, s.r_k,
+                           s.H_kv, s.H_q, p.scale);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_score(const xkv_shape &s, const Plan &p, const void *A_k, const float *P, float *S, hipStream_t st)
+template <int N_REP>
+static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const bf16_t *A_k, const bf16_t *Pfrag,
+                                      float *S, int F8, hipStream_t st)
 {
-    dim3 grid((s.L + 255) / 256, s.batch), block(256);
-    if (s.dtype == XKV_F32)
-        hipLaunchKernelGGL(score_generic_kernel<float>, grid, block, 0, st, (const float *)A_k, P, S, s.L, s.r_k,
-                           s.H_kv, s.H_q, p.scale);
-    else
-        hipLaunchKernelGGL(score_generic_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)A_k, P, S, s.L, s.r_k,
-                           s.H_kv, s.H_q, p.scale);
+    const int nblk = mfma_blocks(s.H_kv, N_REP);
+    const int n_tiles = (s.L + 31) / 32;
+    // enough workgroups to fill the chip several times over, but at least one tile per wavefront
+    long long total_tiles = (long long)n_tiles * s.batch * nblk;
+    int tiles_per_wg = (int)(total_tiles / 2048);
+    tiles_per_wg = tiles_per_wg < 4 ? 4 : (tiles_per_wg > 64 ? 64 : tiles_per_wg);
+    tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;
+    const size_t lds = (size_t)2 * F8 * 64 * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
+    hipLaunchKernelGGL(score_mfma_kernel<N_REP>, grid, block, lds, st, A_k, Pfrag, S, s.L, s.r_k, s.H_kv, F8,
+                       tiles_per_wg, p.scale);
     return hipGetLastError();
+}
+
+hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
+                              const void *q, void *P_ws, float *S, hipStream_t st)
+{
+    if (!score_mfma_ok(s, A_k)) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, st);
+    const int n_rep = s.H_q / s.H_kv;
+    const int F8 = (s.r_k / 16 + 7) / 8 * 8;
+    const int gph = mfma_gph(n_rep), nblk = mfma_blocks(s.H_kv, n_rep);
+    bf16_t *Pfrag = (bf16_t *)P_ws;
+    dim3 pgrid((F8 * 16 * 2 * gph * nblk + 3) / 4, s.batch), block(256);
+    hipLaunchKernelGGL(project_q_frag_kernel, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q, Pfrag, s.G,
+                       layer, s.r_k, s.H_kv, s.H_q, s.d_h, F8);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const bf16_t *A = (const bf16_t *)A_k;
+    switch (n_rep) {
+    case 1: return launch_score_mfma_t<1>(s, p, A, Pfrag, S, F8, st);
+    case 2: return launch_score_mfma_t<2>(s, p, A, Pfrag, S, F8, st);
+    case 3: return launch_score_mfma_t<3>(s, p, A, Pfrag, S, F8, st);
+    case 4: return launch_score_mfma_t<4>(s, p, A, Pfrag, S, F8, st);
+    case 5: return launch_score_mfma_t<5>(s, p, A, Pfrag, S, F8, st);
+    case 6: return launch_score_mfma_t<6>(s, p, A, Pfrag, S, F8, st);
+    case 7: return launch_score_mfma_t<7>(s, p, A, Pfrag, S, F8, st);
+    case 8: return launch_score_mfma_t<8>(s, p, A, Pfrag, S, F8, st);
+    default: return launch_score_mfma_t<16>(s, p, A, Pfrag, S, F8, st);
+    }
 }
 
 }  // namespace xkv

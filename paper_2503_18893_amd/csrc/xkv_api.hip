@@ -52,7 +52,7 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     const size_t b = (size_t)(s.batch > 0 ? s.batch : 1);
     size_t off = 0;
     p.off_p = off;
-    off = align_up(off + b * (size_t)(s.H_q + 32) * s.r_k * sizeof(float), 256);
+    off = align_up(off + b * (size_t)(2 * s.H_q + 64) * (s.r_k + 128) * sizeof(float), 256);  // fp32 P or bf16 hi/lo fragments
     p.off_score = off;
     off = align_up(off + b * s.H_kv * (size_t)s.L * sizeof(float), 256);
     p.off_idx = off;
@@ -110,10 +110,8 @@ xkv_status xkv_score(const xkv_shape *shape, int32_t layer, const void *A_k, con
     if (!A_k || !B_k || !q || !score_out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
-    float *P = at<float>(workspace, p.off_p);
-    hipError_t e = launch_project_q(*shape, p, layer, B_k, q, P, stream);
-    if (e == hipSuccess) e = launch_score(*shape, p, A_k, P, score_out, stream);
-    return hip_status(e);
+    return hip_status(launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), score_out,
+                                         stream));
 }
 
 xkv_status xkv_topk(const xkv_shape *shape, const float *score, int32_t *idx_out, void *workspace,
@@ -156,13 +154,11 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
     if (!A_k || !A_v || !B_k || !B_v || !q || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
-    float *P = at<float>(workspace, p.off_p);
     float *S = score_out ? score_out : at<float>(workspace, p.off_score);
     int32_t *idx = idx_out ? idx_out : at<int32_t>(workspace, p.off_idx);
     float *part_o = at<float>(workspace, p.off_part_o);
     float *part_ml = at<float>(workspace, p.off_part_ml);
-    hipError_t e = launch_project_q(*shape, p, layer, B_k, q, P, stream);
-    if (e == hipSuccess) e = launch_score(*shape, p, A_k, P, S, stream);
+    hipError_t e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S, stream);
     if (e == hipSuccess)
         e = launch_topk(*shape, p, S, idx, at<uint32_t>(workspace, p.off_hist), at<uint32_t>(workspace, p.off_state),
                         stream);

@@ -78,9 +78,8 @@ constexpr int kStateWords = 8;   // per row: (prefix, k_rem) for each resolved l
 xkv_status make_plan(const xkv_shape &s, Plan &p);
 
 // Kernel launchers (each enqueues on `st`; shapes were validated by the caller).
-hipError_t launch_project_q(const xkv_shape &s, const Plan &p, int layer, const void *B_k, const void *q, float *P,
-                            hipStream_t st);
-hipError_t launch_score(const xkv_shape &s, const Plan &p, const void *A_k, const float *P, float *S, hipStream_t st);
+hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
+                              const void *q, void *P_ws, float *S, hipStream_t st);
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
                        uint32_t *state, hipStream_t st);
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,

@@ -126,6 +126,15 @@ SMALL = [
                                      dtype="bf16", a_scale=0.2, sigma_decay=0.8, q_scale=0.3)),
     ("mha_f32", synth.Workload("mha_f32", G=1, H_kv=4, H_q=4, d_h=32, r_k=16, r_v=16, L=300, k=7, batch=3,
                                dtype="f32", a_scale=1.0, sigma_decay=1.0, q_scale=1.0)),
+    # bf16 shapes that exercise the matrix-core paths: several head blocks, padded head slots, ragged rank tails
+    ("gqa8_bf16", synth.Workload("gqa8_bf16", G=1, H_kv=8, H_q=64, d_h=128, r_k=80, r_v=48, L=2100, k=96, batch=2,
+                                 dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    ("gqa16_bf16", synth.Workload("gqa16_bf16", G=1, H_kv=3, H_q=48, d_h=64, r_k=48, r_v=32, L=1111, k=40, batch=1,
+                                  dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    ("mha_bf16", synth.Workload("mha_bf16", G=2, H_kv=20, H_q=20, d_h=64, r_k=32, r_v=64, L=900, k=50, batch=1,
+                                dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    ("gqa2_bf16", synth.Workload("gqa2_bf16", G=1, H_kv=5, H_q=10, d_h=128, r_k=256, r_v=128, L=4097, k=300, batch=1,
+                                 dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
 ]
 
 
