@@ -39,8 +39,11 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     p.topk_chunk = ceil_div(ceil_div(s.L, chunks), 256) * 256;
     p.topk_chunks = ceil_div(s.L, p.topk_chunk);
 
-    int splits = clampi(want, 1, clampi(ceil_div(s.k, 64), 1, 64));
-    p.sr_chunk = ceil_div(ceil_div(s.k, splits), 64) * 64;
+    // the matrix-core kernel walks 256 selected tokens per workgroup iteration, the general one 16
+    p.ga_mfma = gather_attend_mfma_shape_ok(s);
+    const int gran = p.ga_mfma ? 256 : 64;
+    int splits = clampi(want, 1, clampi(ceil_div(s.k, gran), 1, 64));
+    p.sr_chunk = ceil_div(ceil_div(s.k, splits), gran) * gran;
     p.sr_splits = ceil_div(s.k, p.sr_chunk);
 
     splits = clampi(want, 1, clampi(ceil_div(s.L, 256), 1, 128));
@@ -65,6 +68,8 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     off = align_up(off + b * s.H_q * (size_t)p.max_splits * s.d_h * sizeof(float), 256);
     p.off_part_ml = off;
     off = align_up(off + b * s.H_q * (size_t)p.max_splits * 2 * sizeof(float), 256);
+    p.off_bpack = off;
+    if (p.ga_mfma) off = align_up(off + gather_attend_pack_bytes(s), 256);
     p.total = off;
     return XKV_OK;
 }
@@ -139,7 +144,8 @@ xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *
     hipStream_t stream = (hipStream_t)hip_stream;
     float *part_o = at<float>(workspace, p.off_part_o);
     float *part_ml = at<float>(workspace, p.off_part_ml);
-    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, stream);
+    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, at<void>(workspace, p.off_bpack), part_o,
+                                 part_ml, stream);
     if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream);
     return hip_status(e);
 }
@@ -163,7 +169,8 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
         e = launch_topk(*shape, p, S, idx, at<uint32_t>(workspace, p.off_hist), at<uint32_t>(workspace, p.off_state),
                         stream);
     if (e == hipSuccess)
-        e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, stream);
+        e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, at<void>(workspace, p.off_bpack), part_o,
+                                 part_ml, stream);
     if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream);
     return hip_status(e);
 }

@@ -68,7 +68,8 @@ struct Plan {
     int max_splits;
     float scale;
     // byte offsets into the workspace
-    size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, total;
+    size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, off_bpack, total;
+    bool ga_mfma;      // shape fits the matrix-core gather-attend kernel
 };
 
 constexpr int kTopkLevels = 4;   // 8-bit digits of the 32-bit order key
@@ -83,8 +84,13 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
                        uint32_t *state, hipStream_t st);
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
-                                const void *B_k, const void *B_v, const void *q, const int32_t *idx, float *part_o,
-                                float *part_ml, hipStream_t st);
+                                const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
+                                float *part_o, float *part_ml, hipStream_t st);
+bool gather_attend_mfma_shape_ok(const xkv_shape &s);
+size_t gather_attend_pack_bytes(const xkv_shape &s);
+hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
+                                     const void *B_k, const void *B_v, const void *q, const int32_t *idx,
+                                     void *pack_ws, float *part_o, float *part_ml, hipStream_t st);
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st);
 hipError_t launch_combine(const xkv_shape &s, int n_splits, const float *part_o, const float *part_ml, void *out,
