@@ -116,6 +116,184 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     }
 }
 
+// ==========================================================================================
+// bf16 matrix-core path (d_h = 128).  A wavefront walks 32-token blocks of its workgroup's range:
+//   Z^T [tokens x head slots] = K block (rows straight from global memory, 16 B per lane)  x  Q^T (registers)
+//   O [head slots x dims]    += W = exp(Z^T - max) (the result registers of Z^T, packed)   x  V block
+// The contraction of the second product runs over tokens, so each lane needs eight token rows of one
+// column of V: the V block goes through a wavefront-private LDS tile (row pitch 272 B, conflict-free)
+// and is read back transposed.  The four wavefronts merge their partials in LDS before writing.
+// ==========================================================================================
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) float f32x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+constexpr int kVPitch = 272;  // bytes per token row of the LDS tile of V (256 + 16: rows 4 apart land 64 B apart)
+
+__device__ __forceinline__ bf16x8_t pack8_bf16(const f32x16_t &c, int j)
+{
+    f32x8_t x;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = c[8 * j + e];
+    return __builtin_convertvector(x, bf16x8_t);
+}
+
+__global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+                                                            const bf16_t *__restrict__ q, float *__restrict__ part_o,
+                                                            float *__restrict__ part_ml, int L, int H_kv, int H_q,
+                                                            int splits, int chunk, float scale)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * kVPitch];  // 34 KiB; reused for the merge
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int lane = lane_id(), w = wave_id();
+    const int n = lane & 31, hf = lane >> 5;
+    const int n_rep = H_q / H_kv;
+
+    // Q^T fragments: lane (head slot n, hf), fragment f, position e: q[n][16 f + 8 hf + e]
+    bf16x8_t Qf[8];
+    {
+        const u32x4_t *qh = reinterpret_cast<const u32x4_t *>(q + ((size_t)b * H_q + (size_t)g * n_rep +
+                                                                    (n < n_rep ? n : 0)) * 128);
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+            u32x4_t raw = qh[2 * f + hf];
+            if (n >= n_rep) raw = u32x4_t{0u, 0u, 0u, 0u};
+            Qf[f] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+    }
+    const bf16_t *Kg = K + ((size_t)b * H_kv + g) * (size_t)L * 128;
+    const bf16_t *Vg = V + ((size_t)b * H_kv + g) * (size_t)L * 128;
+    const int t_begin = split * chunk;
+    const int t_end = t_begin + chunk < L ? t_begin + chunk : L;
+    unsigned char *vt = smem + w * 32 * kVPitch;  // this wavefront's V tile
+
+    float m_run = -INFINITY, l_run = 0.0f;
+    f32x16_t O[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) O[db][v] = 0.0f;
+
+    for (int t0 = t_begin + w * 32; t0 < t_end; t0 += 128) {
+        // K rows of this block: lane (token n, hf) takes 16 B of each 32 B fragment
+        const int tk = t0 + n < t_end ? t0 + n : t_end - 1;
+        const u32x4_t *krow = reinterpret_cast<const u32x4_t *>(Kg + (size_t)tk * 128) + hf;
+        u32x4_t kf[8];
+#pragma unroll
+        for (int f = 0; f < 8; ++f) kf[f] = krow[2 * f];
+        // V rows: 16 lanes cover one 256 B row, the wavefront 4 rows per load
+        u32x4_t vr[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = i * 4 + (lane >> 4);
+            const int tv = t0 + row < t_end ? t0 + row : t_end - 1;
+            vr[i] = reinterpret_cast<const u32x4_t *>(Vg + (size_t)tv * 128)[lane & 15];
+        }
+        f32x16_t Z;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Z[v] = 0.0f;
+#pragma unroll
+        for (int f = 0; f < 8; ++f)
+            Z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[f]), Qf[f], Z, 0, 0, 0);
+        // lane (head slot n, hf): register v is token 8(v/4) + 4hf + v%4 of the block
+        float m_loc = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int tt = t0 + 8 * (v / 4) + 4 * hf + (v % 4);
+            Z[v] = tt < t_end ? scale * Z[v] : -INFINITY;
+            m_loc = fmaxf(m_loc, Z[v]);
+        }
+        m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, kWave));
+        const float m_new = fmaxf(m_run, m_loc);
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __expf(m_run - m_new);
+        float l_add = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float wv = (Z[v] == -INFINITY) ? 0.0f : __expf(Z[v] - m_new);
+            Z[v] = wv;
+            l_add += wv;
+        }
+        l_run = l_run * alpha + l_add;
+        m_run = m_new;
+        const bf16x8_t W0 = pack8_bf16(Z, 0), W1 = pack8_bf16(Z, 1);
+
+        // stage V in LDS and read it back as [8 tokens of one column] fragments
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = i * 4 + (lane >> 4);
+            *reinterpret_cast<u32x4_t *>(vt + row * kVPitch + (lane & 15) * 16) = vr[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const float a = __shfl(alpha, 8 * (v / 4) + 4 * hf + (v % 4), kWave);
+#pragma unroll
+            for (int db = 0; db < 4; ++db) O[db][v] *= a;
+        }
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                u32x4_t raw;
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    const int e = 2 * e2;
+                    const int tok = 8 * (2 * j + e / 4) + 4 * hf + (e % 4);  // e, e+1 are adjacent tokens
+                    const uint32_t lo = *reinterpret_cast<const uint16_t *>(vt + tok * kVPitch + (db * 32 + n) * 2);
+                    const uint32_t hi =
+                        *reinterpret_cast<const uint16_t *>(vt + (tok + 1) * kVPitch + (db * 32 + n) * 2);
+                    raw[e2] = lo | (hi << 16);
+                }
+                O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(j == 0 ? W0 : W1, __builtin_bit_cast(bf16x8_t, raw),
+                                                                O[db], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // merge the four wavefronts: LDS holds per (wavefront, head) the max, the sum and 128 outputs
+    __syncthreads();
+    float *mg = reinterpret_cast<float *>(smem);  // [4][16][132]
+    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    if (lane < n_rep) {
+        mg[(w * 16 + lane) * 132 + 128] = m_run;
+        mg[(w * 16 + lane) * 132 + 129] = l_tot;
+    }
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        const int hh = 8 * (v / 4) + 4 * hf + (v % 4);
+        if (hh < n_rep) {
+#pragma unroll
+            for (int db = 0; db < 4; ++db) mg[(w * 16 + hh) * 132 + db * 32 + n] = O[db][v];
+        }
+    }
+    __syncthreads();
+    for (int item = threadIdx.x; item < n_rep * 128; item += 256) {
+        const int hh = item >> 7, dim = item & 127;
+        float M = -INFINITY;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, mg[(ww * 16 + hh) * 132 + 128]);
+        float num = 0.0f, den = 0.0f;
+#pragma unroll
+        for (int ww = 0; ww < 4; ++ww) {
+            const float mw = mg[(ww * 16 + hh) * 132 + 128];
+            const float wgt = (mw == -INFINITY) ? 0.0f : __expf(mw - M);
+            num = fmaf(wgt, mg[(ww * 16 + hh) * 132 + dim], num);
+            den = fmaf(wgt, mg[(ww * 16 + hh) * 132 + 129], den);
+        }
+        const size_t slot = ((size_t)b * H_q + g * n_rep + hh) * splits + split;
+        part_o[slot * 128 + dim] = num;
+        if (dim == 0) {
+            part_ml[slot * 2 + 0] = M;
+            part_ml[slot * 2 + 1] = den;
+        }
+    }
+}
+
 template <typename T>
 static hipError_t launch_dense_generic(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q,
                                        float *part_o, float *part_ml, hipStream_t st)
@@ -135,18 +313,26 @@ static hipError_t launch_dense_generic(const xkv_shape &s, const Plan &p, const 
     return hipGetLastError();
 }
 
+bool dense_mfma_shape_ok(const xkv_shape &s) { return s.dtype == XKV_BF16 && s.d_h == 128; }
+
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st)
 {
+    if (p.dense_mfma && ((((uintptr_t)K | (uintptr_t)V | (uintptr_t)q)) & 15u) == 0) {
+        dim3 grid(p.dense_splits, s.H_kv, s.batch), block(256);
+        hipLaunchKernelGGL(dense_mfma_kernel, grid, block, 0, st, (const bf16_t *)K, (const bf16_t *)V,
+                           (const bf16_t *)q, part_o, part_ml, s.L, s.H_kv, s.H_q, p.dense_splits, p.dense_chunk,
+                           p.scale);
+        return hipGetLastError();
+    }
     if (s.dtype == XKV_F32) return launch_dense_generic<float>(s, p, K, V, q, part_o, part_ml, st);
     return launch_dense_generic<bf16_t>(s, p, K, V, q, part_o, part_ml, st);
 }
 
-hipError_t launch_combine(const xkv_shape &s, int n_splits, const float *part_o, const float *part_ml, void *out,
+hipError_t launch_combine(const xkv_shape &s, int n_part, const float *part_o, const float *part_ml, void *out,
                           hipStream_t st)
 {
     dim3 grid(s.H_q, s.batch), block(s.d_h <= 64 ? 64 : (s.d_h <= 128 ? 128 : 256));
-    const int n_part = n_splits * 4;
     if (s.dtype == XKV_F32)
         hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, st, part_o, part_ml, (float *)out, s.H_q, s.d_h,
                            n_part);

@@ -101,36 +101,54 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 __host__ __device__ inline int mfma_gph(int n_rep) { return 16 / n_rep; }
 __host__ __device__ inline int mfma_blocks(int H_kv, int n_rep) { return (H_kv + 2 * mfma_gph(n_rep) - 1) / (2 * mfma_gph(n_rep)); }
 
-// One wavefront per (rank index i, half hf, position u, block): writes the bf16 hi/lo fragments.
+// One thread per (rank index i, slot position): the thread walks its 256 B slice of row i of B^K_l with
+// 16 B loads and keeps one dot product per query head of the KV head (queries sit in LDS as fp32), then
+// writes the bf16 high part and remainder into the fragment layout.  Positions are (block, half, u);
+// positions without a KV head, ranks beyond r_k and the unused tail of a half are written as zeros.
 // Pfrag layout: [batch][block][part(hi,lo)][F8 fragments][64 lanes][8 bf16], F8 = roundup(r_k/16, 8).
 __global__ __launch_bounds__(256) void project_q_frag_kernel(const bf16_t *__restrict__ B_k,
                                                              const bf16_t *__restrict__ q,
                                                              bf16_t *__restrict__ Pfrag, int G, int layer, int r_k,
                                                              int H_kv, int H_q, int d_h, int F8)
 {
+    extern __shared__ float q_lds[];  // [H_q][d_h + 1]
     const int n_rep = H_q / H_kv, d = H_kv * d_h;
     const int gph = mfma_gph(n_rep), nblk = mfma_blocks(H_kv, n_rep);
+    const int n_pos = 2 * gph * nblk;
     const int r_pad = F8 * 16;
     const int b = blockIdx.y;
-    const int item = blockIdx.x * 4 + wave_id();
-    if (item >= r_pad * 2 * gph * nblk) return;
-    const int i = item % r_pad;
-    const int pos = item / r_pad;  // (block, half, u)
+    for (int e = threadIdx.x; e < H_q * d_h; e += 256)
+        q_lds[(e / d_h) * (d_h + 1) + e % d_h] = bf16_to_f32(q[(size_t)b * H_q * d_h + e]);
+    __syncthreads();
+    const int item = blockIdx.x * 256 + threadIdx.x;  // position fastest: a wavefront reads whole rows of B
+    if (item >= r_pad * n_pos) return;
+    const int pos = item % n_pos, i = item / n_pos;
     const int u = pos % gph, hf = (pos / gph) % 2, blk = pos / (2 * gph);
     const int g = blk * 2 * gph + hf * gph + u;
-    const int lane = lane_id();
-    const bool real = (g < H_kv) && (i < r_k);
     float acc[16];
 #pragma unroll
     for (int hh = 0; hh < 16; ++hh) acc[hh] = 0.0f;
-    if (real) {
+    if (g < H_kv && i < r_k) {
         const bf16_t *Brow = B_k + (((size_t)b * G + layer) * r_k + i) * d + (size_t)g * d_h;
-        const bf16_t *qg = q + ((size_t)b * H_q + (size_t)g * n_rep) * d_h;
-        for (int j = lane; j < d_h; j += kWave) {
-            const float bv = bf16_to_f32(Brow[j]);
+        const float *qg = q_lds + (size_t)g * n_rep * (d_h + 1);
+        if ((d_h & 7) == 0) {
+            for (int j0 = 0; j0 < d_h; j0 += 8) {
+                const u32x4_t raw = *reinterpret_cast<const u32x4_t *>(Brow + j0);
 #pragma unroll
-            for (int hh = 0; hh < 16; ++hh)
-                if (hh < n_rep) acc[hh] = fmaf(bv, bf16_to_f32(qg[(size_t)hh * d_h + j]), acc[hh]);
+                for (int e = 0; e < 8; ++e) {
+                    const float bv = __uint_as_float((e & 1) ? (raw[e / 2] & 0xFFFF0000u) : (raw[e / 2] << 16));
+#pragma unroll
+                    for (int hh = 0; hh < 16; ++hh)
+                        if (hh < n_rep) acc[hh] = fmaf(bv, qg[hh * (d_h + 1) + j0 + e], acc[hh]);
+                }
+            }
+        } else {
+            for (int j = 0; j < d_h; ++j) {
+                const float bv = bf16_to_f32(Brow[j]);
+#pragma unroll
+                for (int hh = 0; hh < 16; ++hh)
+                    if (hh < n_rep) acc[hh] = fmaf(bv, qg[hh * (d_h + 1) + j], acc[hh]);
+            }
         }
     }
     // registers of this position: v in [u n_rep, (u+1) n_rep); the last position also clears the unused tail
@@ -142,14 +160,12 @@ __global__ __launch_bounds__(256) void project_q_frag_kernel(const bf16_t *__res
     for (int hh = 0; hh < 16; ++hh) {
         const int v = u * n_rep + hh;
         if (v < v_end) {
-            const float val = (hh < n_rep) ? wave_sum(acc[hh]) : 0.0f;
-            if (lane == 0) {
-                const int m = 8 * (v / 4) + 4 * hf + (v % 4);  // head slot = MFMA row
-                const bf16_t hi = f32_to_bf16(val);
-                const bf16_t lo = f32_to_bf16(val - bf16_to_f32(hi));
-                base[(size_t)(khf * 32 + m) * 8] = hi;
-                base[part_stride + (size_t)(khf * 32 + m) * 8] = lo;
-            }
+            const float val = (hh < n_rep) ? acc[hh] : 0.0f;
+            const int m = 8 * (v / 4) + 4 * hf + (v % 4);  // head slot = MFMA row
+            const bf16_t hi = f32_to_bf16(val);
+            const bf16_t lo = f32_to_bf16(val - bf16_to_f32(hi));
+            base[(size_t)(khf * 32 + m) * 8] = hi;
+            base[part_stride + (size_t)(khf * 32 + m) * 8] = lo;
         }
     }
 }
@@ -223,7 +239,8 @@ static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
 {
     const int n_rep = s.H_q / s.H_kv;
     const bool rep_ok = (n_rep >= 1 && n_rep <= 8) || n_rep == 16;
-    return s.dtype == XKV_BF16 && rep_ok && s.r_k % 16 == 0 && (((uintptr_t)A_k) & 15u) == 0 && s.r_k <= 2048;
+    return s.dtype == XKV_BF16 && rep_ok && s.r_k % 16 == 0 && (((uintptr_t)A_k) & 15u) == 0 && s.r_k <= 2048 &&
+           (size_t)s.H_q * (s.d_h + 1) * sizeof(float) <= 60 * 1024;
 }
 
 static hipError_t launch_score_generic(const xkv_shape &s, const Plan &p, int layer, const void *A_k,
@@ -277,8 +294,9 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;
     const int gph = mfma_gph(n_rep), nblk = mfma_blocks(s.H_kv, n_rep);
     bf16_t *Pfrag = (bf16_t *)P_ws;
-    dim3 pgrid((F8 * 16 * 2 * gph * nblk + 3) / 4, s.batch), block(256);
-    hipLaunchKernelGGL(project_q_frag_kernel, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q, Pfrag, s.G,
+    dim3 pgrid((F8 * 16 * 2 * gph * nblk + 255) / 256, s.batch), block(256);
+    const size_t q_lds = (size_t)s.H_q * (s.d_h + 1) * sizeof(float);
+    hipLaunchKernelGGL(project_q_frag_kernel, pgrid, block, q_lds, st, (const bf16_t *)B_k, (const bf16_t *)q, Pfrag, s.G,
                        layer, s.r_k, s.H_kv, s.H_q, s.d_h, F8);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

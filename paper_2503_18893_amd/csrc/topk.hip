@@ -77,21 +77,30 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(const float *__restrict_
     const float *Srow = S + (size_t)row * L;
     const int lane = lane_id();
     const int base = c * chunk;
-    for (int i = threadIdx.x; i < chunk; i += 256) {  // chunk is a multiple of 256: uniform trip count
-        const int t = base + i;
-        uint32_t key = 0;
-        bool active = t < L;
-        if (active) key = order_key(Srow[t]);
-        if constexpr (LEVEL > 0) active = active && ((key >> (32 - 8 * LEVEL)) == prefix);
-        const uint32_t digit = (key >> (24 - 8 * LEVEL)) & 0xFFu;
-        // scores cluster in few bins at the top levels: add the leader's bin once per wavefront
-        const uint64_t m = __ballot(active);
-        if (m != 0) {
-            const int first = __ffsll((unsigned long long)m) - 1;
-            const uint32_t d0 = __shfl(digit, first, kWave);
-            const uint64_t same = __ballot(active && digit == d0);
-            if (lane == first) atomicAdd(&sh_hist[d0], (uint32_t)__popcll(same));
-            if (active && digit != d0) atomicAdd(&sh_hist[digit], 1u);
+    for (int i0 = 0; i0 < chunk; i0 += 1024) {  // chunk is a multiple of 256: every trip count is uniform
+        float val[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {  // four independent coalesced loads in flight
+            const int t = base + i0 + u * 256 + (int)threadIdx.x;
+            val[u] = (i0 + u * 256 < chunk && t < L) ? Srow[t] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i0 + u * 256 >= chunk) break;
+            const int t = base + i0 + u * 256 + (int)threadIdx.x;
+            const uint32_t key = order_key(val[u]);
+            bool active = t < L;
+            if constexpr (LEVEL > 0) active = active && ((key >> (32 - 8 * LEVEL)) == prefix);
+            const uint32_t digit = (key >> (24 - 8 * LEVEL)) & 0xFFu;
+            // scores cluster in few bins at the top levels: add the leader's bin once per wavefront
+            const uint64_t m = __ballot(active);
+            if (m != 0) {
+                const int first = __ffsll((unsigned long long)m) - 1;
+                const uint32_t d0 = __shfl(digit, first, kWave);
+                const uint64_t same = __ballot(active && digit == d0);
+                if (lane == first) atomicAdd(&sh_hist[d0], (uint32_t)__popcll(same));
+                if (active && digit != d0) atomicAdd(&sh_hist[digit], 1u);
+            }
         }
     }
     __syncthreads();
@@ -145,11 +154,21 @@ __global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict
     const int sub = chunk / 4;
     const int begin = c * chunk + w * sub;
     uint32_t my_gt = 0, my_eq = 0;
-    for (int i = 0; i < sub; i += kWave) {
-        const int t = begin + i + lane;
-        const uint32_t key = t < L ? order_key(Srow[t]) : 0u;
-        my_gt += (uint32_t)__popcll(__ballot(t < L && key > T));
-        my_eq += (uint32_t)__popcll(__ballot(t < L && key == T));
+    for (int i0 = 0; i0 < sub; i0 += 4 * kWave) {  // sub is a multiple of 64
+        float val[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = begin + i0 + u * kWave + lane;
+            val[u] = (i0 + u * kWave < sub && t < L) ? Srow[t] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = begin + i0 + u * kWave + lane;
+            const bool in = i0 + u * kWave < sub && t < L;
+            const uint32_t key = order_key(val[u]);
+            my_gt += (uint32_t)__popcll(__ballot(in && key > T));
+            my_eq += (uint32_t)__popcll(__ballot(in && key == T));
+        }
     }
     if (lane == 0) {
         sh_cnt[0][w] = my_gt;
@@ -162,18 +181,28 @@ __global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict
         eq_run += sh_cnt[1][ww];
     }
     int32_t *out = idx_out + (size_t)row * k;
-    for (int i = 0; i < sub; i += kWave) {
-        const int t = begin + i + lane;
-        const uint32_t key = t < L ? order_key(Srow[t]) : 0u;
-        const bool is_gt = t < L && key > T, is_eq = t < L && key == T;
-        const uint64_t mg = __ballot(is_gt), me = __ballot(is_eq);
-        const uint32_t gt_me = gt_run + lanes_below(mg), eq_me = eq_run + lanes_below(me);
-        if (is_gt || (is_eq && eq_me < need_eq)) {
-            const uint32_t pos = gt_me + (eq_me < need_eq ? eq_me : need_eq);
-            if (pos < (uint32_t)k) out[pos] = t;
+    for (int i0 = 0; i0 < sub; i0 += 4 * kWave) {
+        float val[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = begin + i0 + u * kWave + lane;
+            val[u] = (i0 + u * kWave < sub && t < L) ? Srow[t] : 0.0f;
         }
-        gt_run += (uint32_t)__popcll(mg);
-        eq_run += (uint32_t)__popcll(me);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = begin + i0 + u * kWave + lane;
+            const bool in = i0 + u * kWave < sub && t < L;
+            const uint32_t key = order_key(val[u]);
+            const bool is_gt = in && key > T, is_eq = in && key == T;
+            const uint64_t mg = __ballot(is_gt), me = __ballot(is_eq);
+            const uint32_t gt_me = gt_run + lanes_below(mg), eq_me = eq_run + lanes_below(me);
+            if (is_gt || (is_eq && eq_me < need_eq)) {
+                const uint32_t pos = gt_me + (eq_me < need_eq ? eq_me : need_eq);
+                if (pos < (uint32_t)k) out[pos] = t;
+            }
+            gt_run += (uint32_t)__popcll(mg);
+            eq_run += (uint32_t)__popcll(me);
+        }
     }
 }
 

@@ -43,11 +43,13 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     p.ga_mfma = gather_attend_mfma_shape_ok(s);
     const int gran = p.ga_mfma ? 256 : 64;
     int splits = clampi(want, 1, clampi(ceil_div(s.k, gran), 1, 64));
+    if (splits < ceil_div(s.k, 8192)) splits = ceil_div(s.k, 8192);  // a workgroup keeps at most 8192 token ids in LDS
     p.sr_chunk = ceil_div(ceil_div(s.k, splits), gran) * gran;
     p.sr_splits = ceil_div(s.k, p.sr_chunk);
 
     splits = clampi(want, 1, clampi(ceil_div(s.L, 256), 1, 128));
-    p.dense_chunk = ceil_div(ceil_div(s.L, splits), 64) * 64;
+    p.dense_mfma = dense_mfma_shape_ok(s);
+    p.dense_chunk = ceil_div(ceil_div(s.L, splits), 128) * 128;  // 4 wavefronts x 32-token blocks
     p.dense_splits = ceil_div(s.L, p.dense_chunk);
 
     p.max_splits = 4 * (p.sr_splits > p.dense_splits ? p.sr_splits : p.dense_splits);  // one partial per wavefront
@@ -146,7 +148,7 @@ xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *
     float *part_ml = at<float>(workspace, p.off_part_ml);
     hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, at<void>(workspace, p.off_bpack), part_o,
                                  part_ml, stream);
-    if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, p.ga_mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
 }
 
@@ -171,7 +173,7 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
     if (e == hipSuccess)
         e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, at<void>(workspace, p.off_bpack), part_o,
                                  part_ml, stream);
-    if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, p.ga_mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
 }
 
@@ -187,7 +189,7 @@ xkv_status xkv_dense_decode(const xkv_shape *shape, const void *K, const void *V
     float *part_o = at<float>(workspace, p.off_part_o);
     float *part_ml = at<float>(workspace, p.off_part_ml);
     hipError_t e = launch_dense(*shape, p, K, V, q, part_o, part_ml, stream);
-    if (e == hipSuccess) e = launch_combine(*shape, p.dense_splits, part_o, part_ml, out, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, p.dense_mfma ? p.dense_splits : p.dense_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
 }
 

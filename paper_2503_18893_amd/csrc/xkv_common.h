@@ -69,6 +69,7 @@ struct Plan {
     float scale;
     // byte offsets into the workspace
     size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, off_bpack, total;
+    bool dense_mfma;   // shape fits the matrix-core dense kernel
     bool ga_mfma;      // shape fits the matrix-core gather-attend kernel
 };
 
@@ -93,7 +94,8 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
                                      void *pack_ws, float *part_o, float *part_ml, hipStream_t st);
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st);
-hipError_t launch_combine(const xkv_shape &s, int n_splits, const float *part_o, const float *part_ml, void *out,
+bool dense_mfma_shape_ok(const xkv_shape &s);
+hipError_t launch_combine(const xkv_shape &s, int n_part, const float *part_o, const float *part_ml, void *out,
                           hipStream_t st);
 hipError_t launch_reconstruct(const xkv_shape &s, int layer, const void *A, const void *B, int r, void *X,
                               hipStream_t st);
