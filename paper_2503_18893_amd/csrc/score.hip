@@ -2,6 +2,8 @@
 //   p_h = B^K_{l,rho(h)} q_h                      (Eq. 3 regrouped by associativity)
 //   s[h,t] = scale * A^K[t,:] . p_h               (App. B.1 Alg. 2, scaled scores, per token)
 //   S[g,t] = max_{h: rho(h)=g} s[h,t]             (App. B.1 Alg. 2, GQA pooling)
+#include <cstdlib>
+
 #include "xkv_common.h"
 
 namespace xkv {
@@ -101,71 +103,64 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 __host__ __device__ inline int mfma_gph(int n_rep) { return 16 / n_rep; }
 __host__ __device__ inline int mfma_blocks(int H_kv, int n_rep) { return (H_kv + 2 * mfma_gph(n_rep) - 1) / (2 * mfma_gph(n_rep)); }
 
-// One thread per (rank index i, slot position): the thread walks its 256 B slice of row i of B^K_l with
-// 16 B loads and keeps one dot product per query head of the KV head (queries sit in LDS as fp32), then
-// writes the bf16 high part and remainder into the fragment layout.  Positions are (block, half, u);
-// positions without a KV head, ranks beyond r_k and the unused tail of a half are written as zeros.
+// One wavefront per (slot position, block of 32 ranks): P_g [head slots x 32 ranks] = Q_g [slots x d_h] . B_g^T on
+// the matrix cores, both operands straight from global memory (lane (x, hf) holds 8 consecutive head
+// dims of query slot x / of row i0 + x of B^K_l, KV head g).  In the result lane (n, hf) holds rank i0 + n
+// and head slots 8(v/4) + 4hf + v%4; it splits each value into a bf16 high part and remainder and stores
+// both at their place in the fragment layout.  Positions are (block, half, u); positions without a KV
+// head, ranks beyond r_k and the unused tail of a half are written as zeros.
 // Pfrag layout: [batch][block][part(hi,lo)][F8 fragments][64 lanes][8 bf16], F8 = roundup(r_k/16, 8).
 __global__ __launch_bounds__(256) void project_q_frag_kernel(const bf16_t *__restrict__ B_k,
                                                              const bf16_t *__restrict__ q,
                                                              bf16_t *__restrict__ Pfrag, int G, int layer, int r_k,
                                                              int H_kv, int H_q, int d_h, int F8)
 {
-    extern __shared__ float q_lds[];  // [H_q][d_h + 1]
     const int n_rep = H_q / H_kv, d = H_kv * d_h;
     const int gph = mfma_gph(n_rep), nblk = mfma_blocks(H_kv, n_rep);
-    const int n_pos = 2 * gph * nblk;
-    const int r_pad = F8 * 16;
+    const int n_pos = 2 * gph * nblk, n_rb = F8 / 2;  // rank blocks of 32
     const int b = blockIdx.y;
-    for (int e = threadIdx.x; e < H_q * d_h; e += 256)
-        q_lds[(e / d_h) * (d_h + 1) + e % d_h] = bf16_to_f32(q[(size_t)b * H_q * d_h + e]);
-    __syncthreads();
-    const int item = blockIdx.x * 256 + threadIdx.x;  // position fastest: a wavefront reads whole rows of B
-    if (item >= r_pad * n_pos) return;
-    const int pos = item % n_pos, i = item / n_pos;
-    const int u = pos % gph, hf = (pos / gph) % 2, blk = pos / (2 * gph);
-    const int g = blk * 2 * gph + hf * gph + u;
-    float acc[16];
+    const int item = blockIdx.x * 4 + wave_id();
+    if (item >= n_pos * n_rb) return;
+    const int pos = item % n_pos, i0 = (item / n_pos) * 32;
+    const int u = pos % gph, ghf = (pos / gph) % 2, blk = pos / (2 * gph);
+    const int g = blk * 2 * gph + ghf * gph + u;
+    const int lane = lane_id(), n = lane & 31, hf = lane >> 5;
+    f32x16_t acc;
 #pragma unroll
-    for (int hh = 0; hh < 16; ++hh) acc[hh] = 0.0f;
-    if (g < H_kv && i < r_k) {
-        const bf16_t *Brow = B_k + (((size_t)b * G + layer) * r_k + i) * d + (size_t)g * d_h;
-        const float *qg = q_lds + (size_t)g * n_rep * (d_h + 1);
-        if ((d_h & 7) == 0) {
-            for (int j0 = 0; j0 < d_h; j0 += 8) {
-                const u32x4_t raw = *reinterpret_cast<const u32x4_t *>(Brow + j0);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float bv = __uint_as_float((e & 1) ? (raw[e / 2] & 0xFFFF0000u) : (raw[e / 2] << 16));
-#pragma unroll
-                    for (int hh = 0; hh < 16; ++hh)
-                        if (hh < n_rep) acc[hh] = fmaf(bv, qg[hh * (d_h + 1) + j0 + e], acc[hh]);
-                }
-            }
-        } else {
-            for (int j = 0; j < d_h; ++j) {
-                const float bv = bf16_to_f32(Brow[j]);
-#pragma unroll
-                for (int hh = 0; hh < 16; ++hh)
-                    if (hh < n_rep) acc[hh] = fmaf(bv, qg[hh * (d_h + 1) + j], acc[hh]);
-            }
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    if (g < H_kv) {
+        const int i = i0 + n < r_k ? i0 + n : r_k - 1;
+        const u32x4_t *brow = reinterpret_cast<const u32x4_t *>(B_k + (((size_t)b * G + layer) * r_k + i) * d +
+                                                                 (size_t)g * d_h) + hf;
+        const u32x4_t *qrow = reinterpret_cast<const u32x4_t *>(q + ((size_t)b * H_q + (size_t)g * n_rep +
+                                                                     (n < n_rep ? n : 0)) * d_h) + hf;
+        for (int f = 0; f < d_h / 16; ++f) {
+            u32x4_t qa = qrow[2 * f];
+            if (n >= n_rep) qa = u32x4_t{0u, 0u, 0u, 0u};
+            u32x4_t ba = brow[2 * f];
+            if (i0 + n >= r_k) ba = u32x4_t{0u, 0u, 0u, 0u};
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, qa),
+                                                          __builtin_bit_cast(bf16x8_t, ba), acc, 0, 0, 0);
         }
     }
-    // registers of this position: v in [u n_rep, (u+1) n_rep); the last position also clears the unused tail
-    const int v_end = (u == gph - 1) ? 16 : (u + 1) * n_rep;
+    // this lane's rank and where it sits in the fragment layout
+    const int i = i0 + n;
     const int f = i / 16, khf = (i % 16) / 8, e = i % 8;
     const size_t part_stride = (size_t)F8 * 64 * 8;
-    bf16_t *base = Pfrag + ((size_t)b * nblk + blk) * 2 * part_stride + ((size_t)f * 64) * 8 + e;
+    bf16_t *base = Pfrag + ((size_t)b * nblk + blk) * 2 * part_stride + ((size_t)f * 64 + khf * 32) * 8 + e;
+    // registers of this position: vv in [u n_rep, (u+1) n_rep); the last position also clears the unused tail
+    const int vv_end = (u == gph - 1) ? 16 : (u + 1) * n_rep;
 #pragma unroll
-    for (int hh = 0; hh < 16; ++hh) {
-        const int v = u * n_rep + hh;
-        if (v < v_end) {
-            const float val = (hh < n_rep) ? acc[hh] : 0.0f;
-            const int m = 8 * (v / 4) + 4 * hf + (v % 4);  // head slot = MFMA row
+    for (int v = 0; v < 8; ++v) {
+        const int hh = 8 * (v / 4) + 4 * hf + (v % 4);  // head slot held in acc[v] by this half
+        const int vv = u * n_rep + hh;
+        if (vv < vv_end) {
+            const float val = (hh < n_rep && g < H_kv) ? acc[v] : 0.0f;
+            const int m = 8 * (vv / 4) + 4 * ghf + (vv % 4);  // row of the score MFMA
             const bf16_t hi = f32_to_bf16(val);
             const bf16_t lo = f32_to_bf16(val - bf16_to_f32(hi));
-            base[(size_t)(khf * 32 + m) * 8] = hi;
-            base[part_stride + (size_t)(khf * 32 + m) * 8] = lo;
+            base[(size_t)m * 8] = hi;
+            base[part_stride + (size_t)m * 8] = lo;
         }
     }
 }
@@ -185,10 +180,17 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restric
     const int n = lane & 31, hf = lane >> 5;
     const int F = r_k / 16;
 
-    // stage this block's P fragments (hi and lo parts) in LDS
+    // stage this block's P fragments (hi and lo parts) in LDS, eight 16 B loads in flight per thread
     {
         const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
-        for (int e = threadIdx.x; e < 2 * F8 * 64; e += 256) Pl[e] = src[e];
+        const int total = 2 * F8 * 64;  // a multiple of 4 * 256
+        for (int e0 = threadIdx.x; e0 < total; e0 += 4 * 256) {
+            u32x4_t tmp[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tmp[j] = src[e0 + j * 256];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Pl[e0 + j * 256] = tmp[j];
+        }
     }
     __syncthreads();
 
@@ -196,42 +198,60 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restric
     const int n_tiles = (L + 31) / 32;
     const int tile_begin = blockIdx.x * tiles_per_wg;
     const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
-    for (int tile = tile_begin + w; tile < tile_end; tile += 4) {
+    const int n_steps = F8 / 8;  // steps of 8 fragments per tile
+    // 16 B pieces of a token's row for one step; fragments beyond the rank meet zero P fragments, so the
+    // address is only clamped, never skipped: the loop body is straight-line code
+    auto load_step = [&](int tile, int step, u32x4_t (&a)[8]) __attribute__((always_inline)) {
         const int t = tile * 32 + n;
-        const int t_ld = t < L ? t : L - 1;
-        const u32x4_t *row = reinterpret_cast<const u32x4_t *>(Ab + (size_t)t_ld * r_k) + hf;  // 16 B units
-        f32x16_t acc;
+        const u32x4_t *row = reinterpret_cast<const u32x4_t *>(Ab + (size_t)(t < L ? t : L - 1) * r_k) + hf;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-        for (int f0 = 0; f0 < F8; f0 += 8) {
-            u32x4_t a[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (f0 + j < F)
-                    a[j] = row[2 * (f0 + j)];
-                else
-                    a[j] = u32x4_t{0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const u32x4_t ph = Pl[(f0 + j) * 64 + lane];
-                const u32x4_t pl = Pl[(F8 + f0 + j) * 64 + lane];
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph),
-                                                              __builtin_bit_cast(bf16x8_t, a[j]), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl),
-                                                              __builtin_bit_cast(bf16x8_t, a[j]), acc, 0, 0, 0);
-            }
+        for (int j = 0; j < 8; ++j) {
+            const int f = step * 8 + j;
+            a[j] = row[2 * (f < F ? f : F - 1)];
         }
-        if (t < L) {
+    };
+    int tile = tile_begin + w;
+    if (tile >= tile_end) return;
+    u32x4_t a_cur[8], a_nxt[8];
+    load_step(tile, 0, a_cur);
+    f32x16_t acc_h, acc_l;  // separate chains for the high parts and the remainders of P
 #pragma unroll
-            for (int u = 0; u < GPH; ++u) {
-                float best = acc[u * N_REP];
+    for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
+    int step = 0;
+    while (true) {
+        // pieces of the next step (of this tile, or the first of the wavefront's next tile) before this step's MFMAs
+        const bool last_step = step + 1 == n_steps;
+        const int tile_n = last_step ? tile + 4 : tile, step_n = last_step ? 0 : step + 1;
+        load_step(tile_n < tile_end ? tile_n : tile, step_n, a_nxt);
 #pragma unroll
-                for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc[u * N_REP + hh]);
-                const int g = blk * 2 * GPH + hf * GPH + u;
-                if (g < H_kv) S[((size_t)b * H_kv + g) * L + t] = scale * best;
-            }
+        for (int j = 0; j < 8; ++j) {
+            const u32x4_t ph = Pl[(step * 8 + j) * 64 + lane];
+            const u32x4_t pl = Pl[(F8 + step * 8 + j) * 64 + lane];
+            acc_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph),
+                                                            __builtin_bit_cast(bf16x8_t, a_cur[j]), acc_h, 0, 0, 0);
+            acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl),
+                                                            __builtin_bit_cast(bf16x8_t, a_cur[j]), acc_l, 0, 0, 0);
         }
+        if (last_step) {
+            const int t = tile * 32 + n;
+            if (t < L) {
+#pragma unroll
+                for (int u = 0; u < GPH; ++u) {
+                    float best = acc_h[u * N_REP] + acc_l[u * N_REP];
+#pragma unroll
+                    for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
+                    const int g = blk * 2 * GPH + hf * GPH + u;
+                    if (g < H_kv) S[((size_t)b * H_kv + g) * L + t] = scale * best;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
+            if (tile_n >= tile_end) break;
+        }
+        tile = tile_n;
+        step = step_n;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a_cur[j] = a_nxt[j];
     }
 }
 
@@ -239,8 +259,8 @@ static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
 {
     const int n_rep = s.H_q / s.H_kv;
     const bool rep_ok = (n_rep >= 1 && n_rep <= 8) || n_rep == 16;
-    return s.dtype == XKV_BF16 && rep_ok && s.r_k % 16 == 0 && (((uintptr_t)A_k) & 15u) == 0 && s.r_k <= 2048 &&
-           (size_t)s.H_q * (s.d_h + 1) * sizeof(float) <= 60 * 1024;
+    return s.dtype == XKV_BF16 && rep_ok && s.r_k % 16 == 0 && s.d_h % 16 == 0 && (((uintptr_t)A_k) & 15u) == 0 &&
+           s.r_k <= 2048;
 }
 
 static hipError_t launch_score_generic(const xkv_shape &s, const Plan &p, int layer, const void *A_k,
@@ -267,11 +287,14 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
 {
     const int nblk = mfma_blocks(s.H_kv, N_REP);
     const int n_tiles = (s.L + 31) / 32;
-    // enough workgroups to fill the chip several times over, but at least one tile per wavefront
-    long long total_tiles = (long long)n_tiles * s.batch * nblk;
-    int tiles_per_wg = (int)(total_tiles / 2048);
-    tiles_per_wg = tiles_per_wg < 4 ? 4 : (tiles_per_wg > 64 ? 64 : tiles_per_wg);
+    // about two workgroups per compute unit in a single round, each streaming one contiguous range of a
+    // sequence (staging P costs a fixed 2 KiB per rank-16 fragment, so fewer, longer workgroups win)
+    const int pairs = s.batch * nblk;
+    const int wgs_per_pair = pairs >= 512 ? 1 : 512 / pairs;
+    int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
+    tiles_per_wg = tiles_per_wg < 4 ? 4 : tiles_per_wg;
     tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;
+    if (const char *e = getenv("XKV_TPW")) tiles_per_wg = atoi(e);  // TUNING ONLY
     const size_t lds = (size_t)2 * F8 * 64 * 16;
     static bool attr_set = false;
     if (!attr_set) {
@@ -289,14 +312,13 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, hipStream_t st)
 {
-    if (!score_mfma_ok(s, A_k)) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, st);
+    if (!score_mfma_ok(s, A_k) || ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) != 0) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, st);
     const int n_rep = s.H_q / s.H_kv;
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;
     const int gph = mfma_gph(n_rep), nblk = mfma_blocks(s.H_kv, n_rep);
     bf16_t *Pfrag = (bf16_t *)P_ws;
-    dim3 pgrid((F8 * 16 * 2 * gph * nblk + 255) / 256, s.batch), block(256);
-    const size_t q_lds = (size_t)s.H_q * (s.d_h + 1) * sizeof(float);
-    hipLaunchKernelGGL(project_q_frag_kernel, pgrid, block, q_lds, st, (const bf16_t *)B_k, (const bf16_t *)q, Pfrag, s.G,
+    dim3 pgrid(((F8 / 2) * 2 * gph * nblk + 3) / 4, s.batch), block(256);
+    hipLaunchKernelGGL(project_q_frag_kernel, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q, Pfrag, s.G,
                        layer, s.r_k, s.H_kv, s.H_q, s.d_h, F8);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
