@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise 1 GiB copy kernel three times (reference point for hardware counters)")
     return ap.parse_args()
 
 
@@ -93,6 +95,14 @@ def main():
     if w.n_groups * group_bytes < (2 << 30):
         copies = int(np.ceil((2 << 30) / (w.n_groups * group_bytes)))
     n_sets = w.n_groups * copies
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)   # an elementwise kernel that reads 1 GiB and writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     t0 = time.perf_counter()
     groups = [synth.make_group_device(w, args.seed + 1000 * s) for s in range(n_sets)]
@@ -158,13 +168,50 @@ def main():
     stage_bytes = {"score": bytes_score, "topk": bytes_topk, "gather_attend": bytes_gather}
     stages = {kname: {"ms_per_layer": round(ms, 5), "alg_bytes": stage_bytes[kname],
                       "GBps": round(stage_bytes[kname] / (ms * 1e-3) / 1e9, 1)} for kname, ms in stage_ms.items()}
-    dom = max(("score", "gather_attend"), key=lambda kname: stage_ms[kname])
-    achieved = stage_bytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
-    roofline = {"kernel": {"score": "score kernel (xkv_score stage)",
-                           "gather_attend": "gather-reconstruct + sparse attention kernel (xkv_gather_attend stage)"}[dom],
+    # duration of the two big kernels alone: the library records an event pair around the kernel launch
+    def kernel_ms(stage_id, call):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        ev1.record()                      # creates the HIP events; the library re-records them
+        torch.cuda.synchronize()
+        xb.xkv_profile_kernel(stage_id, ev0.cuda_event, ev1.cuda_event)
+        total, count = 0.0, 0
+        for s in range(min(n_sets, w.n_groups)):
+            for l in range(w.G):
+                call(s, l)
+                torch.cuda.synchronize()
+                total += ev0.elapsed_time(ev1)
+                count += 1
+        xb.xkv_profile_kernel(stage_id, None, None)
+        return total / count
+
+    kern_ms = {
+        "score": kernel_ms(xb.STAGE_SCORE, lambda s, l: xb.xkv_score(shape, l, groups[s]["A_k"], groups[s]["B_k"],
+                                                                     qs[s][l], S, ws)),
+        "gather_attend": kernel_ms(xb.STAGE_GATHER_ATTEND,
+                                   lambda s, l: xb.xkv_gather_attend(shape, l, groups[s]["A_k"], groups[s]["A_v"],
+                                                                     groups[s]["B_k"], groups[s]["B_v"], qs[s][l],
+                                                                     idx, out, ws)),
+    }
+    # algorithmic bytes of the kernels alone (the projection / packing pre-passes read B, not these kernels)
+    kern_bytes = {"score": w.batch * (e * w.L * w.r_k + 4 * w.H_kv * w.L),
+                  "gather_attend": w.batch * e * w.H_kv * w.k * (w.r_k + w.r_v)}
+    for kname in kern_ms:
+        stages[kname]["kernel_ms"] = round(kern_ms[kname], 5)
+        stages[kname]["kernel_GBps"] = round(kern_bytes[kname] / (kern_ms[kname] * 1e-3) / 1e9, 1)
+    dom = max(("score", "gather_attend"), key=lambda kname: kern_ms[kname])
+    achieved = kern_bytes[dom] / (kern_ms[dom] * 1e-3) / 1e9
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{dom}_{args.workload}.txt")
+    if os.path.exists(tfile) and not over:
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(float(line.split(":")[1]))
+    roofline = {"kernel": {"score": "score_mfma_kernel (low-rank score stream + GQA max-pool)",
+                           "gather_attend": "gather_attend_mfma_kernel (gather-reconstruct + sparse attention)"}[dom],
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "alg_bytes_per_launch": stage_bytes[dom], "ms_per_launch": round(stage_ms[dom], 5)}
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "alg_bytes_per_launch": kern_bytes[dom], "ms_per_launch": round(kern_ms[dom], 5)}
 
     # ---------------------------------------------------------------- dense baseline on the uncompressed cache
     dense = None

@@ -121,6 +121,14 @@ XKV_API xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer_in_gr
 XKV_API xkv_status xkv_reconstruct(const xkv_shape *shape, int32_t layer_in_group, const void *A, const void *B,
                                    int32_t r, void *X_out, void *hip_stream);
 
+/* Measurement aid for callers that want the duration of one kernel rather than of a whole call.
+ * Not part of the method.  For stage = 0 (low-rank score kernel), 1 (gather-reconstruct + sparse
+ * attention kernel) or 2 (dense decode kernel), every later call that launches that kernel records
+ * start_event on the call's stream right before the launch and stop_event right after it.  Both are
+ * hipEvent_t created by the caller with timing enabled (HOST handles, passed as void*); NULL for
+ * either switches the recording off.  Process-wide state; not thread safe. */
+XKV_API xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event);
+
 /* Human-readable name of a status code (static storage). */
 XKV_API const char *xkv_status_string(xkv_status status);
 

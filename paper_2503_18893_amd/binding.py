@@ -18,7 +18,7 @@ XKV_F32, XKV_BF16 = 0, 1
 DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
 
 ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_dense_decode", "xkv_score", "xkv_topk",
-                "xkv_gather_attend", "xkv_reconstruct", "xkv_status_string", "xkv_version")
+                "xkv_gather_attend", "xkv_reconstruct", "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
 class XkvError(RuntimeError):
@@ -80,10 +80,11 @@ def load() -> ctypes.CDLL:
         lib.xkv_topk.argtypes = [sp, vp, vp, vp, sz, vp]
         lib.xkv_gather_attend.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_reconstruct.argtypes = [sp, i32, vp, vp, i32, vp, vp]
+        lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:7]:
+        for name in ENTRY_POINTS[:8]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -155,3 +156,13 @@ def xkv_gather_attend(shape, layer_in_group, A_k, A_v, B_k, B_v, q, idx, out, wo
 def xkv_reconstruct(shape, layer_in_group, A, B, r, X_out, stream=None):
     _check(load().xkv_reconstruct(ctypes.byref(shape.c()), layer_in_group, _ptr(A), _ptr(B), r, _ptr(X_out),
                                   _stream(stream)), "xkv_reconstruct")
+
+
+STAGE_SCORE, STAGE_GATHER_ATTEND, STAGE_DENSE = 0, 1, 2
+
+
+def xkv_profile_kernel(stage, start_event=None, stop_event=None):
+    """start_event / stop_event: hipEvent_t handles as integers (e.g. torch.cuda.Event(...).cuda_event), or None."""
+    a = ctypes.c_void_p(int(start_event)) if start_event else None
+    b = ctypes.c_void_p(int(stop_event)) if stop_event else None
+    _check(load().xkv_profile_kernel(stage, a, b), "xkv_profile_kernel")

@@ -303,12 +303,14 @@ static hipError_t launch_dense_generic(const xkv_shape &s, const Plan &p, const 
     hipLaunchKernelGGL((dense_generic_kernel<T, JP>), grid, block, 0, st, (const T *)K, (const T *)V,           \
                        (const T *)q, part_o, part_ml, s.L, s.H_kv, s.H_q, s.d_h, p.dense_splits, p.dense_chunk, \
                        p.scale)
+    profile_begin(2, st);
     if (s.d_h <= 64)
         XKV_DENSE_LAUNCH(1);
     else if (s.d_h <= 128)
         XKV_DENSE_LAUNCH(2);
     else
         XKV_DENSE_LAUNCH(4);
+    profile_end(2, st);
 #undef XKV_DENSE_LAUNCH
     return hipGetLastError();
 }
@@ -320,9 +322,11 @@ hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const 
 {
     if (p.dense_mfma && ((((uintptr_t)K | (uintptr_t)V | (uintptr_t)q)) & 15u) == 0) {
         dim3 grid(p.dense_splits, s.H_kv, s.batch), block(256);
+        profile_begin(2, st);
         hipLaunchKernelGGL(dense_mfma_kernel, grid, block, 0, st, (const bf16_t *)K, (const bf16_t *)V,
                            (const bf16_t *)q, part_o, part_ml, s.L, s.H_kv, s.H_q, p.dense_splits, p.dense_chunk,
                            p.scale);
+        profile_end(2, st);
         return hipGetLastError();
     }
     if (s.dtype == XKV_F32) return launch_dense_generic<float>(s, p, K, V, q, part_o, part_ml, st);

@@ -141,12 +141,14 @@ static hipError_t launch_generic(const xkv_shape &s, const Plan &p, int layer, c
     hipLaunchKernelGGL((gather_attend_generic_kernel<T, JP>), grid, block, 0, st, (const T *)A_k, (const T *)A_v,  \
                        (const T *)B_k, (const T *)B_v, (const T *)q, idx, part_o, part_ml, s.G, layer, s.L, s.r_k, \
                        s.r_v, s.H_kv, s.H_q, s.d_h, s.k, p.sr_splits, p.sr_chunk, p.scale)
+    profile_begin(1, st);
     if (s.d_h <= 64)
         XKV_GA_LAUNCH(1);
     else if (s.d_h <= 128)
         XKV_GA_LAUNCH(2);
     else
         XKV_GA_LAUNCH(4);
+    profile_end(1, st);
 #undef XKV_GA_LAUNCH
     return hipGetLastError();
 }

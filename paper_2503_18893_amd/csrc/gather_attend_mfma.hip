@@ -394,9 +394,11 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
         attr_set = true;
     }
     dim3 grid((unsigned)((long long)p.sr_splits * s.H_kv * s.batch));
+    profile_begin(1, st);
     hipLaunchKernelGGL(gather_attend_mfma_kernel, grid, block, lds, st, (const bf16_t *)A_k, (const bf16_t *)A_v,
                        (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, part_o, part_ml, s.L, s.r_k, s.r_v, s.H_kv,
                        s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v, p.scale);
+    profile_end(1, st);
     return hipGetLastError();
 }
 

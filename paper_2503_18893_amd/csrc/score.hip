@@ -2,8 +2,6 @@
 //   p_h = B^K_{l,rho(h)} q_h                      (Eq. 3 regrouped by associativity)
 //   s[h,t] = scale * A^K[t,:] . p_h               (App. B.1 Alg. 2, scaled scores, per token)
 //   S[g,t] = max_{h: rho(h)=g} s[h,t]             (App. B.1 Alg. 2, GQA pooling)
-#include <cstdlib>
-
 #include "xkv_common.h"
 
 namespace xkv {
@@ -270,13 +268,17 @@ static hipError_t launch_score_generic(const xkv_shape &s, const Plan &p, int la
     if (s.dtype == XKV_F32) {
         hipLaunchKernelGGL(project_q_kernel<float>, pgrid, block, 0, st, (const float *)B_k, (const float *)q, P, s.G,
                            layer, s.r_k, s.H_kv, s.H_q, s.d_h);
+        profile_begin(0, st);
         hipLaunchKernelGGL(score_generic_kernel<float>, grid, block, 0, st, (const float *)A_k, P, S, s.L, s.r_k,
                            s.H_kv, s.H_q, p.scale);
+        profile_end(0, st);
     } else {
         hipLaunchKernelGGL(project_q_kernel<bf16_t>, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q, P,
                            s.G, layer, s.r_k, s.H_kv, s.H_q, s.d_h);
+        profile_begin(0, st);
         hipLaunchKernelGGL(score_generic_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)A_k, P, S, s.L, s.r_k,
                            s.H_kv, s.H_q, p.scale);
+        profile_end(0, st);
     }
     return hipGetLastError();
 }
@@ -294,7 +296,6 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
     int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
     tiles_per_wg = tiles_per_wg < 4 ? 4 : tiles_per_wg;
     tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;
-    if (const char *e = getenv("XKV_TPW")) tiles_per_wg = atoi(e);  // TUNING ONLY
     const size_t lds = (size_t)2 * F8 * 64 * 16;
     static bool attr_set = false;
     if (!attr_set) {
@@ -304,8 +305,10 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
         attr_set = true;
     }
     dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
+    profile_begin(0, st);
     hipLaunchKernelGGL(score_mfma_kernel<N_REP>, grid, block, lds, st, A_k, Pfrag, S, s.L, s.r_k, s.H_kv, F8,
                        tiles_per_wg, p.scale);
+    profile_end(0, st);
     return hipGetLastError();
 }
 

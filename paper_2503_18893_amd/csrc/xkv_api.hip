@@ -7,6 +7,8 @@
 
 namespace xkv {
 
+ProfileEvents g_profile[3] = {};
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
@@ -201,6 +203,14 @@ xkv_status xkv_reconstruct(const xkv_shape *shape, int32_t layer, const void *A,
     if (!A || !B || !X_out || r < 1 || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
     if (shape->batch == 0) return XKV_OK;
     return hip_status(launch_reconstruct(*shape, layer, A, B, r, X_out, (hipStream_t)hip_stream));
+}
+
+xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event)
+{
+    if (stage < 0 || stage > 2) return XKV_ERR_INVALID_ARG;
+    g_profile[stage].start = (start_event && stop_event) ? (hipEvent_t)start_event : nullptr;
+    g_profile[stage].stop = (start_event && stop_event) ? (hipEvent_t)stop_event : nullptr;
+    return XKV_OK;
 }
 
 const char *xkv_status_string(xkv_status status)

@@ -79,6 +79,20 @@ constexpr int kStateWords = 8;   // per row: (prefix, k_rem) for each resolved l
 
 xkv_status make_plan(const xkv_shape &s, Plan &p);
 
+// Optional event pair recorded around the main kernel of a stage (0 score, 1 gather-attend, 2 dense).
+struct ProfileEvents {
+    hipEvent_t start, stop;
+};
+extern ProfileEvents g_profile[3];
+inline void profile_begin(int stage, hipStream_t st)
+{
+    if (g_profile[stage].start && g_profile[stage].stop) (void)hipEventRecord(g_profile[stage].start, st);
+}
+inline void profile_end(int stage, hipStream_t st)
+{
+    if (g_profile[stage].start && g_profile[stage].stop) (void)hipEventRecord(g_profile[stage].stop, st);
+}
+
 // Kernel launchers (each enqueues on `st`; shapes were validated by the caller).
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, hipStream_t st);
