@@ -1,14 +1,16 @@
 // Per-row ArgTopK by radix select on the monotone 32-bit image of the fp32 scores
-// (App. B.1 Alg. 2, top-k step, applied per token).  Bit-exact, deterministic, no global atomics.
+// (App. B.1 Alg. 2, top-k step, applied per token).  Bit-exact and deterministic.
 //
-// A row of L scores is split into chunks; one workgroup owns one (row, chunk).  Four passes
-// resolve the 32-bit key of the k-th largest element 8 bits at a time: each pass histograms,
-// per chunk, the current digit of the keys that still match the resolved prefix.  The next
-// launch sums the per-chunk histograms of its row (every workgroup redundantly, so that no
-// cross-workgroup wait exists), finds the bin holding the k-th element and refines the prefix.
-// The last launch knows the threshold key T and how many keys equal to T are still needed
-// (ties go to the smaller token id), derives each chunk's output offset from the stored
-// histograms and writes the selected ids in ascending order using wavefront ballots.
+// A row of L scores is split into chunks; one workgroup owns one (row, chunk).  Four passes resolve the
+// 32-bit key of the k-th largest element 8 bits at a time.  A pass histograms, per chunk, the current
+// digit of the keys that still match the resolved prefix, keeps the chunk's histogram and adds it to the
+// row's histogram with integer atomics (order-independent, so the result is deterministic).  Launch
+// boundaries are the only synchronisation: every workgroup of the next launch reads the row histogram
+// (1 KiB), finds the bin holding the k-th element, refines the prefix, and counts from its own chunk's
+// stored histogram how many of its keys are thereby known to lie above the threshold.  The last launch
+// knows the threshold key T and how many keys equal to T are still needed (ties go to the smaller token
+// id), sums the counts of the chunks before its own and writes the selected ids in ascending order with
+// wavefront ballots.
 #include "xkv_common.h"
 
 namespace xkv {
@@ -18,29 +20,45 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Sum the per-chunk histograms of `level` for this row and find the bin b with
-// (#keys in bins above b) < k_rem <= (#keys in bins >= b).  All 256 threads take part.
-__device__ __forceinline__ void resolve_level(const uint32_t *__restrict__ hist_row, int chunks, int level,
-                                              uint32_t k_rem, uint32_t *sh /* >= 8 words */, uint32_t &digit,
-                                              uint32_t &k_rem_out)
+// scratch arrays (uint32 words), carved by launch_topk
+struct TopkScratch {
+    uint32_t *hist;      // [rows][chunks][4][256] per-chunk digit histograms (level 3: suffix sums)
+    uint32_t *state;     // [rows][8]  (prefix, k_rem) after each level
+    uint32_t *row_hist;  // [rows][4][256] per-row digit histograms (level 0 zeroed by topk_init_kernel)
+    uint32_t *chunk_gt;  // [rows][chunks] keys of the chunk above the threshold by levels 0..2
+};
+
+__global__ void topk_init_kernel(uint32_t *row_hist, int rows)
 {
-    const int b = threadIdx.x, lane = lane_id(), w = wave_id();
-    uint32_t c = 0;
-    for (int ch = 0; ch < chunks; ++ch) c += hist_row[((size_t)ch * kTopkLevels + level) * kTopkBins + b];
-    uint32_t s = c;  // inclusive suffix sum inside the wavefront
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;  // level 0 of every row
+    if (i < rows * kTopkBins) row_hist[(size_t)(i / kTopkBins) * kTopkLevels * kTopkBins + i % kTopkBins] = 0;
+}
+
+// Inclusive suffix sum over the 256 bins held one per thread.  All 256 threads take part.
+__device__ __forceinline__ uint32_t suffix_sum_256(uint32_t c, uint32_t *sh /* >= 4 words */)
+{
+    const int lane = lane_id(), w = wave_id();
+    uint32_t s = c;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t n = __shfl_down(s, off, kWave);
-        if (lane + off < kWave) s += n;
+        const uint32_t nb = __shfl_down(s, off, kWave);
+        if (lane + off < kWave) s += nb;
     }
     __syncthreads();  // sh may still be read by a previous use
     if (lane == 0) sh[w] = s;
     __syncthreads();
-    uint32_t higher = 0;
-    for (int ww = w + 1; ww < 4; ++ww) higher += sh[ww];
-    const uint32_t incl = s + higher, above = incl - c;
+    for (int ww = w + 1; ww < 4; ++ww) s += sh[ww];
+    return s;
+}
+
+// From the row histogram of `level`: the bin b with (#keys in bins above b) < k_rem <= (#keys in bins >= b).
+__device__ __forceinline__ void resolve_level(const uint32_t *__restrict__ row_hist_level, uint32_t k_rem,
+                                              uint32_t *sh /* >= 8 words */, uint32_t &digit, uint32_t &k_rem_out)
+{
+    const uint32_t c = row_hist_level[threadIdx.x];
+    const uint32_t incl = suffix_sum_256(c, sh), above = incl - c;
     if (above < k_rem && k_rem <= incl) {
-        sh[4] = (uint32_t)b;
+        sh[4] = threadIdx.x;
         sh[5] = k_rem - above;
     }
     __syncthreads();
@@ -49,27 +67,38 @@ __device__ __forceinline__ void resolve_level(const uint32_t *__restrict__ hist_
 }
 
 template <int LEVEL>
-__global__ __launch_bounds__(256) void topk_hist_kernel(const float *__restrict__ S, uint32_t *__restrict__ hist,
-                                                        uint32_t *__restrict__ state, int L, int k, int chunks,
-                                                        int chunk)
+__global__ __launch_bounds__(256) void topk_hist_kernel(const float *__restrict__ S, TopkScratch ws, int L, int k,
+                                                        int chunks, int chunk)
 {
     __shared__ uint32_t sh_hist[kTopkBins];
     __shared__ uint32_t sh_misc[8];
     const int row = blockIdx.y, c = blockIdx.x;
-    uint32_t *hist_row = hist + (size_t)row * chunks * kTopkLevels * kTopkBins;
+    uint32_t *row_hist = ws.row_hist + (size_t)row * kTopkLevels * kTopkBins;
+    uint32_t *my_hist = ws.hist + ((size_t)row * chunks + c) * kTopkLevels * kTopkBins;
     uint32_t prefix = 0, k_rem = (uint32_t)k;
-    if constexpr (LEVEL > 0) {
+    if constexpr (LEVEL == 0) {
+        // the row histograms of the later levels start at zero (nobody adds to them before the next launch)
+        if (c == 0)
+            for (int lv = 1; lv < kTopkLevels; ++lv) row_hist[lv * kTopkBins + threadIdx.x] = 0;
+    } else {
         if constexpr (LEVEL > 1) {
-            prefix = state[(size_t)row * kStateWords + 2 * (LEVEL - 2)];
-            k_rem = state[(size_t)row * kStateWords + 2 * (LEVEL - 2) + 1];
+            prefix = ws.state[(size_t)row * kStateWords + 2 * (LEVEL - 2)];
+            k_rem = ws.state[(size_t)row * kStateWords + 2 * (LEVEL - 2) + 1];
         }
         uint32_t digit, k_new;
-        resolve_level(hist_row, chunks, LEVEL - 1, k_rem, sh_misc, digit, k_new);
+        resolve_level(row_hist + (LEVEL - 1) * kTopkBins, k_rem, sh_misc, digit, k_new);
         prefix = (prefix << 8) | digit;
         k_rem = k_new;
         if (c == 0 && threadIdx.x == 0) {
-            state[(size_t)row * kStateWords + 2 * (LEVEL - 1)] = prefix;
-            state[(size_t)row * kStateWords + 2 * (LEVEL - 1) + 1] = k_rem;
+            ws.state[(size_t)row * kStateWords + 2 * (LEVEL - 1)] = prefix;
+            ws.state[(size_t)row * kStateWords + 2 * (LEVEL - 1) + 1] = k_rem;
+        }
+        // keys of this chunk that matched the old prefix and have a larger digit lie above the threshold
+        const uint32_t mine = my_hist[(LEVEL - 1) * kTopkBins + threadIdx.x];
+        const uint32_t incl = suffix_sum_256(threadIdx.x > digit ? mine : 0u, sh_misc);
+        if (threadIdx.x == 0) {
+            uint32_t *cg = ws.chunk_gt + (size_t)row * chunks + c;
+            *cg = (LEVEL == 1 ? 0u : *cg) + incl;
         }
     }
     sh_hist[threadIdx.x] = 0;
@@ -104,12 +133,17 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(const float *__restrict_
         }
     }
     __syncthreads();
-    hist_row[((size_t)c * kTopkLevels + LEVEL) * kTopkBins + threadIdx.x] = sh_hist[threadIdx.x];
+    const uint32_t cnt = sh_hist[threadIdx.x];
+    if (cnt != 0) atomicAdd(&row_hist[LEVEL * kTopkBins + threadIdx.x], cnt);
+    if constexpr (LEVEL < 3) {
+        my_hist[LEVEL * kTopkBins + threadIdx.x] = cnt;
+    } else {
+        // last level: keep the suffix sums, so that "keys above digit d" is one load for the writer
+        my_hist[LEVEL * kTopkBins + threadIdx.x] = suffix_sum_256(cnt, sh_misc);
+    }
 }
 
-__global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict__ S,
-                                                         const uint32_t *__restrict__ hist,
-                                                         const uint32_t *__restrict__ state,
+__global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict__ S, TopkScratch ws,
                                                          int32_t *__restrict__ idx_out, int L, int k, int chunks,
                                                          int chunk)
 {
@@ -117,25 +151,23 @@ __global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict
     __shared__ uint32_t sh_red[2][4];
     __shared__ uint32_t sh_cnt[2][4];
     const int row = blockIdx.y, c = blockIdx.x;
-    const uint32_t *hist_row = hist + (size_t)row * chunks * kTopkLevels * kTopkBins;
-    uint32_t prefix = state[(size_t)row * kStateWords + 4];
-    uint32_t k_rem = state[(size_t)row * kStateWords + 5];
+    const uint32_t *row_hist = ws.row_hist + (size_t)row * kTopkLevels * kTopkBins;
+    const uint32_t *hist_row = ws.hist + (size_t)row * chunks * kTopkLevels * kTopkBins;
+    const uint32_t prefix = ws.state[(size_t)row * kStateWords + 4];
+    const uint32_t k_rem = ws.state[(size_t)row * kStateWords + 5];
     uint32_t digit, need_eq;
-    resolve_level(hist_row, chunks, 3, k_rem, sh_misc, digit, need_eq);
+    resolve_level(row_hist + 3 * kTopkBins, k_rem, sh_misc, digit, need_eq);
     const uint32_t T = (prefix << 8) | digit;  // key of the k-th largest element
 
-    // selected elements that precede this chunk: keys above T (found level by level) and keys equal to T
+    // selected keys of the chunks before this one: above T (levels 0..2 counted earlier, level 3 from the
+    // stored suffix sums) and equal to T
     const int lane = lane_id(), w = wave_id();
-    const uint32_t b = threadIdx.x;
     uint32_t gt = 0, eq = 0;
-    for (int ch = 0; ch < c; ++ch) {
-        const uint32_t *h = hist_row + (size_t)ch * kTopkLevels * kTopkBins;
-#pragma unroll
-        for (int lv = 0; lv < kTopkLevels; ++lv) {
-            const uint32_t dl = (T >> (24 - 8 * lv)) & 0xFFu;
-            if (b > dl) gt += h[lv * kTopkBins + b];
-            if (lv == 3 && b == dl) eq += h[lv * kTopkBins + b];
-        }
+    for (int ch = threadIdx.x; ch < c; ch += 256) {
+        const uint32_t *h3 = hist_row + ((size_t)ch * kTopkLevels + 3) * kTopkBins;
+        const uint32_t ge = h3[digit], above = digit < 255u ? h3[digit + 1] : 0u;
+        gt += ws.chunk_gt[(size_t)row * chunks + ch] + above;
+        eq += ge - above;
     }
     for (int off = 32; off > 0; off >>= 1) {
         gt += __shfl_xor(gt, off, kWave);
@@ -209,13 +241,20 @@ __global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
                        uint32_t *state, hipStream_t st)
 {
+    // `state` region: [rows][8] state words, then row histograms [rows][4][256], then chunk_gt [rows][chunks]
+    TopkScratch ws;
+    ws.hist = hist;
+    ws.state = state;
+    ws.row_hist = state + (size_t)p.rows * kStateWords;
+    ws.chunk_gt = ws.row_hist + (size_t)p.rows * kTopkLevels * kTopkBins;
+    hipLaunchKernelGGL(topk_init_kernel, dim3((p.rows * kTopkBins + 255) / 256), dim3(256), 0, st, ws.row_hist,
+                       p.rows);
     dim3 grid(p.topk_chunks, p.rows), block(256);
-    hipLaunchKernelGGL(topk_hist_kernel<0>, grid, block, 0, st, S, hist, state, s.L, s.k, p.topk_chunks, p.topk_chunk);
-    hipLaunchKernelGGL(topk_hist_kernel<1>, grid, block, 0, st, S, hist, state, s.L, s.k, p.topk_chunks, p.topk_chunk);
-    hipLaunchKernelGGL(topk_hist_kernel<2>, grid, block, 0, st, S, hist, state, s.L, s.k, p.topk_chunks, p.topk_chunk);
-    hipLaunchKernelGGL(topk_hist_kernel<3>, grid, block, 0, st, S, hist, state, s.L, s.k, p.topk_chunks, p.topk_chunk);
-    hipLaunchKernelGGL(topk_write_kernel, grid, block, 0, st, S, hist, state, idx, s.L, s.k, p.topk_chunks,
-                       p.topk_chunk);
+    hipLaunchKernelGGL(topk_hist_kernel<0>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
+    hipLaunchKernelGGL(topk_hist_kernel<1>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
+    hipLaunchKernelGGL(topk_hist_kernel<2>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
+    hipLaunchKernelGGL(topk_hist_kernel<3>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
+    hipLaunchKernelGGL(topk_write_kernel, grid, block, 0, st, S, ws, idx, s.L, s.k, p.topk_chunks, p.topk_chunk);
     return hipGetLastError();
 }
 

@@ -37,7 +37,7 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     const int rows = p.rows > 0 ? p.rows : 1;
     const int want = ceil_div(1024, rows);  // aim at ~4 workgroups per compute unit
 
-    int chunks = clampi(want, 1, clampi(ceil_div(s.L, 2048), 1, 64));
+    int chunks = clampi(want, 1, clampi(ceil_div(s.L, 1024), 1, 128));
     p.topk_chunk = ceil_div(ceil_div(s.L, chunks), 256) * 256;
     p.topk_chunks = ceil_div(s.L, p.topk_chunk);
 
@@ -67,7 +67,9 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     p.off_hist = off;
     off = align_up(off + (size_t)rows * p.topk_chunks * kTopkLevels * kTopkBins * sizeof(uint32_t), 256);
     p.off_state = off;
-    off = align_up(off + (size_t)rows * kStateWords * sizeof(uint32_t), 256);
+    // per row: state words, the row's digit histograms, per-chunk counts of keys above the threshold
+    off = align_up(off + (size_t)rows * (kStateWords + kTopkLevels * kTopkBins + p.topk_chunks) * sizeof(uint32_t),
+                   256);
     p.off_part_o = off;
     off = align_up(off + b * s.H_q * (size_t)p.max_splits * s.d_h * sizeof(float), 256);
     p.off_part_ml = off;
