@@ -27,20 +27,38 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 constexpr int kMaxChunkTokens = 8192;  // selected tokens per workgroup (their ids sit in LDS)
-constexpr int kGroup = 8;  // fragments (of 16 ranks) per LDS stage: 8 x 4 KiB = 32 KiB, double-buffered
+constexpr int kGroup = 8;  // fragments (of 16 ranks) per LDS stage: 8 x 4 KiB = 32 KiB, three stages
 
 // Pack B_{l,g} (r x 128 slice of B_l) into MFMA fragment order:
 //   pack[f][db][hf*32 + c][e] = B[16f + 8hf + e][g*128 + db*32 + c],  zero beyond r.
-// Output per (sequence, KV head): F8k fragment rows for K then F8v for V, 4 KiB each, F8 = roundup(r/16, 8).
+// Output per (sequence, KV head): F8k fragment rows for K then F8v for V, 4 KiB each, F8 = roundup(r/16, 16).
 __global__ __launch_bounds__(256) void pack_b_kernel(const bf16_t *__restrict__ B_k, const bf16_t *__restrict__ B_v,
-                                                     u32x4_t *__restrict__ pack, int G, int layer, int r_k, int r_v,
-                                                     int H_kv, int F8k, int F8v)
+                                                     const bf16_t *__restrict__ q, u32x4_t *__restrict__ pack,
+                                                     int G, int layer, int r_k, int r_v, int H_kv, int H_q, int F8k,
+                                                     int F8v)
 {
     // one thread per (fragment f, half hf, dim block db, 4 columns): 8 rows x 8 B in, 4 lanes' 16 B pieces out
     const int g = blockIdx.y, b = blockIdx.z;
     const int d = H_kv * 128;
     const int item = blockIdx.x * 256 + threadIdx.x;
-    if (item >= (F8k + F8v) * 64) return;
+    if (item >= (F8k + F8v) * 64) {
+        // the last 512 items build the eight Q^T fragments of this (sequence, KV head), stored behind the B
+        // fragments: lane (head slot n, hf), position e of fragment (db, j) holds q[n][db*32 + 8(2j + e/4) + 4hf + e%4]
+        const int qi = item - (F8k + F8v) * 64;
+        if (qi >= 8 * 64) return;
+        const int lane = qi & 63, fj = qi >> 6, db = fj >> 1, j = fj & 1;
+        const int n = lane & 31, hf = lane >> 5, n_rep = H_q / H_kv;
+        const bf16_t *qh = q + ((size_t)b * H_q + (size_t)g * n_rep + (n < n_rep ? n : 0)) * 128;
+        u32x4_t raw;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const int e = 2 * e2;
+            const int dim = db * 32 + 8 * (2 * j + e / 4) + 4 * hf + e % 4;  // e and e+1 are adjacent dims
+            raw[e2] = n < n_rep ? *reinterpret_cast<const uint32_t *>(qh + dim) : 0u;
+        }
+        pack[((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(F8k + F8v) * 256 + qi] = raw;
+        return;
+    }
     const int c4 = item & 7, db = (item >> 3) & 3, hf = (item >> 5) & 1, fa = item >> 6;
     const bool is_v = fa >= F8k;
     const int f = is_v ? fa - F8k : fa;
@@ -52,8 +70,8 @@ __global__ __launch_bounds__(256) void pack_b_kernel(const bf16_t *__restrict__ 
         const int i = 16 * f + 8 * hf + e;
         wd[e] = i < r ? *reinterpret_cast<const uint64_t *>(src + (size_t)i * d) : 0ull;
     }
-    u32x4_t *dst = pack + ((size_t)b * H_kv + g) * (size_t)(F8k + F8v) * 256 + (size_t)(fa * 4 + db) * 64 + hf * 32 +
-                   c4 * 4;
+    u32x4_t *dst = pack + ((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(fa * 4 + db) * 64 +
+                   hf * 32 + c4 * 4;
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) {
         u32x4_t o;
@@ -75,35 +93,52 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t &c, int j)
     return __builtin_convertvector(x, bf16x8_t);
 }
 
-// One group of 8 fragment steps.  IS_K selects which product the fragments feed.
-// While the group is multiplied out of LDS buffer gg%2, the thread writes its slice of group gg+1's B
-// fragments (loaded one group earlier) into the other buffer, loads its slice of group gg+2 (bsrc2),
-// and loads the A pieces its lane needs in group gg+1 (rows an0/an1, fragments fn0.. of Fn).
-template <bool IS_K>
-__device__ __forceinline__ void run_group(f32x16_t (&acc)[2][4], u32x4_t (&areg)[kGroup][2], u32x4_t (&breg)[kGroup],
-                                          u32x4_t *Bl, const u32x4_t *bsrc2, int gg, int NG, const u32x4_t *an0,
-                                          const u32x4_t *an1, int fn0, int Fn, int tid, int lane)
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// 16 B per lane straight from global memory into LDS at lds_base + lane * 16 (lds_base is wave-uniform).
+// Issued as inline assembly on purpose: the compiler then does not tie later LDS reads of the *other*
+// buffers to this copy (it cannot tell the buffers apart and would drain the whole vector-memory queue before
+// every group); completion is awaited explicitly with XKV_WAIT_VMCNT before the barrier that publishes
+// the buffer.  The copy still counts as one outstanding vector-memory operation, which only makes the
+// compiler's own waits for register loads more conservative, never less.
+__device__ __forceinline__ void copy16_global_to_lds(const void *gptr, uint32_t lds_base)
 {
-    // Buffer gg%2 is complete and nobody still reads buffer (gg+1)%2.  The barrier orders LDS traffic only:
-    // the global loads in flight are this thread's own prefetch and must stay in flight across it.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory");
+}
+
+// s_waitcnt that only bounds the number of outstanding vector-memory operations (gfx9 encoding: vmcnt is
+// split over bits 3:0 and 15:14; expcnt and lgkmcnt are left at "no wait").
+#define XKV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (0xF << 8) | (((n) >> 4) << 14))
+
+constexpr int kGaWaves = 8;  // wavefronts per workgroup, 32 selected tokens each per tile
+
+// One group of 8 fragment steps out of LDS buffer `buf`.  IS_K selects which product the fragments feed,
+// SLOT0 (0 or 8) which half of the 16-deep A ring the group consumes.  Per step the thread
+//  - on even steps copies, global -> LDS without passing through registers, its 16 B of the same two steps
+//    of the group two groups on (source bsrc2, 512 threads x 16 B = two fragment rows),
+//  - multiplies the step's four B fragments (LDS) with its A piece (ring),
+//  - refills the ring entry with the A piece of the same step two groups on (row an0).
+template <bool IS_K, int SLOT0>
+__device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 * kGroup], const u32x4_t *Bl, int buf,
+                                          uint32_t dma_dst, const u32x4_t *bsrc2, const u32x4_t *an0, int fn0, int Fn,
+                                          int lane)
+{
+    // The copies into this buffer were issued two groups ago.  Everything this thread issued since then (one
+    // group: 4 copies and 8 A pieces) may stay in flight, plus the two A pieces that followed the last copy; then
+    // the barrier makes every wavefront's copies visible.  The barrier orders LDS only: prefetches stay in
+    // flight across it.
+    XKV_WAIT_VMCNT(kGroup / 2 + kGroup + 2);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    // Past the last group the "next" sources wrap around to valid memory (the packed B of the first groups,
-    // clamped token rows), so every load and LDS write below is unconditional: the group is one straight
-    // line of code and the wait counters stay exact.
-    (void)NG;
-    u32x4_t *bdst = Bl + ((gg + 1) & 1) * (kGroup * 256) + tid;
-    const u32x4_t *bcur = Bl + (gg & 1) * (kGroup * 256) + lane;
+    const u32x4_t *bcur = Bl + buf * (kGroup * 256) + lane;
     u32x4_t bf_cur[4], bf_nxt[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db) bf_cur[db] = bcur[db * 64];
 #pragma unroll
     for (int fl = 0; fl < kGroup; ++fl) {
-        bdst[fl * 256] = breg[fl];
-        breg[fl] = bsrc2[fl * 256];
-        const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, areg[fl][0]);
-        const bf16x8_t a1 = __builtin_bit_cast(bf16x8_t, areg[fl][1]);
+        if ((fl & 1) == 0) copy16_global_to_lds(bsrc2 + fl * 256, dma_dst + fl * 4096);
+        const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, areg[SLOT0 + fl]);
         if (fl + 1 < kGroup) {
 #pragma unroll
             for (int db = 0; db < 4; ++db) bf_nxt[db] = bcur[((fl + 1) * 4 + db) * 64];  // LDS reads one step ahead
@@ -111,37 +146,34 @@ __device__ __forceinline__ void run_group(f32x16_t (&acc)[2][4], u32x4_t (&areg)
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
             const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, bf_cur[db]);
-            if constexpr (IS_K) {  // (1) K^T tile: rows = head dims, columns = tokens
-                acc[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, a0, acc[0][db], 0, 0, 0);
-                acc[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, a1, acc[1][db], 0, 0, 0);
-            } else {  // (3) V^ tile: rows = tokens, columns = head dims
-                acc[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bf, acc[0][db], 0, 0, 0);
-                acc[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bf, acc[1][db], 0, 0, 0);
-            }
+            if constexpr (IS_K)  // (1) K^T tile: rows = head dims, columns = tokens
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, a0, acc[db], 0, 0, 0);
+            else  // (3) V^ tile: rows = tokens, columns = head dims
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bf, acc[db], 0, 0, 0);
         }
 #pragma unroll
         for (int db = 0; db < 4; ++db) bf_cur[db] = bf_nxt[db];
-        // the lane's A pieces for the same step of the next group, loaded into the registers just consumed
+        // the lane's A piece for the same step two groups on, loaded into the registers just consumed
         const int f = fn0 + fl < Fn ? fn0 + fl : 0;
-        areg[fl][0] = an0[2 * f];
-        areg[fl][1] = an1[2 * f];
-        __builtin_amdgcn_sched_barrier(0);  // keep each step's loads where they are written: they are the prefetch
+        areg[SLOT0 + fl] = an0[2 * f];
+        __builtin_amdgcn_sched_barrier(0);  // keep each step's memory operations where they are written
     }
 }
 
-// Software pipeline.  The work of a workgroup is a linear sequence of groups of 8 fragment steps:
-// per 256-token tile first the K groups, then the V groups.  While group gg is multiplied out of LDS
-// buffer gg%2, every thread (a) writes into the other buffer the slice of group gg+1's B fragments it
-// loaded one group earlier and loads its slice of group gg+2, and (b) loads, one group ahead, the 16 B
-// pieces of the gathered A rows its own lane will need.  One barrier per group.
-__global__ __launch_bounds__(256, 1) void gather_attend_mfma_kernel(
+// Software pipeline.  The work of a workgroup is a linear sequence of groups of 8 fragment steps, taken in
+// pairs: per 256-token tile first the K pairs, then the V pairs (ranks are padded to a multiple of 256 with
+// zero fragments).  While a group is multiplied out of one of three LDS buffers, every thread copies its
+// slice of the B fragments two groups on straight from global memory into the buffer that was read last,
+// and loads, two groups (16 steps) ahead, the 16 B pieces of the gathered A row its own lane will need.
+// Eight wavefronts of 32 tokens each: two share a SIMD, so one multiplies while the other waits for memory.
+__global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     const bf16_t *__restrict__ A_k, const bf16_t *__restrict__ A_v, const u32x4_t *__restrict__ pack,
     const bf16_t *__restrict__ q, const int32_t *__restrict__ idx, float *__restrict__ part_o,
-    float *__restrict__ part_ml, int L, int r_k, int r_v, int H_kv, int H_q, int k, int splits, int chunk, int F8k,
-    int F8v, float scale)
+    float *__restrict__ part_ml, int L, int r_k, int r_v, int H_kv, int H_q, int k, int splits, int chunk, int F16k,
+    int F16v, float scale)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    u32x4_t *Bl = reinterpret_cast<u32x4_t *>(smem_raw);  // [2][kGroup][4][64] 16-byte fragments = 64 KiB
+    u32x4_t *Bl = reinterpret_cast<u32x4_t *>(smem_raw);  // [3][kGroup][4][64] 16-byte fragments = 96 KiB
     // workgroup id -> (KV head fastest, so that a head's packed B stays in one XCD's L2), split, sequence
     const int g = blockIdx.x % H_kv;
     const int split = (blockIdx.x / H_kv) % splits;
@@ -150,54 +182,33 @@ __global__ __launch_bounds__(256, 1) void gather_attend_mfma_kernel(
     const int n = lane & 31, hf = lane >> 5;
     const int n_rep = H_q / H_kv;
     const int Fk = r_k / 16, Fv = r_v / 16;
-    const int GK = F8k / kGroup, GT = (F8k + F8v) / kGroup;
+    const int PK = F16k / (2 * kGroup), PT = (F16k + F16v) / (2 * kGroup);  // pairs of groups per tile: K, total
 
-    // Q^T fragments, kept in LDS (shared by the four wavefronts): lane (head slot n, hf), position e of
-    // fragment (db, j) holds q[n][db*32 + 8(2j + e/4) + 4hf + e%4]
-    u32x4_t *Ql = Bl + 2 * kGroup * 256;  // [8][64]
-    if (w == 0) {
-        const bf16_t *qh = q + ((size_t)b * H_q + (size_t)g * n_rep + (n < n_rep ? n : 0)) * 128;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                u32x4_t raw;
-#pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2) {
-                    const int e = 2 * e2;
-                    const int dim = db * 32 + 8 * (2 * j + e / 4) + 4 * hf + e % 4;  // e and e+1 are adjacent dims
-                    const uint32_t lo = n < n_rep ? qh[dim] : 0u, hi = n < n_rep ? qh[dim + 1] : 0u;
-                    raw[e2] = lo | (hi << 16);
-                }
-                Ql[(db * 2 + j) * 64 + lane] = raw;
-            }
-    }
+    // Q^T fragments (built by pack_b_kernel behind the B fragments), kept in LDS for the four wavefronts
+    const u32x4_t *packg = pack + ((size_t)b * H_kv + g) * ((size_t)(F16k + F16v) * 256 + 512);
+    u32x4_t *Ql = Bl + 3 * kGroup * 256;  // [8][64]
+    Ql[tid] = packg[(size_t)(F16k + F16v) * 256 + tid];
 
-    const u32x4_t *packg = pack + ((size_t)b * H_kv + g) * (size_t)(F8k + F8v) * 256;
     const bf16_t *Ak = A_k + (size_t)b * L * r_k;
     const bf16_t *Av = A_v + (size_t)b * L * r_v;
     const int32_t *ids = idx + ((size_t)b * H_kv + g) * k;
     const int m_begin = split * chunk;
     const int m_end = m_begin + chunk < k ? m_begin + chunk : k;
     const int n_tiles = (m_end - m_begin + 255) / 256;
-    const int NG = n_tiles * GT;
 
     // The split's token ids are staged in LDS once (clamped into [0, L)), so that the main loop issues no
     // global load other than its prefetches: a wait on an id would otherwise drain the whole prefetch queue.
     int *tok_lds = reinterpret_cast<int *>(Ql + 8 * 64);  // [chunk]
-    for (int m = tid; m < m_end - m_begin; m += 256) {
+    for (int m = tid; m < m_end - m_begin; m += kGaWaves * 64) {
         const int t = ids[m_begin + m];
         tok_lds[m] = t < 0 ? 0 : (t >= L ? L - 1 : t);
     }
     __syncthreads();
-    // token ids gathered by this lane (both 32-token blocks) of a tile
-    auto tile_tokens = [&](int tile, int (&tk)[2]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            int m = tile * 256 + w * 64 + tb * 32 + n;
-            m = m < m_end - m_begin ? m : m_end - m_begin - 1;
-            tk[tb] = tok_lds[m];
-        }
+    // token id gathered by this lane in a tile
+    auto tile_token = [&](int tile) __attribute__((always_inline)) {
+        int m = tile * 256 + w * 32 + n;
+        m = m < m_end - m_begin ? m : m_end - m_begin - 1;
+        return tok_lds[m];
     };
     // 16-byte pieces of a gathered row, already offset by the lane's half
     auto krow = [&](int t) __attribute__((always_inline)) {
@@ -206,128 +217,136 @@ __global__ __launch_bounds__(256, 1) void gather_attend_mfma_kernel(
     auto vrow = [&](int t) __attribute__((always_inline)) {
         return reinterpret_cast<const u32x4_t *>(Av + (size_t)t * r_v) + hf;
     };
-    int tok[2], tok_n[2];
-    tile_tokens(0, tok);
-    tile_tokens(n_tiles > 1 ? 1 : 0, tok_n);
+    int tok = tile_token(0), tok_n = tile_token(n_tiles > 1 ? 1 : 0);
 
     float m_run = -INFINITY, l_run = 0.0f;
-    f32x16_t O[4], acc[2][4];
+    // Only head slots 0..15 can hold a query head (n_rep <= 16): of the 16 result registers of an O tile the
+    // first 8 (slots 8(v/4) + 4hf + v%4, v < 8) are kept between tiles, the rest is dropped.
+    float O[4][8];
+    f32x16_t acc[4];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < 4; ++db) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) O[db][v] = acc[0][db][v] = acc[1][db][v] = 0.0f;
-    bf16x8_t Wf[2][2];
+        for (int v = 0; v < 8; ++v) O[db][v] = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[db][v] = 0.0f;
+    }
+    bf16x8_t Wf[2];
 
-    // ---- prologue: B group 0 straight into buffer 0, B group 1 into registers, A pieces of group 0
-    u32x4_t breg[kGroup], areg[kGroup][2];
+    // this wavefront's slice of an LDS buffer as the target of the global -> LDS copies (the hardware adds
+    // lane * 16 B): fragment row fl of buffer `bufi` starts at Bl + (bufi * kGroup + fl) * 256
+    const uint32_t lds_b0 = (uint32_t)(uintptr_t)(lds_void_t *)Bl;
+    auto dma_base = [&](int bufi) __attribute__((always_inline)) {
+        return lds_b0 + (uint32_t)((bufi * (kGroup * 256) + w * 64) * 16);
+    };
+
+    // ---- prologue: the first pair of groups (K fragments 0..15): B copies into buffers 0 and 1, A pieces
+    // into the ring, in the same per-step order as the steady state (keeps the wait counts exact)
+    u32x4_t areg[2 * kGroup];
 #pragma unroll
-    for (int fl = 0; fl < kGroup; ++fl) Bl[fl * 256 + tid] = packg[fl * 256 + tid];
-#pragma unroll
-    for (int fl = 0; fl < kGroup; ++fl) {
-        breg[fl] = packg[(size_t)((1 % GT) * kGroup + fl) * 256 + tid];
-        const int f = fl < Fk ? fl : 0;  // beyond the rank the B fragment is zero: any finite A piece will do
-        areg[fl][0] = krow(tok[0])[2 * f];
-        areg[fl][1] = krow(tok[1])[2 * f];
-        __builtin_amdgcn_sched_barrier(0);  // same issue order as in the steady state (keeps the wait counts exact)
+    for (int s = 0; s < 2 * kGroup; ++s) {
+        if ((s & 1) == 0) copy16_global_to_lds(packg + (size_t)s * 256 + tid, dma_base(s / kGroup) + (s % kGroup) * 4096);
+        const int f = s < Fk ? s : 0;  // beyond the rank the B fragment is zero: any finite A piece will do
+        areg[s] = krow(tok)[2 * f];
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    int gg = 0;
+    int gg = 0;  // group counter: group gg is read from buffer gg % 3
     for (int tile = 0; tile < n_tiles; ++tile) {
-        const int base = m_begin + tile * 256 + w * 64;
-        for (int wi = 0; wi < GK; ++wi, ++gg) {
-            const bool next_k = wi + 1 < GK;  // the group after this one: K or the first V group of this tile
-            run_group<true>(acc, areg, breg, Bl, packg + (size_t)(((wi + 2) % GT) * kGroup) * 256 + tid, gg, NG,
-                            next_k ? krow(tok[0]) : vrow(tok[0]), next_k ? krow(tok[1]) : vrow(tok[1]),
-                            next_k ? (wi + 1) * kGroup : 0, next_k ? Fk : Fv, tid, lane);
+        const int base = m_begin + tile * 256 + w * 32;
+        // descriptor of the pair after pair `pi`: K or V of this tile, or the first K pair of the next tile
+#define XKV_NEXT_PAIR(pi)                                                                                     \
+    const bool wrap = (pi) + 1 == PT;                                                                         \
+    const int pn = wrap ? 0 : (pi) + 1;                                                                       \
+    const bool next_k = pn < PK;                                                                              \
+    const int t0 = wrap ? tok_n : tok;                                                                        \
+    const u32x4_t *p0 = next_k ? krow(t0) : vrow(t0);                                                         \
+    const int fn0 = (next_k ? pn : pn - PK) * 2 * kGroup, Fn = next_k ? Fk : Fv;                              \
+    const u32x4_t *bs = packg + (size_t)(pn * 2 * kGroup) * 256 + tid;                                        \
+    const int buf0 = gg % 3, buf1 = (gg + 1) % 3, buf2 = (gg + 2) % 3 /* groups gg+2, gg+3 go to buf2, buf0 */
+        for (int pi = 0; pi < PK; ++pi, gg += 2) {
+            XKV_NEXT_PAIR(pi);
+            run_group<true, 0>(acc, areg, Bl, buf0, dma_base(buf2), bs, p0, fn0, Fn, lane);
+            run_group<true, kGroup>(acc, areg, Bl, buf1, dma_base(buf0), bs + kGroup * 256, p0, fn0 + kGroup, Fn, lane);
         }
         {
-            // (2) Z^T = K^ Q^T: lane (head slot n, hf), register v <-> token 8(v/4) + 4hf + v%4 of block tb
-            f32x16_t Z[2];
+                // (2) Z^T = K^ Q^T: lane (head slot n, hf), register v <-> token 8(v/4) + 4hf + v%4 of the block
+                f32x16_t Z;
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) Z[tb][v] = 0.0f;
+                for (int v = 0; v < 16; ++v) Z[v] = 0.0f;
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int j = 0; j < 2; ++j) {
                         const bf16x8_t qf = __builtin_bit_cast(bf16x8_t, Ql[(db * 2 + j) * 64 + lane]);
-                        Z[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pack8(acc[tb][db], j), qf, Z[tb], 0, 0, 0);
+                        Z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pack8(acc[db], j), qf, Z, 0, 0, 0);
                     }
-            }
-            // online softmax; selected tokens beyond the end of this split get weight 0
-            float m_loc = -INFINITY;
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+                // online softmax; selected tokens beyond the end of this split get weight 0
+                float m_loc = -INFINITY;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int tt = base + tb * 32 + 8 * (v / 4) + 4 * hf + (v % 4);
-                    Z[tb][v] = tt < m_end ? scale * Z[tb][v] : -INFINITY;
-                    m_loc = fmaxf(m_loc, Z[tb][v]);
+                    const int tt = base + 8 * (v / 4) + 4 * hf + (v % 4);
+                    Z[v] = tt < m_end ? scale * Z[v] : -INFINITY;
+                    m_loc = fmaxf(m_loc, Z[v]);
                 }
-            m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, kWave));
-            const float m_new = fmaxf(m_run, m_loc);
-            const float alpha = (m_new == -INFINITY) ? 1.0f : __expf(m_run - m_new);
-            float l_add = 0.0f;
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
+                m_loc = fmaxf(m_loc, __shfl_xor(m_loc, 32, kWave));
+                const float m_new = fmaxf(m_run, m_loc);
+                const float alpha = (m_new == -INFINITY) ? 1.0f : __expf(m_run - m_new);
+                float l_add = 0.0f;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float wv = (Z[tb][v] == -INFINITY) ? 0.0f : __expf(Z[tb][v] - m_new);
-                    Z[tb][v] = wv;
+                    const float wv = (Z[v] == -INFINITY) ? 0.0f : __expf(Z[v] - m_new);
+                    Z[v] = wv;
                     l_add += wv;
                 }
-                Wf[tb][0] = pack8(Z[tb], 0);
-                Wf[tb][1] = pack8(Z[tb], 1);
-            }
-            l_run = l_run * alpha + l_add;
-            m_run = m_new;
-            // rescale O now: rows are head slots, register v of half hf is slot 8(v/4) + 4hf + v%4
+                Wf[0] = pack8(Z, 0);
+                Wf[1] = pack8(Z, 1);
+                l_run = l_run * alpha + l_add;
+                m_run = m_new;
+                // rescale O now: rows are head slots, register v of half hf is slot 8(v/4) + 4hf + v%4
 #pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                const float a = __shfl(alpha, 8 * (v / 4) + 4 * hf + (v % 4), kWave);
+                for (int v = 0; v < 8; ++v) {
+                    const float a = __shfl(alpha, 8 * (v / 4) + 4 * hf + (v % 4), kWave);
 #pragma unroll
-                for (int db = 0; db < 4; ++db) O[db][v] *= a;
-            }
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+                    for (int db = 0; db < 4; ++db) O[db][v] *= a;
+                }
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[tb][db][v] = 0.0f;
+                    for (int v = 0; v < 16; ++v) acc[db][v] = 0.0f;
         }
-        for (int wi = GK; wi < GT; ++wi, ++gg) {
-            const bool wrap = wi + 1 == GT;  // the next group is the first K group of the next tile
-            run_group<false>(acc, areg, breg, Bl, packg + (size_t)(((wi + 2) % GT) * kGroup) * 256 + tid, gg, NG,
-                             wrap ? krow(tok_n[0]) : vrow(tok[0]), wrap ? krow(tok_n[1]) : vrow(tok[1]),
-                             wrap ? 0 : (wi + 1 - GK) * kGroup, wrap ? Fk : Fv, tid, lane);
+        for (int pi = PK; pi < PT; ++pi, gg += 2) {
+            XKV_NEXT_PAIR(pi);
+            run_group<false, 0>(acc, areg, Bl, buf0, dma_base(buf2), bs, p0, fn0, Fn, lane);
+            run_group<false, kGroup>(acc, areg, Bl, buf1, dma_base(buf0), bs + kGroup * 256, p0, fn0 + kGroup, Fn, lane);
         }
+#undef XKV_NEXT_PAIR
         {
-            // (4) O += W V^
+                // (4) O += W V^, one dim block at a time through a scratch result tile
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+                for (int db = 0; db < 4; ++db) {
+                    f32x16_t ot;
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                    for (int v = 0; v < 16; ++v) ot[v] = 0.0f;
 #pragma unroll
-                    for (int db = 0; db < 4; ++db)
-                        O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Wf[tb][j], pack8(acc[tb][db], j), O[db], 0, 0,
-                                                                        0);
+                    for (int j = 0; j < 2; ++j)
+                        ot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Wf[j], pack8(acc[db], j), ot, 0, 0, 0);
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+                    for (int v = 0; v < 8; ++v) O[db][v] += ot[v];
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[tb][db][v] = 0.0f;
-            // rotate the token ids and fetch those of the tile after next
-            tok[0] = tok_n[0];
-            tok[1] = tok_n[1];
-            tile_tokens(tile + 2 < n_tiles ? tile + 2 : n_tiles - 1, tok_n);
+                    for (int v = 0; v < 16; ++v) acc[db][v] = 0.0f;
+                }
+                // rotate the token ids and fetch the id of the tile after next
+                tok = tok_n;
+                tok_n = tile_token(tile + 2 < n_tiles ? tile + 2 : n_tiles - 1);
         }
     }
 
-    // merge the four wavefronts in LDS, then write one partial per (split, query head)
+    // all global -> LDS copies must have landed before the buffers are reused for the merge
+    XKV_WAIT_VMCNT(0);
     __syncthreads();
-    float *mg = reinterpret_cast<float *>(smem_raw);  // [4][16][132]
+    // merge the eight wavefronts in LDS, then write one partial per (split, query head)
+    float *mg = reinterpret_cast<float *>(smem_raw);  // [8][16][132]
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     if (lane < n_rep) {
         mg[(w * 16 + lane) * 132 + 128] = m_run;
@@ -342,14 +361,14 @@ __global__ __launch_bounds__(256, 1) void gather_attend_mfma_kernel(
         }
     }
     __syncthreads();
-    for (int item = tid; item < n_rep * 128; item += 256) {
+    for (int item = tid; item < n_rep * 128; item += kGaWaves * 64) {
         const int hh = item >> 7, dim = item & 127;
         float M = -INFINITY;
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) M = fmaxf(M, mg[(ww * 16 + hh) * 132 + 128]);
+        for (int ww = 0; ww < kGaWaves; ++ww) M = fmaxf(M, mg[(ww * 16 + hh) * 132 + 128]);
         float num = 0.0f, den = 0.0f;
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) {
+        for (int ww = 0; ww < kGaWaves; ++ww) {
             const float mw = mg[(ww * 16 + hh) * 132 + 128];
             const float wgt = (mw == -INFINITY) ? 0.0f : __expf(mw - M);
             num = fmaf(wgt, mg[(ww * 16 + hh) * 132 + dim], num);
@@ -371,31 +390,31 @@ bool gather_attend_mfma_shape_ok(const xkv_shape &s)
 
 size_t gather_attend_pack_bytes(const xkv_shape &s)
 {
-    const int F8k = (s.r_k / 16 + 7) / 8 * 8, F8v = (s.r_v / 16 + 7) / 8 * 8;
-    return (size_t)(s.batch > 0 ? s.batch : 1) * s.H_kv * (size_t)(F8k + F8v) * 4 * 1024;
+    const int F8k = (s.r_k / 16 + 15) / 16 * 16, F8v = (s.r_v / 16 + 15) / 16 * 16;  // padded to whole pairs of groups
+    return (size_t)(s.batch > 0 ? s.batch : 1) * s.H_kv * ((size_t)(F8k + F8v) * 4 * 1024 + 8 * 1024);
 }
 
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
                                      void *pack_ws, float *part_o, float *part_ml, hipStream_t st)
 {
-    const int F8k = (s.r_k / 16 + 7) / 8 * 8, F8v = (s.r_v / 16 + 7) / 8 * 8;
-    dim3 pgrid(((F8k + F8v) * 64 + 255) / 256, s.H_kv, s.batch), block(256);
-    hipLaunchKernelGGL(pack_b_kernel, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)B_v,
-                       (u32x4_t *)pack_ws, s.G, layer, s.r_k, s.r_v, s.H_kv, F8k, F8v);
+    const int F8k = (s.r_k / 16 + 15) / 16 * 16, F8v = (s.r_v / 16 + 15) / 16 * 16;  // padded to whole pairs of groups
+    dim3 pgrid(((F8k + F8v) * 64 + 512 + 255) / 256, s.H_kv, s.batch), block(256);
+    hipLaunchKernelGGL(pack_b_kernel, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)B_v, (const bf16_t *)q,
+                       (u32x4_t *)pack_ws, s.G, layer, s.r_k, s.r_v, s.H_kv, s.H_q, F8k, F8v);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t lds = 2 * kGroup * 256 * 16 + 8 * 64 * 16 + (size_t)p.sr_chunk * 4;  // B fragments, Q fragments, token ids
+    const size_t lds = 3 * kGroup * 256 * 16 + 8 * 64 * 16 + (size_t)p.sr_chunk * 4;  // B fragments, Q fragments, token ids
     static bool attr_set = false;
     if (!attr_set) {
         e = hipFuncSetAttribute((const void *)gather_attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                2 * kGroup * 256 * 16 + 8 * 64 * 16 + kMaxChunkTokens * 4);
+                                3 * kGroup * 256 * 16 + 8 * 64 * 16 + kMaxChunkTokens * 4);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((long long)p.sr_splits * s.H_kv * s.batch));
     profile_begin(1, st);
-    hipLaunchKernelGGL(gather_attend_mfma_kernel, grid, block, lds, st, (const bf16_t *)A_k, (const bf16_t *)A_v,
+    hipLaunchKernelGGL(gather_attend_mfma_kernel, grid, dim3(kGaWaves * 64), lds, st, (const bf16_t *)A_k, (const bf16_t *)A_v,
                        (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, part_o, part_ml, s.L, s.r_k, s.r_v, s.H_kv,
                        s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v, p.scale);
     profile_end(1, st);
