@@ -26,8 +26,8 @@ typedef __attribute__((ext_vector_type(8))) float f32x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-constexpr int kMaxChunkTokens = 8192;  // selected tokens per workgroup (their ids sit in LDS)
-constexpr int kGroup = 8;  // fragments (of 16 ranks) per LDS stage: 8 x 4 KiB = 32 KiB, three stages
+constexpr int kMaxChunkTokens = 4096;  // selected tokens per workgroup (their ids sit in LDS)
+constexpr int kGroup = 8;  // fragments (of 16 ranks) per LDS stage: 8 x 4 KiB = 32 KiB, two stages
 
 // Pack B_{l,g} (r x 128 slice of B_l) into MFMA fragment order:
 //   pack[f][db][hf*32 + c][e] = B[16f + 8hf + e][g*128 + db*32 + c],  zero beyond r.
@@ -97,7 +97,7 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 
 // 16 B per lane straight from global memory into LDS at lds_base + lane * 16 (lds_base is wave-uniform).
 // Issued as inline assembly on purpose: the compiler then does not tie later LDS reads of the *other*
-// buffers to this copy (it cannot tell the buffers apart and would drain the whole vector-memory queue before
+// buffer to this copy (it cannot tell the buffers apart and would drain the whole vector-memory queue before
 // every group); completion is awaited explicitly with XKV_WAIT_VMCNT before the barrier that publishes
 // the buffer.  The copy still counts as one outstanding vector-memory operation, which only makes the
 // compiler's own waits for register loads more conservative, never less.
@@ -111,60 +111,68 @@ __device__ __forceinline__ void copy16_global_to_lds(const void *gptr, uint32_t 
 #define XKV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (0xF << 8) | (((n) >> 4) << 14))
 
 constexpr int kGaWaves = 8;  // wavefronts per workgroup, 32 selected tokens each per tile
+// LDS map (bytes): B fragments [2][kGroup][4][64][16] | A tiles [kGaWaves][512][16] | Q fragments [8][64][16] | ids
+constexpr int kLdsB = 2 * kGroup * 256 * 16, kLdsA = kGaWaves * 512 * 16, kLdsQ = 8 * 64 * 16;
 
-// One group of 8 fragment steps out of LDS buffer `buf`.  IS_K selects which product the fragments feed,
-// SLOT0 (0 or 8) which half of the 16-deep A ring the group consumes.  Per step the thread
-//  - on even steps copies, global -> LDS without passing through registers, its 16 B of the same two steps
-//    of the group two groups on (source bsrc2, 512 threads x 16 B = two fragment rows),
-//  - multiplies the step's four B fragments (LDS) with its A piece (ring),
-//  - refills the ring entry with the A piece of the same step two groups on (row an0).
+// What a wavefront gathers for one group of 8 fragment steps: 128 ranks = 256 B of each of its 32 rows.
+// Instruction j (0..7) covers rows 4j..4j+3 whole-line-wise: lane l loads the 16 B piece l%16 of row 4j + l/16,
+// so every 128 B line is touched by exactly one instruction (this is what keeps random-row gathers near the
+// streaming rate; one lane per row with 32 B runs does not).  `piece` is the lane's 16 B piece within the row,
+// already clamped into the row; `pieces` is the row length in 16 B units.
+struct AStage {
+    const u32x4_t *base;  // A^K or A^V of this sequence
+    int pieces;
+    int piece;
+};
+
+// One group of 8 fragment steps.  IS_K selects which product the fragments feed, SLOT0 (0 or 8) which half of
+// the two-group-deep ring of gathered pieces the group consumes.  The wavefront
+//  - waits until its copies of this group's B fragments (issued one group ago) have landed, and publishes them,
+//  - starts the global -> LDS copies of the next group's B fragments into the other buffer,
+//  - transposes its gathered pieces through its private LDS tile: written row-wise (rotated by the row number,
+//    so that neither side has bank conflicts), read back as one 16-rank operand fragment per step,
+//  - refills the ring, one instruction per step, with the pieces of the group two groups on,
+//  - per step multiplies the step's four B fragments with the A fragment.
 template <bool IS_K, int SLOT0>
-__device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 * kGroup], const u32x4_t *Bl, int buf,
-                                          uint32_t dma_dst, const u32x4_t *bsrc2, const u32x4_t *an0, int fn0, int Fn,
+__device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 * kGroup], const u32x4_t *Bl,
+                                          u32x4_t *At, int buf, uint32_t dma_dst, const u32x4_t *bsrc_next,
+                                          const AStage &an, const int (&tk)[kGroup], const int (&woff)[4], int rbase,
                                           int lane)
 {
-    // The copies into this buffer were issued two groups ago.  Everything this thread issued since then (one
-    // group: 4 copies and 8 A pieces) may stay in flight, plus the two A pieces that followed the last copy; then
-    // the barrier makes every wavefront's copies visible.  The barrier orders LDS only: prefetches stay in
-    // flight across it.
-    XKV_WAIT_VMCNT(kGroup / 2 + kGroup + 2);
+    // Outstanding at this point, youngest first: the 8 gathers issued during the previous group, then the B copies
+    // for this group, then older gathers.  The barrier orders LDS only: the gathers stay in flight across it.
+    XKV_WAIT_VMCNT(kGroup);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    const u32x4_t *bcur = Bl + buf * (kGroup * 256) + lane;
-    u32x4_t bf_cur[4], bf_nxt[4];
 #pragma unroll
-    for (int db = 0; db < 4; ++db) bf_cur[db] = bcur[db * 64];
+    for (int i = 0; i < 4; ++i) copy16_global_to_lds(bsrc_next + i * 512, dma_dst + i * 8192);
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) At[64 * j + woff[j & 3]] = areg[SLOT0 + j];
+    __builtin_amdgcn_sched_barrier(0);
+    const u32x4_t *bcur = Bl + buf * (kGroup * 256) + lane;
 #pragma unroll
     for (int fl = 0; fl < kGroup; ++fl) {
-        if ((fl & 1) == 0) copy16_global_to_lds(bsrc2 + fl * 256, dma_dst + fl * 4096);
-        const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, areg[SLOT0 + fl]);
-        if (fl + 1 < kGroup) {
-#pragma unroll
-            for (int db = 0; db < 4; ++db) bf_nxt[db] = bcur[((fl + 1) * 4 + db) * 64];  // LDS reads one step ahead
-        }
+        const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, At[(rbase & ~15) + ((rbase + 2 * fl) & 15)]);
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-            const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, bf_cur[db]);
+            const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, bcur[(fl * 4 + db) * 64]);
             if constexpr (IS_K)  // (1) K^T tile: rows = head dims, columns = tokens
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, a0, acc[db], 0, 0, 0);
             else  // (3) V^ tile: rows = tokens, columns = head dims
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bf, acc[db], 0, 0, 0);
         }
-#pragma unroll
-        for (int db = 0; db < 4; ++db) bf_cur[db] = bf_nxt[db];
-        // the lane's A piece for the same step two groups on, loaded into the registers just consumed
-        const int f = fn0 + fl < Fn ? fn0 + fl : 0;
-        areg[SLOT0 + fl] = an0[2 * f];
+        // instruction fl of the gather two groups on, into the ring entry written out above
+        areg[SLOT0 + fl] = an.base[(size_t)tk[fl] * an.pieces + an.piece];
         __builtin_amdgcn_sched_barrier(0);  // keep each step's memory operations where they are written
     }
 }
 
 // Software pipeline.  The work of a workgroup is a linear sequence of groups of 8 fragment steps, taken in
 // pairs: per 256-token tile first the K pairs, then the V pairs (ranks are padded to a multiple of 256 with
-// zero fragments).  While a group is multiplied out of one of three LDS buffers, every thread copies its
-// slice of the B fragments two groups on straight from global memory into the buffer that was read last,
-// and loads, two groups (16 steps) ahead, the 16 B pieces of the gathered A row its own lane will need.
+// zero fragments).  While a group is multiplied out of one of two LDS buffers, the B fragments of the next
+// group are copied straight from global memory into the other, and every wavefront has the gathered pieces of
+// the next two groups in flight in registers.
 // Eight wavefronts of 32 tokens each: two share a SIMD, so one multiplies while the other waits for memory.
 __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     const bf16_t *__restrict__ A_k, const bf16_t *__restrict__ A_v, const u32x4_t *__restrict__ pack,
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     int F16v, float scale)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    u32x4_t *Bl = reinterpret_cast<u32x4_t *>(smem_raw);  // [3][kGroup][4][64] 16-byte fragments = 96 KiB
+    u32x4_t *Bl = reinterpret_cast<u32x4_t *>(smem_raw);
     // workgroup id -> (KV head fastest, so that a head's packed B stays in one XCD's L2), split, sequence
     const int g = blockIdx.x % H_kv;
     const int split = (blockIdx.x / H_kv) % splits;
@@ -181,16 +189,16 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int n = lane & 31, hf = lane >> 5;
     const int n_rep = H_q / H_kv;
-    const int Fk = r_k / 16, Fv = r_v / 16;
     const int PK = F16k / (2 * kGroup), PT = (F16k + F16v) / (2 * kGroup);  // pairs of groups per tile: K, total
 
-    // Q^T fragments (built by pack_b_kernel behind the B fragments), kept in LDS for the four wavefronts
+    // Q^T fragments (built by pack_b_kernel behind the B fragments), kept in LDS for all wavefronts
     const u32x4_t *packg = pack + ((size_t)b * H_kv + g) * ((size_t)(F16k + F16v) * 256 + 512);
-    u32x4_t *Ql = Bl + 3 * kGroup * 256;  // [8][64]
+    u32x4_t *At = reinterpret_cast<u32x4_t *>(smem_raw + kLdsB) + w * 512;
+    u32x4_t *Ql = reinterpret_cast<u32x4_t *>(smem_raw + kLdsB + kLdsA);  // [8][64]
     Ql[tid] = packg[(size_t)(F16k + F16v) * 256 + tid];
 
-    const bf16_t *Ak = A_k + (size_t)b * L * r_k;
-    const bf16_t *Av = A_v + (size_t)b * L * r_v;
+    const u32x4_t *Ak = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
+    const u32x4_t *Av = reinterpret_cast<const u32x4_t *>(A_v + (size_t)b * L * r_v);
     const int32_t *ids = idx + ((size_t)b * H_kv + g) * k;
     const int m_begin = split * chunk;
     const int m_end = m_begin + chunk < k ? m_begin + chunk : k;
@@ -198,26 +206,36 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
 
     // The split's token ids are staged in LDS once (clamped into [0, L)), so that the main loop issues no
     // global load other than its prefetches: a wait on an id would otherwise drain the whole prefetch queue.
-    int *tok_lds = reinterpret_cast<int *>(Ql + 8 * 64);  // [chunk]
+    int *tok_lds = reinterpret_cast<int *>(smem_raw + kLdsB + kLdsA + kLdsQ);  // [chunk]
     for (int m = tid; m < m_end - m_begin; m += kGaWaves * 64) {
         const int t = ids[m_begin + m];
         tok_lds[m] = t < 0 ? 0 : (t >= L ? L - 1 : t);
     }
     __syncthreads();
-    // token id gathered by this lane in a tile
-    auto tile_token = [&](int tile) __attribute__((always_inline)) {
-        int m = tile * 256 + w * 32 + n;
-        m = m < m_end - m_begin ? m : m_end - m_begin - 1;
-        return tok_lds[m];
+    // the eight rows this lane gathers from in a tile: row 4j + lane/16 of the wavefront's 32-token block
+    auto tile_tokens = [&](int tile, int (&tk)[kGroup]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            int m = tile * 256 + w * 32 + 4 * j + (lane >> 4);
+            m = m < m_end - m_begin ? m : m_end - m_begin - 1;
+            tk[j] = tok_lds[m];
+        }
     };
-    // 16-byte pieces of a gathered row, already offset by the lane's half
-    auto krow = [&](int t) __attribute__((always_inline)) {
-        return reinterpret_cast<const u32x4_t *>(Ak + (size_t)t * r_k) + hf;
+    // gather descriptor of group S (128 ranks each) of the K or V rows; pieces beyond the row are replaced by
+    // piece 0 (they meet zero B fragments: any finite value will do)
+    auto stage_of = [&](bool is_k, int S) __attribute__((always_inline)) {
+        AStage st;
+        st.base = is_k ? Ak : Av;
+        st.pieces = (is_k ? r_k : r_v) >> 3;
+        const int pc = 16 * S + (lane & 15);
+        st.piece = pc < st.pieces ? pc : 0;
+        return st;
     };
-    auto vrow = [&](int t) __attribute__((always_inline)) {
-        return reinterpret_cast<const u32x4_t *>(Av + (size_t)t * r_v) + hf;
-    };
-    int tok = tile_token(0), tok_n = tile_token(n_tiles > 1 ? 1 : 0);
+    // LDS tile addressing in 16 B units: piece c of row t sits at 16 t + (c + t) % 16
+    int woff[4];
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) woff[qd] = 16 * (lane >> 4) + (((lane & 15) + (lane >> 4) + 4 * qd) & 15);
+    const int rbase = 16 * n + ((hf + n) & 15);  // step fl reads (rbase & ~15) + (rbase + 2 fl) % 16
 
     float m_run = -INFINITY, l_run = 0.0f;
     // Only head slots 0..15 can hold a query head (n_rep <= 16): of the 16 result registers of an O tile the
@@ -233,41 +251,52 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     }
     bf16x8_t Wf[2];
 
-    // this wavefront's slice of an LDS buffer as the target of the global -> LDS copies (the hardware adds
-    // lane * 16 B): fragment row fl of buffer `bufi` starts at Bl + (bufi * kGroup + fl) * 256
+    // this wavefront's slice of a B buffer as the target of the global -> LDS copies (the hardware adds
+    // lane * 16 B): one copy instruction of the workgroup covers two fragment rows (8 KiB)
     const uint32_t lds_b0 = (uint32_t)(uintptr_t)(lds_void_t *)Bl;
     auto dma_base = [&](int bufi) __attribute__((always_inline)) {
         return lds_b0 + (uint32_t)((bufi * (kGroup * 256) + w * 64) * 16);
     };
 
-    // ---- prologue: the first pair of groups (K fragments 0..15): B copies into buffers 0 and 1, A pieces
-    // into the ring, in the same per-step order as the steady state (keeps the wait counts exact)
-    u32x4_t areg[2 * kGroup];
+    // ---- prologue, in the order the steady state expects: B fragments of group 0, gathers of groups 0 and 1
 #pragma unroll
-    for (int s = 0; s < 2 * kGroup; ++s) {
-        if ((s & 1) == 0) copy16_global_to_lds(packg + (size_t)s * 256 + tid, dma_base(s / kGroup) + (s % kGroup) * 4096);
-        const int f = s < Fk ? s : 0;  // beyond the rank the B fragment is zero: any finite A piece will do
-        areg[s] = krow(tok)[2 * f];
-        __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < 4; ++i) copy16_global_to_lds(packg + i * 512 + tid, dma_base(0) + i * 8192);
+    u32x4_t areg[2 * kGroup];
+    {
+        const AStage s0 = stage_of(true, 0), s1 = stage_of(true, 1);
+        int tk0[kGroup];
+        tile_tokens(0, tk0);
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            areg[j] = s0.base[(size_t)tk0[j] * s0.pieces + s0.piece];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            areg[kGroup + j] = s1.base[(size_t)tk0[j] * s1.pieces + s1.piece];
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
-    int gg = 0;  // group counter: group gg is read from buffer gg % 3
+    int gg = 0;  // group counter: group gg is read from buffer gg % 2
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int base = m_begin + tile * 256 + w * 32;
-        // descriptor of the pair after pair `pi`: K or V of this tile, or the first K pair of the next tile
+        // descriptors of the pair after pair `pi`: K or V of this tile, or the first K pair of the next tile
 #define XKV_NEXT_PAIR(pi)                                                                                     \
     const bool wrap = (pi) + 1 == PT;                                                                         \
     const int pn = wrap ? 0 : (pi) + 1;                                                                       \
     const bool next_k = pn < PK;                                                                              \
-    const int t0 = wrap ? tok_n : tok;                                                                        \
-    const u32x4_t *p0 = next_k ? krow(t0) : vrow(t0);                                                         \
-    const int fn0 = (next_k ? pn : pn - PK) * 2 * kGroup, Fn = next_k ? Fk : Fv;                              \
-    const u32x4_t *bs = packg + (size_t)(pn * 2 * kGroup) * 256 + tid;                                        \
-    const int buf0 = gg % 3, buf1 = (gg + 1) % 3, buf2 = (gg + 2) % 3 /* groups gg+2, gg+3 go to buf2, buf0 */
+    const int S0 = (next_k ? pn : pn - PK) * 2;                                                               \
+    const AStage an0 = stage_of(next_k, S0), an1 = stage_of(next_k, S0 + 1);                                  \
+    int tkn[kGroup]; /* rows of the tile that pair belongs to (past the last tile: the last tile again) */   \
+    tile_tokens(wrap ? (tile + 1 < n_tiles ? tile + 1 : tile) : tile, tkn);                                   \
+    const u32x4_t *bs1 = packg + (size_t)((pi) * 2 + 1) * (kGroup * 256) + tid; /* second group of this pair */ \
+    const u32x4_t *bs2 = packg + (size_t)(pn * 2) * (kGroup * 256) + tid;       /* first group of next pair */  \
+    const int buf0 = gg & 1, buf1 = buf0 ^ 1
         for (int pi = 0; pi < PK; ++pi, gg += 2) {
             XKV_NEXT_PAIR(pi);
-            run_group<true, 0>(acc, areg, Bl, buf0, dma_base(buf2), bs, p0, fn0, Fn, lane);
-            run_group<true, kGroup>(acc, areg, Bl, buf1, dma_base(buf0), bs + kGroup * 256, p0, fn0 + kGroup, Fn, lane);
+            run_group<true, 0>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
+            run_group<true, kGroup>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
         }
         {
                 // (2) Z^T = K^ Q^T: lane (head slot n, hf), register v <-> token 8(v/4) + 4hf + v%4 of the block
@@ -317,8 +346,8 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
         }
         for (int pi = PK; pi < PT; ++pi, gg += 2) {
             XKV_NEXT_PAIR(pi);
-            run_group<false, 0>(acc, areg, Bl, buf0, dma_base(buf2), bs, p0, fn0, Fn, lane);
-            run_group<false, kGroup>(acc, areg, Bl, buf1, dma_base(buf0), bs + kGroup * 256, p0, fn0 + kGroup, Fn, lane);
+            run_group<false, 0>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
+            run_group<false, kGroup>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
         }
 #undef XKV_NEXT_PAIR
         {
@@ -336,9 +365,6 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[db][v] = 0.0f;
                 }
-                // rotate the token ids and fetch the id of the tile after next
-                tok = tok_n;
-                tok_n = tile_token(tile + 2 < n_tiles ? tile + 2 : n_tiles - 1);
         }
     }
 
@@ -404,11 +430,12 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
                        (u32x4_t *)pack_ws, s.G, layer, s.r_k, s.r_v, s.H_kv, s.H_q, F8k, F8v);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t lds = 3 * kGroup * 256 * 16 + 8 * 64 * 16 + (size_t)p.sr_chunk * 4;  // B fragments, Q fragments, token ids
+    if (p.sr_chunk > kMaxChunkTokens) return hipErrorInvalidValue;
+    const size_t lds = kLdsB + kLdsA + kLdsQ + (size_t)p.sr_chunk * 4;  // B fragments, A tiles, Q fragments, token ids
     static bool attr_set = false;
     if (!attr_set) {
         e = hipFuncSetAttribute((const void *)gather_attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                3 * kGroup * 256 * 16 + 8 * 64 * 16 + kMaxChunkTokens * 4);
+                                kLdsB + kLdsA + kLdsQ + kMaxChunkTokens * 4);
         if (e != hipSuccess) return e;
         attr_set = true;
     }

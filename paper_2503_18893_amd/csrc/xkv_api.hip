@@ -45,7 +45,7 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     p.ga_mfma = gather_attend_mfma_shape_ok(s);
     const int gran = p.ga_mfma ? 256 : 64;
     int splits = clampi(want, 1, clampi(ceil_div(s.k, gran), 1, 64));
-    if (splits < ceil_div(s.k, 8192)) splits = ceil_div(s.k, 8192);  // a workgroup keeps at most 8192 token ids in LDS
+    if (splits < ceil_div(s.k, 4096)) splits = ceil_div(s.k, 4096);  // a workgroup keeps at most 4096 token ids in LDS
     p.sr_chunk = ceil_div(ceil_div(s.k, splits), gran) * gran;
     p.sr_splits = ceil_div(s.k, p.sr_chunk);
 
