@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restric
 #pragma unroll
                     for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
                     const int g = blk * 2 * GPH + hf * GPH + u;
-                    if (g < H_kv) S[((size_t)b * H_kv + g) * L + t] = scale * best;
+                    if (g < H_kv) __builtin_nontemporal_store(scale * best, &S[((size_t)b * H_kv + g) * L + t]);
                 }
             }
 #pragma unroll
@@ -250,6 +250,162 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restric
         step = step_n;
 #pragma unroll
         for (int j = 0; j < 8; ++j) a_cur[j] = a_nxt[j];
+    }
+}
+
+// Variant for long streams: the same contraction, but A^K is fetched line-wise and turned into operand
+// fragments through a wavefront-private LDS tile.  A group is 128 ranks (256 B) of each of the wavefront's 32
+// token rows; instruction j of a group covers rows 4j..4j+3, lane l loading the 16 B piece l%16 of row 4j + l/16,
+// so every 128 B line is requested by exactly one instruction (with one lane per row, four instructions share
+// each line and the stream runs well below the memory rate).  The tile is written row-wise, rotated by the row
+// number so that neither side has bank conflicts (piece c of row t at 16 t + (c + t) % 16, in 16 B units), and
+// read back as one fragment per step.  Two groups are in flight in registers per wavefront; nothing in the
+// main loop needs a barrier (P is read-only in LDS, the tiles are private).
+constexpr int kScoreWaves = 8;
+
+template <int SLOT0>
+__device__ __forceinline__ void score_group(f32x16_t &acc_h, f32x16_t &acc_l, u32x4_t (&areg)[16], u32x4_t *At,
+                                            const u32x4_t *Ph, const u32x4_t *Pl_, const u32x4_t *arow, int pieces,
+                                            int t0, int L, const int (&woff)[4], int rbase)
+{
+    // all but the 8 youngest loads (the other half of the ring) have landed: vmcnt(8), other counters untouched
+    __builtin_amdgcn_s_waitcnt(8 | (7 << 4) | (0xF << 8));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) At[64 * j + woff[j & 3]] = areg[SLOT0 + j];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int fl = 0; fl < 8; ++fl) {
+        const bf16x8_t a0 = __builtin_bit_cast(bf16x8_t, At[(rbase & ~15) + ((rbase + 2 * fl) & 15)]);
+        acc_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, Ph[fl * 64]), a0, acc_h, 0, 0, 0);
+        acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, Pl_[fl * 64]), a0, acc_l, 0, 0, 0);
+        // instruction fl of the group two groups on, into the ring entry written out above
+        const int t = t0 + 4 * fl;
+        areg[SLOT0 + fl] = __builtin_nontemporal_load(&arow[(size_t)(t < L ? t : L - 1) * pieces]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int N_REP>
+__global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf16_t *__restrict__ A_k,
+                                                                        const bf16_t *__restrict__ Pfrag,
+                                                                        float *__restrict__ S, int L, int r_k,
+                                                                        int H_kv, int F8, int tiles_per_wg,
+                                                                        float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);  // [2][F8][64] fragments of 16 B per lane
+    constexpr int GPH = 16 / N_REP;
+    const int b = blockIdx.z, blk = blockIdx.y, nblk = gridDim.y;
+    const int lane = lane_id(), w = wave_id();
+    const int n = lane & 31, hf = lane >> 5;
+    u32x4_t *At = Pl + 2 * F8 * 64 + w * 512;
+
+    // stage this block's P fragments (hi and lo parts) in LDS, four 16 B loads in flight per thread
+    {
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
+        const int total = 2 * F8 * 64;  // a multiple of 1024
+        for (int e0 = threadIdx.x; e0 < total; e0 += 2 * kScoreWaves * 64) {
+            u32x4_t tmp[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) tmp[j] = src[e0 + j * kScoreWaves * 64];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) Pl[e0 + j * kScoreWaves * 64] = tmp[j];
+        }
+    }
+    __syncthreads();
+
+    const int pieces = r_k >> 3;  // 16 B pieces per row
+    const u32x4_t *Ab = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
+    const int n_tiles = (L + 31) / 32;
+    const int tile_begin = blockIdx.x * tiles_per_wg;
+    const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
+    const int n_groups = F8 / 8;  // groups per tile
+    int tile = tile_begin + w;
+    if (tile >= tile_end) return;
+
+    int woff[4];
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) woff[qd] = 16 * (lane >> 4) + (((lane & 15) + (lane >> 4) + 4 * qd) & 15);
+    const int rbase = 16 * n + ((hf + n) & 15);
+    // this lane's piece of group S (beyond the row: piece 0, it meets zero P fragments) and first row of a tile
+    auto piece_of = [&](int S) __attribute__((always_inline)) {
+        const int pc = 16 * S + (lane & 15);
+        return pc < pieces ? pc : 0;
+    };
+    const int trow = lane >> 4;
+
+    // (tile, group) two groups ahead of the one being multiplied; past the end it stays on the last tile
+    int tile_p = tile, S_p = 0;
+    auto advance_p = [&]() __attribute__((always_inline)) {
+        if (++S_p == n_groups) {
+            S_p = 0;
+            tile_p = tile_p + kScoreWaves < tile_end ? tile_p + kScoreWaves : tile_p;
+        }
+    };
+    u32x4_t areg[16];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const u32x4_t *arow = Ab + piece_of(S_p);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int t = tile_p * 32 + trow + 4 * j;
+            areg[half * 8 + j] = __builtin_nontemporal_load(&arow[(size_t)(t < L ? t : L - 1) * pieces]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        advance_p();
+    }
+
+    f32x16_t acc_h, acc_l;  // separate chains for the high parts and the remainders of P
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
+    int S_c = 0;
+    auto finish_group = [&]() __attribute__((always_inline)) {  // closes a tile after its last group
+        if (++S_c < n_groups) return;
+        S_c = 0;
+        const int t = tile * 32 + n;
+        if (t < L) {
+#pragma unroll
+            for (int u = 0; u < GPH; ++u) {
+                float best = acc_h[u * N_REP] + acc_l[u * N_REP];
+#pragma unroll
+                for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
+                const int g = blk * 2 * GPH + hf * GPH + u;
+                // Stored through inline assembly, for two reasons.  A store the compiler knows of inside this
+                // conditional code makes its count of outstanding memory operations uncertain, and it then waits
+                // for *all* prefetches at the top of the loop; unknown to it, the store only makes those waits
+                // slightly stricter.  And the non-temporal hint matters: with the default policy the 4 B/token
+                // of scores cost as much time as 20 % of the whole A^K stream.
+                if (g < H_kv) {
+                    float *dst = S + ((size_t)b * H_kv + g) * L + t;
+                    asm volatile("global_store_dword %0, %1, off nt" : : "v"(dst), "v"(scale * best) : "memory");
+                }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
+        tile += kScoreWaves;
+    };
+    // groups of this wavefront, two per iteration (one per half of the ring); an odd total leaves one surplus
+    // group at the end, which multiplies re-fetched rows of the last tile and is dropped
+    const int my_tiles = (tile_end - tile + kScoreWaves - 1) / kScoreWaves;
+    const int my_groups = my_tiles * n_groups;
+    for (int gi = 0; gi < my_groups; gi += 2) {
+        {
+            const u32x4_t *arow = Ab + piece_of(S_p);
+            const int t0 = tile_p * 32 + trow;
+            advance_p();
+            score_group<0>(acc_h, acc_l, areg, At, Pl + (S_c * 8) * 64 + lane, Pl + (F8 + S_c * 8) * 64 + lane, arow,
+                           pieces, t0, L, woff, rbase);
+            finish_group();
+        }
+        {
+            const u32x4_t *arow = Ab + piece_of(S_p);
+            const int t0 = tile_p * 32 + trow;
+            advance_p();
+            score_group<8>(acc_h, acc_l, areg, At, Pl + (S_c * 8) * 64 + lane, Pl + (F8 + S_c * 8) * 64 + lane, arow,
+                           pieces, t0, L, woff, rbase);
+            if (gi + 1 < my_groups) finish_group();
+        }
     }
 }
 
@@ -303,6 +459,27 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
         if (e != hipSuccess) return e;
         attr_set = true;
+    }
+    // Long streams: one 8-wavefront workgroup per compute unit, every wavefront with at least 8 tiles of its own.
+    const size_t lds_stream = lds + (size_t)kScoreWaves * 512 * 16;
+    const long long total_tiles = (long long)pairs * n_tiles;
+    if (total_tiles >= 256LL * kScoreWaves * 8 && lds_stream <= 160 * 1024 - 512) {
+        static bool attr_stream_set = false;
+        if (!attr_stream_set) {
+            hipError_t e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+            if (e != hipSuccess) return e;
+            attr_stream_set = true;
+        }
+        const int wgs = pairs >= 256 ? 1 : 256 / pairs;
+        int tpw = (n_tiles + wgs - 1) / wgs;
+        tpw = (tpw + kScoreWaves - 1) / kScoreWaves * kScoreWaves;
+        dim3 sgrid((n_tiles + tpw - 1) / tpw, nblk, s.batch);
+        profile_begin(0, st);
+        hipLaunchKernelGGL(score_stream_kernel<N_REP>, sgrid, dim3(kScoreWaves * 64), lds_stream, st, A_k, Pfrag, S, s.L,
+                           s.r_k, s.H_kv, F8, tpw, p.scale);
+        profile_end(0, st);
+        return hipGetLastError();
     }
     dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
     profile_begin(0, st);

@@ -272,3 +272,28 @@ def test_error_codes():
     assert e.value.status == xb.XKV_ERR_INVALID_ARG
     xb.xkv_topk(xb.Shape.of(w, batch=0), t, t, ws)                         # empty batch: no-op
     torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("r_k,H_kv,H_q", [(48, 2, 8), (256, 4, 8), (320, 5, 10)])
+def test_score_long_stream(r_k, H_kv, H_q):
+    """Score stage on a shape long enough for the streaming score kernel (one, two or three 128-rank groups per tile,
+    ragged last tile), every pooled score against the oracle."""
+    w = synth.Workload("long_stream", G=2, H_kv=H_kv, H_q=H_q, d_h=64, r_k=r_k, r_v=32, L=131072 + 5, k=64, batch=4,
+                       dtype="bf16", a_scale=r_k ** -0.5, sigma_decay=0.8, q_scale=0.125)
+    case = synth.make_case(w, seed=11)
+    dev = synth.to_device(case, w.dtype)
+    shape = xb.Shape.of(w)
+    ws = xb.alloc_workspace(shape)
+    torch = torch_mod()
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    layer = 1
+    xb.xkv_score(shape, layer, dev["A_k"], dev["B_k"], dev["q"][layer].contiguous(), S, ws)
+    torch.cuda.synchronize()
+    got = S.cpu().numpy()
+    scale = 1.0 / np.sqrt(w.d_h)
+    for b in range(w.batch):
+        ref = oracle.pooled_scores(synth.storage_to_f64(case["A_k"][b]), synth.storage_to_f64(case["B_k"][b, layer]),
+                                   synth.storage_to_f64(case["q"][layer, b]), w.H_kv, scale)
+        err = max_rel(got[b], ref)
+        assert err <= TOL[w.dtype], (b, err)
