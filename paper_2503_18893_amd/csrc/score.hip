@@ -295,51 +295,52 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);  // [2][F8][64] fragments of 16 B per lane
     constexpr int GPH = 16 / N_REP;
+    // Pooled scores are kept in registers and written in bursts of RT tiles: 4 B per (KV head, token) are only 3 %
+    // of the bytes, but dribbled out between the reads they cost the memory system as much as 15 % of the stream.
+    constexpr int RT = 64 / GPH;
     const int b = blockIdx.z, blk = blockIdx.y, nblk = gridDim.y;
-    const int lane = lane_id(), w = wave_id();
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int n = lane & 31, hf = lane >> 5;
     u32x4_t *At = Pl + 2 * F8 * 64 + w * 512;
-
-    // stage this block's P fragments (hi and lo parts) in LDS, four 16 B loads in flight per thread
-    {
-        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
-        const int total = 2 * F8 * 64;  // a multiple of 1024
-        for (int e0 = threadIdx.x; e0 < total; e0 += 2 * kScoreWaves * 64) {
-            u32x4_t tmp[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) tmp[j] = src[e0 + j * kScoreWaves * 64];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) Pl[e0 + j * kScoreWaves * 64] = tmp[j];
-        }
-    }
-    __syncthreads();
 
     const int pieces = r_k >> 3;  // 16 B pieces per row
     const u32x4_t *Ab = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
     const int n_tiles = (L + 31) / 32;
-    const int tile_begin = blockIdx.x * tiles_per_wg;
-    const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
     const int n_groups = F8 / 8;  // groups per tile
-    int tile = tile_begin + w;
-    if (tile >= tile_end) return;
+    // every wavefront streams one contiguous run of tiles
+    const int per_wave = tiles_per_wg / kScoreWaves;
+    const int wg_end = (blockIdx.x + 1) * tiles_per_wg < n_tiles ? (blockIdx.x + 1) * tiles_per_wg : n_tiles;
+    int tile = blockIdx.x * tiles_per_wg + w * per_wave;
+    const int tile_end = tile + per_wave < wg_end ? tile + per_wave : wg_end;
+    const bool has_work = tile < tile_end;  // wave-uniform
 
     int woff[4];
 #pragma unroll
     for (int qd = 0; qd < 4; ++qd) woff[qd] = 16 * (lane >> 4) + (((lane & 15) + (lane >> 4) + 4 * qd) & 15);
     const int rbase = 16 * n + ((hf + n) & 15);
     // this lane's piece of group S (beyond the row: piece 0, it meets zero P fragments) and first row of a tile
-    auto piece_of = [&](int S) __attribute__((always_inline)) {
-        const int pc = 16 * S + (lane & 15);
+    auto piece_of = [&](int S_) __attribute__((always_inline)) {
+        const int pc = 16 * S_ + (lane & 15);
         return pc < pieces ? pc : 0;
     };
     const int trow = lane >> 4;
 
-    // (tile, group) two groups ahead of the one being multiplied; past the end it stays on the last tile
-    int tile_p = tile, S_p = 0;
+    // first part of this block's P fragments (hi and lo parts), eight 16 B loads in flight per thread ...
+    const u32x4_t *psrc = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
+    const int total = 2 * F8 * 64;  // a multiple of 1024
+    u32x4_t ptmp[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int e0 = tid + j * kScoreWaves * 64;
+        ptmp[j] = psrc[e0 < total ? e0 : tid];
+    }
+    // ... and behind them already the first two groups of A^K.  (tile, group) two groups ahead of the one being
+    // multiplied; past the end it stays on the last tile.
+    int tile_p = has_work ? tile : 0, S_p = 0;
     auto advance_p = [&]() __attribute__((always_inline)) {
         if (++S_p == n_groups) {
             S_p = 0;
-            tile_p = tile_p + kScoreWaves < tile_end ? tile_p + kScoreWaves : tile_p;
+            tile_p = tile_p + 1 < tile_end ? tile_p + 1 : tile_p;
         }
     };
     u32x4_t areg[16];
@@ -354,41 +355,71 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
         }
         advance_p();
     }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int e0 = tid + j * kScoreWaves * 64;
+        if (e0 < total) Pl[e0] = ptmp[j];
+    }
+    for (int e0 = tid + 8 * kScoreWaves * 64; e0 < total; e0 += 2 * kScoreWaves * 64) {
+        u32x4_t tmp[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) tmp[j] = psrc[e0 + j * kScoreWaves * 64];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) Pl[e0 + j * kScoreWaves * 64] = tmp[j];
+    }
+    __syncthreads();
+    if (!has_work) return;
 
     f32x16_t acc_h, acc_l;  // separate chains for the high parts and the remainders of P
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
-    int S_c = 0;
-    auto finish_group = [&]() __attribute__((always_inline)) {  // closes a tile after its last group
-        if (++S_c < n_groups) return;
-        S_c = 0;
-        const int t = tile * 32 + n;
-        if (t < L) {
+    float res[RT][GPH];
 #pragma unroll
-            for (int u = 0; u < GPH; ++u) {
-                float best = acc_h[u * N_REP] + acc_l[u * N_REP];
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
-                const int g = blk * 2 * GPH + hf * GPH + u;
-                // Stored through inline assembly, for two reasons.  A store the compiler knows of inside this
-                // conditional code makes its count of outstanding memory operations uncertain, and it then waits
-                // for *all* prefetches at the top of the loop; unknown to it, the store only makes those waits
-                // slightly stricter.  And the non-temporal hint matters: with the default policy the 4 B/token
-                // of scores cost as much time as 20 % of the whole A^K stream.
-                if (g < H_kv) {
-                    float *dst = S + ((size_t)b * H_kv + g) * L + t;
-                    asm volatile("global_store_dword %0, %1, off nt" : : "v"(dst), "v"(scale * best) : "memory");
+        for (int u = 0; u < GPH; ++u) res[i][u] = 0.0f;
+    int S_c = 0, ti = 0, tile0 = tile;  // group within the tile, tiles held in res, first of them
+    // Stores go through inline assembly: a store the compiler knows of inside conditional code makes its count of
+    // outstanding memory operations uncertain, and it then waits for *all* prefetches at the top of the loop.
+    // Unknown to it, the stores only make those waits stricter for a moment.
+    auto flush = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < RT; ++i) {
+            const int t = (tile0 + i) * 32 + n;
+            if (i < ti && t < L) {
+#pragma unroll
+                for (int u = 0; u < GPH; ++u) {
+                    const int g = blk * 2 * GPH + hf * GPH + u;
+                    if (g < H_kv) {
+                        float *dst = S + ((size_t)b * H_kv + g) * L + t;
+                        asm volatile("global_store_dword %0, %1, off" : : "v"(dst), "v"(res[i][u]) : "memory");
+                    }
                 }
             }
         }
+        tile0 += ti;
+        ti = 0;
+    };
+    auto finish_group = [&]() __attribute__((always_inline)) {  // closes a tile after its last group
+        if (++S_c < n_groups) return;
+        S_c = 0;
+#pragma unroll
+        for (int u = 0; u < GPH; ++u) {
+            float best = acc_h[u * N_REP] + acc_l[u * N_REP];
+#pragma unroll
+            for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
+            best *= scale;
+#pragma unroll
+            for (int i = 0; i < RT; ++i) res[i][u] = (i == ti) ? best : res[i][u];
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
-        tile += kScoreWaves;
+        ++tile;
+        if (++ti == RT) flush();
     };
     // groups of this wavefront, two per iteration (one per half of the ring); an odd total leaves one surplus
     // group at the end, which multiplies re-fetched rows of the last tile and is dropped
-    const int my_tiles = (tile_end - tile + kScoreWaves - 1) / kScoreWaves;
-    const int my_groups = my_tiles * n_groups;
+    const int my_groups = (tile_end - tile) * n_groups;
     for (int gi = 0; gi < my_groups; gi += 2) {
         {
             const u32x4_t *arow = Ab + piece_of(S_p);
@@ -407,6 +438,7 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
             if (gi + 1 < my_groups) finish_group();
         }
     }
+    flush();
 }
 
 static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
