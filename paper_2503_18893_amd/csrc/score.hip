@@ -290,7 +290,8 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
                                                                         const bf16_t *__restrict__ Pfrag,
                                                                         float *__restrict__ S, int L, int r_k,
                                                                         int H_kv, int F8, int tiles_per_wg,
-                                                                        float scale)
+                                                                        float scale, uint32_t *__restrict__ row_hist,
+                                                                        uint32_t *__restrict__ chunk_hist)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);  // [2][F8][64] fragments of 16 B per lane
@@ -302,6 +303,12 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int n = lane & 31, hf = lane >> 5;
     u32x4_t *At = Pl + 2 * F8 * 64 + w * 512;
+    // Optional first pass of the top-k stage: histogram of the top 8 bits of the order key of every pooled
+    // score of this workgroup, one 256-bin histogram per KV head slot of the block.
+    uint32_t *hist = reinterpret_cast<uint32_t *>(Pl + 2 * F8 * 64 + kScoreWaves * 512);  // [2 GPH][256]
+    const bool do_hist = row_hist != nullptr;
+    if (do_hist)
+        for (int i = tid; i < 2 * GPH * kTopkBins; i += kScoreWaves * 64) hist[i] = 0;
 
     const int pieces = r_k >> 3;  // 16 B pieces per row
     const u32x4_t *Ab = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
@@ -368,8 +375,7 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
         for (int j = 0; j < 2; ++j) Pl[e0 + j * kScoreWaves * 64] = tmp[j];
     }
     __syncthreads();
-    if (!has_work) return;
-
+    if (has_work) {
     f32x16_t acc_h, acc_l;  // separate chains for the high parts and the remainders of P
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
@@ -411,11 +417,26 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
             best *= scale;
 #pragma unroll
             for (int i = 0; i < RT; ++i) res[i][u] = (i == ti) ? best : res[i][u];
+            if (do_hist) {
+                // Done per tile, where it hides behind the other wavefronts' memory waits.  Scores cluster in few
+                // bins: one LDS add per distinct (head slot, bin) of the wavefront.
+                const int g = blk * 2 * GPH + hf * GPH + u;
+                const uint32_t slot = (uint32_t)(hf * GPH + u) * kTopkBins + (order_key(best) >> 24);
+                const bool active = tile * 32 + n < L && g < H_kv;
+                uint64_t m = __ballot(active);
+                while (m != 0) {
+                    const int first = __ffsll((unsigned long long)m) - 1;
+                    const uint32_t s0 = (uint32_t)__builtin_amdgcn_readlane((int)slot, first);
+                    const uint64_t same = __ballot(active && slot == s0);
+                    if (lane == first) atomicAdd(&hist[s0], (uint32_t)__popcll(same));
+                    m &= ~same;
+                }
+            }
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
         ++tile;
-        if (++ti == RT) flush();
+        ++ti;
     };
     // groups of this wavefront, two per iteration (one per half of the ring); an odd total leaves one surplus
     // group at the end, which multiplies re-fetched rows of the last tile and is dropped
@@ -437,8 +458,24 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
                            pieces, t0, L, woff, rbase);
             if (gi + 1 < my_groups) finish_group();
         }
+        if (ti > RT - 2) flush();  // up to two tiles complete per iteration
     }
     flush();
+    }
+    if (do_hist) {
+        // this workgroup is chunk blockIdx.x of its rows: keep the chunk histograms, add them to the rows'
+        __syncthreads();
+        const int chunks = gridDim.x;
+        for (int i = tid; i < 2 * GPH * kTopkBins; i += kScoreWaves * 64) {
+            const int g = blk * 2 * GPH + i / kTopkBins, bin = i % kTopkBins;
+            if (g < H_kv) {
+                const size_t row = (size_t)b * H_kv + g;
+                const uint32_t cnt = hist[i];
+                chunk_hist[(row * chunks + blockIdx.x) * kTopkLevels * kTopkBins + bin] = cnt;
+                if (cnt != 0) atomicAdd(&row_hist[row * kTopkLevels * kTopkBins + bin], cnt);
+            }
+        }
+    }
 }
 
 static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
@@ -471,31 +508,38 @@ static hipError_t launch_score_generic(const xkv_shape &s, const Plan &p, int la
     return hipGetLastError();
 }
 
+// Whether a shape goes to the long-stream kernel, with how many 32-token tiles per workgroup, and whether its
+// LDS also has room for the top-digit histograms.  One 8-wavefront workgroup per compute unit in a single
+// round; every wavefront gets at least 8 tiles of its own.
+bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits)
+{
+    *tiles_per_wg = 0;
+    *hist_fits = false;
+    if (s.H_kv <= 0 || s.H_q % s.H_kv != 0) return false;
+    const int n_rep = s.H_q / s.H_kv;
+    const bool rep_ok = (n_rep >= 1 && n_rep <= 8) || n_rep == 16;
+    if (s.dtype != XKV_BF16 || !rep_ok || s.r_k % 16 != 0 || s.d_h % 16 != 0 || s.r_k > 2048) return false;
+    const int F8 = (s.r_k / 16 + 7) / 8 * 8;
+    const int n_tiles = (s.L + 31) / 32;
+    const int pairs = s.batch * mfma_blocks(s.H_kv, n_rep);
+    const size_t lds = (size_t)2 * F8 * 64 * 16 + (size_t)kScoreWaves * 512 * 16;
+    if ((long long)pairs * n_tiles < 256LL * kScoreWaves * 8 || lds > 160 * 1024 - 512) return false;
+    const int wgs = pairs >= 256 ? 1 : 256 / pairs;
+    const int tpw = (n_tiles + wgs - 1) / wgs;
+    *tiles_per_wg = (tpw + kScoreWaves - 1) / kScoreWaves * kScoreWaves;
+    *hist_fits = lds + (size_t)2 * mfma_gph(n_rep) * kTopkBins * 4 <= 160 * 1024 - 512;
+    return true;
+}
+
 template <int N_REP>
 static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const bf16_t *A_k, const bf16_t *Pfrag,
-                                      float *S, int F8, hipStream_t st)
+                                      float *S, int F8, uint32_t *row_hist, uint32_t *chunk_hist, bool *hist_done,
+                                      hipStream_t st)
 {
     const int nblk = mfma_blocks(s.H_kv, N_REP);
     const int n_tiles = (s.L + 31) / 32;
-    // about two workgroups per compute unit in a single round, each streaming one contiguous range of a
-    // sequence (staging P costs a fixed 2 KiB per rank-16 fragment, so fewer, longer workgroups win)
-    const int pairs = s.batch * nblk;
-    const int wgs_per_pair = pairs >= 512 ? 1 : 512 / pairs;
-    int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
-    tiles_per_wg = tiles_per_wg < 4 ? 4 : tiles_per_wg;
-    tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;
     const size_t lds = (size_t)2 * F8 * 64 * 16;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    // Long streams: one 8-wavefront workgroup per compute unit, every wavefront with at least 8 tiles of its own.
-    const size_t lds_stream = lds + (size_t)kScoreWaves * 512 * 16;
-    const long long total_tiles = (long long)pairs * n_tiles;
-    if (total_tiles >= 256LL * kScoreWaves * 8 && lds_stream <= 160 * 1024 - 512) {
+    if (p.score_stream) {
         static bool attr_stream_set = false;
         if (!attr_stream_set) {
             hipError_t e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP>,
@@ -503,15 +547,31 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
             if (e != hipSuccess) return e;
             attr_stream_set = true;
         }
-        const int wgs = pairs >= 256 ? 1 : 256 / pairs;
-        int tpw = (n_tiles + wgs - 1) / wgs;
-        tpw = (tpw + kScoreWaves - 1) / kScoreWaves * kScoreWaves;
-        dim3 sgrid((n_tiles + tpw - 1) / tpw, nblk, s.batch);
+        const bool with_hist = p.score_hist && row_hist && chunk_hist;
+        const size_t lds_stream = lds + (size_t)kScoreWaves * 512 * 16 +
+                                  (with_hist ? (size_t)2 * mfma_gph(N_REP) * kTopkBins * 4 : 0);
+        dim3 sgrid((n_tiles + p.score_tpw - 1) / p.score_tpw, nblk, s.batch);
         profile_begin(0, st);
         hipLaunchKernelGGL(score_stream_kernel<N_REP>, sgrid, dim3(kScoreWaves * 64), lds_stream, st, A_k, Pfrag, S, s.L,
-                           s.r_k, s.H_kv, F8, tpw, p.scale);
+                           s.r_k, s.H_kv, F8, p.score_tpw, p.scale, with_hist ? row_hist : nullptr,
+                           with_hist ? chunk_hist : nullptr);
         profile_end(0, st);
+        if (hist_done) *hist_done = with_hist;
         return hipGetLastError();
+    }
+    // about two workgroups per compute unit in a single round, each streaming one contiguous range of a
+    // sequence (staging P costs a fixed 2 KiB per rank-16 fragment, so fewer, longer workgroups win)
+    const int pairs = s.batch * nblk;
+    const int wgs_per_pair = pairs >= 512 ? 1 : 512 / pairs;
+    int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
+    tiles_per_wg = tiles_per_wg < 4 ? 4 : tiles_per_wg;
+    tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e != hipSuccess) return e;
+        attr_set = true;
     }
     dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
     profile_begin(0, st);
@@ -522,8 +582,10 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
 }
 
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
-                              const void *q, void *P_ws, float *S, hipStream_t st)
+                              const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
+                              bool *hist_done, hipStream_t st)
 {
+    if (hist_done) *hist_done = false;
     if (!score_mfma_ok(s, A_k) || ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) != 0) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, st);
     const int n_rep = s.H_q / s.H_kv;
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;
@@ -536,15 +598,15 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     if (e != hipSuccess) return e;
     const bf16_t *A = (const bf16_t *)A_k;
     switch (n_rep) {
-    case 1: return launch_score_mfma_t<1>(s, p, A, Pfrag, S, F8, st);
-    case 2: return launch_score_mfma_t<2>(s, p, A, Pfrag, S, F8, st);
-    case 3: return launch_score_mfma_t<3>(s, p, A, Pfrag, S, F8, st);
-    case 4: return launch_score_mfma_t<4>(s, p, A, Pfrag, S, F8, st);
-    case 5: return launch_score_mfma_t<5>(s, p, A, Pfrag, S, F8, st);
-    case 6: return launch_score_mfma_t<6>(s, p, A, Pfrag, S, F8, st);
-    case 7: return launch_score_mfma_t<7>(s, p, A, Pfrag, S, F8, st);
-    case 8: return launch_score_mfma_t<8>(s, p, A, Pfrag, S, F8, st);
-    default: return launch_score_mfma_t<16>(s, p, A, Pfrag, S, F8, st);
+    case 1: return launch_score_mfma_t<1>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 2: return launch_score_mfma_t<2>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 3: return launch_score_mfma_t<3>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 4: return launch_score_mfma_t<4>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 5: return launch_score_mfma_t<5>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 6: return launch_score_mfma_t<6>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 7: return launch_score_mfma_t<7>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 8: return launch_score_mfma_t<8>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    default: return launch_score_mfma_t<16>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
     }
 }
 

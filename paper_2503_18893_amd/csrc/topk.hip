@@ -24,14 +24,14 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 struct TopkScratch {
     uint32_t *hist;      // [rows][chunks][4][256] per-chunk digit histograms (level 3: suffix sums)
     uint32_t *state;     // [rows][8]  (prefix, k_rem) after each level
-    uint32_t *row_hist;  // [rows][4][256] per-row digit histograms (level 0 zeroed by topk_init_kernel)
+    uint32_t *row_hist;  // [rows][4][256] per-row digit histograms (zeroed by topk_init_kernel)
     uint32_t *chunk_gt;  // [rows][chunks] keys of the chunk above the threshold by levels 0..2
 };
 
-__global__ void topk_init_kernel(uint32_t *row_hist, int rows)
+__global__ void topk_init_kernel(uint32_t *row_hist, int words)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;  // level 0 of every row
-    if (i < rows * kTopkBins) row_hist[(size_t)(i / kTopkBins) * kTopkLevels * kTopkBins + i % kTopkBins] = 0;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;  // every level of every row
+    if (i < words) row_hist[i] = 0;
 }
 
 // Inclusive suffix sum over the 256 bins held one per thread.  All 256 threads take part.
@@ -76,11 +76,7 @@ __global__ __launch_bounds__(256) void topk_hist_kernel(const float *__restrict_
     uint32_t *row_hist = ws.row_hist + (size_t)row * kTopkLevels * kTopkBins;
     uint32_t *my_hist = ws.hist + ((size_t)row * chunks + c) * kTopkLevels * kTopkBins;
     uint32_t prefix = 0, k_rem = (uint32_t)k;
-    if constexpr (LEVEL == 0) {
-        // the row histograms of the later levels start at zero (nobody adds to them before the next launch)
-        if (c == 0)
-            for (int lv = 1; lv < kTopkLevels; ++lv) row_hist[lv * kTopkBins + threadIdx.x] = 0;
-    } else {
+    if constexpr (LEVEL > 0) {
         if constexpr (LEVEL > 1) {
             prefix = ws.state[(size_t)row * kStateWords + 2 * (LEVEL - 2)];
             k_rem = ws.state[(size_t)row * kStateWords + 2 * (LEVEL - 2) + 1];
@@ -238,19 +234,27 @@ __global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict
     }
 }
 
-hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
-                       uint32_t *state, hipStream_t st)
+hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st)
 {
-    // `state` region: [rows][8] state words, then row histograms [rows][4][256], then chunk_gt [rows][chunks]
+    const int words = p.rows * kTopkLevels * kTopkBins;
+    hipLaunchKernelGGL(topk_init_kernel, dim3((words + 255) / 256), dim3(256), 0, st, topk_row_hist(p, state), words);
+    return hipGetLastError();
+}
+
+hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
+                       uint32_t *state, bool level0_done, hipStream_t st)
+{
     TopkScratch ws;
     ws.hist = hist;
     ws.state = state;
-    ws.row_hist = state + (size_t)p.rows * kStateWords;
+    ws.row_hist = topk_row_hist(p, state);
     ws.chunk_gt = ws.row_hist + (size_t)p.rows * kTopkLevels * kTopkBins;
-    hipLaunchKernelGGL(topk_init_kernel, dim3((p.rows * kTopkBins + 255) / 256), dim3(256), 0, st, ws.row_hist,
-                       p.rows);
     dim3 grid(p.topk_chunks, p.rows), block(256);
-    hipLaunchKernelGGL(topk_hist_kernel<0>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
+    if (!level0_done) {
+        hipError_t e = launch_topk_init(p, state, st);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(topk_hist_kernel<0>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
+    }
     hipLaunchKernelGGL(topk_hist_kernel<1>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
     hipLaunchKernelGGL(topk_hist_kernel<2>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);
     hipLaunchKernelGGL(topk_hist_kernel<3>, grid, block, 0, st, S, ws, s.L, s.k, p.topk_chunks, p.topk_chunk);

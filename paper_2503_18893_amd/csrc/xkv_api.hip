@@ -40,6 +40,15 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     int chunks = clampi(want, 1, clampi(ceil_div(s.L, 1024), 1, 128));
     p.topk_chunk = ceil_div(ceil_div(s.L, chunks), 256) * 256;
     p.topk_chunks = ceil_div(s.L, p.topk_chunk);
+    // When the long-stream score kernel can also histogram the top key digit, the top-k chunks are its
+    // workgroups' token ranges.
+    bool hist_fits = false;
+    p.score_stream = score_stream_plan(s, &p.score_tpw, &hist_fits);
+    p.score_hist = p.score_stream && hist_fits && ceil_div(s.L, 32 * p.score_tpw) <= 128;
+    if (p.score_hist) {
+        p.topk_chunk = 32 * p.score_tpw;
+        p.topk_chunks = ceil_div(s.L, p.topk_chunk);
+    }
 
     // the matrix-core kernel walks 256 selected tokens per workgroup iteration, the general one 16
     p.ga_mfma = gather_attend_mfma_shape_ok(s);
@@ -124,7 +133,7 @@ xkv_status xkv_score(const xkv_shape *shape, int32_t layer, const void *A_k, con
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
     return hip_status(launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), score_out,
-                                         stream));
+                                         nullptr, nullptr, nullptr, stream));
 }
 
 xkv_status xkv_topk(const xkv_shape *shape, const float *score, int32_t *idx_out, void *workspace,
@@ -136,7 +145,7 @@ xkv_status xkv_topk(const xkv_shape *shape, const float *score, int32_t *idx_out
     if (!score || !idx_out) return XKV_ERR_INVALID_ARG;
     if (shape->batch == 0) return XKV_OK;
     return hip_status(launch_topk(*shape, p, score, idx_out, at<uint32_t>(workspace, p.off_hist),
-                                  at<uint32_t>(workspace, p.off_state), (hipStream_t)hip_stream));
+                                  at<uint32_t>(workspace, p.off_state), false, (hipStream_t)hip_stream));
 }
 
 xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
@@ -172,10 +181,15 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
     int32_t *idx = idx_out ? idx_out : at<int32_t>(workspace, p.off_idx);
     float *part_o = at<float>(workspace, p.off_part_o);
     float *part_ml = at<float>(workspace, p.off_part_ml);
-    hipError_t e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S, stream);
+    uint32_t *hist = at<uint32_t>(workspace, p.off_hist), *state = at<uint32_t>(workspace, p.off_state);
+    bool level0_done = false;
+    hipError_t e = hipSuccess;
+    if (p.score_hist) e = launch_topk_init(p, state, stream);  // the score kernel adds to the zeroed row histograms
     if (e == hipSuccess)
-        e = launch_topk(*shape, p, S, idx, at<uint32_t>(workspace, p.off_hist), at<uint32_t>(workspace, p.off_state),
-                        stream);
+        e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
+                               p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
+                               &level0_done, stream);
+    if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, level0_done, stream);
     if (e == hipSuccess)
         e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, at<void>(workspace, p.off_bpack), part_o,
                                  part_ml, stream);

@@ -297,3 +297,14 @@ def test_score_long_stream(r_k, H_kv, H_q):
                                    synth.storage_to_f64(case["q"][layer, b]), w.H_kv, scale)
         err = max_rel(got[b], ref)
         assert err <= TOL[w.dtype], (b, err)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("r_k,H_kv,H_q", [(48, 2, 8), (320, 5, 10)])
+def test_long_stream_chain(r_k, H_kv, H_q):
+    """Whole chain on a long-stream shape: here the score kernel also produces the first radix pass of the
+    selection, so the fused call must still give exactly the ids the oracle selects from the same scores."""
+    w = synth.Workload("long_stream_chain", G=2, H_kv=H_kv, H_q=H_q, d_h=64, r_k=r_k, r_v=64, L=131072 + 5, k=1000,
+                       batch=4, dtype="bf16", a_scale=r_k ** -0.5, sigma_decay=0.8, q_scale=0.125)
+    case = synth.make_case(w, seed=12)
+    check_chain(w, case, layer=0)
