@@ -207,7 +207,7 @@ def main():
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = int(float(line.split(":")[1]))
-    roofline = {"kernel": {"score": "score_mfma_kernel (low-rank score stream + GQA max-pool)",
+    roofline = {"kernel": {"score": "score_stream_kernel / score_mfma_kernel (low-rank score stream + GQA max-pool)",
                            "gather_attend": "gather_attend_mfma_kernel (gather-reconstruct + sparse attention)"}[dom],
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
