@@ -261,7 +261,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restric
 // number so that neither side has bank conflicts (piece c of row t at 16 t + (c + t) % 16, in 16 B units), and
 // read back as one fragment per step.  Two groups are in flight in registers per wavefront; nothing in the
 // main loop needs a barrier (P is read-only in LDS, the tiles are private).
-constexpr int kScoreWaves = 8;
+constexpr int kScoreWaves = 8;  // wavefronts per workgroup; 4 when the P fragments leave no room for 8 tiles
 
 template <int SLOT0>
 __device__ __forceinline__ void score_group(f32x16_t &acc_h, f32x16_t &acc_l, u32x4_t (&areg)[16], u32x4_t *At,
@@ -285,8 +285,8 @@ __device__ __forceinline__ void score_group(f32x16_t &acc_h, f32x16_t &acc_l, u3
     }
 }
 
-template <int N_REP>
-__global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf16_t *__restrict__ A_k,
+template <int N_REP, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *__restrict__ A_k,
                                                                         const bf16_t *__restrict__ Pfrag,
                                                                         float *__restrict__ S, int L, int r_k,
                                                                         int H_kv, int F8, int tiles_per_wg,
@@ -305,17 +305,17 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
     u32x4_t *At = Pl + 2 * F8 * 64 + w * 512;
     // Optional first pass of the top-k stage: histogram of the top 8 bits of the order key of every pooled
     // score of this workgroup, one 256-bin histogram per KV head slot of the block.
-    uint32_t *hist = reinterpret_cast<uint32_t *>(Pl + 2 * F8 * 64 + kScoreWaves * 512);  // [2 GPH][256]
+    uint32_t *hist = reinterpret_cast<uint32_t *>(Pl + 2 * F8 * 64 + WAVES * 512);  // [2 GPH][256]
     const bool do_hist = row_hist != nullptr;
     if (do_hist)
-        for (int i = tid; i < 2 * GPH * kTopkBins; i += kScoreWaves * 64) hist[i] = 0;
+        for (int i = tid; i < 2 * GPH * kTopkBins; i += WAVES * 64) hist[i] = 0;
 
     const int pieces = r_k >> 3;  // 16 B pieces per row
     const u32x4_t *Ab = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
     const int n_tiles = (L + 31) / 32;
     const int n_groups = F8 / 8;  // groups per tile
     // every wavefront streams one contiguous run of tiles
-    const int per_wave = tiles_per_wg / kScoreWaves;
+    const int per_wave = tiles_per_wg / WAVES;
     const int wg_end = (blockIdx.x + 1) * tiles_per_wg < n_tiles ? (blockIdx.x + 1) * tiles_per_wg : n_tiles;
     int tile = blockIdx.x * tiles_per_wg + w * per_wave;
     const int tile_end = tile + per_wave < wg_end ? tile + per_wave : wg_end;
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
     u32x4_t ptmp[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const int e0 = tid + j * kScoreWaves * 64;
+        const int e0 = tid + j * WAVES * 64;
         ptmp[j] = psrc[e0 < total ? e0 : tid];
     }
     // ... and behind them already the first two groups of A^K.  (tile, group) two groups ahead of the one being
@@ -364,15 +364,15 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const int e0 = tid + j * kScoreWaves * 64;
+        const int e0 = tid + j * WAVES * 64;
         if (e0 < total) Pl[e0] = ptmp[j];
     }
-    for (int e0 = tid + 8 * kScoreWaves * 64; e0 < total; e0 += 2 * kScoreWaves * 64) {
+    for (int e0 = tid + 8 * WAVES * 64; e0 < total; e0 += 2 * WAVES * 64) {
         u32x4_t tmp[2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) tmp[j] = psrc[e0 + j * kScoreWaves * 64];
+        for (int j = 0; j < 2; ++j) tmp[j] = psrc[e0 + j * WAVES * 64];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) Pl[e0 + j * kScoreWaves * 64] = tmp[j];
+        for (int j = 0; j < 2; ++j) Pl[e0 + j * WAVES * 64] = tmp[j];
     }
     __syncthreads();
     if (has_work) {
@@ -466,7 +466,7 @@ __global__ __launch_bounds__(kScoreWaves * 64) void score_stream_kernel(const bf
         // this workgroup is chunk blockIdx.x of its rows: keep the chunk histograms, add them to the rows'
         __syncthreads();
         const int chunks = gridDim.x;
-        for (int i = tid; i < 2 * GPH * kTopkBins; i += kScoreWaves * 64) {
+        for (int i = tid; i < 2 * GPH * kTopkBins; i += WAVES * 64) {
             const int g = blk * 2 * GPH + i / kTopkBins, bin = i % kTopkBins;
             if (g < H_kv) {
                 const size_t row = (size_t)b * H_kv + g;
@@ -511,10 +511,11 @@ static hipError_t launch_score_generic(const xkv_shape &s, const Plan &p, int la
 // Whether a shape goes to the long-stream kernel, with how many 32-token tiles per workgroup, and whether its
 // LDS also has room for the top-digit histograms.  One 8-wavefront workgroup per compute unit in a single
 // round; every wavefront gets at least 8 tiles of its own.
-bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits)
+bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits, int *waves)
 {
     *tiles_per_wg = 0;
     *hist_fits = false;
+    *waves = 0;
     if (s.H_kv <= 0 || s.H_q % s.H_kv != 0) return false;
     const int n_rep = s.H_q / s.H_kv;
     const bool rep_ok = (n_rep >= 1 && n_rep <= 8) || n_rep == 16;
@@ -522,12 +523,17 @@ bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits)
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;
     const int n_tiles = (s.L + 31) / 32;
     const int pairs = s.batch * mfma_blocks(s.H_kv, n_rep);
-    const size_t lds = (size_t)2 * F8 * 64 * 16 + (size_t)kScoreWaves * 512 * 16;
-    if ((long long)pairs * n_tiles < 256LL * kScoreWaves * 8 || lds > 160 * 1024 - 512) return false;
+    if ((long long)pairs * n_tiles < 256LL * kScoreWaves * 8) return false;
+    const size_t lds_max = 160 * 1024 - 512, lds_p = (size_t)2 * F8 * 64 * 16;
+    const size_t lds_hist = (size_t)2 * mfma_gph(n_rep) * kTopkBins * 4;
+    int wv = kScoreWaves;
+    if (lds_p + (size_t)wv * 512 * 16 > lds_max) wv = 4;
+    if (lds_p + (size_t)wv * 512 * 16 > lds_max) return false;
     const int wgs = pairs >= 256 ? 1 : 256 / pairs;
     const int tpw = (n_tiles + wgs - 1) / wgs;
     *tiles_per_wg = (tpw + kScoreWaves - 1) / kScoreWaves * kScoreWaves;
-    *hist_fits = lds + (size_t)2 * mfma_gph(n_rep) * kTopkBins * 4 <= 160 * 1024 - 512;
+    *hist_fits = lds_p + (size_t)wv * 512 * 16 + lds_hist <= lds_max;
+    *waves = wv;
     return true;
 }
 
@@ -540,22 +546,38 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
     const int n_tiles = (s.L + 31) / 32;
     const size_t lds = (size_t)2 * F8 * 64 * 16;
     if (p.score_stream) {
-        static bool attr_stream_set = false;
-        if (!attr_stream_set) {
-            hipError_t e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-            if (e != hipSuccess) return e;
-            attr_stream_set = true;
-        }
         const bool with_hist = p.score_hist && row_hist && chunk_hist;
-        const size_t lds_stream = lds + (size_t)kScoreWaves * 512 * 16 +
+        const size_t lds_stream = lds + (size_t)p.score_waves * 512 * 16 +
                                   (with_hist ? (size_t)2 * mfma_gph(N_REP) * kTopkBins * 4 : 0);
         dim3 sgrid((n_tiles + p.score_tpw - 1) / p.score_tpw, nblk, s.batch);
-        profile_begin(0, st);
-        hipLaunchKernelGGL(score_stream_kernel<N_REP>, sgrid, dim3(kScoreWaves * 64), lds_stream, st, A_k, Pfrag, S, s.L,
-                           s.r_k, s.H_kv, F8, p.score_tpw, p.scale, with_hist ? row_hist : nullptr,
-                           with_hist ? chunk_hist : nullptr);
-        profile_end(0, st);
+        hipError_t e = hipSuccess;
+        if (p.score_waves == kScoreWaves) {
+            static bool attr8 = false;
+            if (!attr8) {
+                e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP, kScoreWaves>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+                if (e != hipSuccess) return e;
+                attr8 = true;
+            }
+            profile_begin(0, st);
+            hipLaunchKernelGGL((score_stream_kernel<N_REP, kScoreWaves>), sgrid, dim3(kScoreWaves * 64), lds_stream, st,
+                               A_k, Pfrag, S, s.L, s.r_k, s.H_kv, F8, p.score_tpw, p.scale,
+                               with_hist ? row_hist : nullptr, with_hist ? chunk_hist : nullptr);
+            profile_end(0, st);
+        } else {
+            static bool attr4 = false;
+            if (!attr4) {
+                e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP, 4>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+                if (e != hipSuccess) return e;
+                attr4 = true;
+            }
+            profile_begin(0, st);
+            hipLaunchKernelGGL((score_stream_kernel<N_REP, 4>), sgrid, dim3(4 * 64), lds_stream, st, A_k, Pfrag, S, s.L,
+                               s.r_k, s.H_kv, F8, p.score_tpw, p.scale, with_hist ? row_hist : nullptr,
+                               with_hist ? chunk_hist : nullptr);
+            profile_end(0, st);
+        }
         if (hist_done) *hist_done = with_hist;
         return hipGetLastError();
     }

@@ -234,6 +234,153 @@ __global__ __launch_bounds__(256) void topk_write_kernel(const float *__restrict
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Rows of up to 65536 scores: the whole selection in one launch.  One workgroup of 16 wavefronts owns a row
+// and keeps its keys in registers (NV per thread; wavefront w holds the contiguous segment
+// [w 64 NV, (w+1) 64 NV), element j of a lane is w 64 NV + 64 j + lane), so the row is read from memory once
+// and nothing but the ids is written.  The four 8-bit radix passes histogram into LDS counters that are
+// replicated per lane pair ([bin][lane/2], two 16-bit halves per word: a lane position sees at most
+// 16 NV <= 1024 keys), so the clustered top digits cost no serialised atomics; the replicas are summed, the
+// first wavefront finds the bin of the k-th key, and the pass repeats on the next digit.  The ordered write
+// is the same ballot scheme as topk_write_kernel, fed from the registers.
+// ------------------------------------------------------------------------------------------
+constexpr int kRowWaves = 16;
+
+template <int NV>
+__global__ __launch_bounds__(kRowWaves * 64) void topk_row_kernel(const float *__restrict__ S,
+                                                                 int32_t *__restrict__ idx_out, int L, int k)
+{
+    __shared__ uint32_t hist[kTopkBins * 32];
+    __shared__ uint32_t bins[kTopkBins];
+    __shared__ uint32_t sh[2 + 2 * kRowWaves];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    const float *Srow = S + (size_t)row * L;
+    const int base = w * 64 * NV + lane;
+
+    uint32_t key[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int t = base + 64 * j;
+        key[j] = __float_as_uint(Srow[t < L ? t : L - 1]);
+        if (j % 8 == 7) __builtin_amdgcn_sched_barrier(0);  // bounds the address registers alive at once
+    }
+    // Positions beyond the row get key 0, below every real key (those are clamped to >= 1; only one NaN pattern
+    // maps to 0): they can then be histogrammed and compared like the rest and are never selected, k <= L.
+    // (Each phase recomputes its positions from an opaque copy of `base`; otherwise the compiler keeps all NV of
+    // them in registers from the loads to the final write.)
+    int base_v = base;
+    asm volatile("" : "+v"(base_v));
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const uint32_t kk = order_key(__uint_as_float(key[j]));
+        key[j] = base_v + 64 * j < L ? (kk > 1u ? kk : 1u) : 0u;
+    }
+
+    uint32_t prefix = 0, k_rem = (uint32_t)k;
+#pragma unroll
+    for (int level = 0; level < kTopkLevels; ++level) {
+        for (int i = tid; i < kTopkBins * 32; i += kRowWaves * 64) hist[i] = 0;
+        __syncthreads();
+        const uint32_t inc = 1u << (16 * (lane & 1));
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const bool match = level == 0 || (key[j] >> (32 - 8 * level)) == prefix;
+            const uint32_t digit = (key[j] >> (24 - 8 * level)) & 0xFFu;
+            if (match) atomicAdd(&hist[digit * 32 + (lane >> 1)], inc);
+            if (j % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+        {   // sum the replicas: four threads per bin, eight words each
+            const int bin = tid >> 2, part = tid & 3;
+            uint32_t sum = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t v = hist[bin * 32 + part * 8 + i];
+                sum += (v & 0xFFFFu) + (v >> 16);
+            }
+            sum += __shfl_xor(sum, 1, kWave);
+            sum += __shfl_xor(sum, 2, kWave);
+            if (part == 0) bins[bin] = sum;
+        }
+        __syncthreads();
+        if (w == 0) {  // the bin b with (#keys in bins above b) < k_rem <= (#keys in bins >= b)
+            uint32_t c[4], tot = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                c[i] = bins[4 * lane + i];
+                tot += c[i];
+            }
+            uint32_t sfx = tot;  // keys in the bins of this lane and of all higher lanes
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const uint32_t nb = __shfl_down(sfx, off, kWave);
+                if (lane + off < kWave) sfx += nb;
+            }
+            uint32_t above = sfx - tot;
+#pragma unroll
+            for (int i = 3; i >= 0; --i) {
+                const uint32_t incl = above + c[i];
+                if (above < k_rem && k_rem <= incl) {
+                    sh[0] = (uint32_t)(4 * lane + i);
+                    sh[1] = k_rem - above;
+                }
+                above = incl;
+            }
+        }
+        __syncthreads();
+        prefix = (prefix << 8) | sh[0];
+        k_rem = sh[1];
+    }
+    const uint32_t T = prefix, need_eq = k_rem;  // key of the k-th largest; how many keys equal to it are taken
+
+    // keys above / equal to T in this wavefront's segment, then the ordered write
+    uint32_t my_gt = 0, my_eq = 0;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        my_gt += (uint32_t)__popcll(__ballot(key[j] > T));
+        my_eq += (uint32_t)__popcll(__ballot(key[j] == T));
+        asm volatile("" : "+s"(my_gt), "+s"(my_eq));  // sum as you go: do not collect 2 NV lane masks first
+    }
+    if (lane == 0) {
+        sh[2 + w] = my_gt;
+        sh[2 + kRowWaves + w] = my_eq;
+    }
+    __syncthreads();
+    uint32_t gt_run = 0, eq_run = 0;
+    for (int ww = 0; ww < w; ++ww) {
+        gt_run += sh[2 + ww];
+        eq_run += sh[2 + kRowWaves + ww];
+    }
+    int32_t *out = idx_out + (size_t)row * k;
+    // The comparisons are redone rather than kept: 2 NV lane masks would not fit the scalar registers.  The empty
+    // statement hides from the compiler that Tw is T.
+    uint32_t Tw = T;
+    int base_w = base;
+    asm volatile("" : "+v"(Tw), "+v"(base_w));
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int t = base_w + 64 * j;
+        const bool is_gt = key[j] > Tw, is_eq = key[j] == Tw;
+        const uint64_t mg = __ballot(is_gt), me = __ballot(is_eq);
+        const uint32_t gt_me = gt_run + lanes_below(mg), eq_me = eq_run + lanes_below(me);
+        if (is_gt || (is_eq && eq_me < need_eq)) {
+            const uint32_t pos = gt_me + (eq_me < need_eq ? eq_me : need_eq);
+            if (pos < (uint32_t)k) out[pos] = t;
+        }
+        gt_run += (uint32_t)__popcll(mg);
+        eq_run += (uint32_t)__popcll(me);
+        if (j % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+bool topk_row_shape_ok(const xkv_shape &s) { return s.L <= kRowWaves * 64 * 64; }
+
+template <int NV>
+static void launch_topk_row_t(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, hipStream_t st)
+{
+    hipLaunchKernelGGL(topk_row_kernel<NV>, dim3(p.rows), dim3(kRowWaves * 64), 0, st, S, idx, s.L, s.k);
+}
+
 hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st)
 {
     const int words = p.rows * kTopkLevels * kTopkBins;
@@ -244,6 +391,18 @@ hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st)
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
                        uint32_t *state, bool level0_done, hipStream_t st)
 {
+    if (p.topk_row) {
+        const int per_thread = (s.L + kRowWaves * 64 - 1) / (kRowWaves * 64);
+        if (per_thread <= 8)
+            launch_topk_row_t<8>(s, p, S, idx, st);
+        else if (per_thread <= 16)
+            launch_topk_row_t<16>(s, p, S, idx, st);
+        else if (per_thread <= 32)
+            launch_topk_row_t<32>(s, p, S, idx, st);
+        else
+            launch_topk_row_t<64>(s, p, S, idx, st);
+        return hipGetLastError();
+    }
     TopkScratch ws;
     ws.hist = hist;
     ws.state = state;

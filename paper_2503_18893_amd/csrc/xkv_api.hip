@@ -43,8 +43,9 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     // When the long-stream score kernel can also histogram the top key digit, the top-k chunks are its
     // workgroups' token ranges.
     bool hist_fits = false;
-    p.score_stream = score_stream_plan(s, &p.score_tpw, &hist_fits);
-    p.score_hist = p.score_stream && hist_fits && ceil_div(s.L, 32 * p.score_tpw) <= 128;
+    p.score_stream = score_stream_plan(s, &p.score_tpw, &hist_fits, &p.score_waves);
+    p.topk_row = topk_row_shape_ok(s);  // then the selection needs no histogram from the score kernel
+    p.score_hist = !p.topk_row && p.score_stream && hist_fits && ceil_div(s.L, 32 * p.score_tpw) <= 128;
     if (p.score_hist) {
         p.topk_chunk = 32 * p.score_tpw;
         p.topk_chunks = ceil_div(s.L, p.topk_chunk);

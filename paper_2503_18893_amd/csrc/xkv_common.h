@@ -71,9 +71,11 @@ struct Plan {
     size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, off_bpack, total;
     bool dense_mfma;   // shape fits the matrix-core dense kernel
     bool ga_mfma;      // shape fits the matrix-core gather-attend kernel
+    bool topk_row;     // rows short enough for the one-launch, register-resident selection
     bool score_stream; // shape fits the long-stream score kernel
     bool score_hist;   // ... and that kernel can also histogram the top digit of its scores for the top-k stage
     int score_tpw;     // 32-token tiles per workgroup of that kernel (topk_chunk = 32 * score_tpw when score_hist)
+    int score_waves;   // wavefronts per workgroup of that kernel (8, or 4 at large ranks)
 };
 
 constexpr int kTopkLevels = 4;   // 8-bit digits of the 32-bit order key
@@ -100,13 +102,14 @@ inline void profile_end(int stage, hipStream_t st)
 // Top-k scratch (uint32 words).  `state` region: [rows][8] state words, then the row histograms
 // [rows][4][256], then chunk_gt [rows][chunks]; `hist` region: [rows][chunks][4][256].
 inline uint32_t *topk_row_hist(const Plan &p, uint32_t *state) { return state + (size_t)p.rows * kStateWords; }
-bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits);
+bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits, int *waves);
 // If row_hist/chunk_hist are given and the long-stream kernel runs, it also adds the histogram of the top
 // 8 key bits of every pooled score to the row histograms (already zeroed) and stores the per-chunk
 // histograms; *hist_done tells whether it did.
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
                               bool *hist_done, hipStream_t st);
+bool topk_row_shape_ok(const xkv_shape &s);
 hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st);
 // level0_done: launch_topk_init ran and the level-0 histograms were already accumulated by the score stage.
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,

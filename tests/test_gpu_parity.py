@@ -308,3 +308,29 @@ def test_long_stream_chain(r_k, H_kv, H_q):
                        batch=4, dtype="bf16", a_scale=r_k ** -0.5, sigma_decay=0.8, q_scale=0.125)
     case = synth.make_case(w, seed=12)
     check_chain(w, case, layer=0)
+
+
+@pytest.mark.gpu
+def test_score_long_stream_large_rank():
+    """Rank 768 leaves LDS room for only four wavefront tiles in the streaming score kernel: that variant, on
+    device-generated inputs, checked on token ranges at the start, in the middle and at the ragged end."""
+    torch = torch_mod()
+    w = synth.Workload("long_stream_r768", G=1, H_kv=6, H_q=12, d_h=128, r_k=768, r_v=32, L=131072 + 9, k=64, batch=4,
+                       dtype="bf16", a_scale=768 ** -0.5, sigma_decay=0.8, q_scale=128 ** -0.5)
+    dev = synth.make_group_device(w, seed=21)
+    shape = xb.Shape.of(w)
+    ws = xb.alloc_workspace(shape)
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    xb.xkv_score(shape, 0, dev["A_k"], dev["B_k"], dev["q"][0].contiguous(), S, ws)
+    torch.cuda.synchronize()
+    scale = 1.0 / np.sqrt(w.d_h)
+    ranges = [(0, 300), (65536 - 150, 65536 + 150), (w.L - 300, w.L)]
+    for b in (0, w.batch - 1):
+        B_k = synth.storage_to_f64(synth.to_host(dev["B_k"][b, 0]))
+        q = synth.storage_to_f64(synth.to_host(dev["q"][0, b]))
+        for lo, hi in ranges:
+            A_rows = synth.storage_to_f64(synth.to_host(dev["A_k"][b, lo:hi]))
+            ref = oracle.pooled_scores(A_rows, B_k, q, w.H_kv, scale)
+            got = S[b, :, lo:hi].cpu().numpy()
+            err = max_rel(got, ref)
+            assert err <= TOL[w.dtype], (b, lo, err)
