@@ -153,12 +153,19 @@ static hipError_t launch_generic(const xkv_shape &s, const Plan &p, int layer, c
     return hipGetLastError();
 }
 
+bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, const void *B_k, const void *B_v,
+                             const void *pack_ws)
+{
+    return p.ga_mfma &&
+           ((((uintptr_t)A_k | (uintptr_t)A_v | (uintptr_t)B_k | (uintptr_t)B_v | (uintptr_t)pack_ws)) & 15u) == 0;
+}
+
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
-                                float *part_o, float *part_ml, hipStream_t st)
+                                bool packed, float *part_o, float *part_ml, hipStream_t st)
 {
-    if (p.ga_mfma && ((((uintptr_t)A_k | (uintptr_t)A_v | (uintptr_t)B_k | (uintptr_t)B_v | (uintptr_t)pack_ws)) & 15u) == 0)
-        return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, part_o, part_ml, st);
+    if (gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws))
+        return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml, st);
     if (s.dtype == XKV_F32)
         return launch_generic<float>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st);
     return launch_generic<bf16_t>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st);

@@ -18,6 +18,7 @@
 #include <type_traits>
 
 #include "xkv_common.h"
+#include "prepass.h"
 
 namespace xkv {
 
@@ -29,60 +30,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 constexpr int kMaxChunkTokens = 4096;  // selected tokens per workgroup (their ids sit in LDS)
 constexpr int kGroup = 8;  // fragments (of 16 ranks) per LDS stage: 8 x 4 KiB = 32 KiB, two stages
 
-// Pack B_{l,g} (r x 128 slice of B_l) into MFMA fragment order:
-//   pack[f][db][hf*32 + c][e] = B[16f + 8hf + e][g*128 + db*32 + c],  zero beyond r.
-// Output per (sequence, KV head): F8k fragment rows for K then F8v for V, 4 KiB each, F8 = roundup(r/16, 16).
-__global__ __launch_bounds__(256) void pack_b_kernel(const bf16_t *__restrict__ B_k, const bf16_t *__restrict__ B_v,
-                                                     const bf16_t *__restrict__ q, u32x4_t *__restrict__ pack,
-                                                     int G, int layer, int r_k, int r_v, int H_kv, int H_q, int F8k,
-                                                     int F8v)
+__global__ __launch_bounds__(256) void pack_b_kernel(PackArgs a)
 {
-    // one thread per (fragment f, half hf, dim block db, 4 columns): 8 rows x 8 B in, 4 lanes' 16 B pieces out
-    const int g = blockIdx.y, b = blockIdx.z;
-    const int d = H_kv * 128;
-    const int item = blockIdx.x * 256 + threadIdx.x;
-    if (item >= (F8k + F8v) * 64) {
-        // the last 512 items build the eight Q^T fragments of this (sequence, KV head), stored behind the B
-        // fragments: lane (head slot n, hf), position e of fragment (db, j) holds q[n][db*32 + 8(2j + e/4) + 4hf + e%4]
-        const int qi = item - (F8k + F8v) * 64;
-        if (qi >= 8 * 64) return;
-        const int lane = qi & 63, fj = qi >> 6, db = fj >> 1, j = fj & 1;
-        const int n = lane & 31, hf = lane >> 5, n_rep = H_q / H_kv;
-        const bf16_t *qh = q + ((size_t)b * H_q + (size_t)g * n_rep + (n < n_rep ? n : 0)) * 128;
-        u32x4_t raw;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            const int e = 2 * e2;
-            const int dim = db * 32 + 8 * (2 * j + e / 4) + 4 * hf + e % 4;  // e and e+1 are adjacent dims
-            raw[e2] = n < n_rep ? *reinterpret_cast<const uint32_t *>(qh + dim) : 0u;
-        }
-        pack[((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(F8k + F8v) * 256 + qi] = raw;
-        return;
-    }
-    const int c4 = item & 7, db = (item >> 3) & 3, hf = (item >> 5) & 1, fa = item >> 6;
-    const bool is_v = fa >= F8k;
-    const int f = is_v ? fa - F8k : fa;
-    const int r = is_v ? r_v : r_k;
-    const bf16_t *src = (is_v ? B_v : B_k) + ((size_t)b * G + layer) * r * d + (size_t)g * 128 + db * 32 + c4 * 4;
-    uint64_t wd[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int i = 16 * f + 8 * hf + e;
-        wd[e] = i < r ? *reinterpret_cast<const uint64_t *>(src + (size_t)i * d) : 0ull;
-    }
-    u32x4_t *dst = pack + ((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(fa * 4 + db) * 64 +
-                   hf * 32 + c4 * 4;
-#pragma unroll
-    for (int cc = 0; cc < 4; ++cc) {
-        u32x4_t o;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            const uint32_t lo = (uint32_t)(wd[2 * e2] >> (16 * cc)) & 0xFFFFu;
-            const uint32_t hi = (uint32_t)(wd[2 * e2 + 1] >> (16 * cc)) & 0xFFFFu;
-            o[e2] = lo | (hi << 16);
-        }
-        dst[cc] = o;
-    }
+    pack_b_block(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t &c, int j)
@@ -420,16 +370,39 @@ size_t gather_attend_pack_bytes(const xkv_shape &s)
     return (size_t)(s.batch > 0 ? s.batch : 1) * s.H_kv * ((size_t)(F8k + F8v) * 4 * 1024 + 8 * 1024);
 }
 
+PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k, const void *B_v, const void *q,
+                                  void *pack_ws)
+{
+    PackArgs a;
+    a.B_k = (const bf16_t *)B_k;
+    a.B_v = (const bf16_t *)B_v;
+    a.q = (const bf16_t *)q;
+    a.pack = (pack_u32x4_t *)pack_ws;
+    a.G = s.G;
+    a.layer = layer;
+    a.r_k = s.r_k;
+    a.r_v = s.r_v;
+    a.H_kv = s.H_kv;
+    a.H_q = s.H_q;
+    a.F8k = (s.r_k / 16 + 15) / 16 * 16;  // padded to whole pairs of groups
+    a.F8v = (s.r_v / 16 + 15) / 16 * 16;
+    a.batch = s.batch;
+    a.blocks_per_head = ((a.F8k + a.F8v) * 64 + 512 + 255) / 256;
+    return a;
+}
+
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
-                                     void *pack_ws, float *part_o, float *part_ml, hipStream_t st)
+                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st)
 {
-    const int F8k = (s.r_k / 16 + 15) / 16 * 16, F8v = (s.r_v / 16 + 15) / 16 * 16;  // padded to whole pairs of groups
-    dim3 pgrid(((F8k + F8v) * 64 + 512 + 255) / 256, s.H_kv, s.batch), block(256);
-    hipLaunchKernelGGL(pack_b_kernel, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)B_v, (const bf16_t *)q,
-                       (u32x4_t *)pack_ws, s.G, layer, s.r_k, s.r_v, s.H_kv, s.H_q, F8k, F8v);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    const PackArgs pa = gather_attend_pack_args(s, layer, B_k, B_v, q, pack_ws);
+    const int F8k = pa.F8k, F8v = pa.F8v;
+    hipError_t e = hipSuccess;
+    if (!packed) {
+        hipLaunchKernelGGL(pack_b_kernel, dim3(pa.blocks_per_head, s.H_kv, s.batch), dim3(256), 0, st, pa);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (p.sr_chunk > kMaxChunkTokens) return hipErrorInvalidValue;
     const size_t lds = kLdsB + kLdsA + kLdsQ + (size_t)p.sr_chunk * 4;  // B fragments, A tiles, Q fragments, token ids
     static bool attr_set = false;

@@ -1,0 +1,136 @@
+// The two small passes over the per-layer reconstruction matrices that precede the big kernels: the query
+// projection into the rank space (for the score kernel) and the packing of B_l into matrix-core fragment order
+// (for the gather-attend kernel).  Both depend only on the call's inputs, so xkv_sr_decode runs them in one
+// launch; the stage entry points launch them separately.
+#ifndef XKV_PREPASS_H
+#define XKV_PREPASS_H
+
+#include "xkv_common.h"
+
+namespace xkv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 pp_bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float pp_f32x16_t;
+
+__host__ __device__ inline int mfma_gph(int n_rep) { return 16 / n_rep; }
+__host__ __device__ inline int mfma_blocks(int H_kv, int n_rep) { return (H_kv + 2 * mfma_gph(n_rep) - 1) / (2 * mfma_gph(n_rep)); }
+
+// One wavefront per (slot position, block of 32 ranks): P_g [head slots x 32 ranks] = Q_g [slots x d_h] . B_g^T on
+// the matrix cores, both operands straight from global memory (lane (x, hf) holds 8 consecutive head
+// dims of query slot x / of row i0 + x of B^K_l, KV head g).  In the result lane (n, hf) holds rank i0 + n
+// and head slots 8(v/4) + 4hf + v%4; it splits each value into a bf16 high part and remainder and stores
+// both at their place in the fragment layout.  Positions are (block, half, u); positions without a KV
+// head, ranks beyond r_k and the unused tail of a half are written as zeros.
+// Pfrag layout: [batch][block][part(hi,lo)][F8 fragments][64 lanes][8 bf16], F8 = roundup(r_k/16, 8).
+__device__ __forceinline__ void project_q_frag_block(const ProjArgs &a, int blk_x, int b)
+{
+    const bf16_t *__restrict__ B_k = a.B_k, *__restrict__ q = a.q;
+    bf16_t *__restrict__ Pfrag = a.Pfrag;
+    const int G = a.G, layer = a.layer, r_k = a.r_k, H_kv = a.H_kv, H_q = a.H_q, d_h = a.d_h, F8 = a.F8;
+    const int n_rep = H_q / H_kv, d = H_kv * d_h;
+    const int gph = mfma_gph(n_rep), nblk = mfma_blocks(H_kv, n_rep);
+    const int n_pos = 2 * gph * nblk, n_rb = F8 / 2;  // rank blocks of 32
+    const int item = blk_x * 4 + wave_id();
+    if (item >= n_pos * n_rb) return;
+    const int pos = item % n_pos, i0 = (item / n_pos) * 32;
+    const int u = pos % gph, ghf = (pos / gph) % 2, blk = pos / (2 * gph);
+    const int g = blk * 2 * gph + ghf * gph + u;
+    const int lane = lane_id(), n = lane & 31, hf = lane >> 5;
+    pp_f32x16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    if (g < H_kv) {
+        const int i = i0 + n < r_k ? i0 + n : r_k - 1;
+        const pack_u32x4_t *brow = reinterpret_cast<const pack_u32x4_t *>(B_k + (((size_t)b * G + layer) * r_k + i) * d +
+                                                                 (size_t)g * d_h) + hf;
+        const pack_u32x4_t *qrow = reinterpret_cast<const pack_u32x4_t *>(q + ((size_t)b * H_q + (size_t)g * n_rep +
+                                                                     (n < n_rep ? n : 0)) * d_h) + hf;
+        for (int f = 0; f < d_h / 16; ++f) {
+            pack_u32x4_t qa = qrow[2 * f];
+            if (n >= n_rep) qa = pack_u32x4_t{0u, 0u, 0u, 0u};
+            pack_u32x4_t ba = brow[2 * f];
+            if (i0 + n >= r_k) ba = pack_u32x4_t{0u, 0u, 0u, 0u};
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pp_bf16x8_t, qa),
+                                                          __builtin_bit_cast(pp_bf16x8_t, ba), acc, 0, 0, 0);
+        }
+    }
+    // this lane's rank and where it sits in the fragment layout
+    const int i = i0 + n;
+    const int f = i / 16, khf = (i % 16) / 8, e = i % 8;
+    const size_t part_stride = (size_t)F8 * 64 * 8;
+    bf16_t *base = Pfrag + ((size_t)b * nblk + blk) * 2 * part_stride + ((size_t)f * 64 + khf * 32) * 8 + e;
+    // registers of this position: vv in [u n_rep, (u+1) n_rep); the last position also clears the unused tail
+    const int vv_end = (u == gph - 1) ? 16 : (u + 1) * n_rep;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        const int hh = 8 * (v / 4) + 4 * hf + (v % 4);  // head slot held in acc[v] by this half
+        const int vv = u * n_rep + hh;
+        if (vv < vv_end) {
+            const float val = (hh < n_rep && g < H_kv) ? acc[v] : 0.0f;
+            const int m = 8 * (vv / 4) + 4 * ghf + (vv % 4);  // row of the score MFMA
+            const bf16_t hi = f32_to_bf16(val);
+            const bf16_t lo = f32_to_bf16(val - bf16_to_f32(hi));
+            base[(size_t)m * 8] = hi;
+            base[part_stride + (size_t)m * 8] = lo;
+        }
+    }
+}
+
+// Pack B_{l,g} (r x 128 slice of B_l) into MFMA fragment order:
+//   pack[f][db][hf*32 + c][e] = B[16f + 8hf + e][g*128 + db*32 + c],  zero beyond r.
+// Output per (sequence, KV head): F8k fragment rows for K then F8v for V, 4 KiB each, F8 = roundup(r/16, 16).
+__device__ __forceinline__ void pack_b_block(const PackArgs &a, int blk, int g, int b)
+{
+    const bf16_t *__restrict__ B_k = a.B_k, *__restrict__ B_v = a.B_v, *__restrict__ q = a.q;
+    pack_u32x4_t *__restrict__ pack = a.pack;
+    const int G = a.G, layer = a.layer, r_k = a.r_k, r_v = a.r_v, H_kv = a.H_kv, H_q = a.H_q, F8k = a.F8k, F8v = a.F8v;
+    typedef pack_u32x4_t u32x4_t;
+    // one thread per (fragment f, half hf, dim block db, 4 columns): 8 rows x 8 B in, 4 lanes' 16 B pieces out
+    const int d = H_kv * 128;
+    const int item = blk * 256 + threadIdx.x;
+    if (item >= (F8k + F8v) * 64) {
+        // the last 512 items build the eight Q^T fragments of this (sequence, KV head), stored behind the B
+        // fragments: lane (head slot n, hf), position e of fragment (db, j) holds q[n][db*32 + 8(2j + e/4) + 4hf + e%4]
+        const int qi = item - (F8k + F8v) * 64;
+        if (qi >= 8 * 64) return;
+        const int lane = qi & 63, fj = qi >> 6, db = fj >> 1, j = fj & 1;
+        const int n = lane & 31, hf = lane >> 5, n_rep = H_q / H_kv;
+        const bf16_t *qh = q + ((size_t)b * H_q + (size_t)g * n_rep + (n < n_rep ? n : 0)) * 128;
+        u32x4_t raw;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const int e = 2 * e2;
+            const int dim = db * 32 + 8 * (2 * j + e / 4) + 4 * hf + e % 4;  // e and e+1 are adjacent dims
+            raw[e2] = n < n_rep ? *reinterpret_cast<const uint32_t *>(qh + dim) : 0u;
+        }
+        pack[((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(F8k + F8v) * 256 + qi] = raw;
+        return;
+    }
+    const int c4 = item & 7, db = (item >> 3) & 3, hf = (item >> 5) & 1, fa = item >> 6;
+    const bool is_v = fa >= F8k;
+    const int f = is_v ? fa - F8k : fa;
+    const int r = is_v ? r_v : r_k;
+    const bf16_t *src = (is_v ? B_v : B_k) + ((size_t)b * G + layer) * r * d + (size_t)g * 128 + db * 32 + c4 * 4;
+    uint64_t wd[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int i = 16 * f + 8 * hf + e;
+        wd[e] = i < r ? *reinterpret_cast<const uint64_t *>(src + (size_t)i * d) : 0ull;
+    }
+    u32x4_t *dst = pack + ((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(fa * 4 + db) * 64 +
+                   hf * 32 + c4 * 4;
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+        u32x4_t o;
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            const uint32_t lo = (uint32_t)(wd[2 * e2] >> (16 * cc)) & 0xFFFFu;
+            const uint32_t hi = (uint32_t)(wd[2 * e2 + 1] >> (16 * cc)) & 0xFFFFu;
+            o[e2] = lo | (hi << 16);
+        }
+        dst[cc] = o;
+    }
+}
+
+}  // namespace xkv
+#endif

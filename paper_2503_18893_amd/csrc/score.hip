@@ -3,6 +3,7 @@
 //   s[h,t] = scale * A^K[t,:] . p_h               (App. B.1 Alg. 2, scaled scores, per token)
 //   S[g,t] = max_{h: rho(h)=g} s[h,t]             (App. B.1 Alg. 2, GQA pooling)
 #include "xkv_common.h"
+#include "prepass.h"
 
 namespace xkv {
 
@@ -98,68 +99,22 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-__host__ __device__ inline int mfma_gph(int n_rep) { return 16 / n_rep; }
-__host__ __device__ inline int mfma_blocks(int H_kv, int n_rep) { return (H_kv + 2 * mfma_gph(n_rep) - 1) / (2 * mfma_gph(n_rep)); }
 
-// One wavefront per (slot position, block of 32 ranks): P_g [head slots x 32 ranks] = Q_g [slots x d_h] . B_g^T on
-// the matrix cores, both operands straight from global memory (lane (x, hf) holds 8 consecutive head
-// dims of query slot x / of row i0 + x of B^K_l, KV head g).  In the result lane (n, hf) holds rank i0 + n
-// and head slots 8(v/4) + 4hf + v%4; it splits each value into a bf16 high part and remainder and stores
-// both at their place in the fragment layout.  Positions are (block, half, u); positions without a KV
-// head, ranks beyond r_k and the unused tail of a half are written as zeros.
-// Pfrag layout: [batch][block][part(hi,lo)][F8 fragments][64 lanes][8 bf16], F8 = roundup(r_k/16, 8).
-__global__ __launch_bounds__(256) void project_q_frag_kernel(const bf16_t *__restrict__ B_k,
-                                                             const bf16_t *__restrict__ q,
-                                                             bf16_t *__restrict__ Pfrag, int G, int layer, int r_k,
-                                                             int H_kv, int H_q, int d_h, int F8)
+__global__ __launch_bounds__(256) void project_q_frag_kernel(ProjArgs a)
 {
-    const int n_rep = H_q / H_kv, d = H_kv * d_h;
-    const int gph = mfma_gph(n_rep), nblk = mfma_blocks(H_kv, n_rep);
-    const int n_pos = 2 * gph * nblk, n_rb = F8 / 2;  // rank blocks of 32
-    const int b = blockIdx.y;
-    const int item = blockIdx.x * 4 + wave_id();
-    if (item >= n_pos * n_rb) return;
-    const int pos = item % n_pos, i0 = (item / n_pos) * 32;
-    const int u = pos % gph, ghf = (pos / gph) % 2, blk = pos / (2 * gph);
-    const int g = blk * 2 * gph + ghf * gph + u;
-    const int lane = lane_id(), n = lane & 31, hf = lane >> 5;
-    f32x16_t acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-    if (g < H_kv) {
-        const int i = i0 + n < r_k ? i0 + n : r_k - 1;
-        const u32x4_t *brow = reinterpret_cast<const u32x4_t *>(B_k + (((size_t)b * G + layer) * r_k + i) * d +
-                                                                 (size_t)g * d_h) + hf;
-        const u32x4_t *qrow = reinterpret_cast<const u32x4_t *>(q + ((size_t)b * H_q + (size_t)g * n_rep +
-                                                                     (n < n_rep ? n : 0)) * d_h) + hf;
-        for (int f = 0; f < d_h / 16; ++f) {
-            u32x4_t qa = qrow[2 * f];
-            if (n >= n_rep) qa = u32x4_t{0u, 0u, 0u, 0u};
-            u32x4_t ba = brow[2 * f];
-            if (i0 + n >= r_k) ba = u32x4_t{0u, 0u, 0u, 0u};
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, qa),
-                                                          __builtin_bit_cast(bf16x8_t, ba), acc, 0, 0, 0);
-        }
-    }
-    // this lane's rank and where it sits in the fragment layout
-    const int i = i0 + n;
-    const int f = i / 16, khf = (i % 16) / 8, e = i % 8;
-    const size_t part_stride = (size_t)F8 * 64 * 8;
-    bf16_t *base = Pfrag + ((size_t)b * nblk + blk) * 2 * part_stride + ((size_t)f * 64 + khf * 32) * 8 + e;
-    // registers of this position: vv in [u n_rep, (u+1) n_rep); the last position also clears the unused tail
-    const int vv_end = (u == gph - 1) ? 16 : (u + 1) * n_rep;
-#pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        const int hh = 8 * (v / 4) + 4 * hf + (v % 4);  // head slot held in acc[v] by this half
-        const int vv = u * n_rep + hh;
-        if (vv < vv_end) {
-            const float val = (hh < n_rep && g < H_kv) ? acc[v] : 0.0f;
-            const int m = 8 * (vv / 4) + 4 * ghf + (vv % 4);  // row of the score MFMA
-            const bf16_t hi = f32_to_bf16(val);
-            const bf16_t lo = f32_to_bf16(val - bf16_to_f32(hi));
-            base[(size_t)m * 8] = hi;
-            base[part_stride + (size_t)m * 8] = lo;
-        }
+    project_q_frag_block(a, blockIdx.x, blockIdx.y);
+}
+
+// One launch for both small passes: blocks [0, n_proj) project the queries, the rest pack B for the gather-attend
+// kernel (see prepass.h).
+__global__ __launch_bounds__(256) void prepass_kernel(ProjArgs pj, PackArgs pk, int n_proj)
+{
+    if ((int)blockIdx.x < n_proj) {
+        project_q_frag_block(pj, (int)blockIdx.x % pj.blocks_x, (int)blockIdx.x / pj.blocks_x);
+    } else {
+        const int pl = (int)blockIdx.x - n_proj;
+        pack_b_block(pk, pl % pk.blocks_per_head, (pl / pk.blocks_per_head) % pk.H_kv,
+                     pl / (pk.blocks_per_head * pk.H_kv));
     }
 }
 
@@ -605,17 +560,35 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
 
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
-                              bool *hist_done, hipStream_t st)
+                              bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st)
 {
     if (hist_done) *hist_done = false;
+    if (packed_done) *packed_done = false;
     if (!score_mfma_ok(s, A_k) || ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) != 0) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, st);
     const int n_rep = s.H_q / s.H_kv;
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;
     const int gph = mfma_gph(n_rep), nblk = mfma_blocks(s.H_kv, n_rep);
     bf16_t *Pfrag = (bf16_t *)P_ws;
-    dim3 pgrid(((F8 / 2) * 2 * gph * nblk + 3) / 4, s.batch), block(256);
-    hipLaunchKernelGGL(project_q_frag_kernel, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q, Pfrag, s.G,
-                       layer, s.r_k, s.H_kv, s.H_q, s.d_h, F8);
+    ProjArgs pj;
+    pj.B_k = (const bf16_t *)B_k;
+    pj.q = (const bf16_t *)q;
+    pj.Pfrag = Pfrag;
+    pj.G = s.G;
+    pj.layer = layer;
+    pj.r_k = s.r_k;
+    pj.H_kv = s.H_kv;
+    pj.H_q = s.H_q;
+    pj.d_h = s.d_h;
+    pj.F8 = F8;
+    pj.blocks_x = ((F8 / 2) * 2 * gph * nblk + 3) / 4;
+    if (fuse_pack) {
+        const int n_proj = pj.blocks_x * s.batch;
+        const int n_pack = fuse_pack->blocks_per_head * fuse_pack->H_kv * fuse_pack->batch;
+        hipLaunchKernelGGL(prepass_kernel, dim3(n_proj + n_pack), dim3(256), 0, st, pj, *fuse_pack, n_proj);
+        if (packed_done) *packed_done = true;
+    } else {
+        hipLaunchKernelGGL(project_q_frag_kernel, dim3(pj.blocks_x, s.batch), dim3(256), 0, st, pj);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const bf16_t *A = (const bf16_t *)A_k;

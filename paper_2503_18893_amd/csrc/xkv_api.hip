@@ -134,7 +134,7 @@ xkv_status xkv_score(const xkv_shape *shape, int32_t layer, const void *A_k, con
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
     return hip_status(launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), score_out,
-                                         nullptr, nullptr, nullptr, stream));
+                                         nullptr, nullptr, nullptr, nullptr, nullptr, stream));
 }
 
 xkv_status xkv_topk(const xkv_shape *shape, const float *score, int32_t *idx_out, void *workspace,
@@ -162,9 +162,12 @@ xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *
     hipStream_t stream = (hipStream_t)hip_stream;
     float *part_o = at<float>(workspace, p.off_part_o);
     float *part_ml = at<float>(workspace, p.off_part_ml);
-    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, at<void>(workspace, p.off_bpack), part_o,
-                                 part_ml, stream);
-    if (e == hipSuccess) e = launch_combine(*shape, p.ga_mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
+    void *pack_ws = at<void>(workspace, p.off_bpack);
+    const bool mfma = gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws);
+    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, false, part_o, part_ml,
+                                        stream);
+    // the matrix-core kernel writes one partial per split, the general one one per wavefront
+    if (e == hipSuccess) e = launch_combine(*shape, mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
 }
 
@@ -186,15 +189,22 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
     bool level0_done = false;
     hipError_t e = hipSuccess;
     if (p.score_hist) e = launch_topk_init(p, state, stream);  // the score kernel adds to the zeroed row histograms
+    // B is packed for the matrix-core gather-attend kernel in the same launch as the query projection
+    void *pack_ws = at<void>(workspace, p.off_bpack);
+    PackArgs pa{};
+    const bool want_pack = gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws);
+    if (want_pack) pa = gather_attend_pack_args(*shape, layer, B_k, B_v, q, pack_ws);
+    bool packed = false;
     if (e == hipSuccess)
         e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
                                p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
-                               &level0_done, stream);
+                               &level0_done, want_pack ? &pa : nullptr, &packed, stream);
     if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, level0_done, stream);
     if (e == hipSuccess)
-        e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, at<void>(workspace, p.off_bpack), part_o,
-                                 part_ml, stream);
-    if (e == hipSuccess) e = launch_combine(*shape, p.ga_mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
+        e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml,
+                                 stream);
+    // the matrix-core kernel writes one partial per split, the general one one per wavefront
+    if (e == hipSuccess) e = launch_combine(*shape, want_pack ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
 }
 
@@ -210,7 +220,9 @@ xkv_status xkv_dense_decode(const xkv_shape *shape, const void *K, const void *V
     float *part_o = at<float>(workspace, p.off_part_o);
     float *part_ml = at<float>(workspace, p.off_part_ml);
     hipError_t e = launch_dense(*shape, p, K, V, q, part_o, part_ml, stream);
-    if (e == hipSuccess) e = launch_combine(*shape, p.dense_mfma ? p.dense_splits : p.dense_splits * 4, part_o, part_ml, out, stream);
+    // same test as launch_dense: the matrix-core kernel writes one partial per split, the general one one per wavefront
+    const bool mfma = p.dense_mfma && ((((uintptr_t)K | (uintptr_t)V | (uintptr_t)q)) & 15u) == 0;
+    if (e == hipSuccess) e = launch_combine(*shape, mfma ? p.dense_splits : p.dense_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
 }
 

@@ -98,30 +98,52 @@ inline void profile_end(int stage, hipStream_t st)
     if (g_profile[stage].start && g_profile[stage].stop) (void)hipEventRecord(g_profile[stage].stop, st);
 }
 
+// Arguments of the two small passes over B_l (see prepass.h): the query projection into hi/lo bf16 fragments
+// and the packing of B_l and the query heads into matrix-core fragment order.
+typedef __attribute__((ext_vector_type(4))) uint32_t pack_u32x4_t;
+struct ProjArgs {
+    const bf16_t *B_k, *q;
+    bf16_t *Pfrag;
+    int G, layer, r_k, H_kv, H_q, d_h, F8;
+    int blocks_x;  // 256-thread blocks per sequence
+};
+struct PackArgs {
+    const bf16_t *B_k, *B_v, *q;
+    pack_u32x4_t *pack;
+    int G, layer, r_k, r_v, H_kv, H_q, F8k, F8v, batch;
+    int blocks_per_head;  // 256-item blocks per (sequence, KV head): B items, then 512 items for the Q^T fragments
+};
+
 // Kernel launchers (each enqueues on `st`; shapes were validated by the caller).
 // Top-k scratch (uint32 words).  `state` region: [rows][8] state words, then the row histograms
 // [rows][4][256], then chunk_gt [rows][chunks]; `hist` region: [rows][chunks][4][256].
 inline uint32_t *topk_row_hist(const Plan &p, uint32_t *state) { return state + (size_t)p.rows * kStateWords; }
 bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits, int *waves);
-// If row_hist/chunk_hist are given and the long-stream kernel runs, it also adds the histogram of the top
+// fuse_pack (nullable): also pack B for the gather-attend kernel in the projection launch (matrix-core path
+// only; *packed_done tells whether it did).  If row_hist/chunk_hist are given and the long-stream kernel runs, it also adds the histogram of the top
 // 8 key bits of every pooled score to the row histograms (already zeroed) and stores the per-chunk
 // histograms; *hist_done tells whether it did.
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
-                              bool *hist_done, hipStream_t st);
+                              bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st);
 bool topk_row_shape_ok(const xkv_shape &s);
 hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st);
 // level0_done: launch_topk_init ran and the level-0 histograms were already accumulated by the score stage.
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
                        uint32_t *state, bool level0_done, hipStream_t st);
+// packed: pack_ws already holds this layer's packed B and Q fragments (matrix-core path only).
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
-                                float *part_o, float *part_ml, hipStream_t st);
+                                bool packed, float *part_o, float *part_ml, hipStream_t st);
+bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, const void *B_k, const void *B_v,
+                             const void *pack_ws);
+PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k, const void *B_v, const void *q,
+                                 void *pack_ws);
 bool gather_attend_mfma_shape_ok(const xkv_shape &s);
 size_t gather_attend_pack_bytes(const xkv_shape &s);
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
-                                     void *pack_ws, float *part_o, float *part_ml, hipStream_t st);
+                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st);
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st);
 bool dense_mfma_shape_ok(const xkv_shape &s);
