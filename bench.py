@@ -60,7 +60,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); the path shards by sequence "
-              "with no communication, see DESIGN.md", file=sys.stderr)
+              "with no communication (every sequence has its own factors and queries)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

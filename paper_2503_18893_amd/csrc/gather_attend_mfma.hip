@@ -3,18 +3,19 @@
 //
 // Everything is one chain of v_mfma_f32_32x32x16_bf16 whose operand layouts are chosen so that the
 // result registers of one product are, after a bf16 pack, directly the operand of the next:
-//   (1) K^T tile [dims x tokens]  = B^K_g^T (LDS fragment)  x  gathered rows of A^K (global, 16 B/lane)
-//   (2) Z^T [tokens x head slots] = K^ (registers of (1))   x  Q^T fragments (registers)
+//   (1) K^T tile [dims x tokens]  = B^K_g^T (LDS fragment)  x  gathered rows of A^K (fragment from the LDS tile)
+//   (2) Z^T [tokens x head slots] = K^ (registers of (1))   x  Q^T fragments (LDS)
 //   (3) V^ tile [tokens x dims]   = gathered rows of A^V    x  B^V_g (LDS fragment)
 //   (4) O [head slots x dims]    += W = exp(Z^T - max) (registers of (2))  x  V^ (registers of (3))
 // In a 32x32 result lane (n, hf) holds column n and rows 8(v/4) + 4hf + v%4, v = 0..15; eight
 // consecutive registers are a valid 16-deep operand fragment for the next product because both of
-// its operands then agree on which row sits at which position.  Nothing is staged for a transpose.
+// its operands then agree on which row sits at which position: K^ and V^ never leave the registers.
 //
-// A wavefront owns 64 selected tokens per iteration (two 32-token blocks), a workgroup 256; the
-// reconstruction matrices are pre-packed into fragment order (pack_b_kernel) and streamed through
-// LDS 64 ranks at a time, shared by the four wavefronts.  Each wavefront keeps its own online
-// softmax state and writes one partial per query head; combine_kernel merges them.
+// A workgroup is eight wavefronts of 32 selected tokens each (256 per tile).  The reconstruction matrices
+// are pre-packed into fragment order (pack_b_block) and streamed through two LDS buffers 128 ranks at a
+// time, shared by the wavefronts; the gathered rows arrive line-wise and are turned into operand fragments
+// in a wavefront-private LDS tile.  Each wavefront keeps its own online softmax state; the workgroup
+// merges them and writes one partial per query head and split; combine_kernel merges the splits.
 #include <type_traits>
 
 #include "xkv_common.h"
