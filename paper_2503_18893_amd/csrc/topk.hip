@@ -357,6 +357,21 @@ __global__ __launch_bounds__(kRowWaves * 64) void topk_row_kernel(const float *_
     uint32_t Tw = T;
     int base_w = base;
     asm volatile("" : "+v"(Tw), "+v"(base_w));
+    if (my_eq == 0) {
+        // no key of this segment equals the threshold (the usual case): only the keys above it matter
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const bool is_gt = key[j] > Tw;
+            const uint64_t mg = __ballot(is_gt);
+            if (is_gt) {
+                const uint32_t pos = gt_run + lanes_below(mg) + (eq_run < need_eq ? eq_run : need_eq);
+                if (pos < (uint32_t)k) out[pos] = base_w + 64 * j;
+            }
+            gt_run += (uint32_t)__popcll(mg);
+            if (j % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int t = base_w + 64 * j;

@@ -184,7 +184,7 @@ def topk_gpu(rows_np, k):
     return first
 
 
-@pytest.mark.parametrize("L", [1, 63, 64, 255, 256, 257, 1000, 4096, 10007, 70001])
+@pytest.mark.parametrize("L", [1, 63, 64, 255, 256, 257, 1000, 4096, 10007, 32769, 65536, 65537, 70001])
 def test_topk_adversarial_arrays(L):
     rng = np.random.default_rng(L)
     rows = [
