@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void topk_row_kernel(const float *_
 {
     __shared__ uint32_t hist[kTopkBins * 32];
     __shared__ uint32_t bins[kTopkBins];
-    __shared__ uint32_t sh[2 + 2 * kRowWaves];
+    __shared__ uint32_t sh[3 + 2 * kRowWaves];
     const int row = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const float *Srow = S + (size_t)row * L;
     const int base = w * 64 * NV + lane;
@@ -276,21 +276,51 @@ __global__ __launch_bounds__(kRowWaves * 64) void topk_row_kernel(const float *_
         key[j] = base_v + 64 * j < L ? (kk > 1u ? kk : 1u) : 0u;
     }
 
-    uint32_t prefix = 0, k_rem = (uint32_t)k;
+    // Levels 0..2 histogram into `hist`.  While many keys still match the prefix the counters are replicated per
+    // lane pair ([bin][lane/2], two 16-bit halves per word); once at most 4096 match (known exactly from the
+    // previous level's bin count) a plain 256-word histogram is cheaper to clear and to sum.  Level 3 histograms
+    // per wavefront ([wavefront][bin]), so that each wavefront can read off afterwards how many of its own keys
+    // lie above / at the threshold without another pass over its registers.
+    uint32_t prefix = 0, k_rem = (uint32_t)k, n_match = (uint32_t)L;
+    uint32_t above24 = 0;  // level 3: keys of this wavefront whose upper 24 bits are already above the prefix
 #pragma unroll
     for (int level = 0; level < kTopkLevels; ++level) {
-        for (int i = tid; i < kTopkBins * 32; i += kRowWaves * 64) hist[i] = 0;
+        const bool per_wave = level == 3;
+        const bool direct = !per_wave && level > 0 && n_match <= 4096u;  // uniform over the workgroup
+        if (per_wave) {
+            for (int i = tid; i < kRowWaves * kTopkBins; i += kRowWaves * 64) hist[i] = 0;
+        } else if (direct) {
+            if (tid < kTopkBins) hist[tid] = 0;
+        } else {
+            for (int i = tid; i < kTopkBins * 32; i += kRowWaves * 64) hist[i] = 0;
+        }
         __syncthreads();
-        const uint32_t inc = 1u << (16 * (lane & 1));
+        const uint32_t inc = (per_wave || direct) ? 1u : 1u << (16 * (lane & 1));
+        const uint32_t slot0 = per_wave ? (uint32_t)w * kTopkBins : direct ? 0u : (uint32_t)(lane >> 1);
+        const uint32_t dmul = (per_wave || direct) ? 1u : 32u;
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
-            const bool match = level == 0 || (key[j] >> (32 - 8 * level)) == prefix;
+            const uint32_t upper = level == 0 ? 0u : key[j] >> (32 - 8 * level);
+            const bool match = level == 0 || upper == prefix;
             const uint32_t digit = (key[j] >> (24 - 8 * level)) & 0xFFu;
-            if (match) atomicAdd(&hist[digit * 32 + (lane >> 1)], inc);
+            if (match) atomicAdd(&hist[digit * dmul + slot0], inc);
+            if (level == 3) {
+                above24 += (uint32_t)__popcll(__ballot(upper > prefix));
+                asm volatile("" : "+s"(above24));
+            }
             if (j % 4 == 3) __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
-        {   // sum the replicas: four threads per bin, eight words each
+        if (per_wave) {
+            if (tid < kTopkBins) {
+                uint32_t sum = 0;
+#pragma unroll
+                for (int ww = 0; ww < kRowWaves; ++ww) sum += hist[ww * kTopkBins + tid];
+                bins[tid] = sum;
+            }
+        } else if (direct) {
+            if (tid < kTopkBins) bins[tid] = hist[tid];
+        } else {  // sum the replicas: four threads per bin, eight words each
             const int bin = tid >> 2, part = tid & 3;
             uint32_t sum = 0;
 #pragma unroll
@@ -323,6 +353,7 @@ __global__ __launch_bounds__(kRowWaves * 64) void topk_row_kernel(const float *_
                 if (above < k_rem && k_rem <= incl) {
                     sh[0] = (uint32_t)(4 * lane + i);
                     sh[1] = k_rem - above;
+                    sh[2] = c[i];
                 }
                 above = incl;
             }
@@ -330,26 +361,39 @@ __global__ __launch_bounds__(kRowWaves * 64) void topk_row_kernel(const float *_
         __syncthreads();
         prefix = (prefix << 8) | sh[0];
         k_rem = sh[1];
+        n_match = sh[2];
     }
     const uint32_t T = prefix, need_eq = k_rem;  // key of the k-th largest; how many keys equal to it are taken
 
-    // keys above / equal to T in this wavefront's segment, then the ordered write
-    uint32_t my_gt = 0, my_eq = 0;
+    // keys above / equal to T in this wavefront's segment: those above in the upper 24 bits were counted during
+    // the last pass, the rest sit in the wavefront's own level-3 histogram (lane l sums bins 4l .. 4l+3)
+    uint32_t my_gt, my_eq;
+    {
+        const uint32_t d3 = T & 0xFFu;
+        uint32_t g = 0, e = 0;
 #pragma unroll
-    for (int j = 0; j < NV; ++j) {
-        my_gt += (uint32_t)__popcll(__ballot(key[j] > T));
-        my_eq += (uint32_t)__popcll(__ballot(key[j] == T));
-        asm volatile("" : "+s"(my_gt), "+s"(my_eq));  // sum as you go: do not collect 2 NV lane masks first
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t bin = 4 * lane + i, c = hist[w * kTopkBins + bin];
+            g += bin > d3 ? c : 0u;
+            e += bin == d3 ? c : 0u;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            g += __shfl_xor(g, off, kWave);
+            e += __shfl_xor(e, off, kWave);
+        }
+        my_gt = above24 + g;
+        my_eq = e;
     }
     if (lane == 0) {
-        sh[2 + w] = my_gt;
-        sh[2 + kRowWaves + w] = my_eq;
+        sh[3 + w] = my_gt;
+        sh[3 + kRowWaves + w] = my_eq;
     }
     __syncthreads();
     uint32_t gt_run = 0, eq_run = 0;
     for (int ww = 0; ww < w; ++ww) {
-        gt_run += sh[2 + ww];
-        eq_run += sh[2 + kRowWaves + ww];
+        gt_run += sh[3 + ww];
+        eq_run += sh[3 + kRowWaves + ww];
     }
     int32_t *out = idx_out + (size_t)row * k;
     // The comparisons are redone rather than kept: 2 NV lane masks would not fit the scalar registers.  The empty
