@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
 
 // ==========================================================================================
 // bf16 matrix-core path (d_h = 128).  A wavefront walks 32-token blocks of its workgroup's range:
-//   Z^T [tokens x head slots] = K block (rows straight from global memory, 16 B per lane)  x  Q^T (registers)
+//   Z^T [tokens x head slots] = K block (loaded line-wise, operand fragments through an LDS tile)  x  Q^T (registers)
 //   O [head slots x dims]    += W = exp(Z^T - max) (the result registers of Z^T, packed)   x  V block
 // The contraction of the second product runs over tokens, so each lane needs eight token rows of one
 // column of V: the V block goes through a wavefront-private LDS tile (row pitch 272 B, conflict-free)
@@ -144,7 +144,8 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const bf16_t *__rest
                                                             float *__restrict__ part_ml, int L, int H_kv, int H_q,
                                                             int splits, int chunk, float scale)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * kVPitch];  // 34 KiB; reused for the merge
+    // per wavefront a V tile (32 x 272 B) and a K tile (32 x 256 B); 66 KiB; the V part is reused for the merge
+    __shared__ __attribute__((aligned(16))) unsigned char smem[4 * 32 * kVPitch + 4 * 32 * 256];
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = lane_id(), w = wave_id();
     const int n = lane & 31, hf = lane >> 5;
@@ -167,35 +168,50 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const bf16_t *__rest
     const int t_begin = split * chunk;
     const int t_end = t_begin + chunk < L ? t_begin + chunk : L;
     unsigned char *vt = smem + w * 32 * kVPitch;  // this wavefront's V tile
+    // ... and its K tile, in 16 B units: piece c of token row t sits at 16 t + (c + t) % 16 (conflict-free for the
+    // row-wise writes and for the fragment reads: lane (n, hf) reads piece 2 f + hf of row n)
+    u32x4_t *kt = reinterpret_cast<u32x4_t *>(smem + 4 * 32 * kVPitch) + w * 512;
+    const int kw_row = lane >> 4, kw_piece = lane & 15;
+    const int kr_base = 16 * n, kr_rot = hf + n;
 
     float m_run = -INFINITY, l_run = 0.0f;
-    f32x16_t O[4];
+    // Only head slots 0..15 can hold a query head (n_rep <= 16): of the 16 result registers of an O tile the
+    // first 8 (slots 8(v/4) + 4hf + v%4, v < 8) are kept between blocks, the rest is dropped.
+    float O[4][8];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) O[db][v] = 0.0f;
+        for (int v = 0; v < 8; ++v) O[db][v] = 0.0f;
 
     for (int t0 = t_begin + w * 32; t0 < t_end; t0 += 128) {
-        // K rows of this block: lane (token n, hf) takes 16 B of each 32 B fragment
-        const int tk = t0 + n < t_end ? t0 + n : t_end - 1;
-        const u32x4_t *krow = reinterpret_cast<const u32x4_t *>(Kg + (size_t)tk * 128) + hf;
-        u32x4_t kf[8];
-#pragma unroll
-        for (int f = 0; f < 8; ++f) kf[f] = krow[2 * f];
-        // V rows: 16 lanes cover one 256 B row, the wavefront 4 rows per load
-        u32x4_t vr[8];
+        // K and V rows, whole lines per instruction: 16 lanes cover one 256 B row, the wavefront 4 rows per load
+        // (with one lane per row four instructions would share every 128 B line, which streams measurably slower)
+        u32x4_t kr[8], vr[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = i * 4 + (lane >> 4);
             const int tv = t0 + row < t_end ? t0 + row : t_end - 1;
-            vr[i] = reinterpret_cast<const u32x4_t *>(Vg + (size_t)tv * 128)[lane & 15];
+            kr[i] = __builtin_nontemporal_load(&reinterpret_cast<const u32x4_t *>(Kg + (size_t)tv * 128)[lane & 15]);
+            vr[i] = __builtin_nontemporal_load(&reinterpret_cast<const u32x4_t *>(Vg + (size_t)tv * 128)[lane & 15]);
         }
+        // K through its LDS tile: written row-wise, read back as the operand fragment of each 16 head dims
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = i * 4 + kw_row;
+            kt[16 * row + ((kw_piece + row) & 15)] = kr[i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         f32x16_t Z;
 #pragma unroll
         for (int v = 0; v < 16; ++v) Z[v] = 0.0f;
 #pragma unroll
-        for (int f = 0; f < 8; ++f)
-            Z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[f]), Qf[f], Z, 0, 0, 0);
+        for (int f = 0; f < 8; ++f) {
+            const u32x4_t kf = kt[kr_base + ((kr_rot + 2 * f) & 15)];
+            Z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf), Qf[f], Z, 0, 0, 0);
+        }
         // lane (head slot n, hf): register v is token 8(v/4) + 4hf + v%4 of the block
         float m_loc = -INFINITY;
 #pragma unroll
@@ -236,6 +252,9 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const bf16_t *__rest
         }
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
+            f32x16_t ot;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ot[v] = 0.0f;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 u32x4_t raw;
@@ -248,9 +267,11 @@ __global__ __launch_bounds__(256, 2) void dense_mfma_kernel(const bf16_t *__rest
                         *reinterpret_cast<const uint16_t *>(vt + (tok + 1) * kVPitch + (db * 32 + n) * 2);
                     raw[e2] = lo | (hi << 16);
                 }
-                O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(j == 0 ? W0 : W1, __builtin_bit_cast(bf16x8_t, raw),
-                                                                O[db], 0, 0, 0);
+                ot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(j == 0 ? W0 : W1, __builtin_bit_cast(bf16x8_t, raw), ot, 0,
+                                                             0, 0);
             }
+#pragma unroll
+            for (int v = 0; v < 8; ++v) O[db][v] += ot[v];
         }
         __builtin_amdgcn_wave_barrier();
     }
