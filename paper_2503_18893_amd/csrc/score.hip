@@ -269,11 +269,12 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
     const u32x4_t *Ab = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
     const int n_tiles = (L + 31) / 32;
     const int n_groups = F8 / 8;  // groups per tile
-    // every wavefront streams one contiguous run of tiles
-    const int per_wave = tiles_per_wg / WAVES;
     const int wg_end = (blockIdx.x + 1) * tiles_per_wg < n_tiles ? (blockIdx.x + 1) * tiles_per_wg : n_tiles;
-    int tile = blockIdx.x * tiles_per_wg + w * per_wave;
-    const int tile_end = tile + per_wave < wg_end ? tile + per_wave : wg_end;
+    // The wavefronts of a workgroup interleave their tiles (stride TS), so that at any moment the workgroup reads
+    // one compact window of the sequence: measurably faster than eight separate runs per workgroup.
+    constexpr int TS = WAVES;
+    int tile = blockIdx.x * tiles_per_wg + w;
+    const int tile_end = wg_end;
     const bool has_work = tile < tile_end;  // wave-uniform
 
     int woff[4];
@@ -302,7 +303,7 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
     auto advance_p = [&]() __attribute__((always_inline)) {
         if (++S_p == n_groups) {
             S_p = 0;
-            tile_p = tile_p + 1 < tile_end ? tile_p + 1 : tile_p;
+            tile_p = tile_p + TS < tile_end ? tile_p + TS : tile_p;
         }
     };
     u32x4_t areg[16];
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
     auto flush = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
-            const int t = (tile0 + i) * 32 + n;
+            const int t = (tile0 + i * TS) * 32 + n;
             if (i < ti && t < L) {
 #pragma unroll
                 for (int u = 0; u < GPH; ++u) {
@@ -358,7 +359,7 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
                 }
             }
         }
-        tile0 += ti;
+        tile0 += ti * TS;
         ti = 0;
     };
     auto finish_group = [&]() __attribute__((always_inline)) {  // closes a tile after its last group
@@ -390,12 +391,12 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
-        ++tile;
+        tile += TS;
         ++ti;
     };
     // groups of this wavefront, two per iteration (one per half of the ring); an odd total leaves one surplus
     // group at the end, which multiplies re-fetched rows of the last tile and is dropped
-    const int my_groups = (tile_end - tile) * n_groups;
+    const int my_groups = (tile_end - tile + TS - 1) / TS * n_groups;
     for (int gi = 0; gi < my_groups; gi += 2) {
         {
             const u32x4_t *arow = Ab + piece_of(S_p);
