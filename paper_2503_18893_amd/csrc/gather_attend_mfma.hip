@@ -11,7 +11,7 @@
 // consecutive registers are a valid 16-deep operand fragment for the next product because both of
 // its operands then agree on which row sits at which position: K^ and V^ never leave the registers.
 //
-// A workgroup is eight wavefronts of 32 selected tokens each (256 per tile).  The reconstruction matrices
+// A workgroup is eight wavefronts (four for small problems) of 32 selected tokens each (256 per tile).  The reconstruction matrices
 // are pre-packed into fragment order (pack_b_block) and streamed through two LDS buffers 128 ranks at a
 // time, shared by the wavefronts; the gathered rows arrive line-wise and are turned into operand fragments
 // in a wavefront-private LDS tile.  Each wavefront keeps its own online softmax state; the workgroup
@@ -61,9 +61,11 @@ __device__ __forceinline__ void copy16_global_to_lds(const void *gptr, uint32_t 
 // split over bits 3:0 and 15:14; expcnt and lgkmcnt are left at "no wait").
 #define XKV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (0xF << 8) | (((n) >> 4) << 14))
 
-constexpr int kGaWaves = 8;  // wavefronts per workgroup, 32 selected tokens each per tile
-// LDS map (bytes): B fragments [2][kGroup][4][64][16] | A tiles [kGaWaves][512][16] | Q fragments [8][64][16] | ids
-constexpr int kLdsB = 2 * kGroup * 256 * 16, kLdsA = kGaWaves * 512 * 16, kLdsQ = 8 * 64 * 16;
+// Wavefronts per workgroup (WAVES, template parameter): 8 with 32 selected tokens each per tile (256 tokens);
+// 4 when there are too few selected tokens to give every compute unit a 256-token tile.
+// LDS map (bytes): B fragments [2][kGroup][4][64][16] | A tiles [WAVES][512][16] | Q fragments [8][64][16] | ids
+constexpr int kLdsB = 2 * kGroup * 256 * 16, kLdsQ = 8 * 64 * 16;
+constexpr int lds_a_bytes(int waves) { return waves * 512 * 16; }
 
 // What a wavefront gathers for one group of 8 fragment steps: 128 ranks = 256 B of each of its 32 rows.
 // Instruction j (0..7) covers rows 4j..4j+3 whole-line-wise: lane l loads the 16 B piece l%16 of row 4j + l/16,
@@ -84,7 +86,7 @@ struct AStage {
 //    so that neither side has bank conflicts), read back as one 16-rank operand fragment per step,
 //  - refills the ring, one instruction per step, with the pieces of the group two groups on,
 //  - per step multiplies the step's four B fragments with the A fragment.
-template <bool IS_K, int SLOT0>
+template <bool IS_K, int SLOT0, int WAVES>
 __device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 * kGroup], const u32x4_t *Bl,
                                           u32x4_t *At, int buf, uint32_t dma_dst, const u32x4_t *bsrc_next,
                                           const AStage &an, const int (&tk)[kGroup], const int (&woff)[4], int rbase,
@@ -97,7 +99,7 @@ __device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 #pragma unroll
-    for (int i = 0; i < 4; ++i) copy16_global_to_lds(bsrc_next + i * 512, dma_dst + i * 8192);
+    for (int i = 0; i < 32 / WAVES; ++i) copy16_global_to_lds(bsrc_next + i * (WAVES * 64), dma_dst + i * (WAVES * 1024));
 #pragma unroll
     for (int j = 0; j < kGroup; ++j) At[64 * j + woff[j & 3]] = areg[SLOT0 + j];
     __builtin_amdgcn_sched_barrier(0);
@@ -125,12 +127,14 @@ __device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 
 // group are copied straight from global memory into the other, and every wavefront has the gathered pieces of
 // the next two groups in flight in registers.
 // Eight wavefronts of 32 tokens each: two share a SIMD, so one multiplies while the other waits for memory.
-__global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const bf16_t *__restrict__ A_k, const bf16_t *__restrict__ A_v, const u32x4_t *__restrict__ pack,
     const bf16_t *__restrict__ q, const int32_t *__restrict__ idx, float *__restrict__ part_o,
     float *__restrict__ part_ml, int L, int r_k, int r_v, int H_kv, int H_q, int k, int splits, int chunk, int F16k,
     int F16v, float scale)
 {
+    constexpr int kLdsA = lds_a_bytes(WAVES), TILE = WAVES * 32;  // selected tokens per workgroup iteration
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     u32x4_t *Bl = reinterpret_cast<u32x4_t *>(smem_raw);
     // workgroup id -> (KV head fastest, so that a head's packed B stays in one XCD's L2), split, sequence
@@ -146,19 +150,19 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     const u32x4_t *packg = pack + ((size_t)b * H_kv + g) * ((size_t)(F16k + F16v) * 256 + 512);
     u32x4_t *At = reinterpret_cast<u32x4_t *>(smem_raw + kLdsB) + w * 512;
     u32x4_t *Ql = reinterpret_cast<u32x4_t *>(smem_raw + kLdsB + kLdsA);  // [8][64]
-    Ql[tid] = packg[(size_t)(F16k + F16v) * 256 + tid];
+    for (int i = tid; i < 8 * 64; i += WAVES * 64) Ql[i] = packg[(size_t)(F16k + F16v) * 256 + i];
 
     const u32x4_t *Ak = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
     const u32x4_t *Av = reinterpret_cast<const u32x4_t *>(A_v + (size_t)b * L * r_v);
     const int32_t *ids = idx + ((size_t)b * H_kv + g) * k;
     const int m_begin = split * chunk;
     const int m_end = m_begin + chunk < k ? m_begin + chunk : k;
-    const int n_tiles = (m_end - m_begin + 255) / 256;
+    const int n_tiles = (m_end - m_begin + TILE - 1) / TILE;
 
     // The split's token ids are staged in LDS once (clamped into [0, L)), so that the main loop issues no
     // global load other than its prefetches: a wait on an id would otherwise drain the whole prefetch queue.
     int *tok_lds = reinterpret_cast<int *>(smem_raw + kLdsB + kLdsA + kLdsQ);  // [chunk]
-    for (int m = tid; m < m_end - m_begin; m += kGaWaves * 64) {
+    for (int m = tid; m < m_end - m_begin; m += WAVES * 64) {
         const int t = ids[m_begin + m];
         tok_lds[m] = t < 0 ? 0 : (t >= L ? L - 1 : t);
     }
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     auto tile_tokens = [&](int tile, int (&tk)[kGroup]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) {
-            int m = tile * 256 + w * 32 + 4 * j + (lane >> 4);
+            int m = tile * TILE + w * 32 + 4 * j + (lane >> 4);
             m = m < m_end - m_begin ? m : m_end - m_begin - 1;
             tk[j] = tok_lds[m];
         }
@@ -211,7 +215,8 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
 
     // ---- prologue, in the order the steady state expects: B fragments of group 0, gathers of groups 0 and 1
 #pragma unroll
-    for (int i = 0; i < 4; ++i) copy16_global_to_lds(packg + i * 512 + tid, dma_base(0) + i * 8192);
+    for (int i = 0; i < 32 / WAVES; ++i)
+        copy16_global_to_lds(packg + i * (WAVES * 64) + tid, dma_base(0) + i * (WAVES * 1024));
     u32x4_t areg[2 * kGroup];
     {
         const AStage s0 = stage_of(true, 0), s1 = stage_of(true, 1);
@@ -231,7 +236,7 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
 
     int gg = 0;  // group counter: group gg is read from buffer gg % 2
     for (int tile = 0; tile < n_tiles; ++tile) {
-        const int base = m_begin + tile * 256 + w * 32;
+        const int base = m_begin + tile * TILE + w * 32;
         // descriptors of the pair after pair `pi`: K or V of this tile, or the first K pair of the next tile
 #define XKV_NEXT_PAIR(pi)                                                                                     \
     const bool wrap = (pi) + 1 == PT;                                                                         \
@@ -246,8 +251,8 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     const int buf0 = gg & 1, buf1 = buf0 ^ 1
         for (int pi = 0; pi < PK; ++pi, gg += 2) {
             XKV_NEXT_PAIR(pi);
-            run_group<true, 0>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
-            run_group<true, kGroup>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
+            run_group<true, 0, WAVES>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
+            run_group<true, kGroup, WAVES>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
         }
         {
                 // (2) Z^T = K^ Q^T: lane (head slot n, hf), register v <-> token 8(v/4) + 4hf + v%4 of the block
@@ -297,8 +302,8 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
         }
         for (int pi = PK; pi < PT; ++pi, gg += 2) {
             XKV_NEXT_PAIR(pi);
-            run_group<false, 0>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
-            run_group<false, kGroup>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
+            run_group<false, 0, WAVES>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
+            run_group<false, kGroup, WAVES>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
         }
 #undef XKV_NEXT_PAIR
         {
@@ -323,7 +328,7 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
     XKV_WAIT_VMCNT(0);
     __syncthreads();
     // merge the eight wavefronts in LDS, then write one partial per (split, query head)
-    float *mg = reinterpret_cast<float *>(smem_raw);  // [8][16][132]
+    float *mg = reinterpret_cast<float *>(smem_raw);  // [WAVES][16][132]
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     if (lane < n_rep) {
         mg[(w * 16 + lane) * 132 + 128] = m_run;
@@ -338,14 +343,14 @@ __global__ __launch_bounds__(kGaWaves * 64, 2) void gather_attend_mfma_kernel(
         }
     }
     __syncthreads();
-    for (int item = tid; item < n_rep * 128; item += kGaWaves * 64) {
+    for (int item = tid; item < n_rep * 128; item += WAVES * 64) {
         const int hh = item >> 7, dim = item & 127;
         float M = -INFINITY;
 #pragma unroll
-        for (int ww = 0; ww < kGaWaves; ++ww) M = fmaxf(M, mg[(ww * 16 + hh) * 132 + 128]);
+        for (int ww = 0; ww < WAVES; ++ww) M = fmaxf(M, mg[(ww * 16 + hh) * 132 + 128]);
         float num = 0.0f, den = 0.0f;
 #pragma unroll
-        for (int ww = 0; ww < kGaWaves; ++ww) {
+        for (int ww = 0; ww < WAVES; ++ww) {
             const float mw = mg[(ww * 16 + hh) * 132 + 128];
             const float wgt = (mw == -INFINITY) ? 0.0f : __expf(mw - M);
             num = fmaf(wgt, mg[(ww * 16 + hh) * 132 + dim], num);
@@ -405,21 +410,39 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
         if (e != hipSuccess) return e;
     }
     if (p.sr_chunk > kMaxChunkTokens) return hipErrorInvalidValue;
-    const size_t lds = kLdsB + kLdsA + kLdsQ + (size_t)p.sr_chunk * 4;  // B fragments, A tiles, Q fragments, token ids
-    static bool attr_set = false;
-    if (!attr_set) {
-        e = hipFuncSetAttribute((const void *)gather_attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsB + kLdsA + kLdsQ + kMaxChunkTokens * 4);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     dim3 grid((unsigned)((long long)p.sr_splits * s.H_kv * s.batch));
-    profile_begin(1, st);
-    hipLaunchKernelGGL(gather_attend_mfma_kernel, grid, dim3(kGaWaves * 64), lds, st, (const bf16_t *)A_k, (const bf16_t *)A_v,
-                       (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, part_o, part_ml, s.L, s.r_k, s.r_v, s.H_kv,
-                       s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v, p.scale);
-    profile_end(1, st);
+#define XKV_GA_LAUNCH(WV)                                                                                          \
+    do {                                                                                                           \
+        const size_t lds = kLdsB + lds_a_bytes(WV) + kLdsQ + (size_t)p.sr_chunk * 4; /* B, A tiles, Q, token ids */ \
+        static bool attr_set = false;                                                                              \
+        if (!attr_set) {                                                                                           \
+            e = hipFuncSetAttribute((const void *)gather_attend_mfma_kernel<WV>,                                   \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,                                    \
+                                    kLdsB + lds_a_bytes(WV) + kLdsQ + kMaxChunkTokens * 4);                        \
+            if (e != hipSuccess) return e;                                                                         \
+            attr_set = true;                                                                                       \
+        }                                                                                                          \
+        profile_begin(1, st);                                                                                      \
+        hipLaunchKernelGGL(gather_attend_mfma_kernel<WV>, grid, dim3(WV * 64), lds, st, (const bf16_t *)A_k,       \
+                           (const bf16_t *)A_v, (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, part_o, part_ml, \
+                           s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v, p.scale);     \
+        profile_end(1, st);                                                                                        \
+    } while (0)
+    if (p.ga_waves == 8)
+        XKV_GA_LAUNCH(8);
+    else
+        XKV_GA_LAUNCH(4);
+#undef XKV_GA_LAUNCH
     return hipGetLastError();
+}
+
+// Wavefronts per workgroup for a shape: full 256-token tiles when there are enough selected tokens to give every
+// compute unit one, else 128-token tiles so that more compute units take part (64-token tiles lose again: every
+// workgroup streams the whole packed B, and two wavefronts do not hide each other's latencies).
+int gather_attend_mfma_waves(const xkv_shape &s)
+{
+    const long long tokens = (long long)s.batch * s.H_kv * s.k;
+    return tokens >= 256LL * 256 ? 8 : 4;
 }
 
 }  // namespace xkv

@@ -51,12 +51,13 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
         p.topk_chunks = ceil_div(s.L, p.topk_chunk);
     }
 
-    // the matrix-core kernel walks 256 selected tokens per workgroup iteration, the general one 16
+    // the matrix-core kernel walks 32 selected tokens per wavefront and iteration, the general one 16 per workgroup
     p.ga_mfma = gather_attend_mfma_shape_ok(s);
-    const int gran = p.ga_mfma ? 256 : 64;
-    // (its 8-wavefront workgroups occupy a compute unit alone, so about one workgroup per compute unit; but at
-    // least four splits per (sequence, KV head): the splits of a head share its packed B in their XCD's L2, and
-    // with fewer of them more than 8 packs (2 MiB) are live per XCD and the re-streamed fragments start to miss)
+    p.ga_waves = p.ga_mfma ? gather_attend_mfma_waves(s) : 0;
+    const int gran = p.ga_mfma ? 32 * p.ga_waves : 64;
+    // (its workgroups occupy a compute unit alone, so about one workgroup per compute unit; but at least four
+    // splits per (sequence, KV head): the splits of a head share its packed B in their XCD's L2, and with fewer of
+    // them more than 8 packs (2 MiB) are live per XCD and the re-streamed fragments start to miss)
     const int ga_splits = ceil_div(256, rows) < 4 ? 4 : ceil_div(256, rows);
     int splits = clampi(p.ga_mfma ? ga_splits : want, 1, clampi(ceil_div(s.k, gran), 1, 64));
     if (splits < ceil_div(s.k, 4096)) splits = ceil_div(s.k, 4096);  // a workgroup keeps at most 4096 token ids in LDS

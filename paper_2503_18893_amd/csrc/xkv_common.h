@@ -71,6 +71,7 @@ struct Plan {
     size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, off_bpack, total;
     bool dense_mfma;   // shape fits the matrix-core dense kernel
     bool ga_mfma;      // shape fits the matrix-core gather-attend kernel
+    int ga_waves;      // ... with this many wavefronts (32 selected tokens each) per workgroup
     bool topk_row;     // rows short enough for the one-launch, register-resident selection
     bool score_stream; // shape fits the long-stream score kernel
     bool score_hist;   // ... and that kernel can also histogram the top digit of its scores for the top-k stage
@@ -140,6 +141,7 @@ bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, co
 PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k, const void *B_v, const void *q,
                                  void *pack_ws);
 bool gather_attend_mfma_shape_ok(const xkv_shape &s);
+int gather_attend_mfma_waves(const xkv_shape &s);
 size_t gather_attend_pack_bytes(const xkv_shape &s);
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,

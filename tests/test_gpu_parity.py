@@ -135,6 +135,9 @@ SMALL = [
                                 dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
     ("gqa2_bf16", synth.Workload("gqa2_bf16", G=1, H_kv=5, H_q=10, d_h=128, r_k=256, r_v=128, L=4097, k=300, batch=1,
                                  dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    # enough selected tokens (4 x 8 x 2100) for the eight-wavefront form of the gather-attend kernel (the smaller
+    # cases above run its four-wavefront form), ragged last tile
+    ("llama_k2100_bf16", synth.LLAMA_GROUP.with_(L=6000, k=2100, r_k=64, r_v=96, batch=4, G=1)),
 ]
 
 
