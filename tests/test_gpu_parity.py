@@ -254,6 +254,51 @@ def test_llama_group_full_size():
     print("llama_group_full", rep)
 
 
+def _full_size_sampled(w, seqs, seed):
+    """One layer of a benchmark configuration at full size, in the launch configuration bench.py times (fused
+    xkv_sr_decode on device-generated factors), checked on samples the oracle computes one by one: pooled scores of
+    token ranges at the start, in the middle and at the end of every sampled sequence, the complete selection of
+    those sequences (against the oracle's selection on the GPU's own scores), and their attention outputs."""
+    torch = torch_mod()
+    dev = synth.make_group_device(w, seed=seed)
+    shape = xb.Shape.of(w)
+    ws = xb.alloc_workspace(shape)
+    layer = w.G - 1
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
+    out = torch.empty((w.batch, w.H_q, w.d_h), dtype=synth.torch_dtype(w.dtype), device="cuda")
+    xb.xkv_sr_decode(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], dev["q"][layer].contiguous(), out,
+                     idx, S, ws)
+    torch.cuda.synchronize()
+    scale = oracle.default_scale(w.d_h)
+    mid = w.L // 2
+    ranges = [(0, 256), (mid - 128, mid + 128), (w.L - 256, w.L)]
+    for b in seqs:
+        B_k = synth.to_host(dev["B_k"][b, layer])
+        B_v = synth.to_host(dev["B_v"][b, layer])
+        q = synth.to_host(dev["q"][layer, b])
+        for lo, hi in ranges:
+            ref = oracle.pooled_scores(synth.to_host(dev["A_k"][b, lo:hi]), B_k, q, w.H_kv, scale)
+            assert max_rel(S[b, :, lo:hi].cpu().numpy(), ref) <= TOL[w.dtype], (b, lo)
+        S_b, idx_b = S[b].cpu().numpy(), idx[b].cpu().numpy()
+        for g in range(w.H_kv):
+            np.testing.assert_array_equal(idx_b[g], oracle.select(S_b[g], w.k), err_msg=f"seq {b} head {g}")
+        ref_out = oracle.gather_attend(synth.to_host(dev["A_k"][b]), synth.to_host(dev["A_v"][b]), B_k, B_v, q, idx_b,
+                                       scale)
+        err = max_rel(synth.storage_to_f64(synth.to_host(out[b])), ref_out)
+        assert err <= TOL[w.dtype], (b, err)
+
+
+def test_llama_full_size_sampled():
+    """Benchmark configuration 3 (batch 16, L = 65536, r = 512, k = 4096): first and last sequence."""
+    _full_size_sampled(synth.LLAMA_FULL, seqs=(0, synth.LLAMA_FULL.batch - 1), seed=31)
+
+
+def test_qwen_full_size_sampled():
+    """Benchmark configuration 4 (batch 4, L = 131072, r = 384, k = 4096, 7 query heads per KV head)."""
+    _full_size_sampled(synth.QWEN, seqs=(synth.QWEN.batch - 1,), seed=32)
+
+
 # ------------------------------------------------------------------------------ error paths (host side, no launch)
 def test_error_codes():
     torch = torch_mod()
