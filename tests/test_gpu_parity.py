@@ -213,6 +213,8 @@ DENSE = [
     ("tiny_f32", synth.TINY.with_(L=700)),
     ("llama_bf16", synth.LLAMA_GROUP.with_(L=4100, batch=2, r_k=64, r_v=64, G=1)),
     ("qwen_bf16", synth.QWEN.with_(L=2500, k=100, batch=1, r_k=64, r_v=64, G=1)),
+    # ranks that span several 128-rank groups (odd and even counts, ragged last group), several workgroup tiles
+    ("llama_r304_r512_bf16", synth.LLAMA_GROUP.with_(L=1801, k=100, batch=2, r_k=304, r_v=512, G=2)),
 ]
 
 
