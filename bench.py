@@ -248,6 +248,25 @@ def main():
                  "layers_resident": n_dense_layers,
                  "note": "all layers resident" if n_dense_layers >= w.n_layers else
                          f"timed over {n_dense_layers} resident layer caches visited round-robin"}
+        # xKV decode without selection (Sec. 3.2): every layer reconstructs its whole K and V from the factors and
+        # attends densely over them.  Two scratch caches, reused by every layer.
+        if w.dtype == "bf16":
+            Kr, Vr = Ks[0], Vs[0]
+
+            def dense_reconstruct_step():
+                for grp in range(w.n_groups):
+                    g = groups[grp % n_sets]
+                    for l in range(w.G):
+                        xb.xkv_reconstruct(shape, l, g["A_k"], g["B_k"], w.r_k, Kr)
+                        xb.xkv_reconstruct(shape, l, g["A_v"], g["B_v"], w.r_v, Vr)
+                        xb.xkv_dense_decode(shape, Kr, Vr, qs[grp % n_sets][l], out, ws)
+
+            dense_reconstruct_step()
+            ms_dr = time_loop(torch, dense_reconstruct_step, 2)
+            dense["reconstruct_then_dense"] = {"ms_per_step": round(ms_dr, 3),
+                                               "tokens_per_s": round(w.batch / (ms_dr * 1e-3), 2),
+                                               "note": "xKV without selection: K and V of every layer rebuilt from "
+                                                       "the factors (A B_l), then dense attention"}
         del Ks, Vs
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
