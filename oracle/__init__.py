@@ -180,6 +180,35 @@ def sr_decode(A_k, A_v, B_k, B_v, q, H_kv, k, scale=None):
     return out, idx, S32
 
 
+def sr_decode_tail(A_k, A_v, B_k, B_v, q, H_kv, k, K_tail, V_tail, scale=None):
+    """SR step over a context whose most recent T tokens are still uncompressed (Sec. 4, "Implementation
+    details": newly generated tokens are kept uncompressed; Sec. 7, long-generation scenario).
+
+    The L compressed tokens are scored, pooled and selected exactly as in sr_decode (steps 1-4); attention then
+    runs over the k reconstructed rows of each KV head together with all T tail rows, one softmax over the union.
+    K_tail, V_tail: [H_kv][T][d_h].  Written out in numpy on purpose (no blocking, no running maxima).
+    Returns (out[H_q][d_h], idx[H_kv][k]).
+    """
+    A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
+    K_tail, V_tail = widen(K_tail), widen(V_tail)
+    H_q, d_h = q.shape
+    n_rep = H_q // H_kv
+    scale = default_scale(d_h) if scale is None else scale
+    S32 = pooled_scores(A_k, B_k, q, H_kv, scale).astype(np.float32)   # the selection is taken in fp32 (step 4)
+    out = np.empty((H_q, d_h), np.float64)
+    idx = np.empty((H_kv, k), np.int32)
+    for g in range(H_kv):
+        idx[g] = select(S32[g], k)
+        cols = slice(g * d_h, (g + 1) * d_h)
+        K_all = np.concatenate([A_k[idx[g]] @ B_k[:, cols], K_tail[g]], axis=0)   # Eq. 3 rows, then the tail
+        V_all = np.concatenate([A_v[idx[g]] @ B_v[:, cols], V_tail[g]], axis=0)
+        for h in range(g * n_rep, (g + 1) * n_rep):
+            z = scale * (K_all @ q[h])
+            wgt = np.exp(z - z.max())
+            out[h] = (wgt / wgt.sum()) @ V_all
+    return out, idx
+
+
 def factorize(X_cat, r):
     """Eq. 1: (A[L][r], B[r][n], sigma[n]) with A = U Sigma, B = V_r^T."""
     X = widen(X_cat)

@@ -235,6 +235,50 @@ def test_sr_decode_chain_matches_numpy_brute_force():
             np.testing.assert_allclose(out[h], w @ Vhat[sel, g * d_h:(g + 1) * d_h], rtol=1e-10, atol=1e-12)
 
 
+def _tail(c, T, seed):
+    rng = np.random.default_rng(seed)
+    shape = (c["H_kv"], T, c["d_h"])
+    return rng.standard_normal(shape) * 0.5, rng.standard_normal(shape)
+
+
+def test_sr_tail_with_empty_tail_is_plain_sr():
+    """No uncompressed tokens: the tail variant must reduce to the SR step itself."""
+    c = small_case(14, L=150, H_kv=2, H_q=6)
+    K_t, V_t = _tail(c, 0, 1)
+    out_t, idx_t = oracle.sr_decode_tail(c["A_k"], c["A_v"], c["B_k"], c["B_v"], c["q"], c["H_kv"], 13, K_t, V_t)
+    out, idx, _ = oracle.sr_decode(c["A_k"], c["A_v"], c["B_k"], c["B_v"], c["q"], c["H_kv"], 13)
+    np.testing.assert_array_equal(idx_t, idx)
+    np.testing.assert_allclose(out_t, out, rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("H_kv,H_q,T", [(2, 6, 7), (3, 3, 1), (1, 4, 40)])
+def test_sr_tail_with_k_equal_L_is_dense_attention_on_the_whole_context(H_kv, H_q, T):
+    """Selecting every compressed token and keeping T recent tokens uncompressed (Sec. 4, implementation details)
+    is textbook attention over the L reconstructed rows followed by the T exact rows."""
+    c = small_case(15, H_kv=H_kv, H_q=H_q, L=70)
+    K_t, V_t = _tail(c, T, 2)
+    out, idx = oracle.sr_decode_tail(c["A_k"], c["A_v"], c["B_k"], c["B_v"], c["q"], H_kv, c["L"], K_t, V_t)
+    as_rows = lambda X: X.transpose(1, 0, 2).reshape(T, H_kv * c["d_h"])       # [H_kv][T][d_h] -> [T][d]
+    K = np.concatenate([c["A_k"] @ c["B_k"], as_rows(K_t)], axis=0)
+    V = np.concatenate([c["A_v"] @ c["B_v"], as_rows(V_t)], axis=0)
+    ref = np_softmax_attention(K, V, c["q"], H_kv, 1.0 / np.sqrt(c["d_h"]))
+    np.testing.assert_allclose(out, ref, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(out, oracle.dense(K, V, c["q"], H_kv), rtol=1e-11, atol=1e-13)
+
+
+def test_sr_tail_selection_ignores_the_tail_and_a_dominant_tail_token_wins():
+    """The tail takes no part in the selection; a tail key aligned with the query at a huge scale takes all the
+    weight, so the output is that token's value row."""
+    c = small_case(16, L=90, H_kv=1, H_q=2)
+    K_t, V_t = _tail(c, 5, 3)
+    K_t[0, 3] = 50.0 * (c["q"][0] + c["q"][1])
+    out, idx = oracle.sr_decode_tail(c["A_k"], c["A_v"], c["B_k"], c["B_v"], c["q"], 1, 11, K_t, V_t, scale=10.0)
+    _, idx_plain, _ = oracle.sr_decode(c["A_k"], c["A_v"], c["B_k"], c["B_v"], c["q"], 1, 11, 10.0)
+    np.testing.assert_array_equal(idx, idx_plain)
+    for h in range(2):
+        np.testing.assert_allclose(out[h], V_t[0, 3], rtol=1e-9, atol=1e-12)
+
+
 def test_sr_tiny_config_properties():
     """The benchmark's tiny configuration: selected tokens dominate, k distinct indices per head."""
     w = synth.TINY
