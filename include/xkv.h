@@ -87,6 +87,21 @@ XKV_API xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer_in_group,
                                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same step for a context whose T most recent tokens are still uncompressed (Sec. 4, "Implementation
+ * details": newly generated tokens are kept uncompressed; Sec. 7, long-generation scenario).  Scoring, pooling
+ * and selection run over the L compressed tokens exactly as in xkv_sr_decode; attention then runs over the k
+ * reconstructed rows of each KV head together with all T tail rows, one softmax over the union:
+ *   out_h = softmax(scale * [K^_{rho(h)} ; K_tail_{rho(h)}] q_h)^T [V^_{rho(h)} ; V_tail_{rho(h)}].
+ * K_tail, V_tail: [batch][H_kv][T][d_h] in shape->dtype, T >= 0 (T = 0: identical to xkv_sr_decode, the tail
+ * pointers may then be NULL).  XKV_ERR_INVALID_ARG for T < 0 or a missing tail pointer.
+ */
+XKV_API xkv_status xkv_sr_decode_tail(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                      const void *A_v, const void *B_k, const void *B_v, const void *q,
+                                      const void *K_tail, const void *V_tail, int32_t T, void *out,
+                                      int32_t *idx_out, float *score_out, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream);
+
+/*
  * Dense decode attention on an uncompressed cache, the speedup baseline (Sec. 5, "Full
  * Attention"): out_h = softmax(scale * K_{rho(h)} q_h)^T V_{rho(h)} over all L tokens.
  * K, V: [batch][H_kv][L][d_h].  shape->r_k, r_v, k, G are ignored.

@@ -180,25 +180,20 @@ def sr_decode(A_k, A_v, B_k, B_v, q, H_kv, k, scale=None):
     return out, idx, S32
 
 
-def sr_decode_tail(A_k, A_v, B_k, B_v, q, H_kv, k, K_tail, V_tail, scale=None):
-    """SR step over a context whose most recent T tokens are still uncompressed (Sec. 4, "Implementation
-    details": newly generated tokens are kept uncompressed; Sec. 7, long-generation scenario).
-
-    The L compressed tokens are scored, pooled and selected exactly as in sr_decode (steps 1-4); attention then
-    runs over the k reconstructed rows of each KV head together with all T tail rows, one softmax over the union.
-    K_tail, V_tail: [H_kv][T][d_h].  Written out in numpy on purpose (no blocking, no running maxima).
-    Returns (out[H_q][d_h], idx[H_kv][k]).
+def gather_attend_tail(A_k, A_v, B_k, B_v, q, idx, K_tail, V_tail, scale=None):
+    """Steps 5-6 for given index sets idx[H_kv][k] over a context whose T most recent tokens are uncompressed:
+    attention over the k reconstructed rows of each KV head (Eq. 3) together with all T tail rows, one softmax over
+    the union.  K_tail, V_tail: [H_kv][T][d_h].  Written out in numpy on purpose (no blocking, no running maxima).
     """
     A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
     K_tail, V_tail = widen(K_tail), widen(V_tail)
+    idx = np.asarray(idx)
     H_q, d_h = q.shape
+    H_kv = idx.shape[0]
     n_rep = H_q // H_kv
     scale = default_scale(d_h) if scale is None else scale
-    S32 = pooled_scores(A_k, B_k, q, H_kv, scale).astype(np.float32)   # the selection is taken in fp32 (step 4)
     out = np.empty((H_q, d_h), np.float64)
-    idx = np.empty((H_kv, k), np.int32)
     for g in range(H_kv):
-        idx[g] = select(S32[g], k)
         cols = slice(g * d_h, (g + 1) * d_h)
         K_all = np.concatenate([A_k[idx[g]] @ B_k[:, cols], K_tail[g]], axis=0)   # Eq. 3 rows, then the tail
         V_all = np.concatenate([A_v[idx[g]] @ B_v[:, cols], V_tail[g]], axis=0)
@@ -206,7 +201,21 @@ def sr_decode_tail(A_k, A_v, B_k, B_v, q, H_kv, k, K_tail, V_tail, scale=None):
             z = scale * (K_all @ q[h])
             wgt = np.exp(z - z.max())
             out[h] = (wgt / wgt.sum()) @ V_all
-    return out, idx
+    return out
+
+
+def sr_decode_tail(A_k, A_v, B_k, B_v, q, H_kv, k, K_tail, V_tail, scale=None):
+    """SR step over a context whose most recent T tokens are still uncompressed (Sec. 4, "Implementation
+    details": newly generated tokens are kept uncompressed; Sec. 7, long-generation scenario).
+
+    The L compressed tokens are scored, pooled and selected exactly as in sr_decode (steps 1-4); attention then
+    runs over the selected rows and the tail (gather_attend_tail).  Returns (out[H_q][d_h], idx[H_kv][k]).
+    """
+    q64 = widen(q)
+    scale = default_scale(q64.shape[1]) if scale is None else scale
+    S32 = pooled_scores(A_k, B_k, q, H_kv, scale).astype(np.float32)   # the selection is taken in fp32 (step 4)
+    idx = np.stack([select(S32[g], k) for g in range(H_kv)]).astype(np.int32)
+    return gather_attend_tail(A_k, A_v, B_k, B_v, q, idx, K_tail, V_tail, scale), idx
 
 
 def factorize(X_cat, r):

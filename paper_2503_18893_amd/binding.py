@@ -17,8 +17,9 @@ XKV_OK, XKV_ERR_INVALID_ARG, XKV_ERR_UNSUPPORTED, XKV_ERR_WORKSPACE, XKV_ERR_HIP
 XKV_F32, XKV_BF16 = 0, 1
 DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
 
-ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_dense_decode", "xkv_score", "xkv_topk",
-                "xkv_gather_attend", "xkv_reconstruct", "xkv_profile_kernel", "xkv_status_string", "xkv_version")
+ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score",
+                "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_profile_kernel", "xkv_status_string",
+                "xkv_version")
 
 
 class XkvError(RuntimeError):
@@ -75,6 +76,7 @@ def load() -> ctypes.CDLL:
         sp = ctypes.POINTER(xkv_shape)
         lib.xkv_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
         lib.xkv_sr_decode.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_sr_decode_tail.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.xkv_dense_decode.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_score.argtypes = [sp, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_topk.argtypes = [sp, vp, vp, vp, sz, vp]
@@ -84,7 +86,7 @@ def load() -> ctypes.CDLL:
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:8]:
+        for name in ENTRY_POINTS[:9]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -130,6 +132,14 @@ def xkv_sr_decode(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, idx_out, sc
     _check(load().xkv_sr_decode(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k), _ptr(B_v),
                                 _ptr(q), _ptr(out), _ptr(idx_out), _ptr(score_out), _ptr(workspace),
                                 workspace.numel(), _stream(stream)), "xkv_sr_decode")
+
+
+def xkv_sr_decode_tail(shape, layer_in_group, A_k, A_v, B_k, B_v, q, K_tail, V_tail, T, out, idx_out, score_out,
+                       workspace, stream=None):
+    _check(load().xkv_sr_decode_tail(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
+                                     _ptr(B_v), _ptr(q), _ptr(K_tail), _ptr(V_tail), int(T), _ptr(out), _ptr(idx_out),
+                                     _ptr(score_out), _ptr(workspace), workspace.numel(), _stream(stream)),
+           "xkv_sr_decode_tail")
 
 
 def xkv_dense_decode(shape, K, V, q, out, workspace, stream=None):

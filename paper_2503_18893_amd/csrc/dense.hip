@@ -98,12 +98,16 @@ __global__ __launch_bounds__(256) void dense_generic_kernel(const T *__restrict_
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ part_o,
                                                       const float *__restrict__ part_ml, T *__restrict__ out,
-                                                      int H_q, int d_h, int n_part)
+                                                      int H_q, int d_h, int n_part,
+                                                      const float *__restrict__ part_o2,
+                                                      const float *__restrict__ part_ml2, int n_part2)
 {
+    // the second set of partials (n_part2 may be 0) has the same layout; it holds the uncompressed tail tokens
     const int h = blockIdx.x, b = blockIdx.y;
-    const size_t base = ((size_t)b * H_q + h) * n_part;
+    const size_t base = ((size_t)b * H_q + h) * n_part, base2 = ((size_t)b * H_q + h) * n_part2;
     float M = -INFINITY;
     for (int s = 0; s < n_part; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
+    for (int s = 0; s < n_part2; ++s) M = fmaxf(M, part_ml2[(base2 + s) * 2]);
     for (int j = threadIdx.x; j < d_h; j += blockDim.x) {
         float num = 0.0f, den = 0.0f;
         for (int s = 0; s < n_part; ++s) {
@@ -111,6 +115,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
             const float wgt = (m == -INFINITY) ? 0.0f : expf(m - M);
             num = fmaf(wgt, part_o[(base + s) * d_h + j], num);
             den = fmaf(wgt, part_ml[(base + s) * 2 + 1], den);
+        }
+        for (int s = 0; s < n_part2; ++s) {
+            const float m = part_ml2[(base2 + s) * 2];
+            const float wgt = (m == -INFINITY) ? 0.0f : expf(m - M);
+            num = fmaf(wgt, part_o2[(base2 + s) * d_h + j], num);
+            den = fmaf(wgt, part_ml2[(base2 + s) * 2 + 1], den);
         }
         out[((size_t)b * H_q + h) * d_h + j] = from_f32<T>(num / den);
     }
@@ -338,10 +348,12 @@ static hipError_t launch_dense_generic(const xkv_shape &s, const Plan &p, const 
 
 bool dense_mfma_shape_ok(const xkv_shape &s) { return s.dtype == XKV_BF16 && s.d_h == 128; }
 
+bool dense_uses_mfma(const Plan &p, const void *K, const void *V, const void *q);
+
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st)
 {
-    if (p.dense_mfma && ((((uintptr_t)K | (uintptr_t)V | (uintptr_t)q)) & 15u) == 0) {
+    if (dense_uses_mfma(p, K, V, q)) {
         dim3 grid(p.dense_splits, s.H_kv, s.batch), block(256);
         profile_begin(2, st);
         hipLaunchKernelGGL(dense_mfma_kernel, grid, block, 0, st, (const bf16_t *)K, (const bf16_t *)V,
@@ -355,16 +367,22 @@ hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const 
 }
 
 hipError_t launch_combine(const xkv_shape &s, int n_part, const float *part_o, const float *part_ml, void *out,
-                          hipStream_t st)
+                          hipStream_t st, int n_part2, const float *part_o2, const float *part_ml2)
 {
     dim3 grid(s.H_q, s.batch), block(s.d_h <= 64 ? 64 : (s.d_h <= 128 ? 128 : 256));
     if (s.dtype == XKV_F32)
         hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, st, part_o, part_ml, (float *)out, s.H_q, s.d_h,
-                           n_part);
+                           n_part, part_o2, part_ml2, n_part2);
     else
         hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, block, 0, st, part_o, part_ml, (bf16_t *)out, s.H_q, s.d_h,
-                           n_part);
+                           n_part, part_o2, part_ml2, n_part2);
     return hipGetLastError();
+}
+
+// Whether launch_dense takes the matrix-core kernel (one partial per split) or the general one (one per wavefront).
+bool dense_uses_mfma(const Plan &p, const void *K, const void *V, const void *q)
+{
+    return p.dense_mfma && ((((uintptr_t)K | (uintptr_t)V | (uintptr_t)q)) & 15u) == 0;
 }
 
 }  // namespace xkv

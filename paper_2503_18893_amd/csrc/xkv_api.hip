@@ -91,6 +91,10 @@ xkv_status make_plan(const xkv_shape &s, Plan &p)
     off = align_up(off + b * s.H_q * (size_t)p.max_splits * 2 * sizeof(float), 256);
     p.off_bpack = off;
     if (p.ga_mfma) off = align_up(off + gather_attend_pack_bytes(s), 256);
+    p.off_tail_o = off;
+    off = align_up(off + b * s.H_q * (size_t)kTailParts * s.d_h * sizeof(float), 256);
+    p.off_tail_ml = off;
+    off = align_up(off + b * s.H_q * (size_t)kTailParts * 2 * sizeof(float), 256);
     p.total = off;
     return XKV_OK;
 }
@@ -174,9 +178,11 @@ xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *
     return hip_status(e);
 }
 
-xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v, const void *B_k,
-                         const void *B_v, const void *q, void *out, int32_t *idx_out, float *score_out,
-                         void *workspace, size_t workspace_bytes, void *hip_stream)
+// SR step; K_tail / V_tail (T > 0 tokens per KV head, uncompressed) are attended together with the selected rows.
+static xkv_status sr_decode_impl(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                 const void *B_k, const void *B_v, const void *q, const void *K_tail,
+                                 const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     Plan p;
     xkv_status st = prepare(shape, workspace, workspace_bytes, p);
@@ -206,10 +212,45 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
     if (e == hipSuccess)
         e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml,
                                  stream);
+    // The uncompressed tail goes through the dense kernel as a context of T tokens of its own (at most 8 splits),
+    // into a second set of partials; the merge below is one softmax over selected rows and tail.
+    int n_tail = 0;
+    float *tail_o = at<float>(workspace, p.off_tail_o), *tail_ml = at<float>(workspace, p.off_tail_ml);
+    if (T > 0 && e == hipSuccess) {
+        xkv_shape ts = *shape;
+        ts.L = T;
+        Plan tp = p;
+        const int splits = clampi(ceil_div(T, 512), 1, kTailParts / 4);
+        tp.dense_chunk = ceil_div(ceil_div(T, splits), 128) * 128;
+        tp.dense_splits = ceil_div(T, tp.dense_chunk);
+        e = launch_dense(ts, tp, K_tail, V_tail, q, tail_o, tail_ml, stream);
+        n_tail = dense_uses_mfma(tp, K_tail, V_tail, q) ? tp.dense_splits : tp.dense_splits * 4;
+    }
     // the matrix-core kernel writes one partial per split, the general one one per wavefront
-    if (e == hipSuccess) e = launch_combine(*shape, want_pack ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
+    if (e == hipSuccess)
+        e = launch_combine(*shape, want_pack ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream, n_tail,
+                           tail_o, tail_ml);
     return hip_status(e);
 }
+
+xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v, const void *B_k,
+                         const void *B_v, const void *q, void *out, int32_t *idx_out, float *score_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return sr_decode_impl(shape, layer, A_k, A_v, B_k, B_v, q, nullptr, nullptr, 0, out, idx_out, score_out, workspace,
+                          workspace_bytes, hip_stream);
+}
+
+xkv_status xkv_sr_decode_tail(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                              const void *B_k, const void *B_v, const void *q, const void *K_tail,
+                              const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
+                              void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (T < 0 || (T > 0 && (!K_tail || !V_tail))) return XKV_ERR_INVALID_ARG;
+    return sr_decode_impl(shape, layer, A_k, A_v, B_k, B_v, q, K_tail, V_tail, T, out, idx_out, score_out, workspace,
+                          workspace_bytes, hip_stream);
+}
+
 
 xkv_status xkv_dense_decode(const xkv_shape *shape, const void *K, const void *V, const void *q, void *out,
                             void *workspace, size_t workspace_bytes, void *hip_stream)

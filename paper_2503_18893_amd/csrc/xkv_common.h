@@ -68,7 +68,7 @@ struct Plan {
     int max_splits;
     float scale;
     // byte offsets into the workspace
-    size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, off_bpack, total;
+    size_t off_p, off_score, off_idx, off_hist, off_state, off_part_o, off_part_ml, off_bpack, off_tail_o, off_tail_ml, total;
     bool dense_mfma;   // shape fits the matrix-core dense kernel
     bool ga_mfma;      // shape fits the matrix-core gather-attend kernel
     int ga_waves;      // ... with this many wavefronts (32 selected tokens each) per workgroup
@@ -79,6 +79,7 @@ struct Plan {
     int score_waves;   // wavefronts per workgroup of that kernel (8, or 4 at large ranks)
 };
 
+constexpr int kTailParts = 32;   // partials per query head for the uncompressed tail (8 splits x 4 wavefronts)
 constexpr int kTopkLevels = 4;   // 8-bit digits of the 32-bit order key
 constexpr int kTopkBins = 256;
 constexpr int kStateWords = 8;   // per row: (prefix, k_rem) for each resolved level
@@ -150,7 +151,9 @@ hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const 
                         float *part_ml, hipStream_t st);
 bool dense_mfma_shape_ok(const xkv_shape &s);
 hipError_t launch_combine(const xkv_shape &s, int n_part, const float *part_o, const float *part_ml, void *out,
-                          hipStream_t st);
+                          hipStream_t st, int n_part2 = 0, const float *part_o2 = nullptr,
+                          const float *part_ml2 = nullptr);
+bool dense_uses_mfma(const Plan &p, const void *K, const void *V, const void *q);
 hipError_t launch_reconstruct(const xkv_shape &s, int layer, const void *A, const void *B, int r, void *X,
                               hipStream_t st);
 

@@ -20,7 +20,7 @@ def declared_entry_points():
 
 def test_header_declares_the_expected_calls():
     names = declared_entry_points()
-    for must in ("xkv_sr_decode", "xkv_dense_decode", "xkv_score", "xkv_topk", "xkv_gather_attend",
+    for must in ("xkv_sr_decode", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score", "xkv_topk", "xkv_gather_attend",
                  "xkv_workspace_bytes", "xkv_reconstruct"):
         assert must in names
     assert sorted(xb.ENTRY_POINTS) == names      # the binding wraps exactly what the header declares
@@ -71,6 +71,11 @@ def test_calls_reject_null_pointers_before_touching_the_gpu():
     assert lib.xkv_sr_decode(ctypes.byref(c), 0, null, null, null, null, null, null, null, null, null, 0,
                              null) == xb.XKV_ERR_INVALID_ARG
     assert lib.xkv_reconstruct(ctypes.byref(c), 0, null, null, 4, null, null) == xb.XKV_ERR_INVALID_ARG
+    one = ctypes.c_void_p(256)  # never dereferenced: the calls below fail on the host
+    assert lib.xkv_sr_decode_tail(ctypes.byref(c), 0, one, one, one, one, one, null, null, -1, one, null, null, one,
+                                  1 << 30, null) == xb.XKV_ERR_INVALID_ARG      # negative tail length
+    assert lib.xkv_sr_decode_tail(ctypes.byref(c), 0, one, one, one, one, one, null, one, 5, one, null, null, one,
+                                  1 << 30, null) == xb.XKV_ERR_INVALID_ARG      # tail tokens without their keys
 
 
 def test_binding_has_no_cpu_fallback(monkeypatch):

@@ -301,6 +301,52 @@ def test_qwen_full_size_sampled():
     _full_size_sampled(synth.QWEN, seqs=(synth.QWEN.batch - 1,), seed=32)
 
 
+# ------------------------------------------------------------------------------ uncompressed tail of recent tokens
+TAIL = [
+    ("tiny_f32", synth.TINY.with_(L=700, k=40), 37),
+    ("llama_bf16", synth.LLAMA_GROUP.with_(L=3000, k=200, r_k=128, r_v=192, batch=2, G=1), 1),
+    ("llama_bf16_long_tail", synth.LLAMA_GROUP.with_(L=2000, k=300, r_k=64, r_v=64, batch=1, G=1), 1700),
+    ("qwen_bf16", synth.QWEN.with_(L=2500, k=100, batch=2, r_k=64, r_v=64, G=1), 129),
+]
+
+
+@pytest.mark.parametrize("name,w,T", TAIL, ids=[n for n, _, _ in TAIL])
+def test_sr_decode_with_uncompressed_tail(name, w, T):
+    """xkv_sr_decode_tail: same scores and selection as the plain step, output against the oracle's attention over
+    the selected rows plus the tail (fed the GPU's own index sets); T = 0 reproduces xkv_sr_decode bit for bit."""
+    torch = torch_mod()
+    case = synth.make_case(w, seed=23)
+    dev = synth.to_device(case, w.dtype)
+    rng = np.random.default_rng(5)
+    K_t = synth.to_storage(rng.standard_normal((w.batch, w.H_kv, T, w.d_h)) * 0.3, w.dtype)
+    V_t = synth.to_storage(rng.standard_normal((w.batch, w.H_kv, T, w.d_h)), w.dtype)
+    tail = synth.to_device({"K": K_t, "V": V_t}, w.dtype)
+    shape = xb.Shape.of(w)
+    ws = xb.alloc_workspace(shape)
+    dt = synth.torch_dtype(w.dtype)
+    q = dev["q"][0].contiguous()
+    out = torch.empty((w.batch, w.H_q, w.d_h), dtype=dt, device="cuda")
+    out0, out_plain = torch.empty_like(out), torch.empty_like(out)
+    idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
+    idx_plain = torch.empty_like(idx)
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    xb.xkv_sr_decode_tail(shape, 0, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, tail["K"], tail["V"], T, out, idx,
+                          S, ws)
+    xb.xkv_sr_decode_tail(shape, 0, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, None, None, 0, out0, None, None,
+                          ws)
+    xb.xkv_sr_decode(shape, 0, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, out_plain, idx_plain, None, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(synth.to_host(out0), synth.to_host(out_plain))
+    np.testing.assert_array_equal(idx.cpu().numpy(), idx_plain.cpu().numpy())
+    outh, idxh, Sh = synth.storage_to_f64(synth.to_host(out)), idx.cpu().numpy(), S.cpu().numpy()
+    for b in range(w.batch):
+        for g in range(w.H_kv):
+            np.testing.assert_array_equal(idxh[b, g], oracle.select(Sh[b, g], w.k))
+        ref = oracle.gather_attend_tail(case["A_k"][b], case["A_v"][b], case["B_k"][b, 0], case["B_v"][b, 0],
+                                        case["q"][0, b], idxh[b], K_t[b], V_t[b])
+        assert max_rel(outh[b], ref) <= TOL[w.dtype], (name, b)
+
+
 # ------------------------------------------------------------------------------ error paths (host side, no launch)
 def test_error_codes():
     torch = torch_mod()
