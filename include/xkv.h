@@ -136,6 +136,26 @@ XKV_API xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer_in_gr
 XKV_API xkv_status xkv_reconstruct(const xkv_shape *shape, int32_t layer_in_group, const void *A, const void *B,
                                    int32_t r, void *X_out, void *hip_stream);
 
+/*
+ * Cross-Layer Factorization of one layer group (Sec. 3.1, Eq. 1; run once per prompt at prefill, separately for
+ * keys and for values, App. C.6): the caches of the G layers, X [batch][G][H_kv][L][d_h] in shape->dtype (layer l's
+ * cache in the dense K/V layout above), are read as X_cat [L][n], n = G * H_kv * d_h, column l*d + g*d_h + j =
+ * channel j of KV head g of layer l, and replaced by
+ *   B_out [batch][G][r][H_kv*d_h]  r orthonormal rows (before rounding to shape->dtype) spanning the dominant
+ *                                  rank-r right singular subspace of X_cat, cut into the per-layer blocks B_l,
+ *   A_out [batch][L][r]            A = X_cat B^T, so that A [B_1 .. B_G] is X_cat projected onto that subspace.
+ * The subspace is found by `iters` rounds of block power iteration on X_cat^T X_cat from a pseudo-random start
+ * chosen by `seed` (randomised subspace iteration with Cholesky-QR as in App. B.3); the approximation error
+ * ||X_cat - A B||_F approaches the optimum of Eq. 1 (the truncated SVD) as iters grows, 8 is a good default.  The
+ * factors equal (U Sigma, V^T) of Eq. 1 up to an r x r rotation within the subspace, which no product A B_l sees.
+ * The layouts of A_out and B_out are those xkv_sr_decode takes.  shape->r_k, r_v, k, H_q, scale are ignored.
+ * XKV_ERR_UNSUPPORTED unless d_h % 64 == 0, r <= min(1024, n) and n <= 16384; XKV_ERR_INVALID_ARG for iters < 1.
+ * workspace: at least xkv_factorize_workspace_bytes() bytes, 256-byte aligned.
+ */
+XKV_API xkv_status xkv_factorize_workspace_bytes(const xkv_shape *shape, int32_t r, size_t *bytes);
+XKV_API xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32_t iters, uint32_t seed,
+                                 void *A_out, void *B_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Measurement aid for callers that want the duration of one kernel rather than of a whole call.
  * Not part of the method.  For stage = 0 (low-rank score kernel), 1 (gather-reconstruct + sparse
  * attention kernel) or 2 (dense decode kernel), every later call that launches that kernel records

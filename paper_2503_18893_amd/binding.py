@@ -18,8 +18,8 @@ XKV_F32, XKV_BF16 = 0, 1
 DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
 
 ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score",
-                "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_profile_kernel", "xkv_status_string",
-                "xkv_version")
+                "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_factorize_workspace_bytes", "xkv_factorize",
+                "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
 class XkvError(RuntimeError):
@@ -82,11 +82,13 @@ def load() -> ctypes.CDLL:
         lib.xkv_topk.argtypes = [sp, vp, vp, vp, sz, vp]
         lib.xkv_gather_attend.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_reconstruct.argtypes = [sp, i32, vp, vp, i32, vp, vp]
+        lib.xkv_factorize_workspace_bytes.argtypes = [sp, i32, ctypes.POINTER(sz)]
+        lib.xkv_factorize.argtypes = [sp, vp, i32, i32, ctypes.c_uint32, vp, vp, vp, sz, vp]
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:9]:
+        for name in ENTRY_POINTS[:11]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -166,6 +168,19 @@ def xkv_gather_attend(shape, layer_in_group, A_k, A_v, B_k, B_v, q, idx, out, wo
 def xkv_reconstruct(shape, layer_in_group, A, B, r, X_out, stream=None):
     _check(load().xkv_reconstruct(ctypes.byref(shape.c()), layer_in_group, _ptr(A), _ptr(B), r, _ptr(X_out),
                                   _stream(stream)), "xkv_reconstruct")
+
+
+def xkv_factorize_workspace_bytes(shape: Shape, r: int) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().xkv_factorize_workspace_bytes(ctypes.byref(shape.c()), r, ctypes.byref(n)),
+           "xkv_factorize_workspace_bytes")
+    return int(n.value)
+
+
+def xkv_factorize(shape, X, r, iters, seed, A_out, B_out, workspace, stream=None):
+    _check(load().xkv_factorize(ctypes.byref(shape.c()), _ptr(X), r, iters, seed, _ptr(A_out), _ptr(B_out),
+                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_factorize")
 
 
 STAGE_SCORE, STAGE_GATHER_ATTEND, STAGE_DENSE = 0, 1, 2

@@ -1,0 +1,724 @@
+// factorize.hip -- Cross-Layer Factorization (Sec. 3.1, Eq. 1) on the GPU: the caches of the G layers of a
+// group, concatenated along the feature axis into X_cat [L][n] (n = G * H_kv * d_h), are replaced by a shared
+// token basis A [L][r] and per-layer reconstruction matrices B_l [r][d] with A [B_1 .. B_G] the best rank-r
+// approximation of X_cat.
+//
+// How it is computed here.  n is a few thousand while L is tens of thousands, so the right singular subspace
+// is taken from the n x n Gram matrix C = X_cat^T X_cat, which is built once on the matrix cores and then
+// stays in cache:
+//   1. X_cat is rewritten channel-major (Xt [n][Lp], tokens contiguous, zero-padded to a multiple of 64) so
+//      that both operands of the Gram product are contiguous along the summation index;
+//   2. C = Xt Xt^T (lower tiles, split over the tokens, fp32 accumulation), mirrored to the full matrix;
+//   3. block power iteration on C: V <- orth(C V) for a random start V [r][n], `iters` times.  The product
+//      runs on the fp32 matrix cores; orth() is a Cholesky-QR in fp64 (Gram matrix of the r vectors,
+//      Cholesky factor, forward substitution), which keeps r directions apart whose lengths differ by many
+//      orders of magnitude after the multiplication by C;
+//   4. B = V rounded to the storage type (rows of B are an orthonormal basis of the dominant right singular
+//      subspace), A = X_cat B^T (matrix cores again).
+// A B is then X_cat projected onto the span of B's rows.  The factors differ from (U Sigma, V^T) of Eq. 1 by an
+// r x r rotation inside that span, which leaves every product A B_l, and with it every quantity the decode path
+// computes, unchanged.  (Randomised subspace iteration with Cholesky-QR is also what App. B.3 describes for
+// the paper's own implementation; working on the Gram matrix instead of X_cat is this implementation's choice.)
+#include "xkv_common.h"
+
+#include <algorithm>
+
+namespace xkv {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 fz_bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float fz_f32x16_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t fz_u32x4_t;
+typedef __attribute__((ext_vector_type(4))) float fz_f32x4_t;
+typedef __attribute__((address_space(3))) void fz_lds_void_t;
+
+__device__ __forceinline__ void fz_copy16_global_to_lds(const void *gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory");
+}
+#define FZ_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt((0 & 0xF) | (7 << 4) | (0xF << 8) | (0 << 14))
+
+__device__ __forceinline__ void fz_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// ------------------------------------------------------------------------------------------------
+// (1) X [G*H_kv][L][d_h] (one sequence, every layer and head of the group) -> Xt [n][Lp], row
+//     cb * d_h + j = channel j of column block cb, zero beyond token L.  64 x 64 tiles through LDS.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void xt_pack_kernel(const T *__restrict__ X, T *__restrict__ Xt, int L, int Lp, int d_h)
+{
+    constexpr int V = 16 / sizeof(T);  // elements per 16 B
+    constexpr int PPR = 64 / V;        // 16 B pieces per tile row
+    __shared__ __attribute__((aligned(16))) T tile[64][64 + V];
+    const int t0 = blockIdx.x * 64, n0 = blockIdx.y * 64;
+    const int cb = n0 / d_h, c0 = n0 % d_h;
+    const T *src = X + (size_t)cb * L * d_h + c0;
+    for (int i = threadIdx.x; i < 64 * PPR; i += 256) {
+        const int tt = i / PPR, p = i % PPR;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (t0 + tt < L) v = *reinterpret_cast<const uint4 *>(src + (size_t)(t0 + tt) * d_h + p * V);
+        *reinterpret_cast<uint4 *>(&tile[tt][p * V]) = v;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * PPR; i += 256) {
+        const int c = i / PPR, p = i % PPR;
+        __attribute__((aligned(16))) T vals[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) vals[e] = tile[p * V + e][c];
+        *reinterpret_cast<uint4 *>(Xt + (size_t)(n0 + c) * Lp + t0 + p * V) = *reinterpret_cast<const uint4 *>(vals);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// (2) out[m][n] = sum_k P[m][k] Q[n][k] on the matrix cores, both operands contiguous along k.
+//
+// Element (row, k) of an operand lives at base + (k / kbw) * kblk + row * pitch + k % kbw: a plain row-major
+// matrix has kbw = K, and a cache stored as [column block][token][d_h] is read as X_cat [token][n] with
+// kbw = d_h, kblk = L * d_h, pitch = d_h.  K is consumed in slabs of 128 B per row (64 bf16 or 32 fp32
+// values); kbw is a multiple of the slab.
+//
+// Workgroup: 8 wavefronts, a 256 x 256 output tile, wavefront (wm, wn) owns rows 64 wm .. +63 and columns
+// 128 wn .. +127 as 2 x 4 accumulator tiles of 32 x 32.  A slab of the 256 + 256 operand rows (64 KiB) is
+// copied global -> LDS directly, double-buffered: one copy instruction moves 8 rows x 128 B, lane l fetching
+// the 16 B piece (l % 8) ^ (l / 8) of row l / 8, so that a row's pieces sit in LDS xor-swizzled by the row
+// number and the fragment reads (32 rows, same piece) spread over all banks.  Rows beyond the operand's end
+// are clamped to its last row; what they produce is never stored.
+// Output: fp32 partial planes out_f32[split][m][n] (summed by a second kernel), or, with one split, the
+// final matrix in fp32 or bf16.  With lower_only (P == Q) only tiles on or below the diagonal are computed.
+// ------------------------------------------------------------------------------------------------
+struct GemmOperand {
+    const void *base;
+    long long pitch, kblk;  // elements
+    int kbw, rows;
+};
+struct GemmArgs {
+    GemmOperand P, Q;
+    int n_slabs, splits, lower_only, tiles_n;
+    float *out_f32;
+    bf16_t *out_bf16;
+    long long ldo, plane;
+};
+
+constexpr int kGemmThreads = 512, kGemmTile = 256, kGemmStage = 512 * 128, kGemmLds = 2 * kGemmStage;
+
+// Decoding of a linear index into a pair (bi, bj), bj <= bi, enumerated row by row.
+__device__ __forceinline__ void fz_lower_pair(int t, int &bi, int &bj)
+{
+    int m = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+    while ((m + 1) * (m + 2) / 2 <= t) ++m;
+    while (m * (m + 1) / 2 > t) --m;
+    bi = m;
+    bj = t - m * (m + 1) / 2;
+}
+
+// The eight copy instructions of a wavefront for one slab: its 64 operand rows, 8 rows x 128 B each.
+__device__ __forceinline__ void fz_issue_slab(const unsigned char *const (&rowp)[8], size_t off, uint32_t dst)
+{
+#pragma unroll
+    for (int j = 0; j < 8; ++j) fz_copy16_global_to_lds(rowp[j] + off, dst + j * 1024);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
+{
+    constexpr int E = 128 / (int)sizeof(T);  // elements per slab row
+    extern __shared__ __attribute__((aligned(16))) unsigned char fz_smem[];
+    const int tid = threadIdx.x, lane = tid & 63, w = wave_id();
+    const int m32 = lane & 31, h = lane >> 5;
+
+    int tm, tn;
+    if (a.lower_only) {  // blockIdx.x enumerates (tm, tn), tn <= tm, row by row
+        fz_lower_pair(blockIdx.x, tm, tn);
+    } else {
+        tm = blockIdx.x / a.tiles_n;
+        tn = blockIdx.x % a.tiles_n;
+    }
+    const int split = blockIdx.y;
+    const int sb_begin = (int)((long long)a.n_slabs * split / a.splits);
+    const int sb_end = (int)((long long)a.n_slabs * (split + 1) / a.splits);
+
+    // ---- copy side: wavefronts 0-3 bring in P rows 64 w .. +63 of the tile, wavefronts 4-7 the Q rows
+    const bool is_p = w < 4;
+    const void *op_base = is_p ? a.P.base : a.Q.base;
+    const long long op_pitch = is_p ? a.P.pitch : a.Q.pitch, op_kblk = is_p ? a.P.kblk : a.Q.kblk;
+    const int op_kbw = is_p ? a.P.kbw : a.Q.kbw, op_rows = is_p ? a.P.rows : a.Q.rows;
+    const int origin = (is_p ? tm : tn) * kGemmTile + (w & 3) * 64;
+    const int piece = (lane & 7) ^ (lane >> 3);
+    const unsigned char *rowp[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int R = origin + 8 * j + (lane >> 3);
+        R = R < op_rows ? R : op_rows - 1;
+        rowp[j] = reinterpret_cast<const unsigned char *>(op_base) + (size_t)((long long)R * op_pitch) * sizeof(T) + piece * 16;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(fz_lds_void_t *)fz_smem + (uint32_t)(w * 8 * 1024);
+    auto slab_offset = [&](int sb) __attribute__((always_inline)) {
+        const long long kk = (long long)sb * E;
+        return (size_t)((kk / op_kbw) * op_kblk + kk % op_kbw) * sizeof(T);
+    };
+
+    // ---- compute side
+    const int wm = w & 3, wn = w >> 2;
+    fz_f32x16_t acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    // 16 B index of (row, piece c) in a stage: row * 8 + (c ^ row % 8); row % 8 == m32 % 8 for every row read here
+    const int arow = (64 * wm + m32) * 8, qrow = (256 + 128 * wn + m32) * 8, sw = m32 & 7;
+
+    if (sb_begin < sb_end) fz_issue_slab(rowp, slab_offset(sb_begin), lds0);
+    for (int sb = sb_begin; sb < sb_end; ++sb) {
+        const int buf = (sb - sb_begin) & 1;
+        FZ_WAIT_VMCNT0();
+        fz_lds_barrier();  // this slab has landed for every wavefront; nobody reads the other buffer any more
+        if (sb + 1 < sb_end) fz_issue_slab(rowp, slab_offset(sb + 1), lds0 + (uint32_t)((buf ^ 1) * kGemmStage));
+        const fz_u32x4_t *st = reinterpret_cast<const fz_u32x4_t *>(fz_smem + buf * kGemmStage);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int slot = (2 * s + h) ^ sw;
+            fz_u32x4_t af[2], qf[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) af[i] = st[arow + i * 256 + slot];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) qf[j] = st[qrow + j * 256 + slot];
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fz_bf16x8_t, af[i]),
+                                                                            __builtin_bit_cast(fz_bf16x8_t, qf[j]),
+                                                                            acc[i][j], 0, 0, 0);
+            } else {
+                // a 16 B piece holds 4 consecutive k of the lane's row; step e pairs k = 8 s + e (lanes 0-31)
+                // with k = 8 s + 4 + e (lanes 32-63) on both operands
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(fz_f32x4_t, af[i])[e],
+                                                                             __builtin_bit_cast(fz_f32x4_t, qf[j])[e],
+                                                                             acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- store: accumulator register v of a 32 x 32 tile is row 8 (v / 4) + 4 h + v % 4, column m32
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = tn * kGemmTile + 128 * wn + 32 * j + m32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = tm * kGemmTile + 64 * wm + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
+                if (row < a.P.rows && col < a.Q.rows) {
+                    const size_t o = (size_t)row * a.ldo + col;
+                    if (a.out_bf16)
+                        a.out_bf16[o] = f32_to_bf16(acc[i][j][v]);
+                    else
+                        a.out_f32[(size_t)split * a.plane + o] = acc[i][j][v];
+                }
+            }
+        }
+}
+
+// (2b) C = sum of the split planes of the lower 64 x 64 blocks, mirrored into the upper triangle.
+__global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restrict__ part, float *__restrict__ C, int n,
+                                                          int splits, long long plane)
+{
+    const int bm = blockIdx.y, bn = blockIdx.x;
+    if (bn > bm) return;
+    __shared__ float tile[64][65];
+    for (int i = threadIdx.x; i < 4096; i += 256) {
+        const int rr = i >> 6, cc = i & 63, m = bm * 64 + rr, c = bn * 64 + cc;
+        float v = 0.0f;
+        if (m < n && c < n) {
+            for (int s = 0; s < splits; ++s) v += part[(size_t)s * plane + (size_t)m * n + c];
+            C[(size_t)m * n + c] = v;
+        }
+        tile[rr][cc] = v;
+    }
+    __syncthreads();
+    if (bn == bm) return;
+    for (int i = threadIdx.x; i < 4096; i += 256) {
+        const int rr = i >> 6, cc = i & 63, m = bn * 64 + rr, c = bm * 64 + cc;  // element (m, c) of the upper block
+        if (m < n && c < n) C[(size_t)m * n + c] = tile[cc][rr];
+    }
+}
+
+// (2c) out = sum of `splits` planes of `count` floats.
+__global__ __launch_bounds__(256) void sum_planes_kernel(const float *__restrict__ part, float *__restrict__ out,
+                                                         long long count, int splits, long long plane)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    float v = 0.0f;
+    for (int s = 0; s < splits; ++s) v += part[(size_t)s * plane + i];
+    out[i] = v;
+}
+
+// (3a) Start block of the iteration: r x n values in (-1, 1) from a counter hash of (seed, index).
+__global__ __launch_bounds__(256) void init_v_kernel(float *__restrict__ Vt, long long count, uint32_t seed)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    uint32_t x = (uint32_t)i * 0x9E3779B9u + seed * 0x85EBCA6Bu + (uint32_t)(i >> 32) * 0xC2B2AE35u + 0x27D4EB2Fu;
+    x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+    Vt[i] = ((float)(x >> 8) + 0.5f) * (2.0f / 16777216.0f) - 1.0f;
+}
+
+// (3b) Gram matrix of the r vectors, products and sums in fp64: G[i][j] = sum_n W[n][i] W[n][j].  One workgroup
+// per 64 x 64 block on or below the diagonal and per range of n (one partial plane per range, added up in a
+// fixed order by gram_sum_kernel); 4 x 4 outputs per thread; W is widened to fp64 on its way into LDS.
+__global__ __launch_bounds__(256) void gram_f64_kernel(const float *__restrict__ Wn, double *__restrict__ planes, int n,
+                                                       int r, int splits)
+{
+    int bi, bj;
+    fz_lower_pair(blockIdx.x, bi, bj);
+    const int split = blockIdx.y;
+    const int n_begin = (int)((long long)n * split / splits), n_end = (int)((long long)n * (split + 1) / splits);
+    __shared__ double wa[32][64], wb[32][64];
+    const int i0 = bi * 64, j0 = bj * 64, ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    double acc[4][4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+    for (int n0 = n_begin; n0 < n_end; n0 += 32) {
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 32 * 64; idx += 256) {
+            const int nn = idx >> 6, ii = idx & 63;
+            const bool ok = n0 + nn < n_end;
+            wa[nn][ii] = (ok && i0 + ii < r) ? (double)Wn[(size_t)(n0 + nn) * r + i0 + ii] : 0.0;
+            wb[nn][ii] = (ok && j0 + ii < r) ? (double)Wn[(size_t)(n0 + nn) * r + j0 + ii] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int nn = 0; nn < 32; ++nn) {
+            double av[4], bv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) av[u] = wa[nn][ty + 16 * u];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) bv[v] = wb[nn][tx + 16 * v];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[u][v] += av[u] * bv[v];
+        }
+    }
+    double *out = planes + (size_t)split * r * r;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int i = i0 + ty + 16 * u, j = j0 + tx + 16 * v;
+            if (i < r && j < r) out[(size_t)i * r + j] = acc[u][v];
+        }
+}
+
+__global__ __launch_bounds__(256) void gram_sum_kernel(const double *__restrict__ planes, double *__restrict__ G,
+                                                       double *__restrict__ diag0, int r, int splits)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)r * r) return;
+    const int i = (int)(idx / r), j = (int)(idx % r);
+    if ((j >> 6) > (i >> 6)) return;
+    double v = 0.0;
+    for (int s = 0; s < splits; ++s) v += planes[(size_t)s * r * r + idx];
+    G[idx] = v;
+    if (i == j) diag0[i] = v;
+}
+
+// (3c) Cholesky factor Lc of G + shift I, right-looking, one launch per panel of pb columns [c0, c0 + pb).
+// Workgroup j owns rows i0 = c0 + 32 j .. i0 + 31 of G and touches nothing else, so the workgroups of a launch do
+// not depend on each other; what they need of the panel beyond their own rows they recompute:
+//   1. every workgroup factors the pb x pb diagonal block (current values of G, shift added) in LDS;
+//   2. it solves for the panel entries Lc[j'][c0 .. c0 + pb) of all rows j' from the diagonal block down to
+//      its own last row (one thread per row, substitution in registers) and keeps them in LDS;
+//   3. it subtracts the panel's outer product from its own rows of the trailing matrix, G[i][j'] -= Lc[i] . Lc[j'].
+// Own rows of the panel are written to Lt transposed (Lt[k][i] = Lc[i][k], i >= k), so that the column of Lc a
+// later substitution needs is a contiguous row.
+// shift = 1e-13 * max diagonal of the original G (diag0) keeps the factor defined when the r vectors are
+// numerically dependent (an X_cat of rank below r): such directions come out short instead of normalised and
+// contribute nothing to A B.
+constexpr int kCholRB = 32;
+__global__ __launch_bounds__(256) void chol_panel_kernel(double *__restrict__ G, double *__restrict__ Lt,
+                                                         const double *__restrict__ diag0, int r, int c0, int pb)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char fz_smem[];
+    const int RP = r - c0, P1 = pb + 1;
+    double *LD = reinterpret_cast<double *>(fz_smem);  // [pb][pb + 1] working copy of the diagonal block
+    double *LS = LD + pb * P1;                          // [pb][pb + 1] its factor
+    double *dinvs = LS + pb * P1;                       // [pb]
+    double *Lp = dinvs + pb;                            // [pb][RP]: Lc[c0 + rr][c0 + c] at c * RP + rr
+    __shared__ double red[4];
+    const int tid = threadIdx.x;
+    const int pwc = (r - c0) < pb ? (r - c0) : pb;
+    const int i0 = c0 + blockIdx.x * kCholRB;
+    const int own_end = (i0 + kCholRB) < r ? (i0 + kCholRB) : r;
+
+    double mx = 0.0;
+    for (int i = tid; i < r; i += 256) mx = fmax(mx, diag0[i]);
+    for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    for (int e = tid; e < pb * pb; e += 256) {
+        const int a = e / pb, b = e % pb;
+        double v = a == b ? 1.0 : 0.0;
+        if (a < pwc && b <= a) v = G[(size_t)(c0 + a) * r + c0 + b];
+        LD[a * P1 + b] = v;
+        LS[a * P1 + b] = 0.0;
+    }
+    __syncthreads();
+    const double shift = fmax(1e-13 * fmax(fmax(red[0], red[1]), fmax(red[2], red[3])), 1e-300);
+    if (tid < pwc) LD[tid * P1 + tid] += shift;
+
+    // ---- 1. diagonal block; column c of LD stays unscaled while step c reads it, the scaled copy goes to LS
+    for (int c = 0; c < pb; ++c) {
+        __syncthreads();
+        const double dd = LD[c * P1 + c];
+        const double d = sqrt(dd > shift * 1e-3 ? dd : shift * 1e-3), dinv = 1.0 / d;
+        if (tid == 0) dinvs[c] = dinv;
+        for (int e = tid; e < pb * pb; e += 256) {
+            const int a = e / pb, b = e % pb;
+            if (b == c && a >= c) LS[a * P1 + c] = a == c ? d : LD[a * P1 + c] * dinv;
+            if (b > c && a >= b) LD[a * P1 + b] -= (LD[a * P1 + c] * dinv) * (LD[b * P1 + c] * dinv);
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. panel entries of the rows c0 .. own_end - 1
+    const int nrows = own_end - c0;
+    for (int rr = tid; rr < nrows; rr += 256) {
+        const int row = c0 + rr;
+        double x[32];
+        if (rr < pwc) {
+#pragma unroll
+            for (int c = 0; c < 32; ++c) x[c] = (c < pb && c <= rr) ? LS[rr * P1 + c] : 0.0;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 32; ++c) {
+                double v = 0.0;
+                if (c < pwc) {
+                    v = G[(size_t)row * r + c0 + c];
+#pragma unroll
+                    for (int c2 = 0; c2 < c; ++c2) v -= x[c2] * LS[c * P1 + c2];
+                    v *= dinvs[c];
+                }
+                x[c] = v;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 32; ++c)
+            if (c < pb) {
+                Lp[(size_t)c * RP + rr] = x[c];
+                if (row >= i0 && c < pwc && row >= c0 + c) Lt[(size_t)(c0 + c) * r + row] = x[c];
+            }
+    }
+    __syncthreads();
+
+    // ---- 3. own rows of the trailing matrix: thread = (column lane, group of 8 rows)
+    const int cl = tid & 63, rg = tid >> 6;
+    for (int jc = c0 + pwc + cl; jc < own_end; jc += 64) {
+        double acc[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) acc[v] = 0.0;
+        for (int c = 0; c < pwc; ++c) {
+            const double lj = Lp[(size_t)c * RP + (jc - c0)];
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                const int irow = i0 + rg * 8 + v;  // rows beyond own_end read zeros or stale LDS, and are not stored
+                acc[v] += (irow < own_end ? Lp[(size_t)c * RP + (irow - c0)] : 0.0) * lj;
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const int irow = i0 + rg * 8 + v;
+            if (irow < own_end && jc <= irow) G[(size_t)irow * r + jc] -= acc[v];
+        }
+    }
+}
+
+// (3c') Inverses of the 8 x 8 diagonal blocks of Lc: Minv[b][ii][jj] = (Lc_bb^-1)[ii][jj] (rows beyond r: identity).
+__global__ __launch_bounds__(256) void diag_inverse_kernel(const double *__restrict__ Lt, double *__restrict__ Minv, int r)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x, b = t >> 3, jj = t & 7;
+    if (b * 8 >= r) return;
+    double x[8];
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+        double v = ii == jj ? 1.0 : 0.0;
+        const int row = b * 8 + ii;
+        if (ii > jj && row < r) {
+#pragma unroll
+            for (int k = 0; k < ii; ++k)
+                if (k >= jj) v -= Lt[(size_t)(b * 8 + k) * r + row] * x[k];
+        }
+        if (ii >= jj && row < r) v /= Lt[(size_t)row * r + row];
+        x[ii] = ii >= jj ? v : 0.0;
+    }
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) Minv[(size_t)b * 64 + ii * 8 + jj] = x[ii];
+}
+
+// (3d) V = Lc^-1 W by blocked forward substitution: rows of W^T (Wn [n][r]) are independent, a workgroup takes
+// `rows` of them into LDS in fp64 (column-major, so that the lanes of a wavefront sit on consecutive rows) and
+// goes through the columns eight at a time: the eight values of a row are multiplied by the inverse of the
+// 8 x 8 diagonal block, then their multiples of the eight columns of Lc are subtracted from all later columns.
+// The rows of Lt are staged through LDS, the next eight being loaded while the current ones are used.  The
+// result is written transposed as Vt [r][n] in fp32.
+constexpr int kSolveIB = 8;
+__device__ __forceinline__ void fz_fetch_lt(double (&pre)[32], const double *__restrict__ Lt, int i0, int r, int per, int tid)
+{
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+        const int idx = tid + 256 * u, row = i0 + idx / r;
+        pre[u] = (u < per && idx < kSolveIB * r && row < r) ? Lt[(size_t)row * r + idx % r] : 0.0;
+    }
+}
+
+__global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict__ Wn, const double *__restrict__ Lt,
+                                                         const double *__restrict__ Minv, float *__restrict__ Vt, int n, int r,
+                                                         int rows)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char fz_smem[];
+    double *wv = reinterpret_cast<double *>(fz_smem);  // [r][rows]
+    double *lrow = wv + (size_t)r * rows;              // [kSolveIB][r]
+    __shared__ double minv_s[64];
+    const int tid = threadIdx.x, n0 = blockIdx.x * rows;
+    for (int idx = tid; idx < rows * r; idx += 256) {
+        const int rr = idx / r, i = idx % r;
+        wv[(size_t)i * rows + rr] = (n0 + rr < n) ? (double)Wn[(size_t)(n0 + rr) * r + i] : 0.0;
+    }
+    const int per = (kSolveIB * r + 255) / 256;  // staged values per thread (<= 32 for r <= 1024)
+    double pre[32];
+    fz_fetch_lt(pre, Lt, 0, r, per, tid);
+    double mpre = tid < 64 ? Minv[tid] : 0.0;
+    const int rr = tid % rows, part = tid / rows, P = 256 / rows;
+    const int s_ii = tid / rows, s_ok = tid < kSolveIB * rows;  // role in the in-block step
+    for (int i0 = 0; i0 < r; i0 += kSolveIB) {
+        __syncthreads();  // the previous block's update is complete; lrow and minv_s are free
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+            const int idx = tid + 256 * u;
+            if (u < per && idx < kSolveIB * r) lrow[idx] = pre[u];
+        }
+        if (tid < 64) minv_s[tid] = mpre;
+        if (i0 + kSolveIB < r) {
+            fz_fetch_lt(pre, Lt, i0 + kSolveIB, r, per, tid);
+            mpre = tid < 64 ? Minv[(size_t)(i0 / kSolveIB + 1) * 64 + tid] : 0.0;
+        }
+        __syncthreads();
+        double v = 0.0;
+        if (s_ok) {
+#pragma unroll
+            for (int jj = 0; jj < kSolveIB; ++jj)
+                if (jj <= s_ii && i0 + jj < r) v += minv_s[s_ii * 8 + jj] * wv[(size_t)(i0 + jj) * rows + rr];
+        }
+        __syncthreads();
+        if (s_ok && i0 + s_ii < r) wv[(size_t)(i0 + s_ii) * rows + rr] = v;
+        __syncthreads();
+        double vb[kSolveIB];
+#pragma unroll
+        for (int ii = 0; ii < kSolveIB; ++ii) vb[ii] = (i0 + ii < r) ? wv[(size_t)(i0 + ii) * rows + rr] : 0.0;
+        for (int k = i0 + kSolveIB + part; k < r; k += 4 * P) {
+            double w4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int kk = k + u * P;
+                w4[u] = kk < r ? wv[(size_t)kk * rows + rr] : 0.0;
+            }
+#pragma unroll
+            for (int ii = 0; ii < kSolveIB; ++ii)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int kk = k + u * P;
+                    w4[u] -= (kk < r ? lrow[(size_t)ii * r + kk] : 0.0) * vb[ii];
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int kk = k + u * P;
+                if (kk < r) wv[(size_t)kk * rows + rr] = w4[u];
+            }
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < rows * r; idx += 256) {
+        const int i = idx / rows, r2 = idx % rows;
+        if (n0 + r2 < n) Vt[(size_t)i * n + n0 + r2] = (float)wv[(size_t)i * rows + r2];
+    }
+}
+
+// (4a) B_out[l][i][c] = Vt[i][l * d + c] in the storage type.
+template <typename T>
+__global__ __launch_bounds__(256) void write_b_kernel(const float *__restrict__ Vt, T *__restrict__ B, int G, int r, int d)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)G * r * d) return;
+    const int c = (int)(idx % d), i = (int)((idx / d) % r), l = (int)(idx / ((long long)d * r));
+    B[idx] = from_f32<T>(Vt[(size_t)i * ((size_t)G * d) + (size_t)l * d + c]);
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int pow2_floor(int x) { int p = 1; while (2 * p <= x) p *= 2; return p; }
+
+struct FzLayout {
+    int n, Lp, gram_tiles, gram_splits, w_splits, g_splits, chol_pb, solve_rows;
+    size_t esz, off_xt, off_part, off_c, off_vt, off_wn, off_g, off_lt, off_planes, off_diag, off_minv, total;
+};
+
+FzLayout fz_layout(const xkv_shape &s, int r)
+{
+    FzLayout f{};
+    f.esz = s.dtype == XKV_F32 ? 4 : 2;
+    f.n = s.G * s.H_kv * s.d_h;
+    f.Lp = (s.L + 63) / 64 * 64;
+    const int t = (f.n + kGemmTile - 1) / kGemmTile;
+    f.gram_tiles = t * (t + 1) / 2;
+    const int slab = 128 / (int)f.esz, gram_slabs = f.Lp / slab;
+    f.gram_splits = std::max(1, std::min(std::min(16, gram_slabs), (512 + f.gram_tiles - 1) / f.gram_tiles));
+    const int w_tiles = t * ((r + kGemmTile - 1) / kGemmTile);
+    f.w_splits = std::max(1, std::min(std::min(16, f.n / 32), (256 + w_tiles - 1) / w_tiles));
+    const int gb = (r + 63) / 64;
+    f.g_splits = std::max(1, std::min(std::min(16, f.n / 32), (256 + gb * (gb + 1) / 2 - 1) / (gb * (gb + 1) / 2)));
+    f.chol_pb = r <= 512 ? 32 : 16;
+    f.solve_rows = std::max(1, std::min(32, pow2_floor(8192 / r)));
+    size_t o = 0;
+    f.off_xt = o;   o += align256((size_t)f.n * f.Lp * f.esz);
+    f.off_part = o; o += align256(std::max((size_t)f.gram_splits * f.n * f.n, (size_t)f.w_splits * f.n * r) * 4);
+    f.off_c = o;    o += align256((size_t)f.n * f.n * 4);
+    f.off_vt = o;   o += align256((size_t)r * f.n * 4);
+    f.off_wn = o;   o += align256((size_t)f.n * r * 4);
+    f.off_g = o;    o += align256((size_t)r * r * 8);
+    f.off_lt = o;   o += align256((size_t)r * r * 8);
+    f.off_planes = o; o += align256((size_t)f.g_splits * r * r * 8);
+    f.off_diag = o; o += align256((size_t)r * 8);
+    f.off_minv = o; o += align256((size_t)((r + 7) / 8) * 64 * 8);
+    f.total = o;
+    return f;
+}
+
+template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, hipStream_t st)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_nt_kernel<T>, dim3(tiles, a.splits), dim3(kGemmThreads), kGemmLds, st, a);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X, int r, int iters, uint32_t seed,
+                           void *A_out, void *B_out, unsigned char *ws, hipStream_t st)
+{
+    const int n = f.n, d = s.H_kv * s.d_h, tn = (n + kGemmTile - 1) / kGemmTile, tr = (r + kGemmTile - 1) / kGemmTile;
+    constexpr int E = 128 / (int)sizeof(T);
+    T *Xt = reinterpret_cast<T *>(ws + f.off_xt);
+    float *part = reinterpret_cast<float *>(ws + f.off_part), *C = reinterpret_cast<float *>(ws + f.off_c);
+    float *Vt = reinterpret_cast<float *>(ws + f.off_vt), *Wn = reinterpret_cast<float *>(ws + f.off_wn);
+    double *Gm = reinterpret_cast<double *>(ws + f.off_g), *Lt = reinterpret_cast<double *>(ws + f.off_lt);
+    double *planes = reinterpret_cast<double *>(ws + f.off_planes), *diag0 = reinterpret_cast<double *>(ws + f.off_diag);
+    double *Minv = reinterpret_cast<double *>(ws + f.off_minv);
+    const size_t solve_lds = ((size_t)r * f.solve_rows + (size_t)kSolveIB * r) * 8;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)chol_panel_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)orth_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipError_t e = hipSuccess;
+    for (int b = 0; b < s.batch && e == hipSuccess; ++b) {
+        const T *Xb = reinterpret_cast<const T *>(X) + (size_t)b * n * s.L;
+        hipLaunchKernelGGL(xt_pack_kernel<T>, dim3(f.Lp / 64, n / 64), dim3(256), 0, st, Xb, Xt, s.L, f.Lp, s.d_h);
+        {  // C = Xt Xt^T
+            GemmArgs a{};
+            a.P = GemmOperand{Xt, f.Lp, 0, f.Lp, n};
+            a.Q = a.P;
+            a.n_slabs = f.Lp / E; a.splits = f.gram_splits; a.lower_only = 1; a.tiles_n = tn;
+            a.out_f32 = part; a.out_bf16 = nullptr; a.ldo = n; a.plane = (long long)n * n;
+            if ((e = launch_gemm<T>(a, f.gram_tiles, st)) != hipSuccess) break;
+            const int nb = (n + 63) / 64;
+            hipLaunchKernelGGL(gram_finish_kernel, dim3(nb, nb), dim3(256), 0, st, part, C, n, f.gram_splits, a.plane);
+        }
+        const long long vcount = (long long)r * n;
+        hipLaunchKernelGGL(init_v_kernel, dim3((unsigned)((vcount + 255) / 256)), dim3(256), 0, st, Vt, vcount,
+                           seed + 0x9E37u * (uint32_t)b);
+        for (int it = 0; it < iters; ++it) {
+            GemmArgs a{};  // Wn [n][r] = C Vt^T
+            a.P = GemmOperand{C, n, 0, n, n};
+            a.Q = GemmOperand{Vt, n, 0, n, r};
+            a.n_slabs = n / 32; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
+            a.out_f32 = f.w_splits > 1 ? part : Wn; a.out_bf16 = nullptr; a.ldo = r; a.plane = vcount;
+            if ((e = launch_gemm<float>(a, tn * tr, st)) != hipSuccess) break;
+            if (f.w_splits > 1)
+                hipLaunchKernelGGL(sum_planes_kernel, dim3((unsigned)((vcount + 255) / 256)), dim3(256), 0, st, part, Wn,
+                                   vcount, f.w_splits, vcount);
+            const int gb = (r + 63) / 64;
+            hipLaunchKernelGGL(gram_f64_kernel, dim3(gb * (gb + 1) / 2, f.g_splits), dim3(256), 0, st, Wn, planes, n, r, f.g_splits);
+            hipLaunchKernelGGL(gram_sum_kernel, dim3((unsigned)(((long long)r * r + 255) / 256)), dim3(256), 0, st, planes, Gm,
+                               diag0, r, f.g_splits);
+            for (int c0 = 0; c0 < r; c0 += f.chol_pb) {
+                const int pb = f.chol_pb;
+                const size_t lds = ((size_t)2 * pb * (pb + 1) + pb + (size_t)pb * (r - c0)) * 8;
+                hipLaunchKernelGGL(chol_panel_kernel, dim3((r - c0 + kCholRB - 1) / kCholRB), dim3(256), lds, st, Gm, Lt, diag0,
+                                   r, c0, pb);
+            }
+            hipLaunchKernelGGL(diag_inverse_kernel, dim3(((r + 7) / 8 * 8 + 255) / 256), dim3(256), 0, st, Lt, Minv, r);
+            hipLaunchKernelGGL(orth_solve_kernel, dim3((n + f.solve_rows - 1) / f.solve_rows), dim3(256), solve_lds, st, Wn,
+                               Lt, Minv, Vt, n, r, f.solve_rows);
+        }
+        if (e != hipSuccess) break;
+        T *Bb = reinterpret_cast<T *>(B_out) + (size_t)b * s.G * r * d;
+        T *Ab = reinterpret_cast<T *>(A_out) + (size_t)b * s.L * r;
+        const long long bcount = (long long)s.G * r * d;
+        hipLaunchKernelGGL(write_b_kernel<T>, dim3((unsigned)((bcount + 255) / 256)), dim3(256), 0, st, Vt, Bb, s.G, r, d);
+        {  // A = X_cat B^T
+            GemmArgs a{};
+            a.P = GemmOperand{Xb, s.d_h, (long long)s.L * s.d_h, s.d_h, s.L};
+            a.Q = GemmOperand{Bb, d, (long long)r * d, d, r};
+            a.n_slabs = n / E; a.splits = 1; a.lower_only = 0; a.tiles_n = tr;
+            a.out_f32 = sizeof(T) == 4 ? reinterpret_cast<float *>(Ab) : nullptr;
+            a.out_bf16 = sizeof(T) == 2 ? reinterpret_cast<bf16_t *>(Ab) : nullptr;
+            a.ldo = r; a.plane = 0;
+            e = launch_gemm<T>(a, ((s.L + kGemmTile - 1) / kGemmTile) * tr, st);
+        }
+        if (e == hipSuccess) e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace
+
+bool factorize_shape_ok(const xkv_shape &s, int r)
+{
+    const long long n = (long long)s.G * s.H_kv * s.d_h;
+    return s.d_h % 64 == 0 && r >= 1 && r <= 1024 && r <= n && n <= 16384;
+}
+
+size_t factorize_workspace_bytes(const xkv_shape &s, int r) { return fz_layout(s, r).total; }
+
+hipError_t launch_factorize(const xkv_shape &s, const void *X, int r, int iters, uint32_t seed, void *A_out, void *B_out,
+                            void *ws, hipStream_t st)
+{
+    const FzLayout f = fz_layout(s, r);
+    if (s.dtype == XKV_F32)
+        return factorize_typed<float>(s, f, X, r, iters, seed, A_out, B_out, reinterpret_cast<unsigned char *>(ws), st);
+    return factorize_typed<bf16_t>(s, f, X, r, iters, seed, A_out, B_out, reinterpret_cast<unsigned char *>(ws), st);
+}
+
+}  // namespace xkv

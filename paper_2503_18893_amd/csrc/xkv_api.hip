@@ -280,6 +280,30 @@ xkv_status xkv_reconstruct(const xkv_shape *shape, int32_t layer, const void *A,
     return hip_status(launch_reconstruct(*shape, layer, A, B, r, X_out, (hipStream_t)hip_stream));
 }
 
+xkv_status xkv_factorize_workspace_bytes(const xkv_shape *shape, int32_t r, size_t *bytes)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    if (!bytes || r < 1) return XKV_ERR_INVALID_ARG;
+    if (!factorize_shape_ok(*shape, r)) return XKV_ERR_UNSUPPORTED;
+    *bytes = factorize_workspace_bytes(*shape, r);
+    return XKV_OK;
+}
+
+xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32_t iters, uint32_t seed, void *A_out,
+                         void *B_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    if (!X || !A_out || !B_out || r < 1 || iters < 1) return XKV_ERR_INVALID_ARG;
+    if (!factorize_shape_ok(*shape, r)) return XKV_ERR_UNSUPPORTED;
+    if (shape->batch == 0) return XKV_OK;
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < factorize_workspace_bytes(*shape, r))
+        return XKV_ERR_WORKSPACE;
+    if ((((uintptr_t)X | (uintptr_t)A_out | (uintptr_t)B_out) & 15u) != 0) return XKV_ERR_INVALID_ARG;
+    return hip_status(launch_factorize(*shape, X, r, iters, seed, A_out, B_out, workspace, (hipStream_t)hip_stream));
+}
+
 xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event)
 {
     if (stage < 0 || stage > 2) return XKV_ERR_INVALID_ARG;

@@ -156,5 +156,10 @@ hipError_t launch_combine(const xkv_shape &s, int n_part, const float *part_o, c
 bool dense_uses_mfma(const Plan &p, const void *K, const void *V, const void *q);
 hipError_t launch_reconstruct(const xkv_shape &s, int layer, const void *A, const void *B, int r, void *X,
                               hipStream_t st);
+// Cross-layer factorization of the caches of one group (see factorize.hip).
+bool factorize_shape_ok(const xkv_shape &s, int r);
+size_t factorize_workspace_bytes(const xkv_shape &s, int r);
+hipError_t launch_factorize(const xkv_shape &s, const void *X, int r, int iters, uint32_t seed, void *A_out, void *B_out,
+                            void *ws, hipStream_t st);
 
 }  // namespace xkv

@@ -145,6 +145,29 @@ def make_case(w: Workload, seed: int) -> dict:
     }
 
 
+def make_cache(rng: np.random.Generator, G: int, H_kv: int, d_h: int, L: int, decay: float, rank: int | None = None,
+               dtype: str = "bf16") -> np.ndarray:
+    """One sequence's uncompressed cache of a layer group, X [G][H_kv][L][d_h] in storage form (stands in for
+    the keys or values a model would have written at prefill).
+
+    Read as X_cat [L][n], n = G * H_kv * d_h (column l*H_kv*d_h + g*d_h + j), it is Z diag(i^-decay) Q with Z an
+    L x rank Gaussian and Q rank orthonormal rows of length n: a power-law spectrum shared by the layers of the
+    group, exactly of rank `rank` when rank < n (before rounding to the storage type).
+    """
+    n = G * H_kv * d_h
+    rank = n if rank is None else rank
+    z = rng.standard_normal((L, rank)) * (np.arange(1, rank + 1, dtype=np.float64) ** (-decay))[None, :]
+    x_cat = z @ _orthonormal_rows(rng, rank, n)
+    x = x_cat.reshape(L, G, H_kv, d_h).transpose(1, 2, 0, 3)
+    return to_storage(np.ascontiguousarray(x), dtype)
+
+
+def cache_as_matrix(x: np.ndarray) -> np.ndarray:
+    """X [G][H_kv][L][d_h] (storage form) -> X_cat [L][n] in float64."""
+    G, H_kv, L, d_h = x.shape
+    return np.ascontiguousarray(storage_to_f64(x).transpose(2, 0, 1, 3).reshape(L, G * H_kv * d_h))
+
+
 # ---------------------------------------------------------------- device generator
 def torch_dtype(dtype: str):
     import torch

@@ -21,7 +21,7 @@ def declared_entry_points():
 def test_header_declares_the_expected_calls():
     names = declared_entry_points()
     for must in ("xkv_sr_decode", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score", "xkv_topk", "xkv_gather_attend",
-                 "xkv_workspace_bytes", "xkv_reconstruct"):
+                 "xkv_workspace_bytes", "xkv_reconstruct", "xkv_factorize", "xkv_factorize_workspace_bytes"):
         assert must in names
     assert sorted(xb.ENTRY_POINTS) == names      # the binding wraps exactly what the header declares
 
@@ -76,6 +76,22 @@ def test_calls_reject_null_pointers_before_touching_the_gpu():
                                   1 << 30, null) == xb.XKV_ERR_INVALID_ARG      # negative tail length
     assert lib.xkv_sr_decode_tail(ctypes.byref(c), 0, one, one, one, one, one, null, one, 5, one, null, null, one,
                                   1 << 30, null) == xb.XKV_ERR_INVALID_ARG      # tail tokens without their keys
+
+
+def test_factorize_validates_on_the_host():
+    lib = xb.load()
+    good = xb.Shape.of(synth.LLAMA_GROUP)
+    c, null, one = good.c(), ctypes.c_void_p(0), ctypes.c_void_p(256)
+    assert xb.xkv_factorize_workspace_bytes(good, 512) > good.L * good.G * good.H_kv * good.d_h * 2   # holds a copy of X
+    n = ctypes.c_size_t(0)
+    assert lib.xkv_factorize(ctypes.byref(c), null, 512, 8, 0, one, one, one, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_factorize(ctypes.byref(c), one, 512, 0, 0, one, one, one, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_factorize(ctypes.byref(c), one, 0, 8, 0, one, one, one, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_factorize(ctypes.byref(c), one, 2048, 8, 0, one, one, one, 1 << 40, null) == xb.XKV_ERR_UNSUPPORTED
+    assert lib.xkv_factorize(ctypes.byref(c), one, 512, 8, 0, one, one, one, 1024, null) == xb.XKV_ERR_WORKSPACE
+    assert lib.xkv_factorize_workspace_bytes(ctypes.byref(c), 2048, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED
+    c96 = xb.Shape(G=2, H_kv=2, H_q=2, d_h=96, r_k=8, r_v=8, L=100, k=1, batch=1).c()
+    assert lib.xkv_factorize_workspace_bytes(ctypes.byref(c96), 8, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED
 
 
 def test_binding_has_no_cpu_fallback(monkeypatch):
