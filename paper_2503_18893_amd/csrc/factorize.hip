@@ -50,8 +50,11 @@ __device__ __forceinline__ void fz_lds_barrier()
 //     cb * d_h + j = channel j of column block cb, zero beyond token L.  64 x 64 tiles through LDS.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void xt_pack_kernel(const T *__restrict__ X, T *__restrict__ Xt, int L, int Lp, int d_h)
+__global__ __launch_bounds__(256) void xt_pack_kernel(const T *__restrict__ X, T *__restrict__ Xt, int L, int Lp, int d_h,
+                                                      long long x_seq, long long xt_seq)
 {
+    X += (size_t)blockIdx.z * x_seq;
+    Xt += (size_t)blockIdx.z * xt_seq;
     constexpr int V = 16 / sizeof(T);  // elements per 16 B
     constexpr int PPR = 64 / V;        // 16 B pieces per tile row
     __shared__ __attribute__((aligned(16))) T tile[64][64 + V];
@@ -95,13 +98,14 @@ struct GemmOperand {
     const void *base;
     long long pitch, kblk;  // elements
     int kbw, rows;
+    long long seq;  // elements between the matrices of consecutive sequences (blockIdx.z)
 };
 struct GemmArgs {
     GemmOperand P, Q;
     int n_slabs, splits, lower_only, tiles_n;
     float *out_f32;
     bf16_t *out_bf16;
-    long long ldo, plane;
+    long long ldo, plane, out_seq;
 };
 
 constexpr int kGemmThreads = 512, kGemmTile = 256, kGemmStage = 512 * 128, kGemmLds = 2 * kGemmStage;
@@ -144,7 +148,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
 
     // ---- copy side: wavefronts 0-3 bring in P rows 64 w .. +63 of the tile, wavefronts 4-7 the Q rows
     const bool is_p = w < 4;
-    const void *op_base = is_p ? a.P.base : a.Q.base;
+    const unsigned char *op_base = reinterpret_cast<const unsigned char *>(is_p ? a.P.base : a.Q.base) +
+                                   (size_t)blockIdx.z * (size_t)(is_p ? a.P.seq : a.Q.seq) * sizeof(T);
     const long long op_pitch = is_p ? a.P.pitch : a.Q.pitch, op_kblk = is_p ? a.P.kblk : a.Q.kblk;
     const int op_kbw = is_p ? a.P.kbw : a.Q.kbw, op_rows = is_p ? a.P.rows : a.Q.rows;
     const int origin = (is_p ? tm : tn) * kGemmTile + (w & 3) * 64;
@@ -154,7 +159,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
     for (int j = 0; j < 8; ++j) {
         int R = origin + 8 * j + (lane >> 3);
         R = R < op_rows ? R : op_rows - 1;
-        rowp[j] = reinterpret_cast<const unsigned char *>(op_base) + (size_t)((long long)R * op_pitch) * sizeof(T) + piece * 16;
+        rowp[j] = op_base + (size_t)((long long)R * op_pitch) * sizeof(T) + piece * 16;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(fz_lds_void_t *)fz_smem + (uint32_t)(w * 8 * 1024);
     auto slab_offset = [&](int sb) __attribute__((always_inline)) {
@@ -223,7 +228,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
             for (int v = 0; v < 16; ++v) {
                 const int row = tm * kGemmTile + 64 * wm + 32 * i + 8 * (v / 4) + 4 * h + (v % 4);
                 if (row < a.P.rows && col < a.Q.rows) {
-                    const size_t o = (size_t)row * a.ldo + col;
+                    const size_t o = (size_t)blockIdx.z * a.out_seq + (size_t)row * a.ldo + col;
                     if (a.out_bf16)
                         a.out_bf16[o] = f32_to_bf16(acc[i][j][v]);
                     else
@@ -235,8 +240,10 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
 
 // (2b) C = sum of the split planes of the lower 64 x 64 blocks, mirrored into the upper triangle.
 __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restrict__ part, float *__restrict__ C, int n,
-                                                          int splits, long long plane)
+                                                          int splits, long long plane, long long part_seq)
 {
+    part += (size_t)blockIdx.z * part_seq;
+    C += (size_t)blockIdx.z * n * n;
     const int bm = blockIdx.y, bn = blockIdx.x;
     if (bn > bm) return;
     __shared__ float tile[64][65];
@@ -259,8 +266,10 @@ __global__ __launch_bounds__(256) void gram_finish_kernel(const float *__restric
 
 // (2c) out = sum of `splits` planes of `count` floats.
 __global__ __launch_bounds__(256) void sum_planes_kernel(const float *__restrict__ part, float *__restrict__ out,
-                                                         long long count, int splits, long long plane)
+                                                         long long count, int splits, long long plane, long long part_seq)
 {
+    part += (size_t)blockIdx.z * part_seq;
+    out += (size_t)blockIdx.z * count;
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
     float v = 0.0f;
@@ -271,6 +280,8 @@ __global__ __launch_bounds__(256) void sum_planes_kernel(const float *__restrict
 // (3a) Start block of the iteration: r x n values in (-1, 1) from a counter hash of (seed, index).
 __global__ __launch_bounds__(256) void init_v_kernel(float *__restrict__ Vt, long long count, uint32_t seed)
 {
+    Vt += (size_t)blockIdx.z * count;
+    seed += 0x9E37u * blockIdx.z;
     const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
     uint32_t x = (uint32_t)i * 0x9E3779B9u + seed * 0x85EBCA6Bu + (uint32_t)(i >> 32) * 0xC2B2AE35u + 0x27D4EB2Fu;
@@ -278,66 +289,89 @@ __global__ __launch_bounds__(256) void init_v_kernel(float *__restrict__ Vt, lon
     Vt[i] = ((float)(x >> 8) + 0.5f) * (2.0f / 16777216.0f) - 1.0f;
 }
 
-// (3b) Gram matrix of the r vectors, products and sums in fp64: G[i][j] = sum_n W[n][i] W[n][j].  One workgroup
-// per 64 x 64 block on or below the diagonal and per range of n (one partial plane per range, added up in a
-// fixed order by gram_sum_kernel); 4 x 4 outputs per thread; W is widened to fp64 on its way into LDS.
+// fp64 matrix-core instruction v_mfma_f64_16x16x4_f64: D[16][16] += A[16][4] B[4][16], one double per lane for A
+// (row lane % 16, k = lane / 16) and for B (column lane % 16, k = lane / 16); lane l holds D[l / 16 + 4 v][l % 16]
+// in element v of its four results.
+typedef __attribute__((ext_vector_type(4))) double fz_f64x4_t;
+
+// (3b) Gram matrix of the r vectors, products and sums in fp64: G[i][j] = sum_n W[n][i] W[n][j].  One wavefront
+// per 32 x 32 block on or below the diagonal and per range of n (one partial plane per range, added up in a
+// fixed order by gram_sum_kernel); a step multiplies 4 rows of W, widened to fp64 as they are loaded.
 __global__ __launch_bounds__(256) void gram_f64_kernel(const float *__restrict__ Wn, double *__restrict__ planes, int n,
-                                                       int r, int splits)
+                                                       int r, int splits, int n_pairs)
 {
+    Wn += (size_t)blockIdx.z * n * r;
+    planes += (size_t)blockIdx.z * splits * r * r;
+    const int pair = blockIdx.x * 4 + wave_id();
+    if (pair >= n_pairs) return;
     int bi, bj;
-    fz_lower_pair(blockIdx.x, bi, bj);
-    const int split = blockIdx.y;
+    fz_lower_pair(pair, bi, bj);
+    const int split = blockIdx.y, lane = lane_id(), col = lane & 15, kk = lane >> 4;
     const int n_begin = (int)((long long)n * split / splits), n_end = (int)((long long)n * (split + 1) / splits);
-    __shared__ double wa[32][64], wb[32][64];
-    const int i0 = bi * 64, j0 = bj * 64, ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-    double acc[4][4];
+    fz_f64x4_t acc[2][2];
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
-    for (int n0 = n_begin; n0 < n_end; n0 += 32) {
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < 32 * 64; idx += 256) {
-            const int nn = idx >> 6, ii = idx & 63;
-            const bool ok = n0 + nn < n_end;
-            wa[nn][ii] = (ok && i0 + ii < r) ? (double)Wn[(size_t)(n0 + nn) * r + i0 + ii] : 0.0;
-            wb[nn][ii] = (ok && j0 + ii < r) ? (double)Wn[(size_t)(n0 + nn) * r + j0 + ii] : 0.0;
+        for (int v = 0; v < 2; ++v) acc[u][v] = fz_f64x4_t{0.0, 0.0, 0.0, 0.0};
+    int ci[2], cj[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        ci[u] = bi * 32 + 16 * u + col;
+        cj[u] = bj * 32 + 16 * u + col;
+    }
+    for (int n0 = n_begin; n0 < n_end; n0 += 32) {  // eight steps' worth of loads first, then the 32 products
+        float fa[8][2], fb[8][2];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int row = n0 + 4 * q + kk;
+            const bool ok = row < n_end;
+            const float *wr = Wn + (size_t)(ok ? row : n_begin) * r;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                fa[q][u] = (ok && ci[u] < r) ? wr[ci[u]] : 0.0f;
+                fb[q][u] = (ok && cj[u] < r) ? wr[cj[u]] : 0.0f;
+            }
         }
-        __syncthreads();
-#pragma unroll 4
-        for (int nn = 0; nn < 32; ++nn) {
-            double av[4], bv[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) av[u] = wa[nn][ty + 16 * u];
+        for (int q = 0; q < 8; ++q)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) bv[v] = wb[nn][tx + 16 * v];
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc[u][v] += av[u] * bv[v];
-        }
+                for (int v = 0; v < 2; ++v)
+                    acc[u][v] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)fa[q][u], (double)fb[q][v], acc[u][v], 0, 0, 0);
     }
     double *out = planes + (size_t)split * r * r;
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int i = i0 + ty + 16 * u, j = j0 + tx + 16 * v;
-            if (i < r && j < r) out[(size_t)i * r + j] = acc[u][v];
-        }
+        for (int v = 0; v < 2; ++v)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = bi * 32 + 16 * u + kk + 4 * e, j = bj * 32 + 16 * v + col;
+                if (i < r && j < r) out[(size_t)i * r + j] = acc[u][v][e];
+            }
 }
 
 __global__ __launch_bounds__(256) void gram_sum_kernel(const double *__restrict__ planes, double *__restrict__ G,
                                                        double *__restrict__ diag0, int r, int splits)
 {
+    planes += (size_t)blockIdx.z * splits * r * r;
+    G += (size_t)blockIdx.z * r * r;
+    diag0 += (size_t)blockIdx.z * r;
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)r * r) return;
     const int i = (int)(idx / r), j = (int)(idx % r);
-    if ((j >> 6) > (i >> 6)) return;
+    if ((j >> 5) > (i >> 5)) return;
     double v = 0.0;
     for (int s = 0; s < splits; ++s) v += planes[(size_t)s * r * r + idx];
     G[idx] = v;
     if (i == j) diag0[i] = v;
+}
+
+__device__ __forceinline__ double fz_readlane(double v, int l)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), l), hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+    return __hiloint2double(hi, lo);
 }
 
 // (3c) Cholesky factor Lc of G + shift I, right-looking, one launch per panel of pb columns [c0, c0 + pb).
@@ -356,49 +390,65 @@ constexpr int kCholRB = 32;
 __global__ __launch_bounds__(256) void chol_panel_kernel(double *__restrict__ G, double *__restrict__ Lt,
                                                          const double *__restrict__ diag0, int r, int c0, int pb)
 {
+    G += (size_t)blockIdx.z * r * r;
+    Lt += (size_t)blockIdx.z * r * r;
+    diag0 += (size_t)blockIdx.z * r;
     extern __shared__ __attribute__((aligned(16))) unsigned char fz_smem[];
     const int RP = r - c0, P1 = pb + 1;
-    double *LD = reinterpret_cast<double *>(fz_smem);  // [pb][pb + 1] working copy of the diagonal block
-    double *LS = LD + pb * P1;                          // [pb][pb + 1] its factor
-    double *dinvs = LS + pb * P1;                       // [pb]
+    double *LS = reinterpret_cast<double *>(fz_smem);  // [pb][pb + 1] factor of the diagonal block
+    double *dinvs = LS + pb * P1;                       // [pb] reciprocals of its diagonal
     double *Lp = dinvs + pb;                            // [pb][RP]: Lc[c0 + rr][c0 + c] at c * RP + rr
     __shared__ double red[4];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int pwc = (r - c0) < pb ? (r - c0) : pb;
     const int i0 = c0 + blockIdx.x * kCholRB;
     const int own_end = (i0 + kCholRB) < r ? (i0 + kCholRB) : r;
+    const int nrows = own_end - c0;
 
+    // panel entries of G for this thread's first row below the diagonal block: requested now, used in step 2
+    double g0[32];
+    {
+        const bool pre = tid >= pwc && tid < nrows;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) g0[c] = (pre && c < pwc) ? G[(size_t)(c0 + tid) * r + c0 + c] : 0.0;
+    }
     double mx = 0.0;
     for (int i = tid; i < r; i += 256) mx = fmax(mx, diag0[i]);
     for (int o = 32; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o));
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
-    for (int e = tid; e < pb * pb; e += 256) {
-        const int a = e / pb, b = e % pb;
-        double v = a == b ? 1.0 : 0.0;
-        if (a < pwc && b <= a) v = G[(size_t)(c0 + a) * r + c0 + b];
-        LD[a * P1 + b] = v;
-        LS[a * P1 + b] = 0.0;
-    }
+    if (lane == 0) red[tid >> 6] = mx;
     __syncthreads();
     const double shift = fmax(1e-13 * fmax(fmax(red[0], red[1]), fmax(red[2], red[3])), 1e-300);
-    if (tid < pwc) LD[tid * P1 + tid] += shift;
 
-    // ---- 1. diagonal block; column c of LD stays unscaled while step c reads it, the scaled copy goes to LS
-    for (int c = 0; c < pb; ++c) {
-        __syncthreads();
-        const double dd = LD[c * P1 + c];
-        const double d = sqrt(dd > shift * 1e-3 ? dd : shift * 1e-3), dinv = 1.0 / d;
-        if (tid == 0) dinvs[c] = dinv;
-        for (int e = tid; e < pb * pb; e += 256) {
-            const int a = e / pb, b = e % pb;
-            if (b == c && a >= c) LS[a * P1 + c] = a == c ? d : LD[a * P1 + c] * dinv;
-            if (b > c && a >= b) LD[a * P1 + b] -= (LD[a * P1 + c] * dinv) * (LD[b * P1 + c] * dinv);
+    // ---- 1. diagonal block, by wavefront 0 alone and without LDS traffic: lane a keeps row a in registers, the
+    // entries of the pivot column are passed around with readlane.  Rows beyond the panel are identity rows.
+    if (wave_id() == 0) {
+        const int a = lane & 31;
+        double x[32];
+#pragma unroll
+        for (int b2 = 0; b2 < 32; ++b2) {
+            double v = a == b2 ? 1.0 : 0.0;
+            if (a < pwc && b2 <= a) v = G[(size_t)(c0 + a) * r + c0 + b2] + (a == b2 ? shift : 0.0);
+            x[b2] = v;
+        }
+#pragma unroll
+        for (int c = 0; c < 32; ++c) {
+            const double piv = fz_readlane(x[c], c);
+            const double dinv = rsqrt(piv > shift * 1e-3 ? piv : shift * 1e-3);
+            const double l = x[c] * dinv;  // lane a > c: Lc[a][c]; lane c: the square root of the pivot
+            x[c] = l;
+            if (lane == 0 && c < pb) dinvs[c] = dinv;
+#pragma unroll
+            for (int b2 = c + 1; b2 < 32; ++b2) x[b2] -= l * fz_readlane(l, b2);
+        }
+        if (lane < pb) {
+#pragma unroll
+            for (int c = 0; c < 32; ++c)
+                if (c < pb) LS[lane * P1 + c] = c <= lane ? x[c] : 0.0;
         }
     }
     __syncthreads();
 
     // ---- 2. panel entries of the rows c0 .. own_end - 1
-    const int nrows = own_end - c0;
     for (int rr = tid; rr < nrows; rr += 256) {
         const int row = c0 + rr;
         double x[32];
@@ -410,7 +460,7 @@ __global__ __launch_bounds__(256) void chol_panel_kernel(double *__restrict__ G,
             for (int c = 0; c < 32; ++c) {
                 double v = 0.0;
                 if (c < pwc) {
-                    v = G[(size_t)row * r + c0 + c];
+                    v = rr == tid ? g0[c] : G[(size_t)row * r + c0 + c];
 #pragma unroll
                     for (int c2 = 0; c2 < c; ++c2) v -= x[c2] * LS[c * P1 + c2];
                     v *= dinvs[c];
@@ -449,113 +499,99 @@ __global__ __launch_bounds__(256) void chol_panel_kernel(double *__restrict__ G,
     }
 }
 
-// (3c') Inverses of the 8 x 8 diagonal blocks of Lc: Minv[b][ii][jj] = (Lc_bb^-1)[ii][jj] (rows beyond r: identity).
+// (3c') Inverses of the 16 x 16 diagonal blocks of Lc: Minv[b][ii][jj] = (Lc_bb^-1)[ii][jj] (rows beyond r: identity).
+constexpr int kSolveIB = 16;
 __global__ __launch_bounds__(256) void diag_inverse_kernel(const double *__restrict__ Lt, double *__restrict__ Minv, int r)
 {
-    const int t = blockIdx.x * 256 + threadIdx.x, b = t >> 3, jj = t & 7;
-    if (b * 8 >= r) return;
-    double x[8];
+    Lt += (size_t)blockIdx.z * r * r;
+    Minv += (size_t)blockIdx.z * ((r + kSolveIB - 1) / kSolveIB) * (kSolveIB * kSolveIB);
+    const int t = blockIdx.x * 256 + threadIdx.x, b = t / kSolveIB, jj = t % kSolveIB;
+    if (b * kSolveIB >= r) return;
+    double x[kSolveIB];
 #pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
+    for (int ii = 0; ii < kSolveIB; ++ii) {
         double v = ii == jj ? 1.0 : 0.0;
-        const int row = b * 8 + ii;
+        const int row = b * kSolveIB + ii;
         if (ii > jj && row < r) {
 #pragma unroll
             for (int k = 0; k < ii; ++k)
-                if (k >= jj) v -= Lt[(size_t)(b * 8 + k) * r + row] * x[k];
+                if (k >= jj) v -= Lt[(size_t)(b * kSolveIB + k) * r + row] * x[k];
         }
         if (ii >= jj && row < r) v /= Lt[(size_t)row * r + row];
         x[ii] = ii >= jj ? v : 0.0;
     }
 #pragma unroll
-    for (int ii = 0; ii < 8; ++ii) Minv[(size_t)b * 64 + ii * 8 + jj] = x[ii];
+    for (int ii = 0; ii < kSolveIB; ++ii) Minv[(size_t)b * (kSolveIB * kSolveIB) + ii * kSolveIB + jj] = x[ii];
 }
 
-// (3d) V = Lc^-1 W by blocked forward substitution: rows of W^T (Wn [n][r]) are independent, a workgroup takes
-// `rows` of them into LDS in fp64 (column-major, so that the lanes of a wavefront sit on consecutive rows) and
-// goes through the columns eight at a time: the eight values of a row are multiplied by the inverse of the
-// 8 x 8 diagonal block, then their multiples of the eight columns of Lc are subtracted from all later columns.
-// The rows of Lt are staged through LDS, the next eight being loaded while the current ones are used.  The
-// result is written transposed as Vt [r][n] in fp32.
-constexpr int kSolveIB = 8;
-__device__ __forceinline__ void fz_fetch_lt(double (&pre)[32], const double *__restrict__ Lt, int i0, int r, int per, int tid)
-{
-#pragma unroll
-    for (int u = 0; u < 32; ++u) {
-        const int idx = tid + 256 * u, row = i0 + idx / r;
-        pre[u] = (u < per && idx < kSolveIB * r && row < r) ? Lt[(size_t)row * r + idx % r] : 0.0;
-    }
-}
-
+// (3d) V = Lc^-1 W by blocked forward substitution on the fp64 matrix cores.  Rows of W^T (Wn [n][r]) are
+// independent; a workgroup of 4 wavefronts takes 16 of them and keeps them in registers as 16 x 16 accumulator
+// tiles (tile t = columns 16 t .. 16 t + 15, owned by wavefront t % 4).  For tile I in turn: its owner hands the
+// 16 x 16 values to LDS, 256 threads multiply them by the inverse of the diagonal block (one output each: the
+// final rows 16 I .. 16 I + 15 of V for these 16 n, written out as fp32), and every wavefront subtracts
+// V_I Lc[16 t .., 16 I ..]^T from its tiles t > I (four matrix-core steps per tile; the Lc operands come straight
+// from global memory and are requested before the block inverse is applied, which hides their latency).
+template <int MAXT>  // tiles per wavefront: r <= 64 * MAXT
 __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict__ Wn, const double *__restrict__ Lt,
-                                                         const double *__restrict__ Minv, float *__restrict__ Vt, int n, int r,
-                                                         int rows)
+                                                         const double *__restrict__ Minv, float *__restrict__ Vt, int n, int r)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char fz_smem[];
-    double *wv = reinterpret_cast<double *>(fz_smem);  // [r][rows]
-    double *lrow = wv + (size_t)r * rows;              // [kSolveIB][r]
-    __shared__ double minv_s[64];
-    const int tid = threadIdx.x, n0 = blockIdx.x * rows;
-    for (int idx = tid; idx < rows * r; idx += 256) {
-        const int rr = idx / r, i = idx % r;
-        wv[(size_t)i * rows + rr] = (n0 + rr < n) ? (double)Wn[(size_t)(n0 + rr) * r + i] : 0.0;
-    }
-    const int per = (kSolveIB * r + 255) / 256;  // staged values per thread (<= 32 for r <= 1024)
-    double pre[32];
-    fz_fetch_lt(pre, Lt, 0, r, per, tid);
-    double mpre = tid < 64 ? Minv[tid] : 0.0;
-    const int rr = tid % rows, part = tid / rows, P = 256 / rows;
-    const int s_ii = tid / rows, s_ok = tid < kSolveIB * rows;  // role in the in-block step
-    for (int i0 = 0; i0 < r; i0 += kSolveIB) {
-        __syncthreads();  // the previous block's update is complete; lrow and minv_s are free
+    Wn += (size_t)blockIdx.z * n * r;
+    Lt += (size_t)blockIdx.z * r * r;
+    Minv += (size_t)blockIdx.z * ((r + 15) / 16) * 256;
+    Vt += (size_t)blockIdx.z * n * r;
+    __shared__ double wt[16][17], vblk[16][17], minv_s[16][17];
+    const int tid = threadIdx.x, lane = tid & 63, w = wave_id(), col = lane & 15, kk = lane >> 4;
+    const int n0 = blockIdx.x * 16, n_tiles = (r + 15) / 16;
+    fz_f64x4_t acc[MAXT];
 #pragma unroll
-        for (int u = 0; u < 32; ++u) {
-            const int idx = tid + 256 * u;
-            if (u < per && idx < kSolveIB * r) lrow[idx] = pre[u];
+    for (int u = 0; u < MAXT; ++u) {
+        const int c = 16 * (w + 4 * u) + col;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int row = n0 + kk + 4 * e;
+            acc[u][e] = (c < r && row < n) ? (double)Wn[(size_t)row * r + c] : 0.0;
         }
-        if (tid < 64) minv_s[tid] = mpre;
-        if (i0 + kSolveIB < r) {
-            fz_fetch_lt(pre, Lt, i0 + kSolveIB, r, per, tid);
-            mpre = tid < 64 ? Minv[(size_t)(i0 / kSolveIB + 1) * 64 + tid] : 0.0;
+    }
+    const int s_row = tid >> 4, s_ii = tid & 15;  // role when the block inverse is applied: output (row, ii)
+    for (int I = 0; I < n_tiles; ++I) {
+        // operands of the update for this wavefront's tiles behind I: Lc[16 t + col][16 I + 4 g + kk]
+        double bop[MAXT][4];
+#pragma unroll
+        for (int u = 0; u < MAXT; ++u) {
+            const int t = w + 4 * u, c = 16 * t + col;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int lrow = 16 * I + 4 * g + kk;
+                bop[u][g] = (t > I && c < r && lrow < r) ? Lt[(size_t)lrow * r + c] : 0.0;
+            }
         }
+        const double mi = Minv[(size_t)I * 256 + tid];
+        if ((I & 3) == w) {
+#pragma unroll
+            for (int u = 0; u < MAXT; ++u)
+                if (u == (I >> 2)) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) wt[kk + 4 * e][col] = acc[u][e];
+                }
+        }
+        minv_s[tid >> 4][tid & 15] = mi;
         __syncthreads();
         double v = 0.0;
-        if (s_ok) {
 #pragma unroll
-            for (int jj = 0; jj < kSolveIB; ++jj)
-                if (jj <= s_ii && i0 + jj < r) v += minv_s[s_ii * 8 + jj] * wv[(size_t)(i0 + jj) * rows + rr];
-        }
+        for (int jj = 0; jj < 16; ++jj) v += minv_s[s_ii][jj] * wt[s_row][jj];  // entries jj > ii of the inverse are zero
+        vblk[s_row][s_ii] = v;
+        if (16 * I + s_ii < r && n0 + s_row < n) Vt[(size_t)(16 * I + s_ii) * n + n0 + s_row] = (float)v;
         __syncthreads();
-        if (s_ok && i0 + s_ii < r) wv[(size_t)(i0 + s_ii) * rows + rr] = v;
-        __syncthreads();
-        double vb[kSolveIB];
+        double aop[4];
 #pragma unroll
-        for (int ii = 0; ii < kSolveIB; ++ii) vb[ii] = (i0 + ii < r) ? wv[(size_t)(i0 + ii) * rows + rr] : 0.0;
-        for (int k = i0 + kSolveIB + part; k < r; k += 4 * P) {
-            double w4[4];
+        for (int g = 0; g < 4; ++g) aop[g] = -vblk[col][4 * g + kk];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int kk = k + u * P;
-                w4[u] = kk < r ? wv[(size_t)kk * rows + rr] : 0.0;
-            }
+        for (int u = 0; u < MAXT; ++u) {
+            if (w + 4 * u > I && w + 4 * u < n_tiles) {
 #pragma unroll
-            for (int ii = 0; ii < kSolveIB; ++ii)
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int kk = k + u * P;
-                    w4[u] -= (kk < r ? lrow[(size_t)ii * r + kk] : 0.0) * vb[ii];
-                }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int kk = k + u * P;
-                if (kk < r) wv[(size_t)kk * rows + rr] = w4[u];
+                for (int g = 0; g < 4; ++g) acc[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(aop[g], bop[u][g], acc[u], 0, 0, 0);
             }
         }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < rows * r; idx += 256) {
-        const int i = idx / rows, r2 = idx % rows;
-        if (n0 + r2 < n) Vt[(size_t)i * n + n0 + r2] = (float)wv[(size_t)i * rows + r2];
     }
 }
 
@@ -563,6 +599,8 @@ __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict
 template <typename T>
 __global__ __launch_bounds__(256) void write_b_kernel(const float *__restrict__ Vt, T *__restrict__ B, int G, int r, int d)
 {
+    Vt += (size_t)blockIdx.z * G * d * r;
+    B += (size_t)blockIdx.z * G * r * d;
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)G * r * d) return;
     const int c = (int)(idx % d), i = (int)((idx / d) % r), l = (int)(idx / ((long long)d * r));
@@ -570,11 +608,15 @@ __global__ __launch_bounds__(256) void write_b_kernel(const float *__restrict__ 
 }
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-inline int pow2_floor(int x) { int p = 1; while (2 * p <= x) p *= 2; return p; }
+
+// Sequences are processed `bc` at a time (grid dimension z of every kernel), which is what keeps the many small
+// launches of the orthonormalisation busy; the workspace holds the intermediates of one such chunk.
+constexpr int kFzChunk = 16;
 
 struct FzLayout {
-    int n, Lp, gram_tiles, gram_splits, w_splits, g_splits, chol_pb, solve_rows;
-    size_t esz, off_xt, off_part, off_c, off_vt, off_wn, off_g, off_lt, off_planes, off_diag, off_minv, total;
+    int n, Lp, bc, gram_tiles, gram_splits, w_splits, g_splits, chol_pb;
+    size_t esz, xt_seq, part_seq, off_xt, off_part, off_c, off_vt, off_wn, off_g, off_lt, off_planes, off_diag, off_minv,
+        total;
 };
 
 FzLayout fz_layout(const xkv_shape &s, int r)
@@ -583,32 +625,38 @@ FzLayout fz_layout(const xkv_shape &s, int r)
     f.esz = s.dtype == XKV_F32 ? 4 : 2;
     f.n = s.G * s.H_kv * s.d_h;
     f.Lp = (s.L + 63) / 64 * 64;
+    f.bc = std::max(1, std::min(s.batch, kFzChunk));
     const int t = (f.n + kGemmTile - 1) / kGemmTile;
     f.gram_tiles = t * (t + 1) / 2;
     const int slab = 128 / (int)f.esz, gram_slabs = f.Lp / slab;
-    f.gram_splits = std::max(1, std::min(std::min(16, gram_slabs), (512 + f.gram_tiles - 1) / f.gram_tiles));
-    const int w_tiles = t * ((r + kGemmTile - 1) / kGemmTile);
-    f.w_splits = std::max(1, std::min(std::min(16, f.n / 32), (256 + w_tiles - 1) / w_tiles));
-    const int gb = (r + 63) / 64;
-    f.g_splits = std::max(1, std::min(std::min(16, f.n / 32), (256 + gb * (gb + 1) / 2 - 1) / (gb * (gb + 1) / 2)));
+    auto splits_for = [&](int wgs_per_seq, int target, int most) {  // enough workgroups to fill the chip twice over
+        const int wgs = wgs_per_seq * f.bc;
+        return std::max(1, std::min(std::min(16, most), (target + wgs - 1) / wgs));
+    };
+    f.gram_splits = splits_for(f.gram_tiles, 512, gram_slabs);
+    f.w_splits = splits_for(t * ((r + kGemmTile - 1) / kGemmTile), 256, f.n / 32);
+    const int gb = (r + 31) / 32;
+    f.g_splits = splits_for((gb * (gb + 1) / 2 + 3) / 4, 1024, f.n / 64);
     f.chol_pb = r <= 512 ? 32 : 16;
-    f.solve_rows = std::max(1, std::min(32, pow2_floor(8192 / r)));
+    f.xt_seq = (size_t)f.n * f.Lp;
+    f.part_seq = std::max((size_t)f.gram_splits * f.n * f.n, (size_t)f.w_splits * f.n * r);
+    const size_t bc = (size_t)f.bc;
     size_t o = 0;
-    f.off_xt = o;   o += align256((size_t)f.n * f.Lp * f.esz);
-    f.off_part = o; o += align256(std::max((size_t)f.gram_splits * f.n * f.n, (size_t)f.w_splits * f.n * r) * 4);
-    f.off_c = o;    o += align256((size_t)f.n * f.n * 4);
-    f.off_vt = o;   o += align256((size_t)r * f.n * 4);
-    f.off_wn = o;   o += align256((size_t)f.n * r * 4);
-    f.off_g = o;    o += align256((size_t)r * r * 8);
-    f.off_lt = o;   o += align256((size_t)r * r * 8);
-    f.off_planes = o; o += align256((size_t)f.g_splits * r * r * 8);
-    f.off_diag = o; o += align256((size_t)r * 8);
-    f.off_minv = o; o += align256((size_t)((r + 7) / 8) * 64 * 8);
+    f.off_xt = o;     o += align256(bc * f.xt_seq * f.esz);
+    f.off_part = o;   o += align256(bc * f.part_seq * 4);
+    f.off_c = o;      o += align256(bc * f.n * f.n * 4);
+    f.off_vt = o;     o += align256(bc * r * f.n * 4);
+    f.off_wn = o;     o += align256(bc * f.n * r * 4);
+    f.off_g = o;      o += align256(bc * r * r * 8);
+    f.off_lt = o;     o += align256(bc * r * r * 8);
+    f.off_planes = o; o += align256(bc * f.g_splits * r * r * 8);
+    f.off_diag = o;   o += align256(bc * r * 8);
+    f.off_minv = o;   o += align256(bc * ((r + 15) / 16) * 256 * 8);
     f.total = o;
     return f;
 }
 
-template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, hipStream_t st)
+template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, int nseq, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
@@ -616,9 +664,11 @@ template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, hipSt
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemm_nt_kernel<T>, dim3(tiles, a.splits), dim3(kGemmThreads), kGemmLds, st, a);
+    hipLaunchKernelGGL(gemm_nt_kernel<T>, dim3(tiles, a.splits, nseq), dim3(kGemmThreads), kGemmLds, st, a);
     return hipGetLastError();
 }
+
+inline unsigned blocks256(long long count) { return (unsigned)((count + 255) / 256); }
 
 template <typename T>
 hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X, int r, int iters, uint32_t seed,
@@ -632,70 +682,74 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
     double *Gm = reinterpret_cast<double *>(ws + f.off_g), *Lt = reinterpret_cast<double *>(ws + f.off_lt);
     double *planes = reinterpret_cast<double *>(ws + f.off_planes), *diag0 = reinterpret_cast<double *>(ws + f.off_diag);
     double *Minv = reinterpret_cast<double *>(ws + f.off_minv);
-    const size_t solve_lds = ((size_t)r * f.solve_rows + (size_t)kSolveIB * r) * 8;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)chol_panel_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)orth_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     hipError_t e = hipSuccess;
-    for (int b = 0; b < s.batch && e == hipSuccess; ++b) {
-        const T *Xb = reinterpret_cast<const T *>(X) + (size_t)b * n * s.L;
-        hipLaunchKernelGGL(xt_pack_kernel<T>, dim3(f.Lp / 64, n / 64), dim3(256), 0, st, Xb, Xt, s.L, f.Lp, s.d_h);
+    const long long vcount = (long long)r * n, x_seq = (long long)n * s.L;
+    for (int b0 = 0; b0 < s.batch && e == hipSuccess; b0 += f.bc) {
+        const int nb = std::min(f.bc, s.batch - b0);  // sequences of this chunk
+        const T *Xb = reinterpret_cast<const T *>(X) + (size_t)b0 * x_seq;
+        hipLaunchKernelGGL(xt_pack_kernel<T>, dim3(f.Lp / 64, n / 64, nb), dim3(256), 0, st, Xb, Xt, s.L, f.Lp, s.d_h, x_seq,
+                           (long long)f.xt_seq);
         {  // C = Xt Xt^T
             GemmArgs a{};
-            a.P = GemmOperand{Xt, f.Lp, 0, f.Lp, n};
+            a.P = GemmOperand{Xt, f.Lp, 0, f.Lp, n, (long long)f.xt_seq};
             a.Q = a.P;
             a.n_slabs = f.Lp / E; a.splits = f.gram_splits; a.lower_only = 1; a.tiles_n = tn;
-            a.out_f32 = part; a.out_bf16 = nullptr; a.ldo = n; a.plane = (long long)n * n;
-            if ((e = launch_gemm<T>(a, f.gram_tiles, st)) != hipSuccess) break;
-            const int nb = (n + 63) / 64;
-            hipLaunchKernelGGL(gram_finish_kernel, dim3(nb, nb), dim3(256), 0, st, part, C, n, f.gram_splits, a.plane);
+            a.out_f32 = part; a.out_bf16 = nullptr; a.ldo = n; a.plane = (long long)n * n; a.out_seq = (long long)f.part_seq;
+            if ((e = launch_gemm<T>(a, f.gram_tiles, nb, st)) != hipSuccess) break;
+            const int n64 = (n + 63) / 64;
+            hipLaunchKernelGGL(gram_finish_kernel, dim3(n64, n64, nb), dim3(256), 0, st, part, C, n, f.gram_splits, a.plane,
+                               (long long)f.part_seq);
         }
-        const long long vcount = (long long)r * n;
-        hipLaunchKernelGGL(init_v_kernel, dim3((unsigned)((vcount + 255) / 256)), dim3(256), 0, st, Vt, vcount,
-                           seed + 0x9E37u * (uint32_t)b);
+        hipLaunchKernelGGL(init_v_kernel, dim3(blocks256(vcount), 1, nb), dim3(256), 0, st, Vt, vcount,
+                           seed + 0x9E37u * (uint32_t)b0);
         for (int it = 0; it < iters; ++it) {
             GemmArgs a{};  // Wn [n][r] = C Vt^T
-            a.P = GemmOperand{C, n, 0, n, n};
-            a.Q = GemmOperand{Vt, n, 0, n, r};
+            a.P = GemmOperand{C, n, 0, n, n, (long long)n * n};
+            a.Q = GemmOperand{Vt, n, 0, n, r, vcount};
             a.n_slabs = n / 32; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
             a.out_f32 = f.w_splits > 1 ? part : Wn; a.out_bf16 = nullptr; a.ldo = r; a.plane = vcount;
-            if ((e = launch_gemm<float>(a, tn * tr, st)) != hipSuccess) break;
+            a.out_seq = f.w_splits > 1 ? (long long)f.part_seq : vcount;
+            if ((e = launch_gemm<float>(a, tn * tr, nb, st)) != hipSuccess) break;
             if (f.w_splits > 1)
-                hipLaunchKernelGGL(sum_planes_kernel, dim3((unsigned)((vcount + 255) / 256)), dim3(256), 0, st, part, Wn,
-                                   vcount, f.w_splits, vcount);
-            const int gb = (r + 63) / 64;
-            hipLaunchKernelGGL(gram_f64_kernel, dim3(gb * (gb + 1) / 2, f.g_splits), dim3(256), 0, st, Wn, planes, n, r, f.g_splits);
-            hipLaunchKernelGGL(gram_sum_kernel, dim3((unsigned)(((long long)r * r + 255) / 256)), dim3(256), 0, st, planes, Gm,
-                               diag0, r, f.g_splits);
+                hipLaunchKernelGGL(sum_planes_kernel, dim3(blocks256(vcount), 1, nb), dim3(256), 0, st, part, Wn, vcount,
+                                   f.w_splits, vcount, (long long)f.part_seq);
+            const int gb = (r + 31) / 32, pairs = gb * (gb + 1) / 2;
+            hipLaunchKernelGGL(gram_f64_kernel, dim3((pairs + 3) / 4, f.g_splits, nb), dim3(256), 0, st, Wn, planes, n, r,
+                               f.g_splits, pairs);
+            hipLaunchKernelGGL(gram_sum_kernel, dim3(blocks256((long long)r * r), 1, nb), dim3(256), 0, st, planes, Gm, diag0, r,
+                               f.g_splits);
             for (int c0 = 0; c0 < r; c0 += f.chol_pb) {
                 const int pb = f.chol_pb;
-                const size_t lds = ((size_t)2 * pb * (pb + 1) + pb + (size_t)pb * (r - c0)) * 8;
-                hipLaunchKernelGGL(chol_panel_kernel, dim3((r - c0 + kCholRB - 1) / kCholRB), dim3(256), lds, st, Gm, Lt, diag0,
-                                   r, c0, pb);
+                const size_t lds = ((size_t)pb * (pb + 1) + pb + (size_t)pb * (r - c0)) * 8;
+                hipLaunchKernelGGL(chol_panel_kernel, dim3((r - c0 + kCholRB - 1) / kCholRB, 1, nb), dim3(256), lds, st, Gm, Lt,
+                                   diag0, r, c0, pb);
             }
-            hipLaunchKernelGGL(diag_inverse_kernel, dim3(((r + 7) / 8 * 8 + 255) / 256), dim3(256), 0, st, Lt, Minv, r);
-            hipLaunchKernelGGL(orth_solve_kernel, dim3((n + f.solve_rows - 1) / f.solve_rows), dim3(256), solve_lds, st, Wn,
-                               Lt, Minv, Vt, n, r, f.solve_rows);
+            hipLaunchKernelGGL(diag_inverse_kernel, dim3(blocks256((r + 15) / 16 * 16), 1, nb), dim3(256), 0, st, Lt, Minv, r);
+            if (r <= 512)
+                hipLaunchKernelGGL(orth_solve_kernel<8>, dim3((n + 15) / 16, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
+            else
+                hipLaunchKernelGGL(orth_solve_kernel<16>, dim3((n + 15) / 16, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
         }
         if (e != hipSuccess) break;
-        T *Bb = reinterpret_cast<T *>(B_out) + (size_t)b * s.G * r * d;
-        T *Ab = reinterpret_cast<T *>(A_out) + (size_t)b * s.L * r;
+        T *Bb = reinterpret_cast<T *>(B_out) + (size_t)b0 * s.G * r * d;
+        T *Ab = reinterpret_cast<T *>(A_out) + (size_t)b0 * s.L * r;
         const long long bcount = (long long)s.G * r * d;
-        hipLaunchKernelGGL(write_b_kernel<T>, dim3((unsigned)((bcount + 255) / 256)), dim3(256), 0, st, Vt, Bb, s.G, r, d);
+        hipLaunchKernelGGL(write_b_kernel<T>, dim3(blocks256(bcount), 1, nb), dim3(256), 0, st, Vt, Bb, s.G, r, d);
         {  // A = X_cat B^T
             GemmArgs a{};
-            a.P = GemmOperand{Xb, s.d_h, (long long)s.L * s.d_h, s.d_h, s.L};
-            a.Q = GemmOperand{Bb, d, (long long)r * d, d, r};
+            a.P = GemmOperand{Xb, s.d_h, (long long)s.L * s.d_h, s.d_h, s.L, x_seq};
+            a.Q = GemmOperand{Bb, d, (long long)r * d, d, r, bcount};
             a.n_slabs = n / E; a.splits = 1; a.lower_only = 0; a.tiles_n = tr;
             a.out_f32 = sizeof(T) == 4 ? reinterpret_cast<float *>(Ab) : nullptr;
             a.out_bf16 = sizeof(T) == 2 ? reinterpret_cast<bf16_t *>(Ab) : nullptr;
-            a.ldo = r; a.plane = 0;
-            e = launch_gemm<T>(a, ((s.L + kGemmTile - 1) / kGemmTile) * tr, st);
+            a.ldo = r; a.plane = 0; a.out_seq = (long long)s.L * r;
+            e = launch_gemm<T>(a, ((s.L + kGemmTile - 1) / kGemmTile) * tr, nb, st);
         }
         if (e == hipSuccess) e = hipGetLastError();
     }
