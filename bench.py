@@ -38,6 +38,7 @@ def parse_args():
     ap.add_argument("--groups", type=int, default=None, help="override the number of layer groups held in HBM")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-factorize", action="store_true", help="skip the timing of the prefill-side factorization")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise 1 GiB copy kernel three times (reference point for hardware counters)")
@@ -269,6 +270,58 @@ def main():
                                                        "the factors (A B_l), then dense attention"}
         del Ks, Vs
 
+    # ---------------------------------------------------------------- the step before the path: factorization
+    # One layer group's key cache of every sequence (power-law spectrum, full rank) -> A^K, B^K (Eq. 1), as prefill
+    # would do once per prompt and group, for keys and for values.  Not part of the decode step or of `value`.
+    factorize = None
+    n_cat = w.G * w.d
+    if not args.no_factorize and w.dtype == "bf16" and w.d_h % 64 == 0 and w.r_k <= min(1024, n_cat):
+        iters_f = 8
+        try:
+            fz_bytes = xb.xkv_factorize_workspace_bytes(shape, w.r_k)
+            gen = torch.Generator(device="cuda").manual_seed(args.seed + 17)
+            spec = torch.arange(1, n_cat + 1, device="cuda", dtype=torch.float32) ** -0.7
+            mix = torch.linalg.qr(torch.randn((n_cat, n_cat), device="cuda", generator=gen))[0]
+            Xc = torch.empty((w.batch, w.G, w.H_kv, w.L, w.d_h), dtype=dt, device="cuda")
+            for b in range(w.batch):
+                z = torch.randn((w.L, n_cat), device="cuda", generator=gen) * spec
+                Xc[b] = (z @ mix.T).view(w.L, w.G, w.H_kv, w.d_h).permute(1, 2, 0, 3).to(dt)
+                del z
+            fz_ws = torch.empty(fz_bytes, dtype=torch.uint8, device="cuda")
+            A_f = torch.empty((w.batch, w.L, w.r_k), dtype=dt, device="cuda")
+            B_f = torch.empty((w.batch, w.G, w.r_k, w.d), dtype=dt, device="cuda")
+
+            def fz_call():
+                xb.xkv_factorize(shape, Xc, w.r_k, iters_f, args.seed, A_f, B_f, fz_ws)
+
+            fz_call()
+            ms_fz = time_loop(torch, fz_call, 2)
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            ev1.record()
+            torch.cuda.synchronize()
+            xb.xkv_profile_kernel(xb.STAGE_FACTORIZE_GRAM, ev0.cuda_event, ev1.cuda_event)
+            fz_call()                    # with more than 16 sequences the events keep the last chunk's launch
+            torch.cuda.synchronize()
+            ms_gram = ev0.elapsed_time(ev1)
+            xb.xkv_profile_kernel(xb.STAGE_FACTORIZE_GRAM, None, None)
+            chunk = w.batch % 16 or min(w.batch, 16)     # sequences in the last launch (16 per launch)
+            tiles = -(-n_cat // 256)
+            gram_flops = chunk * (tiles * (tiles + 1) // 2) * 256 * 256 * 2 * w.L   # tiles on or below the diagonal
+            captured = float((A_f[0].float() ** 2).sum() / (Xc[0].float() ** 2).sum())
+            factorize = {"ms_per_call": round(ms_fz, 3), "sequences": w.batch, "iters": iters_f, "r": w.r_k, "n": n_cat,
+                         "ms_per_sequence_and_group": round(ms_fz / w.batch, 3),
+                         "gram_kernel": {"ms_per_launch": round(ms_gram, 4), "sequences_per_launch": chunk,
+                                         "bound": "mfma", "achieved": round(gram_flops / (ms_gram * 1e-3) / 1e12, 1),
+                                         "peak": 2500.0, "unit": "TFLOP/s",
+                                         "frac": round(gram_flops / (ms_gram * 1e-3) / 2.5e15, 4)},
+                         "energy_captured_seq0": round(captured, 5),
+                         "note": "xkv_factorize on one group's key cache (synthetic, singular values ~ i^-0.7); "
+                                 "prefill-side, outside the timed decode step"}
+            del Xc, fz_ws, A_f, B_f
+        except xb.XkvError as err:
+            factorize = {"skipped": str(err)}
+
     # ---------------------------------------------------------------- CPU oracle on a bounded sample
     cpu = None
     parity = None
@@ -312,7 +365,7 @@ def main():
                    "factor_sets_in_hbm": n_sets, "copies_rotated": copies},
         "roofline": roofline, "cpu_baseline": cpu, "stages": stages, "dense_baseline": dense,
         "speedup_vs_dense": (round(dense["ms_per_step"] / ms_sr, 3) if dense else None),
-        "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
+        "factorize": factorize, "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
     }
     print(json.dumps(result))
 

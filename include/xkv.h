@@ -158,7 +158,8 @@ XKV_API xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t 
 
 /* Measurement aid for callers that want the duration of one kernel rather than of a whole call.
  * Not part of the method.  For stage = 0 (low-rank score kernel), 1 (gather-reconstruct + sparse
- * attention kernel) or 2 (dense decode kernel), every later call that launches that kernel records
+ * attention kernel), 2 (dense decode kernel) or 3 (the Gram-matrix product X_cat^T X_cat of xkv_factorize, all
+ * sequences of a chunk in one launch), every later call that launches that kernel records
  * start_event on the call's stream right before the launch and stop_event right after it.  Both are
  * hipEvent_t created by the caller with timing enabled (HOST handles, passed as void*); NULL for
  * either switches the recording off.  Process-wide state; not thread safe. */

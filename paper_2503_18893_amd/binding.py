@@ -183,7 +183,7 @@ def xkv_factorize(shape, X, r, iters, seed, A_out, B_out, workspace, stream=None
            "xkv_factorize")
 
 
-STAGE_SCORE, STAGE_GATHER_ATTEND, STAGE_DENSE = 0, 1, 2
+STAGE_SCORE, STAGE_GATHER_ATTEND, STAGE_DENSE, STAGE_FACTORIZE_GRAM = 0, 1, 2, 3
 
 
 def xkv_profile_kernel(stage, start_event=None, stop_event=None):

@@ -701,7 +701,10 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
             a.Q = a.P;
             a.n_slabs = f.Lp / E; a.splits = f.gram_splits; a.lower_only = 1; a.tiles_n = tn;
             a.out_f32 = part; a.out_bf16 = nullptr; a.ldo = n; a.plane = (long long)n * n; a.out_seq = (long long)f.part_seq;
-            if ((e = launch_gemm<T>(a, f.gram_tiles, nb, st)) != hipSuccess) break;
+            profile_begin(3, st);
+            e = launch_gemm<T>(a, f.gram_tiles, nb, st);
+            profile_end(3, st);
+            if (e != hipSuccess) break;
             const int n64 = (n + 63) / 64;
             hipLaunchKernelGGL(gram_finish_kernel, dim3(n64, n64, nb), dim3(256), 0, st, part, C, n, f.gram_splits, a.plane,
                                (long long)f.part_seq);

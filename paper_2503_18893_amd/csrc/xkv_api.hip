@@ -7,7 +7,7 @@
 
 namespace xkv {
 
-ProfileEvents g_profile[3] = {};
+ProfileEvents g_profile[4] = {};
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -306,7 +306,7 @@ xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32
 
 xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event)
 {
-    if (stage < 0 || stage > 2) return XKV_ERR_INVALID_ARG;
+    if (stage < 0 || stage > 3) return XKV_ERR_INVALID_ARG;
     g_profile[stage].start = (start_event && stop_event) ? (hipEvent_t)start_event : nullptr;
     g_profile[stage].stop = (start_event && stop_event) ? (hipEvent_t)stop_event : nullptr;
     return XKV_OK;

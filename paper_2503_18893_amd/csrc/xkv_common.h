@@ -86,11 +86,12 @@ constexpr int kStateWords = 8;   // per row: (prefix, k_rem) for each resolved l
 
 xkv_status make_plan(const xkv_shape &s, Plan &p);
 
-// Optional event pair recorded around the main kernel of a stage (0 score, 1 gather-attend, 2 dense).
+// Optional event pair recorded around the main kernel of a stage (0 score, 1 gather-attend, 2 dense,
+// 3 Gram-matrix product of the factorization).
 struct ProfileEvents {
     hipEvent_t start, stop;
 };
-extern ProfileEvents g_profile[3];
+extern ProfileEvents g_profile[4];
 inline void profile_begin(int stage, hipStream_t st)
 {
     if (g_profile[stage].start && g_profile[stage].stop) (void)hipEventRecord(g_profile[stage].start, st);
