@@ -36,7 +36,8 @@ __device__ __forceinline__ void fz_copy16_global_to_lds(const void *gptr, uint32
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory");
 }
-#define FZ_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt((0 & 0xF) | (7 << 4) | (0xF << 8) | (0 << 14))
+// s_waitcnt bounding only the number of outstanding vector-memory operations (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+#define FZ_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (0xF << 8) | (((n) >> 4) << 14))
 
 __device__ __forceinline__ void fz_lds_barrier()
 {
@@ -82,15 +83,15 @@ __global__ __launch_bounds__(256) void xt_pack_kernel(const T *__restrict__ X, T
 //
 // Element (row, k) of an operand lives at base + (k / kbw) * kblk + row * pitch + k % kbw: a plain row-major
 // matrix has kbw = K, and a cache stored as [column block][token][d_h] is read as X_cat [token][n] with
-// kbw = d_h, kblk = L * d_h, pitch = d_h.  K is consumed in slabs of 128 B per row (64 bf16 or 32 fp32
+// kbw = d_h, kblk = L * d_h, pitch = d_h.  K is consumed in slabs of 64 B per row (32 bf16 or 16 fp32
 // values); kbw is a multiple of the slab.
 //
 // Workgroup: 8 wavefronts, a 256 x 256 output tile, wavefront (wm, wn) owns rows 64 wm .. +63 and columns
-// 128 wn .. +127 as 2 x 4 accumulator tiles of 32 x 32.  A slab of the 256 + 256 operand rows (64 KiB) is
-// copied global -> LDS directly, double-buffered: one copy instruction moves 8 rows x 128 B, lane l fetching
-// the 16 B piece (l % 8) ^ (l / 8) of row l / 8, so that a row's pieces sit in LDS xor-swizzled by the row
-// number and the fragment reads (32 rows, same piece) spread over all banks.  Rows beyond the operand's end
-// are clamped to its last row; what they produce is never stored.
+// 128 wn .. +127 as 2 x 4 accumulator tiles of 32 x 32.  A slab of the 256 + 256 operand rows (32 KiB) is
+// copied global -> LDS directly into a ring of four stages: one copy instruction moves 16 rows x 64 B, lane l
+// fetching the 16 B piece (l % 4) ^ (l / 16) of row l / 4, so that a row's pieces sit in LDS xor-swizzled by
+// (row / 4) % 4 and the fragment reads (consecutive rows, same piece) spread over all 64 banks.  Rows beyond the
+// operand's end are clamped to its last row; what they produce is never stored.
 // Output: fp32 partial planes out_f32[split][m][n] (summed by a second kernel), or, with one split, the
 // final matrix in fp32 or bf16.  With lower_only (P == Q) only tiles on or below the diagonal are computed.
 // ------------------------------------------------------------------------------------------------
@@ -102,13 +103,13 @@ struct GemmOperand {
 };
 struct GemmArgs {
     GemmOperand P, Q;
-    int n_slabs, splits, lower_only, tiles_n;
+    int n_slabs, splits, lower_only, tiles_n, tiles;  // tiles: output tiles per split (lower_only: on or below the diagonal)
     float *out_f32;
     bf16_t *out_bf16;
     long long ldo, plane, out_seq;
 };
 
-constexpr int kGemmThreads = 512, kGemmTile = 256, kGemmStage = 512 * 128, kGemmLds = 2 * kGemmStage;
+constexpr int kGemmThreads = 512, kGemmTile = 256, kGemmStages = 4, kGemmStage = 512 * 64, kGemmLds = kGemmStages * kGemmStage;
 
 // Decoding of a linear index into a pair (bi, bj), bj <= bi, enumerated row by row.
 __device__ __forceinline__ void fz_lower_pair(int t, int &bi, int &bj)
@@ -120,29 +121,58 @@ __device__ __forceinline__ void fz_lower_pair(int t, int &bi, int &bj)
     bj = t - m * (m + 1) / 2;
 }
 
-// The eight copy instructions of a wavefront for one slab: its 64 operand rows, 8 rows x 128 B each.
-__device__ __forceinline__ void fz_issue_slab(const unsigned char *const (&rowp)[8], size_t off, uint32_t dst)
+// The t-th tile on or below the diagonal of a T x T tile grid, counted patch by patch (patches of 4 x 4 tiles,
+// row by row; inside a patch row by row).
+__device__ __forceinline__ void fz_lower_patch_tile(int t, int T, int &tm, int &tn)
+{
+    const int PT = (T + 3) / 4;
+    for (int pr = 0; pr < PT; ++pr)
+        for (int pc = 0; pc <= pr; ++pc) {
+            const int m0 = 4 * pr, n0 = 4 * pc, m1 = (m0 + 4 < T) ? m0 + 4 : T, n1 = (n0 + 4 < T) ? n0 + 4 : T;
+            for (int m = m0; m < m1; ++m) {
+                const int hi = (n1 - 1 < m) ? n1 - 1 : m, cnt = hi - n0 + 1;  // tiles (m, n0 .. hi)
+                if (cnt <= 0) continue;
+                if (t < cnt) {
+                    tm = m;
+                    tn = n0 + t;
+                    return;
+                }
+                t -= cnt;
+            }
+        }
+    tm = tn = 0;  // not reached for t < T (T + 1) / 2
+}
+
+// The four copy instructions of a wavefront for one slab: its 64 operand rows, 16 rows x 64 B each.
+__device__ __forceinline__ void fz_issue_slab(const unsigned char *const (&rowp)[4], size_t off, uint32_t dst)
 {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) fz_copy16_global_to_lds(rowp[j] + off, dst + j * 1024);
+    for (int j = 0; j < 4; ++j) fz_copy16_global_to_lds(rowp[j] + off, dst + j * 1024);
 }
 
 template <typename T>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
 {
-    constexpr int E = 128 / (int)sizeof(T);  // elements per slab row
+    constexpr int E = 64 / (int)sizeof(T);  // elements per slab row
     extern __shared__ __attribute__((aligned(16))) unsigned char fz_smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = wave_id();
     const int m32 = lane & 31, h = lane >> 5;
 
+    // Work item -> compute-unit die.  Workgroups go to the 8 dies (each with its own L2) round-robin by their
+    // linear id, so die x = blockIdx.x % 8 takes the x-th eighth of the item list, in order: the items a die
+    // works on at the same time are neighbours in the list, and the list is ordered so that neighbours share
+    // operand rows (same range of k; tiles in 4 x 4 patches, or side by side along n).
+    const int items = a.tiles * a.splits, per_die = (items + 7) / 8;
+    const int q = (int)(blockIdx.x & 7) * per_die + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_die || q >= items) return;
+    const int split = q / a.tiles, t = q % a.tiles;
     int tm, tn;
-    if (a.lower_only) {  // blockIdx.x enumerates (tm, tn), tn <= tm, row by row
-        fz_lower_pair(blockIdx.x, tm, tn);
+    if (a.lower_only) {
+        fz_lower_patch_tile(t, a.tiles_n, tm, tn);
     } else {
-        tm = blockIdx.x / a.tiles_n;
-        tn = blockIdx.x % a.tiles_n;
+        tm = t / a.tiles_n;
+        tn = t % a.tiles_n;
     }
-    const int split = blockIdx.y;
     const int sb_begin = (int)((long long)a.n_slabs * split / a.splits);
     const int sb_end = (int)((long long)a.n_slabs * (split + 1) / a.splits);
 
@@ -153,15 +183,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
     const long long op_pitch = is_p ? a.P.pitch : a.Q.pitch, op_kblk = is_p ? a.P.kblk : a.Q.kblk;
     const int op_kbw = is_p ? a.P.kbw : a.Q.kbw, op_rows = is_p ? a.P.rows : a.Q.rows;
     const int origin = (is_p ? tm : tn) * kGemmTile + (w & 3) * 64;
-    const int piece = (lane & 7) ^ (lane >> 3);
-    const unsigned char *rowp[8];
+    const int piece = (lane & 3) ^ ((lane >> 4) & 3);
+    const unsigned char *rowp[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        int R = origin + 8 * j + (lane >> 3);
+    for (int j = 0; j < 4; ++j) {
+        int R = origin + 16 * j + (lane >> 2);
         R = R < op_rows ? R : op_rows - 1;
         rowp[j] = op_base + (size_t)((long long)R * op_pitch) * sizeof(T) + piece * 16;
     }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(fz_lds_void_t *)fz_smem + (uint32_t)(w * 8 * 1024);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(fz_lds_void_t *)fz_smem + (uint32_t)(w * 4 * 1024);
     auto slab_offset = [&](int sb) __attribute__((always_inline)) {
         const long long kk = (long long)sb * E;
         return (size_t)((kk / op_kbw) * op_kblk + kk % op_kbw) * sizeof(T);
@@ -176,47 +206,55 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    // 16 B index of (row, piece c) in a stage: row * 8 + (c ^ row % 8); row % 8 == m32 % 8 for every row read here
-    const int arow = (64 * wm + m32) * 8, qrow = (256 + 128 * wn + m32) * 8, sw = m32 & 7;
+    // 16 B index of (row, piece c) in a stage: row * 4 + (c ^ (row / 4) % 4); (row / 4) % 4 == (m32 / 4) % 4 for every row
+    // read here.  With 64 banks of 4 B, 16 consecutive rows x one piece then cover every bank exactly once.
+    const int arow = (64 * wm + m32) * 4, qrow = (256 + 128 * wn + m32) * 4, sw = (m32 >> 2) & 3;
 
-    if (sb_begin < sb_end) fz_issue_slab(rowp, slab_offset(sb_begin), lds0);
-    for (int sb = sb_begin; sb < sb_end; ++sb) {
-        const int buf = (sb - sb_begin) & 1;
-        FZ_WAIT_VMCNT0();
-        fz_lds_barrier();  // this slab has landed for every wavefront; nobody reads the other buffer any more
-        if (sb + 1 < sb_end) fz_issue_slab(rowp, slab_offset(sb + 1), lds0 + (uint32_t)((buf ^ 1) * kGemmStage));
-        const fz_u32x4_t *st = reinterpret_cast<const fz_u32x4_t *>(fz_smem + buf * kGemmStage);
+    // Ring of four stages: the slab three ahead is requested while the current one is multiplied, so a copy has
+    // three slab times to land.  Every iteration issues exactly four copies per wavefront (past the end, the last
+    // slab again, into a stage nobody reads), which keeps the count of outstanding copies, and with it the wait
+    // below, the same in every iteration.
+    const int n_sb = sb_end - sb_begin;
+    auto slab_at = [&](int i) __attribute__((always_inline)) { return slab_offset(sb_begin + (i < n_sb ? i : n_sb - 1)); };
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int slot = (2 * s + h) ^ sw;
+    for (int p = 0; p < kGemmStages - 1; ++p) fz_issue_slab(rowp, slab_at(p), lds0 + (uint32_t)(p * kGemmStage));
+    for (int i = 0; i < n_sb; ++i) {
+        FZ_WAIT_VMCNT(8);   // all but the two youngest slabs have landed: slab i is in LDS
+        fz_lds_barrier();   // ... for every wavefront; and nobody reads stage (i + 3) % 4 = (i - 1) % 4 any more
+        fz_issue_slab(rowp, slab_at(i + kGemmStages - 1), lds0 + (uint32_t)(((i + kGemmStages - 1) & 3) * kGemmStage));
+        const fz_u32x4_t *st = reinterpret_cast<const fz_u32x4_t *>(fz_smem + (i & 3) * kGemmStage);
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int slot = (2 * s2 + h) ^ sw;
             fz_u32x4_t af[2], qf[4];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) af[i] = st[arow + i * 256 + slot];
+            for (int i2 = 0; i2 < 2; ++i2) af[i2] = st[arow + i2 * 128 + slot];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) qf[j] = st[qrow + j * 256 + slot];
+            for (int j = 0; j < 4; ++j) qf[j] = st[qrow + j * 128 + slot];
             if constexpr (sizeof(T) == 2) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fz_bf16x8_t, af[i]),
-                                                                            __builtin_bit_cast(fz_bf16x8_t, qf[j]),
-                                                                            acc[i][j], 0, 0, 0);
+                        acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fz_bf16x8_t, af[i2]),
+                                                                             __builtin_bit_cast(fz_bf16x8_t, qf[j]),
+                                                                             acc[i2][j], 0, 0, 0);
             } else {
-                // a 16 B piece holds 4 consecutive k of the lane's row; step e pairs k = 8 s + e (lanes 0-31)
-                // with k = 8 s + 4 + e (lanes 32-63) on both operands
+                // a 16 B piece holds 4 consecutive k of the lane's row; step e pairs k = 8 s2 + e (lanes 0-31)
+                // with k = 8 s2 + 4 + e (lanes 32-63) on both operands
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
+                    for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(fz_f32x4_t, af[i])[e],
-                                                                             __builtin_bit_cast(fz_f32x4_t, qf[j])[e],
-                                                                             acc[i][j], 0, 0, 0);
+                            acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(fz_f32x4_t, af[i2])[e],
+                                                                              __builtin_bit_cast(fz_f32x4_t, qf[j])[e],
+                                                                              acc[i2][j], 0, 0, 0);
             }
         }
     }
+    FZ_WAIT_VMCNT(0);  // the surplus copies must have landed before this workgroup's LDS is handed on
 
     // ---- store: accumulator register v of a 32 x 32 tile is row 8 (v / 4) + 4 h + v % 4, column m32
 #pragma unroll
@@ -294,6 +332,22 @@ __global__ __launch_bounds__(256) void init_v_kernel(float *__restrict__ Vt, lon
 // in element v of its four results.
 typedef __attribute__((ext_vector_type(4))) double fz_f64x4_t;
 
+__device__ __forceinline__ void fz_gram_fetch(float (&fa)[8][2], float (&fb)[8][2], const float *__restrict__ Wn, int n0,
+                                              int n_begin, int n_end, int r, const int (&ci)[2], const int (&cj)[2], int kk)
+{
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int row = n0 + 4 * q + kk;
+        const bool ok = row < n_end;
+        const float *wr = Wn + (size_t)(ok ? row : n_begin) * r;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            fa[q][u] = (ok && ci[u] < r) ? wr[ci[u]] : 0.0f;
+            fb[q][u] = (ok && cj[u] < r) ? wr[cj[u]] : 0.0f;
+        }
+    }
+}
+
 // (3b) Gram matrix of the r vectors, products and sums in fp64: G[i][j] = sum_n W[n][i] W[n][j].  One wavefront
 // per 32 x 32 block on or below the diagonal and per range of n (one partial plane per range, added up in a
 // fixed order by gram_sum_kernel); a step multiplies 4 rows of W, widened to fp64 as they are loaded.
@@ -319,26 +373,27 @@ __global__ __launch_bounds__(256) void gram_f64_kernel(const float *__restrict__
         ci[u] = bi * 32 + 16 * u + col;
         cj[u] = bj * 32 + 16 * u + col;
     }
-    for (int n0 = n_begin; n0 < n_end; n0 += 32) {  // eight steps' worth of loads first, then the 32 products
-        float fa[8][2], fb[8][2];
+    // eight steps (32 rows of W) at a time; the loads of the next eight are requested before the 32 products of
+    // the current ones
+    float fa[8][2], fb[8][2];
+    fz_gram_fetch(fa, fb, Wn, n_begin, n_begin, n_end, r, ci, cj, kk);
+    for (int n0 = n_begin; n0 < n_end; n0 += 32) {
+        double da[8][2], db[8][2];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int row = n0 + 4 * q + kk;
-            const bool ok = row < n_end;
-            const float *wr = Wn + (size_t)(ok ? row : n_begin) * r;
+        for (int q = 0; q < 8; ++q)
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                fa[q][u] = (ok && ci[u] < r) ? wr[ci[u]] : 0.0f;
-                fb[q][u] = (ok && cj[u] < r) ? wr[cj[u]] : 0.0f;
+                da[q][u] = (double)fa[q][u];
+                db[q][u] = (double)fb[q][u];
             }
-        }
+        if (n0 + 32 < n_end) fz_gram_fetch(fa, fb, Wn, n0 + 32, n_begin, n_end, r, ci, cj, kk);
 #pragma unroll
         for (int q = 0; q < 8; ++q)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int v = 0; v < 2; ++v)
-                    acc[u][v] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)fa[q][u], (double)fb[q][v], acc[u][v], 0, 0, 0);
+                    acc[u][v] = __builtin_amdgcn_mfma_f64_16x16x4f64(da[q][u], db[q][v], acc[u][v], 0, 0, 0);
     }
     double *out = planes + (size_t)split * r * r;
 #pragma unroll
@@ -525,13 +580,13 @@ __global__ __launch_bounds__(256) void diag_inverse_kernel(const double *__restr
 }
 
 // (3d) V = Lc^-1 W by blocked forward substitution on the fp64 matrix cores.  Rows of W^T (Wn [n][r]) are
-// independent; a workgroup of 4 wavefronts takes 16 of them and keeps them in registers as 16 x 16 accumulator
+// independent; a workgroup of 4 wavefronts takes 16 RT of them and keeps them in registers as 16 x 16 accumulator
 // tiles (tile t = columns 16 t .. 16 t + 15, owned by wavefront t % 4).  For tile I in turn: its owner hands the
-// 16 x 16 values to LDS, 256 threads multiply them by the inverse of the diagonal block (one output each: the
-// final rows 16 I .. 16 I + 15 of V for these 16 n, written out as fp32), and every wavefront subtracts
-// V_I Lc[16 t .., 16 I ..]^T from its tiles t > I (four matrix-core steps per tile; the Lc operands come straight
-// from global memory and are requested before the block inverse is applied, which hides their latency).
-template <int MAXT>  // tiles per wavefront: r <= 64 * MAXT
+// values to LDS, the threads multiply them by the inverse of the diagonal block (the final rows 16 I .. 16 I + 15
+// of V for these n, written out as fp32), and every wavefront subtracts V_I Lc[16 t .., 16 I ..]^T from its tiles
+// t > I (four matrix-core steps per tile and row group; the Lc operands come straight from global memory and are
+// requested before the block inverse is applied, the block inverse itself one block ahead).
+template <int MAXT, int RT>  // tiles per wavefront (r <= 64 MAXT), groups of 16 rows per workgroup
 __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict__ Wn, const double *__restrict__ Lt,
                                                          const double *__restrict__ Minv, float *__restrict__ Vt, int n, int r)
 {
@@ -539,20 +594,23 @@ __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict
     Lt += (size_t)blockIdx.z * r * r;
     Minv += (size_t)blockIdx.z * ((r + 15) / 16) * 256;
     Vt += (size_t)blockIdx.z * n * r;
-    __shared__ double wt[16][17], vblk[16][17], minv_s[16][17];
+    __shared__ double wt[16 * RT][17], vblk[16 * RT][17], minv_s[16][17];
     const int tid = threadIdx.x, lane = tid & 63, w = wave_id(), col = lane & 15, kk = lane >> 4;
-    const int n0 = blockIdx.x * 16, n_tiles = (r + 15) / 16;
-    fz_f64x4_t acc[MAXT];
+    const int n0 = blockIdx.x * (16 * RT), n_tiles = (r + 15) / 16;
+    fz_f64x4_t acc[RT][MAXT];
 #pragma unroll
-    for (int u = 0; u < MAXT; ++u) {
-        const int c = 16 * (w + 4 * u) + col;
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int row = n0 + kk + 4 * e;
-            acc[u][e] = (c < r && row < n) ? (double)Wn[(size_t)row * r + c] : 0.0;
+        for (int u = 0; u < MAXT; ++u) {
+            const int c = 16 * (w + 4 * u) + col;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = n0 + 16 * rt + kk + 4 * e;
+                acc[rt][u][e] = (c < r && row < n) ? (double)Wn[(size_t)row * r + c] : 0.0;
+            }
         }
-    }
-    const int s_row = tid >> 4, s_ii = tid & 15;  // role when the block inverse is applied: output (row, ii)
+    const int s_row = tid >> 4, s_ii = tid & 15;  // role when the block inverse is applied: outputs (s_row + 16 rt, ii)
+    double mi = Minv[tid];
     for (int I = 0; I < n_tiles; ++I) {
         // operands of the update for this wavefront's tiles behind I: Lc[16 t + col][16 I + 4 g + kk]
         double bop[MAXT][4];
@@ -565,31 +623,41 @@ __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict
                 bop[u][g] = (t > I && c < r && lrow < r) ? Lt[(size_t)lrow * r + c] : 0.0;
             }
         }
-        const double mi = Minv[(size_t)I * 256 + tid];
         if ((I & 3) == w) {
 #pragma unroll
             for (int u = 0; u < MAXT; ++u)
                 if (u == (I >> 2)) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) wt[kk + 4 * e][col] = acc[u][e];
+                    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) wt[16 * rt + kk + 4 * e][col] = acc[rt][u][e];
                 }
         }
         minv_s[tid >> 4][tid & 15] = mi;
+        if (I + 1 < n_tiles) mi = Minv[(size_t)(I + 1) * 256 + tid];
         __syncthreads();
-        double v = 0.0;
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) v += minv_s[s_ii][jj] * wt[s_row][jj];  // entries jj > ii of the inverse are zero
-        vblk[s_row][s_ii] = v;
-        if (16 * I + s_ii < r && n0 + s_row < n) Vt[(size_t)(16 * I + s_ii) * n + n0 + s_row] = (float)v;
+        for (int rt = 0; rt < RT; ++rt) {
+            double v = 0.0;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) v += minv_s[s_ii][jj] * wt[16 * rt + s_row][jj];  // entries jj > ii of the inverse are zero
+            vblk[16 * rt + s_row][s_ii] = v;
+            const int row = n0 + 16 * rt + s_row;
+            if (16 * I + s_ii < r && row < n) Vt[(size_t)(16 * I + s_ii) * n + row] = (float)v;
+        }
         __syncthreads();
-        double aop[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) aop[g] = -vblk[col][4 * g + kk];
+        for (int rt = 0; rt < RT; ++rt) {
+            double aop[4];
 #pragma unroll
-        for (int u = 0; u < MAXT; ++u) {
-            if (w + 4 * u > I && w + 4 * u < n_tiles) {
+            for (int g = 0; g < 4; ++g) aop[g] = -vblk[16 * rt + col][4 * g + kk];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) acc[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(aop[g], bop[u][g], acc[u], 0, 0, 0);
+            for (int u = 0; u < MAXT; ++u) {
+                if (w + 4 * u > I && w + 4 * u < n_tiles) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        acc[rt][u] = __builtin_amdgcn_mfma_f64_16x16x4f64(aop[g], bop[u][g], acc[rt][u], 0, 0, 0);
+                }
             }
         }
     }
@@ -628,13 +696,13 @@ FzLayout fz_layout(const xkv_shape &s, int r)
     f.bc = std::max(1, std::min(s.batch, kFzChunk));
     const int t = (f.n + kGemmTile - 1) / kGemmTile;
     f.gram_tiles = t * (t + 1) / 2;
-    const int slab = 128 / (int)f.esz, gram_slabs = f.Lp / slab;
+    const int slab = 64 / (int)f.esz, gram_slabs = f.Lp / slab;
     auto splits_for = [&](int wgs_per_seq, int target, int most) {  // enough workgroups to fill the chip twice over
         const int wgs = wgs_per_seq * f.bc;
         return std::max(1, std::min(std::min(16, most), (target + wgs - 1) / wgs));
     };
     f.gram_splits = splits_for(f.gram_tiles, 512, gram_slabs);
-    f.w_splits = splits_for(t * ((r + kGemmTile - 1) / kGemmTile), 256, f.n / 32);
+    f.w_splits = splits_for(t * ((r + kGemmTile - 1) / kGemmTile), 256, f.n / 16);
     const int gb = (r + 31) / 32;
     f.g_splits = splits_for((gb * (gb + 1) / 2 + 3) / 4, 1024, f.n / 64);
     f.chol_pb = r <= 512 ? 32 : 16;
@@ -664,7 +732,10 @@ template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, int n
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemm_nt_kernel<T>, dim3(tiles, a.splits, nseq), dim3(kGemmThreads), kGemmLds, st, a);
+    GemmArgs b = a;
+    b.tiles = tiles;
+    const int per_die = (tiles * a.splits + 7) / 8;
+    hipLaunchKernelGGL(gemm_nt_kernel<T>, dim3(8 * per_die, 1, nseq), dim3(kGemmThreads), kGemmLds, st, b);
     return hipGetLastError();
 }
 
@@ -675,7 +746,7 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
                            void *A_out, void *B_out, unsigned char *ws, hipStream_t st)
 {
     const int n = f.n, d = s.H_kv * s.d_h, tn = (n + kGemmTile - 1) / kGemmTile, tr = (r + kGemmTile - 1) / kGemmTile;
-    constexpr int E = 128 / (int)sizeof(T);
+    constexpr int E = 64 / (int)sizeof(T);
     T *Xt = reinterpret_cast<T *>(ws + f.off_xt);
     float *part = reinterpret_cast<float *>(ws + f.off_part), *C = reinterpret_cast<float *>(ws + f.off_c);
     float *Vt = reinterpret_cast<float *>(ws + f.off_vt), *Wn = reinterpret_cast<float *>(ws + f.off_wn);
@@ -715,7 +786,7 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
             GemmArgs a{};  // Wn [n][r] = C Vt^T
             a.P = GemmOperand{C, n, 0, n, n, (long long)n * n};
             a.Q = GemmOperand{Vt, n, 0, n, r, vcount};
-            a.n_slabs = n / 32; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
+            a.n_slabs = n / 16; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
             a.out_f32 = f.w_splits > 1 ? part : Wn; a.out_bf16 = nullptr; a.ldo = r; a.plane = vcount;
             a.out_seq = f.w_splits > 1 ? (long long)f.part_seq : vcount;
             if ((e = launch_gemm<float>(a, tn * tr, nb, st)) != hipSuccess) break;
@@ -735,9 +806,9 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
             }
             hipLaunchKernelGGL(diag_inverse_kernel, dim3(blocks256((r + 15) / 16 * 16), 1, nb), dim3(256), 0, st, Lt, Minv, r);
             if (r <= 512)
-                hipLaunchKernelGGL(orth_solve_kernel<8>, dim3((n + 15) / 16, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
+                hipLaunchKernelGGL((orth_solve_kernel<8, 2>), dim3((n + 31) / 32, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
             else
-                hipLaunchKernelGGL(orth_solve_kernel<16>, dim3((n + 15) / 16, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
+                hipLaunchKernelGGL((orth_solve_kernel<16, 1>), dim3((n + 15) / 16, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
         }
         if (e != hipSuccess) break;
         T *Bb = reinterpret_cast<T *>(B_out) + (size_t)b0 * s.G * r * d;
