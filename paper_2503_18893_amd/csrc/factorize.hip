@@ -150,6 +150,40 @@ __device__ __forceinline__ void fz_issue_slab(const unsigned char *const (&rowp)
     for (int j = 0; j < 4; ++j) fz_copy16_global_to_lds(rowp[j] + off, dst + j * 1024);
 }
 
+// One k-step of a wavefront: its 2 + 4 operand fragments (32 rows each, the lane's 16 B piece), and the 8 products.
+__device__ __forceinline__ void fz_read_frags(fz_u32x4_t (&af)[2], fz_u32x4_t (&qf)[4], const fz_u32x4_t *st, int arow, int qrow,
+                                              int slot)
+{
+#pragma unroll
+    for (int i = 0; i < 2; ++i) af[i] = st[arow + i * 128 + slot];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) qf[j] = st[qrow + j * 128 + slot];
+}
+
+template <typename T>
+__device__ __forceinline__ void fz_multiply(fz_f32x16_t (&acc)[2][4], const fz_u32x4_t (&af)[2], const fz_u32x4_t (&qf)[4])
+{
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fz_bf16x8_t, af[i]),
+                                                                    __builtin_bit_cast(fz_bf16x8_t, qf[j]), acc[i][j], 0, 0, 0);
+    } else {
+        // a 16 B piece holds 4 consecutive k of the lane's row; step e pairs k = 8 s + e (lanes 0-31) with
+        // k = 8 s + 4 + e (lanes 32-63) on both operands
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(fz_f32x4_t, af[i])[e],
+                                                                     __builtin_bit_cast(fz_f32x4_t, qf[j])[e], acc[i][j], 0, 0, 0);
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
 {
@@ -192,9 +226,25 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
         rowp[j] = op_base + (size_t)((long long)R * op_pitch) * sizeof(T) + piece * 16;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(fz_lds_void_t *)fz_smem + (uint32_t)(w * 4 * 1024);
-    auto slab_offset = [&](int sb) __attribute__((always_inline)) {
-        const long long kk = (long long)sb * E;
-        return (size_t)((kk / op_kbw) * op_kblk + kk % op_kbw) * sizeof(T);
+    // Byte offset of the next slab to request within an operand row, advanced without divisions: slabs are
+    // requested in order, and past the last one the last one again.
+    const long long kk0 = (long long)sb_begin * E;
+    int kin = (int)(kk0 % op_kbw);
+    size_t slab_off = (size_t)((kk0 / op_kbw) * op_kblk + kin) * sizeof(T);
+    const size_t blk_jump = (size_t)(op_kblk - op_kbw) * sizeof(T);
+    int to_advance = sb_end - sb_begin - 1;  // how many more times the offset moves on
+    auto next_slab = [&]() __attribute__((always_inline)) {
+        const size_t cur = slab_off;
+        if (to_advance > 0) {
+            --to_advance;
+            kin += E;
+            slab_off += E * sizeof(T);
+            if (kin >= op_kbw) {
+                kin = 0;
+                slab_off += blk_jump;
+            }
+        }
+        return cur;
     };
 
     // ---- compute side
@@ -215,44 +265,28 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
     // slab again, into a stage nobody reads), which keeps the count of outstanding copies, and with it the wait
     // below, the same in every iteration.
     const int n_sb = sb_end - sb_begin;
-    auto slab_at = [&](int i) __attribute__((always_inline)) { return slab_offset(sb_begin + (i < n_sb ? i : n_sb - 1)); };
 #pragma unroll
-    for (int p = 0; p < kGemmStages - 1; ++p) fz_issue_slab(rowp, slab_at(p), lds0 + (uint32_t)(p * kGemmStage));
+    for (int p = 0; p < kGemmStages - 1; ++p) fz_issue_slab(rowp, next_slab(), lds0 + (uint32_t)(p * kGemmStage));
+    // Fragments are read one step ahead of the products that use them: F0 holds step 0 of the current slab (read
+    // during the previous slab), F1 its step 1.  For that, a barrier guarantees the slab after the current one too.
+    fz_u32x4_t a0[2], q0[4], a1[2], q1[4];
+    FZ_WAIT_VMCNT(8);
+    fz_lds_barrier();
+    fz_read_frags(a0, q0, reinterpret_cast<const fz_u32x4_t *>(fz_smem), arow, qrow, h ^ sw);
     for (int i = 0; i < n_sb; ++i) {
-        FZ_WAIT_VMCNT(8);   // all but the two youngest slabs have landed: slab i is in LDS
+        FZ_WAIT_VMCNT(4);   // all but the youngest slab have landed: slabs i and i + 1 are in LDS
         fz_lds_barrier();   // ... for every wavefront; and nobody reads stage (i + 3) % 4 = (i - 1) % 4 any more
-        fz_issue_slab(rowp, slab_at(i + kGemmStages - 1), lds0 + (uint32_t)(((i + kGemmStages - 1) & 3) * kGemmStage));
+        fz_issue_slab(rowp, next_slab(), lds0 + (uint32_t)(((i + kGemmStages - 1) & 3) * kGemmStage));
         const fz_u32x4_t *st = reinterpret_cast<const fz_u32x4_t *>(fz_smem + (i & 3) * kGemmStage);
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            const int slot = (2 * s2 + h) ^ sw;
-            fz_u32x4_t af[2], qf[4];
-#pragma unroll
-            for (int i2 = 0; i2 < 2; ++i2) af[i2] = st[arow + i2 * 128 + slot];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) qf[j] = st[qrow + j * 128 + slot];
-            if constexpr (sizeof(T) == 2) {
-#pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(fz_bf16x8_t, af[i2]),
-                                                                             __builtin_bit_cast(fz_bf16x8_t, qf[j]),
-                                                                             acc[i2][j], 0, 0, 0);
-            } else {
-                // a 16 B piece holds 4 consecutive k of the lane's row; step e pairs k = 8 s2 + e (lanes 0-31)
-                // with k = 8 s2 + 4 + e (lanes 32-63) on both operands
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i2 = 0; i2 < 2; ++i2)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            acc[i2][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(fz_f32x4_t, af[i2])[e],
-                                                                              __builtin_bit_cast(fz_f32x4_t, qf[j])[e],
-                                                                              acc[i2][j], 0, 0, 0);
-            }
-        }
+        // the scheduling fences keep each group of reads ahead of the products of the step before it
+        fz_read_frags(a1, q1, st, arow, qrow, (2 + h) ^ sw);
+        __builtin_amdgcn_sched_barrier(0);
+        fz_multiply<T>(acc, a0, q0);
+        __builtin_amdgcn_sched_barrier(0);
+        fz_read_frags(a0, q0, reinterpret_cast<const fz_u32x4_t *>(fz_smem + ((i + 1) & 3) * kGemmStage), arow, qrow, h ^ sw);
+        __builtin_amdgcn_sched_barrier(0);
+        fz_multiply<T>(acc, a1, q1);
+        __builtin_amdgcn_sched_barrier(0);
     }
     FZ_WAIT_VMCNT(0);  // the surplus copies must have landed before this workgroup's LDS is handed on
 
@@ -693,6 +727,9 @@ FzLayout fz_layout(const xkv_shape &s, int r)
     f.esz = s.dtype == XKV_F32 ? 4 : 2;
     f.n = s.G * s.H_kv * s.d_h;
     f.Lp = (s.L + 63) / 64 * 64;
+    // a row pitch that is a multiple of 4 KiB would put the same piece of every row of a tile on the same cache
+    // channel; 64 more (zero) tokens move consecutive rows one 128 B line apart
+    if (((size_t)f.Lp * f.esz) % 4096 == 0) f.Lp += 64;
     f.bc = std::max(1, std::min(s.batch, kFzChunk));
     const int t = (f.n + kGemmTile - 1) / kGemmTile;
     f.gram_tiles = t * (t + 1) / 2;
