@@ -218,6 +218,104 @@ def sr_decode_tail(A_k, A_v, B_k, B_v, q, H_kv, k, K_tail, V_tail, scale=None):
     return gather_attend_tail(A_k, A_v, B_k, B_v, q, idx, K_tail, V_tail, scale), idx
 
 
+def landmarks(K_rope, c, o=0):
+    """Landmark construction at prefill (App. B.1, Alg. 1).  K_rope [H_kv][L][d_h] -> (Lm [H_kv][n_c][d_h],
+    m [H_kv][n_c], outliers [H_kv][o]).
+
+    Chunk j holds tokens j c .. min(j c + c, L) - 1; its landmark is the mean of its keys (a shorter last chunk
+    is averaged over the tokens it has); m is the smallest cosine between a key of the chunk and the landmark
+    (0 when either vector is zero); the outliers of a head are its o chunks with the smallest m, i.e.
+    ArgTopK(-m, o), decided on the fp32 values of -m with ties towards the smaller chunk index (the order of the
+    top-k step of Alg. 2), returned ascending.
+    """
+    K = widen(K_rope)
+    H_kv, L, d_h = K.shape
+    n_c = -(-L // c)
+    Lm = np.empty((H_kv, n_c, d_h), np.float64)
+    m = np.empty((H_kv, n_c), np.float64)
+    for g in range(H_kv):
+        for j in range(n_c):
+            chunk = K[g, j * c:min(j * c + c, L)]
+            mean = chunk.sum(axis=0) / chunk.shape[0]
+            Lm[g, j] = mean
+            worst = np.inf
+            for x in chunk:
+                den = np.sqrt(x @ x) * np.sqrt(mean @ mean)
+                worst = min(worst, (x @ mean) / den if den > 0.0 else 0.0)
+            m[g, j] = worst
+    if o > 0:
+        outliers = np.stack([select((-m[g]).astype(np.float32), o) for g in range(H_kv)]).astype(np.int32)
+    else:
+        outliers = np.zeros((H_kv, 0), np.int32)
+    return Lm, m, outliers
+
+
+def chunk_scores(Lm, q, scale=None):
+    """Alg. 2, scoring and pooling: P[h][j] = scale <q_h, Lm[rho(h)][j]>, S[g][j] = max over the heads of g."""
+    Lm, q = widen(Lm), widen(q)
+    H_kv, n_c, d_h = Lm.shape
+    H_q = q.shape[0]
+    n_rep = H_q // H_kv
+    scale = default_scale(d_h) if scale is None else scale
+    S = np.empty((H_kv, n_c), np.float64)
+    for g in range(H_kv):
+        P = scale * (Lm[g] @ q[g * n_rep:(g + 1) * n_rep].T)   # [n_c][n_rep]
+        S[g] = P.max(axis=1)
+    return S
+
+
+def chunk_budget(k, c, n_c):
+    """k_ch = ceil(k / c) (Alg. 2), never more than there are chunks."""
+    return min(-(-k // c), n_c)
+
+
+def expand_chunks(chunks, outliers, c, L):
+    """Union of the selected chunks with the static outliers (Alg. 2), expanded to token rows, ascending."""
+    rows = []
+    for j in sorted(set(int(x) for x in chunks) | set(int(x) for x in outliers)):
+        rows.extend(range(j * c, min(j * c + c, L)))
+    return np.asarray(rows, np.int32)
+
+
+def select_rows_by_landmarks(Lm, outliers, q, k, c, L, scale=None):
+    """Alg. 2 for one layer and decode step: per KV head the token rows to reconstruct (list of ascending int32
+    arrays of different lengths), and the pooled chunk scores as the fp32 values the top-k saw."""
+    S32 = chunk_scores(Lm, q, scale).astype(np.float32)
+    H_kv, n_c = S32.shape
+    k_ch = chunk_budget(k, c, n_c)
+    rows = [expand_chunks(select(S32[g], k_ch), outliers[g], c, L) for g in range(H_kv)]
+    return rows, S32
+
+
+def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None):
+    """Steps 5-6 (Eq. 3 and softmax attention) for per-head row lists of different lengths: out[H_q][d_h].
+    Written out in numpy."""
+    A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
+    H_q, d_h = q.shape
+    H_kv = len(rows)
+    n_rep = H_q // H_kv
+    scale = default_scale(d_h) if scale is None else scale
+    out = np.empty((H_q, d_h), np.float64)
+    for g in range(H_kv):
+        cols = slice(g * d_h, (g + 1) * d_h)
+        K_sel = A_k[rows[g]] @ B_k[:, cols]
+        V_sel = A_v[rows[g]] @ B_v[:, cols]
+        for h in range(g * n_rep, (g + 1) * n_rep):
+            z = scale * (K_sel @ q[h])
+            wgt = np.exp(z - z.max())
+            out[h] = (wgt / wgt.sum()) @ V_sel
+    return out
+
+
+def sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outliers, k, c, scale=None):
+    """SR step with the paper's own selector (App. B.1): chunks are scored against their landmarks, the top
+    ceil(k / c) chunks per KV head plus the static outliers are expanded to rows, those rows are reconstructed
+    (Eq. 3) and attended over.  Returns (out[H_q][d_h], rows, S32[H_kv][n_c])."""
+    L = widen(A_k).shape[0]
+    rows, S32 = select_rows_by_landmarks(Lm, outliers, q, k, c, L, scale)
+    return gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale), rows, S32
+
+
 def factorize(X_cat, r):
     """Eq. 1: (A[L][r], B[r][n], sigma[n]) with A = U Sigma, B = V_r^T."""
     X = widen(X_cat)

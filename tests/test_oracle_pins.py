@@ -366,3 +366,125 @@ def test_generator_recipe():
         np.testing.assert_array_equal(case[name], again[name])
     bits = synth.f32_to_bf16_bits(np.array([1.0, 1.00390625, 1.01171875, -2.5], np.float32))
     np.testing.assert_array_equal(bits, [0x3F80, 0x3F80, 0x3F82, 0xC020])   # ties to even
+
+
+# ----------------------------------------------------------------- landmark selector (App. B.1, Alg. 1-2)
+def _rand_keys(rng, H_kv, L, d_h):
+    return rng.standard_normal((H_kv, L, d_h))
+
+
+def test_landmarks_are_chunk_means_with_a_short_last_chunk():
+    rng = np.random.default_rng(41)
+    K = _rand_keys(rng, 2, 22, 6)
+    Lm, m, out = oracle.landmarks(K, 4)
+    assert Lm.shape == (2, 6, 6) and m.shape == (2, 6) and out.shape == (2, 0)
+    np.testing.assert_allclose(Lm[:, :5], K[:, :20].reshape(2, 5, 4, 6).mean(axis=2), rtol=1e-14)
+    np.testing.assert_allclose(Lm[:, 5], K[:, 20:].mean(axis=1), rtol=1e-14)      # two tokens, divided by two
+
+
+def test_chunks_of_one_token_are_their_own_landmarks():
+    rng = np.random.default_rng(42)
+    K = _rand_keys(rng, 3, 9, 5)
+    Lm, m, _ = oracle.landmarks(K, 1)
+    np.testing.assert_array_equal(Lm, K)
+    np.testing.assert_allclose(m, 1.0, rtol=1e-14)
+
+
+def test_minimum_cosine_has_its_closed_form_and_finds_the_planted_chunks():
+    """A chunk of c - 1 copies of e1 and one copy of e2: landmark ((c-1) e1 + e2) / c, cosines (c-1)/s and 1/s with
+    s = sqrt((c-1)^2 + 1); homogeneous chunks have cosine 1.  The outliers are exactly the planted chunks."""
+    c, n_c, d = 4, 10, 8
+    K = np.zeros((1, n_c * c, d))
+    K[0, :, 0] = 1.0
+    planted = [2, 7]
+    for j in planted:
+        K[0, j * c + 1] = 0.0
+        K[0, j * c + 1, 1] = 1.0
+    Lm, m, out = oracle.landmarks(K, c, o=2)
+    s = np.sqrt((c - 1) ** 2 + 1.0)
+    for j in range(n_c):
+        assert abs(m[0, j] - ((1.0 / s) if j in planted else 1.0)) < 1e-14
+    assert out[0].tolist() == planted
+    np.testing.assert_allclose(Lm[0, 2, :2], [(c - 1) / c, 1 / c], rtol=1e-14)
+
+
+def test_outlier_ties_go_to_the_smaller_chunk_and_zero_vectors_count_as_cosine_zero():
+    K = np.ones((1, 12, 3))
+    K[0, 4:8] = 0.0                      # an all-zero chunk: landmark 0, cosine defined as 0
+    Lm, m, out = oracle.landmarks(K, 4, o=2)
+    np.testing.assert_allclose(m[0], [1.0, 0.0, 1.0], atol=1e-15)
+    assert out[0].tolist() == [0, 1]     # chunk 1 (smallest m), then the tie between 0 and 2 goes to 0
+
+
+def test_landmark_scores_with_unit_chunks_are_the_pooled_scores_of_the_factors():
+    """c = 1: scoring chunks against landmarks = scoring tokens against K = A B, which by associativity is what the
+    factor path computes (steps 1-3)."""
+    rng = np.random.default_rng(43)
+    L, r, H_kv, H_q, d_h = 50, 7, 2, 6, 8
+    A = rng.standard_normal((L, r))
+    B = rng.standard_normal((r, H_kv * d_h))
+    q = rng.standard_normal((H_q, d_h))
+    K = oracle.reconstruct(A, B).reshape(L, H_kv, d_h).transpose(1, 0, 2)
+    S_lm = oracle.chunk_scores(K, q)
+    np.testing.assert_allclose(S_lm, oracle.pooled_scores(A, B, q, H_kv), rtol=1e-12, atol=1e-12)
+    # and against the definition written out
+    n_rep = H_q // H_kv
+    for g in range(H_kv):
+        ref = np.max(np.stack([K[g] @ q[h] for h in range(g * n_rep, (g + 1) * n_rep)]), axis=0) / np.sqrt(d_h)
+        np.testing.assert_allclose(S_lm[g], ref, rtol=1e-13)
+
+
+def test_chunk_budget_and_expansion():
+    assert oracle.chunk_budget(2048, 8, 8192) == 256 and oracle.chunk_budget(10, 4, 100) == 3
+    assert oracle.chunk_budget(1000, 8, 20) == 20
+    rows = oracle.expand_chunks([5, 1], [1, 3], 4, 22)            # union {1, 3, 5}; chunk 5 has two tokens
+    assert rows.tolist() == [4, 5, 6, 7, 12, 13, 14, 15, 20, 21]
+    assert oracle.expand_chunks([0], [], 3, 10).tolist() == [0, 1, 2]
+
+
+def test_selection_by_landmarks_brute_force():
+    rng = np.random.default_rng(44)
+    H_kv, H_q, L, d_h, c, k, o = 2, 4, 37, 6, 5, 11, 2
+    K = _rand_keys(rng, H_kv, L, d_h)
+    q = rng.standard_normal((H_q, d_h))
+    Lm, m, out = oracle.landmarks(K, c, o)
+    rows, S32 = oracle.select_rows_by_landmarks(Lm, out, q, k, c, L)
+    n_c, k_ch = 8, 3
+    for g in range(H_kv):
+        sc = [max(float(Lm[g, j] @ q[h]) for h in (2 * g, 2 * g + 1)) / np.sqrt(d_h) for j in range(n_c)]
+        top = sorted(range(n_c), key=lambda j: (-np.float32(sc[j]), j))[:k_ch]
+        worst = sorted(range(n_c), key=lambda j: (np.float32(m[g, j]), j))[:o]
+        want = sorted(t for j in set(top) | set(worst) for t in range(j * c, min(j * c + c, L)))
+        assert rows[g].tolist() == want
+
+
+def test_landmark_step_with_unit_chunks_equals_the_factor_step():
+    """c = 1, no outliers, landmarks = rows of K^ = A^K B^K_l: the paper's selector and the factor-scoring selector
+    pick the same tokens, and the outputs agree."""
+    rng = np.random.default_rng(45)
+    L, r, H_kv, H_q, d_h, k = 60, 6, 2, 4, 8, 9
+    A_k, A_v = rng.standard_normal((L, r)), rng.standard_normal((L, r))
+    B_k, B_v = rng.standard_normal((r, H_kv * d_h)), rng.standard_normal((r, H_kv * d_h))
+    q = rng.standard_normal((H_q, d_h))
+    out_f, idx_f, _ = oracle.sr_decode(A_k, A_v, B_k, B_v, q, H_kv, k)
+    Lm = oracle.reconstruct(A_k, B_k).reshape(L, H_kv, d_h).transpose(1, 0, 2)
+    out_l, rows, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, np.zeros((H_kv, 0), np.int32), k, 1)
+    for g in range(H_kv):
+        assert rows[g].tolist() == idx_f[g].tolist()
+    np.testing.assert_allclose(out_l, out_f, rtol=1e-11, atol=1e-13)
+    # equal-length row lists: the numpy attention equals the C implementation
+    np.testing.assert_allclose(oracle.gather_attend_rows(A_k, A_v, B_k, B_v, q, [idx_f[0], idx_f[1]]),
+                               oracle.gather_attend(A_k, A_v, B_k, B_v, q, idx_f), rtol=1e-12, atol=1e-14)
+
+
+def test_landmark_step_with_every_chunk_selected_is_dense_attention():
+    rng = np.random.default_rng(46)
+    L, r, H_kv, H_q, d_h, c = 45, 5, 1, 3, 4, 8
+    A_k, A_v = rng.standard_normal((L, r)), rng.standard_normal((L, r))
+    B_k, B_v = rng.standard_normal((r, d_h)), rng.standard_normal((r, d_h))
+    q = rng.standard_normal((H_q, d_h))
+    K = oracle.reconstruct(A_k, B_k)
+    Lm, m, out = oracle.landmarks(K.reshape(L, 1, d_h).transpose(1, 0, 2), c, o=1)
+    got, rows, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, out, L, c)
+    assert rows[0].tolist() == list(range(L))
+    np.testing.assert_allclose(got, oracle.dense(K, oracle.reconstruct(A_v, B_v), q, H_kv), rtol=1e-11, atol=1e-13)
