@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-factorize", action="store_true", help="skip the timing of the prefill-side factorization")
+    ap.add_argument("--no-landmark", action="store_true", help="skip the timing of the landmark-guided step")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise 1 GiB copy kernel three times (reference point for hardware counters)")
@@ -270,6 +271,54 @@ def main():
                                                        "the factors (A B_l), then dense attention"}
         del Ks, Vs
 
+    # ---------------------------------------------------------------- the same step with the paper's own selector
+    # Landmark-guided chunk selection (App. B.1): chunks of c = 8 tokens scored against their mean key, top
+    # ceil(k / c) chunks plus 4 static outlier chunks per KV head, then the same reconstruction and attention.
+    # Landmarks of every resident layer are built once from K = A^K B^K_l (stand-in for post-RoPE keys).
+    landmark = None
+    if not args.no_landmark and w.L >= 64:
+        c_lm, o_lm = 8, 4
+        n_c = -(-w.L // c_lm)
+        lm_ws = torch.empty(xb.xkv_landmark_workspace_bytes(shape, c_lm, o_lm), dtype=torch.uint8, device="cuda")
+        Kscr = torch.empty((w.batch, w.H_kv, w.L, w.d_h), dtype=dt, device="cuda")
+        lms, outls = [], []
+        n_lm_layers = min(n_sets, w.n_groups) * w.G
+        ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ms_build = 0.0
+        for i in range(n_lm_layers):
+            s_i, l_i = divmod(i, w.G)
+            g = groups[s_i]
+            xb.xkv_reconstruct(shape, l_i, g["A_k"], g["B_k"], w.r_k, Kscr)
+            lm_t = torch.empty((w.batch, w.H_kv, n_c, w.d_h), dtype=dt, device="cuda")
+            ol_t = torch.empty((w.batch, w.H_kv, o_lm), dtype=torch.int32, device="cuda")
+            ev_a.record()
+            xb.xkv_landmarks(shape, Kscr, c_lm, o_lm, lm_t, None, ol_t, lm_ws)
+            ev_b.record()
+            torch.cuda.synchronize()
+            ms_build += ev_a.elapsed_time(ev_b)
+            lms.append(lm_t)
+            outls.append(ol_t)
+        del Kscr
+        lstate = {"i": 0}
+
+        def landmark_step():
+            for _ in range(w.n_layers):
+                i = lstate["i"]
+                s_i, l_i = divmod(i, w.G)
+                g = groups[s_i]
+                xb.xkv_sr_decode_landmark(shape, l_i, g["A_k"], g["A_v"], g["B_k"], g["B_v"], qs[s_i][l_i], lms[i],
+                                          outls[i], c_lm, o_lm, out, None, None, None, lm_ws)
+                lstate["i"] = (i + 1) % n_lm_layers
+
+        landmark_step()
+        ms_lm = time_loop(torch, landmark_step, max(2, min(args.steps, 5)))
+        landmark = {"ms_per_step": round(ms_lm, 4), "tokens_per_s": round(w.batch / (ms_lm * 1e-3), 2), "c": c_lm,
+                    "outlier_chunks": o_lm, "rows_per_head_max": (min(-(-w.k // c_lm), n_c) + o_lm) * c_lm,
+                    "landmark_build_ms_per_layer": round(ms_build / n_lm_layers, 4),
+                    "note": "SR decode with landmark-guided chunk selection instead of scoring every token from the "
+                            "factors; same reconstruction and attention kernels"}
+        del lms, outls, lm_ws
+
     # ---------------------------------------------------------------- the step before the path: factorization
     # One layer group's key cache of every sequence (power-law spectrum, full rank) -> A^K, B^K (Eq. 1), as prefill
     # would do once per prompt and group, for keys and for values.  Not part of the decode step or of `value`.
@@ -365,7 +414,7 @@ def main():
                    "factor_sets_in_hbm": n_sets, "copies_rotated": copies},
         "roofline": roofline, "cpu_baseline": cpu, "stages": stages, "dense_baseline": dense,
         "speedup_vs_dense": (round(dense["ms_per_step"] / ms_sr, 3) if dense else None),
-        "factorize": factorize, "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
+        "landmark_selector": landmark, "factorize": factorize, "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
     }
     print(json.dumps(result))
 

@@ -156,6 +156,37 @@ XKV_API xkv_status xkv_factorize_workspace_bytes(const xkv_shape *shape, int32_t
 XKV_API xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32_t iters, uint32_t seed,
                                  void *A_out, void *B_out, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The paper's own selector for Selective Reconstruction (App. B.1 "Landmark-guided Chunk Selector", after ShadowKV),
+ * next to the factor-scoring selector of xkv_sr_decode.  The context is cut into n_c = ceil(L / c) chunks of c
+ * tokens (the last one may be shorter).
+ *
+ * xkv_landmarks (Alg. 1, prefill): K_rope [batch][H_kv][L][d_h] post-RoPE keys in shape->dtype ->
+ *   landmarks_out   [batch][H_kv][n_c][d_h]  chunk means (fp32 sums, rounded once to shape->dtype),
+ *   neg_min_cos_out [batch][H_kv][n_c] fp32 (nullable)  minus the smallest cosine between a key of the chunk and
+ *                   its (unrounded) landmark; a zero vector counts as cosine 0,
+ *   outliers_out    [batch][H_kv][o] int32 (required when o > 0)  ArgTopK(neg_min_cos, o): the o chunks whose
+ *                   minimum cosine is smallest, in the order of xkv_topk (ties: smaller chunk first), ascending.
+ * xkv_sr_decode_landmark (Alg. 2 + Eq. 3, decode): P[h][j] = scale <q_h, landmark[rho(h)][j]>, pooled with the
+ *   maximum over the query heads of a KV head, top k_ch = min(ceil(k / c), n_c) chunks per KV head (k = shape->k is
+ *   the token budget), union with the head's outliers, expansion to token rows; those rows of K and V are
+ *   reconstructed and attended over exactly as in xkv_sr_decode.  The union has between k_ch and k_ch + o chunks:
+ *   rows_out (nullable) [batch][H_kv][(k_ch + o) * c] receives the rows in ascending order, of which the first
+ *   count_out[batch][H_kv] (nullable) are real, the rest 0; score_out (nullable) [batch][H_kv][n_c] the pooled
+ *   chunk scores.  landmarks / outliers are xkv_landmarks' outputs (outliers may be NULL when o == 0).
+ * workspace for both: xkv_landmark_workspace_bytes() bytes, 256-byte aligned (xkv_landmarks needs none for o == 0).
+ * XKV_ERR_INVALID_ARG for c < 1, o < 0 or o > n_c.
+ */
+XKV_API xkv_status xkv_landmark_workspace_bytes(const xkv_shape *shape, int32_t c, int32_t o, size_t *bytes);
+XKV_API xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int32_t c, int32_t o, void *landmarks_out,
+                                 float *neg_min_cos_out, int32_t *outliers_out, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream);
+XKV_API xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                          const void *A_v, const void *B_k, const void *B_v, const void *q,
+                                          const void *landmarks, const int32_t *outliers, int32_t c, int32_t o,
+                                          void *out, int32_t *rows_out, int32_t *count_out, float *score_out,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Measurement aid for callers that want the duration of one kernel rather than of a whole call.
  * Not part of the method.  For stage = 0 (low-rank score kernel), 1 (gather-reconstruct + sparse
  * attention kernel), 2 (dense decode kernel) or 3 (the Gram-matrix product X_cat^T X_cat of xkv_factorize, all

@@ -17,9 +17,9 @@ namespace xkv {
 template <typename T, int JP>
 __global__ __launch_bounds__(256) void gather_attend_generic_kernel(
     const T *__restrict__ A_k, const T *__restrict__ A_v, const T *__restrict__ B_k, const T *__restrict__ B_v,
-    const T *__restrict__ q, const int32_t *__restrict__ idx, float *__restrict__ part_o,
-    float *__restrict__ part_ml, int G, int layer, int L, int r_k, int r_v, int H_kv, int H_q, int d_h, int k,
-    int splits, int chunk, float scale)
+    const T *__restrict__ q, const int32_t *__restrict__ idx, const int32_t *__restrict__ counts,
+    float *__restrict__ part_o, float *__restrict__ part_ml, int G, int layer, int L, int r_k, int r_v, int H_kv,
+    int H_q, int d_h, int k, int splits, int chunk, float scale)
 {
     constexpr int TM = 4;
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
@@ -44,8 +44,13 @@ __global__ __launch_bounds__(256) void gather_attend_generic_kernel(
     const T *Ak = A_k + (size_t)b * L * r_k;
     const T *Av = A_v + (size_t)b * L * r_v;
     const int32_t *ids = idx + ((size_t)b * H_kv + g) * k;
+    int k_eff = k;  // with `counts`, only the first counts[sequence][head] ids of a row are attended over
+    if (counts) {
+        const int cn = counts[b * H_kv + g];
+        k_eff = cn < k ? (cn > 0 ? cn : 0) : k;
+    }
     const int m_begin = split * chunk;
-    const int m_end = (m_begin + chunk < k) ? m_begin + chunk : k;
+    const int m_end = (m_begin + chunk < k_eff) ? m_begin + chunk : k_eff;
 
     for (int m0 = m_begin + w * TM; m0 < m_end; m0 += 4 * TM) {
         int tok[TM];
@@ -134,13 +139,13 @@ __global__ __launch_bounds__(256) void gather_attend_generic_kernel(
 template <typename T>
 static hipError_t launch_generic(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                  const void *B_k, const void *B_v, const void *q, const int32_t *idx, float *part_o,
-                                 float *part_ml, hipStream_t st)
+                                 float *part_ml, hipStream_t st, const int32_t *counts)
 {
     dim3 grid(p.sr_splits, s.H_kv, s.batch), block(256);
 #define XKV_GA_LAUNCH(JP)                                                                                          \
     hipLaunchKernelGGL((gather_attend_generic_kernel<T, JP>), grid, block, 0, st, (const T *)A_k, (const T *)A_v,  \
-                       (const T *)B_k, (const T *)B_v, (const T *)q, idx, part_o, part_ml, s.G, layer, s.L, s.r_k, \
-                       s.r_v, s.H_kv, s.H_q, s.d_h, s.k, p.sr_splits, p.sr_chunk, p.scale)
+                       (const T *)B_k, (const T *)B_v, (const T *)q, idx, counts, part_o, part_ml, s.G, layer,     \
+                       s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.d_h, s.k, p.sr_splits, p.sr_chunk, p.scale)
     profile_begin(1, st);
     if (s.d_h <= 64)
         XKV_GA_LAUNCH(1);
@@ -162,13 +167,14 @@ bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, co
 
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
-                                bool packed, float *part_o, float *part_ml, hipStream_t st)
+                                bool packed, float *part_o, float *part_ml, hipStream_t st, const int32_t *counts)
 {
     if (gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws))
-        return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml, st);
+        return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml, st,
+                                         counts);
     if (s.dtype == XKV_F32)
-        return launch_generic<float>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st);
-    return launch_generic<bf16_t>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st);
+        return launch_generic<float>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts);
+    return launch_generic<bf16_t>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts);
 }
 
 }  // namespace xkv

@@ -130,9 +130,9 @@ __device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const bf16_t *__restrict__ A_k, const bf16_t *__restrict__ A_v, const u32x4_t *__restrict__ pack,
-    const bf16_t *__restrict__ q, const int32_t *__restrict__ idx, float *__restrict__ part_o,
-    float *__restrict__ part_ml, int L, int r_k, int r_v, int H_kv, int H_q, int k, int splits, int chunk, int F16k,
-    int F16v, float scale)
+    const bf16_t *__restrict__ q, const int32_t *__restrict__ idx, const int32_t *__restrict__ counts,
+    float *__restrict__ part_o, float *__restrict__ part_ml, int L, int r_k, int r_v, int H_kv, int H_q, int k,
+    int splits, int chunk, int F16k, int F16v, float scale)
 {
     constexpr int kLdsA = lds_a_bytes(WAVES), TILE = WAVES * 32;  // selected tokens per workgroup iteration
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -155,8 +155,16 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const u32x4_t *Ak = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
     const u32x4_t *Av = reinterpret_cast<const u32x4_t *>(A_v + (size_t)b * L * r_v);
     const int32_t *ids = idx + ((size_t)b * H_kv + g) * k;
+    // with `counts`, only the first counts[sequence][head] of the k ids of a row are attended over; a split that
+    // lies behind them contributes an empty partial (weight 0 in the merge)
+    int k_eff = k;
+    if (counts) {
+        const int cn = counts[b * H_kv + g];
+        k_eff = cn < k ? (cn > 0 ? cn : 0) : k;
+    }
     const int m_begin = split * chunk;
-    const int m_end = m_begin + chunk < k ? m_begin + chunk : k;
+    const int m_end_raw = m_begin + chunk < k_eff ? m_begin + chunk : k_eff;
+    const int m_end = m_end_raw > m_begin ? m_end_raw : m_begin;
     const int n_tiles = (m_end - m_begin + TILE - 1) / TILE;
 
     // The split's token ids are staged in LDS once (clamped into [0, L)), so that the main loop issues no
@@ -166,13 +174,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
         const int t = ids[m_begin + m];
         tok_lds[m] = t < 0 ? 0 : (t >= L ? L - 1 : t);
     }
+    if (m_end == m_begin && tid == 0) tok_lds[0] = 0;  // the prologue below still gathers one (unused) tile
     __syncthreads();
     // the eight rows this lane gathers from in a tile: row 4j + lane/16 of the wavefront's 32-token block
     auto tile_tokens = [&](int tile, int (&tk)[kGroup]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) {
             int m = tile * TILE + w * 32 + 4 * j + (lane >> 4);
-            m = m < m_end - m_begin ? m : m_end - m_begin - 1;
+            m = m < m_end - m_begin ? m : (m_end > m_begin ? m_end - m_begin - 1 : 0);
             tk[j] = tok_lds[m];
         }
     };
@@ -399,7 +408,8 @@ PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k,
 
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
-                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st)
+                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st,
+                                     const int32_t *counts)
 {
     const PackArgs pa = gather_attend_pack_args(s, layer, B_k, B_v, q, pack_ws);
     const int F8k = pa.F8k, F8v = pa.F8v;
@@ -424,8 +434,9 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
         }                                                                                                          \
         profile_begin(1, st);                                                                                      \
         hipLaunchKernelGGL(gather_attend_mfma_kernel<WV>, grid, dim3(WV * 64), lds, st, (const bf16_t *)A_k,       \
-                           (const bf16_t *)A_v, (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, part_o, part_ml, \
-                           s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v, p.scale);     \
+                           (const bf16_t *)A_v, (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, counts, part_o,  \
+                           part_ml, s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v,      \
+                           p.scale);                                                                               \
         profile_end(1, st);                                                                                        \
     } while (0)
     if (p.ga_waves == 8)

@@ -304,6 +304,143 @@ xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32
     return hip_status(launch_factorize(*shape, X, r, iters, seed, A_out, B_out, workspace, (hipStream_t)hip_stream));
 }
 
+}  // extern "C"
+
+namespace {
+
+// Shapes and workspace layout of the landmark-guided step: the reshaped scoring problem (one "sequence" per
+// (sequence, KV head), landmarks in the place of A^K, identity in the place of B^K), the gather-attend problem with
+// the row capacity as k, and where each lives in the workspace.
+struct LandmarkPlan {
+    int n_c, k_ch, k_cap;
+    xkv_shape score_shape, attend_shape, outlier_shape;
+    Plan score_plan, attend_plan, outlier_plan;
+    size_t off_score_ws, off_identity, off_counts, total_decode, total_prefill;
+};
+
+xkv_status make_landmark_plan(const xkv_shape &s, int c, int o, LandmarkPlan &lp)
+{
+    if (c < 1 || o < 0) return XKV_ERR_INVALID_ARG;
+    lp.n_c = ceil_div(s.L, c);
+    if (o > lp.n_c) return XKV_ERR_INVALID_ARG;
+    lp.k_ch = ceil_div(s.k, c) < lp.n_c ? ceil_div(s.k, c) : lp.n_c;
+    if ((long long)(lp.k_ch + o) * c > (1LL << 30)) return XKV_ERR_UNSUPPORTED;
+    lp.k_cap = (lp.k_ch + o) * c;
+    lp.score_shape = s;
+    lp.score_shape.G = 1;
+    lp.score_shape.H_kv = 1;
+    lp.score_shape.H_q = s.H_q / s.H_kv;
+    lp.score_shape.r_k = lp.score_shape.r_v = s.d_h;
+    lp.score_shape.L = lp.n_c;
+    lp.score_shape.k = lp.k_ch;
+    lp.score_shape.batch = s.batch * s.H_kv;
+    if ((long long)lp.score_shape.batch > 65535LL) return XKV_ERR_UNSUPPORTED;
+    make_plan(lp.score_shape, lp.score_plan);
+    lp.attend_shape = s;
+    lp.attend_shape.k = lp.k_cap;
+    make_plan(lp.attend_shape, lp.attend_plan);
+    lp.outlier_shape = s;
+    lp.outlier_shape.L = lp.n_c;
+    lp.outlier_shape.k = o > 0 ? o : 1;
+    make_plan(lp.outlier_shape, lp.outlier_plan);
+    const size_t esz = s.dtype == XKV_F32 ? 4 : 2, rows = (size_t)(s.batch > 0 ? s.batch : 1) * s.H_kv;
+    lp.off_score_ws = align_up(lp.attend_plan.total, 256);
+    lp.off_identity = align_up(lp.off_score_ws + lp.score_plan.total, 256);
+    lp.off_counts = align_up(lp.off_identity + rows * s.d_h * s.d_h * esz, 256);
+    lp.total_decode = align_up(lp.off_counts + rows * sizeof(int32_t), 256);
+    lp.total_prefill = align_up(lp.outlier_plan.total + rows * (size_t)lp.n_c * sizeof(float), 256);
+    return XKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+xkv_status xkv_landmark_workspace_bytes(const xkv_shape *shape, int32_t c, int32_t o, size_t *bytes)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    if (!bytes) return XKV_ERR_INVALID_ARG;
+    LandmarkPlan lp;
+    if ((st = make_landmark_plan(*shape, c, o, lp)) != XKV_OK) return st;
+    *bytes = lp.total_decode > lp.total_prefill ? lp.total_decode : lp.total_prefill;
+    return XKV_OK;
+}
+
+xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int32_t c, int32_t o, void *landmarks_out,
+                         float *neg_min_cos_out, int32_t *outliers_out, void *workspace, size_t workspace_bytes,
+                         void *hip_stream)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    LandmarkPlan lp;
+    if ((st = make_landmark_plan(*shape, c, o, lp)) != XKV_OK) return st;
+    if (!K_rope || !landmarks_out || (o > 0 && !outliers_out)) return XKV_ERR_INVALID_ARG;
+    if (o > 0 && (!workspace || ((uintptr_t)workspace & 255u))) return XKV_ERR_INVALID_ARG;
+    if (o > 0 && workspace_bytes < lp.total_prefill) return XKV_ERR_WORKSPACE;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *neg_m = neg_min_cos_out;
+    if (!neg_m && o > 0) neg_m = at<float>(workspace, align_up(lp.outlier_plan.total, 256));
+    hipError_t e = launch_landmarks(*shape, K_rope, c, landmarks_out, neg_m, stream);
+    if (e == hipSuccess && o > 0)
+        e = launch_topk(lp.outlier_shape, lp.outlier_plan, neg_m, outliers_out, at<uint32_t>(workspace, lp.outlier_plan.off_hist),
+                        at<uint32_t>(workspace, lp.outlier_plan.off_state), false, stream);
+    return hip_status(e);
+}
+
+xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                  const void *B_k, const void *B_v, const void *q, const void *landmarks,
+                                  const int32_t *outliers, int32_t c, int32_t o, void *out, int32_t *rows_out,
+                                  int32_t *count_out, float *score_out, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    LandmarkPlan lp;
+    if ((st = make_landmark_plan(*shape, c, o, lp)) != XKV_OK) return st;
+    if (!A_k || !A_v || !B_k || !B_v || !q || !landmarks || !out || (o > 0 && !outliers) || layer < 0 ||
+        layer >= shape->G)
+        return XKV_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255u)) return XKV_ERR_INVALID_ARG;
+    if (workspace_bytes < lp.total_decode) return XKV_ERR_WORKSPACE;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const Plan &ps = lp.score_plan, &pa = lp.attend_plan;
+    void *ws_s = at<void>(workspace, lp.off_score_ws);
+    void *ident = at<void>(workspace, lp.off_identity);
+    // Alg. 2, scores and pooling: the factor-scoring kernels on (landmarks, identity, queries of one KV head)
+    float *S = score_out ? score_out : at<float>(ws_s, ps.off_score);
+    int32_t *chunks = at<int32_t>(ws_s, ps.off_idx);
+    uint32_t *hist = at<uint32_t>(ws_s, ps.off_hist), *state = at<uint32_t>(ws_s, ps.off_state);
+    bool level0_done = false;
+    hipError_t e = launch_identity(*shape, ident, lp.score_shape.batch, stream);
+    if (e == hipSuccess && ps.score_hist) e = launch_topk_init(ps, state, stream);
+    if (e == hipSuccess)
+        e = launch_score_stage(lp.score_shape, ps, 0, landmarks, ident, q, at<void>(ws_s, ps.off_p), S,
+                               ps.score_hist ? topk_row_hist(ps, state) : nullptr, ps.score_hist ? hist : nullptr,
+                               &level0_done, nullptr, nullptr, stream);
+    // top ceil(k / c) chunks per KV head, union with the outliers, expansion to rows
+    if (e == hipSuccess) e = launch_topk(lp.score_shape, ps, S, chunks, hist, state, level0_done, stream);
+    int32_t *rows = rows_out ? rows_out : at<int32_t>(workspace, pa.off_idx);
+    int32_t *counts = count_out ? count_out : at<int32_t>(workspace, lp.off_counts);
+    if (e == hipSuccess) e = launch_expand_chunks(*shape, chunks, lp.k_ch, outliers, o, c, rows, counts, stream);
+    // Eq. 3 and attention over the rows that are real
+    float *part_o = at<float>(workspace, pa.off_part_o), *part_ml = at<float>(workspace, pa.off_part_ml);
+    void *pack_ws = at<void>(workspace, pa.off_bpack);
+    const bool mfma = gather_attend_uses_mfma(pa, A_k, A_v, B_k, B_v, pack_ws);
+    if (e == hipSuccess)
+        e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, false, part_o, part_ml,
+                                 stream, counts);
+    if (e == hipSuccess)
+        e = launch_combine(*shape, mfma ? pa.sr_splits : pa.sr_splits * 4, part_o, part_ml, out, stream);
+    return hip_status(e);
+}
+
+}  // extern "C"
+
+extern "C" {
+
 xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event)
 {
     if (stage < 0 || stage > 3) return XKV_ERR_INVALID_ARG;

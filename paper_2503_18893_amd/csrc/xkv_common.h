@@ -135,9 +135,11 @@ hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st);
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
                        uint32_t *state, bool level0_done, hipStream_t st);
 // packed: pack_ws already holds this layer's packed B and Q fragments (matrix-core path only).
+// counts (nullable): [batch][H_kv], how many of the s.k ids of each row are real; the rest is ignored.
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
-                                bool packed, float *part_o, float *part_ml, hipStream_t st);
+                                bool packed, float *part_o, float *part_ml, hipStream_t st,
+                                const int32_t *counts = nullptr);
 bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, const void *B_k, const void *B_v,
                              const void *pack_ws);
 PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k, const void *B_v, const void *q,
@@ -147,7 +149,8 @@ int gather_attend_mfma_waves(const xkv_shape &s);
 size_t gather_attend_pack_bytes(const xkv_shape &s);
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
-                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st);
+                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st,
+                                     const int32_t *counts = nullptr);
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st);
 bool dense_mfma_shape_ok(const xkv_shape &s);
@@ -160,6 +163,12 @@ hipError_t launch_reconstruct(const xkv_shape &s, int layer, const void *A, cons
 // Cross-layer factorization of the caches of one group (see factorize.hip).
 bool factorize_shape_ok(const xkv_shape &s, int r);
 size_t factorize_workspace_bytes(const xkv_shape &s, int r);
+// The paper's landmark-guided chunk selector (see landmark.hip).
+hipError_t launch_landmarks(const xkv_shape &s, const void *K_rope, int c, void *landmarks, float *neg_min_cos,
+                            hipStream_t st);
+hipError_t launch_identity(const xkv_shape &s, void *B, int copies, hipStream_t st);
+hipError_t launch_expand_chunks(const xkv_shape &s, const int32_t *chunks, int k_ch, const int32_t *outliers, int o, int c,
+                                int32_t *rows, int32_t *counts, hipStream_t st);
 hipError_t launch_factorize(const xkv_shape &s, const void *X, int r, int iters, uint32_t seed, void *A_out, void *B_out,
                             void *ws, hipStream_t st);
 

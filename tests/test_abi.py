@@ -94,6 +94,26 @@ def test_factorize_validates_on_the_host():
     assert lib.xkv_factorize_workspace_bytes(ctypes.byref(c96), 8, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED
 
 
+def test_landmark_calls_validate_on_the_host():
+    lib = xb.load()
+    good = xb.Shape.of(synth.LLAMA_GROUP)
+    c, null, one = good.c(), ctypes.c_void_p(0), ctypes.c_void_p(256)
+    n = ctypes.c_size_t(0)
+    assert xb.xkv_landmark_workspace_bytes(good, 8, 4) > xb.xkv_workspace_bytes(good)
+    assert lib.xkv_landmark_workspace_bytes(ctypes.byref(c), 0, 0, ctypes.byref(n)) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_landmark_workspace_bytes(ctypes.byref(c), 8, -1, ctypes.byref(n)) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_landmark_workspace_bytes(ctypes.byref(c), 8, good.L, ctypes.byref(n)) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_landmarks(ctypes.byref(c), null, 8, 0, one, null, null, null, 0, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_landmarks(ctypes.byref(c), one, 8, 2, one, null, null, one, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_landmarks(ctypes.byref(c), one, 8, 2, one, null, one, one, 16, null) == xb.XKV_ERR_WORKSPACE
+    args = [ctypes.byref(c), 0, one, one, one, one, one, one, null, 8, 0, one, null, null, null, one]
+    assert lib.xkv_sr_decode_landmark(*args, 16, null) == xb.XKV_ERR_WORKSPACE
+    args[7] = null                                            # no landmarks
+    assert lib.xkv_sr_decode_landmark(*args, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
+    args[7], args[10] = one, 3                                # outliers announced but not given
+    assert lib.xkv_sr_decode_landmark(*args, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
+
+
 def test_binding_has_no_cpu_fallback(monkeypatch):
     monkeypatch.setattr(xb, "_lib", None)
     monkeypatch.setattr(xb, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
