@@ -287,9 +287,29 @@ def select_rows_by_landmarks(Lm, outliers, q, k, c, L, scale=None):
     return rows, S32
 
 
-def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None):
+def rope(X, positions, theta):
+    """Rotary position embedding of rows X [n][d_h] at the given integer positions (the reconstructed keys are
+    pre-RoPE, Sec. 4 and App. C.6 "Setup"; the rotation is re-applied to the rows that are reconstructed).
+    Convention of the Llama / Qwen2 reference implementations: channel j < d_h/2 is paired with channel j + d_h/2,
+    the pair is rotated by the angle position * theta^(-2j/d_h):
+      out[j] = x[j] cos - x[j + d_h/2] sin,   out[j + d_h/2] = x[j + d_h/2] cos + x[j] sin."""
+    X = widen(X)
+    n, d_h = X.shape
+    half = d_h // 2
+    assert d_h == 2 * half
+    inv_freq = float(theta) ** (-np.arange(half, dtype=np.float64) * 2.0 / d_h)
+    ang = np.asarray(positions, np.float64)[:, None] * inv_freq[None, :]
+    cs, sn = np.cos(ang), np.sin(ang)
+    out = np.empty_like(X)
+    out[:, :half] = X[:, :half] * cs - X[:, half:] * sn
+    out[:, half:] = X[:, half:] * cs + X[:, :half] * sn
+    return out
+
+
+def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None, rope_theta=None):
     """Steps 5-6 (Eq. 3 and softmax attention) for per-head row lists of different lengths: out[H_q][d_h].
-    Written out in numpy."""
+    With rope_theta, every reconstructed key row is rotated to its position (= its row number) before it meets
+    the (already rotated) query; values are not rotated.  Written out in numpy."""
     A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
     H_q, d_h = q.shape
     H_kv = len(rows)
@@ -299,6 +319,8 @@ def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None):
     for g in range(H_kv):
         cols = slice(g * d_h, (g + 1) * d_h)
         K_sel = A_k[rows[g]] @ B_k[:, cols]
+        if rope_theta is not None:
+            K_sel = rope(K_sel, rows[g], rope_theta)
         V_sel = A_v[rows[g]] @ B_v[:, cols]
         for h in range(g * n_rep, (g + 1) * n_rep):
             z = scale * (K_sel @ q[h])
@@ -307,13 +329,14 @@ def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None):
     return out
 
 
-def sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outliers, k, c, scale=None):
+def sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outliers, k, c, scale=None, rope_theta=None):
     """SR step with the paper's own selector (App. B.1): chunks are scored against their landmarks, the top
     ceil(k / c) chunks per KV head plus the static outliers are expanded to rows, those rows are reconstructed
-    (Eq. 3) and attended over.  Returns (out[H_q][d_h], rows, S32[H_kv][n_c])."""
+    (Eq. 3), with rope_theta rotated to their positions, and attended over.  Returns (out[H_q][d_h], rows,
+    S32[H_kv][n_c])."""
     L = widen(A_k).shape[0]
     rows, S32 = select_rows_by_landmarks(Lm, outliers, q, k, c, L, scale)
-    return gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale), rows, S32
+    return gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale, rope_theta), rows, S32
 
 
 def factorize(X_cat, r):

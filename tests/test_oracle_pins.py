@@ -488,3 +488,47 @@ def test_landmark_step_with_every_chunk_selected_is_dense_attention():
     got, rows, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, out, L, c)
     assert rows[0].tolist() == list(range(L))
     np.testing.assert_allclose(got, oracle.dense(K, oracle.reconstruct(A_v, B_v), q, H_kv), rtol=1e-11, atol=1e-13)
+
+
+# ----------------------------------------------------------------- rotary embedding of reconstructed rows
+def test_rope_is_a_rotation_of_each_channel_pair_by_position_times_frequency():
+    """Independent form: the pair (x[j], x[j + d/2]) as a complex number times exp(i p theta^(-2j/d))."""
+    rng = np.random.default_rng(51)
+    n, d, theta = 7, 8, 10000.0
+    X = rng.standard_normal((n, d))
+    pos = np.array([0, 1, 2, 5, 100, 4097, 65535])
+    got = oracle.rope(X, pos, theta)
+    z = (X[:, :d // 2] + 1j * X[:, d // 2:]) * np.exp(1j * pos[:, None] * theta ** (-np.arange(d // 2) / (d // 2)))
+    np.testing.assert_allclose(got[:, :d // 2], z.real, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(got[:, d // 2:], z.imag, rtol=1e-11, atol=1e-12)
+    np.testing.assert_array_equal(got[0], X[0])                                  # position 0 is the identity
+    np.testing.assert_allclose((got ** 2).sum(axis=1), (X ** 2).sum(axis=1), rtol=1e-12)
+    # two channels, frequency 1: the textbook 2-D rotation by `position` radians
+    np.testing.assert_allclose(oracle.rope(np.array([[1.0, 0.0]]), [3], 10000.0), [[np.cos(3.0), np.sin(3.0)]], rtol=1e-13)
+
+
+def test_rope_scores_depend_on_the_distance_only():
+    rng = np.random.default_rng(52)
+    d, theta = 16, 500000.0
+    q, k = rng.standard_normal((1, d)), rng.standard_normal((1, d))
+    a = float(oracle.rope(q, [40], theta) @ oracle.rope(k, [33], theta).T)
+    b = float(oracle.rope(q, [1007], theta) @ oracle.rope(k, [1000], theta).T)
+    assert abs(a - b) <= 1e-10 * (np.abs(q).sum() * np.abs(k).sum())
+
+
+def test_landmark_step_with_rope_and_every_chunk_selected_is_dense_attention_on_rotated_keys():
+    rng = np.random.default_rng(53)
+    L, r, H_kv, H_q, d_h, c, theta = 40, 5, 2, 4, 8, 4, 10000.0
+    A_k, A_v = rng.standard_normal((L, r)), rng.standard_normal((L, r))
+    B_k, B_v = rng.standard_normal((r, H_kv * d_h)), rng.standard_normal((r, H_kv * d_h))
+    q = rng.standard_normal((H_q, d_h))
+    K_pre = oracle.reconstruct(A_k, B_k).reshape(L, H_kv, d_h).transpose(1, 0, 2)
+    K_rope = np.stack([oracle.rope(K_pre[g], np.arange(L), theta) for g in range(H_kv)])
+    Lm, _, outl = oracle.landmarks(K_rope, c, o=1)
+    got, rows, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outl, L, c, rope_theta=theta)
+    assert all(rw.tolist() == list(range(L)) for rw in rows)
+    K_flat = K_rope.transpose(1, 0, 2).reshape(L, H_kv * d_h)
+    np.testing.assert_allclose(got, oracle.dense(K_flat, oracle.reconstruct(A_v, B_v), q, H_kv), rtol=1e-11, atol=1e-13)
+    # without the rotation the result differs: the rotation is not a no-op in this check
+    plain, _, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outl, L, c)
+    assert np.abs(plain - got).max() > 1e-3
