@@ -511,8 +511,8 @@ def test_rope_scores_depend_on_the_distance_only():
     rng = np.random.default_rng(52)
     d, theta = 16, 500000.0
     q, k = rng.standard_normal((1, d)), rng.standard_normal((1, d))
-    a = float(oracle.rope(q, [40], theta) @ oracle.rope(k, [33], theta).T)
-    b = float(oracle.rope(q, [1007], theta) @ oracle.rope(k, [1000], theta).T)
+    a = float((oracle.rope(q, [40], theta) @ oracle.rope(k, [33], theta).T)[0, 0])
+    b = float((oracle.rope(q, [1007], theta) @ oracle.rope(k, [1000], theta).T)[0, 0])
     assert abs(a - b) <= 1e-10 * (np.abs(q).sum() * np.abs(k).sum())
 
 
