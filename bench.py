@@ -312,9 +312,29 @@ def main():
 
         landmark_step()
         ms_lm = time_loop(torch, landmark_step, max(2, min(args.steps, 5)))
+        rope_theta = 500000.0     # Llama-3.1's rotary base; reconstructed key rows are rotated to their positions
+
+        def landmark_rope_step():
+            for _ in range(w.n_layers):
+                i = lstate["i"]
+                s_i, l_i = divmod(i, w.G)
+                g = groups[s_i]
+                xb.xkv_sr_decode_landmark(shape, l_i, g["A_k"], g["A_v"], g["B_k"], g["B_v"], qs[s_i][l_i], lms[i],
+                                          outls[i], c_lm, o_lm, out, None, None, None, lm_ws, rope_theta=rope_theta)
+                lstate["i"] = (i + 1) % n_lm_layers
+
+        ms_lm_rope = None
+        try:
+            landmark_rope_step()
+            ms_lm_rope = time_loop(torch, landmark_rope_step, max(2, min(args.steps, 5)))
+        except xb.XkvError:
+            pass                  # head widths the rotation does not cover
         landmark = {"ms_per_step": round(ms_lm, 4), "tokens_per_s": round(w.batch / (ms_lm * 1e-3), 2), "c": c_lm,
                     "outlier_chunks": o_lm, "rows_per_head_max": (min(-(-w.k // c_lm), n_c) + o_lm) * c_lm,
                     "landmark_build_ms_per_layer": round(ms_build / n_lm_layers, 4),
+                    "with_rope": None if ms_lm_rope is None else {
+                        "ms_per_step": round(ms_lm_rope, 4), "tokens_per_s": round(w.batch / (ms_lm_rope * 1e-3), 2),
+                        "rope_theta": rope_theta},
                     "note": "SR decode with landmark-guided chunk selection instead of scoring every token from the "
                             "factors; same reconstruction and attention kernels"}
         del lms, outls, lm_ws

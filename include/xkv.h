@@ -173,7 +173,9 @@ XKV_API xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t 
  *   reconstructed and attended over exactly as in xkv_sr_decode.  The union has between k_ch and k_ch + o chunks:
  *   rows_out (nullable) [batch][H_kv][(k_ch + o) * c] receives the rows in ascending order, of which the first
  *   count_out[batch][H_kv] (nullable) are real, the rest 0; score_out (nullable) [batch][H_kv][n_c] the pooled
- *   chunk scores.  landmarks / outliers are xkv_landmarks' outputs (outliers may be NULL when o == 0).
+ *   chunk scores.  landmarks / outliers are xkv_landmarks' outputs (outliers may be NULL when o == 0).  rope_theta
+ *   as in xkv_gather_attend_ex below: with landmarks of post-RoPE keys and factors of pre-RoPE keys this is the
+ *   paper's arrangement; 0 leaves the reconstructed rows as they are.
  * workspace for both: xkv_landmark_workspace_bytes() bytes, 256-byte aligned (xkv_landmarks needs none for o == 0).
  * XKV_ERR_INVALID_ARG for c < 1, o < 0 or o > n_c.
  */
@@ -184,8 +186,24 @@ XKV_API xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int
 XKV_API xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
                                           const void *A_v, const void *B_k, const void *B_v, const void *q,
                                           const void *landmarks, const int32_t *outliers, int32_t c, int32_t o,
-                                          void *out, int32_t *rows_out, int32_t *count_out, float *score_out,
-                                          void *workspace, size_t workspace_bytes, void *hip_stream);
+                                          float rope_theta, void *out, int32_t *rows_out, int32_t *count_out,
+                                          float *score_out, void *workspace, size_t workspace_bytes,
+                                          void *hip_stream);
+
+/*
+ * xkv_gather_attend with two options (stages 3-4 of the step on their own):
+ *   counts (nullable) [batch][H_kv]: only the first counts[..] of the k ids of a row are attended over (row lists of
+ *     different lengths, as the landmark selector produces them; the other ids must still lie in [0, L));
+ *   rope_theta > 0: the cache was factorized before the rotary position embedding (Sec. 4 "Implementation details",
+ *     App. C.6 "Setup"), so every reconstructed key row is rotated to its position, which is its row number t, before
+ *     it meets the (already rotated) query: channel j < d_h/2 is paired with channel j + d_h/2 (Llama / Qwen2
+ *     convention) and the pair is turned by t * rope_theta^(-2j/d_h).  Values are not rotated.  0 = no rotation.
+ *     XKV_ERR_UNSUPPORTED unless d_h is even and (d_h <= 64 or d_h/2 is a multiple of 64).
+ */
+XKV_API xkv_status xkv_gather_attend_ex(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                        const void *A_v, const void *B_k, const void *B_v, const void *q,
+                                        const int32_t *idx, const int32_t *counts, float rope_theta, void *out,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Measurement aid for callers that want the duration of one kernel rather than of a whole call.
  * Not part of the method.  For stage = 0 (low-rank score kernel), 1 (gather-reconstruct + sparse

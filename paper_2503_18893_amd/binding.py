@@ -19,7 +19,8 @@ DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
 
 ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score",
                 "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_factorize_workspace_bytes", "xkv_factorize",
-                "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_profile_kernel", "xkv_status_string", "xkv_version")
+                "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_gather_attend_ex",
+                "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
 class XkvError(RuntimeError):
@@ -86,12 +87,14 @@ def load() -> ctypes.CDLL:
         lib.xkv_factorize.argtypes = [sp, vp, i32, i32, ctypes.c_uint32, vp, vp, vp, sz, vp]
         lib.xkv_landmark_workspace_bytes.argtypes = [sp, i32, i32, ctypes.POINTER(sz)]
         lib.xkv_landmarks.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
-        lib.xkv_sr_decode_landmark.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_sr_decode_landmark.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
+                                               vp, vp, sz, vp]
+        lib.xkv_gather_attend_ex.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:14]:
+        for name in ENTRY_POINTS[:15]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -199,10 +202,19 @@ def xkv_landmarks(shape, K_rope, c, o, landmarks_out, neg_min_cos_out, outliers_
                                 _ptr(outliers_out), _ptr(workspace), nbytes, _stream(stream)), "xkv_landmarks")
 
 
+def xkv_gather_attend_ex(shape, layer_in_group, A_k, A_v, B_k, B_v, q, idx, counts, rope_theta, out, workspace,
+                         stream=None):
+    _check(load().xkv_gather_attend_ex(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
+                                       _ptr(B_v), _ptr(q), _ptr(idx), _ptr(counts), float(rope_theta), _ptr(out),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_gather_attend_ex")
+
+
 def xkv_sr_decode_landmark(shape, layer_in_group, A_k, A_v, B_k, B_v, q, landmarks, outliers, c, o, out, rows_out,
-                           count_out, score_out, workspace, stream=None):
+                           count_out, score_out, workspace, stream=None, rope_theta=0.0):
     _check(load().xkv_sr_decode_landmark(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
-                                         _ptr(B_v), _ptr(q), _ptr(landmarks), _ptr(outliers), c, o, _ptr(out),
+                                         _ptr(B_v), _ptr(q), _ptr(landmarks), _ptr(outliers), c, o, float(rope_theta),
+                                         _ptr(out),
                                          _ptr(rows_out), _ptr(count_out), _ptr(score_out), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(stream)),
            "xkv_sr_decode_landmark")

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void gather_attend_generic_kernel(
     const T *__restrict__ A_k, const T *__restrict__ A_v, const T *__restrict__ B_k, const T *__restrict__ B_v,
     const T *__restrict__ q, const int32_t *__restrict__ idx, const int32_t *__restrict__ counts,
     float *__restrict__ part_o, float *__restrict__ part_ml, int G, int layer, int L, int r_k, int r_v, int H_kv,
-    int H_q, int d_h, int k, int splits, int chunk, float scale)
+    int H_q, int d_h, int k, int splits, int chunk, float scale, float rope_theta)
 {
     constexpr int TM = 4;
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void gather_attend_generic_kernel(
             t = t < 0 ? 0 : (t >= L ? L - 1 : t);  // ids are validated by contract; never read out of bounds
             tok[mm] = t;
         }
-        float kh[TM][JP], vh[TM][JP];
+        float kh[TM][JP], vh[TM][JP], vrot[TM][JP];
 #pragma unroll
         for (int mm = 0; mm < TM; ++mm)
 #pragma unroll
@@ -94,6 +94,36 @@ __global__ __launch_bounds__(256) void gather_attend_generic_kernel(
 #pragma unroll
                 for (int jj = 0; jj < JP; ++jj) vh[mm][jj] = fmaf(a, bv[jj], vh[mm][jj]);
             }
+        }
+        if (rope_theta > 0.0f) {
+            // The reconstructed key rows are pre-RoPE: rotate each to its position (its row number).  Channel
+            // j < d_h/2 is paired with j + d_h/2; the partner sits in this lane's other register when d_h/2 is a
+            // multiple of 64, else (d_h <= 64) in lane j +- d_h/2 of the same register.  Angles in double.
+            const int half = d_h / 2;
+#pragma unroll
+            for (int mm = 0; mm < TM; ++mm)
+#pragma unroll
+                for (int jj = 0; jj < JP; ++jj) {
+                    const int j = lane + jj * kWave;
+                    const bool low = j < half;
+                    float partner;
+                    if constexpr (JP >= 2)
+                        partner = kh[mm][(jj + JP / 2) % JP];  // d_h = 64 JP: the partner is JP / 2 registers away
+                    else
+                        partner = __shfl(kh[mm][jj], low ? lane + half : lane - half, kWave);
+                    const int jf = low ? j : j - half;
+                    float cs = 1.0f, sn = 0.0f;
+                    if (j < d_h) {
+                        const double ang = (double)tok[mm] * pow((double)rope_theta, -2.0 * (double)jf / (double)d_h);
+                        cs = (float)cos(ang);
+                        sn = (float)sin(ang);
+                    }
+                    vrot[mm][jj] = low ? kh[mm][jj] * cs - partner * sn : kh[mm][jj] * cs + partner * sn;
+                }
+#pragma unroll
+            for (int mm = 0; mm < TM; ++mm)
+#pragma unroll
+                for (int jj = 0; jj < JP; ++jj) kh[mm][jj] = vrot[mm][jj];
         }
 #pragma unroll
         for (int mm = 0; mm < TM; ++mm) {
@@ -139,13 +169,13 @@ __global__ __launch_bounds__(256) void gather_attend_generic_kernel(
 template <typename T>
 static hipError_t launch_generic(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                  const void *B_k, const void *B_v, const void *q, const int32_t *idx, float *part_o,
-                                 float *part_ml, hipStream_t st, const int32_t *counts)
+                                 float *part_ml, hipStream_t st, const int32_t *counts, float rope_theta)
 {
     dim3 grid(p.sr_splits, s.H_kv, s.batch), block(256);
 #define XKV_GA_LAUNCH(JP)                                                                                          \
     hipLaunchKernelGGL((gather_attend_generic_kernel<T, JP>), grid, block, 0, st, (const T *)A_k, (const T *)A_v,  \
                        (const T *)B_k, (const T *)B_v, (const T *)q, idx, counts, part_o, part_ml, s.G, layer,     \
-                       s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.d_h, s.k, p.sr_splits, p.sr_chunk, p.scale)
+                       s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.d_h, s.k, p.sr_splits, p.sr_chunk, p.scale, rope_theta)
     profile_begin(1, st);
     if (s.d_h <= 64)
         XKV_GA_LAUNCH(1);
@@ -158,6 +188,9 @@ static hipError_t launch_generic(const xkv_shape &s, const Plan &p, int layer, c
     return hipGetLastError();
 }
 
+// Channel pairs (j, j + d_h/2) must sit in one lane or in one register of the general kernel.
+bool rope_shape_ok(const xkv_shape &s) { return s.d_h % 2 == 0 && (s.d_h <= 64 || (s.d_h / 2) % 64 == 0); }
+
 bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, const void *B_k, const void *B_v,
                              const void *pack_ws)
 {
@@ -167,14 +200,15 @@ bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, co
 
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
-                                bool packed, float *part_o, float *part_ml, hipStream_t st, const int32_t *counts)
+                                bool packed, float *part_o, float *part_ml, hipStream_t st, const int32_t *counts,
+                                float rope_theta)
 {
     if (gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws))
         return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml, st,
-                                         counts);
+                                         counts, rope_theta);
     if (s.dtype == XKV_F32)
-        return launch_generic<float>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts);
-    return launch_generic<bf16_t>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts);
+        return launch_generic<float>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts, rope_theta);
+    return launch_generic<bf16_t>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts, rope_theta);
 }
 
 }  // namespace xkv

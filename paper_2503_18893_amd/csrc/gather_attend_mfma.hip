@@ -19,6 +19,8 @@
 #include <type_traits>
 
 #include "xkv_common.h"
+
+#include <cmath>
 #include "prepass.h"
 
 namespace xkv {
@@ -127,12 +129,23 @@ __device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 
 // group are copied straight from global memory into the other, and every wavefront has the gathered pieces of
 // the next two groups in flight in registers.
 // Eight wavefronts of 32 tokens each: two share a SIMD, so one multiplies while the other waits for memory.
-template <int WAVES>
+// ROPE: the reconstructed key rows are pre-RoPE (Sec. 4, App. C.6 "Setup") and are rotated to their position (the
+// row number) before they meet the query: channel j < 64 is paired with channel j + 64 (Llama / Qwen2 convention) and
+// the pair is turned by position * theta^(-j/64).  In the K^T tile both channels of a pair sit in the same lane (blocks
+// db and db + 2, same register), so the rotation is register-local.  The angle in revolutions is formed from the
+// position split into position / 256 and position % 256 against two per-channel constants (the fraction of 256
+// revolutions and of one), which keeps it accurate to 2^-16 of a turn over the whole context, and goes through the
+// hardware sine and cosine; the kernel is bound by its gathers, so the extra arithmetic is hidden.
+struct RopeTable {
+    float f0[64], f1[64];  // theta^(-j/64) / 2 pi, and frac(256 * that)
+};
+
+template <int WAVES, bool ROPE>
 __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const bf16_t *__restrict__ A_k, const bf16_t *__restrict__ A_v, const u32x4_t *__restrict__ pack,
     const bf16_t *__restrict__ q, const int32_t *__restrict__ idx, const int32_t *__restrict__ counts,
     float *__restrict__ part_o, float *__restrict__ part_ml, int L, int r_k, int r_v, int H_kv, int H_q, int k,
-    int splits, int chunk, int F16k, int F16v, float scale)
+    int splits, int chunk, int F16k, int F16v, float scale, const RopeTable rope)
 {
     constexpr int kLdsA = lds_a_bytes(WAVES), TILE = WAVES * 32;  // selected tokens per workgroup iteration
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -169,7 +182,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
 
     // The split's token ids are staged in LDS once (clamped into [0, L)), so that the main loop issues no
     // global load other than its prefetches: a wait on an id would otherwise drain the whole prefetch queue.
-    int *tok_lds = reinterpret_cast<int *>(smem_raw + kLdsB + kLdsA + kLdsQ);  // [chunk]
+    float *rope_lds = reinterpret_cast<float *>(smem_raw + kLdsB + kLdsA + kLdsQ);  // [128] (ROPE only)
+    if constexpr (ROPE) {
+        if (tid < 64) rope_lds[tid] = rope.f0[tid];
+        else if (tid < 128) rope_lds[tid] = rope.f1[tid - 64];
+    }
+    int *tok_lds = reinterpret_cast<int *>(smem_raw + kLdsB + kLdsA + kLdsQ + (ROPE ? 512 : 0));  // [chunk]
     for (int m = tid; m < m_end - m_begin; m += WAVES * 64) {
         const int t = ids[m_begin + m];
         tok_lds[m] = t < 0 ? 0 : (t >= L ? L - 1 : t);
@@ -264,6 +282,24 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
             run_group<true, kGroup, WAVES>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
         }
         {
+                if constexpr (ROPE) {
+                    // K^T tile: lane (token n, hf), register v of block db <-> channel 32 db + 8(v/4) + 4hf + v%4
+                    int ml = tile * TILE + w * 32 + n;
+                    ml = ml < m_end - m_begin ? ml : (m_end > m_begin ? m_end - m_begin - 1 : 0);
+                    const int tpos = tok_lds[ml];
+                    const float t_hi = (float)(tpos >> 8), t_lo = (float)(tpos & 255);
+#pragma unroll
+                    for (int db = 0; db < 2; ++db)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int j = 32 * db + 8 * (v / 4) + 4 * hf + (v % 4);
+                            const float rev = __builtin_amdgcn_fractf(t_hi * rope_lds[64 + j] + t_lo * rope_lds[j]);
+                            const float sn = __builtin_amdgcn_sinf(rev), cs = __builtin_amdgcn_cosf(rev);
+                            const float x = acc[db][v], y = acc[db + 2][v];
+                            acc[db][v] = x * cs - y * sn;
+                            acc[db + 2][v] = y * cs + x * sn;
+                        }
+                }
                 // (2) Z^T = K^ Q^T: lane (head slot n, hf), register v <-> token 8(v/4) + 4hf + v%4 of the block
                 f32x16_t Z;
 #pragma unroll
@@ -409,8 +445,17 @@ PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k,
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
                                      void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st,
-                                     const int32_t *counts)
+                                     const int32_t *counts, float rope_theta)
 {
+    RopeTable rope{};
+    const bool use_rope = rope_theta > 0.0f;
+    if (use_rope)
+        for (int j = 0; j < 64; ++j) {
+            const double f = std::pow((double)rope_theta, -(double)j / 64.0) / 6.283185307179586476925286766559;
+            const double f256 = 256.0 * f;
+            rope.f0[j] = (float)f;
+            rope.f1[j] = (float)(f256 - std::floor(f256));
+        }
     const PackArgs pa = gather_attend_pack_args(s, layer, B_k, B_v, q, pack_ws);
     const int F8k = pa.F8k, F8v = pa.F8v;
     hipError_t e = hipSuccess;
@@ -421,28 +466,36 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
     }
     if (p.sr_chunk > kMaxChunkTokens) return hipErrorInvalidValue;
     dim3 grid((unsigned)((long long)p.sr_splits * s.H_kv * s.batch));
-#define XKV_GA_LAUNCH(WV)                                                                                          \
+#define XKV_GA_LAUNCH(WV, RP)                                                                                      \
     do {                                                                                                           \
-        const size_t lds = kLdsB + lds_a_bytes(WV) + kLdsQ + (size_t)p.sr_chunk * 4; /* B, A tiles, Q, token ids */ \
+        /* B, A tiles, Q, (rotation constants,) token ids */                                                      \
+        const size_t lds = kLdsB + lds_a_bytes(WV) + kLdsQ + (RP ? 512 : 0) + (size_t)p.sr_chunk * 4;              \
         static bool attr_set = false;                                                                              \
         if (!attr_set) {                                                                                           \
-            e = hipFuncSetAttribute((const void *)gather_attend_mfma_kernel<WV>,                                   \
+            e = hipFuncSetAttribute((const void *)gather_attend_mfma_kernel<WV, RP>,                               \
                                     hipFuncAttributeMaxDynamicSharedMemorySize,                                    \
-                                    kLdsB + lds_a_bytes(WV) + kLdsQ + kMaxChunkTokens * 4);                        \
+                                    kLdsB + lds_a_bytes(WV) + kLdsQ + 512 + kMaxChunkTokens * 4);                  \
             if (e != hipSuccess) return e;                                                                         \
             attr_set = true;                                                                                       \
         }                                                                                                          \
         profile_begin(1, st);                                                                                      \
-        hipLaunchKernelGGL(gather_attend_mfma_kernel<WV>, grid, dim3(WV * 64), lds, st, (const bf16_t *)A_k,       \
+        hipLaunchKernelGGL((gather_attend_mfma_kernel<WV, RP>), grid, dim3(WV * 64), lds, st, (const bf16_t *)A_k, \
                            (const bf16_t *)A_v, (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, counts, part_o,  \
                            part_ml, s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v,      \
-                           p.scale);                                                                               \
+                           p.scale, rope);                                                                         \
         profile_end(1, st);                                                                                        \
     } while (0)
-    if (p.ga_waves == 8)
-        XKV_GA_LAUNCH(8);
-    else
-        XKV_GA_LAUNCH(4);
+    if (p.ga_waves == 8) {
+        if (use_rope)
+            XKV_GA_LAUNCH(8, true);
+        else
+            XKV_GA_LAUNCH(8, false);
+    } else {
+        if (use_rope)
+            XKV_GA_LAUNCH(4, true);
+        else
+            XKV_GA_LAUNCH(4, false);
+    }
 #undef XKV_GA_LAUNCH
     return hipGetLastError();
 }

@@ -391,9 +391,9 @@ xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int32_t c, 
 
 xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
                                   const void *B_k, const void *B_v, const void *q, const void *landmarks,
-                                  const int32_t *outliers, int32_t c, int32_t o, void *out, int32_t *rows_out,
-                                  int32_t *count_out, float *score_out, void *workspace, size_t workspace_bytes,
-                                  void *hip_stream)
+                                  const int32_t *outliers, int32_t c, int32_t o, float rope_theta, void *out,
+                                  int32_t *rows_out, int32_t *count_out, float *score_out, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream)
 {
     xkv_status st = validate(shape);
     if (st != XKV_OK) return st;
@@ -402,6 +402,8 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     if (!A_k || !A_v || !B_k || !B_v || !q || !landmarks || !out || (o > 0 && !outliers) || layer < 0 ||
         layer >= shape->G)
         return XKV_ERR_INVALID_ARG;
+    if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return XKV_ERR_INVALID_ARG;
+    if (rope_theta > 0.0f && !rope_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255u)) return XKV_ERR_INVALID_ARG;
     if (workspace_bytes < lp.total_decode) return XKV_ERR_WORKSPACE;
     if (shape->batch == 0) return XKV_OK;
@@ -431,7 +433,7 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     const bool mfma = gather_attend_uses_mfma(pa, A_k, A_v, B_k, B_v, pack_ws);
     if (e == hipSuccess)
         e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, false, part_o, part_ml,
-                                 stream, counts);
+                                 stream, counts, rope_theta);
     if (e == hipSuccess)
         e = launch_combine(*shape, mfma ? pa.sr_splits : pa.sr_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
@@ -440,6 +442,30 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
 }  // extern "C"
 
 extern "C" {
+
+xkv_status xkv_gather_attend_ex(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                const void *B_k, const void *B_v, const void *q, const int32_t *idx,
+                                const int32_t *counts, float rope_theta, void *out, void *workspace,
+                                size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    xkv_status st = prepare(shape, workspace, workspace_bytes, p);
+    if (st != XKV_OK) return st;
+    if (!A_k || !A_v || !B_k || !B_v || !q || !idx || !out || layer < 0 || layer >= shape->G)
+        return XKV_ERR_INVALID_ARG;
+    if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return XKV_ERR_INVALID_ARG;
+    if (rope_theta > 0.0f && !rope_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *part_o = at<float>(workspace, p.off_part_o);
+    float *part_ml = at<float>(workspace, p.off_part_ml);
+    void *pack_ws = at<void>(workspace, p.off_bpack);
+    const bool mfma = gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws);
+    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, false, part_o, part_ml,
+                                        stream, counts, rope_theta);
+    if (e == hipSuccess) e = launch_combine(*shape, mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
+    return hip_status(e);
+}
 
 xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event)
 {

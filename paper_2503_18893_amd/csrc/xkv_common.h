@@ -139,7 +139,9 @@ hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
                                 bool packed, float *part_o, float *part_ml, hipStream_t st,
-                                const int32_t *counts = nullptr);
+                                const int32_t *counts = nullptr, float rope_theta = 0.0f);
+// rope_theta > 0: the reconstructed key rows are rotated to their positions (RoPE base theta) before the scores.
+bool rope_shape_ok(const xkv_shape &s);
 bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, const void *B_k, const void *B_v,
                              const void *pack_ws);
 PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k, const void *B_v, const void *q,
@@ -150,7 +152,7 @@ size_t gather_attend_pack_bytes(const xkv_shape &s);
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
                                      void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st,
-                                     const int32_t *counts = nullptr);
+                                     const int32_t *counts = nullptr, float rope_theta = 0.0f);
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st);
 bool dense_mfma_shape_ok(const xkv_shape &s);

@@ -6,7 +6,11 @@ Chain of strict links, as for the factor-scoring step (each stage is fed what th
   (ii)  xkv_sr_decode_landmark: pooled chunk scores vs oracle.chunk_scores(stored landmarks) within tolerance
         rows[:count]              vs oracle: top chunks of the GPU's scores, union, expansion identical
         out                       vs oracle.gather_attend_rows on the GPU's rows              within tolerance
-Post-RoPE keys are stood in for by K = A^K B^K_l (this build applies no rotation anywhere).
+  (iii) xkv_gather_attend_ex: row counts and the rotary embedding of the reconstructed key rows (Sec. 4) vs
+        oracle.gather_attend_rows(rope_theta) on random rows over contexts up to 131072 tokens    within tolerance
+  (iv)  factors of pre-RoPE keys + landmarks of post-RoPE keys + rotation of the reconstructed rows: the paper's
+        arrangement, checked against dense attention over the rotated keys when every chunk is selected
+In (i)-(ii) the post-RoPE keys are stood in for by K = A^K B^K_l and no rotation is applied.
 Tolerance: max|gpu - ref| / max|ref|, 1e-5 for fp32 and 2e-2 for bf16 storage; cosines absolute 1e-4.
 """
 import numpy as np
@@ -169,3 +173,89 @@ def test_landmark_step_at_full_size_sampled():
                                         qh, [want])
         got = synth.storage_to_f64(synth.to_host(out[b, h * n_rep:(h + 1) * n_rep]))
         assert max_rel(got, ref) <= TOL["bf16"], (b, h)
+
+
+# ----------------------------------------------------------------- rotary embedding of the reconstructed rows
+ROPE_CASES = {
+    # name: workload fields, theta   (k ids per head are drawn at random over the whole context)
+    "generic_f32_dh32": (dict(G=1, H_kv=2, H_q=4, d_h=32, r_k=8, r_v=8, L=5000, k=40, batch=2, dtype="f32"), 10000.0),
+    "generic_bf16_dh64": (dict(G=1, H_kv=2, H_q=4, d_h=64, r_k=16, r_v=16, L=3000, k=70, batch=1, dtype="bf16"), 10000.0),
+    "mfma_bf16_dh128": (dict(G=2, H_kv=2, H_q=8, d_h=128, r_k=64, r_v=32, L=70000, k=300, batch=2, dtype="bf16"), 500000.0),
+    "mfma_bf16_long_rows": (dict(G=1, H_kv=1, H_q=4, d_h=128, r_k=32, r_v=32, L=131072, k=1100, batch=1, dtype="bf16"), 1000000.0),
+}
+
+
+@pytest.mark.parametrize("name", list(ROPE_CASES))
+def test_gather_attend_with_counts_and_rope(name):
+    torch = torch_mod()
+    fields, theta = ROPE_CASES[name]
+    w = workload(fields)
+    case = synth.make_case(w, seed=70 + len(name))
+    layer = w.G - 1
+    rng = np.random.default_rng(len(name))
+    idx = np.stack([np.stack([np.sort(rng.choice(w.L, size=w.k, replace=False)) for _ in range(w.H_kv)])
+                    for _ in range(w.batch)]).astype(np.int32)
+    idx[:, :, -1] = w.L - 1                                   # the largest position is always there
+    counts = rng.integers(1, w.k + 1, size=(w.batch, w.H_kv)).astype(np.int32)
+    counts[0, 0] = w.k
+    shape = xb.Shape.of(w)
+    dev = synth.to_device(case, w.dtype)
+    ws = xb.alloc_workspace(shape)
+    q = dev["q"][layer].contiguous()
+    qh = synth.to_host(q)
+    idx_d, cnt_d = torch.from_numpy(idx).cuda(), torch.from_numpy(counts).cuda()
+    out = torch.zeros((w.batch, w.H_q, w.d_h), dtype=synth.torch_dtype(w.dtype), device="cuda")
+    for use_counts, th in ((True, theta), (False, theta), (True, 0.0)):
+        xb.xkv_gather_attend_ex(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, idx_d,
+                                cnt_d if use_counts else None, th, out, ws)
+        torch.cuda.synchronize()
+        got = synth.storage_to_f64(synth.to_host(out))
+        for b in range(w.batch):
+            rows = [idx[b, g, :(counts[b, g] if use_counts else w.k)] for g in range(w.H_kv)]
+            ref = oracle.gather_attend_rows(case["A_k"][b], case["A_v"][b], case["B_k"][b, layer], case["B_v"][b, layer],
+                                            qh[b], rows, rope_theta=(th if th > 0 else None))
+            assert max_rel(got[b], ref) <= TOL[w.dtype], (name, use_counts, th, b)
+
+
+def test_landmark_step_with_rope_is_the_papers_arrangement():
+    """Factors of pre-RoPE keys, landmarks of post-RoPE keys, rotation re-applied to the reconstructed rows: with every
+    chunk selected the step equals dense attention over the rotated keys; with a budget it equals the oracle on the
+    GPU's rows."""
+    torch = torch_mod()
+    theta, c, o = 500000.0, 8, 2
+    w = workload(dict(G=1, H_kv=2, H_q=8, d_h=128, r_k=32, r_v=32, L=1200, k=1200, batch=1, dtype="bf16"))
+    case = synth.make_case(w, seed=123)
+    K_pre = keys_of(case, w, 0)                                               # [1][H_kv][L][d_h], storage form
+    K_rope = np.stack([oracle.rope(synth.storage_to_f64(K_pre[0, g]), np.arange(w.L), theta) for g in range(w.H_kv)])
+    K_rope_s = synth.to_storage(K_rope[None], w.dtype)
+    dev = synth.to_device(case, w.dtype)
+    K_dev = synth.to_device({"K": K_rope_s}, w.dtype)["K"]
+    dt = synth.torch_dtype(w.dtype)
+    q = dev["q"][0].contiguous()
+    qh = synth.to_host(q)
+    for k in (w.L, 160):
+        shape = xb.Shape.of(w, k=k)
+        n_c = w.L // c
+        k_ch = oracle.chunk_budget(k, c, n_c)
+        cap = (k_ch + o) * c
+        ws = torch.empty(xb.xkv_landmark_workspace_bytes(shape, c, o), dtype=torch.uint8, device="cuda")
+        Lm = torch.zeros((1, w.H_kv, n_c, w.d_h), dtype=dt, device="cuda")
+        outl = torch.zeros((1, w.H_kv, o), dtype=torch.int32, device="cuda")
+        xb.xkv_landmarks(shape, K_dev, c, o, Lm, None, outl, ws)
+        out = torch.zeros((1, w.H_q, w.d_h), dtype=dt, device="cuda")
+        rows = torch.zeros((1, w.H_kv, cap), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((1, w.H_kv), dtype=torch.int32, device="cuda")
+        xb.xkv_sr_decode_landmark(shape, 0, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, Lm, outl, c, o, out, rows,
+                                  cnt, None, ws, rope_theta=theta)
+        torch.cuda.synchronize()
+        got = synth.storage_to_f64(synth.to_host(out))[0]
+        rows_h, cnt_h = rows.cpu().numpy()[0], cnt.cpu().numpy()[0]
+        row_lists = [rows_h[g, :cnt_h[g]] for g in range(w.H_kv)]
+        ref = oracle.gather_attend_rows(case["A_k"][0], case["A_v"][0], case["B_k"][0, 0], case["B_v"][0, 0], qh[0],
+                                        row_lists, rope_theta=theta)
+        assert max_rel(got, ref) <= TOL["bf16"], k
+        if k == w.L:
+            assert all(rl.tolist() == list(range(w.L)) for rl in row_lists)
+            K_flat = synth.storage_to_f64(K_rope_s[0]).transpose(1, 0, 2).reshape(w.L, w.H_kv * w.d_h)
+            V_flat = oracle.reconstruct(case["A_v"][0], case["B_v"][0, 0])
+            assert max_rel(got, oracle.dense(K_flat, V_flat, qh[0], w.H_kv)) <= TOL["bf16"]
