@@ -198,3 +198,34 @@ def test_full_size_group_known_spectrum():
     ref_A = Xs @ Bc.T
     got_A = synth.storage_to_f64(synth.to_host(A[0, torch.from_numpy(rows).cuda()]))
     assert np.abs(got_A - ref_A).max() <= ELEM[dtype] * np.abs(ref_A).max()
+
+
+@pytest.mark.parametrize("G,H_kv,d_h,L,r,batch,dtype", [
+    (1, 1, 64, 40, 1, 1, "f32"),        # one direction, a context shorter than one token tile
+    (1, 1, 64, 500, 64, 1, "f32"),      # r = n: nothing is discarded
+    (1, 2, 64, 300, 20, 18, "bf16"),    # more sequences than one pass takes (16 + 2)
+    (3, 1, 64, 257, 33, 2, "bf16"),     # n = 192 (no full 256-row tile), odd sizes everywhere
+])
+def test_factorize_edge_shapes(G, H_kv, d_h, L, r, batch, dtype):
+    rng = np.random.default_rng(G * 1000 + L)
+    caches = [synth.make_cache(rng, G, H_kv, d_h, L, 0.8, dtype=dtype) for _ in range(batch)]
+    A, B, _ = gpu_factorize(caches, G, H_kv, d_h, L, r, dtype, iters=12)
+    n = G * H_kv * d_h
+    for b in (0, batch - 1):
+        X = synth.cache_as_matrix(caches[b])
+        sv = np.linalg.svd(X, compute_uv=False)
+        opt, tot = float(np.sum(sv[r:] ** 2)), float(np.sum(sv ** 2))
+        res = float(np.sum((X - A[b] @ B[b]) ** 2))
+        assert res <= 1.02 * opt + max(ROUND_SQ[dtype], 1e-9) * tot, (b, res, opt)
+        assert np.abs(B[b] @ B[b].T - np.eye(r)).max() <= ORTH[dtype]
+    if r == n:
+        assert np.sum((synth.cache_as_matrix(caches[0]) - A[0] @ B[0]) ** 2) <= 1e-9 * tot
+
+
+def test_factorize_of_an_empty_batch_is_a_no_op():
+    torch = torch_mod()
+    shape = xb.Shape(G=1, H_kv=1, H_q=1, d_h=64, r_k=8, r_v=8, L=100, k=1, batch=0, dtype="bf16")
+    ws = torch.empty(max(256, xb.xkv_factorize_workspace_bytes(shape, 8)), dtype=torch.uint8, device="cuda")
+    dummy = torch.zeros(64, dtype=torch.bfloat16, device="cuda")
+    xb.xkv_factorize(shape, dummy, 8, 4, 0, dummy, dummy, ws)
+    torch.cuda.synchronize()

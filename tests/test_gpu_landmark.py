@@ -259,3 +259,46 @@ def test_landmark_step_with_rope_is_the_papers_arrangement():
             K_flat = synth.storage_to_f64(K_rope_s[0]).transpose(1, 0, 2).reshape(w.L, w.H_kv * w.d_h)
             V_flat = oracle.reconstruct(case["A_v"][0], case["B_v"][0, 0])
             assert max_rel(got, oracle.dense(K_flat, V_flat, qh[0], w.H_kv)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("L,c,o,k", [(5, 8, 1, 3), (64, 8, 8, 64), (100, 1, 0, 7), (1000, 16, 0, 1)])
+def test_landmark_selector_edge_shapes(L, c, o, k):
+    """A context shorter than one chunk; every chunk an outlier; chunks of one token; a budget of one token."""
+    torch = torch_mod()
+    w = workload(dict(G=1, H_kv=2, H_q=4, d_h=128, r_k=16, r_v=16, L=L, k=k, batch=2, dtype="bf16"))
+    case = synth.make_case(w, seed=L + c)
+    K_host = keys_of(case, w, 0)
+    shape = xb.Shape.of(w)
+    dev = synth.to_device(case, w.dtype)
+    K_dev = synth.to_device({"K": K_host}, w.dtype)["K"]
+    dt = synth.torch_dtype(w.dtype)
+    n_c = -(-L // c)
+    k_ch = oracle.chunk_budget(k, c, n_c)
+    cap = (k_ch + o) * c
+    ws = torch.empty(xb.xkv_landmark_workspace_bytes(shape, c, o), dtype=torch.uint8, device="cuda")
+    Lm = torch.zeros((w.batch, w.H_kv, n_c, w.d_h), dtype=dt, device="cuda")
+    outl = torch.zeros((w.batch, w.H_kv, max(o, 1)), dtype=torch.int32, device="cuda")
+    negm = torch.zeros((w.batch, w.H_kv, n_c), dtype=torch.float32, device="cuda")
+    xb.xkv_landmarks(shape, K_dev, c, o, Lm, negm, outl if o else None, ws)
+    q = dev["q"][0].contiguous()
+    out = torch.zeros((w.batch, w.H_q, w.d_h), dtype=dt, device="cuda")
+    rows = torch.zeros((w.batch, w.H_kv, cap), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((w.batch, w.H_kv), dtype=torch.int32, device="cuda")
+    S = torch.zeros((w.batch, w.H_kv, n_c), dtype=torch.float32, device="cuda")
+    xb.xkv_sr_decode_landmark(shape, 0, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, Lm, outl if o else None, c, o,
+                              out, rows, cnt, S, ws)
+    torch.cuda.synchronize()
+    qh, S_h, rows_h, cnt_h = synth.to_host(q), S.cpu().numpy(), rows.cpu().numpy(), cnt.cpu().numpy()
+    outl_h, negm_h = outl.cpu().numpy(), negm.cpu().numpy()
+    got = synth.storage_to_f64(synth.to_host(out))
+    for b in range(w.batch):
+        row_lists = []
+        for g in range(w.H_kv):
+            if o:
+                assert outl_h[b, g].tolist() == oracle.select(negm_h[b, g], o).tolist()
+            want = oracle.expand_chunks(oracle.select(S_h[b, g], k_ch), outl_h[b, g][:o], c, L)
+            assert cnt_h[b, g] == len(want) and rows_h[b, g, :len(want)].tolist() == want.tolist()
+            row_lists.append(want)
+        ref = oracle.gather_attend_rows(case["A_k"][b], case["A_v"][b], case["B_k"][b, 0], case["B_v"][b, 0], qh[b],
+                                        row_lists)
+        assert max_rel(got[b], ref) <= TOL["bf16"]
