@@ -430,3 +430,44 @@ def test_score_long_stream_large_rank():
             got = S[b, :, lo:hi].cpu().numpy()
             err = max_rel(got, ref)
             assert err <= TOL[w.dtype], (b, lo, err)
+
+
+def test_step_can_be_recorded_into_a_graph_and_replayed():
+    """The calls allocate nothing and synchronise nothing: a whole step can be recorded once and replayed.  Every replay
+    is compared with the eager result, with the program's own eager work and synchronisations in between."""
+    torch = torch_mod()
+    w = synth.LLAMA_GROUP.with_(L=4096, k=512, batch=2)
+    case = synth.make_case(w, seed=17)
+    shape = xb.Shape.of(w)
+    dev = synth.to_device(case, w.dtype)
+    ws = xb.alloc_workspace(shape)
+    dt = synth.torch_dtype(w.dtype)
+    qs = [dev["q"][l].contiguous() for l in range(w.G)]
+    outs = [torch.zeros((w.batch, w.H_q, w.d_h), dtype=dt, device="cuda") for _ in range(w.G)]
+    idxs = [torch.zeros((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda") for _ in range(w.G)]
+
+    def step():
+        for l in range(w.G):
+            xb.xkv_sr_decode(shape, l, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], qs[l], outs[l], idxs[l], None, ws)
+
+    step()
+    torch.cuda.synchronize()
+    want_out = [o.clone() for o in outs]
+    want_idx = [i.clone() for i in idxs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        for o, i in zip(outs, idxs):
+            o.zero_()
+            i.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(w.G):
+            assert torch.equal(outs[l], want_out[l]) and torch.equal(idxs[l], want_idx[l]), (rep, l)
+        step()                       # eager work between the replays
+        torch.cuda.synchronize()
