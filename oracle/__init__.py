@@ -306,11 +306,15 @@ def rope(X, positions, theta):
     return out
 
 
-def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None, rope_theta=None):
+def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None, rope_theta=None, K_tail=None, V_tail=None):
     """Steps 5-6 (Eq. 3 and softmax attention) for per-head row lists of different lengths: out[H_q][d_h].
     With rope_theta, every reconstructed key row is rotated to its position (= its row number) before it meets
-    the (already rotated) query; values are not rotated.  Written out in numpy."""
+    the (already rotated) query; values are not rotated.  With K_tail, V_tail [H_kv][T][d_h], the uncompressed
+    most recent tokens (Sec. 4: newly generated tokens are kept uncompressed; their keys are stored as the model
+    produced them, rotated) join the same softmax.  Written out in numpy."""
     A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
+    if K_tail is not None:
+        K_tail, V_tail = widen(K_tail), widen(V_tail)
     H_q, d_h = q.shape
     H_kv = len(rows)
     n_rep = H_q // H_kv
@@ -322,6 +326,9 @@ def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None, rope_theta=None)
         if rope_theta is not None:
             K_sel = rope(K_sel, rows[g], rope_theta)
         V_sel = A_v[rows[g]] @ B_v[:, cols]
+        if K_tail is not None:
+            K_sel = np.concatenate([K_sel, K_tail[g]], axis=0)
+            V_sel = np.concatenate([V_sel, V_tail[g]], axis=0)
         for h in range(g * n_rep, (g + 1) * n_rep):
             z = scale * (K_sel @ q[h])
             wgt = np.exp(z - z.max())
@@ -329,14 +336,15 @@ def gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale=None, rope_theta=None)
     return out
 
 
-def sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outliers, k, c, scale=None, rope_theta=None):
+def sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outliers, k, c, scale=None, rope_theta=None, K_tail=None,
+                       V_tail=None):
     """SR step with the paper's own selector (App. B.1): chunks are scored against their landmarks, the top
     ceil(k / c) chunks per KV head plus the static outliers are expanded to rows, those rows are reconstructed
-    (Eq. 3), with rope_theta rotated to their positions, and attended over.  Returns (out[H_q][d_h], rows,
-    S32[H_kv][n_c])."""
+    (Eq. 3), with rope_theta rotated to their positions, and attended over together with the uncompressed tail
+    if there is one.  Returns (out[H_q][d_h], rows, S32[H_kv][n_c])."""
     L = widen(A_k).shape[0]
     rows, S32 = select_rows_by_landmarks(Lm, outliers, q, k, c, L, scale)
-    return gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale, rope_theta), rows, S32
+    return gather_attend_rows(A_k, A_v, B_k, B_v, q, rows, scale, rope_theta, K_tail, V_tail), rows, S32
 
 
 def factorize(X_cat, r):

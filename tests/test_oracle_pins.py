@@ -532,3 +532,31 @@ def test_landmark_step_with_rope_and_every_chunk_selected_is_dense_attention_on_
     # without the rotation the result differs: the rotation is not a no-op in this check
     plain, _, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outl, L, c)
     assert np.abs(plain - got).max() > 1e-3
+
+
+def test_landmark_step_with_an_uncompressed_tail():
+    """Empty tail = no tail; every chunk selected + tail = dense attention over [rotated compressed keys ; tail]; and
+    the same rows with the tail equals gather_attend_tail (written independently for equal-length row lists)."""
+    rng = np.random.default_rng(54)
+    L, T, r, H_kv, H_q, d_h, c, theta = 32, 5, 4, 2, 4, 8, 4, 10000.0
+    A_k, A_v = rng.standard_normal((L, r)), rng.standard_normal((L, r))
+    B_k, B_v = rng.standard_normal((r, H_kv * d_h)), rng.standard_normal((r, H_kv * d_h))
+    q = rng.standard_normal((H_q, d_h))
+    K_tail, V_tail = rng.standard_normal((H_kv, T, d_h)), rng.standard_normal((H_kv, T, d_h))
+    K_pre = oracle.reconstruct(A_k, B_k).reshape(L, H_kv, d_h).transpose(1, 0, 2)
+    K_rope = np.stack([oracle.rope(K_pre[g], np.arange(L), theta) for g in range(H_kv)])
+    Lm, _, outl = oracle.landmarks(K_rope, c, o=0)
+    none, rows0, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outl, 8, c, rope_theta=theta)
+    empty, _, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outl, 8, c, rope_theta=theta,
+                                            K_tail=K_tail[:, :0], V_tail=V_tail[:, :0])
+    np.testing.assert_array_equal(none, empty)
+    full, rows, _ = oracle.sr_decode_landmark(A_k, A_v, B_k, B_v, q, Lm, outl, L, c, rope_theta=theta, K_tail=K_tail,
+                                              V_tail=V_tail)
+    K_all = np.concatenate([K_rope, K_tail], axis=1).transpose(1, 0, 2).reshape(L + T, H_kv * d_h)
+    V_cmp = oracle.reconstruct(A_v, B_v).reshape(L, H_kv, d_h).transpose(1, 0, 2)
+    V_all = np.concatenate([V_cmp, V_tail], axis=1).transpose(1, 0, 2).reshape(L + T, H_kv * d_h)
+    np.testing.assert_allclose(full, oracle.dense(K_all, V_all, q, H_kv), rtol=1e-11, atol=1e-13)
+    same_len = np.stack(rows0)                                     # no outliers, full chunks: equal lengths
+    np.testing.assert_allclose(
+        oracle.gather_attend_rows(A_k, A_v, B_k, B_v, q, rows0, K_tail=K_tail, V_tail=V_tail),
+        oracle.gather_attend_tail(A_k, A_v, B_k, B_v, q, same_len, K_tail, V_tail), rtol=1e-12, atol=1e-14)
