@@ -175,7 +175,9 @@ XKV_API xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t 
  *   count_out[batch][H_kv] (nullable) are real, the rest 0; score_out (nullable) [batch][H_kv][n_c] the pooled
  *   chunk scores.  landmarks / outliers are xkv_landmarks' outputs (outliers may be NULL when o == 0).  rope_theta
  *   as in xkv_gather_attend_ex below: with landmarks of post-RoPE keys and factors of pre-RoPE keys this is the
- *   paper's arrangement; 0 leaves the reconstructed rows as they are.
+ *   paper's arrangement; 0 leaves the reconstructed rows as they are.  K_tail, V_tail, T as in xkv_sr_decode_tail:
+ *   the T most recent, uncompressed tokens (keys as the model stored them, i.e. already rotated) join the softmax;
+ *   T = 0 and NULL for none.
  * workspace for both: xkv_landmark_workspace_bytes() bytes, 256-byte aligned (xkv_landmarks needs none for o == 0).
  * XKV_ERR_INVALID_ARG for c < 1, o < 0 or o > n_c.
  */
@@ -186,9 +188,9 @@ XKV_API xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int
 XKV_API xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
                                           const void *A_v, const void *B_k, const void *B_v, const void *q,
                                           const void *landmarks, const int32_t *outliers, int32_t c, int32_t o,
-                                          float rope_theta, void *out, int32_t *rows_out, int32_t *count_out,
-                                          float *score_out, void *workspace, size_t workspace_bytes,
-                                          void *hip_stream);
+                                          float rope_theta, const void *K_tail, const void *V_tail, int32_t T,
+                                          void *out, int32_t *rows_out, int32_t *count_out, float *score_out,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * xkv_gather_attend with two options (stages 3-4 of the step on their own):

@@ -87,8 +87,8 @@ def load() -> ctypes.CDLL:
         lib.xkv_factorize.argtypes = [sp, vp, i32, i32, ctypes.c_uint32, vp, vp, vp, sz, vp]
         lib.xkv_landmark_workspace_bytes.argtypes = [sp, i32, i32, ctypes.POINTER(sz)]
         lib.xkv_landmarks.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
-        lib.xkv_sr_decode_landmark.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, vp,
-                                               vp, vp, sz, vp]
+        lib.xkv_sr_decode_landmark.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, i32,
+                                               vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_gather_attend_ex.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
@@ -211,10 +211,10 @@ def xkv_gather_attend_ex(shape, layer_in_group, A_k, A_v, B_k, B_v, q, idx, coun
 
 
 def xkv_sr_decode_landmark(shape, layer_in_group, A_k, A_v, B_k, B_v, q, landmarks, outliers, c, o, out, rows_out,
-                           count_out, score_out, workspace, stream=None, rope_theta=0.0):
+                           count_out, score_out, workspace, stream=None, rope_theta=0.0, K_tail=None, V_tail=None, T=0):
     _check(load().xkv_sr_decode_landmark(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
                                          _ptr(B_v), _ptr(q), _ptr(landmarks), _ptr(outliers), c, o, float(rope_theta),
-                                         _ptr(out),
+                                         _ptr(K_tail), _ptr(V_tail), T, _ptr(out),
                                          _ptr(rows_out), _ptr(count_out), _ptr(score_out), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(stream)),
            "xkv_sr_decode_landmark")

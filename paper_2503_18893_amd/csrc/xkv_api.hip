@@ -179,6 +179,22 @@ xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *
 }
 
 // SR step; K_tail / V_tail (T > 0 tokens per KV head, uncompressed) are attended together with the selected rows.
+// Dense pass over the T uncompressed tail tokens (at most 8 splits) into their own set of partials; *n_part is how
+// many partials per query head it wrote.
+static hipError_t launch_tail(const xkv_shape &shape, const Plan &p, const void *K_tail, const void *V_tail, const void *q,
+                              int T, float *tail_o, float *tail_ml, int *n_part, hipStream_t stream)
+{
+    xkv_shape ts = shape;
+    ts.L = T;
+    Plan tp = p;
+    const int splits = clampi(ceil_div(T, 512), 1, kTailParts / 4);
+    tp.dense_chunk = ceil_div(ceil_div(T, splits), 128) * 128;
+    tp.dense_splits = ceil_div(T, tp.dense_chunk);
+    const hipError_t e = launch_dense(ts, tp, K_tail, V_tail, q, tail_o, tail_ml, stream);
+    *n_part = dense_uses_mfma(tp, K_tail, V_tail, q) ? tp.dense_splits : tp.dense_splits * 4;
+    return e;
+}
+
 static xkv_status sr_decode_impl(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
                                  const void *B_k, const void *B_v, const void *q, const void *K_tail,
                                  const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
@@ -216,16 +232,7 @@ static xkv_status sr_decode_impl(const xkv_shape *shape, int32_t layer, const vo
     // into a second set of partials; the merge below is one softmax over selected rows and tail.
     int n_tail = 0;
     float *tail_o = at<float>(workspace, p.off_tail_o), *tail_ml = at<float>(workspace, p.off_tail_ml);
-    if (T > 0 && e == hipSuccess) {
-        xkv_shape ts = *shape;
-        ts.L = T;
-        Plan tp = p;
-        const int splits = clampi(ceil_div(T, 512), 1, kTailParts / 4);
-        tp.dense_chunk = ceil_div(ceil_div(T, splits), 128) * 128;
-        tp.dense_splits = ceil_div(T, tp.dense_chunk);
-        e = launch_dense(ts, tp, K_tail, V_tail, q, tail_o, tail_ml, stream);
-        n_tail = dense_uses_mfma(tp, K_tail, V_tail, q) ? tp.dense_splits : tp.dense_splits * 4;
-    }
+    if (T > 0 && e == hipSuccess) e = launch_tail(*shape, p, K_tail, V_tail, q, T, tail_o, tail_ml, &n_tail, stream);
     // the matrix-core kernel writes one partial per split, the general one one per wavefront
     if (e == hipSuccess)
         e = launch_combine(*shape, want_pack ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream, n_tail,
@@ -391,9 +398,9 @@ xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int32_t c, 
 
 xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
                                   const void *B_k, const void *B_v, const void *q, const void *landmarks,
-                                  const int32_t *outliers, int32_t c, int32_t o, float rope_theta, void *out,
-                                  int32_t *rows_out, int32_t *count_out, float *score_out, void *workspace,
-                                  size_t workspace_bytes, void *hip_stream)
+                                  const int32_t *outliers, int32_t c, int32_t o, float rope_theta, const void *K_tail,
+                                  const void *V_tail, int32_t T, void *out, int32_t *rows_out, int32_t *count_out,
+                                  float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     xkv_status st = validate(shape);
     if (st != XKV_OK) return st;
@@ -403,6 +410,7 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
         layer >= shape->G)
         return XKV_ERR_INVALID_ARG;
     if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return XKV_ERR_INVALID_ARG;
+    if (T < 0 || (T > 0 && (!K_tail || !V_tail))) return XKV_ERR_INVALID_ARG;
     if (rope_theta > 0.0f && !rope_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255u)) return XKV_ERR_INVALID_ARG;
     if (workspace_bytes < lp.total_decode) return XKV_ERR_WORKSPACE;
@@ -434,8 +442,13 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     if (e == hipSuccess)
         e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, false, part_o, part_ml,
                                  stream, counts, rope_theta);
+    // the uncompressed tail, as in xkv_sr_decode_tail: a dense pass over its T tokens into a second set of partials
+    int n_tail = 0;
+    float *tail_o = at<float>(workspace, pa.off_tail_o), *tail_ml = at<float>(workspace, pa.off_tail_ml);
+    if (T > 0 && e == hipSuccess) e = launch_tail(*shape, pa, K_tail, V_tail, q, T, tail_o, tail_ml, &n_tail, stream);
     if (e == hipSuccess)
-        e = launch_combine(*shape, mfma ? pa.sr_splits : pa.sr_splits * 4, part_o, part_ml, out, stream);
+        e = launch_combine(*shape, mfma ? pa.sr_splits : pa.sr_splits * 4, part_o, part_ml, out, stream, n_tail, tail_o,
+                           tail_ml);
     return hip_status(e);
 }
 

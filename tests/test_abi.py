@@ -106,11 +106,14 @@ def test_landmark_calls_validate_on_the_host():
     assert lib.xkv_landmarks(ctypes.byref(c), null, 8, 0, one, null, null, null, 0, null) == xb.XKV_ERR_INVALID_ARG
     assert lib.xkv_landmarks(ctypes.byref(c), one, 8, 2, one, null, null, one, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
     assert lib.xkv_landmarks(ctypes.byref(c), one, 8, 2, one, null, one, one, 16, null) == xb.XKV_ERR_WORKSPACE
-    args = [ctypes.byref(c), 0, one, one, one, one, one, one, null, 8, 0, ctypes.c_float(0.0), one, null, null, null, one]
+    args = [ctypes.byref(c), 0, one, one, one, one, one, one, null, 8, 0, ctypes.c_float(0.0), null, null, 0, one, null, null,
+            null, one]
     assert lib.xkv_sr_decode_landmark(*args, 16, null) == xb.XKV_ERR_WORKSPACE
     args[7] = null                                            # no landmarks
     assert lib.xkv_sr_decode_landmark(*args, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
     args[7], args[10] = one, 3                                # outliers announced but not given
+    assert lib.xkv_sr_decode_landmark(*args, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
+    args[10], args[14] = 0, 5                                 # tail tokens without their keys
     assert lib.xkv_sr_decode_landmark(*args, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
 
 

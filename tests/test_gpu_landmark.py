@@ -302,3 +302,46 @@ def test_landmark_selector_edge_shapes(L, c, o, k):
         ref = oracle.gather_attend_rows(case["A_k"][b], case["A_v"][b], case["B_k"][b, 0], case["B_v"][b, 0], qh[b],
                                         row_lists)
         assert max_rel(got[b], ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("T", [1, 77, 700])
+def test_landmark_step_with_rope_and_uncompressed_tail(T):
+    """The paper's complete decode arrangement: landmark selection, rotation of the reconstructed rows, and the T most
+    recent tokens kept uncompressed in the same softmax."""
+    torch = torch_mod()
+    theta, c, o = 500000.0, 8, 2
+    w = workload(dict(G=1, H_kv=2, H_q=8, d_h=128, r_k=32, r_v=48, L=2000, k=200, batch=2, dtype="bf16"))
+    case = synth.make_case(w, seed=300 + T)
+    rng = np.random.default_rng(T)
+    K_pre = keys_of(case, w, 0)
+    K_rope = np.stack([[oracle.rope(synth.storage_to_f64(K_pre[b, g]), np.arange(w.L), theta) for g in range(w.H_kv)]
+                       for b in range(w.batch)])
+    K_tail_h = synth.to_storage(rng.standard_normal((w.batch, w.H_kv, T, w.d_h)) * 0.5, w.dtype)
+    V_tail_h = synth.to_storage(rng.standard_normal((w.batch, w.H_kv, T, w.d_h)), w.dtype)
+    dev = synth.to_device(case, w.dtype)
+    extra = synth.to_device({"K": synth.to_storage(K_rope, w.dtype), "Kt": K_tail_h, "Vt": V_tail_h}, w.dtype)
+    shape = xb.Shape.of(w)
+    dt = synth.torch_dtype(w.dtype)
+    n_c = w.L // c
+    cap = (oracle.chunk_budget(w.k, c, n_c) + o) * c
+    ws = torch.empty(xb.xkv_landmark_workspace_bytes(shape, c, o), dtype=torch.uint8, device="cuda")
+    Lm = torch.zeros((w.batch, w.H_kv, n_c, w.d_h), dtype=dt, device="cuda")
+    outl = torch.zeros((w.batch, w.H_kv, o), dtype=torch.int32, device="cuda")
+    xb.xkv_landmarks(shape, extra["K"], c, o, Lm, None, outl, ws)
+    q = dev["q"][0].contiguous()
+    out = torch.zeros((w.batch, w.H_q, w.d_h), dtype=dt, device="cuda")
+    rows = torch.zeros((w.batch, w.H_kv, cap), dtype=torch.int32, device="cuda")
+    cnt = torch.zeros((w.batch, w.H_kv), dtype=torch.int32, device="cuda")
+    xb.xkv_sr_decode_landmark(shape, 0, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, Lm, outl, c, o, out, rows, cnt,
+                              None, ws, rope_theta=theta, K_tail=extra["Kt"], V_tail=extra["Vt"], T=T)
+    torch.cuda.synchronize()
+    got = synth.storage_to_f64(synth.to_host(out))
+    rows_h, cnt_h, qh = rows.cpu().numpy(), cnt.cpu().numpy(), synth.to_host(q)
+    for b in range(w.batch):
+        row_lists = [rows_h[b, g, :cnt_h[b, g]] for g in range(w.H_kv)]
+        ref = oracle.gather_attend_rows(case["A_k"][b], case["A_v"][b], case["B_k"][b, 0], case["B_v"][b, 0], qh[b],
+                                        row_lists, rope_theta=theta, K_tail=K_tail_h[b], V_tail=V_tail_h[b])
+        assert max_rel(got[b], ref) <= TOL["bf16"], (T, b)
+        no_tail = oracle.gather_attend_rows(case["A_k"][b], case["A_v"][b], case["B_k"][b, 0], case["B_v"][b, 0], qh[b],
+                                            row_lists, rope_theta=theta)
+        assert np.abs(no_tail - ref).max() > 1e-3 * np.abs(ref).max()      # the tail does matter in this case
