@@ -83,15 +83,15 @@ __global__ __launch_bounds__(256) void xt_pack_kernel(const T *__restrict__ X, T
 //
 // Element (row, k) of an operand lives at base + (k / kbw) * kblk + row * pitch + k % kbw: a plain row-major
 // matrix has kbw = K, and a cache stored as [column block][token][d_h] is read as X_cat [token][n] with
-// kbw = d_h, kblk = L * d_h, pitch = d_h.  K is consumed in slabs of 64 B per row (32 bf16 or 16 fp32
+// kbw = d_h, kblk = L * d_h, pitch = d_h.  K is consumed in slabs of 128 B per row (64 bf16 or 32 fp32
 // values); kbw is a multiple of the slab.
 //
 // Workgroup: 8 wavefronts, a 256 x 256 output tile, wavefront (wm, wn) owns rows 64 wm .. +63 and columns
-// 128 wn .. +127 as 2 x 4 accumulator tiles of 32 x 32.  A slab of the 256 + 256 operand rows (32 KiB) is
-// copied global -> LDS directly into a ring of four stages: one copy instruction moves 16 rows x 64 B, lane l
-// fetching the 16 B piece (l % 4) ^ (l / 16) of row l / 4, so that a row's pieces sit in LDS xor-swizzled by
-// (row / 4) % 4 and the fragment reads (consecutive rows, same piece) spread over all 64 banks.  Rows beyond the
-// operand's end are clamped to its last row; what they produce is never stored.
+// 128 wn .. +127 as 2 x 4 accumulator tiles of 32 x 32.  A slab of the 256 + 256 operand rows (64 KiB) is
+// copied global -> LDS directly, two stages: one copy instruction moves 8 rows x 128 B, lane l fetching the 16 B
+// piece (l % 8) ^ (row / 2) % 8 of row l / 8, so that a row's pieces sit in LDS xor-swizzled by (row / 2) % 8 and
+// the fragment reads (consecutive rows, same piece) spread over all 64 banks.  Rows beyond the operand's end are
+// clamped to its last row; what they produce is never stored.
 // Output: fp32 partial planes out_f32[split][m][n] (summed by a second kernel), or, with one split, the
 // final matrix in fp32 or bf16.  With lower_only (P == Q) only tiles on or below the diagonal are computed.
 // ------------------------------------------------------------------------------------------------
@@ -109,7 +109,7 @@ struct GemmArgs {
     long long ldo, plane, out_seq;
 };
 
-constexpr int kGemmThreads = 512, kGemmTile = 256, kGemmStages = 4, kGemmStage = 512 * 64, kGemmLds = kGemmStages * kGemmStage;
+constexpr int kGemmThreads = 512, kGemmTile = 256, kGemmStages = 2, kGemmStage = 512 * 128, kGemmLds = kGemmStages * kGemmStage;
 
 // Decoding of a linear index into a pair (bi, bj), bj <= bi, enumerated row by row.
 __device__ __forceinline__ void fz_lower_pair(int t, int &bi, int &bj)
@@ -143,11 +143,11 @@ __device__ __forceinline__ void fz_lower_patch_tile(int t, int T, int &tm, int &
     tm = tn = 0;  // not reached for t < T (T + 1) / 2
 }
 
-// The four copy instructions of a wavefront for one slab: its 64 operand rows, 16 rows x 64 B each.
-__device__ __forceinline__ void fz_issue_slab(const unsigned char *const (&rowp)[4], size_t off, uint32_t dst)
+// The eight copy instructions of a wavefront for one slab: its 64 operand rows, 8 rows x 128 B each.
+__device__ __forceinline__ void fz_issue_slab(const unsigned char *const (&rowp)[8], size_t off, uint32_t dst)
 {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fz_copy16_global_to_lds(rowp[j] + off, dst + j * 1024);
+    for (int j = 0; j < 8; ++j) fz_copy16_global_to_lds(rowp[j] + off, dst + j * 1024);
 }
 
 // One k-step of a wavefront: its 2 + 4 operand fragments (32 rows each, the lane's 16 B piece), and the 8 products.
@@ -155,9 +155,9 @@ __device__ __forceinline__ void fz_read_frags(fz_u32x4_t (&af)[2], fz_u32x4_t (&
                                               int slot)
 {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) af[i] = st[arow + i * 128 + slot];
+    for (int i = 0; i < 2; ++i) af[i] = st[arow + i * 256 + slot];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) qf[j] = st[qrow + j * 128 + slot];
+    for (int j = 0; j < 4; ++j) qf[j] = st[qrow + j * 256 + slot];
 }
 
 template <typename T>
@@ -187,7 +187,7 @@ __device__ __forceinline__ void fz_multiply(fz_f32x16_t (&acc)[2][4], const fz_u
 template <typename T>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
 {
-    constexpr int E = 64 / (int)sizeof(T);  // elements per slab row
+    constexpr int E = 128 / (int)sizeof(T);  // elements per slab row
     extern __shared__ __attribute__((aligned(16))) unsigned char fz_smem[];
     const int tid = threadIdx.x, lane = tid & 63, w = wave_id();
     const int m32 = lane & 31, h = lane >> 5;
@@ -217,15 +217,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
     const long long op_pitch = is_p ? a.P.pitch : a.Q.pitch, op_kblk = is_p ? a.P.kblk : a.Q.kblk;
     const int op_kbw = is_p ? a.P.kbw : a.Q.kbw, op_rows = is_p ? a.P.rows : a.Q.rows;
     const int origin = (is_p ? tm : tn) * kGemmTile + (w & 3) * 64;
-    const int piece = (lane & 3) ^ ((lane >> 4) & 3);
-    const unsigned char *rowp[4];
+    const unsigned char *rowp[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int R = origin + 16 * j + (lane >> 2);
+    for (int j = 0; j < 8; ++j) {
+        int R = origin + 8 * j + (lane >> 3);
         R = R < op_rows ? R : op_rows - 1;
+        const int piece = (lane & 7) ^ ((4 * j + (lane >> 4)) & 7);  // slot ^ (stage row / 2) % 8
         rowp[j] = op_base + (size_t)((long long)R * op_pitch) * sizeof(T) + piece * 16;
     }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(fz_lds_void_t *)fz_smem + (uint32_t)(w * 4 * 1024);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(fz_lds_void_t *)fz_smem + (uint32_t)(w * 8 * 1024);
     // Byte offset of the next slab to request within an operand row, advanced without divisions: slabs are
     // requested in order, and past the last one the last one again.
     const long long kk0 = (long long)sb_begin * E;
@@ -256,39 +256,39 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(const GemmArgs a)
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    // 16 B index of (row, piece c) in a stage: row * 4 + (c ^ (row / 4) % 4); (row / 4) % 4 == (m32 / 4) % 4 for every row
+    // 16 B index of (row, piece c) in a stage: row * 8 + (c ^ (row / 2) % 8); (row / 2) % 8 == (m32 / 2) % 8 for every row
     // read here.  With 64 banks of 4 B, 16 consecutive rows x one piece then cover every bank exactly once.
-    const int arow = (64 * wm + m32) * 4, qrow = (256 + 128 * wn + m32) * 4, sw = (m32 >> 2) & 3;
+    const int arow = (64 * wm + m32) * 8, qrow = (256 + 128 * wn + m32) * 8, sw = (m32 >> 1) & 7;
 
-    // Ring of four stages: the slab three ahead is requested while the current one is multiplied, so a copy has
-    // three slab times to land.  Every iteration issues exactly four copies per wavefront (past the end, the last
-    // slab again, into a stage nobody reads), which keeps the count of outstanding copies, and with it the wait
-    // below, the same in every iteration.
+    // Two stages of 128 B per row (a whole cache line per row and request: row-scattered 64 B pieces reach only about
+    // 60 % of the L2 -> LDS rate of whole lines): the next slab is requested right after the barrier that retires
+    // the previous one, while the current one is multiplied.  Within a slab the fragments of a step are read during
+    // the products of the step before (the scheduling fences keep that order).
     const int n_sb = sb_end - sb_begin;
-#pragma unroll
-    for (int p = 0; p < kGemmStages - 1; ++p) fz_issue_slab(rowp, next_slab(), lds0 + (uint32_t)(p * kGemmStage));
-    // Fragments are read one step ahead of the products that use them: F0 holds step 0 of the current slab (read
-    // during the previous slab), F1 its step 1.  For that, a barrier guarantees the slab after the current one too.
+    fz_issue_slab(rowp, next_slab(), lds0);
     fz_u32x4_t a0[2], q0[4], a1[2], q1[4];
-    FZ_WAIT_VMCNT(8);
-    fz_lds_barrier();
-    fz_read_frags(a0, q0, reinterpret_cast<const fz_u32x4_t *>(fz_smem), arow, qrow, h ^ sw);
     for (int i = 0; i < n_sb; ++i) {
-        FZ_WAIT_VMCNT(4);   // all but the youngest slab have landed: slabs i and i + 1 are in LDS
-        fz_lds_barrier();   // ... for every wavefront; and nobody reads stage (i + 3) % 4 = (i - 1) % 4 any more
-        fz_issue_slab(rowp, next_slab(), lds0 + (uint32_t)(((i + kGemmStages - 1) & 3) * kGemmStage));
-        const fz_u32x4_t *st = reinterpret_cast<const fz_u32x4_t *>(fz_smem + (i & 3) * kGemmStage);
-        // the scheduling fences keep each group of reads ahead of the products of the step before it
+        FZ_WAIT_VMCNT(0);   // slab i is in LDS
+        fz_lds_barrier();   // ... for every wavefront; and nobody reads the other stage any more
+        if (i + 1 < n_sb) fz_issue_slab(rowp, next_slab(), lds0 + (uint32_t)(((i + 1) & 1) * kGemmStage));
+        const fz_u32x4_t *st = reinterpret_cast<const fz_u32x4_t *>(fz_smem + (i & 1) * kGemmStage);
+        fz_read_frags(a0, q0, st, arow, qrow, h ^ sw);
+        __builtin_amdgcn_sched_barrier(0);
         fz_read_frags(a1, q1, st, arow, qrow, (2 + h) ^ sw);
         __builtin_amdgcn_sched_barrier(0);
         fz_multiply<T>(acc, a0, q0);
         __builtin_amdgcn_sched_barrier(0);
-        fz_read_frags(a0, q0, reinterpret_cast<const fz_u32x4_t *>(fz_smem + ((i + 1) & 3) * kGemmStage), arow, qrow, h ^ sw);
+        fz_read_frags(a0, q0, st, arow, qrow, (4 + h) ^ sw);
+        __builtin_amdgcn_sched_barrier(0);
+        fz_multiply<T>(acc, a1, q1);
+        __builtin_amdgcn_sched_barrier(0);
+        fz_read_frags(a1, q1, st, arow, qrow, (6 + h) ^ sw);
+        __builtin_amdgcn_sched_barrier(0);
+        fz_multiply<T>(acc, a0, q0);
         __builtin_amdgcn_sched_barrier(0);
         fz_multiply<T>(acc, a1, q1);
         __builtin_amdgcn_sched_barrier(0);
     }
-    FZ_WAIT_VMCNT(0);  // the surplus copies must have landed before this workgroup's LDS is handed on
 
     // ---- store: accumulator register v of a 32 x 32 tile is row 8 (v / 4) + 4 h + v % 4, column m32
 #pragma unroll
@@ -733,13 +733,13 @@ FzLayout fz_layout(const xkv_shape &s, int r)
     f.bc = std::max(1, std::min(s.batch, kFzChunk));
     const int t = (f.n + kGemmTile - 1) / kGemmTile;
     f.gram_tiles = t * (t + 1) / 2;
-    const int slab = 64 / (int)f.esz, gram_slabs = f.Lp / slab;
+    const int slab = 128 / (int)f.esz, gram_slabs = f.Lp / slab;
     auto splits_for = [&](int wgs_per_seq, int target, int most) {  // enough workgroups to fill the chip twice over
         const int wgs = wgs_per_seq * f.bc;
         return std::max(1, std::min(std::min(16, most), (target + wgs - 1) / wgs));
     };
     f.gram_splits = splits_for(f.gram_tiles, 512, gram_slabs);
-    f.w_splits = splits_for(t * ((r + kGemmTile - 1) / kGemmTile), 256, f.n / 16);
+    f.w_splits = splits_for(t * ((r + kGemmTile - 1) / kGemmTile), 256, f.n / 32);
     const int gb = (r + 31) / 32;
     f.g_splits = splits_for((gb * (gb + 1) / 2 + 3) / 4, 1024, f.n / 64);
     f.chol_pb = r <= 512 ? 32 : 16;
@@ -783,7 +783,7 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
                            void *A_out, void *B_out, unsigned char *ws, hipStream_t st)
 {
     const int n = f.n, d = s.H_kv * s.d_h, tn = (n + kGemmTile - 1) / kGemmTile, tr = (r + kGemmTile - 1) / kGemmTile;
-    constexpr int E = 64 / (int)sizeof(T);
+    constexpr int E = 128 / (int)sizeof(T);
     T *Xt = reinterpret_cast<T *>(ws + f.off_xt);
     float *part = reinterpret_cast<float *>(ws + f.off_part), *C = reinterpret_cast<float *>(ws + f.off_c);
     float *Vt = reinterpret_cast<float *>(ws + f.off_vt), *Wn = reinterpret_cast<float *>(ws + f.off_wn);
@@ -823,7 +823,7 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
             GemmArgs a{};  // Wn [n][r] = C Vt^T
             a.P = GemmOperand{C, n, 0, n, n, (long long)n * n};
             a.Q = GemmOperand{Vt, n, 0, n, r, vcount};
-            a.n_slabs = n / 16; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
+            a.n_slabs = n / 32; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
             a.out_f32 = f.w_splits > 1 ? part : Wn; a.out_bf16 = nullptr; a.ldo = r; a.plane = vcount;
             a.out_seq = f.w_splits > 1 ? (long long)f.part_seq : vcount;
             if ((e = launch_gemm<float>(a, tn * tr, nb, st)) != hipSuccess) break;
