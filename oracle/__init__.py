@@ -149,6 +149,35 @@ def gather_attend(A_k, A_v, B_k, B_v, q, idx, scale=None):
     return out
 
 
+def head_scores(A_k, B_k, q, H_kv, scale=None):
+    """Steps 1-2 without the pooling: s[H_q][L] = scale * A^K (B^K_{rho(h)} q_h), the per-head logits of every token."""
+    q = widen(q)
+    scale = default_scale(q.shape[1]) if scale is None else scale
+    return scores(A_k, project(B_k, q, H_kv), scale)
+
+
+def gather_attend_absorbed(A_k, A_v, B_k, B_v, q, idx, scale=None):
+    """Steps 5-6 in the form that never builds K^ or V^ (associativity of Eq. 3, valid as long as nothing such as a
+    rotation sits between the factors and the query): the logits of the selected tokens are entries of the head
+    scores, logits = s[h][I_g]; the weighted sum runs over rows of A^V and B^V is applied once at the end,
+    o_h = ((w^T A^V[I_g]) B^V_g).  Written out in numpy; equals gather_attend."""
+    A_k, A_v, B_k, B_v, q = map(widen, (A_k, A_v, B_k, B_v, q))
+    idx = np.asarray(idx)
+    H_q, d_h = q.shape
+    H_kv = idx.shape[0]
+    n_rep = H_q // H_kv
+    s = head_scores(A_k, B_k, q, H_kv, scale)
+    out = np.empty((H_q, d_h), np.float64)
+    for g in range(H_kv):
+        rows_v = A_v[idx[g]]
+        for h in range(g * n_rep, (g + 1) * n_rep):
+            z = s[h][idx[g]]
+            wgt = np.exp(z - z.max())
+            u = (wgt / wgt.sum()) @ rows_v
+            out[h] = u @ B_v[:, g * d_h:(g + 1) * d_h]
+    return out
+
+
 def dense(K, V, q, H_kv, scale=None):
     """Textbook decode attention, K and V as [L][H_kv*d_h]: out[H_q][d_h]."""
     K, V, q = widen(K), widen(V), widen(q)

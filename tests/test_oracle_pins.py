@@ -560,3 +560,22 @@ def test_landmark_step_with_an_uncompressed_tail():
     np.testing.assert_allclose(
         oracle.gather_attend_rows(A_k, A_v, B_k, B_v, q, rows0, K_tail=K_tail, V_tail=V_tail),
         oracle.gather_attend_tail(A_k, A_v, B_k, B_v, q, same_len, K_tail, V_tail), rtol=1e-12, atol=1e-14)
+
+
+def test_absorbed_form_equals_reconstruct_then_attend():
+    """o_h = ((w^T A^V[I]) B^V) with logits taken from the head scores is the same number as attention over the
+    reconstructed rows (associativity); the head scores pool to the scores the selection sees."""
+    rng = np.random.default_rng(61)
+    L, r_k, r_v, H_kv, H_q, d_h, k = 70, 6, 9, 2, 6, 8, 11
+    A_k, A_v = rng.standard_normal((L, r_k)), rng.standard_normal((L, r_v))
+    B_k, B_v = rng.standard_normal((r_k, H_kv * d_h)), rng.standard_normal((r_v, H_kv * d_h))
+    q = rng.standard_normal((H_q, d_h))
+    idx = np.stack([np.sort(rng.choice(L, size=k, replace=False)) for _ in range(H_kv)]).astype(np.int32)
+    np.testing.assert_allclose(oracle.gather_attend_absorbed(A_k, A_v, B_k, B_v, q, idx),
+                               oracle.gather_attend(A_k, A_v, B_k, B_v, q, idx), rtol=1e-11, atol=1e-13)
+    s = oracle.head_scores(A_k, B_k, q, H_kv)
+    np.testing.assert_allclose(oracle.pool(s, H_kv), oracle.pooled_scores(A_k, B_k, q, H_kv), rtol=1e-15)
+    K = oracle.reconstruct(A_k, B_k)
+    for h in range(H_q):
+        g = h // (H_q // H_kv)
+        np.testing.assert_allclose(s[h], K[:, g * d_h:(g + 1) * d_h] @ q[h] / np.sqrt(d_h), rtol=1e-11, atol=1e-13)
