@@ -41,6 +41,7 @@ def parse_args():
     ap.add_argument("--no-factorize", action="store_true", help="skip the timing of the prefill-side factorization")
     ap.add_argument("--no-landmark", action="store_true", help="skip the timing of the landmark-guided step")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--no-absorbed", action="store_true", help="skip the timing of the absorbed form of the step")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise 1 GiB copy kernel three times (reference point for hardware counters)")
@@ -374,6 +375,48 @@ def main():
                             "factors; same reconstruction and attention kernels"}
         del lms, outls, lm_ws
 
+    # ---------------------------------------------------------------- the absorbed form of the step (an extra)
+    # Same scores and selection; stages 3-4 gather the selected tokens' head scores and sum rows of A^V instead of
+    # rebuilding K^ and V^.  Valid where no rotation follows the reconstruction.  Not `value`.
+    absorbed = None
+    if not args.no_absorbed:
+        try:
+            ab_ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+            heads = torch.empty((w.batch, w.H_kv, w.L, xb.head_pitch(shape)), dtype=torch.float32, device="cuda")
+
+            def absorbed_step():
+                base = state["set0"]
+                for grp in range(w.n_groups):
+                    s = (base + grp) % n_sets
+                    g = groups[s]
+                    for l in range(w.G):
+                        xb.xkv_sr_decode_absorbed(shape, l, g["A_k"], g["A_v"], g["B_k"], g["B_v"], qs[s][l], out, None,
+                                                  None, ab_ws)
+                state["set0"] = (base + w.n_groups) % n_sets
+
+            absorbed_step()
+            ms_ab = time_loop(torch, absorbed_step, max(2, min(args.steps, 5)))
+            ab_kern = {
+                "head_scores": kernel_ms(xb.STAGE_SCORE,
+                                         lambda s, l: xb.xkv_head_scores(shape, l, groups[s]["A_k"], groups[s]["B_k"],
+                                                                         qs[s][l], S, heads, ab_ws)),
+                "absorb_rows": kernel_ms(xb.STAGE_ABSORB_ROWS,
+                                         lambda s, l: xb.xkv_attend_absorbed(shape, l, groups[s]["A_v"], groups[s]["B_v"],
+                                                                             heads, idx, out, ab_ws)),
+            }
+            ab_bytes = {"head_scores": w.batch * (e * w.L * w.r_k + 4 * w.H_kv * w.L * (1 + xb.head_pitch(shape))),
+                        "absorb_rows": w.batch * w.H_kv * w.k * (e * w.r_v + 4 * xb.head_pitch(shape))}
+            absorbed = {"ms_per_step": round(ms_ab, 4), "tokens_per_s": round(w.batch / (ms_ab * 1e-3), 2),
+                        "speedup_vs_gather_reconstruct": round(ms_sr / ms_ab, 3),
+                        "kernels": {kn: {"kernel_ms": round(ab_kern[kn], 5), "alg_bytes": ab_bytes[kn],
+                                         "kernel_GBps": round(ab_bytes[kn] / (ab_kern[kn] * 1e-3) / 1e9, 1)}
+                                    for kn in ab_kern},
+                        "note": "xkv_sr_decode_absorbed: per-head scores kept by the score kernel, softmax over the "
+                                "selected ones, weighted sum of rows of A^V, B^V applied once per head"}
+            del ab_ws, heads
+        except xb.XkvError as err:
+            absorbed = {"skipped": str(err)}
+
     # ---------------------------------------------------------------- the step before the path: factorization
     # One layer group's key cache of every sequence (power-law spectrum, full rank) -> A^K, B^K (Eq. 1), as prefill
     # would do once per prompt and group, for keys and for values.  Not part of the decode step or of `value`.
@@ -469,7 +512,7 @@ def main():
                    "factor_sets_in_hbm": n_sets, "copies_rotated": copies},
         "roofline": roofline, "cpu_baseline": cpu, "stages": stages, "dense_baseline": dense,
         "speedup_vs_dense": (round(dense["ms_per_step"] / ms_sr, 3) if dense else None),
-        "graph_replay": graph_replay, "landmark_selector": landmark, "factorize": factorize, "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
+        "graph_replay": graph_replay, "landmark_selector": landmark, "absorbed": absorbed, "factorize": factorize, "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
     }
     print(json.dumps(result))
 

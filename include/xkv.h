@@ -207,10 +207,43 @@ XKV_API xkv_status xkv_gather_attend_ex(const xkv_shape *shape, int32_t layer_in
                                         const int32_t *idx, const int32_t *counts, float rope_theta, void *out,
                                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The SR step in the absorbed form (Sec. 3.3, Fig. 1: B_l is multiplied into the query and into the output once,
+ * instead of into every selected token).  Stages 1-2 are unchanged -- same scores, same index sets as
+ * xkv_sr_decode -- but the score kernel also keeps every query head's score; stages 3-4 then become
+ *     w_h = softmax_j( s_h[I_j] ),      o_h = ( sum_j w_hj A^V[I_j, :] ) B^V_g,
+ * which equals softmax(q_h K^_g^T / sqrt(d_h)) V^_g with K^ = A^K[I] B^K, V^ = A^V[I] B^V up to rounding order
+ * (K^ and V^ are never rounded to the storage type here).  Only valid where the reconstructed keys need no
+ * per-token treatment (no rotary embedding after reconstruction).  xkv_sr_decode remains the named
+ * gather-reconstruct path; this is an additional one.
+ *   xkv_head_scores: stage 1 + 2a; heads_out [batch][H_kv][L][nrp] fp32 (device, 16-byte aligned), nrp = H_q/H_kv
+ *     rounded up to a power of two, padding written as 0; score_out (nullable) [batch][H_kv][L] is the pooled
+ *     score and is the maximum of exactly the values in heads_out.
+ *   xkv_attend_absorbed: stages 3-4 from given head scores and ids idx [batch][H_kv][k] (each in [0, L); ids
+ *     outside are clamped); out [batch][H_q][d_h] in the shape's dtype.
+ *   xkv_sr_decode_absorbed: the whole step; idx_out / score_out nullable as in xkv_sr_decode; K_tail, V_tail, T as
+ *     in xkv_sr_decode_tail (the T most recent tokens, uncompressed, join the softmax; T = 0 and NULL for none).
+ * workspace for all three: xkv_absorbed_workspace_bytes() bytes, 256-byte aligned (it contains the head scores of
+ * one layer, batch * H_kv * L * nrp * 4 bytes).  XKV_ERR_UNSUPPORTED unless rows of A^V are whole 16-byte pieces
+ * (r_v a multiple of 8 for bf16, of 4 for fp32); A_v must be 16-byte aligned.
+ */
+XKV_API xkv_status xkv_absorbed_workspace_bytes(const xkv_shape *shape, size_t *bytes);
+XKV_API xkv_status xkv_head_scores(const xkv_shape *shape, int32_t layer_in_group, const void *A_k, const void *B_k,
+                                   const void *q, float *score_out, float *heads_out, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream);
+XKV_API xkv_status xkv_attend_absorbed(const xkv_shape *shape, int32_t layer_in_group, const void *A_v,
+                                       const void *B_v, const float *head_scores, const int32_t *idx, void *out,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+XKV_API xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                          const void *A_v, const void *B_k, const void *B_v, const void *q,
+                                          const void *K_tail, const void *V_tail, int32_t T, void *out,
+                                          int32_t *idx_out, float *score_out, void *workspace, size_t workspace_bytes,
+                                          void *hip_stream);
+
 /* Measurement aid for callers that want the duration of one kernel rather than of a whole call.
  * Not part of the method.  For stage = 0 (low-rank score kernel), 1 (gather-reconstruct + sparse
- * attention kernel), 2 (dense decode kernel) or 3 (the Gram-matrix product X_cat^T X_cat of xkv_factorize, all
- * sequences of a chunk in one launch), every later call that launches that kernel records
+ * attention kernel), 2 (dense decode kernel), 3 (the Gram-matrix product X_cat^T X_cat of xkv_factorize, all
+ * sequences of a chunk in one launch) or 4 (the row-sum kernel of xkv_attend_absorbed), every later call that launches that kernel records
  * start_event on the call's stream right before the launch and stop_event right after it.  Both are
  * hipEvent_t created by the caller with timing enabled (HOST handles, passed as void*); NULL for
  * either switches the recording off.  Process-wide state; not thread safe. */

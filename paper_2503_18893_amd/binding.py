@@ -20,6 +20,7 @@ DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
 ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score",
                 "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_factorize_workspace_bytes", "xkv_factorize",
                 "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_gather_attend_ex",
+                "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
                 "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
@@ -90,11 +91,15 @@ def load() -> ctypes.CDLL:
         lib.xkv_sr_decode_landmark.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, i32,
                                                vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_gather_attend_ex.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+        lib.xkv_absorbed_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
+        lib.xkv_head_scores.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_attend_absorbed.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_sr_decode_absorbed.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:15]:
+        for name in ENTRY_POINTS[:19]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -220,7 +225,41 @@ def xkv_sr_decode_landmark(shape, layer_in_group, A_k, A_v, B_k, B_v, q, landmar
            "xkv_sr_decode_landmark")
 
 
-STAGE_SCORE, STAGE_GATHER_ATTEND, STAGE_DENSE, STAGE_FACTORIZE_GRAM = 0, 1, 2, 3
+def head_pitch(shape) -> int:
+    """Row length of the per-head score array: query heads per KV head rounded up to a power of two."""
+    n_rep = shape.H_q // shape.H_kv
+    return 1 << max(0, (n_rep - 1).bit_length())
+
+
+def xkv_absorbed_workspace_bytes(shape) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().xkv_absorbed_workspace_bytes(ctypes.byref(shape.c()), ctypes.byref(n)), "xkv_absorbed_workspace_bytes")
+    return int(n.value)
+
+
+def xkv_head_scores(shape, layer_in_group, A_k, B_k, q, score_out, heads_out, workspace, stream=None):
+    _check(load().xkv_head_scores(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(B_k), _ptr(q), _ptr(score_out),
+                                  _ptr(heads_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                  _stream(stream)), "xkv_head_scores")
+
+
+def xkv_attend_absorbed(shape, layer_in_group, A_v, B_v, head_scores, idx, out, workspace, stream=None):
+    _check(load().xkv_attend_absorbed(ctypes.byref(shape.c()), layer_in_group, _ptr(A_v), _ptr(B_v), _ptr(head_scores),
+                                      _ptr(idx), _ptr(out), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_attend_absorbed")
+
+
+def xkv_sr_decode_absorbed(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, idx_out, score_out, workspace,
+                           stream=None, K_tail=None, V_tail=None, T=0):
+    _check(load().xkv_sr_decode_absorbed(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
+                                         _ptr(B_v), _ptr(q), _ptr(K_tail), _ptr(V_tail), int(T), _ptr(out),
+                                         _ptr(idx_out), _ptr(score_out), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_sr_decode_absorbed")
+
+
+STAGE_SCORE, STAGE_GATHER_ATTEND, STAGE_DENSE, STAGE_FACTORIZE_GRAM, STAGE_ABSORB_ROWS = 0, 1, 2, 3, 4
 
 
 def xkv_profile_kernel(stage, start_event=None, stop_event=None):

@@ -81,6 +81,48 @@ __global__ __launch_bounds__(256) void score_generic_kernel(const T *__restrict_
     }
 }
 
+// Same walk, but every query head's score is kept as well: S_heads is [batch][H_kv][L][nrp] with nrp the
+// number of query heads per KV head rounded up to a power of two (the padding is written as zero).  The pooled
+// score is the maximum of exactly the values stored, so a softmax over stored head scores agrees with the
+// selection made on S.
+template <typename T>
+__global__ __launch_bounds__(256) void score_heads_generic_kernel(const T *__restrict__ A_k,     // [batch][L][r_k]
+                                                                  const float *__restrict__ P,  // [batch][H_q][r_k]
+                                                                  float *__restrict__ S,        // [batch][H_kv][L]
+                                                                  float *__restrict__ S_heads, int L, int r_k,
+                                                                  int H_kv, int H_q, int nrp, float scale)
+{
+    const int b = blockIdx.y;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= L) return;
+    const int n_rep = H_q / H_kv;
+    const T *Arow = A_k + ((size_t)b * L + t) * r_k;
+    const float *Pb = P + (size_t)b * H_q * r_k;
+    for (int g = 0; g < H_kv; ++g) {
+        float best = -INFINITY;
+        float *dst = S_heads + (((size_t)b * H_kv + g) * L + t) * nrp;
+        for (int h0 = 0; h0 < nrp; h0 += 8) {
+            float acc[8];
+#pragma unroll
+            for (int hh = 0; hh < 8; ++hh) acc[hh] = 0.0f;
+            const float *Pg = Pb + (size_t)(g * n_rep + h0) * r_k;
+            const int nh = n_rep - h0 < 8 ? n_rep - h0 : 8;  // may be <= 0 inside the padding
+            for (int i = 0; i < r_k && nh > 0; ++i) {
+                const float a = to_f32(Arow[i]);
+#pragma unroll
+                for (int hh = 0; hh < 8; ++hh)
+                    if (hh < nh) acc[hh] = fmaf(a, Pg[(size_t)hh * r_k + i], acc[hh]);
+            }
+#pragma unroll
+            for (int hh = 0; hh < 8; ++hh) {
+                if (hh < nh) best = fmaxf(best, scale * acc[hh]);
+                if (h0 + hh < nrp) dst[h0 + hh] = hh < nh ? scale * acc[hh] : 0.0f;
+            }
+        }
+        S[((size_t)b * H_kv + g) * L + t] = best;
+    }
+}
+
 // ==========================================================================================
 // bf16 MFMA path.  The contraction S^T = P_slots (32 x r) . A^T (r x tokens) runs on
 // v_mfma_f32_32x32x16_bf16: the MFMA "A" operand is a fragment of P (32 head slots x 16 ranks)
@@ -240,20 +282,50 @@ __device__ __forceinline__ void score_group(f32x16_t &acc_h, f32x16_t &acc_l, u3
     }
 }
 
-template <int N_REP, int WAVES>
+// Heads per KV head rounded up to a power of two: the row length of the per-head score array.
+constexpr int head_pitch(int n_rep) { return n_rep <= 1 ? 1 : n_rep <= 2 ? 2 : n_rep <= 4 ? 4 : n_rep <= 8 ? 8 : 16; }
+
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// One token's head scores (NRP consecutive floats, v[] already zero beyond the real heads), as hidden stores
+// like the pooled ones below.
+template <int NRP> __device__ __forceinline__ void store_head_row(float *dst, const float (&v)[16])
+{
+    if constexpr (NRP == 1) {
+        asm volatile("global_store_dword %0, %1, off" : : "v"(dst), "v"(v[0]) : "memory");
+    } else if constexpr (NRP == 2) {
+        const f32x2_t x = {v[0], v[1]};
+        asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(dst), "v"(x) : "memory");
+    } else {
+#pragma unroll
+        for (int c = 0; c < NRP / 4; ++c) {
+            const f32x4_t x = {v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]};
+            asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(dst + 4 * c), "v"(x) : "memory");
+        }
+    }
+}
+
+// HEADS: also write every query head's score, S_heads [batch][H_kv][L][head_pitch(N_REP)] (padding zero); the
+// pooled score is the maximum of exactly those values.
+template <int N_REP, int WAVES, bool HEADS>
 __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *__restrict__ A_k,
                                                                         const bf16_t *__restrict__ Pfrag,
                                                                         float *__restrict__ S, int L, int r_k,
                                                                         int H_kv, int F8, int tiles_per_wg,
                                                                         float scale, uint32_t *__restrict__ row_hist,
-                                                                        uint32_t *__restrict__ chunk_hist)
+                                                                        uint32_t *__restrict__ chunk_hist,
+                                                                        float *__restrict__ S_heads)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);  // [2][F8][64] fragments of 16 B per lane
     constexpr int GPH = 16 / N_REP;
     // Pooled scores are kept in registers and written in bursts of RT tiles: 4 B per (KV head, token) are only 3 %
     // of the bytes, but dribbled out between the reads they cost the memory system as much as 15 % of the stream.
-    constexpr int RT = 64 / GPH;
+    // (with HEADS all 16 head slots of a tile are kept instead, and bursts are four tiles)
+    constexpr int RT = HEADS ? 4 : 64 / GPH;
+    constexpr int RW = HEADS ? 16 : GPH;
+    constexpr int NRP = head_pitch(N_REP);
     const int b = blockIdx.z, blk = blockIdx.y, nblk = gridDim.y;
     const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
     const int n = lane & 31, hf = lane >> 5;
@@ -335,11 +407,11 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
     f32x16_t acc_h, acc_l;  // separate chains for the high parts and the remainders of P
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc_h[v] = acc_l[v] = 0.0f;
-    float res[RT][GPH];
+    float res[RT][RW];
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int u = 0; u < GPH; ++u) res[i][u] = 0.0f;
+        for (int u = 0; u < RW; ++u) res[i][u] = 0.0f;
     int S_c = 0, ti = 0, tile0 = tile;  // group within the tile, tiles held in res, first of them
     // Stores go through inline assembly: a store the compiler knows of inside conditional code makes its count of
     // outstanding memory operations uncertain, and it then waits for *all* prefetches at the top of the loop.
@@ -354,7 +426,18 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
                     const int g = blk * 2 * GPH + hf * GPH + u;
                     if (g < H_kv) {
                         float *dst = S + ((size_t)b * H_kv + g) * L + t;
-                        asm volatile("global_store_dword %0, %1, off" : : "v"(dst), "v"(res[i][u]) : "memory");
+                        if constexpr (HEADS) {
+                            float hv[16];
+#pragma unroll
+                            for (int hh = 0; hh < 16; ++hh) hv[hh] = hh < N_REP ? res[i][(u * N_REP + hh) & 15] : 0.0f;
+                            float best = hv[0];
+#pragma unroll
+                            for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, hv[hh]);
+                            asm volatile("global_store_dword %0, %1, off" : : "v"(dst), "v"(best) : "memory");
+                            store_head_row<NRP>(S_heads + (((size_t)b * H_kv + g) * L + t) * NRP, hv);
+                        } else {
+                            asm volatile("global_store_dword %0, %1, off" : : "v"(dst), "v"(res[i][u]) : "memory");
+                        }
                     }
                 }
             }
@@ -371,8 +454,17 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
 #pragma unroll
             for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
             best *= scale;
+            if constexpr (HEADS) {
 #pragma unroll
-            for (int i = 0; i < RT; ++i) res[i][u] = (i == ti) ? best : res[i][u];
+                for (int hh = 0; hh < N_REP; ++hh) {
+                    const float hs = scale * (acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
+#pragma unroll
+                    for (int i = 0; i < RT; ++i) res[i][u * N_REP + hh] = (i == ti) ? hs : res[i][u * N_REP + hh];
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < RT; ++i) res[i][u] = (i == ti) ? best : res[i][u];
+            }
             if (do_hist) {
                 // Done per tile, where it hides behind the other wavefronts' memory waits.  Scores cluster in few
                 // bins: one LDS add per distinct (head slot, bin) of the wavefront.
@@ -443,9 +535,29 @@ static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
 }
 
 static hipError_t launch_score_generic(const xkv_shape &s, const Plan &p, int layer, const void *A_k,
-                                       const void *B_k, const void *q, float *P, float *S, hipStream_t st)
+                                       const void *B_k, const void *q, float *P, float *S, float *S_heads,
+                                       hipStream_t st)
 {
     dim3 pgrid((s.r_k * s.H_kv + 3) / 4, s.batch), grid((s.L + 255) / 256, s.batch), block(256);
+    if (S_heads) {
+        const int nrp = head_pitch(s.H_q / s.H_kv);
+        if (s.dtype == XKV_F32) {
+            hipLaunchKernelGGL(project_q_kernel<float>, pgrid, block, 0, st, (const float *)B_k, (const float *)q, P,
+                               s.G, layer, s.r_k, s.H_kv, s.H_q, s.d_h);
+            profile_begin(0, st);
+            hipLaunchKernelGGL(score_heads_generic_kernel<float>, grid, block, 0, st, (const float *)A_k, P, S, S_heads,
+                               s.L, s.r_k, s.H_kv, s.H_q, nrp, p.scale);
+            profile_end(0, st);
+        } else {
+            hipLaunchKernelGGL(project_q_kernel<bf16_t>, pgrid, block, 0, st, (const bf16_t *)B_k, (const bf16_t *)q,
+                               P, s.G, layer, s.r_k, s.H_kv, s.H_q, s.d_h);
+            profile_begin(0, st);
+            hipLaunchKernelGGL(score_heads_generic_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)A_k, P, S,
+                               S_heads, s.L, s.r_k, s.H_kv, s.H_q, nrp, p.scale);
+            profile_end(0, st);
+        }
+        return hipGetLastError();
+    }
     if (s.dtype == XKV_F32) {
         hipLaunchKernelGGL(project_q_kernel<float>, pgrid, block, 0, st, (const float *)B_k, (const float *)q, P, s.G,
                            layer, s.r_k, s.H_kv, s.H_q, s.d_h);
@@ -493,10 +605,30 @@ bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits, i
     return true;
 }
 
+// The long-stream kernel, with or without the per-head output (S_heads only read when HEADS).
+template <int N_REP, int WAVES, bool HEADS>
+static hipError_t launch_score_stream_t(const xkv_shape &s, const Plan &p, const bf16_t *A_k, const bf16_t *Pfrag,
+                                        float *S, int F8, dim3 sgrid, size_t lds_stream, uint32_t *row_hist,
+                                        uint32_t *chunk_hist, float *S_heads, hipStream_t st)
+{
+    static bool attr = false;
+    if (!attr) {
+        hipError_t e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP, WAVES, HEADS>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e != hipSuccess) return e;
+        attr = true;
+    }
+    profile_begin(0, st);
+    hipLaunchKernelGGL((score_stream_kernel<N_REP, WAVES, HEADS>), sgrid, dim3(WAVES * 64), lds_stream, st, A_k, Pfrag, S,
+                       s.L, s.r_k, s.H_kv, F8, p.score_tpw, p.scale, row_hist, chunk_hist, S_heads);
+    profile_end(0, st);
+    return hipGetLastError();
+}
+
 template <int N_REP>
 static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const bf16_t *A_k, const bf16_t *Pfrag,
                                       float *S, int F8, uint32_t *row_hist, uint32_t *chunk_hist, bool *hist_done,
-                                      hipStream_t st)
+                                      float *S_heads, hipStream_t st)
 {
     const int nblk = mfma_blocks(s.H_kv, N_REP);
     const int n_tiles = (s.L + 31) / 32;
@@ -506,36 +638,21 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
         const size_t lds_stream = lds + (size_t)p.score_waves * 512 * 16 +
                                   (with_hist ? (size_t)2 * mfma_gph(N_REP) * kTopkBins * 4 : 0);
         dim3 sgrid((n_tiles + p.score_tpw - 1) / p.score_tpw, nblk, s.batch);
-        hipError_t e = hipSuccess;
-        if (p.score_waves == kScoreWaves) {
-            static bool attr8 = false;
-            if (!attr8) {
-                e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP, kScoreWaves>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-                if (e != hipSuccess) return e;
-                attr8 = true;
-            }
-            profile_begin(0, st);
-            hipLaunchKernelGGL((score_stream_kernel<N_REP, kScoreWaves>), sgrid, dim3(kScoreWaves * 64), lds_stream, st,
-                               A_k, Pfrag, S, s.L, s.r_k, s.H_kv, F8, p.score_tpw, p.scale,
-                               with_hist ? row_hist : nullptr, with_hist ? chunk_hist : nullptr);
-            profile_end(0, st);
-        } else {
-            static bool attr4 = false;
-            if (!attr4) {
-                e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP, 4>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-                if (e != hipSuccess) return e;
-                attr4 = true;
-            }
-            profile_begin(0, st);
-            hipLaunchKernelGGL((score_stream_kernel<N_REP, 4>), sgrid, dim3(4 * 64), lds_stream, st, A_k, Pfrag, S, s.L,
-                               s.r_k, s.H_kv, F8, p.score_tpw, p.scale, with_hist ? row_hist : nullptr,
-                               with_hist ? chunk_hist : nullptr);
-            profile_end(0, st);
-        }
+        uint32_t *rh = with_hist ? row_hist : nullptr, *ch = with_hist ? chunk_hist : nullptr;
+        hipError_t e;
+        if (p.score_waves == kScoreWaves)
+            e = S_heads ? launch_score_stream_t<N_REP, kScoreWaves, true>(s, p, A_k, Pfrag, S, F8, sgrid, lds_stream, rh,
+                                                                          ch, S_heads, st)
+                        : launch_score_stream_t<N_REP, kScoreWaves, false>(s, p, A_k, Pfrag, S, F8, sgrid, lds_stream,
+                                                                           rh, ch, nullptr, st);
+        else
+            e = S_heads ? launch_score_stream_t<N_REP, 4, true>(s, p, A_k, Pfrag, S, F8, sgrid, lds_stream, rh, ch,
+                                                                S_heads, st)
+                        : launch_score_stream_t<N_REP, 4, false>(s, p, A_k, Pfrag, S, F8, sgrid, lds_stream, rh, ch,
+                                                                 nullptr, st);
+        if (e != hipSuccess) return e;
         if (hist_done) *hist_done = with_hist;
-        return hipGetLastError();
+        return hipSuccess;
     }
     // about two workgroups per compute unit in a single round, each streaming one contiguous range of a
     // sequence (staging P costs a fixed 2 KiB per rank-16 fragment, so fewer, longer workgroups win)
@@ -561,11 +678,15 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
 
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
-                              bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st)
+                              bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st,
+                              float *S_heads)
 {
     if (hist_done) *hist_done = false;
     if (packed_done) *packed_done = false;
-    if (!score_mfma_ok(s, A_k) || ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) != 0) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, st);
+    // per-head scores come from the long-stream kernel or from the general one
+    const bool mfma = score_mfma_ok(s, A_k) && ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) == 0 &&
+                      (!S_heads || (p.score_stream && (((uintptr_t)S_heads) & 15u) == 0));
+    if (!mfma) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, S_heads, st);
     const int n_rep = s.H_q / s.H_kv;
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;
     const int gph = mfma_gph(n_rep), nblk = mfma_blocks(s.H_kv, n_rep);
@@ -594,15 +715,15 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     if (e != hipSuccess) return e;
     const bf16_t *A = (const bf16_t *)A_k;
     switch (n_rep) {
-    case 1: return launch_score_mfma_t<1>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    case 2: return launch_score_mfma_t<2>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    case 3: return launch_score_mfma_t<3>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    case 4: return launch_score_mfma_t<4>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    case 5: return launch_score_mfma_t<5>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    case 6: return launch_score_mfma_t<6>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    case 7: return launch_score_mfma_t<7>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    case 8: return launch_score_mfma_t<8>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
-    default: return launch_score_mfma_t<16>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, st);
+    case 1: return launch_score_mfma_t<1>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    case 2: return launch_score_mfma_t<2>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    case 3: return launch_score_mfma_t<3>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    case 4: return launch_score_mfma_t<4>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    case 5: return launch_score_mfma_t<5>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    case 6: return launch_score_mfma_t<6>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    case 7: return launch_score_mfma_t<7>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    case 8: return launch_score_mfma_t<8>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    default: return launch_score_mfma_t<16>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
     }
 }
 

@@ -7,7 +7,7 @@
 
 namespace xkv {
 
-ProfileEvents g_profile[4] = {};
+ProfileEvents g_profile[5] = {};
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -480,9 +480,108 @@ xkv_status xkv_gather_attend_ex(const xkv_shape *shape, int32_t layer, const voi
     return hip_status(e);
 }
 
+// Workspace of the absorbed calls: the ordinary plan's, then per-head scores and the partial row sums.
+static xkv_status prepare_absorbed(const xkv_shape *s, void *ws, size_t ws_bytes, Plan &p, AbsorbPlan &a)
+{
+    xkv_status st = validate(s);
+    if (st != XKV_OK) return st;
+    if (!absorb_shape_ok(*s)) return XKV_ERR_UNSUPPORTED;
+    make_plan(*s, p);
+    a = make_absorb_plan(*s, p.total);
+    if (!ws) return XKV_ERR_INVALID_ARG;
+    if (ws_bytes < a.total) return XKV_ERR_WORKSPACE;
+    if (((uintptr_t)ws) & 255u) return XKV_ERR_INVALID_ARG;
+    return XKV_OK;
+}
+
+xkv_status xkv_absorbed_workspace_bytes(const xkv_shape *shape, size_t *bytes)
+{
+    if (!bytes) return XKV_ERR_INVALID_ARG;
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    if (!absorb_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
+    Plan p;
+    make_plan(*shape, p);
+    *bytes = make_absorb_plan(*shape, p.total).total;
+    return XKV_OK;
+}
+
+xkv_status xkv_head_scores(const xkv_shape *shape, int32_t layer, const void *A_k, const void *B_k, const void *q,
+                           float *score_out, float *heads_out, void *workspace, size_t workspace_bytes,
+                           void *hip_stream)
+{
+    Plan p;
+    AbsorbPlan a;
+    xkv_status st = prepare_absorbed(shape, workspace, workspace_bytes, p, a);
+    if (st != XKV_OK) return st;
+    if (!A_k || !B_k || !q || !heads_out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if (((uintptr_t)heads_out) & 15u) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    float *S = score_out ? score_out : at<float>(workspace, p.off_score);
+    return hip_status(launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S, nullptr, nullptr,
+                                         nullptr, nullptr, nullptr, (hipStream_t)hip_stream, heads_out));
+}
+
+xkv_status xkv_attend_absorbed(const xkv_shape *shape, int32_t layer, const void *A_v, const void *B_v,
+                               const float *head_scores, const int32_t *idx, void *out, void *workspace,
+                               size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    AbsorbPlan a;
+    xkv_status st = prepare_absorbed(shape, workspace, workspace_bytes, p, a);
+    if (st != XKV_OK) return st;
+    if (!A_v || !B_v || !head_scores || !idx || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)A_v) | ((uintptr_t)head_scores)) & 15u) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *po = at<float>(workspace, a.off_po), *pml = at<float>(workspace, a.off_pml);
+    hipError_t e = launch_absorbed(*shape, a, layer, A_v, B_v, head_scores, idx, po, pml,
+                                   at<float>(workspace, a.off_part_u), at<float>(workspace, a.off_part_ml), stream);
+    if (e == hipSuccess) e = launch_combine(*shape, a.slices, po, pml, out, stream);
+    return hip_status(e);
+}
+
+xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                  const void *B_k, const void *B_v, const void *q, const void *K_tail,
+                                  const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (T < 0 || (T > 0 && (!K_tail || !V_tail))) return XKV_ERR_INVALID_ARG;
+    Plan p;
+    AbsorbPlan a;
+    xkv_status st = prepare_absorbed(shape, workspace, workspace_bytes, p, a);
+    if (st != XKV_OK) return st;
+    if (!A_k || !A_v || !B_k || !B_v || !q || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if (((uintptr_t)A_v) & 15u) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *S = score_out ? score_out : at<float>(workspace, p.off_score);
+    int32_t *idx = idx_out ? idx_out : at<int32_t>(workspace, p.off_idx);
+    float *heads = at<float>(workspace, a.off_heads);
+    uint32_t *hist = at<uint32_t>(workspace, p.off_hist), *state = at<uint32_t>(workspace, p.off_state);
+    bool level0_done = false;
+    hipError_t e = hipSuccess;
+    if (p.score_hist) e = launch_topk_init(p, state, stream);
+    if (e == hipSuccess)
+        e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
+                               p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
+                               &level0_done, nullptr, nullptr, stream, heads);
+    if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, level0_done, stream);
+    float *po = at<float>(workspace, a.off_po), *pml = at<float>(workspace, a.off_pml);
+    if (e == hipSuccess)
+        e = launch_absorbed(*shape, a, layer, A_v, B_v, heads, idx, po, pml, at<float>(workspace, a.off_part_u),
+                            at<float>(workspace, a.off_part_ml), stream);
+    // the uncompressed tail, if any, joins the same softmax through its own set of partials (as in xkv_sr_decode_tail)
+    int n_tail = 0;
+    float *tail_o = at<float>(workspace, p.off_tail_o), *tail_ml = at<float>(workspace, p.off_tail_ml);
+    if (T > 0 && e == hipSuccess) e = launch_tail(*shape, p, K_tail, V_tail, q, T, tail_o, tail_ml, &n_tail, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, a.slices, po, pml, out, stream, n_tail, tail_o, tail_ml);
+    return hip_status(e);
+}
+
 xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event)
 {
-    if (stage < 0 || stage > 3) return XKV_ERR_INVALID_ARG;
+    if (stage < 0 || stage > 4) return XKV_ERR_INVALID_ARG;
     g_profile[stage].start = (start_event && stop_event) ? (hipEvent_t)start_event : nullptr;
     g_profile[stage].stop = (start_event && stop_event) ? (hipEvent_t)stop_event : nullptr;
     return XKV_OK;

@@ -87,11 +87,11 @@ constexpr int kStateWords = 8;   // per row: (prefix, k_rem) for each resolved l
 xkv_status make_plan(const xkv_shape &s, Plan &p);
 
 // Optional event pair recorded around the main kernel of a stage (0 score, 1 gather-attend, 2 dense,
-// 3 Gram-matrix product of the factorization).
+// 3 Gram-matrix product of the factorization, 4 row sums of the absorbed attention).
 struct ProfileEvents {
     hipEvent_t start, stop;
 };
-extern ProfileEvents g_profile[4];
+extern ProfileEvents g_profile[5];
 inline void profile_begin(int stage, hipStream_t st)
 {
     if (g_profile[stage].start && g_profile[stage].stop) (void)hipEventRecord(g_profile[stage].start, st);
@@ -128,7 +128,11 @@ bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits, i
 // histograms; *hist_done tells whether it did.
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
-                              bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st);
+                              bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st,
+                              float *S_heads = nullptr);
+// S_heads (nullable): also store every query head's score, [batch][H_kv][L][head_pitch(H_q / H_kv)] fp32 with the
+// padding zero; S is then the maximum of exactly the stored values.
+inline int head_pitch_of(int n_rep) { return n_rep <= 1 ? 1 : n_rep <= 2 ? 2 : n_rep <= 4 ? 4 : n_rep <= 8 ? 8 : 16; }
 bool topk_row_shape_ok(const xkv_shape &s);
 hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st);
 // level0_done: launch_topk_init ran and the level-0 histograms were already accumulated by the score stage.
@@ -162,6 +166,21 @@ hipError_t launch_combine(const xkv_shape &s, int n_part, const float *part_o, c
 bool dense_uses_mfma(const Plan &p, const void *K, const void *V, const void *q);
 hipError_t launch_reconstruct(const xkv_shape &s, int layer, const void *A, const void *B, int r, void *X,
                               hipStream_t st);
+// Attention over selected tokens in the absorbed form (see absorbed.hip): extra workspace laid out behind the
+// `base_bytes` of the ordinary plan.
+struct AbsorbPlan {
+    int nrp;         // row length of the per-head score array
+    int chunk;       // selected tokens per split
+    int splits;
+    int col_blocks;  // blocks of 64 sixteen-byte pieces of a row of A^V
+    int slices;      // attention partials per query head that the projection with B^V leaves
+    size_t off_heads, off_part_u, off_part_ml, off_po, off_pml, total;
+};
+bool absorb_shape_ok(const xkv_shape &s);
+AbsorbPlan make_absorb_plan(const xkv_shape &s, size_t base_bytes);
+hipError_t launch_absorbed(const xkv_shape &s, const AbsorbPlan &a, int layer, const void *A_v, const void *B_v,
+                           const float *S_heads, const int32_t *idx, float *po, float *pml, float *part_u,
+                           float *part_ml, hipStream_t st);
 // Cross-layer factorization of the caches of one group (see factorize.hip).
 bool factorize_shape_ok(const xkv_shape &s, int r);
 size_t factorize_workspace_bytes(const xkv_shape &s, int r);

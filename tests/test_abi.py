@@ -117,6 +117,35 @@ def test_landmark_calls_validate_on_the_host():
     assert lib.xkv_sr_decode_landmark(*args, 1 << 40, null) == xb.XKV_ERR_INVALID_ARG
 
 
+def test_absorbed_calls_validate_on_the_host():
+    lib = xb.load()
+    good = xb.Shape.of(synth.LLAMA_FULL)
+    c, null, one, al = good.c(), ctypes.c_void_p(0), ctypes.c_void_p(256), ctypes.c_void_p(4096)
+    n = ctypes.c_size_t(0)
+    need = xb.xkv_absorbed_workspace_bytes(good)
+    heads = good.batch * good.H_kv * good.L * xb.head_pitch(good) * 4          # the head scores live in the workspace
+    assert need >= xb.xkv_workspace_bytes(good) + heads
+    assert xb.head_pitch(xb.Shape.of(synth.QWEN)) == 8 and xb.head_pitch(good) == 4
+    ragged = xb.Shape.of(synth.LLAMA_FULL.with_(r_v=508)).c()                   # rows of A^V not whole 16-byte pieces
+    assert lib.xkv_absorbed_workspace_bytes(ctypes.byref(ragged), ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED
+    assert lib.xkv_absorbed_workspace_bytes(ctypes.byref(c), None) == xb.XKV_ERR_INVALID_ARG
+    big = 1 << 40
+    assert lib.xkv_head_scores(ctypes.byref(c), 0, one, one, one, null, null, al, big, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_head_scores(ctypes.byref(c), 0, one, one, one, null, ctypes.c_void_p(260), al, big, null) \
+        == xb.XKV_ERR_INVALID_ARG                                               # misaligned head scores
+    assert lib.xkv_head_scores(ctypes.byref(c), 9, one, one, one, null, al, al, big, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_attend_absorbed(ctypes.byref(c), 0, al, one, al, null, one, al, big, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_attend_absorbed(ctypes.byref(c), 0, ctypes.c_void_p(264), one, al, one, one, al, big, null) \
+        == xb.XKV_ERR_INVALID_ARG                                               # misaligned A^V
+    assert lib.xkv_attend_absorbed(ctypes.byref(c), 0, al, one, al, one, one, al, need - 1, null) == xb.XKV_ERR_WORKSPACE
+    assert lib.xkv_sr_decode_absorbed(ctypes.byref(c), 0, al, al, one, one, one, null, null, 0, null, null, null, al, big,
+                                      null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_sr_decode_absorbed(ctypes.byref(c), 0, al, al, one, one, one, null, null, 5, one, null, null, al, big,
+                                      null) == xb.XKV_ERR_INVALID_ARG          # a tail length without tail tensors
+    assert lib.xkv_sr_decode_absorbed(ctypes.byref(c), 0, al, al, one, one, one, null, null, 0, one, null, null, al,
+                                      xb.xkv_workspace_bytes(good), null) == xb.XKV_ERR_WORKSPACE
+
+
 def test_binding_has_no_cpu_fallback(monkeypatch):
     monkeypatch.setattr(xb, "_lib", None)
     monkeypatch.setattr(xb, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
