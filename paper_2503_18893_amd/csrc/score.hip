@@ -147,16 +147,21 @@ __global__ __launch_bounds__(256) void project_q_frag_kernel(ProjArgs a)
     project_q_frag_block(a, blockIdx.x, blockIdx.y);
 }
 
-// One launch for both small passes: blocks [0, n_proj) project the queries, the rest pack B for the gather-attend
-// kernel (see prepass.h).
-__global__ __launch_bounds__(256) void prepass_kernel(ProjArgs pj, PackArgs pk, int n_proj)
+// One launch for the small passes that precede the score kernel: blocks [0, n_proj) project the queries, the next
+// n_pack pack B for the gather-attend kernel (see prepass.h), the rest clear the row histograms that the score
+// kernel adds to (zero_words a multiple of 4).
+__global__ __launch_bounds__(256) void prepass_kernel(ProjArgs pj, PackArgs pk, int n_proj, int n_pack,
+                                                      uint32_t *__restrict__ zero, int zero_words)
 {
     if ((int)blockIdx.x < n_proj) {
         project_q_frag_block(pj, (int)blockIdx.x % pj.blocks_x, (int)blockIdx.x / pj.blocks_x);
-    } else {
+    } else if ((int)blockIdx.x < n_proj + n_pack) {
         const int pl = (int)blockIdx.x - n_proj;
         pack_b_block(pk, pl % pk.blocks_per_head, (pl / pk.blocks_per_head) % pk.H_kv,
                      pl / (pk.blocks_per_head * pk.H_kv));
+    } else {
+        const int i = 4 * (((int)blockIdx.x - n_proj - n_pack) * 256 + (int)threadIdx.x);
+        if (i < zero_words) *reinterpret_cast<u32x4_t *>(zero + i) = u32x4_t{0u, 0u, 0u, 0u};
     }
 }
 
@@ -703,11 +708,15 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     pj.d_h = s.d_h;
     pj.F8 = F8;
     pj.blocks_x = ((F8 / 2) * 2 * gph * nblk + 3) / 4;
-    if (fuse_pack) {
+    // the row histograms of the top-k stage are cleared in the same launch when the score kernel will add to them
+    const bool zero_hist = p.score_stream && p.score_hist && row_hist && chunk_hist;
+    const int zero_words = zero_hist ? p.rows * kTopkLevels * kTopkBins : 0;  // a multiple of 1024
+    if (fuse_pack || zero_hist) {
         const int n_proj = pj.blocks_x * s.batch;
-        const int n_pack = fuse_pack->blocks_per_head * fuse_pack->H_kv * fuse_pack->batch;
-        hipLaunchKernelGGL(prepass_kernel, dim3(n_proj + n_pack), dim3(256), 0, st, pj, *fuse_pack, n_proj);
-        if (packed_done) *packed_done = true;
+        const int n_pack = fuse_pack ? fuse_pack->blocks_per_head * fuse_pack->H_kv * fuse_pack->batch : 0;
+        hipLaunchKernelGGL(prepass_kernel, dim3(n_proj + n_pack + zero_words / 1024), dim3(256), 0, st, pj,
+                           fuse_pack ? *fuse_pack : PackArgs{}, n_proj, n_pack, row_hist, zero_words);
+        if (packed_done) *packed_done = fuse_pack != nullptr;
     } else {
         hipLaunchKernelGGL(project_q_frag_kernel, dim3(pj.blocks_x, s.batch), dim3(256), 0, st, pj);
     }

@@ -213,7 +213,6 @@ static xkv_status sr_decode_impl(const xkv_shape *shape, int32_t layer, const vo
     uint32_t *hist = at<uint32_t>(workspace, p.off_hist), *state = at<uint32_t>(workspace, p.off_state);
     bool level0_done = false;
     hipError_t e = hipSuccess;
-    if (p.score_hist) e = launch_topk_init(p, state, stream);  // the score kernel adds to the zeroed row histograms
     // B is packed for the matrix-core gather-attend kernel in the same launch as the query projection
     void *pack_ws = at<void>(workspace, p.off_bpack);
     PackArgs pa{};
@@ -425,7 +424,6 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     uint32_t *hist = at<uint32_t>(ws_s, ps.off_hist), *state = at<uint32_t>(ws_s, ps.off_state);
     bool level0_done = false;
     hipError_t e = launch_identity(*shape, ident, lp.score_shape.batch, stream);
-    if (e == hipSuccess && ps.score_hist) e = launch_topk_init(ps, state, stream);
     if (e == hipSuccess)
         e = launch_score_stage(lp.score_shape, ps, 0, landmarks, ident, q, at<void>(ws_s, ps.off_p), S,
                                ps.score_hist ? topk_row_hist(ps, state) : nullptr, ps.score_hist ? hist : nullptr,
@@ -560,10 +558,7 @@ xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer, const v
     float *heads = at<float>(workspace, a.off_heads);
     uint32_t *hist = at<uint32_t>(workspace, p.off_hist), *state = at<uint32_t>(workspace, p.off_state);
     bool level0_done = false;
-    hipError_t e = hipSuccess;
-    if (p.score_hist) e = launch_topk_init(p, state, stream);
-    if (e == hipSuccess)
-        e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
+    hipError_t e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
                                p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
                                &level0_done, nullptr, nullptr, stream, heads);
     if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, level0_done, stream);

@@ -123,9 +123,10 @@ struct PackArgs {
 inline uint32_t *topk_row_hist(const Plan &p, uint32_t *state) { return state + (size_t)p.rows * kStateWords; }
 bool score_stream_plan(const xkv_shape &s, int *tiles_per_wg, bool *hist_fits, int *waves);
 // fuse_pack (nullable): also pack B for the gather-attend kernel in the projection launch (matrix-core path
-// only; *packed_done tells whether it did).  If row_hist/chunk_hist are given and the long-stream kernel runs, it also adds the histogram of the top
-// 8 key bits of every pooled score to the row histograms (already zeroed) and stores the per-chunk
-// histograms; *hist_done tells whether it did.
+// only; *packed_done tells whether it did).  If row_hist/chunk_hist are given and the long-stream kernel runs, the
+// projection launch also clears the row histograms (all levels) and the score kernel adds the histogram of the top
+// 8 key bits of every pooled score to them and stores the per-chunk histograms; *hist_done tells whether it did
+// (if not, the row histograms were not touched).
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
                               bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st,
