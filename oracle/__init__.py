@@ -395,3 +395,82 @@ _RATIO = {"C_K": 0, "C_V": 1, "xKV": 2, "xK-SR-gpu": 3, "xK-SR-total": 4, "xKV-S
 def compression_ratio(which, N, W, d, L, r_k, r_v=0, c=0):
     """Closed-form compression ratios of App. C.6."""
     return float(_load().oracle_compression_ratio(_RATIO[which], N, W, d, float(L), r_k, r_v, c))
+
+
+# ---------------------------------------------------------------------------------------------
+# Round-to-nearest quantisation of the token basis A (App. "Integrate with Quantization": a plain RTN
+# quantiser applied to the compressed cache; 4 bits -> 25.6x, 3 bits -> 32x on top of xKV's 8x).  The paper
+# gives no format.  The reading taken here is the one its two ratios fix: 25.6 / 8 = 16 / 5 and 32 / 8 = 16 / 4,
+# i.e. one extra bit per element of side information = two 16-bit numbers per group of 32 elements
+# (asymmetric quantisation: a step and an offset per group).  Groups are 32 consecutive ranks of one token's
+# row.  Where floating point decides an integer (the code), the arithmetic is fp32, the same on both sides.
+# ---------------------------------------------------------------------------------------------
+Q_GROUP = 32
+
+
+def _bf16_rne(x32: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest bf16 (ties to even), returned as fp32.  Finite inputs."""
+    u = np.ascontiguousarray(x32, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
+def quantize_rows(X, bits=4):
+    """RTN quantisation of X [rows][r] (r a multiple of 32) in groups of 32 along a row.
+
+    Per group: lo = min, step = bf16((max - lo) / (2^bits - 1)) (1 if that is 0), inv = 1 / step,
+    code = clip(rint((x - lo) * inv), 0, 2^bits - 1); every operation is a single fp32 operation.  lo is stored as
+    bf16 (exact when X is bf16).  Returns codes uint8 [rows][r], step and lo as fp32 [rows][r / 32]."""
+    X = np.asarray(X)
+    if X.dtype == np.uint16:
+        X = (X.astype(np.uint32) << 16).view(np.float32)
+    X = np.ascontiguousarray(X, np.float32)
+    rows, r = X.shape
+    assert r % Q_GROUP == 0 and 2 <= bits <= 8
+    g = X.reshape(rows, r // Q_GROUP, Q_GROUP)
+    qmax = np.float32((1 << bits) - 1)
+    lo = _bf16_rne(g.min(axis=2))
+    step = _bf16_rne((g.max(axis=2) - lo) / qmax)
+    step = np.where(step > 0, step, np.float32(1.0)).astype(np.float32)
+    inv = (np.float32(1.0) / step).astype(np.float32)
+    t = ((g - lo[:, :, None]).astype(np.float32) * inv[:, :, None]).astype(np.float32)
+    codes = np.clip(np.rint(t), 0, qmax).astype(np.uint8)
+    return codes.reshape(rows, r), step, lo
+
+
+def dequantize_rows(codes, step, lo):
+    """x^ = step * code + lo in float64: the values every later stage of the path sees."""
+    rows, r = codes.shape
+    c = codes.reshape(rows, r // Q_GROUP, Q_GROUP).astype(np.float64)
+    return (c * step.astype(np.float64)[:, :, None] + lo.astype(np.float64)[:, :, None]).reshape(rows, r)
+
+
+def pack_q4(codes, step, lo):
+    """Byte layout of a 4-bit row as the library stores it: r/2 bytes of codes (rank 2i in the low nibble of
+    byte i, rank 2i+1 in the high nibble), then per group (step, lo) as two bf16 numbers.  5r/8 bytes per row."""
+    rows, r = codes.shape
+    assert codes.max(initial=0) < 16
+    nib = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8)
+    par = np.empty((rows, r // Q_GROUP, 2), np.uint16)
+    par[:, :, 0] = (np.ascontiguousarray(step, np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    par[:, :, 1] = (np.ascontiguousarray(lo, np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    return np.concatenate([nib, par.reshape(rows, -1).view(np.uint8)], axis=1)
+
+
+def unpack_q4(packed, r):
+    """Inverse of pack_q4: (codes, step, lo)."""
+    packed = np.ascontiguousarray(packed, np.uint8)
+    rows = packed.shape[0]
+    nib = packed[:, :r // 2]
+    codes = np.empty((rows, r), np.uint8)
+    codes[:, 0::2] = nib & 15
+    codes[:, 1::2] = nib >> 4
+    par = np.ascontiguousarray(packed[:, r // 2:]).view(np.uint16).reshape(rows, r // Q_GROUP, 2)
+    step = (par[:, :, 0].astype(np.uint32) << 16).view(np.float32)
+    lo = (par[:, :, 1].astype(np.uint32) << 16).view(np.float32)
+    return codes, np.ascontiguousarray(step), np.ascontiguousarray(lo)
+
+
+def quantized_bits_per_element(bits):
+    """Storage per element of a quantised row: the code plus two 16-bit numbers per group of 32."""
+    return bits + 2 * 16 / Q_GROUP

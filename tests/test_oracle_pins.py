@@ -579,3 +579,65 @@ def test_absorbed_form_equals_reconstruct_then_attend():
     for h in range(H_q):
         g = h // (H_q // H_kv)
         np.testing.assert_allclose(s[h], K[:, g * d_h:(g + 1) * d_h] @ q[h] / np.sqrt(d_h), rtol=1e-11, atol=1e-13)
+
+
+# ------------------------------------------------------------------------------ RTN quantisation of the token basis
+def test_quantiser_reproduces_the_papers_two_compression_ratios():
+    """App. 'Integrate with Quantization': 8x becomes 25.6x with 4 bits and 32x with 3 bits.  With one extra bit per
+    element of side information (two 16-bit numbers per group of 32) 16-bit storage shrinks by 16/5 and 16/4."""
+    assert oracle.quantized_bits_per_element(4) == 5.0 and oracle.quantized_bits_per_element(3) == 4.0
+    assert abs(8.0 * 16 / oracle.quantized_bits_per_element(4) - 25.6) < 1e-12
+    assert abs(8.0 * 16 / oracle.quantized_bits_per_element(3) - 32.0) < 1e-12
+    # the packed 4-bit row really has that size: 5r/8 bytes against 2r
+    codes, step, lo = oracle.quantize_rows(np.zeros((3, 128), np.float32))
+    assert oracle.pack_q4(codes, step, lo).shape == (3, 80)
+
+
+def test_quantiser_on_a_group_worked_by_hand():
+    # 32 values 0, 0.5, ..., 15.5: lo = 0, step = 15.5/15 -> bf16(1.0333..) = 1.03125, inv = fp32(1/1.03125)
+    x = (np.arange(32, dtype=np.float32) * 0.5)[None, :]
+    codes, step, lo = oracle.quantize_rows(x)
+    assert lo[0, 0] == 0.0 and step[0, 0] == np.float32(1.03125)
+    want = np.clip(np.rint(x[0] / 1.03125), 0, 15)
+    np.testing.assert_array_equal(codes[0], want)
+    assert codes[0, 0] == 0 and codes[0, -1] == 15 and codes[0, 1] == 0 and codes[0, 2] == 1
+    # a constant group: step falls back to 1, all codes 0, the value comes back exactly
+    c2, s2, l2 = oracle.quantize_rows(np.full((1, 32), -0.75, np.float32))
+    assert s2[0, 0] == 1.0 and not c2.any()
+    np.testing.assert_array_equal(oracle.dequantize_rows(c2, s2, l2), np.full((1, 32), -0.75))
+
+
+def test_quantiser_error_bound_and_extremes():
+    rng = np.random.default_rng(4)
+    x = synth.to_storage(rng.standard_normal((50, 256)) * np.exp(rng.standard_normal((50, 1))), "bf16")
+    xf = oracle.widen(x)
+    for bits in (3, 4, 8):
+        codes, step, lo = oracle.quantize_rows(x, bits)
+        assert codes.max() <= (1 << bits) - 1
+        xh = oracle.dequantize_rows(codes, step, lo)
+        g = xf.reshape(50, 8, 32)
+        # the minimum of a group is reproduced exactly (lo is a bf16 element of the group, code 0)
+        np.testing.assert_array_equal(xh.reshape(50, 8, 32).min(axis=2), g.min(axis=2))
+        # half a step, plus what rounding the step to bf16 can clip at the top of the range
+        span = g.max(axis=2) - g.min(axis=2)
+        bound = 0.5 * step.astype(np.float64) + span * 2.0 ** -8
+        assert (np.abs(xh - xf).reshape(50, 8, 32).max(axis=2) <= bound + 1e-12).all()
+        # the maximum of a group gets the top code (the bf16 rounding of the step moves it by at most
+        # (2^bits - 1) 2^-9 codes: nothing up to 4 bits, one code at 8 bits)
+        top = codes.reshape(50, 8, 32)[np.arange(50)[:, None], np.arange(8)[None, :], g.argmax(axis=2)]
+        assert (top >= (1 << bits) - (2 if bits == 8 else 1)).all()
+
+
+def test_q4_pack_layout_and_round_trip():
+    codes = (np.arange(64, dtype=np.uint8) % 16)[None, :].repeat(2, axis=0)
+    codes[1] = codes[1, ::-1]
+    step = np.array([[0.5, 2.0], [1.0, 0.25]], np.float32)
+    lo = np.array([[-1.0, 3.0], [0.0, -8.0]], np.float32)
+    p = oracle.pack_q4(codes, step, lo)
+    assert p.shape == (2, 40) and p.dtype == np.uint8
+    assert p[0, 0] == 0x10 and p[0, 1] == 0x32 and p[0, 7] == 0xFE          # rank 2i low nibble, 2i+1 high nibble
+    assert p[0, 32:36].tolist() == [0x00, 0x3F, 0x80, 0xBF]                 # bf16(0.5) = 0x3F00, bf16(-1) = 0xBF80
+    c2, s2, l2 = oracle.unpack_q4(p, 64)
+    np.testing.assert_array_equal(c2, codes)
+    np.testing.assert_array_equal(s2, step)
+    np.testing.assert_array_equal(l2, lo)
