@@ -240,6 +240,26 @@ XKV_API xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer_
                                           int32_t *idx_out, float *score_out, void *workspace, size_t workspace_bytes,
                                           void *hip_stream);
 
+/*
+ * 4-bit round-to-nearest quantisation of the token basis (App. "Integrate with Quantization": a plain RTN quantiser
+ * applied to the compressed cache, 25.6x total at 4 bits).  The paper gives no format; this one is what its ratios
+ * imply (one extra bit per element: two 16-bit numbers per group of 32).  A row of r bf16 numbers (r a multiple of
+ * 128) becomes 5r/8 bytes: r/2 bytes of codes (rank 2i in the low nibble of byte i, rank 2i+1 in the high nibble),
+ * then r/32 pairs (step, lo) of bf16.  Per group of 32 consecutive ranks: lo = min, step = bf16((max - lo) / 15)
+ * (1 if that is 0), code = clip(rint((x - lo) * (1 / step)), 0, 15) in fp32; the value every later stage sees is
+ * x^ = step * code + lo.
+ *   xkv_quantized_row_bytes: 5r/8, or XKV_ERR_UNSUPPORTED (bits != 4, r not a multiple of 128).
+ *   xkv_quantize_rows: X [rows][r] bf16 -> out [rows][5r/8] bytes (both device, 16-byte aligned).
+ *   xkv_attend_absorbed_q4: xkv_attend_absorbed with A^V given as quantised rows Aq_v [batch][L][5 r_v / 8]; the
+ *     rows are de-quantised in registers inside the row-sum kernel, so the gather moves 5/16 of the bytes.  bf16
+ *     shapes only; B_v, head_scores, idx, out and the workspace as in xkv_attend_absorbed.
+ */
+XKV_API xkv_status xkv_quantized_row_bytes(int32_t r, int32_t bits, size_t *bytes);
+XKV_API xkv_status xkv_quantize_rows(const void *X, int64_t rows, int32_t r, int32_t bits, void *out, void *hip_stream);
+XKV_API xkv_status xkv_attend_absorbed_q4(const xkv_shape *shape, int32_t layer_in_group, const void *Aq_v,
+                                          const void *B_v, const float *head_scores, const int32_t *idx, void *out,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Measurement aid for callers that want the duration of one kernel rather than of a whole call.
  * Not part of the method.  For stage = 0 (low-rank score kernel), 1 (gather-reconstruct + sparse
  * attention kernel), 2 (dense decode kernel), 3 (the Gram-matrix product X_cat^T X_cat of xkv_factorize, all

@@ -21,6 +21,7 @@ ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_tail", "x
                 "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_factorize_workspace_bytes", "xkv_factorize",
                 "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_gather_attend_ex",
                 "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
+                "xkv_quantized_row_bytes", "xkv_quantize_rows", "xkv_attend_absorbed_q4",
                 "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
@@ -95,11 +96,14 @@ def load() -> ctypes.CDLL:
         lib.xkv_head_scores.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_attend_absorbed.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_sr_decode_absorbed.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.xkv_quantized_row_bytes.argtypes = [i32, i32, ctypes.POINTER(sz)]
+        lib.xkv_quantize_rows.argtypes = [vp, ctypes.c_int64, i32, i32, vp, vp]
+        lib.xkv_attend_absorbed_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:19]:
+        for name in ENTRY_POINTS[:22]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -248,6 +252,24 @@ def xkv_attend_absorbed(shape, layer_in_group, A_v, B_v, head_scores, idx, out, 
                                       _ptr(idx), _ptr(out), _ptr(workspace),
                                       workspace.numel() * workspace.element_size(), _stream(stream)),
            "xkv_attend_absorbed")
+
+
+def xkv_quantized_row_bytes(r: int, bits: int = 4) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().xkv_quantized_row_bytes(r, bits, ctypes.byref(n)), "xkv_quantized_row_bytes")
+    return int(n.value)
+
+
+def xkv_quantize_rows(X, rows, r, out, bits=4, stream=None):
+    _check(load().xkv_quantize_rows(_ptr(X), int(rows), int(r), int(bits), _ptr(out), _stream(stream)),
+           "xkv_quantize_rows")
+
+
+def xkv_attend_absorbed_q4(shape, layer_in_group, Aq_v, B_v, head_scores, idx, out, workspace, stream=None):
+    _check(load().xkv_attend_absorbed_q4(ctypes.byref(shape.c()), layer_in_group, _ptr(Aq_v), _ptr(B_v),
+                                         _ptr(head_scores), _ptr(idx), _ptr(out), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_attend_absorbed_q4")
 
 
 def xkv_sr_decode_absorbed(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, idx_out, score_out, workspace,

@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libxkv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["xkv_api.hip", "score.hip", "topk.hip", "gather_attend.hip", "gather_attend_mfma.hip", "dense.hip", "reconstruct.hip",
-           "factorize.hip", "landmark.hip", "absorbed.hip"]
+           "factorize.hip", "landmark.hip", "absorbed.hip", "quant.hip"]
 
 # packed-fp32 instructions are switched off on purpose (they have produced wrong results on the test machines)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

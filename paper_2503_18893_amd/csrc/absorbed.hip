@@ -47,7 +47,12 @@ template <> struct Piece<bf16_t> {
 // wavefront is one token's contiguous run of 1 KiB.  Output per workgroup: the un-normalised sums
 // U[hh][col] = sum_j exp(logit_hj - m_h) A^V[I_j][col] and, from column block 0, (m_h, l_h).
 // ------------------------------------------------------------------------------------------
-template <typename T, int NRP>
+//
+// Q4: the rows of A^V are 4-bit quantised (quant.hip: r_v/2 bytes of codes, then (step, offset) as two bf16 per
+// group of 32 ranks; 5 r_v / 8 bytes per row).  Lane l owns one dword of codes = 8 ranks, so a wavefront load is a
+// token's contiguous 256 B, and the dword with its group's parameters.  The affine map is taken out of the inner
+// loop: sum_j w_j (step_j c_je + lo_j) = sum_j (w_j step_j) c_je + sum_j w_j lo_j, the second sum once per lane.
+template <typename T, int NRP, bool Q4>
 __global__ __launch_bounds__(kAbsorbWaves * 64) void absorb_rows_kernel(const T *__restrict__ A_v,          // [batch][L][r_v]
                                                                         const float *__restrict__ S_heads,  // [batch][H_kv][L][NRP]
                                                                         const int32_t *__restrict__ idx,    // [batch][H_kv][k]
@@ -55,7 +60,7 @@ __global__ __launch_bounds__(kAbsorbWaves * 64) void absorb_rows_kernel(const T 
                                                                         float *__restrict__ part_ml,  // [rows][splits][2][NRP]
                                                                         int L, int r_v, int H_kv, int k, int chunk)
 {
-    constexpr int E = Piece<T>::E;
+    constexpr int E = Q4 ? 8 : Piece<T>::E;
     constexpr int CW = 64 * E;  // columns per block
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int32_t *tok = reinterpret_cast<int32_t *>(smem);                // [chunk]
@@ -146,7 +151,52 @@ __global__ __launch_bounds__(kAbsorbWaves * 64) void absorb_rows_kernel(const T 
     for (int hh = 0; hh < NRP; ++hh)
 #pragma unroll
         for (int e = 0; e < E; ++e) acc[hh][e] = 0.0f;
-    if (active) {
+    if constexpr (Q4) {
+        if (active) {
+            const size_t pitch = (size_t)r_v * 5 / 8;
+            const unsigned char *Ab = reinterpret_cast<const unsigned char *>(A_v) + (size_t)b * L * pitch;
+            const size_t par_off = (size_t)(r_v >> 1) + 4 * (size_t)(pc >> 2);
+            float accl[NRP];
+#pragma unroll
+            for (int hh = 0; hh < NRP; ++hh) accl[hh] = 0.0f;
+            for (int jb = w * kAbsorbUnroll; jb < n; jb += kAbsorbWaves * kAbsorbUnroll) {
+                uint32_t cw[kAbsorbUnroll], pw[kAbsorbUnroll];
+#pragma unroll
+                for (int u = 0; u < kAbsorbUnroll; ++u) {
+                    const int j = jb + u < n ? jb + u : n - 1;
+                    const int t = __builtin_amdgcn_readfirstlane(tok[j]);
+                    const unsigned char *rowp = Ab + (size_t)t * pitch;
+                    cw[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(rowp) + pc);
+                    pw[u] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(rowp + par_off));
+                }
+#pragma unroll
+                for (int u = 0; u < kAbsorbUnroll; ++u) {
+                    if (jb + u < n) {  // wave-uniform
+                        const float step = __uint_as_float(pw[u] << 16), lo = __uint_as_float(pw[u] & 0xFFFF0000u);
+                        const uint32_t t0 = cw[u] & 0x0F0F0F0Fu, t1 = (cw[u] >> 4) & 0x0F0F0F0Fu;
+                        float c[8];  // byte i of the dword holds rank 2i (low nibble) and 2i + 1 (high nibble)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            c[2 * i] = (float)((t0 >> (8 * i)) & 0xFFu);
+                            c[2 * i + 1] = (float)((t1 >> (8 * i)) & 0xFFu);
+                        }
+#pragma unroll
+                        for (int hh = 0; hh < NRP; ++hh) {
+                            const float wv = wl[(jb + u) * NRP + hh];
+                            const float ws = wv * step;
+                            accl[hh] = fmaf(wv, lo, accl[hh]);
+#pragma unroll
+                            for (int e = 0; e < E; ++e) acc[hh][e] = fmaf(ws, c[e], acc[hh][e]);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int hh = 0; hh < NRP; ++hh)
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[hh][e] += accl[hh];
+        }
+    } else if (active) {
         const ab_u32x4_t *Ab = reinterpret_cast<const ab_u32x4_t *>(A_v + (size_t)b * L * r_v) + pc;
         for (int jb = w * kAbsorbUnroll; jb < n; jb += kAbsorbWaves * kAbsorbUnroll) {
             ab_u32x4_t r[kAbsorbUnroll];
@@ -350,19 +400,19 @@ AbsorbPlan make_absorb_plan(const xkv_shape &s, size_t base_bytes)
     return a;
 }
 
-template <typename T, int NRP>
+template <typename T, int NRP, bool Q4>
 static hipError_t launch_absorbed_t(const xkv_shape &s, const AbsorbPlan &a, int layer, const T *A_v, const T *B_v,
                                     const float *S_heads, const int32_t *idx, float *po, float *pml, float *part_u, float *part_ml,
                                     hipStream_t st)
 {
-    constexpr int E = Piece<T>::E;
+    constexpr int E = Q4 ? 8 : Piece<T>::E;
     const size_t lds_rows = (size_t)a.chunk * 4 + ((size_t)a.chunk * NRP + NRP * 64 * E + kAbsorbWaves * NRP) * 4;
     const size_t lds_comb = ((size_t)a.splits * 3 * NRP + 2 * NRP + NRP * kProjRows + (size_t)4 * NRP * s.d_h) * 4;
     const size_t lds_max = 160 * 1024 - 512;
     if (lds_rows > lds_max || lds_comb > lds_max) return hipErrorInvalidValue;
     static bool attr = false;
     if (!attr) {
-        hipError_t e = hipFuncSetAttribute((const void *)absorb_rows_kernel<T, NRP>,
+        hipError_t e = hipFuncSetAttribute((const void *)absorb_rows_kernel<T, NRP, Q4>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void *)absorb_project_kernel<T, NRP>,
@@ -371,7 +421,7 @@ static hipError_t launch_absorbed_t(const xkv_shape &s, const AbsorbPlan &a, int
         attr = true;
     }
     profile_begin(4, st);
-    hipLaunchKernelGGL((absorb_rows_kernel<T, NRP>), dim3(a.splits, a.col_blocks, s.batch * s.H_kv),
+    hipLaunchKernelGGL((absorb_rows_kernel<T, NRP, Q4>), dim3(a.splits, a.col_blocks, s.batch * s.H_kv),
                        dim3(kAbsorbWaves * 64), lds_rows, st, A_v, S_heads, idx, part_u, part_ml, s.L, s.r_v, s.H_kv,
                        s.k, a.chunk);
     profile_end(4, st);
@@ -382,30 +432,36 @@ static hipError_t launch_absorbed_t(const xkv_shape &s, const AbsorbPlan &a, int
     return hipGetLastError();
 }
 
-template <typename T>
+template <typename T, bool Q4>
 static hipError_t launch_absorbed_n(const xkv_shape &s, const AbsorbPlan &a, int layer, const T *A_v, const T *B_v,
-                                    const float *S_heads, const int32_t *idx, float *po, float *pml, float *part_u, float *part_ml,
-                                    hipStream_t st)
+                                    const float *S_heads, const int32_t *idx, float *po, float *pml, float *part_u,
+                                    float *part_ml, hipStream_t st)
 {
     switch (a.nrp) {
-    case 1: return launch_absorbed_t<T, 1>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
-    case 2: return launch_absorbed_t<T, 2>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
-    case 4: return launch_absorbed_t<T, 4>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
-    case 8: return launch_absorbed_t<T, 8>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
-    default: return launch_absorbed_t<T, 16>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
+    case 1: return launch_absorbed_t<T, 1, Q4>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
+    case 2: return launch_absorbed_t<T, 2, Q4>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
+    case 4: return launch_absorbed_t<T, 4, Q4>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
+    case 8: return launch_absorbed_t<T, 8, Q4>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
+    default: return launch_absorbed_t<T, 16, Q4>(s, a, layer, A_v, B_v, S_heads, idx, po, pml, part_u, part_ml, st);
     }
 }
 
 // Leaves a.slices attention partials per query head in po / pml; the caller merges them with launch_combine.
+// q4: A_v holds 4-bit rows (bf16 shapes only; B_v and the output stay bf16).
 hipError_t launch_absorbed(const xkv_shape &s, const AbsorbPlan &a, int layer, const void *A_v, const void *B_v,
                            const float *S_heads, const int32_t *idx, float *po, float *pml, float *part_u,
-                           float *part_ml, hipStream_t st)
+                           float *part_ml, hipStream_t st, bool q4)
 {
+    if (q4) {
+        if (s.dtype != XKV_BF16) return hipErrorInvalidValue;
+        return launch_absorbed_n<bf16_t, true>(s, a, layer, (const bf16_t *)A_v, (const bf16_t *)B_v, S_heads, idx, po, pml,
+                                               part_u, part_ml, st);
+    }
     if (s.dtype == XKV_F32)
-        return launch_absorbed_n<float>(s, a, layer, (const float *)A_v, (const float *)B_v, S_heads, idx, po, pml,
-                                        part_u, part_ml, st);
-    return launch_absorbed_n<bf16_t>(s, a, layer, (const bf16_t *)A_v, (const bf16_t *)B_v, S_heads, idx, po, pml, part_u,
-                                     part_ml, st);
+        return launch_absorbed_n<float, false>(s, a, layer, (const float *)A_v, (const float *)B_v, S_heads, idx, po, pml,
+                                               part_u, part_ml, st);
+    return launch_absorbed_n<bf16_t, false>(s, a, layer, (const bf16_t *)A_v, (const bf16_t *)B_v, S_heads, idx, po, pml,
+                                            part_u, part_ml, st);
 }
 
 }  // namespace xkv

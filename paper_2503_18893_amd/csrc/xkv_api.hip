@@ -522,21 +522,59 @@ xkv_status xkv_head_scores(const xkv_shape *shape, int32_t layer, const void *A_
 
 xkv_status xkv_attend_absorbed(const xkv_shape *shape, int32_t layer, const void *A_v, const void *B_v,
                                const float *head_scores, const int32_t *idx, void *out, void *workspace,
-                               size_t workspace_bytes, void *hip_stream)
+                               size_t workspace_bytes, void *hip_stream);
+
+static xkv_status attend_absorbed_impl(const xkv_shape *shape, int32_t layer, const void *A_v, const void *B_v,
+                                       const float *head_scores, const int32_t *idx, void *out, void *workspace,
+                                       size_t workspace_bytes, void *hip_stream, bool q4)
 {
     Plan p;
     AbsorbPlan a;
     xkv_status st = prepare_absorbed(shape, workspace, workspace_bytes, p, a);
     if (st != XKV_OK) return st;
+    if (q4 && (shape->dtype != XKV_BF16 || !quant_rank_ok(shape->r_v))) return XKV_ERR_UNSUPPORTED;
     if (!A_v || !B_v || !head_scores || !idx || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
     if ((((uintptr_t)A_v) | ((uintptr_t)head_scores)) & 15u) return XKV_ERR_INVALID_ARG;
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
     float *po = at<float>(workspace, a.off_po), *pml = at<float>(workspace, a.off_pml);
     hipError_t e = launch_absorbed(*shape, a, layer, A_v, B_v, head_scores, idx, po, pml,
-                                   at<float>(workspace, a.off_part_u), at<float>(workspace, a.off_part_ml), stream);
+                                   at<float>(workspace, a.off_part_u), at<float>(workspace, a.off_part_ml), stream, q4);
     if (e == hipSuccess) e = launch_combine(*shape, a.slices, po, pml, out, stream);
     return hip_status(e);
+}
+
+xkv_status xkv_attend_absorbed(const xkv_shape *shape, int32_t layer, const void *A_v, const void *B_v,
+                               const float *head_scores, const int32_t *idx, void *out, void *workspace,
+                               size_t workspace_bytes, void *hip_stream)
+{
+    return attend_absorbed_impl(shape, layer, A_v, B_v, head_scores, idx, out, workspace, workspace_bytes, hip_stream,
+                                false);
+}
+
+xkv_status xkv_quantized_row_bytes(int32_t r, int32_t bits, size_t *bytes)
+{
+    if (!bytes || r < 1) return XKV_ERR_INVALID_ARG;
+    if (bits != 4 || !quant_rank_ok(r)) return XKV_ERR_UNSUPPORTED;
+    *bytes = quant_row_bytes(r);
+    return XKV_OK;
+}
+
+xkv_status xkv_quantize_rows(const void *X, int64_t rows, int32_t r, int32_t bits, void *out, void *hip_stream)
+{
+    if (rows < 0 || r < 1) return XKV_ERR_INVALID_ARG;
+    if (bits != 4 || !quant_rank_ok(r)) return XKV_ERR_UNSUPPORTED;
+    if (rows == 0) return XKV_OK;
+    if (!X || !out || ((((uintptr_t)X) | ((uintptr_t)out)) & 15u)) return XKV_ERR_INVALID_ARG;
+    return hip_status(launch_quantize_rows(X, rows, r, out, (hipStream_t)hip_stream));
+}
+
+xkv_status xkv_attend_absorbed_q4(const xkv_shape *shape, int32_t layer, const void *Aq_v, const void *B_v,
+                                  const float *head_scores, const int32_t *idx, void *out, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream)
+{
+    return attend_absorbed_impl(shape, layer, Aq_v, B_v, head_scores, idx, out, workspace, workspace_bytes, hip_stream,
+                                true);
 }
 
 xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,

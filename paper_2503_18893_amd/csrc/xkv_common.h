@@ -181,7 +181,11 @@ bool absorb_shape_ok(const xkv_shape &s);
 AbsorbPlan make_absorb_plan(const xkv_shape &s, size_t base_bytes);
 hipError_t launch_absorbed(const xkv_shape &s, const AbsorbPlan &a, int layer, const void *A_v, const void *B_v,
                            const float *S_heads, const int32_t *idx, float *po, float *pml, float *part_u,
-                           float *part_ml, hipStream_t st);
+                           float *part_ml, hipStream_t st, bool q4 = false);
+// 4-bit round-to-nearest rows (see quant.hip): 5 r / 8 bytes per row, r a multiple of 128.
+inline bool quant_rank_ok(int r) { return r > 0 && r % 128 == 0; }
+__host__ __device__ inline size_t quant_row_bytes(int r) { return (size_t)r * 5 / 8; }
+hipError_t launch_quantize_rows(const void *X, long long rows, int r, void *out, hipStream_t st);
 // Cross-layer factorization of the caches of one group (see factorize.hip).
 bool factorize_shape_ok(const xkv_shape &s, int r);
 size_t factorize_workspace_bytes(const xkv_shape &s, int r);

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_entry_points():
     text = open(os.path.join(ROOT, "include", "xkv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"XKV_API[^;(]*?\b(xkv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"XKV_API[^;(]*?\b(xkv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_expected_calls():

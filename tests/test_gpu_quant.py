@@ -1,0 +1,135 @@
+"""GPU parity of the 4-bit quantisation of the token basis and of the kernels that read quantised rows.
+
+  xkv_quantize_rows      vs oracle.quantize_rows + pack_q4      bit for bit (codes, steps, offsets, byte layout)
+  xkv_attend_absorbed_q4 vs oracle.gather_attend on the de-quantised A^V (x^ = step * code + lo, taken from the
+                         GPU's own quantised rows, which equal the oracle's), within the bf16 tolerance
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2503_18893_amd import synth
+from paper_2503_18893_amd import binding as xb
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+
+
+def torch_mod():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch
+
+
+def max_rel(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+def quantize_gpu(x_bits):
+    """x_bits: uint16 bf16 patterns [rows][r] -> packed uint8 [rows][5r/8] from the library."""
+    torch = torch_mod()
+    rows, r = x_bits.shape
+    X = torch.from_numpy(x_bits.view(np.int16)).cuda()
+    out = torch.full((rows, xb.xkv_quantized_row_bytes(r)), 0xAB, dtype=torch.uint8, device="cuda")
+    xb.xkv_quantize_rows(X, rows, r, out)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("rows,r", [(1, 128), (7, 128), (333, 384), (1000, 512), (65, 2048), (0, 256)])
+def test_quantiser_matches_the_oracle_bit_for_bit(rows, r):
+    rng = np.random.default_rng(rows * 7 + r)
+    x = rng.standard_normal((rows, r)) * np.exp(rng.standard_normal((rows, 1)))
+    if rows > 2:
+        x[1, :32] = 0.25                      # a constant group: step falls back to 1
+        x[2, 32:64] = 0.0
+        x[0, :32] = np.arange(32) * 0.5       # the group worked by hand in the CPU pins
+    xbits = synth.to_storage(x, "bf16")
+    got = quantize_gpu(xbits).cpu().numpy()
+    codes, step, lo = oracle.quantize_rows(xbits)
+    want = oracle.pack_q4(codes, step, lo) if rows else np.zeros((0, 5 * r // 8), np.uint8)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_quantiser_full_size_sampled():
+    """A^V of one sequence group at benchmark size (16 x 65536 rows of 512): sampled rows against the oracle."""
+    torch = torch_mod()
+    w = synth.LLAMA_FULL
+    dev = synth.make_group_device(w, seed=41)
+    A = dev["A_v"]
+    rows = w.batch * w.L
+    out = torch.empty((rows, xb.xkv_quantized_row_bytes(w.r_v)), dtype=torch.uint8, device="cuda")
+    xb.xkv_quantize_rows(A, rows, w.r_v, out)
+    torch.cuda.synchronize()
+    pick = np.unique(np.concatenate([np.arange(64), rows // 2 + np.arange(64), rows - 64 + np.arange(64),
+                                     np.random.default_rng(1).integers(0, rows, 200)]))
+    sel = torch.from_numpy(pick).cuda()
+    a_host = synth.to_host(A.view(rows, w.r_v)[sel])
+    codes, step, lo = oracle.quantize_rows(a_host)
+    np.testing.assert_array_equal(out[sel].cpu().numpy(), oracle.pack_q4(codes, step, lo))
+
+
+CASES = [
+    ("llama_small", synth.LLAMA_GROUP.with_(L=3000, k=200, r_k=128, r_v=256, batch=2, G=2)),
+    ("qwen_small", synth.QWEN.with_(L=5001, k=257, r_k=128, r_v=128, batch=1, G=1)),
+    ("wide_rv", synth.LLAMA_GROUP.with_(L=2500, k=700, r_k=64, r_v=640, batch=1, G=1)),
+    ("gqa16_dh64", synth.Workload("gqa16", G=1, H_kv=3, H_q=48, d_h=64, r_k=48, r_v=128, L=1111, k=40, batch=1,
+                                  dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    ("k2100_dh256", synth.Workload("k2100", G=1, H_kv=2, H_q=8, d_h=256, r_k=64, r_v=384, L=6000, k=2100, batch=2,
+                                   dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+]
+
+
+@pytest.mark.parametrize("name,w", CASES, ids=[n for n, _ in CASES])
+def test_attend_absorbed_on_quantised_values(name, w):
+    torch = torch_mod()
+    case = synth.make_case(w, seed=17)
+    dev = synth.to_device(case, w.dtype)
+    shape = xb.Shape.of(w)
+    layer = w.G - 1
+    ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    q = dev["q"][layer].contiguous()
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    heads = torch.empty((w.batch, w.H_kv, w.L, xb.head_pitch(shape)), dtype=torch.float32, device="cuda")
+    idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
+    out = torch.empty((w.batch, w.H_q, w.d_h), dtype=torch.bfloat16, device="cuda")
+    Aq = torch.empty((w.batch, w.L, xb.xkv_quantized_row_bytes(w.r_v)), dtype=torch.uint8, device="cuda")
+    xb.xkv_quantize_rows(dev["A_v"], w.batch * w.L, w.r_v, Aq)
+    xb.xkv_head_scores(shape, layer, dev["A_k"], dev["B_k"], q, S, heads, ws)
+    xb.xkv_topk(shape, S, idx, ws)
+    xb.xkv_attend_absorbed_q4(shape, layer, Aq, dev["B_v"], heads, idx, out, ws)
+    torch.cuda.synchronize()
+    outh, idxh, Aqh = synth.storage_to_f64(synth.to_host(out)), idx.cpu().numpy(), Aq.cpu().numpy()
+    sc = oracle.default_scale(w.d_h)
+    for b in range(w.batch):
+        codes, step, lo = oracle.quantize_rows(case["A_v"][b])
+        np.testing.assert_array_equal(Aqh[b], oracle.pack_q4(codes, step, lo))
+        A_v_hat = oracle.dequantize_rows(codes, step, lo)
+        ref = oracle.gather_attend(case["A_k"][b], A_v_hat, case["B_k"][b, layer], case["B_v"][b, layer],
+                                   case["q"][layer, b], idxh[b], sc)
+        err = max_rel(outh[b], ref)
+        assert err <= TOL, (name, b, err)
+        # and the quantisation itself costs little at these spectra: against the unquantised values
+        ref0 = oracle.gather_attend(case["A_k"][b], case["A_v"][b], case["B_k"][b, layer], case["B_v"][b, layer],
+                                    case["q"][layer, b], idxh[b], sc)
+        print(name, b, "vs quantised oracle", err, "quantisation effect", max_rel(ref, ref0), flush=True)
+
+
+def test_quantised_calls_reject_what_they_do_not_cover():
+    torch = torch_mod()
+    with pytest.raises(xb.XkvError) as ei:
+        xb.xkv_quantized_row_bytes(96)
+    assert ei.value.status == xb.XKV_ERR_UNSUPPORTED
+    with pytest.raises(xb.XkvError) as ei:
+        xb.xkv_quantized_row_bytes(128, bits=3)
+    assert ei.value.status == xb.XKV_ERR_UNSUPPORTED
+    w = synth.TINY.with_(r_v=128, G=1, H_kv=2, H_q=4)       # fp32 shape: quantised rows go with bf16 shapes only
+    shape = xb.Shape.of(w)
+    ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    t = torch.zeros(4096, device="cuda")
+    with pytest.raises(xb.XkvError) as ei:
+        xb.xkv_attend_absorbed_q4(shape, 0, t, t, t, t, t, ws)
+    assert ei.value.status == xb.XKV_ERR_UNSUPPORTED
