@@ -446,11 +446,16 @@ def dequantize_rows(codes, step, lo):
 
 
 def pack_q4(codes, step, lo):
-    """Byte layout of a 4-bit row as the library stores it: r/2 bytes of codes (rank 2i in the low nibble of
-    byte i, rank 2i+1 in the high nibble), then per group (step, lo) as two bf16 numbers.  5r/8 bytes per row."""
+    """Byte layout of a 4-bit row as the library stores it: r/8 little-endian 32-bit words of codes -- word j holds
+    ranks 8j .. 8j+7, rank 8j + 2i in bits [4i, 4i+4) and rank 8j + 2i + 1 in bits [16 + 4i, 16 + 4i + 4), i = 0..3,
+    so that two adjacent ranks sit 16 bits apart like a packed pair of 16-bit numbers -- then per group (step, lo) as
+    two bf16 numbers.  5r/8 bytes per row."""
     rows, r = codes.shape
     assert codes.max(initial=0) < 16
-    nib = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8)
+    c = codes.reshape(rows, r // 8, 4, 2).astype(np.uint32)          # [word][i][even / odd rank]
+    sh = (4 * np.arange(4, dtype=np.uint32))[None, None, :]
+    words = ((c[:, :, :, 0] << sh) | (c[:, :, :, 1] << (sh + 16))).sum(axis=2).astype('<u4')
+    nib = np.ascontiguousarray(words).view(np.uint8).reshape(rows, r // 2)
     par = np.empty((rows, r // Q_GROUP, 2), np.uint16)
     par[:, :, 0] = (np.ascontiguousarray(step, np.float32).view(np.uint32) >> 16).astype(np.uint16)
     par[:, :, 1] = (np.ascontiguousarray(lo, np.float32).view(np.uint32) >> 16).astype(np.uint16)
@@ -461,10 +466,12 @@ def unpack_q4(packed, r):
     """Inverse of pack_q4: (codes, step, lo)."""
     packed = np.ascontiguousarray(packed, np.uint8)
     rows = packed.shape[0]
-    nib = packed[:, :r // 2]
-    codes = np.empty((rows, r), np.uint8)
-    codes[:, 0::2] = nib & 15
-    codes[:, 1::2] = nib >> 4
+    words = np.ascontiguousarray(packed[:, :r // 2]).view('<u4').reshape(rows, r // 8)
+    codes = np.empty((rows, r // 8, 4, 2), np.uint8)
+    for i in range(4):
+        codes[:, :, i, 0] = (words >> (4 * i)) & 15
+        codes[:, :, i, 1] = (words >> (16 + 4 * i)) & 15
+    codes = codes.reshape(rows, r)
     par = np.ascontiguousarray(packed[:, r // 2:]).view(np.uint16).reshape(rows, r // Q_GROUP, 2)
     step = (par[:, :, 0].astype(np.uint32) << 16).view(np.float32)
     lo = (par[:, :, 1].astype(np.uint32) << 16).view(np.float32)

@@ -21,7 +21,8 @@ ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_tail", "x
                 "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_factorize_workspace_bytes", "xkv_factorize",
                 "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_gather_attend_ex",
                 "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
-                "xkv_quantized_row_bytes", "xkv_quantize_rows", "xkv_attend_absorbed_q4",
+                "xkv_quantized_row_bytes", "xkv_quantize_rows", "xkv_attend_absorbed_q4", "xkv_head_scores_q4",
+                "xkv_sr_decode_absorbed_q4",
                 "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
@@ -99,11 +100,13 @@ def load() -> ctypes.CDLL:
         lib.xkv_quantized_row_bytes.argtypes = [i32, i32, ctypes.POINTER(sz)]
         lib.xkv_quantize_rows.argtypes = [vp, ctypes.c_int64, i32, i32, vp, vp]
         lib.xkv_attend_absorbed_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_head_scores_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_sr_decode_absorbed_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:22]:
+        for name in ENTRY_POINTS[:24]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -270,6 +273,21 @@ def xkv_attend_absorbed_q4(shape, layer_in_group, Aq_v, B_v, head_scores, idx, o
                                          _ptr(head_scores), _ptr(idx), _ptr(out), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(stream)),
            "xkv_attend_absorbed_q4")
+
+
+def xkv_head_scores_q4(shape, layer_in_group, Aq_k, B_k, q, score_out, heads_out, workspace, stream=None):
+    _check(load().xkv_head_scores_q4(ctypes.byref(shape.c()), layer_in_group, _ptr(Aq_k), _ptr(B_k), _ptr(q),
+                                     _ptr(score_out), _ptr(heads_out), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)), "xkv_head_scores_q4")
+
+
+def xkv_sr_decode_absorbed_q4(shape, layer_in_group, Aq_k, Aq_v, B_k, B_v, q, out, idx_out, score_out, workspace,
+                              stream=None, K_tail=None, V_tail=None, T=0):
+    _check(load().xkv_sr_decode_absorbed_q4(ctypes.byref(shape.c()), layer_in_group, _ptr(Aq_k), _ptr(Aq_v), _ptr(B_k),
+                                            _ptr(B_v), _ptr(q), _ptr(K_tail), _ptr(V_tail), int(T), _ptr(out),
+                                            _ptr(idx_out), _ptr(score_out), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_sr_decode_absorbed_q4")
 
 
 def xkv_sr_decode_absorbed(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, idx_out, score_out, workspace,

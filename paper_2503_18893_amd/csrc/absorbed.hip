@@ -174,12 +174,13 @@ __global__ __launch_bounds__(kAbsorbWaves * 64) void absorb_rows_kernel(const T 
                     if (jb + u < n) {  // wave-uniform
                         const float step = __uint_as_float(pw[u] << 16), lo = __uint_as_float(pw[u] & 0xFFFF0000u);
                         const uint32_t t0 = cw[u] & 0x0F0F0F0Fu, t1 = (cw[u] >> 4) & 0x0F0F0F0Fu;
-                        float c[8];  // byte i of the dword holds rank 2i (low nibble) and 2i + 1 (high nibble)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            c[2 * i] = (float)((t0 >> (8 * i)) & 0xFFu);
-                            c[2 * i + 1] = (float)((t1 >> (8 * i)) & 0xFFu);
-                        }
+                        // rank 2i sits in bits [4i, 4i+4), rank 2i+1 in bits [16+4i, 16+4i+4): after the two masks
+                        // every code is a byte of t0 (i even) or t1 (i odd)
+                        float c[8];
+                        c[0] = (float)(t0 & 0xFFu), c[4] = (float)((t0 >> 8) & 0xFFu);
+                        c[1] = (float)((t0 >> 16) & 0xFFu), c[5] = (float)(t0 >> 24);
+                        c[2] = (float)(t1 & 0xFFu), c[6] = (float)((t1 >> 8) & 0xFFu);
+                        c[3] = (float)((t1 >> 16) & 0xFFu), c[7] = (float)(t1 >> 24);
 #pragma unroll
                         for (int hh = 0; hh < NRP; ++hh) {
                             const float wv = wl[(jb + u) * NRP + hh];

@@ -2,8 +2,10 @@
 // RTN quantiser on the compressed cache; the format below is the one the two published ratios imply -- one extra
 // bit per element of side information = two 16-bit numbers per group of 32 elements).
 //
-// Row layout, r a multiple of 128:  r/2 bytes of codes (rank 2i in the low nibble of byte i, rank 2i+1 in the high
-// nibble), then r/32 pairs (step, lo) of bf16: 5r/8 bytes per row, every row and every group 16-byte aligned.
+// Row layout, r a multiple of 128:  r/8 32-bit words of codes (word j holds ranks 8j..8j+7: rank 8j+2i in bits
+// [4i, 4i+4), rank 8j+2i+1 in bits [16+4i, 16+4i+4), so two adjacent ranks are one shift and one mask away from a
+// packed pair of 16-bit numbers), then r/32 pairs (step, lo) of bf16: 5r/8 bytes per row, every row and every
+// group 16-byte aligned.
 //   lo = min of the group, step = bf16((max - lo) / 15) (1 if that is 0), code = clip(rint((x - lo) * (1 / step)), 0, 15),
 // each a single fp32 operation (the same sequence as the CPU oracle: the codes agree bit for bit);  x^ = step * code + lo.
 #include "xkv_common.h"
@@ -50,7 +52,7 @@ __global__ __launch_bounds__(256) void quantize_rows_q4_kernel(const bf16_t *__r
     for (int e = 0; e < 8; ++e) {
         const float t = (x[e] - lo) * inv;
         const float c = fminf(fmaxf(rintf(t), 0.0f), 15.0f);
-        word |= (uint32_t)c << (4 * e);
+        word |= (uint32_t)c << (4 * (e >> 1) + 16 * (e & 1));
     }
     if (!in) return;
     unsigned char *orow = out + row * (long long)quant_row_bytes(r);

@@ -531,6 +531,141 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Scores from a 4-bit quantised token basis (quant.hip: per row r/8 words of codes, then (step, lo) per group of
+// 32 ranks).  Same contraction and head-slot layout as above, with the codes themselves as the matrix-core
+// operand: a code c in 0..15 is the bf16 number 128 + c when 0x4300 is or-ed on top of it, and a pair of adjacent
+// ranks is one shift and one mask away from a packed bf16 pair.  Per group g and token t the matrix cores give
+//   acc_g[slot] = sum_{i in g} (128 + c_ti) p[slot][i]      (exact products, fp32 sums, P as bf16 hi + lo)
+// and the affine map of the group is applied to the sum, not to the elements:
+//   s[slot] += step_tg (acc_g[slot] - 128 Ps_g[slot]) + lo_tg Ps_g[slot],   Ps_g[slot] = sum_{i in g} p[slot][i].
+// Lane (n, hf) loads the 16 bytes of token n's group (both halves load the same piece) and its parameter word,
+// one group ahead of the products.  Always writes the per-head scores as well as the pooled ones.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8_t q4_fragment(uint32_t w)
+{
+    u32x4_t o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = ((w >> (4 * i)) & 0x000F000Fu) | 0x43004300u;
+    return __builtin_bit_cast(bf16x8_t, o);
+}
+
+template <int N_REP>
+__global__ __launch_bounds__(256) void score_q4_kernel(const unsigned char *__restrict__ Aq,  // [batch][L][5 r_k / 8]
+                                                       const bf16_t *__restrict__ Pfrag, float *__restrict__ S,
+                                                       float *__restrict__ S_heads, int L, int r_k, int H_kv, int F8,
+                                                       int tiles_per_wg, float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);                   // [2][F8][64] fragments of 16 B per lane
+    float *Ps = reinterpret_cast<float *>(Pl + 2 * F8 * 64);            // [F8 / 2 groups][32 slots]
+    constexpr int GPH = 16 / N_REP;
+    constexpr int NRP = head_pitch(N_REP);
+    const int b = blockIdx.z, blk = blockIdx.y, nblk = gridDim.y;
+    const int lane = lane_id(), w = wave_id();
+    const int n = lane & 31, hf = lane >> 5;
+    const int n_groups = r_k >> 5;  // real groups; fragments beyond them hold zero P
+    {
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
+        const int total = 2 * F8 * 64;  // a multiple of 4 * 256
+        for (int e0 = threadIdx.x; e0 < total; e0 += 4 * 256) {
+            u32x4_t tmp[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tmp[j] = src[e0 + j * 256];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Pl[e0 + j * 256] = tmp[j];
+        }
+    }
+    __syncthreads();
+    // Ps: lane (slot m, hf) sums its 8 ranks of both fragments and both parts of a group, the halves are added
+    for (int g = w; g < F8 / 2; g += 4) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int part = 0; part < 2; ++part)
+#pragma unroll
+            for (int ff = 0; ff < 2; ++ff) {
+                const u32x4_t v = Pl[(part * F8 + 2 * g + ff) * 64 + lane];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sum += __uint_as_float(v[e] << 16) + __uint_as_float(v[e] & 0xFFFF0000u);
+            }
+        sum += __shfl_xor(sum, 32, kWave);
+        if (hf == 0) Ps[g * 32 + n] = sum;
+    }
+    __syncthreads();
+
+    const size_t pitch = (size_t)r_k * 5 / 8;
+    const unsigned char *Ab = Aq + (size_t)b * L * pitch;
+    const int n_tiles = (L + 31) / 32;
+    const int tile_begin = blockIdx.x * tiles_per_wg;
+    const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
+    for (int tile = tile_begin + w; tile < tile_end; tile += 4) {
+        const int t = tile * 32 + n;
+        const unsigned char *rowp = Ab + (size_t)(t < L ? t : L - 1) * pitch;
+        const u32x4_t *codes = reinterpret_cast<const u32x4_t *>(rowp);
+        const uint32_t *params = reinterpret_cast<const uint32_t *>(rowp + (r_k >> 1));
+        float tot[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
+        u32x4_t cw = codes[0];
+        uint32_t pw = params[0];
+        for (int g = 0; g < n_groups; ++g) {
+            const int gn = g + 1 < n_groups ? g + 1 : g;
+            const u32x4_t cw_n = codes[gn];
+            const uint32_t pw_n = params[gn];
+            f32x16_t acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll
+            for (int ff = 0; ff < 2; ++ff) {
+                // fragment 2g + ff covers ranks 32g + 16ff ..; this half takes its 8 ranks: word 2ff + hf of the group
+                const uint32_t word = hf ? (ff ? cw[3] : cw[1]) : (ff ? cw[2] : cw[0]);
+                const bf16x8_t bop = q4_fragment(word);
+                const u32x4_t ph = Pl[(2 * g + ff) * 64 + lane];
+                const u32x4_t pl = Pl[(F8 + 2 * g + ff) * 64 + lane];
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph), bop, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl), bop, acc, 0, 0, 0);
+            }
+            const float step = __uint_as_float(pw << 16), lo = __uint_as_float(pw & 0xFFFF0000u);
+            const float c2 = fmaf(-128.0f, step, lo);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float4 ps = *reinterpret_cast<const float4 *>(Ps + g * 32 + 8 * j + 4 * hf);
+                tot[4 * j + 0] = fmaf(step, acc[4 * j + 0], fmaf(c2, ps.x, tot[4 * j + 0]));
+                tot[4 * j + 1] = fmaf(step, acc[4 * j + 1], fmaf(c2, ps.y, tot[4 * j + 1]));
+                tot[4 * j + 2] = fmaf(step, acc[4 * j + 2], fmaf(c2, ps.z, tot[4 * j + 2]));
+                tot[4 * j + 3] = fmaf(step, acc[4 * j + 3], fmaf(c2, ps.w, tot[4 * j + 3]));
+            }
+            cw = cw_n;
+            pw = pw_n;
+        }
+        if (t < L) {
+#pragma unroll
+            for (int u = 0; u < GPH; ++u) {
+                const int g = blk * 2 * GPH + hf * GPH + u;
+                if (g < H_kv) {
+                    float hv[16];
+#pragma unroll
+                    for (int hh = 0; hh < 16; ++hh) hv[hh] = hh < N_REP ? scale * tot[(u * N_REP + hh) & 15] : 0.0f;
+                    float best = hv[0];
+#pragma unroll
+                    for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, hv[hh]);
+                    S[((size_t)b * H_kv + g) * L + t] = best;
+                    float *dst = S_heads + (((size_t)b * H_kv + g) * L + t) * NRP;
+                    if constexpr (NRP >= 4) {
+#pragma unroll
+                        for (int c = 0; c < NRP / 4; ++c)
+                            *reinterpret_cast<float4 *>(dst + 4 * c) =
+                                make_float4(hv[4 * c], hv[4 * c + 1], hv[4 * c + 2], hv[4 * c + 3]);
+                    } else {
+#pragma unroll
+                        for (int hh = 0; hh < NRP; ++hh) dst[hh] = hv[hh];
+                    }
+                }
+            }
+        }
+    }
+}
+
 static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
 {
     const int n_rep = s.H_q / s.H_kv;
@@ -733,6 +868,78 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     case 7: return launch_score_mfma_t<7>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
     case 8: return launch_score_mfma_t<8>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
     default: return launch_score_mfma_t<16>(s, p, A, Pfrag, S, F8, row_hist, chunk_hist, hist_done, S_heads, st);
+    }
+}
+
+template <int N_REP>
+static hipError_t launch_score_q4_t(const xkv_shape &s, const Plan &p, const unsigned char *Aq, const bf16_t *Pfrag, float *S,
+                                    float *S_heads, int F8, hipStream_t st)
+{
+    const int nblk = mfma_blocks(s.H_kv, N_REP);
+    const int n_tiles = (s.L + 31) / 32;
+    const size_t lds = (size_t)2 * F8 * 64 * 16 + (size_t)(F8 / 2) * 32 * 4;
+    // about four workgroups per compute unit, each over one contiguous range of a sequence
+    const int pairs = s.batch * nblk;
+    const int wgs_per_pair = pairs >= 1024 ? 1 : 1024 / pairs;
+    int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
+    tiles_per_wg = tiles_per_wg < 4 ? 4 : (tiles_per_wg + 3) / 4 * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)score_q4_kernel<N_REP>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
+    profile_begin(0, st);
+    hipLaunchKernelGGL(score_q4_kernel<N_REP>, grid, block, lds, st, Aq, Pfrag, S, S_heads, s.L, s.r_k, s.H_kv, F8,
+                       tiles_per_wg, p.scale);
+    profile_end(0, st);
+    return hipGetLastError();
+}
+
+bool score_q4_shape_ok(const xkv_shape &s)
+{
+    if (s.H_kv <= 0 || s.H_q % s.H_kv != 0) return false;
+    const int n_rep = s.H_q / s.H_kv;
+    const bool rep_ok = (n_rep >= 1 && n_rep <= 8) || n_rep == 16;
+    return s.dtype == XKV_BF16 && rep_ok && quant_rank_ok(s.r_k) && s.r_k <= 2048 && s.d_h % 16 == 0;
+}
+
+// Projection (as for the bf16 stream) and the score kernel over quantised rows; S and S_heads are both written.
+hipError_t launch_score_q4_stage(const xkv_shape &s, const Plan &p, int layer, const void *Aq_k, const void *B_k,
+                                 const void *q, void *P_ws, float *S, float *S_heads, hipStream_t st)
+{
+    const int n_rep = s.H_q / s.H_kv;
+    const int F8 = (s.r_k / 16 + 7) / 8 * 8;
+    const int gph = mfma_gph(n_rep), nblk = mfma_blocks(s.H_kv, n_rep);
+    bf16_t *Pfrag = (bf16_t *)P_ws;
+    ProjArgs pj;
+    pj.B_k = (const bf16_t *)B_k;
+    pj.q = (const bf16_t *)q;
+    pj.Pfrag = Pfrag;
+    pj.G = s.G;
+    pj.layer = layer;
+    pj.r_k = s.r_k;
+    pj.H_kv = s.H_kv;
+    pj.H_q = s.H_q;
+    pj.d_h = s.d_h;
+    pj.F8 = F8;
+    pj.blocks_x = ((F8 / 2) * 2 * gph * nblk + 3) / 4;
+    hipLaunchKernelGGL(project_q_frag_kernel, dim3(pj.blocks_x, s.batch), dim3(256), 0, st, pj);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const unsigned char *A = (const unsigned char *)Aq_k;
+    switch (n_rep) {
+    case 1: return launch_score_q4_t<1>(s, p, A, Pfrag, S, S_heads, F8, st);
+    case 2: return launch_score_q4_t<2>(s, p, A, Pfrag, S, S_heads, F8, st);
+    case 3: return launch_score_q4_t<3>(s, p, A, Pfrag, S, S_heads, F8, st);
+    case 4: return launch_score_q4_t<4>(s, p, A, Pfrag, S, S_heads, F8, st);
+    case 5: return launch_score_q4_t<5>(s, p, A, Pfrag, S, S_heads, F8, st);
+    case 6: return launch_score_q4_t<6>(s, p, A, Pfrag, S, S_heads, F8, st);
+    case 7: return launch_score_q4_t<7>(s, p, A, Pfrag, S, S_heads, F8, st);
+    case 8: return launch_score_q4_t<8>(s, p, A, Pfrag, S, S_heads, F8, st);
+    default: return launch_score_q4_t<16>(s, p, A, Pfrag, S, S_heads, F8, st);
     }
 }
 

@@ -577,18 +577,20 @@ xkv_status xkv_attend_absorbed_q4(const xkv_shape *shape, int32_t layer, const v
                                 true);
 }
 
-xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
-                                  const void *B_k, const void *B_v, const void *q, const void *K_tail,
-                                  const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
-                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+static xkv_status sr_decode_absorbed_impl(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                          const void *B_k, const void *B_v, const void *q, const void *K_tail,
+                                          const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream, bool q4)
 {
     if (T < 0 || (T > 0 && (!K_tail || !V_tail))) return XKV_ERR_INVALID_ARG;
     Plan p;
     AbsorbPlan a;
     xkv_status st = prepare_absorbed(shape, workspace, workspace_bytes, p, a);
     if (st != XKV_OK) return st;
+    if (q4 && (!score_q4_shape_ok(*shape) || !quant_rank_ok(shape->r_v))) return XKV_ERR_UNSUPPORTED;
     if (!A_k || !A_v || !B_k || !B_v || !q || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
     if (((uintptr_t)A_v) & 15u) return XKV_ERR_INVALID_ARG;
+    if (q4 && ((((uintptr_t)A_k) | ((uintptr_t)B_k) | ((uintptr_t)q)) & 15u)) return XKV_ERR_INVALID_ARG;
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
     float *S = score_out ? score_out : at<float>(workspace, p.off_score);
@@ -596,20 +598,57 @@ xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer, const v
     float *heads = at<float>(workspace, a.off_heads);
     uint32_t *hist = at<uint32_t>(workspace, p.off_hist), *state = at<uint32_t>(workspace, p.off_state);
     bool level0_done = false;
-    hipError_t e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
-                               p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
-                               &level0_done, nullptr, nullptr, stream, heads);
+    hipError_t e =
+        q4 ? launch_score_q4_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S, heads, stream)
+           : launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
+                                p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
+                                &level0_done, nullptr, nullptr, stream, heads);
     if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, level0_done, stream);
     float *po = at<float>(workspace, a.off_po), *pml = at<float>(workspace, a.off_pml);
     if (e == hipSuccess)
         e = launch_absorbed(*shape, a, layer, A_v, B_v, heads, idx, po, pml, at<float>(workspace, a.off_part_u),
-                            at<float>(workspace, a.off_part_ml), stream);
+                            at<float>(workspace, a.off_part_ml), stream, q4);
     // the uncompressed tail, if any, joins the same softmax through its own set of partials (as in xkv_sr_decode_tail)
     int n_tail = 0;
     float *tail_o = at<float>(workspace, p.off_tail_o), *tail_ml = at<float>(workspace, p.off_tail_ml);
     if (T > 0 && e == hipSuccess) e = launch_tail(*shape, p, K_tail, V_tail, q, T, tail_o, tail_ml, &n_tail, stream);
     if (e == hipSuccess) e = launch_combine(*shape, a.slices, po, pml, out, stream, n_tail, tail_o, tail_ml);
     return hip_status(e);
+}
+
+xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                  const void *B_k, const void *B_v, const void *q, const void *K_tail,
+                                  const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return sr_decode_absorbed_impl(shape, layer, A_k, A_v, B_k, B_v, q, K_tail, V_tail, T, out, idx_out, score_out,
+                                   workspace, workspace_bytes, hip_stream, false);
+}
+
+xkv_status xkv_sr_decode_absorbed_q4(const xkv_shape *shape, int32_t layer, const void *Aq_k, const void *Aq_v,
+                                     const void *B_k, const void *B_v, const void *q, const void *K_tail,
+                                     const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return sr_decode_absorbed_impl(shape, layer, Aq_k, Aq_v, B_k, B_v, q, K_tail, V_tail, T, out, idx_out, score_out,
+                                   workspace, workspace_bytes, hip_stream, true);
+}
+
+xkv_status xkv_head_scores_q4(const xkv_shape *shape, int32_t layer, const void *Aq_k, const void *B_k, const void *q,
+                              float *score_out, float *heads_out, void *workspace, size_t workspace_bytes,
+                              void *hip_stream)
+{
+    Plan p;
+    AbsorbPlan a;
+    xkv_status st = prepare_absorbed(shape, workspace, workspace_bytes, p, a);
+    if (st != XKV_OK) return st;
+    if (!score_q4_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
+    if (!Aq_k || !B_k || !q || !heads_out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)heads_out) | ((uintptr_t)Aq_k) | ((uintptr_t)B_k) | ((uintptr_t)q)) & 15u) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    float *S = score_out ? score_out : at<float>(workspace, p.off_score);
+    return hip_status(launch_score_q4_stage(*shape, p, layer, Aq_k, B_k, q, at<void>(workspace, p.off_p), S, heads_out,
+                                            (hipStream_t)hip_stream));
 }
 
 xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event)

@@ -185,6 +185,9 @@ hipError_t launch_absorbed(const xkv_shape &s, const AbsorbPlan &a, int layer, c
 // 4-bit round-to-nearest rows (see quant.hip): 5 r / 8 bytes per row, r a multiple of 128.
 inline bool quant_rank_ok(int r) { return r > 0 && r % 128 == 0; }
 __host__ __device__ inline size_t quant_row_bytes(int r) { return (size_t)r * 5 / 8; }
+bool score_q4_shape_ok(const xkv_shape &s);
+hipError_t launch_score_q4_stage(const xkv_shape &s, const Plan &p, int layer, const void *Aq_k, const void *B_k,
+                                 const void *q, void *P_ws, float *S, float *S_heads, hipStream_t st);
 hipError_t launch_quantize_rows(const void *X, long long rows, int r, void *out, hipStream_t st);
 // Cross-layer factorization of the caches of one group (see factorize.hip).
 bool factorize_shape_ok(const xkv_shape &s, int r);

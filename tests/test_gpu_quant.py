@@ -118,6 +118,112 @@ def test_attend_absorbed_on_quantised_values(name, w):
         print(name, b, "vs quantised oracle", err, "quantisation effect", max_rel(ref, ref0), flush=True)
 
 
+STEP_CASES = [
+    ("llama_small", synth.LLAMA_GROUP.with_(L=3000, k=200, r_k=128, r_v=256, batch=2, G=2)),
+    ("qwen_small", synth.QWEN.with_(L=5001, k=257, r_k=384, r_v=128, batch=1, G=1)),
+    ("gqa16_dh64", synth.Workload("gqa16", G=1, H_kv=3, H_q=48, d_h=64, r_k=128, r_v=128, L=1111, k=40, batch=1,
+                                  dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    ("gqa2_many_heads", synth.Workload("gqa2", G=1, H_kv=20, H_q=40, d_h=128, r_k=256, r_v=128, L=4097, k=300, batch=1,
+                                       dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    ("mha_r640", synth.Workload("mha", G=2, H_kv=20, H_q=20, d_h=64, r_k=640, r_v=256, L=900, k=50, batch=2,
+                                dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+]
+
+
+@pytest.mark.parametrize("name,w", STEP_CASES, ids=[n for n, _ in STEP_CASES])
+def test_quantised_step_chain(name, w):
+    """Head scores from quantised A^K, selection, absorbed attention over quantised A^V; then the fused call.
+    References: the oracle on the de-quantised values (x^ = step * code + lo of the oracle's own quantiser, whose
+    packed rows equal the GPU's bit for bit)."""
+    torch = torch_mod()
+    case = synth.make_case(w, seed=19)
+    dev = synth.to_device(case, w.dtype)
+    shape = xb.Shape.of(w)
+    layer = w.G - 1
+    n_rep = w.H_q // w.H_kv
+    nrp = xb.head_pitch(shape)
+    ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    q = dev["q"][layer].contiguous()
+    Aqk = torch.empty((w.batch, w.L, xb.xkv_quantized_row_bytes(w.r_k)), dtype=torch.uint8, device="cuda")
+    Aqv = torch.empty((w.batch, w.L, xb.xkv_quantized_row_bytes(w.r_v)), dtype=torch.uint8, device="cuda")
+    xb.xkv_quantize_rows(dev["A_k"], w.batch * w.L, w.r_k, Aqk)
+    xb.xkv_quantize_rows(dev["A_v"], w.batch * w.L, w.r_v, Aqv)
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    heads = torch.full((w.batch, w.H_kv, w.L, nrp), float("nan"), dtype=torch.float32, device="cuda")
+    idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
+    out = torch.empty((w.batch, w.H_q, w.d_h), dtype=torch.bfloat16, device="cuda")
+    xb.xkv_head_scores_q4(shape, layer, Aqk, dev["B_k"], q, S, heads, ws)
+    xb.xkv_topk(shape, S, idx, ws)
+    xb.xkv_attend_absorbed_q4(shape, layer, Aqv, dev["B_v"], heads, idx, out, ws)
+    S2, idx2, out2 = torch.empty_like(S), torch.empty_like(idx), torch.empty_like(out)
+    xb.xkv_sr_decode_absorbed_q4(shape, layer, Aqk, Aqv, dev["B_k"], dev["B_v"], q, out2, idx2, S2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(S2, S) and torch.equal(idx2, idx) and torch.equal(out2, out)
+    Sh, hh, idxh = S.cpu().numpy(), heads.cpu().numpy(), idx.cpu().numpy()
+    outh = synth.storage_to_f64(synth.to_host(out))
+    np.testing.assert_array_equal(Sh, hh[..., :n_rep].max(axis=-1))
+    np.testing.assert_array_equal(hh[..., n_rep:], 0.0)
+    sc = oracle.default_scale(w.d_h)
+    for b in range(w.batch):
+        Ak_hat = oracle.dequantize_rows(*oracle.quantize_rows(case["A_k"][b]))
+        Av_hat = oracle.dequantize_rows(*oracle.quantize_rows(case["A_v"][b]))
+        s_ref = oracle.head_scores(Ak_hat, case["B_k"][b, layer], case["q"][layer, b], w.H_kv, sc)
+        s_gpu = hh[b, :, :, :n_rep].transpose(0, 2, 1).reshape(w.H_q, w.L)
+        err_s = max_rel(s_gpu, s_ref)
+        assert err_s <= TOL, (name, b, err_s)
+        for g in range(w.H_kv):
+            np.testing.assert_array_equal(idxh[b, g], oracle.select(Sh[b, g], w.k))
+        ref = oracle.gather_attend(Ak_hat, Av_hat, case["B_k"][b, layer], case["B_v"][b, layer], case["q"][layer, b],
+                                   idxh[b], sc)
+        err_o = max_rel(outh[b], ref)
+        assert err_o <= TOL, (name, b, err_o)
+        print(name, b, "head scores", err_s, "attention", err_o, flush=True)
+
+
+def test_quantised_step_full_size_sampled():
+    """Benchmark configuration 3 with both token bases quantised, the launch configuration the benchmark times:
+    sampled head scores, the complete selection of the sampled sequences, and their outputs."""
+    torch = torch_mod()
+    w = synth.LLAMA_FULL
+    dev = synth.make_group_device(w, seed=43)
+    shape = xb.Shape.of(w)
+    layer = w.G - 1
+    n_rep = w.H_q // w.H_kv
+    ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    q_l = dev["q"][layer].contiguous()
+    Aqk = torch.empty((w.batch, w.L, xb.xkv_quantized_row_bytes(w.r_k)), dtype=torch.uint8, device="cuda")
+    Aqv = torch.empty((w.batch, w.L, xb.xkv_quantized_row_bytes(w.r_v)), dtype=torch.uint8, device="cuda")
+    xb.xkv_quantize_rows(dev["A_k"], w.batch * w.L, w.r_k, Aqk)
+    xb.xkv_quantize_rows(dev["A_v"], w.batch * w.L, w.r_v, Aqv)
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    heads = torch.empty((w.batch, w.H_kv, w.L, xb.head_pitch(shape)), dtype=torch.float32, device="cuda")
+    idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
+    out = torch.empty((w.batch, w.H_q, w.d_h), dtype=torch.bfloat16, device="cuda")
+    xb.xkv_sr_decode_absorbed_q4(shape, layer, Aqk, Aqv, dev["B_k"], dev["B_v"], q_l, out, idx, S, ws)
+    S1 = torch.empty_like(S)
+    xb.xkv_head_scores_q4(shape, layer, Aqk, dev["B_k"], q_l, S1, heads, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(S1, S) and torch.equal(heads[..., :n_rep].max(dim=-1).values, S)
+    sc = oracle.default_scale(w.d_h)
+    mid = w.L // 2
+    for b in (0, w.batch - 1):
+        B_k, B_v = synth.to_host(dev["B_k"][b, layer]), synth.to_host(dev["B_v"][b, layer])
+        q = synth.to_host(dev["q"][layer, b])
+        Ak_hat = oracle.dequantize_rows(*oracle.quantize_rows(synth.to_host(dev["A_k"][b])))
+        Av_hat = oracle.dequantize_rows(*oracle.quantize_rows(synth.to_host(dev["A_v"][b])))
+        for lo_, hi_ in [(0, 256), (mid - 128, mid + 128), (w.L - 256, w.L)]:
+            ref = oracle.head_scores(Ak_hat[lo_:hi_], B_k, q, w.H_kv, sc)
+            got = heads[b, :, lo_:hi_, :n_rep].cpu().numpy().transpose(0, 2, 1).reshape(w.H_q, hi_ - lo_)
+            assert max_rel(got, ref) <= TOL, (b, lo_)
+        S_b, idx_b = S[b].cpu().numpy(), idx[b].cpu().numpy()
+        for g in range(w.H_kv):
+            np.testing.assert_array_equal(idx_b[g], oracle.select(S_b[g], w.k))
+        ref_out = oracle.gather_attend(Ak_hat, Av_hat, B_k, B_v, q, idx_b, sc)
+        err = max_rel(synth.storage_to_f64(synth.to_host(out[b])), ref_out)
+        assert err <= TOL, (b, err)
+        print("seq", b, "quantised step vs oracle", err, flush=True)
+
+
 def test_quantised_calls_reject_what_they_do_not_cover():
     torch = torch_mod()
     with pytest.raises(xb.XkvError) as ei:

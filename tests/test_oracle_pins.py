@@ -635,7 +635,8 @@ def test_q4_pack_layout_and_round_trip():
     lo = np.array([[-1.0, 3.0], [0.0, -8.0]], np.float32)
     p = oracle.pack_q4(codes, step, lo)
     assert p.shape == (2, 40) and p.dtype == np.uint8
-    assert p[0, 0] == 0x10 and p[0, 1] == 0x32 and p[0, 7] == 0xFE          # rank 2i low nibble, 2i+1 high nibble
+    # word 0 = ranks 0..7 = codes 0..7: even ranks 0,2,4,6 in bits 0..15, odd ranks 1,3,5,7 in bits 16..31
+    assert p[0, 0:4].tolist() == [0x20, 0x64, 0x31, 0x75] and p[0, 4:8].tolist() == [0xA8, 0xEC, 0xB9, 0xFD]
     assert p[0, 32:36].tolist() == [0x00, 0x3F, 0x80, 0xBF]                 # bf16(0.5) = 0x3F00, bf16(-1) = 0xBF80
     c2, s2, l2 = oracle.unpack_q4(p, 64)
     np.testing.assert_array_equal(c2, codes)
