@@ -42,6 +42,7 @@ def parse_args():
     ap.add_argument("--no-landmark", action="store_true", help="skip the timing of the landmark-guided step")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
     ap.add_argument("--no-absorbed", action="store_true", help="skip the timing of the absorbed form of the step")
+    ap.add_argument("--no-quantized", action="store_true", help="skip the timing of the step on 4-bit token bases")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise 1 GiB copy kernel three times (reference point for hardware counters)")
@@ -417,6 +418,86 @@ def main():
         except xb.XkvError as err:
             absorbed = {"skipped": str(err)}
 
+    # ---------------------------------------------------------------- the absorbed step on 4-bit token bases (an extra)
+    # A^K and A^V of every factor set quantised once (as prefill would), then the absorbed step straight from the
+    # quantised rows.  What it computes is the step on the de-quantised values.  Not `value`.
+    quantized = None
+    if not args.no_quantized and w.dtype == "bf16":
+        try:
+            rb_k, rb_v = xb.xkv_quantized_row_bytes(w.r_k), xb.xkv_quantized_row_bytes(w.r_v)
+            q_ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+            n_q = min(n_sets, w.n_groups)
+            Aqk, Aqv = [], []
+            ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ms_quant = 0.0
+            for s_i in range(n_q):
+                ak = torch.empty((w.batch, w.L, rb_k), dtype=torch.uint8, device="cuda")
+                av = torch.empty((w.batch, w.L, rb_v), dtype=torch.uint8, device="cuda")
+                ev_a.record()
+                xb.xkv_quantize_rows(groups[s_i]["A_k"], w.batch * w.L, w.r_k, ak)
+                xb.xkv_quantize_rows(groups[s_i]["A_v"], w.batch * w.L, w.r_v, av)
+                ev_b.record()
+                torch.cuda.synchronize()
+                ms_quant += ev_a.elapsed_time(ev_b)
+                Aqk.append(ak)
+                Aqv.append(av)
+            qstate = {"set0": 0}
+
+            def quantized_step():
+                base = qstate["set0"]
+                for grp in range(w.n_groups):
+                    s_i = (base + grp) % n_q
+                    g = groups[s_i]
+                    for l in range(w.G):
+                        xb.xkv_sr_decode_absorbed_q4(shape, l, Aqk[s_i], Aqv[s_i], g["B_k"], g["B_v"], qs[s_i][l], out,
+                                                     None, None, q_ws)
+                qstate["set0"] = (base + w.n_groups) % n_q
+
+            quantized_step()
+            ms_q = time_loop(torch, quantized_step, max(2, min(args.steps, 5)))
+            heads_q = torch.empty((w.batch, w.H_kv, w.L, xb.head_pitch(shape)), dtype=torch.float32, device="cuda")
+
+            def kernel_ms_q(stage_id, call):
+                ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                ev0.record()
+                ev1.record()
+                torch.cuda.synchronize()
+                xb.xkv_profile_kernel(stage_id, ev0.cuda_event, ev1.cuda_event)
+                total, count = 0.0, 0
+                for s_i in range(n_q):
+                    for l in range(w.G):
+                        call(s_i, l)
+                        torch.cuda.synchronize()
+                        total += ev0.elapsed_time(ev1)
+                        count += 1
+                xb.xkv_profile_kernel(stage_id, None, None)
+                return total / count
+
+            qk = {
+                "head_scores_q4": kernel_ms_q(xb.STAGE_SCORE,
+                                              lambda s_i, l: xb.xkv_head_scores_q4(shape, l, Aqk[s_i], groups[s_i]["B_k"],
+                                                                                   qs[s_i][l], S, heads_q, q_ws)),
+                "absorb_rows_q4": kernel_ms_q(xb.STAGE_ABSORB_ROWS,
+                                              lambda s_i, l: xb.xkv_attend_absorbed_q4(shape, l, Aqv[s_i],
+                                                                                       groups[s_i]["B_v"], heads_q, idx,
+                                                                                       out, q_ws)),
+            }
+            qb = {"head_scores_q4": w.batch * (w.L * rb_k + 4 * w.H_kv * w.L * (1 + xb.head_pitch(shape))),
+                  "absorb_rows_q4": w.batch * w.H_kv * w.k * (rb_v + 4 * xb.head_pitch(shape))}
+            quantized = {"ms_per_step": round(ms_q, 4), "tokens_per_s": round(w.batch / (ms_q * 1e-3), 2),
+                         "speedup_vs_bf16_gather_reconstruct": round(ms_sr / ms_q, 3), "bits": 4,
+                         "bytes_per_row": {"A_k": rb_k, "A_v": rb_v, "bf16": {"A_k": 2 * w.r_k, "A_v": 2 * w.r_v}},
+                         "quantize_ms_per_group": round(ms_quant / n_q, 3),
+                         "quantize_GBps": round(n_q * w.batch * w.L * (2 * (w.r_k + w.r_v) + rb_k + rb_v)
+                                                / (ms_quant * 1e-3) / 1e9, 1),
+                         "kernels": {kn: {"kernel_ms": round(qk[kn], 5), "alg_bytes": qb[kn],
+                                          "kernel_GBps": round(qb[kn] / (qk[kn] * 1e-3) / 1e9, 1)} for kn in qk},
+                         "note": "xkv_sr_decode_absorbed_q4: both token bases as 4-bit round-to-nearest rows (groups of "
+                                 "32 ranks, bf16 step and offset), de-quantised inside the score and row-sum kernels"}
+            del Aqk, Aqv, q_ws, heads_q
+        except xb.XkvError as err:
+            quantized = {"skipped": str(err)}
+
     # ---------------------------------------------------------------- the step before the path: factorization
     # One layer group's key cache of every sequence (power-law spectrum, full rank) -> A^K, B^K (Eq. 1), as prefill
     # would do once per prompt and group, for keys and for values.  Not part of the decode step or of `value`.
@@ -512,7 +593,7 @@ def main():
                    "factor_sets_in_hbm": n_sets, "copies_rotated": copies},
         "roofline": roofline, "cpu_baseline": cpu, "stages": stages, "dense_baseline": dense,
         "speedup_vs_dense": (round(dense["ms_per_step"] / ms_sr, 3) if dense else None),
-        "graph_replay": graph_replay, "landmark_selector": landmark, "absorbed": absorbed, "factorize": factorize, "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
+        "graph_replay": graph_replay, "landmark_selector": landmark, "absorbed": absorbed, "quantized": quantized, "factorize": factorize, "parity": parity, "setup_s": round(t_gen, 1), "timed_wall_s": round(t_wall, 2),
     }
     print(json.dumps(result))
 

@@ -539,8 +539,10 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
 //   acc_g[slot] = sum_{i in g} (128 + c_ti) p[slot][i]      (exact products, fp32 sums, P as bf16 hi + lo)
 // and the affine map of the group is applied to the sum, not to the elements:
 //   s[slot] += step_tg (acc_g[slot] - 128 Ps_g[slot]) + lo_tg Ps_g[slot],   Ps_g[slot] = sum_{i in g} p[slot][i].
-// Lane (n, hf) loads the 16 bytes of token n's group (both halves load the same piece) and its parameter word,
-// one group ahead of the products.  Always writes the per-head scores as well as the pooled ones.
+// (The second part is kept in fp32 multiply-adds: as a matrix-core product with bf16 high parts and remainders it
+// was measured 7 % faster but 200 times less accurate, because 128 step Ps cancels against the first part.)
+// Lane (n, hf) loads the 16 bytes of each of token n's groups (both halves load the same pieces) and the parameter
+// words.  Always writes the per-head scores as well as the pooled ones.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ bf16x8_t q4_fragment(uint32_t w)
 {
@@ -564,7 +566,7 @@ __global__ __launch_bounds__(256) void score_q4_kernel(const unsigned char *__re
     const int b = blockIdx.z, blk = blockIdx.y, nblk = gridDim.y;
     const int lane = lane_id(), w = wave_id();
     const int n = lane & 31, hf = lane >> 5;
-    const int n_groups = r_k >> 5;  // real groups; fragments beyond them hold zero P
+    const int n_groups = r_k >> 5;  // = F8 / 2 for the ranks this kernel takes (multiples of 128)
     {
         const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
         const int total = 2 * F8 * 64;  // a multiple of 4 * 256
@@ -598,45 +600,52 @@ __global__ __launch_bounds__(256) void score_q4_kernel(const unsigned char *__re
     const int n_tiles = (L + 31) / 32;
     const int tile_begin = blockIdx.x * tiles_per_wg;
     const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
+    // A token's whole row is requested at once (up to 16 groups = 256 B of codes and 64 B of parameters per pass,
+    // 80 registers): with one group in flight per lane the stream is bound by load latency, not by bytes.
+    constexpr int GP = 16;  // groups per pass
     for (int tile = tile_begin + w; tile < tile_end; tile += 4) {
         const int t = tile * 32 + n;
         const unsigned char *rowp = Ab + (size_t)(t < L ? t : L - 1) * pitch;
         const u32x4_t *codes = reinterpret_cast<const u32x4_t *>(rowp);
-        const uint32_t *params = reinterpret_cast<const uint32_t *>(rowp + (r_k >> 1));
-        float tot[16];
+        const u32x4_t *params = reinterpret_cast<const u32x4_t *>(rowp + (r_k >> 1));  // n_groups is a multiple of 4
+        f32x16_t tot;
 #pragma unroll
         for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
-        u32x4_t cw = codes[0];
-        uint32_t pw = params[0];
-        for (int g = 0; g < n_groups; ++g) {
-            const int gn = g + 1 < n_groups ? g + 1 : g;
-            const u32x4_t cw_n = codes[gn];
-            const uint32_t pw_n = params[gn];
-            f32x16_t acc;
+        const f32x16_t zero = tot;
+        for (int g0 = 0; g0 < n_groups; g0 += GP) {
+            u32x4_t cw[GP], pw[GP / 4];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+            for (int j = 0; j < GP; ++j) cw[j] = codes[g0 + j < n_groups ? g0 + j : n_groups - 1];
 #pragma unroll
-            for (int ff = 0; ff < 2; ++ff) {
-                // fragment 2g + ff covers ranks 32g + 16ff ..; this half takes its 8 ranks: word 2ff + hf of the group
-                const uint32_t word = hf ? (ff ? cw[3] : cw[1]) : (ff ? cw[2] : cw[0]);
-                const bf16x8_t bop = q4_fragment(word);
-                const u32x4_t ph = Pl[(2 * g + ff) * 64 + lane];
-                const u32x4_t pl = Pl[(F8 + 2 * g + ff) * 64 + lane];
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph), bop, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl), bop, acc, 0, 0, 0);
+            for (int j = 0; j < GP / 4; ++j) pw[j] = params[g0 + 4 * j < n_groups ? (g0 >> 2) + j : (n_groups >> 2) - 1];
+#pragma unroll
+            for (int j = 0; j < GP; ++j) {
+                const int g = g0 + j;
+                if (g < n_groups) {  // wave-uniform
+                    f32x16_t acc = zero;
+#pragma unroll
+                    for (int ff = 0; ff < 2; ++ff) {
+                        // fragment 2g + ff covers ranks 32g + 16ff ..; this half takes word 2ff + hf of the group
+                        const uint32_t word = hf ? (ff ? cw[j][3] : cw[j][1]) : (ff ? cw[j][2] : cw[j][0]);
+                        const bf16x8_t bop = q4_fragment(word);
+                        const u32x4_t ph = Pl[(2 * g + ff) * 64 + lane];
+                        const u32x4_t pl = Pl[(F8 + 2 * g + ff) * 64 + lane];
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph), bop, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl), bop, acc, 0, 0, 0);
+                    }
+                    const uint32_t pword = pw[j >> 2][j & 3];
+                    const float step = __uint_as_float(pword << 16), lo = __uint_as_float(pword & 0xFFFF0000u);
+                    const float c2 = fmaf(-128.0f, step, lo);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float4 ps = *reinterpret_cast<const float4 *>(Ps + g * 32 + 8 * i + 4 * hf);
+                        tot[4 * i + 0] = fmaf(step, acc[4 * i + 0], fmaf(c2, ps.x, tot[4 * i + 0]));
+                        tot[4 * i + 1] = fmaf(step, acc[4 * i + 1], fmaf(c2, ps.y, tot[4 * i + 1]));
+                        tot[4 * i + 2] = fmaf(step, acc[4 * i + 2], fmaf(c2, ps.z, tot[4 * i + 2]));
+                        tot[4 * i + 3] = fmaf(step, acc[4 * i + 3], fmaf(c2, ps.w, tot[4 * i + 3]));
+                    }
+                }
             }
-            const float step = __uint_as_float(pw << 16), lo = __uint_as_float(pw & 0xFFFF0000u);
-            const float c2 = fmaf(-128.0f, step, lo);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float4 ps = *reinterpret_cast<const float4 *>(Ps + g * 32 + 8 * j + 4 * hf);
-                tot[4 * j + 0] = fmaf(step, acc[4 * j + 0], fmaf(c2, ps.x, tot[4 * j + 0]));
-                tot[4 * j + 1] = fmaf(step, acc[4 * j + 1], fmaf(c2, ps.y, tot[4 * j + 1]));
-                tot[4 * j + 2] = fmaf(step, acc[4 * j + 2], fmaf(c2, ps.z, tot[4 * j + 2]));
-                tot[4 * j + 3] = fmaf(step, acc[4 * j + 3], fmaf(c2, ps.w, tot[4 * j + 3]));
-            }
-            cw = cw_n;
-            pw = pw_n;
         }
         if (t < L) {
 #pragma unroll
@@ -878,9 +887,9 @@ static hipError_t launch_score_q4_t(const xkv_shape &s, const Plan &p, const uns
     const int nblk = mfma_blocks(s.H_kv, N_REP);
     const int n_tiles = (s.L + 31) / 32;
     const size_t lds = (size_t)2 * F8 * 64 * 16 + (size_t)(F8 / 2) * 32 * 4;
-    // about four workgroups per compute unit, each over one contiguous range of a sequence
+    // two workgroups per compute unit (what the LDS holds), each over one contiguous range of a sequence
     const int pairs = s.batch * nblk;
-    const int wgs_per_pair = pairs >= 1024 ? 1 : 1024 / pairs;
+    const int wgs_per_pair = pairs >= 512 ? 1 : 512 / pairs;
     int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
     tiles_per_wg = tiles_per_wg < 4 ? 4 : (tiles_per_wg + 3) / 4 * 4;
     static bool attr_set = false;
