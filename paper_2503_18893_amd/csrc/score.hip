@@ -552,8 +552,23 @@ __device__ __forceinline__ bf16x8_t q4_fragment(uint32_t w)
     return __builtin_bit_cast(bf16x8_t, o);
 }
 
-template <int N_REP>
-__global__ __launch_bounds__(256) void score_q4_kernel(const unsigned char *__restrict__ Aq,  // [batch][L][5 r_k / 8]
+// One pass of a token's quantised row: GP groups of codes from group g0 on (clamped to the last real group) and
+// their parameter words.  n_groups is a multiple of 4.
+template <int GP>
+__device__ __forceinline__ void q4_load_pass(u32x4_t (&cw)[GP], u32x4_t (&pw)[GP / 4], const unsigned char *Ab, size_t pitch,
+                                             int r_k, int t, int L, int g0, int n_groups)
+{
+    const unsigned char *rowp = Ab + (size_t)(t < L ? t : L - 1) * pitch;
+    const u32x4_t *codes = reinterpret_cast<const u32x4_t *>(rowp);
+    const u32x4_t *params = reinterpret_cast<const u32x4_t *>(rowp + (r_k >> 1));
+#pragma unroll
+    for (int j = 0; j < GP; ++j) cw[j] = codes[g0 + j < n_groups ? g0 + j : n_groups - 1];
+#pragma unroll
+    for (int j = 0; j < GP / 4; ++j) pw[j] = params[g0 + 4 * j < n_groups ? (g0 >> 2) + j : (n_groups >> 2) - 1];
+}
+
+template <int N_REP, int WAVES, int GP>
+__global__ __launch_bounds__(WAVES * 64) void score_q4_kernel(const unsigned char *__restrict__ Aq,  // [batch][L][5 r_k / 8]
                                                        const bf16_t *__restrict__ Pfrag, float *__restrict__ S,
                                                        float *__restrict__ S_heads, int L, int r_k, int H_kv, int F8,
                                                        int tiles_per_wg, float scale)
@@ -569,18 +584,19 @@ __global__ __launch_bounds__(256) void score_q4_kernel(const unsigned char *__re
     const int n_groups = r_k >> 5;  // = F8 / 2 for the ranks this kernel takes (multiples of 128)
     {
         const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
-        const int total = 2 * F8 * 64;  // a multiple of 4 * 256
-        for (int e0 = threadIdx.x; e0 < total; e0 += 4 * 256) {
+        const int total = 2 * F8 * 64;  // a multiple of 1024
+        for (int e0 = threadIdx.x; e0 < total; e0 += 4 * WAVES * 64) {
             u32x4_t tmp[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) tmp[j] = src[e0 + j * 256];
+            for (int j = 0; j < 4; ++j) tmp[j] = src[e0 + j * WAVES * 64 < total ? e0 + j * WAVES * 64 : e0];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) Pl[e0 + j * 256] = tmp[j];
+            for (int j = 0; j < 4; ++j)
+                if (e0 + j * WAVES * 64 < total) Pl[e0 + j * WAVES * 64] = tmp[j];
         }
     }
     __syncthreads();
     // Ps: lane (slot m, hf) sums its 8 ranks of both fragments and both parts of a group, the halves are added
-    for (int g = w; g < F8 / 2; g += 4) {
+    for (int g = w; g < F8 / 2; g += WAVES) {
         float sum = 0.0f;
 #pragma unroll
         for (int part = 0; part < 2; ++part)
@@ -600,53 +616,63 @@ __global__ __launch_bounds__(256) void score_q4_kernel(const unsigned char *__re
     const int n_tiles = (L + 31) / 32;
     const int tile_begin = blockIdx.x * tiles_per_wg;
     const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
-    // A token's whole row is requested at once (up to 16 groups = 256 B of codes and 64 B of parameters per pass,
-    // 80 registers): with one group in flight per lane the stream is bound by load latency, not by bytes.
-    constexpr int GP = 16;  // groups per pass
-    for (int tile = tile_begin + w; tile < tile_end; tile += 4) {
-        const int t = tile * 32 + n;
-        const unsigned char *rowp = Ab + (size_t)(t < L ? t : L - 1) * pitch;
-        const u32x4_t *codes = reinterpret_cast<const u32x4_t *>(rowp);
-        const u32x4_t *params = reinterpret_cast<const u32x4_t *>(rowp + (r_k >> 1));  // n_groups is a multiple of 4
-        f32x16_t tot;
+    // A token's row is requested a pass at a time (a pass = GP groups = 16 GP bytes of codes and 4 GP bytes of
+    // parameters per lane), and the next pass -- of this tile or of the wavefront's next tile -- is requested
+    // before the products of the current one: with one group in flight per lane the stream is bound by load
+    // latency, not by bytes.
+    const int n_pass = (n_groups + GP - 1) / GP;
+    int tile = tile_begin + w;
+    if (tile >= tile_end) return;
+    u32x4_t cw[GP], pw[GP / 4];
+    q4_load_pass<GP>(cw, pw, Ab, pitch, r_k, tile * 32 + n, L, 0, n_groups);
+    f32x16_t tot;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
-        const f32x16_t zero = tot;
-        for (int g0 = 0; g0 < n_groups; g0 += GP) {
-            u32x4_t cw[GP], pw[GP / 4];
+    for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
+    const f32x16_t zero = tot;
+    int pass = 0;
+    while (true) {
+        const bool last_pass = pass + 1 == n_pass;
+        const int tile_n = last_pass ? tile + WAVES : tile, pass_n = last_pass ? 0 : pass + 1;
+        u32x4_t cw_n[GP], pw_n[GP / 4];
+        q4_load_pass<GP>(cw_n, pw_n, Ab, pitch, r_k, (tile_n < tile_end ? tile_n : tile) * 32 + n, L, pass_n * GP, n_groups);
+        const int g0 = pass * GP;
 #pragma unroll
-            for (int j = 0; j < GP; ++j) cw[j] = codes[g0 + j < n_groups ? g0 + j : n_groups - 1];
+        for (int j = 0; j < GP; ++j) {
+            const int g = g0 + j;
+            if (g < n_groups) {  // wave-uniform
+                f32x16_t acc = zero;
 #pragma unroll
-            for (int j = 0; j < GP / 4; ++j) pw[j] = params[g0 + 4 * j < n_groups ? (g0 >> 2) + j : (n_groups >> 2) - 1];
+                for (int ff = 0; ff < 2; ++ff) {
+                    // fragment 2g + ff covers ranks 32g + 16ff ..; this half takes word 2ff + hf of the group
+                    const uint32_t word = hf ? (ff ? cw[j][3] : cw[j][1]) : (ff ? cw[j][2] : cw[j][0]);
+                    const bf16x8_t bop = q4_fragment(word);
+                    const u32x4_t ph = Pl[(2 * g + ff) * 64 + lane];
+                    const u32x4_t pl = Pl[(F8 + 2 * g + ff) * 64 + lane];
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph), bop, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl), bop, acc, 0, 0, 0);
+                }
+                const uint32_t pword = pw[j >> 2][j & 3];
+                const float step = __uint_as_float(pword << 16), lo = __uint_as_float(pword & 0xFFFF0000u);
+                const float c2 = fmaf(-128.0f, step, lo);
 #pragma unroll
-            for (int j = 0; j < GP; ++j) {
-                const int g = g0 + j;
-                if (g < n_groups) {  // wave-uniform
-                    f32x16_t acc = zero;
-#pragma unroll
-                    for (int ff = 0; ff < 2; ++ff) {
-                        // fragment 2g + ff covers ranks 32g + 16ff ..; this half takes word 2ff + hf of the group
-                        const uint32_t word = hf ? (ff ? cw[j][3] : cw[j][1]) : (ff ? cw[j][2] : cw[j][0]);
-                        const bf16x8_t bop = q4_fragment(word);
-                        const u32x4_t ph = Pl[(2 * g + ff) * 64 + lane];
-                        const u32x4_t pl = Pl[(F8 + 2 * g + ff) * 64 + lane];
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph), bop, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl), bop, acc, 0, 0, 0);
-                    }
-                    const uint32_t pword = pw[j >> 2][j & 3];
-                    const float step = __uint_as_float(pword << 16), lo = __uint_as_float(pword & 0xFFFF0000u);
-                    const float c2 = fmaf(-128.0f, step, lo);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float4 ps = *reinterpret_cast<const float4 *>(Ps + g * 32 + 8 * i + 4 * hf);
-                        tot[4 * i + 0] = fmaf(step, acc[4 * i + 0], fmaf(c2, ps.x, tot[4 * i + 0]));
-                        tot[4 * i + 1] = fmaf(step, acc[4 * i + 1], fmaf(c2, ps.y, tot[4 * i + 1]));
-                        tot[4 * i + 2] = fmaf(step, acc[4 * i + 2], fmaf(c2, ps.z, tot[4 * i + 2]));
-                        tot[4 * i + 3] = fmaf(step, acc[4 * i + 3], fmaf(c2, ps.w, tot[4 * i + 3]));
-                    }
+                for (int i = 0; i < 4; ++i) {
+                    const float4 ps = *reinterpret_cast<const float4 *>(Ps + g * 32 + 8 * i + 4 * hf);
+                    tot[4 * i + 0] = fmaf(step, acc[4 * i + 0], fmaf(c2, ps.x, tot[4 * i + 0]));
+                    tot[4 * i + 1] = fmaf(step, acc[4 * i + 1], fmaf(c2, ps.y, tot[4 * i + 1]));
+                    tot[4 * i + 2] = fmaf(step, acc[4 * i + 2], fmaf(c2, ps.z, tot[4 * i + 2]));
+                    tot[4 * i + 3] = fmaf(step, acc[4 * i + 3], fmaf(c2, ps.w, tot[4 * i + 3]));
                 }
             }
         }
+#pragma unroll
+        for (int j = 0; j < GP; ++j) cw[j] = cw_n[j];
+#pragma unroll
+        for (int j = 0; j < GP / 4; ++j) pw[j] = pw_n[j];
+        if (!last_pass) {
+            pass = pass_n;
+            continue;
+        }
+        const int t = tile * 32 + n;
         if (t < L) {
 #pragma unroll
             for (int u = 0; u < GPH; ++u) {
@@ -672,7 +698,165 @@ __global__ __launch_bounds__(256) void score_q4_kernel(const unsigned char *__re
                 }
             }
         }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
+        if (tile_n >= tile_end) break;
+        tile = tile_n;
+        pass = 0;
     }
+}
+
+// The same kernel with the rows fetched line-wise: the 32 token rows of a tile are one contiguous block of
+// 32 * 5r/8 bytes, which a wavefront requests as whole 1 KiB runs (lane l = 16-byte piece i * 64 + l, NL requests)
+// and passes to the lanes that need them through a wavefront-private LDS tile.  With one lane per row (kernel
+// above) every request touches 32 different lines and the load path, not the arithmetic, bounds the kernel (measured:
+// 81 of 175 us).  Rows sit in the tile at a pitch of an odd number of 16-byte units, so the per-row reads are free
+// of bank conflicts.  The next tile waits in registers while the current one is multiplied; nothing needs a
+// barrier (P is read-only, the tiles are private).
+constexpr int kQ4TileWaves = 8;
+constexpr int kQ4MaxLoads = 10;  // 16-byte requests per lane and tile: 32 rows * 5r/8 bytes <= 10 KiB, r <= 512
+
+__host__ __device__ inline int q4_tile_pitch(int r) { return r * 5 / 8 + ((r / 128) % 2 == 0 ? 16 : 0); }  // bytes
+
+template <int N_REP>
+__global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const unsigned char *__restrict__ Aq,
+                                                                          const bf16_t *__restrict__ Pfrag,
+                                                                          float *__restrict__ S,
+                                                                          float *__restrict__ S_heads, int L, int r_k,
+                                                                          int H_kv, int F8, int tiles_per_wg, float scale)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int WAVES = kQ4TileWaves;
+    u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);         // [2][F8][64] fragments of 16 B per lane
+    float *Ps = reinterpret_cast<float *>(Pl + 2 * F8 * 64);  // [F8 / 2 groups][32 slots]
+    constexpr int GPH = 16 / N_REP;
+    constexpr int NRP = head_pitch(N_REP);
+    const int b = blockIdx.z, blk = blockIdx.y, nblk = gridDim.y;
+    const int lane = lane_id(), w = wave_id();
+    const int n = lane & 31, hf = lane >> 5;
+    const int n_groups = r_k >> 5;
+    const int tpitch = q4_tile_pitch(r_k);
+    unsigned char *tile_lds = reinterpret_cast<unsigned char *>(Ps + (F8 / 2) * 32) + (size_t)w * 32 * tpitch;
+    {
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
+        const int total = 2 * F8 * 64;  // a multiple of 1024
+        for (int e0 = threadIdx.x; e0 < total; e0 += 4 * WAVES * 64) {
+            u32x4_t tmp[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tmp[j] = src[e0 + j * WAVES * 64 < total ? e0 + j * WAVES * 64 : e0];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (e0 + j * WAVES * 64 < total) Pl[e0 + j * WAVES * 64] = tmp[j];
+        }
+    }
+    __syncthreads();
+    for (int g = w; g < F8 / 2; g += WAVES) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int part = 0; part < 2; ++part)
+#pragma unroll
+            for (int ff = 0; ff < 2; ++ff) {
+                const u32x4_t v = Pl[(part * F8 + 2 * g + ff) * 64 + lane];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sum += __uint_as_float(v[e] << 16) + __uint_as_float(v[e] & 0xFFFF0000u);
+            }
+        sum += __shfl_xor(sum, 32, kWave);
+        if (hf == 0) Ps[g * 32 + n] = sum;
+    }
+    __syncthreads();
+
+    const int pitch = r_k * 5 / 8;
+    const int ppr = pitch >> 4;            // 16-byte pieces per row
+    const int pieces = 32 * ppr;           // per tile
+    const unsigned char *Ab = Aq + (size_t)b * L * pitch;
+    const size_t seq_last = (size_t)L * pitch - 16;  // last piece of the sequence: requests beyond it are redirected
+    const int n_tiles = (L + 31) / 32;
+    const int tile_begin = blockIdx.x * tiles_per_wg;
+    const int tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
+    int tile = tile_begin + w;
+    if (tile >= tile_end) return;
+    // where this lane's pieces go in the LDS tile (the same for every tile); -1: no such piece
+    int dst_off[kQ4MaxLoads];
+#pragma unroll
+    for (int i = 0; i < kQ4MaxLoads; ++i) {
+        const int pc = i * 64 + lane;
+        dst_off[i] = pc < pieces ? (pc / ppr) * tpitch + (pc % ppr) * 16 : -1;
+    }
+    u32x4_t stage[kQ4MaxLoads];
+#define XKV_Q4_REQUEST(TL)                                                                              \
+    _Pragma("unroll") for (int i = 0; i < kQ4MaxLoads; ++i)                                             \
+    {                                                                                                   \
+        const size_t off = (size_t)(TL) * 32 * pitch + (size_t)(i * 64 + lane) * 16;                    \
+        stage[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(Ab + (off < seq_last ? off : seq_last))); \
+    }
+    XKV_Q4_REQUEST(tile);
+    f32x16_t tot;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
+    const f32x16_t zero = tot;
+    const unsigned char *my_row = tile_lds + n * tpitch;
+    while (true) {
+#pragma unroll
+        for (int i = 0; i < kQ4MaxLoads; ++i)
+            if (dst_off[i] >= 0) *reinterpret_cast<u32x4_t *>(tile_lds + dst_off[i]) = stage[i];
+        const int tile_n = tile + WAVES;
+        XKV_Q4_REQUEST(tile_n < tile_end ? tile_n : tile);
+        for (int g = 0; g < n_groups; ++g) {
+            const u32x4_t cw = *reinterpret_cast<const u32x4_t *>(my_row + 16 * g);
+            const uint32_t pword = *reinterpret_cast<const uint32_t *>(my_row + (r_k >> 1) + 4 * g);
+            f32x16_t acc = zero;
+#pragma unroll
+            for (int ff = 0; ff < 2; ++ff) {
+                const uint32_t word = hf ? (ff ? cw[3] : cw[1]) : (ff ? cw[2] : cw[0]);
+                const bf16x8_t bop = q4_fragment(word);
+                const u32x4_t ph = Pl[(2 * g + ff) * 64 + lane];
+                const u32x4_t pl = Pl[(F8 + 2 * g + ff) * 64 + lane];
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph), bop, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl), bop, acc, 0, 0, 0);
+            }
+            const float step = __uint_as_float(pword << 16), lo = __uint_as_float(pword & 0xFFFF0000u);
+            const float c2 = fmaf(-128.0f, step, lo);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float4 ps = *reinterpret_cast<const float4 *>(Ps + g * 32 + 8 * i + 4 * hf);
+                tot[4 * i + 0] = fmaf(step, acc[4 * i + 0], fmaf(c2, ps.x, tot[4 * i + 0]));
+                tot[4 * i + 1] = fmaf(step, acc[4 * i + 1], fmaf(c2, ps.y, tot[4 * i + 1]));
+                tot[4 * i + 2] = fmaf(step, acc[4 * i + 2], fmaf(c2, ps.z, tot[4 * i + 2]));
+                tot[4 * i + 3] = fmaf(step, acc[4 * i + 3], fmaf(c2, ps.w, tot[4 * i + 3]));
+            }
+        }
+        const int t = tile * 32 + n;
+        if (t < L) {
+#pragma unroll
+            for (int u = 0; u < GPH; ++u) {
+                const int g = blk * 2 * GPH + hf * GPH + u;
+                if (g < H_kv) {
+                    float hv[16];
+#pragma unroll
+                    for (int hh = 0; hh < 16; ++hh) hv[hh] = hh < N_REP ? scale * tot[(u * N_REP + hh) & 15] : 0.0f;
+                    float best = hv[0];
+#pragma unroll
+                    for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, hv[hh]);
+                    S[((size_t)b * H_kv + g) * L + t] = best;
+                    float *dst = S_heads + (((size_t)b * H_kv + g) * L + t) * NRP;
+                    if constexpr (NRP >= 4) {
+#pragma unroll
+                        for (int c = 0; c < NRP / 4; ++c)
+                            *reinterpret_cast<float4 *>(dst + 4 * c) =
+                                make_float4(hv[4 * c], hv[4 * c + 1], hv[4 * c + 2], hv[4 * c + 3]);
+                    } else {
+#pragma unroll
+                        for (int hh = 0; hh < NRP; ++hh) dst[hh] = hv[hh];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
+        if (tile_n >= tile_end) break;
+        tile = tile_n;
+    }
+#undef XKV_Q4_REQUEST
 }
 
 static bool score_mfma_ok(const xkv_shape &s, const void *A_k)
@@ -880,6 +1064,8 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     }
 }
 
+// The line-wise kernel (eight wavefronts, one workgroup per compute unit) whenever its LDS fits -- ranks up to 512 --
+// else the kernel with one lane per row (four wavefronts, long passes).
 template <int N_REP>
 static hipError_t launch_score_q4_t(const xkv_shape &s, const Plan &p, const unsigned char *Aq, const bf16_t *Pfrag, float *S,
                                     float *S_heads, int F8, hipStream_t st)
@@ -887,23 +1073,42 @@ static hipError_t launch_score_q4_t(const xkv_shape &s, const Plan &p, const uns
     const int nblk = mfma_blocks(s.H_kv, N_REP);
     const int n_tiles = (s.L + 31) / 32;
     const size_t lds = (size_t)2 * F8 * 64 * 16 + (size_t)(F8 / 2) * 32 * 4;
-    // two workgroups per compute unit (what the LDS holds), each over one contiguous range of a sequence
+    const size_t lds_tile = lds + (size_t)kQ4TileWaves * 32 * q4_tile_pitch(s.r_k);
+    const bool tiled = lds_tile <= 160 * 1024 - 512 && 32 * (s.r_k * 5 / 8) <= kQ4MaxLoads * 1024;
+    const int waves = tiled ? kQ4TileWaves : 4;
+    // one (line-wise) or two workgroups per compute unit, each over one contiguous range of a sequence
     const int pairs = s.batch * nblk;
-    const int wgs_per_pair = pairs >= 512 ? 1 : 512 / pairs;
+    const int want = tiled ? 256 : 512;
+    const int wgs_per_pair = pairs >= want ? 1 : want / pairs;
     int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
-    tiles_per_wg = tiles_per_wg < 4 ? 4 : (tiles_per_wg + 3) / 4 * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)score_q4_kernel<N_REP>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-        if (e != hipSuccess) return e;
-        attr_set = true;
+    tiles_per_wg = tiles_per_wg < waves ? waves : (tiles_per_wg + waves - 1) / waves * waves;
+    dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch);
+    hipError_t e = hipSuccess;
+    if (tiled) {
+        static bool attr8 = false;
+        if (!attr8) {
+            e = hipFuncSetAttribute((const void *)score_q4_tile_kernel<N_REP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024 - 512);
+            if (e != hipSuccess) return e;
+            attr8 = true;
+        }
+        profile_begin(0, st);
+        hipLaunchKernelGGL((score_q4_tile_kernel<N_REP>), grid, dim3(kQ4TileWaves * 64), lds_tile, st, Aq, Pfrag, S, S_heads,
+                           s.L, s.r_k, s.H_kv, F8, tiles_per_wg, p.scale);
+        profile_end(0, st);
+    } else {
+        static bool attr4 = false;
+        if (!attr4) {
+            e = hipFuncSetAttribute((const void *)score_q4_kernel<N_REP, 4, 16>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024 - 512);
+            if (e != hipSuccess) return e;
+            attr4 = true;
+        }
+        profile_begin(0, st);
+        hipLaunchKernelGGL((score_q4_kernel<N_REP, 4, 16>), grid, dim3(256), lds, st, Aq, Pfrag, S, S_heads, s.L, s.r_k,
+                           s.H_kv, F8, tiles_per_wg, p.scale);
+        profile_end(0, st);
     }
-    dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
-    profile_begin(0, st);
-    hipLaunchKernelGGL(score_q4_kernel<N_REP>, grid, block, lds, st, Aq, Pfrag, S, S_heads, s.L, s.r_k, s.H_kv, F8,
-                       tiles_per_wg, p.scale);
-    profile_end(0, st);
     return hipGetLastError();
 }
 
