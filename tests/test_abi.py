@@ -146,6 +146,32 @@ def test_absorbed_calls_validate_on_the_host():
                                       xb.xkv_workspace_bytes(good), null) == xb.XKV_ERR_WORKSPACE
 
 
+def test_quantised_calls_validate_on_the_host():
+    lib = xb.load()
+    good = xb.Shape.of(synth.LLAMA_FULL)
+    c, null, one, al = good.c(), ctypes.c_void_p(0), ctypes.c_void_p(256), ctypes.c_void_p(4096)
+    n = ctypes.c_size_t(0)
+    assert xb.xkv_quantized_row_bytes(512) == 320 and xb.xkv_quantized_row_bytes(384) == 240     # 5r/8
+    assert lib.xkv_quantized_row_bytes(512, 3, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED          # 3-bit rows: not built
+    assert lib.xkv_quantized_row_bytes(96, 4, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED           # r % 128 != 0
+    assert lib.xkv_quantized_row_bytes(512, 4, None) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_quantize_rows(al, 0, 512, 4, al, null) == xb.XKV_OK                             # nothing to do
+    assert lib.xkv_quantize_rows(null, 5, 512, 4, al, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_quantize_rows(ctypes.c_void_p(260), 5, 512, 4, al, null) == xb.XKV_ERR_INVALID_ARG   # misaligned
+    assert lib.xkv_quantize_rows(al, -1, 512, 4, al, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_quantize_rows(al, 5, 500, 4, al, null) == xb.XKV_ERR_UNSUPPORTED
+    big = 1 << 40
+    odd = xb.Shape.of(synth.LLAMA_FULL.with_(r_k=448)).c()                                         # r_k not a multiple of 128
+    assert lib.xkv_head_scores_q4(ctypes.byref(odd), 0, al, al, al, null, al, al, big, null) == xb.XKV_ERR_UNSUPPORTED
+    assert lib.xkv_head_scores_q4(ctypes.byref(c), 0, null, al, al, null, al, al, big, null) == xb.XKV_ERR_INVALID_ARG
+    f32 = xb.Shape.of(synth.LLAMA_FULL.with_(dtype="f32")).c()
+    assert lib.xkv_attend_absorbed_q4(ctypes.byref(f32), 0, al, one, al, one, one, al, big, null) == xb.XKV_ERR_UNSUPPORTED
+    assert lib.xkv_sr_decode_absorbed_q4(ctypes.byref(f32), 0, al, al, al, al, al, null, null, 0, one, null, null, al,
+                                         big, null) == xb.XKV_ERR_UNSUPPORTED
+    assert lib.xkv_sr_decode_absorbed_q4(ctypes.byref(c), 0, al, al, al, al, al, null, null, 0, one, null, null, al, 64,
+                                         null) == xb.XKV_ERR_WORKSPACE
+
+
 def test_binding_has_no_cpu_fallback(monkeypatch):
     monkeypatch.setattr(xb, "_lib", None)
     monkeypatch.setattr(xb, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
