@@ -539,8 +539,8 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
 //   acc_g[slot] = sum_{i in g} (128 + c_ti) p[slot][i]      (exact products, fp32 sums, P as bf16 hi + lo)
 // and the affine map of the group is applied to the sum, not to the elements:
 //   s[slot] += step_tg (acc_g[slot] - 128 Ps_g[slot]) + lo_tg Ps_g[slot],   Ps_g[slot] = sum_{i in g} p[slot][i].
-// (The second part is kept in fp32 multiply-adds: as a matrix-core product with bf16 high parts and remainders it
-// was measured 7 % faster but 200 times less accurate, because 128 step Ps cancels against the first part.)
+// (In this kernel the second part is kept in fp32 multiply-adds; the line-wise kernel below runs it on the matrix
+// cores with exact three-way splits.)
 // Lane (n, hf) loads the 16 bytes of each of token n's groups (both halves load the same pieces) and the parameter
 // words.  Always writes the per-head scores as well as the pooled ones.
 // ------------------------------------------------------------------------------------------
@@ -717,6 +717,9 @@ constexpr int kQ4TileWaves = 8;
 constexpr int kQ4MaxLoads = 10;  // 16-byte requests per lane and tile: 32 rows * 5r/8 bytes <= 10 KiB, r <= 512
 
 __host__ __device__ inline int q4_tile_pitch(int r) { return r * 5 / 8 + ((r / 128) % 2 == 0 ? 16 : 0); }  // bytes
+// (the offset term reads a row's parameters in runs of 64 bytes; the last run may reach up to 48 bytes past the
+// row, into the next row of the tile or, for the last row, the 64 bytes of slack behind the wavefront's tile)
+constexpr int kQ4TileSlack = 64;
 
 template <int N_REP>
 __global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const unsigned char *__restrict__ Aq,
@@ -736,7 +739,9 @@ __global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const 
     const int n = lane & 31, hf = lane >> 5;
     const int n_groups = r_k >> 5;
     const int tpitch = q4_tile_pitch(r_k);
-    unsigned char *tile_lds = reinterpret_cast<unsigned char *>(Ps + (F8 / 2) * 32) + (size_t)w * 32 * tpitch;
+    const int n_pass = (n_groups + 15) >> 4;  // passes of 16 groups of the offset term
+    u32x4_t *PsF = reinterpret_cast<u32x4_t *>(Ps + (F8 / 2) * 32);  // [n_pass][3 parts][64]: Ps as operand fragments
+    unsigned char *tile_lds = reinterpret_cast<unsigned char *>(PsF + n_pass * 3 * 64) + (size_t)w * (32 * tpitch + kQ4TileSlack);
     {
         const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Pfrag) + ((size_t)b * nblk + blk) * 2 * F8 * 64;
         const int total = 2 * F8 * 64;  // a multiple of 1024
@@ -762,6 +767,33 @@ __global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const 
             }
         sum += __shfl_xor(sum, 32, kWave);
         if (hf == 0) Ps[g * 32 + n] = sum;
+    }
+    __syncthreads();
+    // The offset term sum_g (lo_tg - 128 step_tg) Ps_g[slot] is a product [slots x groups] . [groups x tokens] and
+    // runs on the matrix cores, 16 groups per instruction.  Because 128 step Ps cancels against the first term it
+    // needs full fp32 accuracy: both factors are split *exactly* into three bf16 numbers (8 + 8 + 8 mantissa bits,
+    // by truncation) and the six largest of the nine partial products are taken; the dropped ones are below 2^-24
+    // of the term.  Here: Ps as operand fragments, lane (slot m, hf), position e = group 16 pass + 8 hf + e.
+    for (int ps = w; ps < n_pass; ps += WAVES) {
+        u32x4_t f3[3];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+            uint32_t part[2][3];
+#pragma unroll
+            for (int o = 0; o < 2; ++o) {
+                const int g = 16 * ps + 8 * hf + 2 * e2 + o;
+                float v = g < n_groups ? Ps[g * 32 + n] : 0.0f;
+#pragma unroll
+                for (int q3 = 0; q3 < 3; ++q3) {
+                    part[o][q3] = __float_as_uint(v) & 0xFFFF0000u;
+                    v -= __uint_as_float(part[o][q3]);
+                }
+            }
+#pragma unroll
+            for (int q3 = 0; q3 < 3; ++q3) f3[q3][e2] = (part[0][q3] >> 16) | part[1][q3];
+        }
+#pragma unroll
+        for (int q3 = 0; q3 < 3; ++q3) PsF[(ps * 3 + q3) * 64 + lane] = f3[q3];
     }
     __syncthreads();
 
@@ -801,6 +833,42 @@ __global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const 
             if (dst_off[i] >= 0) *reinterpret_cast<u32x4_t *>(tile_lds + dst_off[i]) = stage[i];
         const int tile_n = tile + WAVES;
         XKV_Q4_REQUEST(tile_n < tile_end ? tile_n : tile);
+        for (int ps = 0; ps < n_pass; ++ps) {
+            // (lo - 128 step) of this half's eight groups of the pass, split like Ps
+            const u32x4_t *par = reinterpret_cast<const u32x4_t *>(my_row + (r_k >> 1) + 64 * ps + 32 * hf);
+            const u32x4_t pa = par[0], pb = par[1];
+            u32x4_t c3[3];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                uint32_t part[2][3];
+#pragma unroll
+                for (int o = 0; o < 2; ++o) {
+                    const int e = 2 * e2 + o;
+                    const uint32_t pword = e < 4 ? pa[e & 3] : pb[e & 3];
+                    float v = fmaf(-128.0f, __uint_as_float(pword << 16), __uint_as_float(pword & 0xFFFF0000u));
+                    v = 16 * ps + 8 * hf + e < n_groups ? v : 0.0f;  // beyond the row: whatever the tile holds there
+#pragma unroll
+                    for (int q3 = 0; q3 < 3; ++q3) {
+                        part[o][q3] = __float_as_uint(v) & 0xFFFF0000u;
+                        v -= __uint_as_float(part[o][q3]);
+                    }
+                }
+#pragma unroll
+                for (int q3 = 0; q3 < 3; ++q3) c3[q3][e2] = (part[0][q3] >> 16) | part[1][q3];
+            }
+            const u32x4_t *pf = PsF + ps * 3 * 64 + lane;
+            const bf16x8_t p0 = __builtin_bit_cast(bf16x8_t, pf[0]), p1 = __builtin_bit_cast(bf16x8_t, pf[64]);
+            const bf16x8_t p2 = __builtin_bit_cast(bf16x8_t, pf[128]);
+            const bf16x8_t c0 = __builtin_bit_cast(bf16x8_t, c3[0]), c1 = __builtin_bit_cast(bf16x8_t, c3[1]);
+            const bf16x8_t c2v = __builtin_bit_cast(bf16x8_t, c3[2]);
+            // smallest products first
+            tot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, c1, tot, 0, 0, 0);
+            tot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p2, c0, tot, 0, 0, 0);
+            tot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, c2v, tot, 0, 0, 0);
+            tot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p1, c0, tot, 0, 0, 0);
+            tot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, c1, tot, 0, 0, 0);
+            tot = __builtin_amdgcn_mfma_f32_32x32x16_bf16(p0, c0, tot, 0, 0, 0);
+        }
         for (int g = 0; g < n_groups; ++g) {
             const u32x4_t cw = *reinterpret_cast<const u32x4_t *>(my_row + 16 * g);
             const uint32_t pword = *reinterpret_cast<const uint32_t *>(my_row + (r_k >> 1) + 4 * g);
@@ -814,16 +882,9 @@ __global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const 
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ph), bop, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pl), bop, acc, 0, 0, 0);
             }
-            const float step = __uint_as_float(pword << 16), lo = __uint_as_float(pword & 0xFFFF0000u);
-            const float c2 = fmaf(-128.0f, step, lo);
+            const float step = __uint_as_float(pword << 16);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float4 ps = *reinterpret_cast<const float4 *>(Ps + g * 32 + 8 * i + 4 * hf);
-                tot[4 * i + 0] = fmaf(step, acc[4 * i + 0], fmaf(c2, ps.x, tot[4 * i + 0]));
-                tot[4 * i + 1] = fmaf(step, acc[4 * i + 1], fmaf(c2, ps.y, tot[4 * i + 1]));
-                tot[4 * i + 2] = fmaf(step, acc[4 * i + 2], fmaf(c2, ps.z, tot[4 * i + 2]));
-                tot[4 * i + 3] = fmaf(step, acc[4 * i + 3], fmaf(c2, ps.w, tot[4 * i + 3]));
-            }
+            for (int v = 0; v < 16; ++v) tot[v] = fmaf(step, acc[v], tot[v]);
         }
         const int t = tile * 32 + n;
         if (t < L) {
@@ -1073,7 +1134,8 @@ static hipError_t launch_score_q4_t(const xkv_shape &s, const Plan &p, const uns
     const int nblk = mfma_blocks(s.H_kv, N_REP);
     const int n_tiles = (s.L + 31) / 32;
     const size_t lds = (size_t)2 * F8 * 64 * 16 + (size_t)(F8 / 2) * 32 * 4;
-    const size_t lds_tile = lds + (size_t)kQ4TileWaves * 32 * q4_tile_pitch(s.r_k);
+    const size_t lds_tile = lds + (size_t)((F8 / 2 + 15) / 16) * 3 * 64 * 16 +
+                            (size_t)kQ4TileWaves * (32 * q4_tile_pitch(s.r_k) + kQ4TileSlack);
     const bool tiled = lds_tile <= 160 * 1024 - 512 && 32 * (s.r_k * 5 / 8) <= kQ4MaxLoads * 1024;
     const int waves = tiled ? kQ4TileWaves : 4;
     // one (line-wise) or two workgroups per compute unit, each over one contiguous range of a sequence
