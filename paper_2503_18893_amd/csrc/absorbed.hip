@@ -378,8 +378,9 @@ AbsorbPlan make_absorb_plan(const xkv_shape &s, size_t base_bytes)
     a.nrp = head_pitch_of(s.H_q / s.H_kv);
     a.col_blocks = ab_ceil_div(s.r_v, 64 * E);
     const int rows = s.batch * s.H_kv > 0 ? s.batch * s.H_kv : 1;
-    // about eight workgroups per compute unit; a split holds 64..512 tokens (ids and weights live in LDS)
-    const int want = ab_ceil_div(2048, rows * a.col_blocks);
+    // about four workgroups per compute unit (more, shorter splits only add partial sums to write and to merge);
+    // a split holds 64..512 tokens (ids and weights live in LDS)
+    const int want = ab_ceil_div(1024, rows * a.col_blocks);
     int chunk = ab_ceil_div(ab_ceil_div(s.k, want), 32) * 32;
     chunk = chunk < 64 ? 64 : (chunk > 512 ? 512 : chunk);
     a.chunk = chunk;
