@@ -180,6 +180,42 @@ def test_quantised_step_chain(name, w):
         print(name, b, "head scores", err_s, "attention", err_o, flush=True)
 
 
+@pytest.mark.parametrize("T", [1, 77, 700])
+def test_quantised_step_with_uncompressed_tail(T):
+    """The quantised step with T uncompressed recent tokens in the same softmax, against the oracle's attention over
+    the de-quantised reconstructed rows plus the tail (fed the GPU's own index sets)."""
+    torch = torch_mod()
+    w = synth.LLAMA_GROUP.with_(L=3000, k=200, r_k=128, r_v=256, batch=2, G=1)
+    case = synth.make_case(w, seed=29)
+    dev = synth.to_device(case, w.dtype)
+    rng = np.random.default_rng(6)
+    K_t = synth.to_storage(rng.standard_normal((w.batch, w.H_kv, T, w.d_h)) * 0.3, w.dtype)
+    V_t = synth.to_storage(rng.standard_normal((w.batch, w.H_kv, T, w.d_h)), w.dtype)
+    tail = synth.to_device({"K": K_t, "V": V_t}, w.dtype)
+    shape = xb.Shape.of(w)
+    ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    q = dev["q"][0].contiguous()
+    Aqk = torch.empty((w.batch, w.L, xb.xkv_quantized_row_bytes(w.r_k)), dtype=torch.uint8, device="cuda")
+    Aqv = torch.empty((w.batch, w.L, xb.xkv_quantized_row_bytes(w.r_v)), dtype=torch.uint8, device="cuda")
+    xb.xkv_quantize_rows(dev["A_k"], w.batch * w.L, w.r_k, Aqk)
+    xb.xkv_quantize_rows(dev["A_v"], w.batch * w.L, w.r_v, Aqv)
+    out = torch.empty((w.batch, w.H_q, w.d_h), dtype=torch.bfloat16, device="cuda")
+    idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
+    S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
+    xb.xkv_sr_decode_absorbed_q4(shape, 0, Aqk, Aqv, dev["B_k"], dev["B_v"], q, out, idx, S, ws, K_tail=tail["K"],
+                                 V_tail=tail["V"], T=T)
+    torch.cuda.synchronize()
+    outh, idxh, Sh = synth.storage_to_f64(synth.to_host(out)), idx.cpu().numpy(), S.cpu().numpy()
+    for b in range(w.batch):
+        for g in range(w.H_kv):
+            np.testing.assert_array_equal(idxh[b, g], oracle.select(Sh[b, g], w.k))
+        Ak_hat = oracle.dequantize_rows(*oracle.quantize_rows(case["A_k"][b]))
+        Av_hat = oracle.dequantize_rows(*oracle.quantize_rows(case["A_v"][b]))
+        ref = oracle.gather_attend_tail(Ak_hat, Av_hat, case["B_k"][b, 0], case["B_v"][b, 0], case["q"][0, b], idxh[b],
+                                        K_t[b], V_t[b])
+        assert max_rel(outh[b], ref) <= TOL, (T, b)
+
+
 def test_quantised_step_full_size_sampled():
     """Benchmark configuration 3 with both token bases quantised, the launch configuration the benchmark times:
     sampled head scores, the complete selection of the sampled sequences, and their outputs."""
