@@ -33,7 +33,8 @@ def parse_args():
     ap.add_argument("--workload", default="llama_full", choices=["llama_group", "llama_full", "qwen"])
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch")
     ap.add_argument("--L", type=int, default=None)
-    ap.add_argument("--r", type=int, default=None)
+    ap.add_argument("--r", type=int, default=None, help="rank of both token bases (r_k = r_v)")
+    ap.add_argument("--r-v", type=int, default=None, help="rank of the value basis alone (e.g. 1.5 x r_k)")
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--groups", type=int, default=None, help="override the number of layer groups held in HBM")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense baseline")
@@ -86,6 +87,8 @@ def main():
         over["L"] = args.L
     if args.r is not None:
         over.update(r_k=args.r, r_v=args.r, a_scale=1.0 / float(np.sqrt(args.r)))
+    if args.r_v is not None:
+        over["r_v"] = args.r_v
     if args.k is not None:
         over["k"] = args.k
     if args.groups is not None:

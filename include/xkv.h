@@ -244,18 +244,18 @@ XKV_API xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer_
  * 4-bit round-to-nearest quantisation of the token basis (App. "Integrate with Quantization": a plain RTN quantiser
  * applied to the compressed cache, 25.6x total at 4 bits).  The paper gives no format; this one is what its ratios
  * imply (one extra bit per element: two 16-bit numbers per group of 32).  A row of r bf16 numbers (r a multiple of
- * 128) becomes 5r/8 bytes: r/8 little-endian 32-bit words of codes (word j holds ranks 8j..8j+7: rank 8j+2i in bits
+ * 32) becomes 5r/8 bytes, padded with zero bytes to a multiple of 16 (no padding when r is a multiple of 128): r/8 little-endian 32-bit words of codes (word j holds ranks 8j..8j+7: rank 8j+2i in bits
  * [4i, 4i+4), rank 8j+2i+1 in bits [16+4i, 16+4i+4), i = 0..3), then r/32 pairs (step, lo) of bf16.  Per group of 32 consecutive ranks: lo = min, step = bf16((max - lo) / 15)
  * (1 if that is 0), code = clip(rint((x - lo) * (1 / step)), 0, 15) in fp32; the value every later stage sees is
  * x^ = step * code + lo.
- *   xkv_quantized_row_bytes: 5r/8, or XKV_ERR_UNSUPPORTED (bits != 4, r not a multiple of 128).
- *   xkv_quantize_rows: X [rows][r] bf16 -> out [rows][5r/8] bytes (both device, 16-byte aligned).
- *   xkv_attend_absorbed_q4: xkv_attend_absorbed with A^V given as quantised rows Aq_v [batch][L][5 r_v / 8]; the
+ *   xkv_quantized_row_bytes: the row size, or XKV_ERR_UNSUPPORTED (bits != 4, r not a multiple of 32).
+ *   xkv_quantize_rows: X [rows][r] bf16 -> out [rows][row size] bytes (both device, 16-byte aligned).
+ *   xkv_attend_absorbed_q4: xkv_attend_absorbed with A^V given as quantised rows Aq_v [batch][L][row size]; the
  *     rows are de-quantised in registers inside the row-sum kernel, so the gather moves 5/16 of the bytes.  bf16
  *     shapes only; B_v, head_scores, idx, out and the workspace as in xkv_attend_absorbed.
  *   xkv_head_scores_q4: xkv_head_scores with A^K given as quantised rows Aq_k [batch][L][5 r_k / 8]: the codes are
  *     the matrix-core operand and a group's (step, lo) is applied to the group's partial sum, so the score stream
- *     is 5/16 of the bytes.  bf16 shapes with at most 8, or 16, query heads per KV head.
+ *     is 5/16 of the bytes.  bf16 shapes with at most 8, or 16, query heads per KV head, r_k a multiple of 128.
  *   xkv_sr_decode_absorbed_q4: xkv_sr_decode_absorbed on quantised A^K and A^V (B_k, B_v, q, the tail and the
  *     output stay bf16).  What it computes is the absorbed step on the de-quantised values x^.
  */

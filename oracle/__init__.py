@@ -449,7 +449,7 @@ def pack_q4(codes, step, lo):
     """Byte layout of a 4-bit row as the library stores it: r/8 little-endian 32-bit words of codes -- word j holds
     ranks 8j .. 8j+7, rank 8j + 2i in bits [4i, 4i+4) and rank 8j + 2i + 1 in bits [16 + 4i, 16 + 4i + 4), i = 0..3,
     so that two adjacent ranks sit 16 bits apart like a packed pair of 16-bit numbers -- then per group (step, lo) as
-    two bf16 numbers.  5r/8 bytes per row."""
+    two bf16 numbers: 5r/8 bytes, then zero bytes up to the next multiple of 16 (none when r is a multiple of 128)."""
     rows, r = codes.shape
     assert codes.max(initial=0) < 16
     c = codes.reshape(rows, r // 8, 4, 2).astype(np.uint32)          # [word][i][even / odd rank]
@@ -459,7 +459,9 @@ def pack_q4(codes, step, lo):
     par = np.empty((rows, r // Q_GROUP, 2), np.uint16)
     par[:, :, 0] = (np.ascontiguousarray(step, np.float32).view(np.uint32) >> 16).astype(np.uint16)
     par[:, :, 1] = (np.ascontiguousarray(lo, np.float32).view(np.uint32) >> 16).astype(np.uint16)
-    return np.concatenate([nib, par.reshape(rows, -1).view(np.uint8)], axis=1)
+    row = np.concatenate([nib, par.reshape(rows, -1).view(np.uint8)], axis=1)
+    pad = (-row.shape[1]) % 16
+    return np.concatenate([row, np.zeros((rows, pad), np.uint8)], axis=1) if pad else row
 
 
 def unpack_q4(packed, r):
@@ -472,7 +474,7 @@ def unpack_q4(packed, r):
         codes[:, :, i, 0] = (words >> (4 * i)) & 15
         codes[:, :, i, 1] = (words >> (16 + 4 * i)) & 15
     codes = codes.reshape(rows, r)
-    par = np.ascontiguousarray(packed[:, r // 2:]).view(np.uint16).reshape(rows, r // Q_GROUP, 2)
+    par = np.ascontiguousarray(packed[:, r // 2:r // 2 + r // 8]).view(np.uint16).reshape(rows, r // Q_GROUP, 2)
     step = (par[:, :, 0].astype(np.uint32) << 16).view(np.float32)
     lo = (par[:, :, 1].astype(np.uint32) << 16).view(np.float32)
     return codes, np.ascontiguousarray(step), np.ascontiguousarray(lo)

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kAbsorbWaves * 64) void absorb_rows_kernel(const T 
         for (int e = 0; e < E; ++e) acc[hh][e] = 0.0f;
     if constexpr (Q4) {
         if (active) {
-            const size_t pitch = (size_t)r_v * 5 / 8;
+            const size_t pitch = quant_row_bytes(r_v);
             const unsigned char *Ab = reinterpret_cast<const unsigned char *>(A_v) + (size_t)b * L * pitch;
             const size_t par_off = (size_t)(r_v >> 1) + 4 * (size_t)(pc >> 2);
             float accl[NRP];

@@ -2,10 +2,10 @@
 // RTN quantiser on the compressed cache; the format below is the one the two published ratios imply -- one extra
 // bit per element of side information = two 16-bit numbers per group of 32 elements).
 //
-// Row layout, r a multiple of 128:  r/8 32-bit words of codes (word j holds ranks 8j..8j+7: rank 8j+2i in bits
+// Row layout, r a multiple of 32:  r/8 32-bit words of codes (word j holds ranks 8j..8j+7: rank 8j+2i in bits
 // [4i, 4i+4), rank 8j+2i+1 in bits [16+4i, 16+4i+4), so two adjacent ranks are one shift and one mask away from a
-// packed pair of 16-bit numbers), then r/32 pairs (step, lo) of bf16: 5r/8 bytes per row, every row and every
-// group 16-byte aligned.
+// packed pair of 16-bit numbers), then r/32 pairs (step, lo) of bf16: 5r/8 bytes, then zero bytes up to the next
+// multiple of 16 (none when r is a multiple of 128), so that every row and every group is 16-byte aligned.
 //   lo = min of the group, step = bf16((max - lo) / 15) (1 if that is 0), code = clip(rint((x - lo) * (1 / step)), 0, 15),
 // each a single fp32 operation (the same sequence as the CPU oracle: the codes agree bit for bit);  x^ = step * code + lo.
 #include "xkv_common.h"
@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void quantize_rows_q4_kernel(const bf16_t *__r
                                                                long long pieces, int r)
 {
     const long long p = (long long)blockIdx.x * 256 + threadIdx.x;
-    // pieces is a multiple of 16 (r % 128 == 0), so a group's four lanes are all inside or all outside
+    // pieces is a multiple of 4 (r % 32 == 0), so a group's four lanes are all inside or all outside
     const bool in = p < pieces;
     const int ppr = r >> 3;  // pieces per row
     const long long row = (in ? p : 0) / ppr;
@@ -59,6 +59,8 @@ __global__ __launch_bounds__(256) void quantize_rows_q4_kernel(const bf16_t *__r
     reinterpret_cast<uint32_t *>(orow)[pc] = word;
     if ((pc & 3) == 0)
         reinterpret_cast<uint32_t *>(orow + (r >> 1))[pc >> 2] = (uint32_t)f32_to_bf16(step) | ((uint32_t)f32_to_bf16(lo) << 16);
+    if (pc == 0)  // the row's padding
+        for (int i = (r >> 3) + (r >> 5); i < (int)(quant_row_bytes(r) >> 2); ++i) reinterpret_cast<uint32_t *>(orow)[i] = 0u;
 }
 
 hipError_t launch_quantize_rows(const void *X, long long rows, int r, void *out, hipStream_t st)

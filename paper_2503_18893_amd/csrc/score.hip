@@ -1179,7 +1179,7 @@ bool score_q4_shape_ok(const xkv_shape &s)
     if (s.H_kv <= 0 || s.H_q % s.H_kv != 0) return false;
     const int n_rep = s.H_q / s.H_kv;
     const bool rep_ok = (n_rep >= 1 && n_rep <= 8) || n_rep == 16;
-    return s.dtype == XKV_BF16 && rep_ok && quant_rank_ok(s.r_k) && s.r_k <= 2048 && s.d_h % 16 == 0;
+    return s.dtype == XKV_BF16 && rep_ok && s.r_k > 0 && s.r_k % 128 == 0 && s.r_k <= 2048 && s.d_h % 16 == 0;
 }
 
 // Projection (as for the bf16 stream) and the score kernel over quantised rows; S and S_heads are both written.

@@ -182,9 +182,10 @@ AbsorbPlan make_absorb_plan(const xkv_shape &s, size_t base_bytes);
 hipError_t launch_absorbed(const xkv_shape &s, const AbsorbPlan &a, int layer, const void *A_v, const void *B_v,
                            const float *S_heads, const int32_t *idx, float *po, float *pml, float *part_u,
                            float *part_ml, hipStream_t st, bool q4 = false);
-// 4-bit round-to-nearest rows (see quant.hip): 5 r / 8 bytes per row, r a multiple of 128.
-inline bool quant_rank_ok(int r) { return r > 0 && r % 128 == 0; }
-__host__ __device__ inline size_t quant_row_bytes(int r) { return (size_t)r * 5 / 8; }
+// 4-bit round-to-nearest rows (see quant.hip): r a multiple of 32; 5 r / 8 bytes per row, padded with zero bytes to
+// a multiple of 16 (no padding when r is a multiple of 128).  The score kernels take multiples of 128 only.
+inline bool quant_rank_ok(int r) { return r > 0 && r % 32 == 0; }
+__host__ __device__ inline size_t quant_row_bytes(int r) { return ((size_t)r * 5 / 8 + 15) / 16 * 16; }
 bool score_q4_shape_ok(const xkv_shape &s);
 hipError_t launch_score_q4_stage(const xkv_shape &s, const Plan &p, int layer, const void *Aq_k, const void *B_k,
                                  const void *q, void *P_ws, float *S, float *S_heads, hipStream_t st);

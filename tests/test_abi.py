@@ -153,7 +153,8 @@ def test_quantised_calls_validate_on_the_host():
     n = ctypes.c_size_t(0)
     assert xb.xkv_quantized_row_bytes(512) == 320 and xb.xkv_quantized_row_bytes(384) == 240     # 5r/8
     assert lib.xkv_quantized_row_bytes(512, 3, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED          # 3-bit rows: not built
-    assert lib.xkv_quantized_row_bytes(96, 4, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED           # r % 128 != 0
+    assert xb.xkv_quantized_row_bytes(96) == 64 and xb.xkv_quantized_row_bytes(576) == 368      # padded to 16 bytes
+    assert lib.xkv_quantized_row_bytes(100, 4, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED          # r % 32 != 0
     assert lib.xkv_quantized_row_bytes(512, 4, None) == xb.XKV_ERR_INVALID_ARG
     assert lib.xkv_quantize_rows(al, 0, 512, 4, al, null) == xb.XKV_OK                             # nothing to do
     assert lib.xkv_quantize_rows(null, 5, 512, 4, al, null) == xb.XKV_ERR_INVALID_ARG

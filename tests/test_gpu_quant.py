@@ -39,7 +39,8 @@ def quantize_gpu(x_bits):
     return out
 
 
-@pytest.mark.parametrize("rows,r", [(1, 128), (7, 128), (333, 384), (1000, 512), (65, 2048), (0, 256)])
+@pytest.mark.parametrize("rows,r", [(1, 128), (7, 128), (333, 384), (1000, 512), (65, 2048), (0, 256), (50, 32),
+                                    (77, 96), (500, 576)])
 def test_quantiser_matches_the_oracle_bit_for_bit(rows, r):
     rng = np.random.default_rng(rows * 7 + r)
     x = rng.standard_normal((rows, r)) * np.exp(rng.standard_normal((rows, 1)))
@@ -50,7 +51,7 @@ def test_quantiser_matches_the_oracle_bit_for_bit(rows, r):
     xbits = synth.to_storage(x, "bf16")
     got = quantize_gpu(xbits).cpu().numpy()
     codes, step, lo = oracle.quantize_rows(xbits)
-    want = oracle.pack_q4(codes, step, lo) if rows else np.zeros((0, 5 * r // 8), np.uint8)
+    want = oracle.pack_q4(codes, step, lo) if rows else np.zeros((0, xb.xkv_quantized_row_bytes(r)), np.uint8)
     np.testing.assert_array_equal(got, want)
 
 
@@ -76,6 +77,8 @@ CASES = [
     ("llama_small", synth.LLAMA_GROUP.with_(L=3000, k=200, r_k=128, r_v=256, batch=2, G=2)),
     ("qwen_small", synth.QWEN.with_(L=5001, k=257, r_k=128, r_v=128, batch=1, G=1)),
     ("wide_rv", synth.LLAMA_GROUP.with_(L=2500, k=700, r_k=64, r_v=640, batch=1, G=1)),
+    ("paper_ranks_384_576", synth.LLAMA_GROUP.with_(L=2100, k=300, r_k=384, r_v=576, batch=1, G=1)),
+    ("rv_96", synth.LLAMA_GROUP.with_(L=1500, k=100, r_k=64, r_v=96, batch=2, G=1)),
     ("gqa16_dh64", synth.Workload("gqa16", G=1, H_kv=3, H_q=48, d_h=64, r_k=48, r_v=128, L=1111, k=40, batch=1,
                                   dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
     ("k2100_dh256", synth.Workload("k2100", G=1, H_kv=2, H_q=8, d_h=256, r_k=64, r_v=384, L=6000, k=2100, batch=2,
@@ -127,6 +130,8 @@ STEP_CASES = [
                                        dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
     ("mha_r640", synth.Workload("mha", G=2, H_kv=20, H_q=20, d_h=64, r_k=640, r_v=256, L=900, k=50, batch=2,
                                 dtype="bf16", a_scale=0.3, sigma_decay=0.8, q_scale=0.2)),
+    # the paper's ranks at window 4 (r_K : r_V = 1 : 1.5); rows of A^V are padded from 360 to 368 bytes
+    ("paper_ranks_384_576", synth.LLAMA_GROUP.with_(L=2100, k=300, r_k=384, r_v=576, batch=1, G=1)),
 ]
 
 
@@ -263,7 +268,7 @@ def test_quantised_step_full_size_sampled():
 def test_quantised_calls_reject_what_they_do_not_cover():
     torch = torch_mod()
     with pytest.raises(xb.XkvError) as ei:
-        xb.xkv_quantized_row_bytes(96)
+        xb.xkv_quantized_row_bytes(100)
     assert ei.value.status == xb.XKV_ERR_UNSUPPORTED
     with pytest.raises(xb.XkvError) as ei:
         xb.xkv_quantized_row_bytes(128, bits=3)

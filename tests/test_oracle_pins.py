@@ -591,6 +591,10 @@ def test_quantiser_reproduces_the_papers_two_compression_ratios():
     # the packed 4-bit row really has that size: 5r/8 bytes against 2r
     codes, step, lo = oracle.quantize_rows(np.zeros((3, 128), np.float32))
     assert oracle.pack_q4(codes, step, lo).shape == (3, 80)
+    # ranks that are not multiples of 128 are padded to whole 16-byte units: 5 * 96 / 8 = 60 -> 64, 576 -> 360 -> 368
+    c96 = oracle.pack_q4(*oracle.quantize_rows(np.ones((2, 96), np.float32)))
+    assert c96.shape == (2, 64) and not c96[:, 60:].any()
+    assert oracle.pack_q4(*oracle.quantize_rows(np.zeros((1, 576), np.float32))).shape == (1, 368)
 
 
 def test_quantiser_on_a_group_worked_by_hand():
@@ -634,7 +638,7 @@ def test_q4_pack_layout_and_round_trip():
     step = np.array([[0.5, 2.0], [1.0, 0.25]], np.float32)
     lo = np.array([[-1.0, 3.0], [0.0, -8.0]], np.float32)
     p = oracle.pack_q4(codes, step, lo)
-    assert p.shape == (2, 40) and p.dtype == np.uint8
+    assert p.shape == (2, 48) and p.dtype == np.uint8 and not p[:, 40:].any()   # 40 bytes, padded to 16-byte units
     # word 0 = ranks 0..7 = codes 0..7: even ranks 0,2,4,6 in bits 0..15, odd ranks 1,3,5,7 in bits 16..31
     assert p[0, 0:4].tolist() == [0x20, 0x64, 0x31, 0x75] and p[0, 4:8].tolist() == [0xA8, 0xEC, 0xB9, 0xFD]
     assert p[0, 32:36].tolist() == [0x00, 0x3F, 0x80, 0xBF]                 # bf16(0.5) = 0x3F00, bf16(-1) = 0xBF80
