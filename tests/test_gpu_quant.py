@@ -265,6 +265,62 @@ def test_quantised_step_full_size_sampled():
         print("seq", b, "quantised step vs oracle", err, flush=True)
 
 
+def test_prefill_to_decode_chain_factorize_quantise_decode():
+    """The whole chain on the GPU: caches -> xkv_factorize (keys and values) -> xkv_quantize_rows ->
+    xkv_sr_decode_absorbed_q4 with k = L.  Reference: the oracle's attention on the factors the GPU produced, with
+    their token bases quantised by the oracle's quantiser (whose packed rows must equal the GPU's); and the
+    bf16 absorbed and gather-reconstruct steps on the unquantised factors must agree with each other."""
+    torch = torch_mod()
+    G, H_kv, H_q, d_h, L, r, dtype = 2, 2, 8, 64, 640, 128, "bf16"
+    rng = np.random.default_rng(12)
+    caches = [synth.make_cache(rng, G, H_kv, d_h, L, 0.5, dtype=dtype) for _ in range(2)]   # keys, values (full rank)
+    fshape = xb.Shape(G=G, H_kv=H_kv, H_q=H_kv, d_h=d_h, r_k=r, r_v=r, L=L, k=1, batch=1, dtype=dtype)
+    fws = torch.empty(xb.xkv_factorize_workspace_bytes(fshape, r), dtype=torch.uint8, device="cuda")
+    fac = []
+    for i, X in enumerate(caches):
+        Xd = synth.to_device({"X": X[None]}, dtype)["X"]
+        A = torch.zeros((1, L, r), dtype=torch.bfloat16, device="cuda")
+        B = torch.zeros((1, G, r, H_kv * d_h), dtype=torch.bfloat16, device="cuda")
+        xb.xkv_factorize(fshape, Xd, r, 8, 7 + i, A, B, fws)
+        fac.append((A, B))
+    (A_k, B_k), (A_v, B_v) = fac
+    shape = xb.Shape(G=G, H_kv=H_kv, H_q=H_q, d_h=d_h, r_k=r, r_v=r, L=L, k=L, batch=1, dtype=dtype)
+    ws = torch.empty(xb.xkv_absorbed_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    Aqk = torch.empty((1, L, xb.xkv_quantized_row_bytes(r)), dtype=torch.uint8, device="cuda")
+    Aqv = torch.empty_like(Aqk)
+    xb.xkv_quantize_rows(A_k, L, r, Aqk)
+    xb.xkv_quantize_rows(A_v, L, r, Aqv)
+    q_host = synth.to_storage(rng.standard_normal((G, 1, H_q, d_h)) * 0.5, dtype)
+    q_dev = synth.to_device({"q": q_host}, dtype)["q"]
+    torch.cuda.synchronize()
+    Ak_h, Av_h = synth.to_host(A_k[0]), synth.to_host(A_v[0])
+    qk, qv = oracle.quantize_rows(Ak_h), oracle.quantize_rows(Av_h)
+    np.testing.assert_array_equal(Aqk[0].cpu().numpy(), oracle.pack_q4(*qk))
+    np.testing.assert_array_equal(Aqv[0].cpu().numpy(), oracle.pack_q4(*qv))
+    Ak_hat, Av_hat = oracle.dequantize_rows(*qk), oracle.dequantize_rows(*qv)
+    idx_all = np.tile(np.arange(L, dtype=np.int32), (H_kv, 1))
+    for layer in range(G):
+        outs = {}
+        for kind in ("q4", "absorbed", "gather"):
+            out = torch.empty((1, H_q, d_h), dtype=torch.bfloat16, device="cuda")
+            ql = q_dev[layer].contiguous()
+            if kind == "q4":
+                xb.xkv_sr_decode_absorbed_q4(shape, layer, Aqk, Aqv, B_k, B_v, ql, out, None, None, ws)
+            elif kind == "absorbed":
+                xb.xkv_sr_decode_absorbed(shape, layer, A_k, A_v, B_k, B_v, ql, out, None, None, ws)
+            else:
+                xb.xkv_sr_decode(shape, layer, A_k, A_v, B_k, B_v, ql, out, None, None, ws)
+            torch.cuda.synchronize()
+            outs[kind] = synth.storage_to_f64(synth.to_host(out))[0]
+        Bk_h, Bv_h = synth.to_host(B_k[0, layer]), synth.to_host(B_v[0, layer])
+        ref_q = oracle.gather_attend(Ak_hat, Av_hat, Bk_h, Bv_h, q_host[layer, 0], idx_all)
+        ref = oracle.gather_attend(Ak_h, Av_h, Bk_h, Bv_h, q_host[layer, 0], idx_all)
+        assert max_rel(outs["q4"], ref_q) <= TOL, layer
+        assert max_rel(outs["absorbed"], ref) <= TOL and max_rel(outs["gather"], ref) <= TOL, layer
+        print("layer", layer, "q4 vs oracle on x^", max_rel(outs["q4"], ref_q), "4-bit vs bf16 factors",
+              max_rel(ref_q, ref), flush=True)
+
+
 def test_quantised_calls_reject_what_they_do_not_cover():
     torch = torch_mod()
     with pytest.raises(xb.XkvError) as ei:
