@@ -460,27 +460,11 @@ def main():
             ms_q = time_loop(torch, quantized_step, max(2, min(args.steps, 5)))
             heads_q = torch.empty((w.batch, w.H_kv, w.L, xb.head_pitch(shape)), dtype=torch.float32, device="cuda")
 
-            def kernel_ms_q(stage_id, call):
-                ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                ev0.record()
-                ev1.record()
-                torch.cuda.synchronize()
-                xb.xkv_profile_kernel(stage_id, ev0.cuda_event, ev1.cuda_event)
-                total, count = 0.0, 0
-                for s_i in range(n_q):
-                    for l in range(w.G):
-                        call(s_i, l)
-                        torch.cuda.synchronize()
-                        total += ev0.elapsed_time(ev1)
-                        count += 1
-                xb.xkv_profile_kernel(stage_id, None, None)
-                return total / count
-
             qk = {
-                "head_scores_q4": kernel_ms_q(xb.STAGE_SCORE,
+                "head_scores_q4": kernel_ms(xb.STAGE_SCORE,
                                               lambda s_i, l: xb.xkv_head_scores_q4(shape, l, Aqk[s_i], groups[s_i]["B_k"],
                                                                                    qs[s_i][l], S, heads_q, q_ws)),
-                "absorb_rows_q4": kernel_ms_q(xb.STAGE_ABSORB_ROWS,
+                "absorb_rows_q4": kernel_ms(xb.STAGE_ABSORB_ROWS,
                                               lambda s_i, l: xb.xkv_attend_absorbed_q4(shape, l, Aqv[s_i],
                                                                                        groups[s_i]["B_v"], heads_q, idx,
                                                                                        out, q_ws)),

@@ -106,8 +106,9 @@ def load() -> ctypes.CDLL:
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
         lib.xkv_version.restype = i32
-        for name in ENTRY_POINTS[:24]:
-            getattr(lib, name).restype = ctypes.c_int
+        for name in ENTRY_POINTS:
+            if name not in ("xkv_status_string", "xkv_version"):   # every other call returns an xkv_status
+                getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
 
