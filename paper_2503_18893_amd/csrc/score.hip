@@ -306,7 +306,9 @@ template <int NRP> __device__ __forceinline__ void store_head_row(float *dst, co
 #pragma unroll
         for (int c = 0; c < NRP / 4; ++c) {
             const f32x4_t x = {v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]};
-            asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(dst + 4 * c), "v"(x) : "memory");
+            // (a store of more than 64 bits reads its data registers a cycle or two after issue; the compiler inserts
+            // the wait states for stores it knows, not for these)
+            asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(dst + 4 * c), "v"(x) : "memory");
         }
     }
 }
