@@ -246,7 +246,9 @@ __global__ __launch_bounds__(kRcWaves * 64) void reconstruct_mfma_kernel(const b
             const rc_u32x4_t val = At[16 * tt + (((lane & 15) + tt) & 15)];
             if (t < L) {
                 rc_u32x4_t *dst = reinterpret_cast<rc_u32x4_t *>(Xg + (size_t)t * 128) + (lane & 15);
-                asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(dst), "v"(val) : "memory");
+                // (wait states: a store of more than 64 bits reads its data registers after issue, and the compiler
+                // does not cover stores it cannot see)
+                asm volatile("global_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(dst), "v"(val) : "memory");
             }
         }
     };
