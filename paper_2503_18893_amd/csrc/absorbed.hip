@@ -251,7 +251,12 @@ __global__ __launch_bounds__(kAbsorbWaves * 64) void absorb_rows_kernel(const T 
 // others 0), so that the ordinary merge kernel sums the slices and divides -- and can take the partials of an
 // uncompressed tail into the same softmax.
 // ------------------------------------------------------------------------------------------
-template <typename T, int NRP>
+//
+// WIDE: rows of B^V_g are fetched 16 bytes per lane, 64 / lpr rows per request (lpr = lanes per row, a power of
+// two), instead of one element per lane.  With one element per lane a request is 128 bytes and the number of
+// requests a compute unit can have in flight caps the whole chip at about 1.5 TB/s: phase timestamps showed 11 of
+// the kernel's 15 us waiting for these 16 MB.
+template <typename T, int NRP, bool WIDE>
 __global__ __launch_bounds__(256) void absorb_project_kernel(const float *__restrict__ part_u,
                                                              const float *__restrict__ part_ml,
                                                              const T *__restrict__ B_v,   // [batch][G][r_v][d]
@@ -276,16 +281,31 @@ __global__ __launch_bounds__(256) void absorb_project_kernel(const float *__rest
     // depend on nothing, are requested first and wait in registers (rows w, w + 4, ... of the slice per wavefront).
     constexpr int DI = 4;               // d_h <= 256
     constexpr int RPW = kProjRows / 4;  // rows per wavefront
+    constexpr int E = Piece<T>::E;
     const T *Bg = B_v + (((size_t)b * G + layer) * r_v + c0) * d + (size_t)g * d_h;
-    T xraw[RPW][DI];
+    T xraw[WIDE ? 1 : RPW][DI];
+    ab_u32x4_t xwide[WIDE ? RPW : 1];
+    // WIDE: wavefront w takes rows 16 w .. 16 w + 15, request u covers rows 16 w + u rpl + sub
+    const int lpr = d_h / E, rpl = 64 / lpr;
+    const int sub = lane / lpr, pc = lane - sub * lpr;
+    const int n_req = RPW / rpl > 0 ? RPW / rpl : 1;
+    if constexpr (WIDE) {
 #pragma unroll
-    for (int u = 0; u < RPW; ++u) {
-        const int c = w + 4 * u;
-        const T *brow = Bg + (size_t)(c < cn ? c : 0) * d;
+        for (int u = 0; u < RPW; ++u) {
+            const int c = RPW * w + u * rpl + sub;
+            if (u < n_req)
+                xwide[u] = *reinterpret_cast<const ab_u32x4_t *>(Bg + (size_t)(c < cn ? c : 0) * d + pc * E);
+        }
+    } else {
 #pragma unroll
-        for (int i = 0; i < DI; ++i) {
-            const int col = lane + 64 * i;
-            xraw[u][i] = col < d_h ? brow[col] : T(0);
+        for (int u = 0; u < RPW; ++u) {
+            const int c = w + 4 * u;
+            const T *brow = Bg + (size_t)(c < cn ? c : 0) * d;
+#pragma unroll
+            for (int i = 0; i < DI; ++i) {
+                const int col = lane + 64 * i;
+                xraw[u][i] = col < d_h ? brow[col] : T(0);
+            }
         }
     }
     for (int i = tid; i < splits * 2 * NRP; i += 256) ml[i] = part_ml[(size_t)row * splits * 2 * NRP + i];
@@ -321,6 +341,40 @@ __global__ __launch_bounds__(256) void absorb_project_kernel(const float *__rest
         U[i] = u;
     }
     __syncthreads();
+    if constexpr (WIDE) {
+        float accw[NRP][E];
+#pragma unroll
+        for (int hh = 0; hh < NRP; ++hh)
+#pragma unroll
+            for (int e = 0; e < E; ++e) accw[hh][e] = 0.0f;
+#pragma unroll
+        for (int u = 0; u < RPW; ++u) {
+            const int c = RPW * w + u * rpl + sub;
+            if (u < n_req && c < cn) {
+                float x[E];
+                Piece<T>::unpack(xwide[u], x);
+#pragma unroll
+                for (int hh = 0; hh < NRP; ++hh) {
+                    const float uv = U[hh * kProjRows + c];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) accw[hh][e] = fmaf(uv, x[e], accw[hh][e]);
+                }
+            }
+        }
+        // the rows of a request sit lpr lanes apart: fold them onto the first lpr lanes, always in the same order
+        for (int off = lpr; off < 64; off <<= 1) {
+#pragma unroll
+            for (int hh = 0; hh < NRP; ++hh)
+#pragma unroll
+                for (int e = 0; e < E; ++e) accw[hh][e] += __shfl_xor(accw[hh][e], off, kWave);
+        }
+        if (sub == 0) {
+#pragma unroll
+            for (int hh = 0; hh < NRP; ++hh)
+#pragma unroll
+                for (int e = 0; e < E; ++e) red[((size_t)w * NRP + hh) * d_h + pc * E + e] = accw[hh][e];
+        }
+    } else {
     float acc[NRP][DI];
 #pragma unroll
     for (int hh = 0; hh < NRP; ++hh)
@@ -345,6 +399,7 @@ __global__ __launch_bounds__(256) void absorb_project_kernel(const float *__rest
             const int col = lane + 64 * i;
             if (col < d_h) red[((size_t)w * NRP + hh) * d_h + col] = acc[hh][i];
         }
+    }
     __syncthreads();
     for (int i = tid; i < n_rep * d_h; i += 256) {
         const int hh = i / d_h, col = i % d_h;
@@ -417,7 +472,10 @@ static hipError_t launch_absorbed_t(const xkv_shape &s, const AbsorbPlan &a, int
         hipError_t e = hipFuncSetAttribute((const void *)absorb_rows_kernel<T, NRP, Q4>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)absorb_project_kernel<T, NRP>,
+            e = hipFuncSetAttribute((const void *)absorb_project_kernel<T, NRP, false>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)absorb_project_kernel<T, NRP, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
         if (e != hipSuccess) return e;
         attr = true;
@@ -429,8 +487,15 @@ static hipError_t launch_absorbed_t(const xkv_shape &s, const AbsorbPlan &a, int
     profile_end(4, st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((absorb_project_kernel<T, NRP>), dim3(a.slices, s.H_kv, s.batch), dim3(256), lds_comb, st, part_u,
-                       part_ml, B_v, po, pml, s.G, layer, s.r_v, s.H_kv, s.H_q, s.d_h, a.splits);
+    // rows of B^V 16 bytes per lane when a row of the head is a power-of-two number (4..64) of aligned pieces
+    const int lpr = s.d_h % E == 0 ? s.d_h / E : 0;
+    const bool wide = lpr >= 4 && lpr <= 64 && (lpr & (lpr - 1)) == 0 && (((uintptr_t)B_v) & 15u) == 0;
+    if (wide)
+        hipLaunchKernelGGL((absorb_project_kernel<T, NRP, true>), dim3(a.slices, s.H_kv, s.batch), dim3(256), lds_comb, st,
+                           part_u, part_ml, B_v, po, pml, s.G, layer, s.r_v, s.H_kv, s.H_q, s.d_h, a.splits);
+    else
+        hipLaunchKernelGGL((absorb_project_kernel<T, NRP, false>), dim3(a.slices, s.H_kv, s.batch), dim3(256), lds_comb, st,
+                           part_u, part_ml, B_v, po, pml, s.G, layer, s.r_v, s.H_kv, s.H_q, s.d_h, a.splits);
     return hipGetLastError();
 }
 
