@@ -165,12 +165,17 @@ __global__ __launch_bounds__(256) void prepass_kernel(ProjArgs pj, PackArgs pk, 
     }
 }
 
-template <int N_REP>
+// Heads per KV head rounded up to a power of two: the row length of the per-head score array.
+constexpr int head_pitch(int n_rep) { return n_rep <= 1 ? 1 : n_rep <= 2 ? 2 : n_rep <= 4 ? 4 : n_rep <= 8 ? 8 : 16; }
+
+// HEADS: also write every query head's score, S_heads [batch][H_kv][L][head_pitch(N_REP)] (padding zero); the
+// pooled score is the maximum of exactly those values.
+template <int N_REP, bool HEADS>
 __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restrict__ A_k,    // [batch][L][r_k]
                                                          const bf16_t *__restrict__ Pfrag,  // see above
                                                          float *__restrict__ S,             // [batch][H_kv][L]
                                                          int L, int r_k, int H_kv, int F8, int tiles_per_wg,
-                                                         float scale)
+                                                         float scale, float *__restrict__ S_heads)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4_t *Pl = reinterpret_cast<u32x4_t *>(smem);  // [2][F8][64] fragments of 16 B per lane
@@ -237,11 +242,36 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(const bf16_t *__restric
             if (t < L) {
 #pragma unroll
                 for (int u = 0; u < GPH; ++u) {
-                    float best = acc_h[u * N_REP] + acc_l[u * N_REP];
-#pragma unroll
-                    for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
                     const int g = blk * 2 * GPH + hf * GPH + u;
-                    if (g < H_kv) __builtin_nontemporal_store(scale * best, &S[((size_t)b * H_kv + g) * L + t]);
+                    if constexpr (HEADS) {
+                        constexpr int NRP = head_pitch(N_REP);
+                        float hv[16];
+#pragma unroll
+                        for (int hh = 0; hh < 16; ++hh)
+                            hv[hh] = hh < N_REP ? scale * (acc_h[(u * N_REP + hh) & 15] + acc_l[(u * N_REP + hh) & 15]) : 0.0f;
+                        float best = hv[0];
+#pragma unroll
+                        for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, hv[hh]);
+                        if (g < H_kv) {
+                            S[((size_t)b * H_kv + g) * L + t] = best;
+                            float *dst = S_heads + (((size_t)b * H_kv + g) * L + t) * NRP;
+                            if constexpr (NRP >= 4) {
+#pragma unroll
+                                for (int c = 0; c < NRP / 4; ++c)
+                                    *reinterpret_cast<float4 *>(dst + 4 * c) =
+                                        make_float4(hv[4 * c], hv[4 * c + 1], hv[4 * c + 2], hv[4 * c + 3]);
+                            } else {
+#pragma unroll
+                                for (int hh = 0; hh < NRP; ++hh) dst[hh] = hv[hh];
+                            }
+                        }
+                    } else {
+                        float best = acc_h[u * N_REP] + acc_l[u * N_REP];
+#pragma unroll
+                        for (int hh = 1; hh < N_REP; ++hh)
+                            best = fmaxf(best, acc_h[u * N_REP + hh] + acc_l[u * N_REP + hh]);
+                        if (g < H_kv) __builtin_nontemporal_store(scale * best, &S[((size_t)b * H_kv + g) * L + t]);
+                    }
                 }
             }
 #pragma unroll
@@ -286,9 +316,6 @@ __device__ __forceinline__ void score_group(f32x16_t &acc_h, f32x16_t &acc_l, u3
         __builtin_amdgcn_sched_barrier(0);
     }
 }
-
-// Heads per KV head rounded up to a power of two: the row length of the per-head score array.
-constexpr int head_pitch(int n_rep) { return n_rep <= 1 ? 1 : n_rep <= 2 ? 2 : n_rep <= 4 ? 4 : n_rep <= 8 ? 8 : 16; }
 
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -1059,15 +1086,22 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
     tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP>,
+        hipError_t e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP, false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP, true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
     profile_begin(0, st);
-    hipLaunchKernelGGL(score_mfma_kernel<N_REP>, grid, block, lds, st, A_k, Pfrag, S, s.L, s.r_k, s.H_kv, F8,
-                       tiles_per_wg, p.scale);
+    if (S_heads)
+        hipLaunchKernelGGL((score_mfma_kernel<N_REP, true>), grid, block, lds, st, A_k, Pfrag, S, s.L, s.r_k, s.H_kv, F8,
+                           tiles_per_wg, p.scale, S_heads);
+    else
+        hipLaunchKernelGGL((score_mfma_kernel<N_REP, false>), grid, block, lds, st, A_k, Pfrag, S, s.L, s.r_k, s.H_kv, F8,
+                           tiles_per_wg, p.scale, (float *)nullptr);
     profile_end(0, st);
     return hipGetLastError();
 }
@@ -1079,9 +1113,9 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
 {
     if (hist_done) *hist_done = false;
     if (packed_done) *packed_done = false;
-    // per-head scores come from the long-stream kernel or from the general one
+    // per-head scores come from either matrix-core kernel, or from the general one
     const bool mfma = score_mfma_ok(s, A_k) && ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) == 0 &&
-                      (!S_heads || (p.score_stream && (((uintptr_t)S_heads) & 15u) == 0));
+                      (!S_heads || (((uintptr_t)S_heads) & 15u) == 0);
     if (!mfma) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, S_heads, st);
     const int n_rep = s.H_q / s.H_kv;
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;

@@ -25,7 +25,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def run_point(L, batch, r, kfrac, steps, timeout_s):
     k = max(1, int(round(L * kfrac)))
     cmd = [sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "llama_full", "--L", str(L), "--batch",
-           str(batch), "--r", str(r), "--k", str(k), "--no-cpu", "--steps", str(steps), "--warmup", "1"]
+           str(batch), "--r", str(r), "--k", str(k), "--no-cpu", "--no-factorize", "--no-landmark", "--no-graph",
+           "--steps", str(steps), "--warmup", "1"]
     t0 = time.perf_counter()
     try:
         res = subprocess.run(cmd, capture_output=True, text=True, timeout=timeout_s)
@@ -42,26 +43,33 @@ def run_point(L, batch, r, kfrac, steps, timeout_s):
                dense_ms=dense.get("ms_per_step"), dense_GBps=dense.get("GBps"), dense_note=dense.get("note"),
                speedup=d.get("speedup_vs_dense"), score_GBps=d["stages"]["score"].get("kernel_GBps"),
                gather_GBps=d["stages"]["gather_attend"].get("kernel_GBps"),
-               topk_ms=d["stages"]["topk"]["ms_per_layer"])
+               topk_ms=d["stages"]["topk"]["ms_per_layer"],
+               absorbed_tokens_per_s=(d.get("absorbed") or {}).get("tokens_per_s"),
+               q4_tokens_per_s=(d.get("quantized") or {}).get("tokens_per_s"))
     return rec
 
 
 def table(records):
-    out = ["| L | batch | r | k | SR tok/s | dense tok/s | SR/dense | score TB/s | gather TB/s | dense TB/s |",
-           "|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|"]
+    out = ["| L | batch | r | k | SR tok/s | dense tok/s | SR/dense | score TB/s | gather TB/s | dense TB/s | "
+           "absorbed tok/s | 4-bit absorbed tok/s |",
+           "|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|---:|"]
 
     def tb(x):
         return "-" if x is None else f"{x / 1000:.2f}"
 
+    def tk(x):   # the two absorbed forms are extras of bench.py; records made before they existed have none
+        return "-" if x is None else f"{x:.0f}"
+
     for r in records:
         if "error" in r:
-            out.append(f"| {r['L']} | {r['batch']} | {r['r']} | {r['k']} | {r['error']} | | | | | |")
+            out.append(f"| {r['L']} | {r['batch']} | {r['r']} | {r['k']} | {r['error']} | | | | | | | |")
             continue
         dn = "" if not r.get("dense_note") or r["dense_note"].startswith("all") else "*"
         dense_tok = "-" if r["dense_tokens_per_s"] is None else f"{r['dense_tokens_per_s']:.0f}{dn}"
         out.append(f"| {r['L']} | {r['batch']} | {r['r']} | {r['k']} | {r['sr_tokens_per_s']:.0f} | "
                    f"{dense_tok} | {r['speedup'] if r['speedup'] is not None else '-'} | "
-                   f"{tb(r['score_GBps'])} | {tb(r['gather_GBps'])} | {tb(r['dense_GBps'])} |")
+                   f"{tb(r['score_GBps'])} | {tb(r['gather_GBps'])} | {tb(r['dense_GBps'])} | "
+                   f"{tk(r.get('absorbed_tokens_per_s'))} | {tk(r.get('q4_tokens_per_s'))} |")
     return "\n".join(out)
 
 
