@@ -856,6 +856,13 @@ __global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const 
     for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
     const f32x16_t zero = tot;
     const unsigned char *my_row = tile_lds + n * tpitch;
+    constexpr int kQ4Burst = 4;
+    float res[kQ4Burst][16];
+#pragma unroll
+    for (int i = 0; i < kQ4Burst; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) res[i][v] = 0.0f;
+    int ti = 0, tile0 = tile;  // tiles held in res, first of them
     while (true) {
 #pragma unroll
         for (int i = 0; i < kQ4MaxLoads; ++i)
@@ -915,35 +922,50 @@ __global__ __launch_bounds__(kQ4TileWaves * 64) void score_q4_tile_kernel(const 
 #pragma unroll
             for (int v = 0; v < 16; ++v) tot[v] = fmaf(step, acc[v], tot[v]);
         }
-        const int t = tile * 32 + n;
-        if (t < L) {
+        // results wait in registers and are written in bursts of kQ4Burst tiles (as in the bf16 stream kernel:
+        // stores dribbled out between the reads cost the memory system more than their bytes)
 #pragma unroll
-            for (int u = 0; u < GPH; ++u) {
-                const int g = blk * 2 * GPH + hf * GPH + u;
-                if (g < H_kv) {
-                    float hv[16];
+        for (int i = 0; i < kQ4Burst; ++i)
 #pragma unroll
-                    for (int hh = 0; hh < 16; ++hh) hv[hh] = hh < N_REP ? scale * tot[(u * N_REP + hh) & 15] : 0.0f;
-                    float best = hv[0];
+            for (int v = 0; v < 16; ++v) res[i][v] = (i == ti) ? scale * tot[v] : res[i][v];
+        ++ti;
 #pragma unroll
-                    for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, hv[hh]);
-                    S[((size_t)b * H_kv + g) * L + t] = best;
-                    float *dst = S_heads + (((size_t)b * H_kv + g) * L + t) * NRP;
-                    if constexpr (NRP >= 4) {
+        for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
+        const bool done = tile_n >= tile_end;
+        if (ti == kQ4Burst || done) {
 #pragma unroll
-                        for (int c = 0; c < NRP / 4; ++c)
-                            *reinterpret_cast<float4 *>(dst + 4 * c) =
-                                make_float4(hv[4 * c], hv[4 * c + 1], hv[4 * c + 2], hv[4 * c + 3]);
-                    } else {
+            for (int i = 0; i < kQ4Burst; ++i) {
+                const int t = (tile0 + i * WAVES) * 32 + n;
+                if (i < ti && t < L) {
 #pragma unroll
-                        for (int hh = 0; hh < NRP; ++hh) dst[hh] = hv[hh];
+                    for (int u = 0; u < GPH; ++u) {
+                        const int g = blk * 2 * GPH + hf * GPH + u;
+                        if (g < H_kv) {
+                            float hv[16];
+#pragma unroll
+                            for (int hh = 0; hh < 16; ++hh) hv[hh] = hh < N_REP ? res[i][(u * N_REP + hh) & 15] : 0.0f;
+                            float best = hv[0];
+#pragma unroll
+                            for (int hh = 1; hh < N_REP; ++hh) best = fmaxf(best, hv[hh]);
+                            S[((size_t)b * H_kv + g) * L + t] = best;
+                            float *dst = S_heads + (((size_t)b * H_kv + g) * L + t) * NRP;
+                            if constexpr (NRP >= 4) {
+#pragma unroll
+                                for (int c = 0; c < NRP / 4; ++c)
+                                    *reinterpret_cast<float4 *>(dst + 4 * c) =
+                                        make_float4(hv[4 * c], hv[4 * c + 1], hv[4 * c + 2], hv[4 * c + 3]);
+                            } else {
+#pragma unroll
+                                for (int hh = 0; hh < NRP; ++hh) dst[hh] = hv[hh];
+                            }
+                        }
                     }
                 }
             }
+            tile0 += ti * WAVES;
+            ti = 0;
         }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) tot[v] = 0.0f;
-        if (tile_n >= tile_end) break;
+        if (done) break;
         tile = tile_n;
     }
 #undef XKV_Q4_REQUEST
