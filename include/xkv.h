@@ -195,7 +195,8 @@ XKV_API xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer_
 /*
  * xkv_gather_attend with two options (stages 3-4 of the step on their own):
  *   counts (nullable) [batch][H_kv]: only the first counts[..] of the k ids of a row are attended over (row lists of
- *     different lengths, as the landmark selector produces them; the other ids must still lie in [0, L));
+ *     different lengths, as the landmark selector produces them; the other ids must still lie in [0, L)); a KV head
+ *     whose count is 0 attends over nothing and its query heads' outputs are written as zeros;
  *   rope_theta > 0: the cache was factorized before the rotary position embedding (Sec. 4 "Implementation details",
  *     App. C.6 "Setup"), so every reconstructed key row is rotated to its position, which is its row number t, before
  *     it meets the (already rotated) query: channel j < d_h/2 is paired with channel j + d_h/2 (Llama / Qwen2
@@ -208,13 +209,14 @@ XKV_API xkv_status xkv_gather_attend_ex(const xkv_shape *shape, int32_t layer_in
                                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * The SR step in the absorbed form (Sec. 3.3, Fig. 1: B_l is multiplied into the query and into the output once,
- * instead of into every selected token).  Stages 1-2 are unchanged -- same scores, same index sets as
+ * The SR step in the absorbed form.  Not in the paper: it is this library's re-association of Eq. 3,
+ * (A[S] B_l) q = A[S] (B_l q) for the logits and w^T (A^V[S] B^V_l) = (w^T A^V[S]) B^V_l for the output, so that B_l is
+ * multiplied into the query and into the output once instead of into every selected token.  Stages 1-2 are unchanged -- same scores, same index sets as
  * xkv_sr_decode -- but the score kernel also keeps every query head's score; stages 3-4 then become
  *     w_h = softmax_j( s_h[I_j] ),      o_h = ( sum_j w_hj A^V[I_j, :] ) B^V_g,
  * which equals softmax(q_h K^_g^T / sqrt(d_h)) V^_g with K^ = A^K[I] B^K, V^ = A^V[I] B^V up to rounding order
- * (K^ and V^ are never rounded to the storage type here).  Only valid where the reconstructed keys need no
- * per-token treatment (no rotary embedding after reconstruction).  xkv_sr_decode remains the named
+ * (K^ and V^ are never rounded to the storage type here).  Only valid where nothing is applied to the reconstructed
+ * rows -- not with the rotary embedding of Sec. 4 "Implementation details" applied after reconstruction.  xkv_sr_decode remains the named
  * gather-reconstruct path; this is an additional one.
  *   xkv_head_scores: stage 1 + 2a; heads_out [batch][H_kv][L][nrp] fp32 (device, 16-byte aligned), nrp = H_q/H_kv
  *     rounded up to a power of two, padding written as 0; score_out (nullable) [batch][H_kv][L] is the pooled
@@ -279,7 +281,8 @@ XKV_API xkv_status xkv_sr_decode_absorbed_q4(const xkv_shape *shape, int32_t lay
  * sequences of a chunk in one launch) or 4 (the row-sum kernel of xkv_attend_absorbed), every later call that launches that kernel records
  * start_event on the call's stream right before the launch and stop_event right after it.  Both are
  * hipEvent_t created by the caller with timing enabled (HOST handles, passed as void*); NULL for
- * either switches the recording off.  Process-wide state; not thread safe. */
+ * either switches the recording off.  The setting belongs to the calling host thread: only that thread's later calls
+ * record, other threads are not affected. */
 XKV_API xkv_status xkv_profile_kernel(int32_t stage, void *start_event, void *stop_event);
 
 /* Human-readable name of a status code (static storage). */

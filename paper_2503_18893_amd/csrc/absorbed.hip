@@ -1,6 +1,7 @@
-// Attention over the selected tokens without rebuilding their key and value rows (the absorbed form of the
-// paper's selective reconstruction, Sec. 3.3 / Fig. 1: the per-layer factor B is folded into the query and into
-// the output instead of into every token).
+// Attention over the selected tokens without rebuilding their key and value rows: the absorbed form of the
+// paper's selective reconstruction.  The paper does not describe it; it is a re-association of Eq. 3,
+// (A[S] B_l) q = A[S] (B_l q) and w^T (A^V[S] B^V_l) = (w^T A^V[S]) B^V_l: the per-layer factor B is folded into the
+// query and into the output instead of into every token.
 //
 //   logits  : the selected tokens' per-head scores  scale * (A^K[t] . B^K_g q_h)  were already computed by the
 //             score stage for every token, so they are gathered, not recomputed;
@@ -467,19 +468,12 @@ static hipError_t launch_absorbed_t(const xkv_shape &s, const AbsorbPlan &a, int
     const size_t lds_comb = ((size_t)a.splits * 3 * NRP + 2 * NRP + NRP * kProjRows + (size_t)4 * NRP * s.d_h) * 4;
     const size_t lds_max = 160 * 1024 - 512;
     if (lds_rows > lds_max || lds_comb > lds_max) return hipErrorInvalidValue;
-    static bool attr = false;
-    if (!attr) {
-        hipError_t e = hipFuncSetAttribute((const void *)absorb_rows_kernel<T, NRP, Q4>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)absorb_project_kernel<T, NRP, false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)absorb_project_kernel<T, NRP, true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
-        if (e != hipSuccess) return e;
-        attr = true;
-    }
+    static DynamicLdsOnce attr_rows, attr_proj, attr_proj_wide;
+    if (hipError_t e0 = attr_rows.ensure((const void *)absorb_rows_kernel<T, NRP, Q4>, lds_max); e0 != hipSuccess) return e0;
+    if (hipError_t e0 = attr_proj.ensure((const void *)absorb_project_kernel<T, NRP, false>, lds_max); e0 != hipSuccess)
+        return e0;
+    if (hipError_t e0 = attr_proj_wide.ensure((const void *)absorb_project_kernel<T, NRP, true>, lds_max); e0 != hipSuccess)
+        return e0;
     profile_begin(4, st);
     hipLaunchKernelGGL((absorb_rows_kernel<T, NRP, Q4>), dim3(a.splits, a.col_blocks, s.batch * s.H_kv),
                        dim3(kAbsorbWaves * 64), lds_rows, st, A_v, S_heads, idx, part_u, part_ml, s.L, s.r_v, s.H_kv,

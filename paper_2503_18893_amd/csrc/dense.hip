@@ -122,7 +122,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
             num = fmaf(wgt, part_o2[(base2 + s) * d_h + j], num);
             den = fmaf(wgt, part_ml2[(base2 + s) * 2 + 1], den);
         }
-        out[((size_t)b * H_q + h) * d_h + j] = from_f32<T>(num / den);
+        // a head with no token at all (every list empty, no tail) has den == 0: its output is defined as zero
+        out[((size_t)b * H_q + h) * d_h + j] = from_f32<T>(den > 0.0f ? num / den : 0.0f);
     }
 }
 

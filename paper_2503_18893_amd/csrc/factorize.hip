@@ -34,7 +34,7 @@ typedef __attribute__((address_space(3))) void fz_lds_void_t;
 
 __device__ __forceinline__ void fz_copy16_global_to_lds(const void *gptr, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
 }
 // s_waitcnt bounding only the number of outstanding vector-memory operations (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 #define FZ_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (0xF << 8) | (((n) >> 4) << 14))
@@ -763,12 +763,8 @@ FzLayout fz_layout(const xkv_shape &s, int r)
 
 template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, int nseq, hipStream_t st)
 {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_nt_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e0 = attr.ensure((const void *)gemm_nt_kernel<T>, kGemmLds); e0 != hipSuccess) return e0;
     GemmArgs b = a;
     b.tiles = tiles;
     const int per_die = (tiles * a.splits + 7) / 8;
@@ -790,12 +786,8 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
     double *Gm = reinterpret_cast<double *>(ws + f.off_g), *Lt = reinterpret_cast<double *>(ws + f.off_lt);
     double *planes = reinterpret_cast<double *>(ws + f.off_planes), *diag0 = reinterpret_cast<double *>(ws + f.off_diag);
     double *Minv = reinterpret_cast<double *>(ws + f.off_minv);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)chol_panel_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e0 = attr.ensure((const void *)chol_panel_kernel, 160 * 1024 - 256); e0 != hipSuccess) return e0;
     hipError_t e = hipSuccess;
     const long long vcount = (long long)r * n, x_seq = (long long)n * s.L;
     for (int b0 = 0; b0 < s.batch && e == hipSuccess; b0 += f.bc) {

@@ -56,7 +56,7 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 // compiler's own waits for register loads more conservative, never less.
 __device__ __forceinline__ void copy16_global_to_lds(const void *gptr, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
 }
 
 // s_waitcnt that only bounds the number of outstanding vector-memory operations (gfx9 encoding: vmcnt is
@@ -470,14 +470,10 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
     do {                                                                                                           \
         /* B, A tiles, Q, (rotation constants,) token ids */                                                      \
         const size_t lds = kLdsB + lds_a_bytes(WV) + kLdsQ + (RP ? 512 : 0) + (size_t)p.sr_chunk * 4;              \
-        static bool attr_set = false;                                                                              \
-        if (!attr_set) {                                                                                           \
-            e = hipFuncSetAttribute((const void *)gather_attend_mfma_kernel<WV, RP>,                               \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,                                    \
-                                    kLdsB + lds_a_bytes(WV) + kLdsQ + 512 + kMaxChunkTokens * 4);                  \
-            if (e != hipSuccess) return e;                                                                         \
-            attr_set = true;                                                                                       \
-        }                                                                                                          \
+        static DynamicLdsOnce attr;                                                                                \
+        e = attr.ensure((const void *)gather_attend_mfma_kernel<WV, RP>,                                           \
+                        kLdsB + lds_a_bytes(WV) + kLdsQ + 512 + kMaxChunkTokens * 4);                              \
+        if (e != hipSuccess) return e;                                                                             \
         profile_begin(1, st);                                                                                      \
         hipLaunchKernelGGL((gather_attend_mfma_kernel<WV, RP>), grid, dim3(WV * 64), lds, st, (const bf16_t *)A_k, \
                            (const bf16_t *)A_v, (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, counts, part_o,  \

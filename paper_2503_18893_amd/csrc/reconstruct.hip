@@ -285,13 +285,8 @@ hipError_t launch_reconstruct(const xkv_shape &s, int layer, const void *A, cons
                               hipStream_t st)
 {
     if (reconstruct_mfma_ok(s, r, A, B, X)) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void *)reconstruct_mfma_kernel,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kRcLdsB + kRcLdsA);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        static DynamicLdsOnce attr;
+        if (hipError_t e0 = attr.ensure((const void *)reconstruct_mfma_kernel, kRcLdsB + kRcLdsA); e0 != hipSuccess) return e0;
         // about two workgroups per compute unit over the launch (one resident at a time)
         const int n_tiles = (s.L + 255) / 256, rows = s.batch * s.H_kv;
         int chunks = rows >= 512 ? 1 : (512 + rows - 1) / rows;

@@ -1056,13 +1056,9 @@ static hipError_t launch_score_stream_t(const xkv_shape &s, const Plan &p, const
                                         float *S, int F8, dim3 sgrid, size_t lds_stream, uint32_t *row_hist,
                                         uint32_t *chunk_hist, float *S_heads, hipStream_t st)
 {
-    static bool attr = false;
-    if (!attr) {
-        hipError_t e = hipFuncSetAttribute((const void *)score_stream_kernel<N_REP, WAVES, HEADS>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-        if (e != hipSuccess) return e;
-        attr = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e0 = attr.ensure((const void *)score_stream_kernel<N_REP, WAVES, HEADS>, 160 * 1024 - 512); e0 != hipSuccess)
+        return e0;
     profile_begin(0, st);
     hipLaunchKernelGGL((score_stream_kernel<N_REP, WAVES, HEADS>), sgrid, dim3(WAVES * 64), lds_stream, st, A_k, Pfrag, S,
                        s.L, s.r_k, s.H_kv, F8, p.score_tpw, p.scale, row_hist, chunk_hist, S_heads);
@@ -1106,16 +1102,11 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
     int tiles_per_wg = (n_tiles + wgs_per_pair - 1) / wgs_per_pair;
     tiles_per_wg = tiles_per_wg < 4 ? 4 : tiles_per_wg;
     tiles_per_wg = (tiles_per_wg + 3) / 4 * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP, false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)score_mfma_kernel<N_REP, true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static DynamicLdsOnce attr_pooled, attr_heads;
+    if (hipError_t e0 = attr_pooled.ensure((const void *)score_mfma_kernel<N_REP, false>, 160 * 1024 - 512); e0 != hipSuccess)
+        return e0;
+    if (hipError_t e0 = attr_heads.ensure((const void *)score_mfma_kernel<N_REP, true>, 160 * 1024 - 512); e0 != hipSuccess)
+        return e0;
     dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch), block(256);
     profile_begin(0, st);
     if (S_heads)
@@ -1205,25 +1196,17 @@ static hipError_t launch_score_q4_t(const xkv_shape &s, const Plan &p, const uns
     dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, nblk, s.batch);
     hipError_t e = hipSuccess;
     if (tiled) {
-        static bool attr8 = false;
-        if (!attr8) {
-            e = hipFuncSetAttribute((const void *)score_q4_tile_kernel<N_REP>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    160 * 1024 - 512);
-            if (e != hipSuccess) return e;
-            attr8 = true;
-        }
+        static DynamicLdsOnce attr8;
+        e = attr8.ensure((const void *)score_q4_tile_kernel<N_REP>, 160 * 1024 - 512);
+        if (e != hipSuccess) return e;
         profile_begin(0, st);
         hipLaunchKernelGGL((score_q4_tile_kernel<N_REP>), grid, dim3(kQ4TileWaves * 64), lds_tile, st, Aq, Pfrag, S, S_heads,
                            s.L, s.r_k, s.H_kv, F8, tiles_per_wg, p.scale);
         profile_end(0, st);
     } else {
-        static bool attr4 = false;
-        if (!attr4) {
-            e = hipFuncSetAttribute((const void *)score_q4_kernel<N_REP, 4, 16>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    160 * 1024 - 512);
-            if (e != hipSuccess) return e;
-            attr4 = true;
-        }
+        static DynamicLdsOnce attr4;
+        e = attr4.ensure((const void *)score_q4_kernel<N_REP, 4, 16>, 160 * 1024 - 512);
+        if (e != hipSuccess) return e;
         profile_begin(0, st);
         hipLaunchKernelGGL((score_q4_kernel<N_REP, 4, 16>), grid, dim3(256), lds, st, Aq, Pfrag, S, S_heads, s.L, s.r_k,
                            s.H_kv, F8, tiles_per_wg, p.scale);

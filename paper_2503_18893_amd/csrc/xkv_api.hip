@@ -7,7 +7,7 @@
 
 namespace xkv {
 
-ProfileEvents g_profile[5] = {};
+thread_local ProfileEvents g_profile[5] = {};
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "xkv.h"
 
 namespace xkv {
@@ -87,11 +89,12 @@ constexpr int kStateWords = 8;   // per row: (prefix, k_rem) for each resolved l
 xkv_status make_plan(const xkv_shape &s, Plan &p);
 
 // Optional event pair recorded around the main kernel of a stage (0 score, 1 gather-attend, 2 dense,
-// 3 Gram-matrix product of the factorization, 4 row sums of the absorbed attention).
+// 3 Gram-matrix product of the factorization, 4 row sums of the absorbed attention).  Kept per host thread: the
+// thread that asks for a measurement is the one whose calls are measured, and no other thread sees the pair.
 struct ProfileEvents {
     hipEvent_t start, stop;
 };
-extern ProfileEvents g_profile[5];
+extern thread_local ProfileEvents g_profile[5];
 inline void profile_begin(int stage, hipStream_t st)
 {
     if (g_profile[stage].start && g_profile[stage].stop) (void)hipEventRecord(g_profile[stage].start, st);
@@ -115,6 +118,23 @@ struct PackArgs {
     pack_u32x4_t *pack;
     int G, layer, r_k, r_v, H_kv, H_q, F8k, F8v, batch;
     int blocks_per_head;  // 256-item blocks per (sequence, KV head): B items, then 512 items for the Q^T fragments
+};
+
+// Raises a kernel's dynamic-LDS limit the first time the kernel is launched on each device.  One static instance
+// per kernel; safe for concurrent host threads (the attribute call is idempotent, the flag word is atomic).
+struct DynamicLdsOnce {
+    std::atomic<uint64_t> done{0};  // bit d: set on device d (devices 64 and up share bits: they repeat the call)
+    hipError_t ensure(const void *kernel, size_t bytes)
+    {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const uint64_t bit = 1ull << (dev & 63);
+        if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+        return e;
+    }
 };
 
 // Kernel launchers (each enqueues on `st`; shapes were validated by the caller).
