@@ -102,6 +102,22 @@ XKV_API xkv_status xkv_sr_decode_tail(const xkv_shape *shape, int32_t layer_in_g
                                       size_t workspace_bytes, void *hip_stream);
 
 /*
+ * xkv_sr_decode for callers that cannot allocate device memory or keep a workspace of their own: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit for bit the same
+ * results as xkv_sr_decode, but the scratch is an array of XKV_STATIC_SCRATCH_BYTES bytes that is part of the library's
+ * code object (each GPU the library runs on holds its own copy until the process ends); the call allocates and frees
+ * nothing.  The first call on a device looks the array's address up once (hipGetSymbolAddress).
+ * XKV_ERR_WORKSPACE when xkv_workspace_bytes(shape) exceeds XKV_STATIC_SCRATCH_BYTES (nothing is launched): use
+ * xkv_sr_decode with a workspace of the caller's then.  All calls on one GPU share the array: calls that may overlap
+ * on one GPU (different streams, or different host threads) race and must be serialised by the caller; consecutive
+ * calls on one stream are fine.  Nothing in the array is carried from one call to the next.
+ */
+#define XKV_STATIC_SCRATCH_BYTES (40u << 20)
+XKV_API xkv_status xkv_sr_decode_static(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                        const void *A_v, const void *B_k, const void *B_v, const void *q, void *out,
+                                        int32_t *idx_out, float *score_out, void *hip_stream);
+
+/*
  * Dense decode attention on an uncompressed cache, the speedup baseline (Sec. 5, "Full
  * Attention"): out_h = softmax(scale * K_{rho(h)} q_h)^T V_{rho(h)} over all L tokens.
  * K, V: [batch][H_kv][L][d_h].  shape->r_k, r_v, k, G are ignored.

@@ -2,6 +2,7 @@
 // Every step of the path runs in the HIP kernels of this library; nothing here computes.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "xkv_common.h"
 
@@ -245,6 +246,53 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
 {
     return sr_decode_impl(shape, layer, A_k, A_v, B_k, B_v, q, nullptr, nullptr, 0, out, idx_out, score_out, workspace,
                           workspace_bytes, hip_stream);
+}
+
+}  // extern "C"
+
+// Scratch of xkv_sr_decode_static: one array per GPU, part of the loaded code object, never allocated or freed.
+// Host code must not use the array's name as an address (on the host it is only a handle for the symbol lookup);
+// static_scratch() resolves it once per device to that device's copy.
+static __device__ __align__(256) unsigned char scratch[XKV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+xkv_status static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return XKV_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return XKV_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return XKV_OK;
+}
+}  // namespace
+
+extern "C" {
+
+xkv_status xkv_sr_decode_static(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v, const void *B_k,
+                                const void *B_v, const void *q, void *out, int32_t *idx_out, float *score_out,
+                                void *hip_stream)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    Plan p;
+    make_plan(*shape, p);
+    if (p.total > (size_t)XKV_STATIC_SCRATCH_BYTES) return XKV_ERR_WORKSPACE;  // shape too large for the built-in scratch
+    void *ws = nullptr;
+    if ((st = static_scratch(&ws)) != XKV_OK) return st;
+    // Every array the step keeps in the scratch is written by the step's own kernels before it is read (the row
+    // histograms of the long-row selection are cleared by the launch that precedes the score kernel), so the
+    // contents a previous call left behind need no clearing here.
+    return sr_decode_impl(shape, layer, A_k, A_v, B_k, B_v, q, nullptr, nullptr, 0, out, idx_out, score_out, ws,
+                          XKV_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 xkv_status xkv_sr_decode_tail(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
