@@ -256,14 +256,14 @@ def test_llama_group_full_size():
     print("llama_group_full", rep)
 
 
-def _full_size_sampled(w, seqs, seed):
+def _full_size_sampled(w, seqs, seed, scale=None, whole_rows=True):
     """One layer of a benchmark configuration at full size, in the launch configuration bench.py times (fused
-    xkv_sr_decode on device-generated factors), checked on samples the oracle computes one by one: pooled scores of
-    token ranges at the start, in the middle and at the end of every sampled sequence, the complete selection of
-    those sequences (against the oracle's selection on the GPU's own scores), and their attention outputs."""
+    xkv_sr_decode on device-generated factors), checked on the sampled sequences: every pooled score of the sequence
+    (whole_rows; else token ranges at the start, in the middle and at the end), the complete selection (against the
+    oracle's selection on the GPU's own scores), and the attention outputs."""
     torch = torch_mod()
     dev = synth.make_group_device(w, seed=seed)
-    shape = xb.Shape.of(w)
+    shape = xb.Shape.of(w, scale=0.0 if scale is None else scale)
     ws = xb.alloc_workspace(shape)
     layer = w.G - 1
     S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
@@ -272,16 +272,19 @@ def _full_size_sampled(w, seqs, seed):
     xb.xkv_sr_decode(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], dev["q"][layer].contiguous(), out,
                      idx, S, ws)
     torch.cuda.synchronize()
-    scale = oracle.default_scale(w.d_h)
+    scale = oracle.default_scale(w.d_h) if scale is None else scale
     mid = w.L // 2
-    ranges = [(0, 256), (mid - 128, mid + 128), (w.L - 256, w.L)]
+    ranges = [(0, w.L)] if whole_rows else [(0, 256), (mid - 128, mid + 128), (w.L - 256, w.L)]
+    report = {}
     for b in seqs:
         B_k = synth.to_host(dev["B_k"][b, layer])
         B_v = synth.to_host(dev["B_v"][b, layer])
         q = synth.to_host(dev["q"][layer, b])
+        err_s = 0.0
         for lo, hi in ranges:
             ref = oracle.pooled_scores(synth.to_host(dev["A_k"][b, lo:hi]), B_k, q, w.H_kv, scale)
-            assert max_rel(S[b, :, lo:hi].cpu().numpy(), ref) <= TOL[w.dtype], (b, lo)
+            err_s = max(err_s, max_rel(S[b, :, lo:hi].cpu().numpy(), ref))
+            assert err_s <= TOL[w.dtype], (b, lo, err_s)
         S_b, idx_b = S[b].cpu().numpy(), idx[b].cpu().numpy()
         for g in range(w.H_kv):
             np.testing.assert_array_equal(idx_b[g], oracle.select(S_b[g], w.k), err_msg=f"seq {b} head {g}")
@@ -289,16 +292,69 @@ def _full_size_sampled(w, seqs, seed):
                                        scale)
         err = max_rel(synth.storage_to_f64(synth.to_host(out[b])), ref_out)
         assert err <= TOL[w.dtype], (b, err)
+        report[b] = dict(score=err_s, attend=err)
+    return report
 
 
 def test_llama_full_size_sampled():
-    """Benchmark configuration 3 (batch 16, L = 65536, r = 512, k = 4096): first and last sequence."""
-    _full_size_sampled(synth.LLAMA_FULL, seqs=(0, synth.LLAMA_FULL.batch - 1), seed=31)
+    """Benchmark configuration 3 (batch 16, L = 65536, r = 512, k = 4096): first and last sequence, every token's
+    pooled score (the four-rank-group instantiation of the streaming score kernel that the benchmark times)."""
+    print(_full_size_sampled(synth.LLAMA_FULL, seqs=(0, synth.LLAMA_FULL.batch - 1), seed=31))
 
 
 def test_qwen_full_size_sampled():
-    """Benchmark configuration 4 (batch 4, L = 131072, r = 384, k = 4096, 7 query heads per KV head)."""
-    _full_size_sampled(synth.QWEN, seqs=(synth.QWEN.batch - 1,), seed=32)
+    """Benchmark configuration 4 (batch 4, L = 131072, r = 384, k = 4096, 7 query heads per KV head): two of the
+    four sequences, every token's pooled score."""
+    print(_full_size_sampled(synth.QWEN, seqs=(0, synth.QWEN.batch - 1), seed=32))
+
+
+def test_llama_full_size_peaked_softmax():
+    """Configuration 3's size and launch configuration with the logit scale raised 20000-fold: the workload's own
+    logits have a spread of 2e-4 (softmax nearly uniform), here it is about 4, so that a few dozen of the 4096
+    selected tokens carry the output and a mis-selected or mis-weighted token would show."""
+    w = synth.LLAMA_FULL
+    rep = _full_size_sampled(w, seqs=(w.batch - 1,), seed=33, scale=20000.0 / np.sqrt(w.d_h), whole_rows=False)
+    print("peaked full size", rep)
+
+
+# The sweep (benchmark configuration 5) publishes points at ranks 256, 512, 768, budgets from 1.5 % to 12.5 %, batches
+# up to 32 and contexts up to 131072; the corners that no other test reaches, each in the sweep's own launch
+# configuration (device-generated factors, fused call), on a sampled sequence.
+SWEEP_CORNERS = [
+    # rank 768: six rank groups per product in the gather-reconstruct kernel, the four-wavefront score stream
+    ("r768_L64k_b16_k6pct", synth.llama_sweep_point(65536, 16, 768, 0.0625), (15,)),
+    # the paper's own ranks at window 4, r_K : r_V = 1 : 1.5 (Sec. 4), on the bf16 gather-reconstruct path
+    ("r384_576_L64k_b16", synth.LLAMA_FULL.with_(r_k=384, r_v=576, a_scale=384 ** -0.5), (7,)),
+    # batch 32 x L = 131072: A holds more than 2^31 elements; the last sequence lies beyond that offset
+    ("r512_L128k_b32_k3pct", synth.llama_sweep_point(131072, 32, 512, 0.03), (31,)),
+    # smallest rank and budget, short context, single sequence (the four-wavefront gather kernel, short score kernel)
+    ("r256_L16k_b1_k1.5pct", synth.llama_sweep_point(16384, 1, 256, 0.015), (0,)),
+    # largest budget at rank 768 (the point where SR moves more bytes than dense attention)
+    ("r768_L32k_b4_k12pct", synth.llama_sweep_point(32768, 4, 768, 0.125), (3,)),
+]
+
+
+@pytest.mark.parametrize("name,w,seqs", SWEEP_CORNERS, ids=[c[0] for c in SWEEP_CORNERS])
+def test_sweep_corner_full_size_sampled(name, w, seqs):
+    rep = _full_size_sampled(w.with_(n_groups=1), seqs=seqs, seed=41, whole_rows=w.L <= 65536)
+    print(name, rep)
+
+
+GA_RANKS = [
+    ("r768_bf16", synth.LLAMA_GROUP.with_(L=9000, k=2100, r_k=768, r_v=768, batch=4, G=1, a_scale=768 ** -0.5)),
+    ("r384_576_bf16", synth.LLAMA_GROUP.with_(L=9000, k=2100, r_k=384, r_v=576, batch=4, G=1, a_scale=384 ** -0.5)),
+    ("r448_288_qwen_bf16", synth.QWEN.with_(L=7001, k=1111, r_k=448, r_v=288, batch=2, G=1, a_scale=448 ** -0.5)),
+]
+
+
+@pytest.mark.parametrize("name,w", GA_RANKS, ids=[n for n, _ in GA_RANKS])
+def test_large_and_unequal_ranks_chain(name, w):
+    """Every link of the chain, every sequence, on host-generated inputs at rank 768, at r_K : r_V = 1 : 1.5 and at
+    ranks that are not whole 128-rank groups (bf16 gather-reconstruct kernel with six rank groups, with different group
+    counts for K and V, with ragged last groups)."""
+    case = synth.make_case(w, seed=13)
+    rep = check_chain(w, case, layer=0)
+    print(name, rep)
 
 
 # ------------------------------------------------------------------------------ uncompressed tail of recent tokens
