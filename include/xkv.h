@@ -102,6 +102,28 @@ XKV_API xkv_status xkv_sr_decode_tail(const xkv_shape *shape, int32_t layer_in_g
                                       size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same step with the reconstruction matrices prepared once per prompt.  B_l does not change between decode steps
+ * (Sec. 3.2: the factors are computed at prefill and kept), but the matrix-core gather-reconstruct kernel reads
+ * B^K_{l,g} and B^V_{l,g} in its operand-fragment order, and xkv_sr_decode re-orders them on every call so that it can
+ * take the plain layout.  A serving loop re-orders once:
+ *   xkv_packed_b_bytes: size of the re-ordered copy of one group's B_k and B_v (all G layers, all sequences); about
+ *     the size of B_k and B_v themselves, ranks padded to multiples of 256.
+ *   xkv_pack_b: B_k [batch][G][r_k][d], B_v [batch][G][r_v][d] -> packed_out (device, 16-byte aligned, opaque:
+ *     [batch][G][H_kv] blocks of 16-rank operand fragments, keys then values, zero beyond the rank).
+ *   xkv_sr_decode_packed: xkv_sr_decode with B_v replaced by the packed copy; B_k is still read in its plain layout
+ *     by the query projection.  Same kernels otherwise, bit for bit the same results as xkv_sr_decode.
+ * XKV_ERR_UNSUPPORTED for shapes the matrix-core kernel does not take (dtype bf16, d_h = 128, ranks multiples of 16,
+ * all pointers 16-byte aligned): those callers use xkv_sr_decode.
+ */
+XKV_API xkv_status xkv_packed_b_bytes(const xkv_shape *shape, size_t *bytes);
+XKV_API xkv_status xkv_pack_b(const xkv_shape *shape, const void *B_k, const void *B_v, void *packed_out,
+                              void *hip_stream);
+XKV_API xkv_status xkv_sr_decode_packed(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                        const void *A_v, const void *B_k, const void *B_packed, const void *q,
+                                        void *out, int32_t *idx_out, float *score_out, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream);
+
+/*
  * xkv_sr_decode for callers that cannot allocate device memory or keep a workspace of their own: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit for bit the same
  * results as xkv_sr_decode, but the scratch is an array of XKV_STATIC_SCRATCH_BYTES bytes that is part of the library's

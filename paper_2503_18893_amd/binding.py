@@ -17,7 +17,8 @@ XKV_OK, XKV_ERR_INVALID_ARG, XKV_ERR_UNSUPPORTED, XKV_ERR_WORKSPACE, XKV_ERR_HIP
 XKV_F32, XKV_BF16 = 0, 1
 DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
 
-ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_static", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score",
+ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_static", "xkv_packed_b_bytes", "xkv_pack_b",
+                "xkv_sr_decode_packed", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score",
                 "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_factorize_workspace_bytes", "xkv_factorize",
                 "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_gather_attend_ex",
                 "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
@@ -80,6 +81,9 @@ def load() -> ctypes.CDLL:
         sp = ctypes.POINTER(xkv_shape)
         lib.xkv_workspace_bytes.argtypes = [sp, ctypes.POINTER(sz)]
         lib.xkv_sr_decode.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_packed_b_bytes.argtypes = [sp, ctypes.POINTER(sz)]
+        lib.xkv_pack_b.argtypes = [sp, vp, vp, vp, vp]
+        lib.xkv_sr_decode_packed.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_sr_decode_static.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.xkv_sr_decode_tail.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.xkv_dense_decode.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
@@ -154,6 +158,24 @@ def xkv_sr_decode(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, idx_out, sc
     _check(load().xkv_sr_decode(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k), _ptr(B_v),
                                 _ptr(q), _ptr(out), _ptr(idx_out), _ptr(score_out), _ptr(workspace),
                                 workspace.numel(), _stream(stream)), "xkv_sr_decode")
+
+
+def xkv_packed_b_bytes(shape: Shape) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load().xkv_packed_b_bytes(ctypes.byref(shape.c()), ctypes.byref(n)), "xkv_packed_b_bytes")
+    return int(n.value)
+
+
+def xkv_pack_b(shape, B_k, B_v, packed_out, stream=None):
+    _check(load().xkv_pack_b(ctypes.byref(shape.c()), _ptr(B_k), _ptr(B_v), _ptr(packed_out), _stream(stream)),
+           "xkv_pack_b")
+
+
+def xkv_sr_decode_packed(shape, layer_in_group, A_k, A_v, B_k, B_packed, q, out, idx_out, score_out, workspace,
+                         stream=None):
+    _check(load().xkv_sr_decode_packed(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
+                                       _ptr(B_packed), _ptr(q), _ptr(out), _ptr(idx_out), _ptr(score_out),
+                                       _ptr(workspace), workspace.numel(), _stream(stream)), "xkv_sr_decode_packed")
 
 
 STATIC_SCRATCH_BYTES = 40 << 20

@@ -200,12 +200,12 @@ bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, co
 
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
-                                bool packed, float *part_o, float *part_ml, hipStream_t st, const int32_t *counts,
-                                float rope_theta)
+                                const void *B_packed, bool packed, float *part_o, float *part_ml, hipStream_t st,
+                                const int32_t *counts, float rope_theta)
 {
     if (gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws))
-        return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml, st,
-                                         counts, rope_theta);
+        return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, B_packed, packed, part_o,
+                                         part_ml, st, counts, rope_theta);
     if (s.dtype == XKV_F32)
         return launch_generic<float>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts, rope_theta);
     return launch_generic<bf16_t>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts, rope_theta);

@@ -33,9 +33,13 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 constexpr int kMaxChunkTokens = 4096;  // selected tokens per workgroup (their ids sit in LDS)
 constexpr int kGroup = 8;  // fragments (of 16 ranks) per LDS stage: 8 x 4 KiB = 32 KiB, two stages
 
+// blocks [0, blocks_per_head) of a (sequence, KV head) pack B, the next kPackQBlocks the Q^T fragments
 __global__ __launch_bounds__(256) void pack_b_kernel(PackArgs a)
 {
-    pack_b_block(a, blockIdx.x, blockIdx.y, blockIdx.z);
+    if ((int)blockIdx.x < a.blocks_per_head)
+        pack_b_block(a, blockIdx.x, blockIdx.y, blockIdx.z);
+    else if (a.pack_q)
+        pack_q_block(a, (int)blockIdx.x - a.blocks_per_head, blockIdx.y, blockIdx.z);
 }
 
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t &c, int j)
@@ -143,7 +147,8 @@ struct RopeTable {
 template <int WAVES, bool ROPE>
 __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const bf16_t *__restrict__ A_k, const bf16_t *__restrict__ A_v, const u32x4_t *__restrict__ pack,
-    const bf16_t *__restrict__ q, const int32_t *__restrict__ idx, const int32_t *__restrict__ counts,
+    size_t pack_seq_stride, const u32x4_t *__restrict__ pack_q, const int32_t *__restrict__ idx,
+    const int32_t *__restrict__ counts,
     float *__restrict__ part_o, float *__restrict__ part_ml, int L, int r_k, int r_v, int H_kv, int H_q, int k,
     int splits, int chunk, int F16k, int F16v, float scale, const RopeTable rope)
 {
@@ -159,11 +164,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const int n_rep = H_q / H_kv;
     const int PK = F16k / (2 * kGroup), PT = (F16k + F16v) / (2 * kGroup);  // pairs of groups per tile: K, total
 
-    // Q^T fragments (built by pack_b_kernel behind the B fragments), kept in LDS for all wavefronts
-    const u32x4_t *packg = pack + ((size_t)b * H_kv + g) * ((size_t)(F16k + F16v) * 256 + 512);
+    // this head's B fragments (pack_seq_stride pieces from one sequence to the next: a per-call pack holds one layer,
+    // a group's pack all of its layers) and its Q^T fragments, the latter kept in LDS for all wavefronts
+    const u32x4_t *packg = pack + (size_t)b * pack_seq_stride + (size_t)g * ((size_t)(F16k + F16v) * 256);
     u32x4_t *At = reinterpret_cast<u32x4_t *>(smem_raw + kLdsB) + w * 512;
     u32x4_t *Ql = reinterpret_cast<u32x4_t *>(smem_raw + kLdsB + kLdsA);  // [8][64]
-    for (int i = tid; i < 8 * 64; i += WAVES * 64) Ql[i] = packg[(size_t)(F16k + F16v) * 256 + i];
+    for (int i = tid; i < 8 * 64; i += WAVES * 64) Ql[i] = pack_q[((size_t)b * H_kv + g) * 512 + i];
 
     const u32x4_t *Ak = reinterpret_cast<const u32x4_t *>(A_k + (size_t)b * L * r_k);
     const u32x4_t *Av = reinterpret_cast<const u32x4_t *>(A_v + (size_t)b * L * r_v);
@@ -415,37 +421,62 @@ bool gather_attend_mfma_shape_ok(const xkv_shape &s)
     return s.dtype == XKV_BF16 && s.d_h == 128 && s.r_k % 16 == 0 && s.r_v % 16 == 0;
 }
 
-size_t gather_attend_pack_bytes(const xkv_shape &s)
+static inline int frag_rows(int r) { return (r / 16 + 15) / 16 * 16; }  // fragments of 16 ranks, padded to whole pairs of groups
+
+// one layer's packed B, all sequences
+static size_t layer_pack_bytes(const xkv_shape &s)
 {
-    const int F8k = (s.r_k / 16 + 15) / 16 * 16, F8v = (s.r_v / 16 + 15) / 16 * 16;  // padded to whole pairs of groups
-    return (size_t)(s.batch > 0 ? s.batch : 1) * s.H_kv * ((size_t)(F8k + F8v) * 4 * 1024 + 8 * 1024);
+    return (size_t)(s.batch > 0 ? s.batch : 1) * s.H_kv * (size_t)(frag_rows(s.r_k) + frag_rows(s.r_v)) * 4 * 1024;
 }
+static size_t q_pack_bytes(const xkv_shape &s) { return (size_t)(s.batch > 0 ? s.batch : 1) * s.H_kv * 8 * 1024; }
+
+size_t gather_attend_pack_bytes(const xkv_shape &s) { return q_pack_bytes(s) + layer_pack_bytes(s); }
+size_t gather_attend_group_pack_bytes(const xkv_shape &s) { return layer_pack_bytes(s) * (size_t)s.G; }
 
 PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k, const void *B_v, const void *q,
-                                  void *pack_ws)
+                                  void *pack_ws, bool with_b)
 {
     PackArgs a;
     a.B_k = (const bf16_t *)B_k;
     a.B_v = (const bf16_t *)B_v;
     a.q = (const bf16_t *)q;
-    a.pack = (pack_u32x4_t *)pack_ws;
+    a.pack_q = (pack_u32x4_t *)pack_ws;
+    a.pack = (pack_u32x4_t *)((char *)pack_ws + q_pack_bytes(s));
     a.G = s.G;
     a.layer = layer;
     a.r_k = s.r_k;
     a.r_v = s.r_v;
     a.H_kv = s.H_kv;
     a.H_q = s.H_q;
-    a.F8k = (s.r_k / 16 + 15) / 16 * 16;  // padded to whole pairs of groups
-    a.F8v = (s.r_v / 16 + 15) / 16 * 16;
+    a.F8k = frag_rows(s.r_k);
+    a.F8v = frag_rows(s.r_v);
     a.batch = s.batch;
-    a.blocks_per_head = ((a.F8k + a.F8v) * 64 + 512 + 255) / 256;
+    a.dst_G = 1;
+    a.dst_layer = 0;
+    a.blocks_per_head = with_b ? ((a.F8k + a.F8v) * 64 + 255) / 256 : 0;
     return a;
+}
+
+// B of every layer of a group into fragment order, [batch][G][H_kv][...]: what xkv_sr_decode_packed reads.
+hipError_t launch_pack_group(const xkv_shape &s, const void *B_k, const void *B_v, void *packed, hipStream_t st)
+{
+    for (int layer = 0; layer < s.G; ++layer) {
+        PackArgs a = gather_attend_pack_args(s, layer, B_k, B_v, nullptr, nullptr, true);
+        a.pack = (pack_u32x4_t *)packed;
+        a.pack_q = nullptr;
+        a.dst_G = s.G;
+        a.dst_layer = layer;
+        hipLaunchKernelGGL(pack_b_kernel, dim3(a.blocks_per_head, s.H_kv, s.batch), dim3(256), 0, st, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
-                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st,
-                                     const int32_t *counts, float rope_theta)
+                                     void *pack_ws, const void *B_packed, bool packed, float *part_o, float *part_ml,
+                                     hipStream_t st, const int32_t *counts, float rope_theta)
 {
     RopeTable rope{};
     const bool use_rope = rope_theta > 0.0f;
@@ -456,15 +487,19 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
             rope.f0[j] = (float)f;
             rope.f1[j] = (float)(f256 - std::floor(f256));
         }
-    const PackArgs pa = gather_attend_pack_args(s, layer, B_k, B_v, q, pack_ws);
+    const PackArgs pa = gather_attend_pack_args(s, layer, B_k, B_v, q, pack_ws, B_packed == nullptr);
     const int F8k = pa.F8k, F8v = pa.F8v;
     hipError_t e = hipSuccess;
     if (!packed) {
-        hipLaunchKernelGGL(pack_b_kernel, dim3(pa.blocks_per_head, s.H_kv, s.batch), dim3(256), 0, st, pa);
+        hipLaunchKernelGGL(pack_b_kernel, dim3(pa.blocks_per_head + kPackQBlocks, s.H_kv, s.batch), dim3(256), 0, st, pa);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (p.sr_chunk > kMaxChunkTokens) return hipErrorInvalidValue;
+    // where the kernel finds B: this layer of the group's pack, or the one layer packed into the workspace
+    const size_t per_head = (size_t)(F8k + F8v) * 256;  // pieces of 16 B
+    const u32x4_t *bsrc = B_packed ? (const u32x4_t *)B_packed + (size_t)layer * s.H_kv * per_head : (const u32x4_t *)pa.pack;
+    const size_t seq_stride = (B_packed ? (size_t)s.G : 1) * s.H_kv * per_head;
     dim3 grid((unsigned)((long long)p.sr_splits * s.H_kv * s.batch));
 #define XKV_GA_LAUNCH(WV, RP)                                                                                      \
     do {                                                                                                           \
@@ -476,7 +511,7 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
         if (e != hipSuccess) return e;                                                                             \
         profile_begin(1, st);                                                                                      \
         hipLaunchKernelGGL((gather_attend_mfma_kernel<WV, RP>), grid, dim3(WV * 64), lds, st, (const bf16_t *)A_k, \
-                           (const bf16_t *)A_v, (const u32x4_t *)pack_ws, (const bf16_t *)q, idx, counts, part_o,  \
+                           (const bf16_t *)A_v, bsrc, seq_stride, (const u32x4_t *)pa.pack_q, idx, counts, part_o, \
                            part_ml, s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v,      \
                            p.scale, rope);                                                                         \
         profile_end(1, st);                                                                                        \

@@ -78,34 +78,19 @@ __device__ __forceinline__ void project_q_frag_block(const ProjArgs &a, int blk_
 
 // Pack B_{l,g} (r x 128 slice of B_l) into MFMA fragment order:
 //   pack[f][db][hf*32 + c][e] = B[16f + 8hf + e][g*128 + db*32 + c],  zero beyond r.
-// Output per (sequence, KV head): F8k fragment rows for K then F8v for V, 4 KiB each, F8 = roundup(r/16, 16).
+// Output per (sequence, layer, KV head): F8k fragment rows for K then F8v for V, 4 KiB each, F8 = roundup(r/16, 16);
+// the destination holds dst_G layers per sequence and this call fills layer dst_layer of it (a per-call pack in the
+// workspace has dst_G = 1; the pack of a whole group, made once per prompt, has dst_G = G).
 __device__ __forceinline__ void pack_b_block(const PackArgs &a, int blk, int g, int b)
 {
-    const bf16_t *__restrict__ B_k = a.B_k, *__restrict__ B_v = a.B_v, *__restrict__ q = a.q;
+    const bf16_t *__restrict__ B_k = a.B_k, *__restrict__ B_v = a.B_v;
     pack_u32x4_t *__restrict__ pack = a.pack;
-    const int G = a.G, layer = a.layer, r_k = a.r_k, r_v = a.r_v, H_kv = a.H_kv, H_q = a.H_q, F8k = a.F8k, F8v = a.F8v;
+    const int G = a.G, layer = a.layer, r_k = a.r_k, r_v = a.r_v, H_kv = a.H_kv, F8k = a.F8k, F8v = a.F8v;
     typedef pack_u32x4_t u32x4_t;
     // one thread per (fragment f, half hf, dim block db, 4 columns): 8 rows x 8 B in, 4 lanes' 16 B pieces out
     const int d = H_kv * 128;
     const int item = blk * 256 + threadIdx.x;
-    if (item >= (F8k + F8v) * 64) {
-        // the last 512 items build the eight Q^T fragments of this (sequence, KV head), stored behind the B
-        // fragments: lane (head slot n, hf), position e of fragment (db, j) holds q[n][db*32 + 8(2j + e/4) + 4hf + e%4]
-        const int qi = item - (F8k + F8v) * 64;
-        if (qi >= 8 * 64) return;
-        const int lane = qi & 63, fj = qi >> 6, db = fj >> 1, j = fj & 1;
-        const int n = lane & 31, hf = lane >> 5, n_rep = H_q / H_kv;
-        const bf16_t *qh = q + ((size_t)b * H_q + (size_t)g * n_rep + (n < n_rep ? n : 0)) * 128;
-        u32x4_t raw;
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            const int e = 2 * e2;
-            const int dim = db * 32 + 8 * (2 * j + e / 4) + 4 * hf + e % 4;  // e and e+1 are adjacent dims
-            raw[e2] = n < n_rep ? *reinterpret_cast<const uint32_t *>(qh + dim) : 0u;
-        }
-        pack[((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(F8k + F8v) * 256 + qi] = raw;
-        return;
-    }
+    if (item >= (F8k + F8v) * 64) return;
     const int c4 = item & 7, db = (item >> 3) & 3, hf = (item >> 5) & 1, fa = item >> 6;
     const bool is_v = fa >= F8k;
     const int f = is_v ? fa - F8k : fa;
@@ -117,8 +102,8 @@ __device__ __forceinline__ void pack_b_block(const PackArgs &a, int blk, int g, 
         const int i = 16 * f + 8 * hf + e;
         wd[e] = i < r ? *reinterpret_cast<const uint64_t *>(src + (size_t)i * d) : 0ull;
     }
-    u32x4_t *dst = pack + ((size_t)b * H_kv + g) * ((size_t)(F8k + F8v) * 256 + 512) + (size_t)(fa * 4 + db) * 64 +
-                   hf * 32 + c4 * 4;
+    u32x4_t *dst = pack + (((size_t)b * a.dst_G + a.dst_layer) * H_kv + g) * ((size_t)(F8k + F8v) * 256) +
+                   (size_t)(fa * 4 + db) * 64 + hf * 32 + c4 * 4;
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) {
         u32x4_t o;
@@ -130,6 +115,27 @@ __device__ __forceinline__ void pack_b_block(const PackArgs &a, int blk, int g, 
         }
         dst[cc] = o;
     }
+}
+
+// The eight Q^T fragments of one (sequence, KV head), 512 items (two blocks of 256 threads): lane (head slot n, hf),
+// position e of fragment (db, j) holds q[n][db*32 + 8(2j + e/4) + 4hf + e%4].  Output [batch][H_kv][8][64] pieces.
+__device__ __forceinline__ void pack_q_block(const PackArgs &a, int blk, int g, int b)
+{
+    const bf16_t *__restrict__ q = a.q;
+    typedef pack_u32x4_t u32x4_t;
+    const int qi = blk * 256 + threadIdx.x;
+    if (qi >= 8 * 64) return;
+    const int lane = qi & 63, fj = qi >> 6, db = fj >> 1, j = fj & 1;
+    const int n = lane & 31, hf = lane >> 5, n_rep = a.H_q / a.H_kv;
+    const bf16_t *qh = q + ((size_t)b * a.H_q + (size_t)g * n_rep + (n < n_rep ? n : 0)) * 128;
+    u32x4_t raw;
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+        const int e = 2 * e2;
+        const int dim = db * 32 + 8 * (2 * j + e / 4) + 4 * hf + e % 4;  // e and e+1 are adjacent dims
+        raw[e2] = n < n_rep ? *reinterpret_cast<const uint32_t *>(qh + dim) : 0u;
+    }
+    a.pack_q[((size_t)b * a.H_kv + g) * 512 + qi] = raw;
 }
 
 }  // namespace xkv

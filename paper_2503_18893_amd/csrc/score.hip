@@ -148,17 +148,22 @@ __global__ __launch_bounds__(256) void project_q_frag_kernel(ProjArgs a)
 }
 
 // One launch for the small passes that precede the score kernel: blocks [0, n_proj) project the queries, the next
-// n_pack pack B for the gather-attend kernel (see prepass.h), the rest clear the row histograms that the score
-// kernel adds to (zero_words a multiple of 4).
+// n_pack put the Q^T fragments and (unless the caller brought a packed B) B_l into fragment order for the
+// gather-attend kernel (see prepass.h), the rest clear the row histograms that the score kernel adds to (zero_words a
+// multiple of 4).
 __global__ __launch_bounds__(256) void prepass_kernel(ProjArgs pj, PackArgs pk, int n_proj, int n_pack,
                                                       uint32_t *__restrict__ zero, int zero_words)
 {
     if ((int)blockIdx.x < n_proj) {
         project_q_frag_block(pj, (int)blockIdx.x % pj.blocks_x, (int)blockIdx.x / pj.blocks_x);
     } else if ((int)blockIdx.x < n_proj + n_pack) {
-        const int pl = (int)blockIdx.x - n_proj;
-        pack_b_block(pk, pl % pk.blocks_per_head, (pl / pk.blocks_per_head) % pk.H_kv,
-                     pl / (pk.blocks_per_head * pk.H_kv));
+        const int per_head = pk.blocks_per_head + kPackQBlocks;
+        const int pl = (int)blockIdx.x - n_proj, blk = pl % per_head;
+        const int g = (pl / per_head) % pk.H_kv, b = pl / (per_head * pk.H_kv);
+        if (blk < pk.blocks_per_head)
+            pack_b_block(pk, blk, g, b);
+        else
+            pack_q_block(pk, blk - pk.blocks_per_head, g, b);
     } else {
         const int i = 4 * (((int)blockIdx.x - n_proj - n_pack) * 256 + (int)threadIdx.x);
         if (i < zero_words) *reinterpret_cast<u32x4_t *>(zero + i) = u32x4_t{0u, 0u, 0u, 0u};
@@ -1151,7 +1156,7 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     const int zero_words = zero_hist ? p.rows * kTopkLevels * kTopkBins : 0;  // a multiple of 1024
     if (fuse_pack || zero_hist) {
         const int n_proj = pj.blocks_x * s.batch;
-        const int n_pack = fuse_pack ? fuse_pack->blocks_per_head * fuse_pack->H_kv * fuse_pack->batch : 0;
+        const int n_pack = fuse_pack ? (fuse_pack->blocks_per_head + kPackQBlocks) * fuse_pack->H_kv * fuse_pack->batch : 0;
         hipLaunchKernelGGL(prepass_kernel, dim3(n_proj + n_pack + zero_words / 1024), dim3(256), 0, st, pj,
                            fuse_pack ? *fuse_pack : PackArgs{}, n_proj, n_pack, row_hist, zero_words);
         if (packed_done) *packed_done = fuse_pack != nullptr;

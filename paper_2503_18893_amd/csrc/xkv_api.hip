@@ -172,7 +172,7 @@ xkv_status xkv_gather_attend(const xkv_shape *shape, int32_t layer, const void *
     float *part_ml = at<float>(workspace, p.off_part_ml);
     void *pack_ws = at<void>(workspace, p.off_bpack);
     const bool mfma = gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws);
-    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, false, part_o, part_ml,
+    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, nullptr, false, part_o, part_ml,
                                         stream);
     // the matrix-core kernel writes one partial per split, the general one one per wavefront
     if (e == hipSuccess) e = launch_combine(*shape, mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
@@ -196,15 +196,20 @@ static hipError_t launch_tail(const xkv_shape &shape, const Plan &p, const void 
     return e;
 }
 
+// B_packed (nullable): the group's B_l in fragment order from xkv_pack_b; B_v may then be NULL.
 static xkv_status sr_decode_impl(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
                                  const void *B_k, const void *B_v, const void *q, const void *K_tail,
                                  const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
-                                 void *workspace, size_t workspace_bytes, void *hip_stream)
+                                 void *workspace, size_t workspace_bytes, void *hip_stream,
+                                 const void *B_packed = nullptr)
 {
     Plan p;
     xkv_status st = prepare(shape, workspace, workspace_bytes, p);
     if (st != XKV_OK) return st;
-    if (!A_k || !A_v || !B_k || !B_v || !q || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if (!A_k || !A_v || !B_k || (!B_v && !B_packed) || !q || !out || layer < 0 || layer >= shape->G)
+        return XKV_ERR_INVALID_ARG;
+    if (B_packed && (!p.ga_mfma || ((((uintptr_t)A_k | (uintptr_t)A_v | (uintptr_t)B_k | (uintptr_t)B_packed)) & 15u)))
+        return XKV_ERR_UNSUPPORTED;  // the packed form belongs to the matrix-core kernel
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
     float *S = score_out ? score_out : at<float>(workspace, p.off_score);
@@ -217,17 +222,17 @@ static xkv_status sr_decode_impl(const xkv_shape *shape, int32_t layer, const vo
     // B is packed for the matrix-core gather-attend kernel in the same launch as the query projection
     void *pack_ws = at<void>(workspace, p.off_bpack);
     PackArgs pa{};
-    const bool want_pack = gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws);
-    if (want_pack) pa = gather_attend_pack_args(*shape, layer, B_k, B_v, q, pack_ws);
+    const bool want_pack = gather_attend_uses_mfma(p, A_k, A_v, B_k, B_packed ? B_k : B_v, pack_ws);
+    if (want_pack) pa = gather_attend_pack_args(*shape, layer, B_k, B_v, q, pack_ws, B_packed == nullptr);
     bool packed = false;
     if (e == hipSuccess)
         e = launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
-                               p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
-                               &level0_done, want_pack ? &pa : nullptr, &packed, stream);
+                               p.score_hist ? topk_row_hist(p, state) : nullptr,
+                               p.score_hist ? hist : nullptr, &level0_done, want_pack ? &pa : nullptr, &packed, stream);
     if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, level0_done, stream);
     if (e == hipSuccess)
-        e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, packed, part_o, part_ml,
-                                 stream);
+        e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_packed ? B_k : B_v, q, idx, pack_ws, B_packed, packed,
+                                 part_o, part_ml, stream);
     // The uncompressed tail goes through the dense kernel as a context of T tokens of its own (at most 8 splits),
     // into a second set of partials; the merge below is one softmax over selected rows and tail.
     int n_tail = 0;
@@ -246,6 +251,36 @@ xkv_status xkv_sr_decode(const xkv_shape *shape, int32_t layer, const void *A_k,
 {
     return sr_decode_impl(shape, layer, A_k, A_v, B_k, B_v, q, nullptr, nullptr, 0, out, idx_out, score_out, workspace,
                           workspace_bytes, hip_stream);
+}
+
+xkv_status xkv_packed_b_bytes(const xkv_shape *shape, size_t *bytes)
+{
+    if (!bytes) return XKV_ERR_INVALID_ARG;
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    if (!gather_attend_mfma_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
+    *bytes = gather_attend_group_pack_bytes(*shape);
+    return XKV_OK;
+}
+
+xkv_status xkv_pack_b(const xkv_shape *shape, const void *B_k, const void *B_v, void *packed_out, void *hip_stream)
+{
+    xkv_status st = validate(shape);
+    if (st != XKV_OK) return st;
+    if (!gather_attend_mfma_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
+    if (!B_k || !B_v || !packed_out) return XKV_ERR_INVALID_ARG;
+    if ((((uintptr_t)B_k | (uintptr_t)B_v | (uintptr_t)packed_out)) & 15u) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    return hip_status(launch_pack_group(*shape, B_k, B_v, packed_out, (hipStream_t)hip_stream));
+}
+
+xkv_status xkv_sr_decode_packed(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v, const void *B_k,
+                                const void *B_packed, const void *q, void *out, int32_t *idx_out, float *score_out,
+                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!B_packed) return XKV_ERR_INVALID_ARG;
+    return sr_decode_impl(shape, layer, A_k, A_v, B_k, nullptr, q, nullptr, nullptr, 0, out, idx_out, score_out, workspace,
+                          workspace_bytes, hip_stream, B_packed);
 }
 
 }  // extern "C"
@@ -474,8 +509,8 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     hipError_t e = launch_identity(*shape, ident, lp.score_shape.batch, stream);
     if (e == hipSuccess)
         e = launch_score_stage(lp.score_shape, ps, 0, landmarks, ident, q, at<void>(ws_s, ps.off_p), S,
-                               ps.score_hist ? topk_row_hist(ps, state) : nullptr, ps.score_hist ? hist : nullptr,
-                               &level0_done, nullptr, nullptr, stream);
+                               ps.score_hist ? topk_row_hist(ps, state) : nullptr,
+                               ps.score_hist ? hist : nullptr, &level0_done, nullptr, nullptr, stream);
     // top ceil(k / c) chunks per KV head, union with the outliers, expansion to rows
     if (e == hipSuccess) e = launch_topk(lp.score_shape, ps, S, chunks, hist, state, level0_done, stream);
     int32_t *rows = rows_out ? rows_out : at<int32_t>(workspace, pa.off_idx);
@@ -486,7 +521,7 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     void *pack_ws = at<void>(workspace, pa.off_bpack);
     const bool mfma = gather_attend_uses_mfma(pa, A_k, A_v, B_k, B_v, pack_ws);
     if (e == hipSuccess)
-        e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, false, part_o, part_ml,
+        e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, nullptr, false, part_o, part_ml,
                                  stream, counts, rope_theta);
     // the uncompressed tail, as in xkv_sr_decode_tail: a dense pass over its T tokens into a second set of partials
     int n_tail = 0;
@@ -520,7 +555,7 @@ xkv_status xkv_gather_attend_ex(const xkv_shape *shape, int32_t layer, const voi
     float *part_ml = at<float>(workspace, p.off_part_ml);
     void *pack_ws = at<void>(workspace, p.off_bpack);
     const bool mfma = gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws);
-    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, false, part_o, part_ml,
+    hipError_t e = launch_gather_attend(*shape, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, nullptr, false, part_o, part_ml,
                                         stream, counts, rope_theta);
     if (e == hipSuccess) e = launch_combine(*shape, mfma ? p.sr_splits : p.sr_splits * 4, part_o, part_ml, out, stream);
     return hip_status(e);
@@ -649,8 +684,8 @@ static xkv_status sr_decode_absorbed_impl(const xkv_shape *shape, int32_t layer,
     hipError_t e =
         q4 ? launch_score_q4_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S, heads, stream)
            : launch_score_stage(*shape, p, layer, A_k, B_k, q, at<void>(workspace, p.off_p), S,
-                                p.score_hist ? topk_row_hist(p, state) : nullptr, p.score_hist ? hist : nullptr,
-                                &level0_done, nullptr, nullptr, stream, heads);
+                                p.score_hist ? topk_row_hist(p, state) : nullptr,
+                                p.score_hist ? hist : nullptr, &level0_done, nullptr, nullptr, stream, heads);
     if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, level0_done, stream);
     float *po = at<float>(workspace, a.off_po), *pml = at<float>(workspace, a.off_pml);
     if (e == hipSuccess)

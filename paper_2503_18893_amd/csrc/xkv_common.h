@@ -115,10 +115,13 @@ struct ProjArgs {
 };
 struct PackArgs {
     const bf16_t *B_k, *B_v, *q;
-    pack_u32x4_t *pack;
+    pack_u32x4_t *pack;    // packed B, [batch][dst_G][H_kv][(F8k + F8v) * 256] pieces of 16 B
+    pack_u32x4_t *pack_q;  // Q^T fragments, [batch][H_kv][512] pieces
     int G, layer, r_k, r_v, H_kv, H_q, F8k, F8v, batch;
-    int blocks_per_head;  // 256-item blocks per (sequence, KV head): B items, then 512 items for the Q^T fragments
+    int dst_G, dst_layer;  // the destination holds dst_G layers per sequence; this call fills dst_layer
+    int blocks_per_head;   // 256-item blocks per (sequence, KV head) for the B items (0: B is already packed)
 };
+constexpr int kPackQBlocks = 2;  // 256-item blocks per (sequence, KV head) for the Q^T fragments
 
 // Raises a kernel's dynamic-LDS limit the first time the kernel is launched on each device.  One static instance
 // per kernel; safe for concurrent host threads (the attribute call is idempotent, the flag word is atomic).
@@ -159,25 +162,30 @@ hipError_t launch_topk_init(const Plan &p, uint32_t *state, hipStream_t st);
 // level0_done: launch_topk_init ran and the level-0 histograms were already accumulated by the score stage.
 hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_t *idx, uint32_t *hist,
                        uint32_t *state, bool level0_done, hipStream_t st);
-// packed: pack_ws already holds this layer's packed B and Q fragments (matrix-core path only).
+// pack_ws: workspace for the operands in fragment order (Q^T fragments, then this layer's packed B).
+// B_packed (nullable): the group's B already in fragment order (xkv_pack_b), then nothing of B is packed per call.
+// packed: pack_ws already holds this call's fragments (written by the launch that projected the queries).
 // counts (nullable): [batch][H_kv], how many of the s.k ids of each row are real; the rest is ignored.
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
-                                bool packed, float *part_o, float *part_ml, hipStream_t st,
+                                const void *B_packed, bool packed, float *part_o, float *part_ml, hipStream_t st,
                                 const int32_t *counts = nullptr, float rope_theta = 0.0f);
 // rope_theta > 0: the reconstructed key rows are rotated to their positions (RoPE base theta) before the scores.
 bool rope_shape_ok(const xkv_shape &s);
 bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, const void *B_k, const void *B_v,
                              const void *pack_ws);
+// with_b: also pack B_l into the workspace (false when the caller supplies the group's packed B)
 PackArgs gather_attend_pack_args(const xkv_shape &s, int layer, const void *B_k, const void *B_v, const void *q,
-                                 void *pack_ws);
+                                 void *pack_ws, bool with_b);
 bool gather_attend_mfma_shape_ok(const xkv_shape &s);
 int gather_attend_mfma_waves(const xkv_shape &s);
-size_t gather_attend_pack_bytes(const xkv_shape &s);
+size_t gather_attend_pack_bytes(const xkv_shape &s);        // Q^T fragments + one layer's packed B (workspace)
+size_t gather_attend_group_pack_bytes(const xkv_shape &s);  // packed B of all G layers of a group (xkv_pack_b)
+hipError_t launch_pack_group(const xkv_shape &s, const void *B_k, const void *B_v, void *packed, hipStream_t st);
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
-                                     void *pack_ws, bool packed, float *part_o, float *part_ml, hipStream_t st,
-                                     const int32_t *counts = nullptr, float rope_theta = 0.0f);
+                                     void *pack_ws, const void *B_packed, bool packed, float *part_o, float *part_ml,
+                                     hipStream_t st, const int32_t *counts = nullptr, float rope_theta = 0.0f);
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st);
 bool dense_mfma_shape_ok(const xkv_shape &s);

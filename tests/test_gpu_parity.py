@@ -357,6 +357,56 @@ def test_large_and_unequal_ranks_chain(name, w):
     print(name, rep)
 
 
+# ------------------------------------------------------------------------------ B_l packed once per prompt
+PACKED = [
+    ("llama_small", synth.LLAMA_GROUP.with_(L=3000, k=200, r_k=128, r_v=192, batch=2, G=3)),
+    ("qwen_ragged_ranks", synth.QWEN.with_(L=5001, k=257, r_k=448, r_v=288, batch=2, G=2, a_scale=448 ** -0.5)),
+    ("llama_k2100", synth.LLAMA_GROUP.with_(L=6000, k=2100, r_k=64, r_v=96, batch=4, G=2)),
+]
+
+
+@pytest.mark.parametrize("name,w", PACKED, ids=[n for n, _ in PACKED])
+def test_packed_b_step_matches_plain_step(name, w):
+    """xkv_pack_b once, then xkv_sr_decode_packed for every layer of the group: outputs, selections and scores
+    bit for bit those of xkv_sr_decode (same kernels, same operands), and the outputs against the oracle on the
+    step's own selection."""
+    torch = torch_mod()
+    case = synth.make_case(w, seed=19)
+    dev = synth.to_device(case, w.dtype)
+    shape = xb.Shape.of(w)
+    ws = xb.alloc_workspace(shape)
+    packed = torch.full((xb.xkv_packed_b_bytes(shape),), 0xAB, dtype=torch.uint8, device="cuda")
+    xb.xkv_pack_b(shape, dev["B_k"], dev["B_v"], packed)
+    dt = synth.torch_dtype(w.dtype)
+    for layer in range(w.G):
+        q = dev["q"][layer].contiguous()
+        res = []
+        for which in ("plain", "packed"):
+            out = torch.full((w.batch, w.H_q, w.d_h), float("nan"), dtype=dt, device="cuda")
+            idx = torch.full((w.batch, w.H_kv, w.k), -1, dtype=torch.int32, device="cuda")
+            S = torch.full((w.batch, w.H_kv, w.L), float("nan"), dtype=torch.float32, device="cuda")
+            if which == "plain":
+                xb.xkv_sr_decode(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], q, out, idx, S, ws)
+            else:
+                xb.xkv_sr_decode_packed(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], packed, q, out, idx, S, ws)
+            torch.cuda.synchronize()
+            res.append((synth.to_host(out), idx.cpu().numpy(), S.cpu().numpy()))
+        for a, b_ in zip(res[0], res[1]):
+            np.testing.assert_array_equal(a, b_)
+        out_h, idx_h, _ = res[1]
+        for b in range(w.batch):
+            ref = oracle.gather_attend(case["A_k"][b], case["A_v"][b], case["B_k"][b, layer], case["B_v"][b, layer],
+                                       case["q"][layer, b], idx_h[b])
+            assert max_rel(synth.storage_to_f64(out_h[b]), ref) <= TOL[w.dtype], (name, layer, b)
+
+
+def test_packed_b_rejects_shapes_of_the_general_kernels():
+    torch_mod()
+    with pytest.raises(xb.XkvError) as e:
+        xb.xkv_packed_b_bytes(xb.Shape.of(synth.TINY))
+    assert e.value.status == xb.XKV_ERR_UNSUPPORTED
+
+
 # ------------------------------------------------------------------------------ uncompressed tail of recent tokens
 TAIL = [
     ("tiny_f32", synth.TINY.with_(L=700, k=40), 37),
