@@ -288,7 +288,7 @@ XKV_API xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer_
  * [4i, 4i+4), rank 8j+2i+1 in bits [16+4i, 16+4i+4), i = 0..3), then r/32 pairs (step, lo) of bf16.  Per group of 32 consecutive ranks: lo = min, step = bf16((max - lo) / 15)
  * (1 if that is 0), code = clip(rint((x - lo) * (1 / step)), 0, 15) in fp32; the value every later stage sees is
  * x^ = step * code + lo.
- *   xkv_quantized_row_bytes: the row size, or XKV_ERR_UNSUPPORTED (bits != 4, r not a multiple of 32).
+ *   xkv_quantized_row_bytes: the row size, or XKV_ERR_UNSUPPORTED (bits not 4 or 3, r not a multiple of 32).
  *   xkv_quantize_rows: X [rows][r] bf16 -> out [rows][row size] bytes (both device, 16-byte aligned).
  *   xkv_attend_absorbed_q4: xkv_attend_absorbed with A^V given as quantised rows Aq_v [batch][L][row size]; the
  *     rows are de-quantised in registers inside the row-sum kernel, so the gather moves 5/16 of the bytes.  bf16
@@ -299,6 +299,40 @@ XKV_API xkv_status xkv_sr_decode_absorbed(const xkv_shape *shape, int32_t layer_
  *   xkv_sr_decode_absorbed_q4: xkv_sr_decode_absorbed on quantised A^K and A^V (B_k, B_v, q, the tail and the
  *     output stay bf16).  What it computes is the absorbed step on the de-quantised values x^.
  */
+/*
+ * 3-bit rows (App. "Integrate with Quantization": 32x total at 3 bits = 4 bits per element with the same side
+ * information) and the quantised cache in the gather-reconstruct kernels.  bits = 3 in xkv_quantized_row_bytes /
+ * xkv_quantize_rows gives r/2 bytes per row: one 16-byte piece per group of 32 ranks, 96 bits of codes read as one
+ * little-endian number -- unit u (ranks 8u..8u+7 of the group) in bits [24u, 24u+24), inside a unit rank 8u+2i at bits
+ * [3i, 3i+3) and rank 8u+2i+1 at bits [12+3i, 12+3i+3) -- then (step, lo) as two bf16; step = bf16((max - lo) / 7).
+ * The calls below run stages 3-4 (Eq. 3 and attention) straight from quantised rows of A^K and A^V: codes and
+ * parameters are gathered as they are, de-quantised in registers (x^ = step * code + lo, rounded once to bf16 as the
+ * matrix-core operand) and multiplied with B_l, so a rotation can still be applied to the reconstructed key rows -- the
+ * paper's own arrangement (factors of pre-RoPE keys, landmark selector, RoPE on reconstruction; Sec. 4 "Implementation
+ * details", App. B.1) on a quantised cache.  What they compute is the named step on the de-quantised values x^.
+ * bf16 shapes with d_h = 128 and ranks that are multiples of 32 (XKV_ERR_UNSUPPORTED otherwise); bits 4 or 3.
+ *   xkv_gather_attend_q: xkv_gather_attend_ex with Aq_k [batch][L][row bytes of r_k], Aq_v likewise.
+ *   xkv_sr_decode_landmark_q: xkv_sr_decode_landmark on quantised rows (landmarks stay in shape->dtype).
+ *   xkv_sr_decode_q4: the factor-scoring step of xkv_sr_decode on 4-bit rows -- scores from the quantised A^K
+ *     (xkv_head_scores_q4's kernel), selection, gather-reconstruct and attention from the quantised rows; rope_theta
+ *     and the tail as above; workspace of xkv_absorbed_workspace_bytes() bytes.  (No score kernel reads 3-bit rows:
+ *     a 3-bit cache goes with the landmark selector.)
+ */
+XKV_API xkv_status xkv_gather_attend_q(const xkv_shape *shape, int32_t layer_in_group, const void *Aq_k,
+                                       const void *Aq_v, int32_t bits, const void *B_k, const void *B_v, const void *q,
+                                       const int32_t *idx, const int32_t *counts, float rope_theta, void *out,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+XKV_API xkv_status xkv_sr_decode_landmark_q(const xkv_shape *shape, int32_t layer_in_group, const void *Aq_k,
+                                            const void *Aq_v, int32_t bits, const void *B_k, const void *B_v,
+                                            const void *q, const void *landmarks, const int32_t *outliers, int32_t c,
+                                            int32_t o, float rope_theta, const void *K_tail, const void *V_tail,
+                                            int32_t T, void *out, int32_t *rows_out, int32_t *count_out,
+                                            float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+XKV_API xkv_status xkv_sr_decode_q4(const xkv_shape *shape, int32_t layer_in_group, const void *Aq_k, const void *Aq_v,
+                                    const void *B_k, const void *B_v, const void *q, float rope_theta,
+                                    const void *K_tail, const void *V_tail, int32_t T, void *out, int32_t *idx_out,
+                                    float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 XKV_API xkv_status xkv_quantized_row_bytes(int32_t r, int32_t bits, size_t *bytes);
 XKV_API xkv_status xkv_quantize_rows(const void *X, int64_t rows, int32_t r, int32_t bits, void *out, void *hip_stream);
 XKV_API xkv_status xkv_attend_absorbed_q4(const xkv_shape *shape, int32_t layer_in_group, const void *Aq_v,

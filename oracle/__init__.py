@@ -480,6 +480,49 @@ def unpack_q4(packed, r):
     return codes, np.ascontiguousarray(step), np.ascontiguousarray(lo)
 
 
+def pack_q3(codes, step, lo):
+    """Byte layout of a 3-bit row as the library stores it: one 16-byte piece per group of 32 ranks.  The first 12
+    bytes are 96 bits of codes, read as one little-endian number: unit u (ranks 8u .. 8u+7 of the group) occupies bits
+    [24u, 24u + 24); inside a unit rank 8u + 2i sits at bits [3i, 3i + 3) and rank 8u + 2i + 1 at bits
+    [12 + 3i, 12 + 3i + 3), i = 0..3.  The last 4 bytes are (step, lo) as two bf16 numbers.  r/2 bytes per row."""
+    rows, r = codes.shape
+    assert codes.max(initial=0) < 8
+    n_g = r // Q_GROUP
+    c = codes.reshape(rows, n_g, 4, 4, 2).astype(object)              # [group][unit][i][even / odd rank]
+    big = np.zeros((rows, n_g), dtype=object)
+    for u in range(4):
+        for i in range(4):
+            big = big + (c[:, :, u, i, 0] << (24 * u + 3 * i)) + (c[:, :, u, i, 1] << (24 * u + 12 + 3 * i))
+    out = np.zeros((rows, n_g, 16), np.uint8)
+    for byte in range(12):
+        out[:, :, byte] = ((big >> (8 * byte)) & 0xFF).astype(np.uint8)
+    par = np.empty((rows, n_g, 2), np.uint16)
+    par[:, :, 0] = (np.ascontiguousarray(step, np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    par[:, :, 1] = (np.ascontiguousarray(lo, np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    out[:, :, 12:16] = par.reshape(rows, n_g, 2).view(np.uint8).reshape(rows, n_g, 4)
+    return out.reshape(rows, n_g * 16)
+
+
+def unpack_q3(packed, r):
+    """Inverse of pack_q3: (codes, step, lo)."""
+    packed = np.ascontiguousarray(packed, np.uint8)
+    rows = packed.shape[0]
+    n_g = r // Q_GROUP
+    pieces = packed.reshape(rows, n_g, 16)
+    big = np.zeros((rows, n_g), dtype=object)
+    for byte in range(12):
+        big = big + (pieces[:, :, byte].astype(object) << (8 * byte))
+    codes = np.empty((rows, n_g, 4, 4, 2), np.uint8)
+    for u in range(4):
+        for i in range(4):
+            codes[:, :, u, i, 0] = ((big >> (24 * u + 3 * i)) & 7).astype(np.uint8)
+            codes[:, :, u, i, 1] = ((big >> (24 * u + 12 + 3 * i)) & 7).astype(np.uint8)
+    par = np.ascontiguousarray(pieces[:, :, 12:16]).view(np.uint16).reshape(rows, n_g, 2)
+    step = (par[:, :, 0].astype(np.uint32) << 16).view(np.float32)
+    lo = (par[:, :, 1].astype(np.uint32) << 16).view(np.float32)
+    return codes.reshape(rows, r), np.ascontiguousarray(step), np.ascontiguousarray(lo)
+
+
 def quantized_bits_per_element(bits):
     """Storage per element of a quantised row: the code plus two 16-bit numbers per group of 32."""
     return bits + 2 * 16 / Q_GROUP

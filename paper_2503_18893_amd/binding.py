@@ -23,7 +23,7 @@ ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_static", 
                 "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_gather_attend_ex",
                 "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
                 "xkv_quantized_row_bytes", "xkv_quantize_rows", "xkv_attend_absorbed_q4", "xkv_head_scores_q4",
-                "xkv_sr_decode_absorbed_q4",
+                "xkv_sr_decode_absorbed_q4", "xkv_gather_attend_q", "xkv_sr_decode_landmark_q", "xkv_sr_decode_q4",
                 "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
@@ -107,6 +107,10 @@ def load() -> ctypes.CDLL:
         lib.xkv_attend_absorbed_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_head_scores_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_sr_decode_absorbed_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.xkv_gather_attend_q.argtypes = [sp, i32, vp, vp, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, sz, vp]
+        lib.xkv_sr_decode_landmark_q.argtypes = [sp, i32, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp,
+                                                 i32, vp, vp, vp, vp, vp, sz, vp]
+        lib.xkv_sr_decode_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
@@ -330,6 +334,33 @@ def xkv_sr_decode_absorbed(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, id
                                          _ptr(idx_out), _ptr(score_out), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(stream)),
            "xkv_sr_decode_absorbed")
+
+
+def xkv_gather_attend_q(shape, layer_in_group, Aq_k, Aq_v, bits, B_k, B_v, q, idx, counts, rope_theta, out, workspace,
+                        stream=None):
+    _check(load().xkv_gather_attend_q(ctypes.byref(shape.c()), layer_in_group, _ptr(Aq_k), _ptr(Aq_v), int(bits),
+                                      _ptr(B_k), _ptr(B_v), _ptr(q), _ptr(idx), _ptr(counts), float(rope_theta),
+                                      _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)), "xkv_gather_attend_q")
+
+
+def xkv_sr_decode_landmark_q(shape, layer_in_group, Aq_k, Aq_v, bits, B_k, B_v, q, landmarks, outliers, c, o, out,
+                             rows_out, count_out, score_out, workspace, stream=None, rope_theta=0.0, K_tail=None,
+                             V_tail=None, T=0):
+    _check(load().xkv_sr_decode_landmark_q(ctypes.byref(shape.c()), layer_in_group, _ptr(Aq_k), _ptr(Aq_v), int(bits),
+                                           _ptr(B_k), _ptr(B_v), _ptr(q), _ptr(landmarks), _ptr(outliers), c, o,
+                                           float(rope_theta), _ptr(K_tail), _ptr(V_tail), T, _ptr(out), _ptr(rows_out),
+                                           _ptr(count_out), _ptr(score_out), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_sr_decode_landmark_q")
+
+
+def xkv_sr_decode_q4(shape, layer_in_group, Aq_k, Aq_v, B_k, B_v, q, out, idx_out, score_out, workspace, stream=None,
+                     rope_theta=0.0, K_tail=None, V_tail=None, T=0):
+    _check(load().xkv_sr_decode_q4(ctypes.byref(shape.c()), layer_in_group, _ptr(Aq_k), _ptr(Aq_v), _ptr(B_k), _ptr(B_v),
+                                   _ptr(q), float(rope_theta), _ptr(K_tail), _ptr(V_tail), int(T), _ptr(out),
+                                   _ptr(idx_out), _ptr(score_out), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)), "xkv_sr_decode_q4")
 
 
 STAGE_SCORE, STAGE_GATHER_ATTEND, STAGE_DENSE, STAGE_FACTORIZE_GRAM, STAGE_ABSORB_ROWS = 0, 1, 2, 3, 4

@@ -198,14 +198,22 @@ bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, co
            ((((uintptr_t)A_k | (uintptr_t)A_v | (uintptr_t)B_k | (uintptr_t)B_v | (uintptr_t)pack_ws)) & 15u) == 0;
 }
 
+bool gather_attend_quant_ok(const xkv_shape &s, const Plan &p, const void *Aq_k, const void *Aq_v, const void *B_k,
+                            const void *B_v, const void *pack_ws, int qbits)
+{
+    return (qbits == 4 || qbits == 3) && quant_rank_ok(s.r_k) && quant_rank_ok(s.r_v) &&
+           gather_attend_uses_mfma(p, Aq_k, Aq_v, B_k, B_v, pack_ws);
+}
+
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
                                 const void *B_packed, bool packed, float *part_o, float *part_ml, hipStream_t st,
-                                const int32_t *counts, float rope_theta)
+                                const int32_t *counts, float rope_theta, int qbits)
 {
     if (gather_attend_uses_mfma(p, A_k, A_v, B_k, B_v, pack_ws))
         return launch_gather_attend_mfma(s, p, layer, A_k, A_v, B_k, B_v, q, idx, pack_ws, B_packed, packed, part_o,
-                                         part_ml, st, counts, rope_theta);
+                                         part_ml, st, counts, rope_theta, qbits);
+    if (qbits != 0) return hipErrorInvalidValue;  // quantised rows are read by the matrix-core kernel only
     if (s.dtype == XKV_F32)
         return launch_generic<float>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts, rope_theta);
     return launch_generic<bf16_t>(s, p, layer, A_k, A_v, B_k, B_v, q, idx, part_o, part_ml, st, counts, rope_theta);

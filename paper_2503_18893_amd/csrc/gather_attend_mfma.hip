@@ -127,6 +127,122 @@ __device__ __forceinline__ void run_group(f32x16_t (&acc)[4], u32x4_t (&areg)[2 
     }
 }
 
+// ---- rows of A given as 4-bit or 3-bit round-to-nearest codes (quant.hip) --------------------------------------
+// The gathers then move the codes and parameters of a pair of groups (256 ranks) of the wavefront's 32 rows at a
+// time -- 4 instructions of 8 rows x 128 B of codes, and for 4-bit rows one more for the 32 B of parameters of
+// each row (3-bit rows carry them inside the 16-byte group pieces) -- into a wavefront-private LDS tile that keeps
+// them as they are; a fragment step reads one word of codes (8 ranks) and the group's (step, lo) back and
+// de-quantises in registers, x^ = step * code + lo rounded once to bf16, which is the matrix-core operand.
+template <int QB> struct QuantTile {
+    static constexpr int NG = QB == 4 ? 5 : 4;          // gather instructions per pair of groups and wavefront
+    static constexpr int PITCH = QB == 4 ? 176 : 144;   // bytes per row of the code tile (pieces stay 16-byte aligned)
+};
+
+// A word with eight codes, even ranks in the low half and odd ranks in the high half, QB bits apart (two adjacent
+// ranks are 16 bits apart), and the group's (step, lo) word -> eight bf16 operands.  A code c or-ed onto 0x4300 is
+// the bf16 number 128 + c, so x^ = step (128 + c) + (lo - 128 step) is one fused multiply-add per element.
+template <int QB> __device__ __forceinline__ bf16x8_t dequant8(uint32_t codes, uint32_t param)
+{
+    constexpr uint32_t kMask = QB == 4 ? 0x000F000Fu : 0x00070007u;
+    const float step = __uint_as_float(param << 16), lo = __uint_as_float(param & 0xFFFF0000u);
+    const float lo2 = fmaf(-128.0f, step, lo);
+    f32x8_t x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t pr = ((codes >> (QB * i)) & kMask) | 0x43004300u;
+        x[2 * i] = fmaf(step, __uint_as_float(pr << 16), lo2);
+        x[2 * i + 1] = fmaf(step, __uint_as_float(pr & 0xFFFF0000u), lo2);
+    }
+    return __builtin_convertvector(x, bf16x8_t);
+}
+
+// Gather descriptor of one pair of groups of quantised rows.
+struct QStage {
+    const unsigned char *base;  // quantised A^K or A^V of this sequence
+    size_t pitch;               // bytes per row
+    int code_off;               // byte offset of this lane's 16-byte piece of codes within a row
+    int par_off;                // byte offset of this lane's 16 bytes of parameters (4-bit rows)
+};
+
+// The eight fragment steps of one group (gsel: first or second group of the pair held in the code tile).
+template <bool IS_K, int QB>
+__device__ __forceinline__ void q_steps(f32x16_t (&acc)[4], const u32x4_t *bcur, const unsigned char *crow, int gsel, int hf)
+{
+    u32x4_t piece = u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int fl = 0; fl < kGroup; ++fl) {
+        uint32_t codes, param;
+        if constexpr (QB == 4) {
+            codes = *reinterpret_cast<const uint32_t *>(crow + 4 * (16 * gsel + 2 * fl + hf));
+            param = *reinterpret_cast<const uint32_t *>(crow + 128 + 4 * (4 * gsel + fl / 2));
+        } else {
+            // the group's 16-byte piece: 96 bits of codes (four units of 24, unit 2 (fl % 2) + hf is this lane's), then (step, lo)
+            if (fl % 2 == 0) piece = *reinterpret_cast<const u32x4_t *>(crow + 16 * (4 * gsel + fl / 2));
+            uint32_t u;
+            if (fl % 2 == 0)
+                u = hf ? ((piece[0] >> 24) | (piece[1] << 8)) : piece[0];
+            else
+                u = hf ? (piece[2] >> 8) : ((piece[1] >> 16) | (piece[2] << 16));
+            codes = (u & 0xFFFu) | ((u << 4) & 0x0FFF0000u);  // odd ranks (bits 12..23) up to bit 16
+            param = piece[3];
+        }
+        const bf16x8_t a0 = dequant8<QB>(codes, param);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+            const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, bcur[(fl * 4 + db) * 64]);
+            if constexpr (IS_K)
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, a0, acc[db], 0, 0, 0);
+            else
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bf, acc[db], 0, 0, 0);
+        }
+    }
+}
+
+// One pair of groups from quantised rows.  Vector-memory operations complete in order, so the copies of the B
+// fragments must never be the youngest ones when they are awaited: the pair's first group waits for everything (its B
+// fragments and this pair's rows, both issued a whole group or more ago), then starts the copy of the second group's B
+// fragments and, behind it, the gathers of the next pair; the second group waits until only those gathers are left.
+template <bool IS_K, int WAVES, int QB>
+__device__ __forceinline__ void run_pair_q(f32x16_t (&acc)[4], u32x4_t (&creg)[QuantTile<QB>::NG], const u32x4_t *Bl,
+                                           unsigned char *Ct, uint32_t dma_buf0, uint32_t dma_buf1, const u32x4_t *bsrc1,
+                                           const u32x4_t *bsrc2, const QStage &qn, const int (&tkc)[4], int tkp, int lane)
+{
+    constexpr int NG = QuantTile<QB>::NG, PITCH = QuantTile<QB>::PITCH;
+    const int n = lane & 31, hf = lane >> 5;
+    XKV_WAIT_VMCNT(0);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+#pragma unroll
+    for (int i = 0; i < 32 / WAVES; ++i) copy16_global_to_lds(bsrc1 + i * (WAVES * 64), dma_buf1 + i * (WAVES * 1024));
+    // this pair's codes (and parameters) into the code tile, then the registers take the next pair's
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<u32x4_t *>(Ct + (8 * i + (lane >> 3)) * PITCH + 16 * (lane & 7)) = creg[i];
+    if constexpr (QB == 4) *reinterpret_cast<u32x4_t *>(Ct + (lane >> 1) * PITCH + 128 + 16 * (lane & 1)) = creg[4];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        creg[i] = *reinterpret_cast<const u32x4_t *>(qn.base + (size_t)tkc[i] * qn.pitch + qn.code_off);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (QB == 4) {
+        creg[4] = *reinterpret_cast<const u32x4_t *>(qn.base + (size_t)tkp * qn.pitch + qn.par_off);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    q_steps<IS_K, QB>(acc, Bl + lane, Ct + n * PITCH, 0, hf);
+    __builtin_amdgcn_sched_barrier(0);
+    XKV_WAIT_VMCNT(NG);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+#pragma unroll
+    for (int i = 0; i < 32 / WAVES; ++i) copy16_global_to_lds(bsrc2 + i * (WAVES * 64), dma_buf0 + i * (WAVES * 1024));
+    __builtin_amdgcn_sched_barrier(0);
+    q_steps<IS_K, QB>(acc, Bl + kGroup * 256 + lane, Ct + n * PITCH, 1, hf);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // Software pipeline.  The work of a workgroup is a linear sequence of groups of 8 fragment steps, taken in
 // pairs: per 256-token tile first the K pairs, then the V pairs (ranks are padded to a multiple of 256 with
 // zero fragments).  While a group is multiplied out of one of two LDS buffers, the B fragments of the next
@@ -144,7 +260,8 @@ struct RopeTable {
     float f0[64], f1[64];  // theta^(-j/64) / 2 pi, and frac(256 * that)
 };
 
-template <int WAVES, bool ROPE>
+// QB: 0 = rows of A in bf16; 4 or 3 = rows given as 4-bit / 3-bit codes (A_k, A_v then point to quantised rows).
+template <int WAVES, bool ROPE, int QB>
 __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const bf16_t *__restrict__ A_k, const bf16_t *__restrict__ A_v, const u32x4_t *__restrict__ pack,
     size_t pack_seq_stride, const u32x4_t *__restrict__ pack_q, const int32_t *__restrict__ idx,
@@ -246,12 +363,42 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
         return lds_b0 + (uint32_t)((bufi * (kGroup * 256) + w * 64) * 16);
     };
 
+    // quantised rows: descriptors of a pair of groups, and the rows each lane gathers from (instruction i covers rows
+    // 8i .. 8i+7 with 8 pieces of codes each, the parameter instruction rows lane/2)
+    constexpr int NGq = QuantTile<QB>::NG;
+    const size_t qpitch_k = quant_row_bytes(r_k, QB), qpitch_v = quant_row_bytes(r_v, QB);
+    const unsigned char *Qk = reinterpret_cast<const unsigned char *>(A_k) + (size_t)b * L * qpitch_k;
+    const unsigned char *Qv = reinterpret_cast<const unsigned char *>(A_v) + (size_t)b * L * qpitch_v;
+    unsigned char *Ct = reinterpret_cast<unsigned char *>(At);
+    auto qstage_of = [&](bool is_k, int pidx) __attribute__((always_inline)) {
+        QStage st;
+        const int r = is_k ? r_k : r_v, ng = r >> 5;  // quantisation groups of 32 ranks in a row
+        st.base = is_k ? Qk : Qv;
+        st.pitch = is_k ? qpitch_k : qpitch_v;
+        // groups beyond the row are replaced by group 0 (finite values that meet zero B fragments)
+        const int grp = 8 * pidx + (lane & 7), pg = 8 * pidx + 4 * (lane & 1);
+        st.code_off = 16 * (grp < ng ? grp : 0);
+        st.par_off = (r >> 1) + 4 * (pg < ng ? pg : 0);
+        return st;
+    };
+    auto q_tokens = [&](int tile, int (&tkc)[4], int &tkp) __attribute__((always_inline)) {
+        const int last = m_end > m_begin ? m_end - m_begin - 1 : 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = tile * TILE + w * 32 + 8 * i + (lane >> 3);
+            tkc[i] = tok_lds[m < m_end - m_begin ? m : last];
+        }
+        const int mp = tile * TILE + w * 32 + (lane >> 1);
+        tkp = tok_lds[mp < m_end - m_begin ? mp : last];
+    };
+
     // ---- prologue, in the order the steady state expects: B fragments of group 0, gathers of groups 0 and 1
 #pragma unroll
     for (int i = 0; i < 32 / WAVES; ++i)
         copy16_global_to_lds(packg + i * (WAVES * 64) + tid, dma_base(0) + i * (WAVES * 1024));
-    u32x4_t areg[2 * kGroup];
-    {
+    u32x4_t areg[QB == 0 ? 2 * kGroup : 1];
+    u32x4_t creg[NGq];
+    if constexpr (QB == 0) {
         const AStage s0 = stage_of(true, 0), s1 = stage_of(true, 1);
         int tk0[kGroup];
         tile_tokens(0, tk0);
@@ -265,6 +412,16 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
             areg[kGroup + j] = s1.base[(size_t)tk0[j] * s1.pieces + s1.piece];
             __builtin_amdgcn_sched_barrier(0);
         }
+    } else {
+        const QStage q0 = qstage_of(true, 0);
+        int tkc[4], tkp;
+        q_tokens(0, tkc, tkp);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            creg[i] = *reinterpret_cast<const u32x4_t *>(q0.base + (size_t)tkc[i] * q0.pitch + q0.code_off);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (QB == 4) creg[4] = *reinterpret_cast<const u32x4_t *>(q0.base + (size_t)tkp * q0.pitch + q0.par_off);
     }
 
     int gg = 0;  // group counter: group gg is read from buffer gg % 2
@@ -282,10 +439,25 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const u32x4_t *bs1 = packg + (size_t)((pi) * 2 + 1) * (kGroup * 256) + tid; /* second group of this pair */ \
     const u32x4_t *bs2 = packg + (size_t)(pn * 2) * (kGroup * 256) + tid;       /* first group of next pair */  \
     const int buf0 = gg & 1, buf1 = buf0 ^ 1
+        // the same for quantised rows: the pair after pair `pi`, its rows, and where the B fragments come from
+#define XKV_NEXT_PAIR_Q(pi)                                                                                   \
+    const bool wrap = (pi) + 1 == PT;                                                                         \
+    const int pn = wrap ? 0 : (pi) + 1;                                                                       \
+    const bool next_k = pn < PK;                                                                              \
+    const QStage qn = qstage_of(next_k, next_k ? pn : pn - PK);                                               \
+    int tkc[4], tkp;                                                                                          \
+    q_tokens(wrap ? (tile + 1 < n_tiles ? tile + 1 : tile) : tile, tkc, tkp);                                 \
+    const u32x4_t *bs1 = packg + (size_t)((pi) * 2 + 1) * (kGroup * 256) + tid;                               \
+    const u32x4_t *bs2 = packg + (size_t)(pn * 2) * (kGroup * 256) + tid
         for (int pi = 0; pi < PK; ++pi, gg += 2) {
-            XKV_NEXT_PAIR(pi);
-            run_group<true, 0, WAVES>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
-            run_group<true, kGroup, WAVES>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
+            if constexpr (QB == 0) {
+                XKV_NEXT_PAIR(pi);
+                run_group<true, 0, WAVES>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
+                run_group<true, kGroup, WAVES>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
+            } else {
+                XKV_NEXT_PAIR_Q(pi);
+                run_pair_q<true, WAVES, QB>(acc, creg, Bl, Ct, dma_base(0), dma_base(1), bs1, bs2, qn, tkc, tkp, lane);
+            }
         }
         {
                 if constexpr (ROPE) {
@@ -352,11 +524,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
                     for (int v = 0; v < 16; ++v) acc[db][v] = 0.0f;
         }
         for (int pi = PK; pi < PT; ++pi, gg += 2) {
-            XKV_NEXT_PAIR(pi);
-            run_group<false, 0, WAVES>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
-            run_group<false, kGroup, WAVES>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
+            if constexpr (QB == 0) {
+                XKV_NEXT_PAIR(pi);
+                run_group<false, 0, WAVES>(acc, areg, Bl, At, buf0, dma_base(buf1), bs1, an0, tkn, woff, rbase, lane);
+                run_group<false, kGroup, WAVES>(acc, areg, Bl, At, buf1, dma_base(buf0), bs2, an1, tkn, woff, rbase, lane);
+            } else {
+                XKV_NEXT_PAIR_Q(pi);
+                run_pair_q<false, WAVES, QB>(acc, creg, Bl, Ct, dma_base(0), dma_base(1), bs1, bs2, qn, tkc, tkp, lane);
+            }
         }
 #undef XKV_NEXT_PAIR
+#undef XKV_NEXT_PAIR_Q
         {
                 // (4) O += W V^, one dim block at a time through a scratch result tile
 #pragma unroll
@@ -476,7 +654,7 @@ hipError_t launch_pack_group(const xkv_shape &s, const void *B_k, const void *B_
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
                                      void *pack_ws, const void *B_packed, bool packed, float *part_o, float *part_ml,
-                                     hipStream_t st, const int32_t *counts, float rope_theta)
+                                     hipStream_t st, const int32_t *counts, float rope_theta, int qbits)
 {
     RopeTable rope{};
     const bool use_rope = rope_theta > 0.0f;
@@ -501,32 +679,42 @@ hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int laye
     const u32x4_t *bsrc = B_packed ? (const u32x4_t *)B_packed + (size_t)layer * s.H_kv * per_head : (const u32x4_t *)pa.pack;
     const size_t seq_stride = (B_packed ? (size_t)s.G : 1) * s.H_kv * per_head;
     dim3 grid((unsigned)((long long)p.sr_splits * s.H_kv * s.batch));
-#define XKV_GA_LAUNCH(WV, RP)                                                                                      \
+#define XKV_GA_LAUNCH(WV, RP, QB)                                                                                  \
     do {                                                                                                           \
         /* B, A tiles, Q, (rotation constants,) token ids */                                                      \
         const size_t lds = kLdsB + lds_a_bytes(WV) + kLdsQ + (RP ? 512 : 0) + (size_t)p.sr_chunk * 4;              \
         static DynamicLdsOnce attr;                                                                                \
-        e = attr.ensure((const void *)gather_attend_mfma_kernel<WV, RP>,                                           \
+        e = attr.ensure((const void *)gather_attend_mfma_kernel<WV, RP, QB>,                                       \
                         kLdsB + lds_a_bytes(WV) + kLdsQ + 512 + kMaxChunkTokens * 4);                              \
         if (e != hipSuccess) return e;                                                                             \
         profile_begin(1, st);                                                                                      \
-        hipLaunchKernelGGL((gather_attend_mfma_kernel<WV, RP>), grid, dim3(WV * 64), lds, st, (const bf16_t *)A_k, \
-                           (const bf16_t *)A_v, bsrc, seq_stride, (const u32x4_t *)pa.pack_q, idx, counts, part_o, \
-                           part_ml, s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.k, p.sr_splits, p.sr_chunk, F8k, F8v,      \
-                           p.scale, rope);                                                                         \
+        hipLaunchKernelGGL((gather_attend_mfma_kernel<WV, RP, QB>), grid, dim3(WV * 64), lds, st,                  \
+                           (const bf16_t *)A_k, (const bf16_t *)A_v, bsrc, seq_stride, (const u32x4_t *)pa.pack_q, \
+                           idx, counts, part_o, part_ml, s.L, s.r_k, s.r_v, s.H_kv, s.H_q, s.k, p.sr_splits,       \
+                           p.sr_chunk, F8k, F8v, p.scale, rope);                                                   \
         profile_end(1, st);                                                                                        \
+    } while (0)
+#define XKV_GA_LAUNCH_Q(WV, RP)                                                                                    \
+    do {                                                                                                           \
+        if (qbits == 4)                                                                                            \
+            XKV_GA_LAUNCH(WV, RP, 4);                                                                              \
+        else if (qbits == 3)                                                                                       \
+            XKV_GA_LAUNCH(WV, RP, 3);                                                                              \
+        else                                                                                                       \
+            XKV_GA_LAUNCH(WV, RP, 0);                                                                              \
     } while (0)
     if (p.ga_waves == 8) {
         if (use_rope)
-            XKV_GA_LAUNCH(8, true);
+            XKV_GA_LAUNCH_Q(8, true);
         else
-            XKV_GA_LAUNCH(8, false);
+            XKV_GA_LAUNCH_Q(8, false);
     } else {
         if (use_rope)
-            XKV_GA_LAUNCH(4, true);
+            XKV_GA_LAUNCH_Q(4, true);
         else
-            XKV_GA_LAUNCH(4, false);
+            XKV_GA_LAUNCH_Q(4, false);
     }
+#undef XKV_GA_LAUNCH_Q
 #undef XKV_GA_LAUNCH
     return hipGetLastError();
 }

@@ -478,11 +478,13 @@ xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int32_t c, 
     return hip_status(e);
 }
 
-xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
-                                  const void *B_k, const void *B_v, const void *q, const void *landmarks,
-                                  const int32_t *outliers, int32_t c, int32_t o, float rope_theta, const void *K_tail,
-                                  const void *V_tail, int32_t T, void *out, int32_t *rows_out, int32_t *count_out,
-                                  float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+// qbits: 0 = A_k, A_v in shape->dtype; 4 or 3 = rows of 4-bit / 3-bit codes
+static xkv_status sr_decode_landmark_impl(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                          int qbits, const void *B_k, const void *B_v, const void *q,
+                                          const void *landmarks, const int32_t *outliers, int32_t c, int32_t o,
+                                          float rope_theta, const void *K_tail, const void *V_tail, int32_t T, void *out,
+                                          int32_t *rows_out, int32_t *count_out, float *score_out, void *workspace,
+                                          size_t workspace_bytes, void *hip_stream)
 {
     xkv_status st = validate(shape);
     if (st != XKV_OK) return st;
@@ -496,6 +498,9 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     if (rope_theta > 0.0f && !rope_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
     if (!workspace || ((uintptr_t)workspace & 255u)) return XKV_ERR_INVALID_ARG;
     if (workspace_bytes < lp.total_decode) return XKV_ERR_WORKSPACE;
+    if (qbits != 0 && !gather_attend_quant_ok(lp.attend_shape, lp.attend_plan, A_k, A_v, B_k, B_v,
+                                              at<void>(workspace, lp.attend_plan.off_bpack), qbits))
+        return XKV_ERR_UNSUPPORTED;
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
     const Plan &ps = lp.score_plan, &pa = lp.attend_plan;
@@ -522,7 +527,7 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     const bool mfma = gather_attend_uses_mfma(pa, A_k, A_v, B_k, B_v, pack_ws);
     if (e == hipSuccess)
         e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, nullptr, false, part_o, part_ml,
-                                 stream, counts, rope_theta);
+                                 stream, counts, rope_theta, qbits);
     // the uncompressed tail, as in xkv_sr_decode_tail: a dense pass over its T tokens into a second set of partials
     int n_tail = 0;
     float *tail_o = at<float>(workspace, pa.off_tail_o), *tail_ml = at<float>(workspace, pa.off_tail_ml);
@@ -533,9 +538,55 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
     return hip_status(e);
 }
 
+xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                  const void *B_k, const void *B_v, const void *q, const void *landmarks,
+                                  const int32_t *outliers, int32_t c, int32_t o, float rope_theta, const void *K_tail,
+                                  const void *V_tail, int32_t T, void *out, int32_t *rows_out, int32_t *count_out,
+                                  float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return sr_decode_landmark_impl(shape, layer, A_k, A_v, 0, B_k, B_v, q, landmarks, outliers, c, o, rope_theta, K_tail,
+                                   V_tail, T, out, rows_out, count_out, score_out, workspace, workspace_bytes, hip_stream);
+}
+
+xkv_status xkv_sr_decode_landmark_q(const xkv_shape *shape, int32_t layer, const void *Aq_k, const void *Aq_v,
+                                    int32_t bits, const void *B_k, const void *B_v, const void *q, const void *landmarks,
+                                    const int32_t *outliers, int32_t c, int32_t o, float rope_theta, const void *K_tail,
+                                    const void *V_tail, int32_t T, void *out, int32_t *rows_out, int32_t *count_out,
+                                    float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (bits != 4 && bits != 3) return XKV_ERR_UNSUPPORTED;
+    return sr_decode_landmark_impl(shape, layer, Aq_k, Aq_v, bits, B_k, B_v, q, landmarks, outliers, c, o, rope_theta,
+                                   K_tail, V_tail, T, out, rows_out, count_out, score_out, workspace, workspace_bytes,
+                                   hip_stream);
+}
+
 }  // extern "C"
 
 extern "C" {
+
+// Stages 3-4 from rows of A^K, A^V given as 4-bit or 3-bit codes.
+xkv_status xkv_gather_attend_q(const xkv_shape *shape, int32_t layer, const void *Aq_k, const void *Aq_v, int32_t bits,
+                               const void *B_k, const void *B_v, const void *q, const int32_t *idx,
+                               const int32_t *counts, float rope_theta, void *out, void *workspace,
+                               size_t workspace_bytes, void *hip_stream)
+{
+    Plan p;
+    xkv_status st = prepare(shape, workspace, workspace_bytes, p);
+    if (st != XKV_OK) return st;
+    if (!Aq_k || !Aq_v || !B_k || !B_v || !q || !idx || !out || layer < 0 || layer >= shape->G)
+        return XKV_ERR_INVALID_ARG;
+    if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return XKV_ERR_INVALID_ARG;
+    if (rope_theta > 0.0f && !rope_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
+    void *pack_ws = at<void>(workspace, p.off_bpack);
+    if (!gather_attend_quant_ok(*shape, p, Aq_k, Aq_v, B_k, B_v, pack_ws, bits)) return XKV_ERR_UNSUPPORTED;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *part_o = at<float>(workspace, p.off_part_o), *part_ml = at<float>(workspace, p.off_part_ml);
+    hipError_t e = launch_gather_attend(*shape, p, layer, Aq_k, Aq_v, B_k, B_v, q, idx, pack_ws, nullptr, false, part_o,
+                                        part_ml, stream, counts, rope_theta, bits);
+    if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream);
+    return hip_status(e);
+}
 
 xkv_status xkv_gather_attend_ex(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx,
@@ -638,18 +689,18 @@ xkv_status xkv_attend_absorbed(const xkv_shape *shape, int32_t layer, const void
 xkv_status xkv_quantized_row_bytes(int32_t r, int32_t bits, size_t *bytes)
 {
     if (!bytes || r < 1) return XKV_ERR_INVALID_ARG;
-    if (bits != 4 || !quant_rank_ok(r)) return XKV_ERR_UNSUPPORTED;
-    *bytes = quant_row_bytes(r);
+    if ((bits != 4 && bits != 3) || !quant_rank_ok(r)) return XKV_ERR_UNSUPPORTED;
+    *bytes = quant_row_bytes(r, bits);
     return XKV_OK;
 }
 
 xkv_status xkv_quantize_rows(const void *X, int64_t rows, int32_t r, int32_t bits, void *out, void *hip_stream)
 {
     if (rows < 0 || r < 1) return XKV_ERR_INVALID_ARG;
-    if (bits != 4 || !quant_rank_ok(r)) return XKV_ERR_UNSUPPORTED;
+    if ((bits != 4 && bits != 3) || !quant_rank_ok(r)) return XKV_ERR_UNSUPPORTED;
     if (rows == 0) return XKV_OK;
     if (!X || !out || ((((uintptr_t)X) | ((uintptr_t)out)) & 15u)) return XKV_ERR_INVALID_ARG;
-    return hip_status(launch_quantize_rows(X, rows, r, out, (hipStream_t)hip_stream));
+    return hip_status(launch_quantize_rows(X, rows, r, bits, out, (hipStream_t)hip_stream));
 }
 
 xkv_status xkv_attend_absorbed_q4(const xkv_shape *shape, int32_t layer, const void *Aq_v, const void *B_v,
@@ -715,6 +766,44 @@ xkv_status xkv_sr_decode_absorbed_q4(const xkv_shape *shape, int32_t layer, cons
 {
     return sr_decode_absorbed_impl(shape, layer, Aq_k, Aq_v, B_k, B_v, q, K_tail, V_tail, T, out, idx_out, score_out,
                                    workspace, workspace_bytes, hip_stream, true);
+}
+
+// The gather-reconstruct step on 4-bit rows: scores from the quantised A^K (which also leaves the per-head scores in
+// the workspace, unused here), selection, then Eq. 3 and attention from the quantised rows.
+xkv_status xkv_sr_decode_q4(const xkv_shape *shape, int32_t layer, const void *Aq_k, const void *Aq_v, const void *B_k,
+                            const void *B_v, const void *q, float rope_theta, const void *K_tail, const void *V_tail,
+                            int32_t T, void *out, int32_t *idx_out, float *score_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream)
+{
+    if (T < 0 || (T > 0 && (!K_tail || !V_tail))) return XKV_ERR_INVALID_ARG;
+    Plan p;
+    AbsorbPlan a;
+    xkv_status st = prepare_absorbed(shape, workspace, workspace_bytes, p, a);
+    if (st != XKV_OK) return st;
+    if (!Aq_k || !Aq_v || !B_k || !B_v || !q || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
+    if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return XKV_ERR_INVALID_ARG;
+    if (rope_theta > 0.0f && !rope_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
+    void *pack_ws = at<void>(workspace, p.off_bpack);
+    if (!score_q4_shape_ok(*shape) || !gather_attend_quant_ok(*shape, p, Aq_k, Aq_v, B_k, B_v, pack_ws, 4))
+        return XKV_ERR_UNSUPPORTED;
+    if (((uintptr_t)q) & 15u) return XKV_ERR_INVALID_ARG;
+    if (shape->batch == 0) return XKV_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    float *S = score_out ? score_out : at<float>(workspace, p.off_score);
+    int32_t *idx = idx_out ? idx_out : at<int32_t>(workspace, p.off_idx);
+    uint32_t *hist = at<uint32_t>(workspace, p.off_hist), *state = at<uint32_t>(workspace, p.off_state);
+    float *part_o = at<float>(workspace, p.off_part_o), *part_ml = at<float>(workspace, p.off_part_ml);
+    hipError_t e = launch_score_q4_stage(*shape, p, layer, Aq_k, B_k, q, at<void>(workspace, p.off_p), S,
+                                         at<float>(workspace, a.off_heads), stream);
+    if (e == hipSuccess) e = launch_topk(*shape, p, S, idx, hist, state, false, stream);
+    if (e == hipSuccess)
+        e = launch_gather_attend(*shape, p, layer, Aq_k, Aq_v, B_k, B_v, q, idx, pack_ws, nullptr, false, part_o, part_ml,
+                                 stream, nullptr, rope_theta, 4);
+    int n_tail = 0;
+    float *tail_o = at<float>(workspace, p.off_tail_o), *tail_ml = at<float>(workspace, p.off_tail_ml);
+    if (T > 0 && e == hipSuccess) e = launch_tail(*shape, p, K_tail, V_tail, q, T, tail_o, tail_ml, &n_tail, stream);
+    if (e == hipSuccess) e = launch_combine(*shape, p.sr_splits, part_o, part_ml, out, stream, n_tail, tail_o, tail_ml);
+    return hip_status(e);
 }
 
 xkv_status xkv_head_scores_q4(const xkv_shape *shape, int32_t layer, const void *Aq_k, const void *B_k, const void *q,

@@ -169,7 +169,11 @@ hipError_t launch_topk(const xkv_shape &s, const Plan &p, const float *S, int32_
 hipError_t launch_gather_attend(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                 const void *B_k, const void *B_v, const void *q, const int32_t *idx, void *pack_ws,
                                 const void *B_packed, bool packed, float *part_o, float *part_ml, hipStream_t st,
-                                const int32_t *counts = nullptr, float rope_theta = 0.0f);
+                                const int32_t *counts = nullptr, float rope_theta = 0.0f, int qbits = 0);
+// qbits 4 or 3: A_k and A_v are rows of 4-bit / 3-bit codes (quant.hip); matrix-core shapes with ranks that are
+// multiples of 32 only (gather_attend_quant_ok).
+bool gather_attend_quant_ok(const xkv_shape &s, const Plan &p, const void *Aq_k, const void *Aq_v, const void *B_k,
+                            const void *B_v, const void *pack_ws, int qbits);
 // rope_theta > 0: the reconstructed key rows are rotated to their positions (RoPE base theta) before the scores.
 bool rope_shape_ok(const xkv_shape &s);
 bool gather_attend_uses_mfma(const Plan &p, const void *A_k, const void *A_v, const void *B_k, const void *B_v,
@@ -185,7 +189,8 @@ hipError_t launch_pack_group(const xkv_shape &s, const void *B_k, const void *B_
 hipError_t launch_gather_attend_mfma(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *A_v,
                                      const void *B_k, const void *B_v, const void *q, const int32_t *idx,
                                      void *pack_ws, const void *B_packed, bool packed, float *part_o, float *part_ml,
-                                     hipStream_t st, const int32_t *counts = nullptr, float rope_theta = 0.0f);
+                                     hipStream_t st, const int32_t *counts = nullptr, float rope_theta = 0.0f,
+                                     int qbits = 0);
 hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const void *V, const void *q, float *part_o,
                         float *part_ml, hipStream_t st);
 bool dense_mfma_shape_ok(const xkv_shape &s);
@@ -214,10 +219,12 @@ hipError_t launch_absorbed(const xkv_shape &s, const AbsorbPlan &a, int layer, c
 // a multiple of 16 (no padding when r is a multiple of 128).  The score kernels take multiples of 128 only.
 inline bool quant_rank_ok(int r) { return r > 0 && r % 32 == 0; }
 __host__ __device__ inline size_t quant_row_bytes(int r) { return ((size_t)r * 5 / 8 + 15) / 16 * 16; }
+// 3-bit rows: one 16-byte piece per group of 32 ranks (96 bits of codes, then step and offset), r / 2 bytes per row.
+__host__ __device__ inline size_t quant_row_bytes(int r, int bits) { return bits == 3 ? (size_t)r / 2 : quant_row_bytes(r); }
 bool score_q4_shape_ok(const xkv_shape &s);
 hipError_t launch_score_q4_stage(const xkv_shape &s, const Plan &p, int layer, const void *Aq_k, const void *B_k,
                                  const void *q, void *P_ws, float *S, float *S_heads, hipStream_t st);
-hipError_t launch_quantize_rows(const void *X, long long rows, int r, void *out, hipStream_t st);
+hipError_t launch_quantize_rows(const void *X, long long rows, int r, int bits, void *out, hipStream_t st);
 // Cross-layer factorization of the caches of one group (see factorize.hip).
 bool factorize_shape_ok(const xkv_shape &s, int r);
 size_t factorize_workspace_bytes(const xkv_shape &s, int r);

@@ -152,7 +152,8 @@ def test_quantised_calls_validate_on_the_host():
     c, null, one, al = good.c(), ctypes.c_void_p(0), ctypes.c_void_p(256), ctypes.c_void_p(4096)
     n = ctypes.c_size_t(0)
     assert xb.xkv_quantized_row_bytes(512) == 320 and xb.xkv_quantized_row_bytes(384) == 240     # 5r/8
-    assert lib.xkv_quantized_row_bytes(512, 3, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED          # 3-bit rows: not built
+    assert lib.xkv_quantized_row_bytes(512, 3, ctypes.byref(n)) == xb.XKV_OK and n.value == 256    # 3-bit rows: r/2
+    assert lib.xkv_quantized_row_bytes(512, 2, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED          # 2-bit rows: not built
     assert xb.xkv_quantized_row_bytes(96) == 64 and xb.xkv_quantized_row_bytes(576) == 368      # padded to 16 bytes
     assert lib.xkv_quantized_row_bytes(100, 4, ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED          # r % 32 != 0
     assert lib.xkv_quantized_row_bytes(512, 4, None) == xb.XKV_ERR_INVALID_ARG

@@ -646,3 +646,38 @@ def test_q4_pack_layout_and_round_trip():
     np.testing.assert_array_equal(c2, codes)
     np.testing.assert_array_equal(s2, step)
     np.testing.assert_array_equal(l2, lo)
+
+
+def test_q3_pack_layout_and_round_trip():
+    """3-bit rows: one 16-byte piece per group of 32 ranks, 12 bytes of codes + (step, lo); r/2 bytes per row, which is
+    the 4 bits per element behind the paper's 32x (App. 'Integrate with Quantization')."""
+    codes = (np.arange(64, dtype=np.uint8) % 8)[None, :].repeat(2, axis=0)
+    codes[1] = codes[1, ::-1]
+    step = np.array([[0.5, 2.0], [1.0, 0.25]], np.float32)
+    lo = np.array([[-1.0, 3.0], [0.0, -8.0]], np.float32)
+    p = oracle.pack_q3(codes, step, lo)
+    assert p.shape == (2, 32) and p.dtype == np.uint8                       # 64 ranks -> 32 bytes = 4 bits per element
+    # unit 0 = ranks 0..7 = codes 0..7: even ranks 0,2,4,6 -> 0 | 2<<3 | 4<<6 | 6<<9 = 0xD10 in bits 0..11,
+    # odd ranks 1,3,5,7 -> 1 | 3<<3 | 5<<6 | 7<<9 = 0xF59 in bits 12..23: the 24-bit unit is 0xF59D10
+    assert p[0, 0:3].tolist() == [0x10, 0x9D, 0xF5]
+    assert p[0, 3:6].tolist() == [0x10, 0x9D, 0xF5]                          # unit 1 holds the same codes (8..15 mod 8)
+    assert p[0, 12:16].tolist() == [0x00, 0x3F, 0x80, 0xBF]                 # bf16(0.5) = 0x3F00, bf16(-1) = 0xBF80
+    assert p[0, 28:32].tolist() == [0x00, 0x40, 0x40, 0x40]                 # bf16(2) = 0x4000, bf16(3) = 0x4040
+    c2, s2, l2 = oracle.unpack_q3(p, 64)
+    np.testing.assert_array_equal(c2, codes)
+    np.testing.assert_array_equal(s2, step)
+    np.testing.assert_array_equal(l2, lo)
+    rng = np.random.default_rng(8)
+    x = synth.to_storage(rng.standard_normal((9, 160)), "bf16")
+    c, s, l = oracle.quantize_rows(x, 3)
+    for a, b in zip(oracle.unpack_q3(oracle.pack_q3(c, s, l), 160), (c, s, l)):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_three_bit_quantiser_on_a_group_worked_by_hand():
+    # 32 values 0, 0.25, ..., 7.75: lo = 0, step = 7.75/7 = 1.10714.. -> bf16 = 1.109375 (0x3F8E), inv = fp32(1/step)
+    x = (np.arange(32, dtype=np.float32) * 0.25)[None, :]
+    codes, step, lo = oracle.quantize_rows(x, 3)
+    assert lo[0, 0] == 0.0 and step[0, 0] == np.float32(1.109375)
+    np.testing.assert_array_equal(codes[0], np.clip(np.rint(x[0] / 1.109375), 0, 7))
+    assert codes[0, 0] == 0 and codes[0, -1] == 7 and codes[0, 2] == 0 and codes[0, 3] == 1
