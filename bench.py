@@ -520,6 +520,47 @@ def main():
                                           "kernel_GBps": round(qb[kn] / (qk[kn] * 1e-3) / 1e9, 1)} for kn in qk},
                          "note": "xkv_sr_decode_absorbed_q4: both token bases as 4-bit round-to-nearest rows (groups of "
                                  "32 ranks, bf16 step and offset), de-quantised inside the score and row-sum kernels"}
+            # the gather-reconstruct form of the step on the same 4-bit rows (scores from the quantised A^K, Eq. 3 and
+            # attention from quantised rows: the form that still allows a rotation of the reconstructed keys), and
+            # its big kernel alone on 4-bit and on 3-bit rows
+            try:
+                def q4_gather_step():
+                    base = qstate["set0"]
+                    for grp in range(w.n_groups):
+                        s_i = (base + grp) % n_q
+                        g = groups[s_i]
+                        for l in range(w.G):
+                            xb.xkv_sr_decode_q4(shape, l, Aqk[s_i], Aqv[s_i], g["B_k"], g["B_v"], qs[s_i][l], out, None,
+                                                None, q_ws)
+                    qstate["set0"] = (base + w.n_groups) % n_q
+
+                q4_gather_step()
+                ms_qg = time_loop(torch, q4_gather_step, max(2, min(args.steps, 5)))
+                gk = {}
+                for bits in (4, 3):
+                    rbk, rbv = xb.xkv_quantized_row_bytes(w.r_k, bits), xb.xkv_quantized_row_bytes(w.r_v, bits)
+                    if bits == 4:
+                        ak3, av3 = Aqk[0], Aqv[0]
+                    else:
+                        ak3 = torch.empty((w.batch, w.L, rbk), dtype=torch.uint8, device="cuda")
+                        av3 = torch.empty((w.batch, w.L, rbv), dtype=torch.uint8, device="cuda")
+                        xb.xkv_quantize_rows(groups[0]["A_k"], w.batch * w.L, w.r_k, ak3, bits=3)
+                        xb.xkv_quantize_rows(groups[0]["A_v"], w.batch * w.L, w.r_v, av3, bits=3)
+                    ms_k = kernel_ms(xb.STAGE_GATHER_ATTEND,
+                                     lambda s_i, l: xb.xkv_gather_attend_q(shape, l, ak3, av3, bits, groups[0]["B_k"],
+                                                                           groups[0]["B_v"], qs[0][l], idx, None, 0.0,
+                                                                           out, ws))
+                    gbytes = w.batch * w.H_kv * w.k * (rbk + rbv)
+                    gk[f"gather_attend_q{bits}"] = {"kernel_ms": round(ms_k, 5), "alg_bytes": gbytes,
+                                                    "kernel_GBps": round(gbytes / (ms_k * 1e-3) / 1e9, 1),
+                                                    "bytes_per_row": {"A_k": rbk, "A_v": rbv}}
+                quantized["gather_reconstruct"] = {
+                    "ms_per_step": round(ms_qg, 4), "tokens_per_s": round(w.batch / (ms_qg * 1e-3), 2),
+                    "speedup_vs_bf16_gather_reconstruct": round(ms_sr / ms_qg, 3), "kernels": gk,
+                    "note": "xkv_sr_decode_q4: Eq. 3 and attention from 4-bit rows de-quantised in registers inside "
+                            "the matrix-core kernel; 3-bit rows through xkv_gather_attend_q (kernel time only)"}
+            except xb.XkvError as err:
+                quantized["gather_reconstruct"] = {"skipped": str(err)}
             del Aqk, Aqv, q_ws, heads_q
         except xb.XkvError as err:
             quantized = {"skipped": str(err)}

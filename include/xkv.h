@@ -179,20 +179,30 @@ XKV_API xkv_status xkv_reconstruct(const xkv_shape *shape, int32_t layer_in_grou
  * keys and for values, App. C.6): the caches of the G layers, X [batch][G][H_kv][L][d_h] in shape->dtype (layer l's
  * cache in the dense K/V layout above), are read as X_cat [L][n], n = G * H_kv * d_h, column l*d + g*d_h + j =
  * channel j of KV head g of layer l, and replaced by
- *   B_out [batch][G][r][H_kv*d_h]  r orthonormal rows (before rounding to shape->dtype) spanning the dominant
- *                                  rank-r right singular subspace of X_cat, cut into the per-layer blocks B_l,
- *   A_out [batch][L][r]            A = X_cat B^T, so that A [B_1 .. B_G] is X_cat projected onto that subspace.
- * The subspace is found by `iters` rounds of block power iteration on X_cat^T X_cat from a pseudo-random start
- * chosen by `seed` (randomised subspace iteration with Cholesky-QR as in App. B.3); the approximation error
- * ||X_cat - A B||_F approaches the optimum of Eq. 1 (the truncated SVD) as iters grows, 8 is a good default.  The
- * factors equal (U Sigma, V^T) of Eq. 1 up to an r x r rotation within the subspace, which no product A B_l sees.
+ *   B_out [batch][G][r][H_kv*d_h]  B = V^T: the r leading right singular vectors of X_cat as orthonormal rows (before
+ *                                  rounding to shape->dtype), in descending order of their singular values, cut into
+ *                                  the per-layer blocks B_l,
+ *   A_out [batch][L][r]            A = U Sigma = X_cat B^T, so that A^T A = Sigma^2 is diagonal and descending and
+ *                                  A [B_1 .. B_G] is the rank-r approximation of Eq. 1.
+ * The dominant subspace is found by `iters` rounds of block power iteration on X_cat^T X_cat from a pseudo-random start
+ * chosen by `seed` (randomised subspace iteration with Cholesky-QR as in App. B.3); inside it the r x r Rayleigh-Ritz
+ * matrix is diagonalised in fp64 (block Jacobi) and the basis rotated to the singular vectors.  The approximation
+ * error ||X_cat - A B||_F approaches the optimum of Eq. 1 (the truncated SVD) as iters grows, 8 is a good default;
+ * singular vectors are unique up to sign (and up to rotations among equal singular values).
+ * xkv_factorize_svd is the same with two options: r_out <= r writes only the leading r_out directions (A_out
+ * [batch][L][r_out], B_out [batch][G][r_out][H_kv*d_h]) of a subspace iteration run with r vectors -- the surplus
+ * r - r_out act as oversampling, and one run can serve ranks r_K != r_V (Sec. 4: r_K : r_V = 1 : 1.5) by truncation
+ * after the fact -- and sigma_out (nullable, device, fp32 [batch][r_out]) receives the singular values.
  * The layouts of A_out and B_out are those xkv_sr_decode takes.  shape->r_k, r_v, k, H_q, scale are ignored.
- * XKV_ERR_UNSUPPORTED unless d_h % 64 == 0, r <= min(1024, n) and n <= 16384; XKV_ERR_INVALID_ARG for iters < 1.
- * workspace: at least xkv_factorize_workspace_bytes() bytes, 256-byte aligned.
+ * XKV_ERR_UNSUPPORTED unless d_h % 64 == 0, r <= min(1024, n) and n <= 16384; XKV_ERR_INVALID_ARG for iters < 1 or
+ * r_out outside [1, r].  workspace: at least xkv_factorize_workspace_bytes() bytes (for r), 256-byte aligned.
  */
 XKV_API xkv_status xkv_factorize_workspace_bytes(const xkv_shape *shape, int32_t r, size_t *bytes);
 XKV_API xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32_t iters, uint32_t seed,
                                  void *A_out, void *B_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+XKV_API xkv_status xkv_factorize_svd(const xkv_shape *shape, const void *X, int32_t r, int32_t r_out, int32_t iters,
+                                     uint32_t seed, void *A_out, void *B_out, float *sigma_out, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream);
 
 /*
  * The paper's own selector for Selective Reconstruction (App. B.1 "Landmark-guided Chunk Selector", after ShadowKV),

@@ -20,6 +20,7 @@ DTYPES = {"f32": XKV_F32, "bf16": XKV_BF16}
 ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_static", "xkv_packed_b_bytes", "xkv_pack_b",
                 "xkv_sr_decode_packed", "xkv_sr_decode_tail", "xkv_dense_decode", "xkv_score",
                 "xkv_topk", "xkv_gather_attend", "xkv_reconstruct", "xkv_factorize_workspace_bytes", "xkv_factorize",
+                "xkv_factorize_svd",
                 "xkv_landmark_workspace_bytes", "xkv_landmarks", "xkv_sr_decode_landmark", "xkv_gather_attend_ex",
                 "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
                 "xkv_quantized_row_bytes", "xkv_quantize_rows", "xkv_attend_absorbed_q4", "xkv_head_scores_q4",
@@ -93,6 +94,7 @@ def load() -> ctypes.CDLL:
         lib.xkv_reconstruct.argtypes = [sp, i32, vp, vp, i32, vp, vp]
         lib.xkv_factorize_workspace_bytes.argtypes = [sp, i32, ctypes.POINTER(sz)]
         lib.xkv_factorize.argtypes = [sp, vp, i32, i32, ctypes.c_uint32, vp, vp, vp, sz, vp]
+        lib.xkv_factorize_svd.argtypes = [sp, vp, i32, i32, i32, ctypes.c_uint32, vp, vp, vp, vp, sz, vp]
         lib.xkv_landmark_workspace_bytes.argtypes = [sp, i32, i32, ctypes.POINTER(sz)]
         lib.xkv_landmarks.argtypes = [sp, vp, i32, i32, vp, vp, vp, vp, sz, vp]
         lib.xkv_sr_decode_landmark.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp, i32,
@@ -236,6 +238,12 @@ def xkv_factorize(shape, X, r, iters, seed, A_out, B_out, workspace, stream=None
     _check(load().xkv_factorize(ctypes.byref(shape.c()), _ptr(X), r, iters, seed, _ptr(A_out), _ptr(B_out),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "xkv_factorize")
+
+
+def xkv_factorize_svd(shape, X, r, r_out, iters, seed, A_out, B_out, sigma_out, workspace, stream=None):
+    _check(load().xkv_factorize_svd(ctypes.byref(shape.c()), _ptr(X), r, r_out, iters, seed, _ptr(A_out), _ptr(B_out),
+                                    _ptr(sigma_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                    _stream(stream)), "xkv_factorize_svd")
 
 
 def xkv_landmark_workspace_bytes(shape: Shape, c: int, o: int) -> int:

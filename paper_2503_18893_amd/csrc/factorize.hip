@@ -697,11 +697,265 @@ __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// (5) Rotation to singular vectors (Sec. 3.1 Eq. 1: A = U Sigma, B = V^T).  The iteration leaves an orthonormal basis
+// V of the dominant subspace; within it the Rayleigh-Ritz matrix M = V C V^T (= A^T A for A = X_cat V^T) is
+// diagonalised, M = R Lambda R^T, and V is replaced by R^T V with the eigenvalues in descending order, after which
+// A^T A = Lambda is diagonal and descending and any leading block of rows of B spans the best subspace of that size
+// that the basis contains.  M is r x r, symmetric positive semi-definite, fp64.
+//
+// Eigen-solver: one-sided (Hestenes) Jacobi on the columns of M itself, in blocks.  Plane rotations J are applied from
+// the right until the columns of M J are mutually orthogonal; then J^T M^2 J is diagonal, so J holds the eigenvectors
+// of M^2, which are those of M, and the column norms are the eigenvalues.  Both M J and J are stored transposed (row c
+// = column vector c), so a rotation touches two contiguous rows.  The r columns are cut into blocks of NC / 2; a launch
+// is one round of a round-robin tournament between blocks, workgroup = one pair of blocks: it loads its NC column
+// vectors into LDS, runs a complete inner tournament over them (wavefront = one column pair per inner round: three dot
+// products, one rotation), writes them back, and applies the accumulated NC x NC transform to its NC rows of J^T.
+// Workgroups of a launch touch disjoint rows; launch boundaries are the only synchronisation between rounds.
+// ------------------------------------------------------------------------------------------------
+
+// (4z) Wn[c][i] = Vt[i][c]: the basis in the layout the orthonormalisation reads, for its second pass.
+__global__ __launch_bounds__(256) void transpose_v_kernel(const float *__restrict__ Vt, float *__restrict__ Wn, int n, int r)
+{
+    __shared__ float tile[32][33];
+    Vt += (size_t)blockIdx.z * r * n;
+    Wn += (size_t)blockIdx.z * n * r;
+    const int c0 = blockIdx.x * 32, i0 = blockIdx.y * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = i0 + ty + 8 * u, c = c0 + tx;
+        tile[ty + 8 * u][tx] = (i < r && c < n) ? Vt[(size_t)i * n + c] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int c = c0 + ty + 8 * u, i = i0 + tx;
+        if (c < n && i < r) Wn[(size_t)c * r + i] = tile[tx][ty + 8 * u];
+    }
+}
+
+// (5a) M = V W with W = C V^T, fp64 accumulation: 32 x 32 tile per workgroup.
+__global__ __launch_bounds__(256) void ritz_matrix_kernel(const float *__restrict__ Vt, const float *__restrict__ Wn,
+                                                          double *__restrict__ M, int n, int r)
+{
+    __shared__ double sv[32][33], sw[32][33];
+    Vt += (size_t)blockIdx.z * r * n;
+    Wn += (size_t)blockIdx.z * n * r;
+    M += (size_t)blockIdx.z * r * r;
+    const int i0 = blockIdx.y * 32, j0 = blockIdx.x * 32, tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // ty 0..7
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int c0 = 0; c0 < n; c0 += 32) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = ty + 8 * u;
+            sv[row][tx] = (i0 + row < r && c0 + tx < n) ? (double)Vt[(size_t)(i0 + row) * n + c0 + tx] : 0.0;
+            sw[row][tx] = (c0 + row < n && j0 + tx < r) ? (double)Wn[(size_t)(c0 + row) * r + j0 + tx] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int c = 0; c < 32; ++c) {
+            const double wv = sw[c][tx];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = fma(sv[ty + 8 * u][c], wv, acc[u]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (i0 + ty + 8 * u < r && j0 + tx < r) M[(size_t)(i0 + ty + 8 * u) * r + j0 + tx] = acc[u];
+}
+
+// (5b) Gt = (M + M^T) / 2 (row c = column c of the symmetric matrix), Jt = identity.
+__global__ __launch_bounds__(256) void jacobi_init_kernel(const double *__restrict__ M, double *__restrict__ Gt,
+                                                          double *__restrict__ Jt, int r)
+{
+    M += (size_t)blockIdx.z * r * r;
+    Gt += (size_t)blockIdx.z * r * r;
+    Jt += (size_t)blockIdx.z * r * r;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)r * r) return;
+    const int i = (int)(idx / r), j = (int)(idx % r);
+    Gt[idx] = 0.5 * (M[idx] + M[(size_t)j * r + i]);
+    Jt[idx] = i == j ? 1.0 : 0.0;
+}
+
+// Opponent of player `who` in round `round` of a round-robin tournament of m players (m even): player m - 1 stays,
+// the others rotate.  Every pair meets exactly once in m - 1 rounds.
+__device__ __forceinline__ int fz_opponent(int who, int round, int m)
+{
+    const int q = m - 1;
+    if (who == q) return round % q;
+    if (who == round % q) return q;
+    return ((2 * round - who) % q + q) % q;
+}
+
+__device__ __forceinline__ double fz_wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// (5c) one tournament round between column blocks.  NC local columns (two blocks of NC / 2), NC / 2 wavefronts.
+template <int NC>
+__global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__restrict__ Gt, double *__restrict__ Jt, int r,
+                                                                  int n_blocks, int round)
+{
+    extern __shared__ double fz_sm[];
+    double *cols = fz_sm;                // [NC][r]
+    double *T = fz_sm + (size_t)NC * r;  // [NC][NC]: row c = coefficients of local column c in terms of the old ones
+    Gt += (size_t)blockIdx.z * r * r;
+    Jt += (size_t)blockIdx.z * r * r;
+    constexpr int BS = NC / 2, THREADS = NC / 2 * 64;
+    const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+    // this workgroup's pair of blocks: the blockIdx.x-th pair of the round
+    int P = -1, Q = -1;
+    {
+        int seen = 0;
+        for (int a = 0; a < n_blocks && P < 0; ++a) {
+            const int bq = fz_opponent(a, round, n_blocks);
+            if (a < bq) {
+                if (seen == (int)blockIdx.x) {
+                    P = a;
+                    Q = bq;
+                }
+                ++seen;
+            }
+        }
+    }
+    auto gcol = [&](int c) { return c < BS ? P * BS + c : Q * BS + (c - BS); };  // columns >= r do not exist
+    for (int idx = tid; idx < NC * r; idx += THREADS) {
+        const int c = idx / r, i = idx % r, gc = gcol(c);
+        cols[idx] = gc < r ? Gt[(size_t)gc * r + i] : 0.0;
+    }
+    for (int idx = tid; idx < NC * NC; idx += THREADS) T[idx] = (idx / NC == idx % NC) ? 1.0 : 0.0;
+    __syncthreads();
+    for (int t = 0; t < NC - 1; ++t) {
+        // wavefront w plays the w-th pair of the inner round
+        int a = -1, b = -1;
+        {
+            int seen = 0;
+            for (int x = 0; x < NC && a < 0; ++x) {
+                const int y = fz_opponent(x, t, NC);
+                if (x < y) {
+                    if (seen == w) {
+                        a = x;
+                        b = y;
+                    }
+                    ++seen;
+                }
+            }
+        }
+        if (gcol(a) < r && gcol(b) < r) {
+            double *ga = cols + (size_t)a * r, *gb = cols + (size_t)b * r;
+            double alpha = 0.0, beta = 0.0, gamma = 0.0;
+            for (int i = lane; i < r; i += kWave) {
+                const double x = ga[i], y = gb[i];
+                alpha = fma(x, y, alpha);
+                beta = fma(x, x, beta);
+                gamma = fma(y, y, gamma);
+            }
+            alpha = fz_wave_sum_f64(alpha);
+            beta = fz_wave_sum_f64(beta);
+            gamma = fz_wave_sum_f64(gamma);
+            // rotate unless the two columns are already orthogonal to working accuracy (or one of them is zero)
+            if (fabs(alpha) > 1e-15 * sqrt(beta * gamma) && beta > 0.0 && gamma > 0.0) {
+                const double zeta = (gamma - beta) / (2.0 * alpha);
+                const double tn = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+                const double cs = 1.0 / sqrt(1.0 + tn * tn), sn = cs * tn;
+                for (int i = lane; i < r; i += kWave) {
+                    const double x = ga[i], y = gb[i];
+                    ga[i] = cs * x - sn * y;
+                    gb[i] = sn * x + cs * y;
+                }
+                if (lane < NC) {
+                    const double x = T[a * NC + lane], y = T[b * NC + lane];
+                    T[a * NC + lane] = cs * x - sn * y;
+                    T[b * NC + lane] = sn * x + cs * y;
+                }
+            }
+        }
+        __syncthreads();
+    }
+    for (int idx = tid; idx < NC * r; idx += THREADS) {
+        const int c = idx / r, i = idx % r, gc = gcol(c);
+        if (gc < r) Gt[(size_t)gc * r + i] = cols[idx];
+    }
+    __syncthreads();
+    // the same transform on this workgroup's rows of J^T: load them where the columns were, combine, store
+    for (int idx = tid; idx < NC * r; idx += THREADS) {
+        const int c = idx / r, i = idx % r, gc = gcol(c);
+        cols[idx] = gc < r ? Jt[(size_t)gc * r + i] : 0.0;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < NC * r; idx += THREADS) {
+        const int c = idx / r, i = idx % r, gc = gcol(c);
+        if (gc >= r) continue;
+        double v = 0.0;
+#pragma unroll 8
+        for (int c2 = 0; c2 < NC; ++c2) v = fma(T[c * NC + c2], cols[(size_t)c2 * r + i], v);
+        Jt[(size_t)gc * r + i] = v;
+    }
+}
+
+// (5d) eigenvalues = norms of the rows of Gt; order[k] = the column with the k-th largest one (ties: smaller index);
+// sigma (nullable) receives the singular values sqrt(lambda) of the leading r_out, in that order.
+__global__ __launch_bounds__(1024) void ritz_order_kernel(const double *__restrict__ Gt, int *__restrict__ order,
+                                                          float *__restrict__ sigma, int r, int r_out)
+{
+    __shared__ double lam[1024];
+    Gt += (size_t)blockIdx.x * r * r;
+    order += (size_t)blockIdx.x * r;
+    const int lane = lane_id(), w = wave_id();
+    for (int c = w; c < r; c += 16) {
+        double sum = 0.0;
+        for (int i = lane; i < r; i += kWave) sum = fma(Gt[(size_t)c * r + i], Gt[(size_t)c * r + i], sum);
+        sum = fz_wave_sum_f64(sum);
+        if (lane == 0) lam[c] = sqrt(sum);
+    }
+    __syncthreads();
+    const int c = threadIdx.x;
+    if (c < r) {
+        int rank = 0;
+        const double mine = lam[c];
+        for (int j = 0; j < r; ++j) rank += (lam[j] > mine || (lam[j] == mine && j < c)) ? 1 : 0;
+        order[rank] = c;
+        if (sigma && rank < r_out) sigma[(size_t)blockIdx.x * r_out + rank] = (float)sqrt(mine);
+    }
+}
+
+// (5e) the leading r_out rotated basis vectors: Vr[k][c] = sum_j Jt[order[k]][j] Vt[j][c], thread = column c, eight k.
+__global__ __launch_bounds__(256) void rotate_basis_kernel(const double *__restrict__ Jt, const int *__restrict__ order,
+                                                           const float *__restrict__ Vt, float *__restrict__ Vr, int n,
+                                                           int r, int r_out, long long vr_seq)
+{
+    Jt += (size_t)blockIdx.z * r * r;
+    order += (size_t)blockIdx.z * r;
+    Vt += (size_t)blockIdx.z * r * n;
+    Vr += (size_t)blockIdx.z * vr_seq;
+    const int c = blockIdx.x * 256 + threadIdx.x, k0 = blockIdx.y * 8;
+    const double *jrow[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) jrow[u] = Jt + (size_t)order[k0 + u < r_out ? k0 + u : r_out - 1] * r;
+    double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    const int cc = c < n ? c : n - 1;
+    for (int j = 0; j < r; ++j) {
+        const double v = (double)Vt[(size_t)j * n + cc];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc[u] = fma(jrow[u][j], v, acc[u]);
+    }
+    if (c < n)
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (k0 + u < r_out) Vr[(size_t)(k0 + u) * n + c] = (float)acc[u];
+}
+
 // (4a) B_out[l][i][c] = Vt[i][l * d + c] in the storage type.
 template <typename T>
-__global__ __launch_bounds__(256) void write_b_kernel(const float *__restrict__ Vt, T *__restrict__ B, int G, int r, int d)
+__global__ __launch_bounds__(256) void write_b_kernel(const float *__restrict__ Vt, long long vt_seq, T *__restrict__ B,
+                                                      int G, int r, int d)
 {
-    Vt += (size_t)blockIdx.z * G * d * r;
+    Vt += (size_t)blockIdx.z * vt_seq;
     B += (size_t)blockIdx.z * G * r * d;
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)G * r * d) return;
@@ -774,9 +1028,11 @@ template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, int n
 
 inline unsigned blocks256(long long count) { return (unsigned)((count + 255) / 256); }
 
+constexpr int kJacobiSweeps = 8;  // sweeps of the block Jacobi eigen-solver (each: every pair of column blocks once)
+
 template <typename T>
-hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X, int r, int iters, uint32_t seed,
-                           void *A_out, void *B_out, unsigned char *ws, hipStream_t st)
+hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X, int r, int r_out, int iters, uint32_t seed,
+                           void *A_out, void *B_out, float *sigma_out, unsigned char *ws, hipStream_t st)
 {
     const int n = f.n, d = s.H_kv * s.d_h, tn = (n + kGemmTile - 1) / kGemmTile, tr = (r + kGemmTile - 1) / kGemmTile;
     constexpr int E = 128 / (int)sizeof(T);
@@ -811,17 +1067,8 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
         }
         hipLaunchKernelGGL(init_v_kernel, dim3(blocks256(vcount), 1, nb), dim3(256), 0, st, Vt, vcount,
                            seed + 0x9E37u * (uint32_t)b0);
-        for (int it = 0; it < iters; ++it) {
-            GemmArgs a{};  // Wn [n][r] = C Vt^T
-            a.P = GemmOperand{C, n, 0, n, n, (long long)n * n};
-            a.Q = GemmOperand{Vt, n, 0, n, r, vcount};
-            a.n_slabs = n / 32; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
-            a.out_f32 = f.w_splits > 1 ? part : Wn; a.out_bf16 = nullptr; a.ldo = r; a.plane = vcount;
-            a.out_seq = f.w_splits > 1 ? (long long)f.part_seq : vcount;
-            if ((e = launch_gemm<float>(a, tn * tr, nb, st)) != hipSuccess) break;
-            if (f.w_splits > 1)
-                hipLaunchKernelGGL(sum_planes_kernel, dim3(blocks256(vcount), 1, nb), dim3(256), 0, st, part, Wn, vcount,
-                                   f.w_splits, vcount, (long long)f.part_seq);
+        // Vt <- orthonormal basis of the columns of Wn (Cholesky-QR: r x r Gram matrix, Cholesky factor, solve; fp64)
+        auto orthonormalise = [&]() {
             const int gb = (r + 31) / 32, pairs = gb * (gb + 1) / 2;
             hipLaunchKernelGGL(gram_f64_kernel, dim3((pairs + 3) / 4, f.g_splits, nb), dim3(256), 0, st, Wn, planes, n, r,
                                f.g_splits, pairs);
@@ -838,21 +1085,83 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
                 hipLaunchKernelGGL((orth_solve_kernel<8, 2>), dim3((n + 31) / 32, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
             else
                 hipLaunchKernelGGL((orth_solve_kernel<16, 1>), dim3((n + 15) / 16, 1, nb), dim3(256), 0, st, Wn, Lt, Minv, Vt, n, r);
+        };
+        for (int it = 0; it < iters; ++it) {
+            GemmArgs a{};  // Wn [n][r] = C Vt^T
+            a.P = GemmOperand{C, n, 0, n, n, (long long)n * n};
+            a.Q = GemmOperand{Vt, n, 0, n, r, vcount};
+            a.n_slabs = n / 32; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
+            a.out_f32 = f.w_splits > 1 ? part : Wn; a.out_bf16 = nullptr; a.ldo = r; a.plane = vcount;
+            a.out_seq = f.w_splits > 1 ? (long long)f.part_seq : vcount;
+            if ((e = launch_gemm<float>(a, tn * tr, nb, st)) != hipSuccess) break;
+            if (f.w_splits > 1)
+                hipLaunchKernelGGL(sum_planes_kernel, dim3(blocks256(vcount), 1, nb), dim3(256), 0, st, part, Wn, vcount,
+                                   f.w_splits, vcount, (long long)f.part_seq);
+            orthonormalise();
         }
         if (e != hipSuccess) break;
-        T *Bb = reinterpret_cast<T *>(B_out) + (size_t)b0 * s.G * r * d;
-        T *Ab = reinterpret_cast<T *>(A_out) + (size_t)b0 * s.L * r;
-        const long long bcount = (long long)s.G * r * d;
-        hipLaunchKernelGGL(write_b_kernel<T>, dim3(blocks256(bcount), 1, nb), dim3(256), 0, st, Vt, Bb, s.G, r, d);
+        // Cholesky-QR once more on the basis itself: after the last multiplication by C the weakest directions are
+        // orthonormal only to fp32 rounding times the spread of the spectrum; a second pass on a matrix that is already
+        // nearly orthonormal brings them to fp32 rounding
+        hipLaunchKernelGGL(transpose_v_kernel, dim3((n + 31) / 32, (r + 31) / 32, nb), dim3(256), 0, st, Vt, Wn, n, r);
+        orthonormalise();
+        if (e != hipSuccess) break;
+        // ---- rotation to singular vectors (5): Wn = C Vt^T once more, M = Vt Wn, eigenvectors of M by block Jacobi
+        {
+            GemmArgs a{};
+            a.P = GemmOperand{C, n, 0, n, n, (long long)n * n};
+            a.Q = GemmOperand{Vt, n, 0, n, r, vcount};
+            a.n_slabs = n / 32; a.splits = f.w_splits; a.lower_only = 0; a.tiles_n = tr;
+            a.out_f32 = f.w_splits > 1 ? part : Wn; a.out_bf16 = nullptr; a.ldo = r; a.plane = vcount;
+            a.out_seq = f.w_splits > 1 ? (long long)f.part_seq : vcount;
+            if ((e = launch_gemm<float>(a, tn * tr, nb, st)) != hipSuccess) break;
+            if (f.w_splits > 1)
+                hipLaunchKernelGGL(sum_planes_kernel, dim3(blocks256(vcount), 1, nb), dim3(256), 0, st, part, Wn, vcount,
+                                   f.w_splits, vcount, (long long)f.part_seq);
+        }
+        double *Mr = planes, *Gt = Gm, *Jt = Lt;  // r x r each per sequence
+        int *order = reinterpret_cast<int *>(Minv);
+        const int rb = (r + 31) / 32;
+        hipLaunchKernelGGL(ritz_matrix_kernel, dim3(rb, rb, nb), dim3(256), 0, st, Vt, Wn, Mr, n, r);
+        hipLaunchKernelGGL(jacobi_init_kernel, dim3(blocks256((long long)r * r), 1, nb), dim3(256), 0, st, Mr, Gt, Jt, r);
+        {
+            const int nc = r <= 512 ? 32 : 16, bs = nc / 2;
+            const int n_blocks = std::max(2, ((r + bs - 1) / bs + 1) / 2 * 2);  // an even number of column blocks
+            const size_t lds = ((size_t)nc * r + (size_t)nc * nc) * 8;
+            static DynamicLdsOnce attr32, attr16;
+            e = nc == 32 ? attr32.ensure((const void *)jacobi_round_kernel<32>, 160 * 1024 - 256)
+                         : attr16.ensure((const void *)jacobi_round_kernel<16>, 160 * 1024 - 256);
+            if (e != hipSuccess) break;
+            for (int sweep = 0; sweep < kJacobiSweeps; ++sweep)
+                for (int round = 0; round < n_blocks - 1; ++round) {
+                    if (nc == 32)
+                        hipLaunchKernelGGL(jacobi_round_kernel<32>, dim3(n_blocks / 2, 1, nb), dim3(16 * 64), lds, st, Gt, Jt,
+                                           r, n_blocks, round);
+                    else
+                        hipLaunchKernelGGL(jacobi_round_kernel<16>, dim3(n_blocks / 2, 1, nb), dim3(8 * 64), lds, st, Gt, Jt, r,
+                                           n_blocks, round);
+                }
+        }
+        hipLaunchKernelGGL(ritz_order_kernel, dim3(nb), dim3(1024), 0, st, Gt, order,
+                           sigma_out ? sigma_out + (size_t)b0 * r_out : nullptr, r, r_out);
+        float *Vr = Wn;  // [r_out][n] per sequence, in the place of W
+        hipLaunchKernelGGL(rotate_basis_kernel, dim3((n + 255) / 256, (r_out + 7) / 8, nb), dim3(256), 0, st, Jt, order, Vt,
+                           Vr, n, r, r_out, vcount);
+        if ((e = hipGetLastError()) != hipSuccess) break;
+        T *Bb = reinterpret_cast<T *>(B_out) + (size_t)b0 * s.G * r_out * d;
+        T *Ab = reinterpret_cast<T *>(A_out) + (size_t)b0 * s.L * r_out;
+        const long long bcount = (long long)s.G * r_out * d;
+        const int tro = (r_out + kGemmTile - 1) / kGemmTile;
+        hipLaunchKernelGGL(write_b_kernel<T>, dim3(blocks256(bcount), 1, nb), dim3(256), 0, st, Vr, vcount, Bb, s.G, r_out, d);
         {  // A = X_cat B^T
             GemmArgs a{};
             a.P = GemmOperand{Xb, s.d_h, (long long)s.L * s.d_h, s.d_h, s.L, x_seq};
-            a.Q = GemmOperand{Bb, d, (long long)r * d, d, r, bcount};
-            a.n_slabs = n / E; a.splits = 1; a.lower_only = 0; a.tiles_n = tr;
+            a.Q = GemmOperand{Bb, d, (long long)r_out * d, d, r_out, bcount};
+            a.n_slabs = n / E; a.splits = 1; a.lower_only = 0; a.tiles_n = tro;
             a.out_f32 = sizeof(T) == 4 ? reinterpret_cast<float *>(Ab) : nullptr;
             a.out_bf16 = sizeof(T) == 2 ? reinterpret_cast<bf16_t *>(Ab) : nullptr;
-            a.ldo = r; a.plane = 0; a.out_seq = (long long)s.L * r;
-            e = launch_gemm<T>(a, ((s.L + kGemmTile - 1) / kGemmTile) * tr, nb, st);
+            a.ldo = r_out; a.plane = 0; a.out_seq = (long long)s.L * r_out;
+            e = launch_gemm<T>(a, ((s.L + kGemmTile - 1) / kGemmTile) * tro, nb, st);
         }
         if (e == hipSuccess) e = hipGetLastError();
     }
@@ -869,13 +1178,15 @@ bool factorize_shape_ok(const xkv_shape &s, int r)
 
 size_t factorize_workspace_bytes(const xkv_shape &s, int r) { return fz_layout(s, r).total; }
 
-hipError_t launch_factorize(const xkv_shape &s, const void *X, int r, int iters, uint32_t seed, void *A_out, void *B_out,
-                            void *ws, hipStream_t st)
+hipError_t launch_factorize(const xkv_shape &s, const void *X, int r, int r_out, int iters, uint32_t seed, void *A_out,
+                            void *B_out, float *sigma_out, void *ws, hipStream_t st)
 {
     const FzLayout f = fz_layout(s, r);
     if (s.dtype == XKV_F32)
-        return factorize_typed<float>(s, f, X, r, iters, seed, A_out, B_out, reinterpret_cast<unsigned char *>(ws), st);
-    return factorize_typed<bf16_t>(s, f, X, r, iters, seed, A_out, B_out, reinterpret_cast<unsigned char *>(ws), st);
+        return factorize_typed<float>(s, f, X, r, r_out, iters, seed, A_out, B_out, sigma_out,
+                                      reinterpret_cast<unsigned char *>(ws), st);
+    return factorize_typed<bf16_t>(s, f, X, r, r_out, iters, seed, A_out, B_out, sigma_out,
+                                   reinterpret_cast<unsigned char *>(ws), st);
 }
 
 }  // namespace xkv

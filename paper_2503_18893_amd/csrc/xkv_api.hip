@@ -379,18 +379,26 @@ xkv_status xkv_factorize_workspace_bytes(const xkv_shape *shape, int32_t r, size
     return XKV_OK;
 }
 
-xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32_t iters, uint32_t seed, void *A_out,
-                         void *B_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+xkv_status xkv_factorize_svd(const xkv_shape *shape, const void *X, int32_t r, int32_t r_out, int32_t iters, uint32_t seed,
+                             void *A_out, void *B_out, float *sigma_out, void *workspace, size_t workspace_bytes,
+                             void *hip_stream)
 {
     xkv_status st = validate(shape);
     if (st != XKV_OK) return st;
-    if (!X || !A_out || !B_out || r < 1 || iters < 1) return XKV_ERR_INVALID_ARG;
+    if (!X || !A_out || !B_out || r < 1 || iters < 1 || r_out < 1 || r_out > r) return XKV_ERR_INVALID_ARG;
     if (!factorize_shape_ok(*shape, r)) return XKV_ERR_UNSUPPORTED;
     if (shape->batch == 0) return XKV_OK;
     if (!workspace || ((uintptr_t)workspace & 255u) != 0 || workspace_bytes < factorize_workspace_bytes(*shape, r))
         return XKV_ERR_WORKSPACE;
     if ((((uintptr_t)X | (uintptr_t)A_out | (uintptr_t)B_out) & 15u) != 0) return XKV_ERR_INVALID_ARG;
-    return hip_status(launch_factorize(*shape, X, r, iters, seed, A_out, B_out, workspace, (hipStream_t)hip_stream));
+    return hip_status(launch_factorize(*shape, X, r, r_out, iters, seed, A_out, B_out, sigma_out, workspace,
+                                       (hipStream_t)hip_stream));
+}
+
+xkv_status xkv_factorize(const xkv_shape *shape, const void *X, int32_t r, int32_t iters, uint32_t seed, void *A_out,
+                         void *B_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return xkv_factorize_svd(shape, X, r, r, iters, seed, A_out, B_out, nullptr, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -234,7 +234,8 @@ hipError_t launch_landmarks(const xkv_shape &s, const void *K_rope, int c, void 
 hipError_t launch_identity(const xkv_shape &s, void *B, int copies, hipStream_t st);
 hipError_t launch_expand_chunks(const xkv_shape &s, const int32_t *chunks, int k_ch, const int32_t *outliers, int o, int c,
                                 int32_t *rows, int32_t *counts, hipStream_t st);
-hipError_t launch_factorize(const xkv_shape &s, const void *X, int r, int iters, uint32_t seed, void *A_out, void *B_out,
-                            void *ws, hipStream_t st);
+// r_out <= r: how many of the leading singular directions are written; sigma_out (nullable) [batch][r_out].
+hipError_t launch_factorize(const xkv_shape &s, const void *X, int r, int r_out, int iters, uint32_t seed, void *A_out,
+                            void *B_out, float *sigma_out, void *ws, hipStream_t st);
 
 }  // namespace xkv

@@ -1,7 +1,10 @@
 """GPU parity of xkv_factorize (Cross-Layer Factorization, Sec. 3.1, Eq. 1) against the CPU oracle.
 
-The factors of Eq. 1 are unique only up to a rotation inside the rank-r subspace (and the GPU path finds that
-subspace iteratively, App. B.3), so the comparison is on what is unique:
+The GPU path finds the rank-r subspace iteratively (App. B.3) and then rotates its basis to the singular vectors,
+which are unique up to sign where the singular values are distinct; the comparison is on what is unique:
+  * A^T A is diagonal and descending, its diagonal the squared singular values (also returned by
+    xkv_factorize_svd), against the oracle's / LAPACK's where the iteration has converged (Eq. 1: A = U Sigma);
+  * a leading block of r_out < r directions is the best rank-r_out approximation the subspace offers;
   * the approximation error ||X_cat - A B||_F^2 against the optimum sum_{i>r} sigma_i^2 of the oracle's exact
     truncated SVD (Eckart-Young), within 2 % of the optimum plus the rounding of A and B to the storage type;
   * the well-separated leading right singular vectors of the oracle lie in the row space of B;
@@ -220,6 +223,89 @@ def test_factorize_edge_shapes(G, H_kv, d_h, L, r, batch, dtype):
         assert np.abs(B[b] @ B[b].T - np.eye(r)).max() <= ORTH[dtype]
     if r == n:
         assert np.sum((synth.cache_as_matrix(caches[0]) - A[0] @ B[0]) ** 2) <= 1e-9 * tot
+
+
+# what the rotation to singular vectors leaves of A^T A beside its diagonal, relative to the largest eigenvalue: the
+# Rayleigh-Ritz matrix is formed from fp32 products (f32: 1e-6 sigma_1^2), and B is rounded to the storage type before A
+# is formed from it (bf16: 2^-9 per element)
+OFFDIAG = {"bf16": 1e-2, "f32": 1e-4}
+
+
+def gpu_factorize_svd(caches, G, H_kv, d_h, L, r, r_out, dtype, iters=ITERS, seed=7):
+    torch = torch_mod()
+    batch = len(caches)
+    shape = xb.Shape(G=G, H_kv=H_kv, H_q=H_kv, d_h=d_h, r_k=r, r_v=r, L=L, k=1, batch=batch, dtype=dtype)
+    X = synth.to_device({"X": np.stack(caches)}, dtype)["X"]
+    dt = synth.torch_dtype(dtype)
+    A = torch.zeros((batch, L, r_out), dtype=dt, device="cuda")
+    B = torch.zeros((batch, G, r_out, H_kv * d_h), dtype=dt, device="cuda")
+    sig = torch.zeros((batch, r_out), dtype=torch.float32, device="cuda")
+    ws = torch.empty(xb.xkv_factorize_workspace_bytes(shape, r), dtype=torch.uint8, device="cuda")
+    xb.xkv_factorize_svd(shape, X, r, r_out, iters, seed, A, B, sig, ws)
+    torch.cuda.synchronize()
+    A64 = synth.storage_to_f64(synth.to_host(A))
+    B64 = synth.storage_to_f64(synth.to_host(B)).transpose(0, 2, 1, 3).reshape(batch, r_out, G * H_kv * d_h)
+    return A64, B64, sig.cpu().numpy().astype(np.float64)
+
+
+SVD_CASES = {
+    # name: G, H_kv, d_h, L, r, batch, dtype, decay, iters
+    "f32_r48": (2, 2, 64, 1000, 48, 2, "f32", 0.7, 12),
+    "bf16_r100": (5, 1, 64, 2500, 100, 1, "bf16", 0.7, 8),
+    "bf16_steep_r30": (1, 2, 128, 700, 30, 1, "bf16", 1.2, 8),
+    "bf16_r512_n1024": (2, 4, 128, 3000, 512, 1, "bf16", 0.8, 8),      # 32 column blocks of the eigen-solver
+    "f32_r640_n1024": (2, 4, 128, 2000, 640, 1, "f32", 0.8, 8),        # the 16-column form of the eigen-solver
+}
+
+
+@pytest.mark.parametrize("name", list(SVD_CASES))
+def test_factors_are_u_sigma_and_v_transposed(name):
+    """Sec. 3.1, Eq. 1: A = U Sigma, B = V^T.  A^T A diagonal and descending, equal to the returned sigma^2; B B^T = I;
+    singular values against the exact ones where the subspace iteration has separated them."""
+    G, H_kv, d_h, L, r, batch, dtype, decay, iters = SVD_CASES[name]
+    rng = np.random.default_rng(np.random.SeedSequence([41, len(name)]))
+    caches = [synth.make_cache(rng, G, H_kv, d_h, L, decay, dtype=dtype) for _ in range(batch)]
+    A, B, sig = gpu_factorize_svd(caches, G, H_kv, d_h, L, r, r, dtype, iters=iters)
+    for b in range(batch):
+        X = synth.cache_as_matrix(caches[b])
+        sv = np.linalg.svd(X, compute_uv=False)
+        AtA = A[b].T @ A[b]
+        lam = np.diag(AtA)
+        off = AtA - np.diag(lam)
+        assert np.abs(off).max() <= OFFDIAG[dtype] * lam.max(), (name, b, np.abs(off).max() / lam.max())
+        # descending (neighbours may swap inside the rounding of the storage type)
+        assert (lam[1:] <= lam[:-1] * (1 + 4 * OFFDIAG[dtype])).all()
+        np.testing.assert_allclose(sig[b] ** 2, lam, rtol=4 * OFFDIAG[dtype], atol=OFFDIAG[dtype] * lam.max())
+        assert np.abs(B[b] @ B[b].T - np.eye(r)).max() <= ORTH[dtype]
+        # converged part of the spectrum: singular values well above the last one kept
+        lead = int(np.sum(sv[:r] >= 2.5 * sv[r - 1]))
+        np.testing.assert_allclose(sig[b][:lead], sv[:lead], rtol=1e-2)
+        # and the rotation has not changed the subspace: error against the optimum as before
+        opt, tot = float(np.sum(sv[r:] ** 2)), float(np.sum(sv ** 2))
+        res = float(np.sum((X - A[b] @ B[b]) ** 2))
+        assert opt * (1 - 1e-9) <= res <= 1.02 * opt + ROUND_SQ[dtype] * tot, (name, b, res / opt)
+
+
+def test_leading_block_of_a_larger_run_is_a_good_smaller_factorization():
+    """r_out < r: the leading r_out directions of a run with r vectors.  They are the first rows of the full result
+    (same run), their error is within 2 % of the rank-r_out optimum (the surplus vectors act as oversampling), and
+    one run serves two ranks (keys at r_out, values at r: Sec. 4, r_K : r_V = 1 : 1.5)."""
+    G, H_kv, d_h, L, r, r_out, dtype = 2, 2, 64, 1500, 96, 64, "bf16"
+    rng = np.random.default_rng(17)
+    cache = synth.make_cache(rng, G, H_kv, d_h, L, 0.7, dtype=dtype)
+    X = synth.cache_as_matrix(cache)
+    A_full, B_full, sig_full = gpu_factorize_svd([cache], G, H_kv, d_h, L, r, r, dtype)
+    A_lead, B_lead, sig_lead = gpu_factorize_svd([cache], G, H_kv, d_h, L, r, r_out, dtype)
+    np.testing.assert_array_equal(B_lead[0], B_full[0][:r_out])
+    np.testing.assert_array_equal(sig_lead[0], sig_full[0][:r_out])
+    np.testing.assert_allclose(A_lead[0], A_full[0][:, :r_out], rtol=0, atol=2.0 ** -7 * np.abs(A_full[0]).max())
+    sv = np.linalg.svd(X, compute_uv=False)
+    opt, tot = float(np.sum(sv[r_out:] ** 2)), float(np.sum(sv ** 2))
+    res = float(np.sum((X - A_lead[0] @ B_lead[0]) ** 2))
+    assert opt * (1 - 1e-9) <= res <= 1.02 * opt + ROUND_SQ[dtype] * tot, res / opt
+    # a run with only r_out vectors and the same number of iterations is no better than the truncated larger run
+    A_small, B_small, _ = gpu_factorize_svd([cache], G, H_kv, d_h, L, r_out, r_out, dtype)
+    assert res <= float(np.sum((X - A_small[0] @ B_small[0]) ** 2)) * (1 + 1e-3)
 
 
 def test_factorize_of_an_empty_batch_is_a_no_op():

@@ -326,8 +326,9 @@ def test_quantised_calls_reject_what_they_do_not_cover():
     with pytest.raises(xb.XkvError) as ei:
         xb.xkv_quantized_row_bytes(100)
     assert ei.value.status == xb.XKV_ERR_UNSUPPORTED
+    assert xb.xkv_quantized_row_bytes(128, bits=3) == 64           # 3-bit rows: r/2 bytes
     with pytest.raises(xb.XkvError) as ei:
-        xb.xkv_quantized_row_bytes(128, bits=3)
+        xb.xkv_quantized_row_bytes(128, bits=2)
     assert ei.value.status == xb.XKV_ERR_UNSUPPORTED
     w = synth.TINY.with_(r_v=128, G=1, H_kv=2, H_q=4)       # fp32 shape: quantised rows go with bf16 shapes only
     shape = xb.Shape.of(w)
