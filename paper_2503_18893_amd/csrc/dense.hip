@@ -95,6 +95,8 @@ __global__ __launch_bounds__(256) void dense_generic_kernel(const T *__restrict_
 // Merge the split partials of one (sequence, query head) with the log-sum-exp rule and write
 // the normalised output in the storage dtype.  A partial that saw no token has max = -inf.
 // ------------------------------------------------------------------------------------------
+constexpr int kMaxCombineParts = 1024;  // partials per query head that one merge takes (splits and tail together)
+
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ part_o,
                                                       const float *__restrict__ part_ml, T *__restrict__ out,
@@ -105,23 +107,43 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     // the second set of partials (n_part2 may be 0) has the same layout; it holds the uncompressed tail tokens
     const int h = blockIdx.x, b = blockIdx.y;
     const size_t base = ((size_t)b * H_q + h) * n_part, base2 = ((size_t)b * H_q + h) * n_part2;
+    // (maximum, sum) of every partial into LDS with all loads in flight at once, then one weight per partial; the
+    // accumulation below runs four partials at a time for the same reason (the kernel is a chain of small dependent
+    // loads otherwise: its time is their latency)
+    __shared__ float sm_m[kMaxCombineParts], sm_w[kMaxCombineParts];
+    __shared__ float sm_den;
+    const int n_all = n_part + n_part2;
+    for (int s = threadIdx.x; s < n_all; s += blockDim.x)
+        sm_m[s] = s < n_part ? part_ml[(base + s) * 2] : part_ml2[(base2 + (s - n_part)) * 2];
+    __syncthreads();
     float M = -INFINITY;
-    for (int s = 0; s < n_part; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
-    for (int s = 0; s < n_part2; ++s) M = fmaxf(M, part_ml2[(base2 + s) * 2]);
+    for (int s = 0; s < n_all; ++s) M = fmaxf(M, sm_m[s]);
+    __syncthreads();
+    for (int s = threadIdx.x; s < n_all; s += blockDim.x) {
+        const float m = sm_m[s];
+        sm_w[s] = (m == -INFINITY) ? 0.0f : expf(m - M);
+        sm_m[s] = s < n_part ? part_ml[(base + s) * 2 + 1] : part_ml2[(base2 + (s - n_part)) * 2 + 1];  // now the sums
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float den = 0.0f;
+        for (int s = 0; s < n_all; ++s) den = fmaf(sm_w[s], sm_m[s], den);
+        sm_den = den;
+    }
+    __syncthreads();
+    const float den = sm_den;
     for (int j = threadIdx.x; j < d_h; j += blockDim.x) {
-        float num = 0.0f, den = 0.0f;
-        for (int s = 0; s < n_part; ++s) {
-            const float m = part_ml[(base + s) * 2];
-            const float wgt = (m == -INFINITY) ? 0.0f : expf(m - M);
-            num = fmaf(wgt, part_o[(base + s) * d_h + j], num);
-            den = fmaf(wgt, part_ml[(base + s) * 2 + 1], den);
+        float num = 0.0f;
+        int s = 0;
+        for (; s + 4 <= n_part; s += 4) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = part_o[(base + s + u) * d_h + j];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) num = fmaf(sm_w[s + u], v[u], num);
         }
-        for (int s = 0; s < n_part2; ++s) {
-            const float m = part_ml2[(base2 + s) * 2];
-            const float wgt = (m == -INFINITY) ? 0.0f : expf(m - M);
-            num = fmaf(wgt, part_o2[(base2 + s) * d_h + j], num);
-            den = fmaf(wgt, part_ml2[(base2 + s) * 2 + 1], den);
-        }
+        for (; s < n_part; ++s) num = fmaf(sm_w[s], part_o[(base + s) * d_h + j], num);
+        for (int s2 = 0; s2 < n_part2; ++s2) num = fmaf(sm_w[n_part + s2], part_o2[(base2 + s2) * d_h + j], num);
         // a head with no token at all (every list empty, no tail) has den == 0: its output is defined as zero
         out[((size_t)b * H_q + h) * d_h + j] = from_f32<T>(den > 0.0f ? num / den : 0.0f);
     }
@@ -370,6 +392,7 @@ hipError_t launch_dense(const xkv_shape &s, const Plan &p, const void *K, const 
 hipError_t launch_combine(const xkv_shape &s, int n_part, const float *part_o, const float *part_ml, void *out,
                           hipStream_t st, int n_part2, const float *part_o2, const float *part_ml2)
 {
+    if (n_part + n_part2 > kMaxCombineParts) return hipErrorInvalidValue;
     dim3 grid(s.H_q, s.batch), block(s.d_h <= 64 ? 64 : (s.d_h <= 128 ? 128 : 256));
     if (s.dtype == XKV_F32)
         hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, st, part_o, part_ml, (float *)out, s.H_q, s.d_h,
