@@ -317,13 +317,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     }
     if (m_end == m_begin && tid == 0) tok_lds[0] = 0;  // the prologue below still gathers one (unused) tile
     __syncthreads();
-    // the eight rows this lane gathers from in a tile: row 4j + lane/16 of the wavefront's 32-token block
+    // the eight rows this lane gathers from in a tile: row 4j + lane/16 of the wavefront's 32-token block.  Past the
+    // last tile the pipeline still issues its prefetches (the count of outstanding loads is what its waits rely
+    // on); they then all go to the split's first row, which costs a cache hit instead of a tile's worth of memory
+    // traffic.
     auto tile_tokens = [&](int tile, int (&tk)[kGroup]) __attribute__((always_inline)) {
+        const bool past = tile >= n_tiles;
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) {
             int m = tile * TILE + w * 32 + 4 * j + (lane >> 4);
             m = m < m_end - m_begin ? m : (m_end > m_begin ? m_end - m_begin - 1 : 0);
-            tk[j] = tok_lds[m];
+            tk[j] = tok_lds[past ? 0 : m];
         }
     };
     // gather descriptor of group S (128 ranks each) of the K or V rows; pieces beyond the row are replaced by
@@ -383,13 +387,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     };
     auto q_tokens = [&](int tile, int (&tkc)[4], int &tkp) __attribute__((always_inline)) {
         const int last = m_end > m_begin ? m_end - m_begin - 1 : 0;
+        const bool past = tile >= n_tiles;  // prefetches past the last tile: all to the split's first row
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = tile * TILE + w * 32 + 8 * i + (lane >> 3);
-            tkc[i] = tok_lds[m < m_end - m_begin ? m : last];
+            tkc[i] = tok_lds[past ? 0 : (m < m_end - m_begin ? m : last)];
         }
         const int mp = tile * TILE + w * 32 + (lane >> 1);
-        tkp = tok_lds[mp < m_end - m_begin ? mp : last];
+        tkp = tok_lds[past ? 0 : (mp < m_end - m_begin ? mp : last)];
     };
 
     // ---- prologue, in the order the steady state expects: B fragments of group 0, gathers of groups 0 and 1
@@ -434,8 +439,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const bool next_k = pn < PK;                                                                              \
     const int S0 = (next_k ? pn : pn - PK) * 2;                                                               \
     const AStage an0 = stage_of(next_k, S0), an1 = stage_of(next_k, S0 + 1);                                  \
-    int tkn[kGroup]; /* rows of the tile that pair belongs to (past the last tile: the last tile again) */   \
-    tile_tokens(wrap ? (tile + 1 < n_tiles ? tile + 1 : tile) : tile, tkn);                                   \
+    int tkn[kGroup]; /* rows of the tile that pair belongs to */                                              \
+    tile_tokens(wrap ? tile + 1 : tile, tkn);                                                                 \
     const u32x4_t *bs1 = packg + (size_t)((pi) * 2 + 1) * (kGroup * 256) + tid; /* second group of this pair */ \
     const u32x4_t *bs2 = packg + (size_t)(pn * 2) * (kGroup * 256) + tid;       /* first group of next pair */  \
     const int buf0 = gg & 1, buf1 = buf0 ^ 1
@@ -446,7 +451,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void gather_attend_mfma_kernel(
     const bool next_k = pn < PK;                                                                              \
     const QStage qn = qstage_of(next_k, next_k ? pn : pn - PK);                                               \
     int tkc[4], tkp;                                                                                          \
-    q_tokens(wrap ? (tile + 1 < n_tiles ? tile + 1 : tile) : tile, tkc, tkp);                                 \
+    q_tokens(wrap ? tile + 1 : tile, tkc, tkp);                                                               \
     const u32x4_t *bs1 = packg + (size_t)((pi) * 2 + 1) * (kGroup * 256) + tid;                               \
     const u32x4_t *bs2 = packg + (size_t)(pn * 2) * (kGroup * 256) + tid
         for (int pi = 0; pi < PK; ++pi, gg += 2) {

@@ -303,7 +303,7 @@ constexpr int kScoreWaves = 8;  // wavefronts per workgroup; 4 when the P fragme
 template <int SLOT0>
 __device__ __forceinline__ void score_group(f32x16_t &acc_h, f32x16_t &acc_l, u32x4_t (&areg)[16], u32x4_t *At,
                                             const u32x4_t *Ph, const u32x4_t *Pl_, const u32x4_t *arow, int pieces,
-                                            int t0, int L, const int (&woff)[4], int rbase)
+                                            int t0, int row_step, int L, const int (&woff)[4], int rbase)
 {
     // all but the 8 youngest loads (the other half of the ring) have landed: vmcnt(8), other counters untouched
     __builtin_amdgcn_s_waitcnt(8 | (7 << 4) | (0xF << 8));
@@ -316,7 +316,7 @@ __device__ __forceinline__ void score_group(f32x16_t &acc_h, f32x16_t &acc_l, u3
         acc_h = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, Ph[fl * 64]), a0, acc_h, 0, 0, 0);
         acc_l = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, Pl_[fl * 64]), a0, acc_l, 0, 0, 0);
         // instruction fl of the group two groups on, into the ring entry written out above
-        const int t = t0 + 4 * fl;
+        const int t = t0 + row_step * fl;
         areg[SLOT0 + fl] = __builtin_nontemporal_load(&arow[(size_t)(t < L ? t : L - 1) * pieces]);
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -411,10 +411,18 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
     // ... and behind them already the first two groups of A^K.  (tile, group) two groups ahead of the one being
     // multiplied; past the end it stays on the last tile.
     int tile_p = has_work ? tile : 0, S_p = 0;
+    // (the prefetches keep being issued past the wavefront's last tile -- the waits count outstanding loads -- but
+    // then every one of them goes to one row, a cache hit, instead of streaming the last tile from memory again)
+    int row_step = 4, row_lane = 1;  // rows between the instructions of a group, and between a lane's row and lane/16
     auto advance_p = [&]() __attribute__((always_inline)) {
         if (++S_p == n_groups) {
             S_p = 0;
-            tile_p = tile_p + TS < tile_end ? tile_p + TS : tile_p;
+            if (tile_p + TS < tile_end) {
+                tile_p += TS;
+            } else {
+                row_step = 0;
+                row_lane = 0;
+            }
         }
     };
     u32x4_t areg[16];
@@ -531,18 +539,18 @@ __global__ __launch_bounds__(WAVES * 64) void score_stream_kernel(const bf16_t *
     for (int gi = 0; gi < my_groups; gi += 2) {
         {
             const u32x4_t *arow = Ab + piece_of(S_p);
-            const int t0 = tile_p * 32 + trow;
+            const int t0 = tile_p * 32 + trow * row_lane, rs = row_step;
             advance_p();
             score_group<0>(acc_h, acc_l, areg, At, Pl + (S_c * 8) * 64 + lane, Pl + (F8 + S_c * 8) * 64 + lane, arow,
-                           pieces, t0, L, woff, rbase);
+                           pieces, t0, rs, L, woff, rbase);
             finish_group();
         }
         {
             const u32x4_t *arow = Ab + piece_of(S_p);
-            const int t0 = tile_p * 32 + trow;
+            const int t0 = tile_p * 32 + trow * row_lane, rs = row_step;
             advance_p();
             score_group<8>(acc_h, acc_l, areg, At, Pl + (S_c * 8) * 64 + lane, Pl + (F8 + S_c * 8) * 64 + lane, arow,
-                           pieces, t0, L, woff, rbase);
+                           pieces, t0, rs, L, woff, rbase);
             if (gi + 1 < my_groups) finish_group();
         }
         if (ti > RT - 2) flush();  // up to two tiles complete per iteration
