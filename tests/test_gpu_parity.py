@@ -344,6 +344,13 @@ GA_RANKS = [
     ("r768_bf16", synth.LLAMA_GROUP.with_(L=9000, k=2100, r_k=768, r_v=768, batch=4, G=1, a_scale=768 ** -0.5)),
     ("r384_576_bf16", synth.LLAMA_GROUP.with_(L=9000, k=2100, r_k=384, r_v=576, batch=4, G=1, a_scale=384 ** -0.5)),
     ("r448_288_qwen_bf16", synth.QWEN.with_(L=7001, k=1111, r_k=448, r_v=288, batch=2, G=1, a_scale=448 ** -0.5)),
+    # group counts (K, V) of the gather-reconstruct kernel: (1, 1) and (3, 3), where the softmax falls between the two
+    # groups of one step; (2, 1) and (1, 2), where V is padded by a zero group; (3, 2), odd K with an even rest
+    ("r128_128_bf16", synth.LLAMA_GROUP.with_(L=5000, k=700, r_k=128, r_v=128, batch=3, G=2, a_scale=128 ** -0.5)),
+    ("r384_384_bf16", synth.LLAMA_GROUP.with_(L=5000, k=700, r_k=384, r_v=384, batch=3, G=2, a_scale=384 ** -0.5)),
+    ("r256_128_bf16", synth.LLAMA_GROUP.with_(L=5000, k=700, r_k=256, r_v=128, batch=3, G=2, a_scale=256 ** -0.5)),
+    ("r112_240_bf16", synth.LLAMA_GROUP.with_(L=5000, k=700, r_k=112, r_v=240, batch=3, G=2, a_scale=112 ** -0.5)),
+    ("r368_256_bf16", synth.LLAMA_GROUP.with_(L=5000, k=700, r_k=368, r_v=256, batch=3, G=2, a_scale=368 ** -0.5)),
 ]
 
 
@@ -353,7 +360,7 @@ def test_large_and_unequal_ranks_chain(name, w):
     ranks that are not whole 128-rank groups (bf16 gather-reconstruct kernel with six rank groups, with different group
     counts for K and V, with ragged last groups)."""
     case = synth.make_case(w, seed=13)
-    rep = check_chain(w, case, layer=0)
+    rep = check_chain(w, case, layer=w.G - 1)
     print(name, rep)
 
 
