@@ -712,6 +712,10 @@ __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict
 // vectors into LDS, runs a complete inner tournament over them (wavefront = one column pair per inner round: three dot
 // products, one rotation), writes them back, and applies the accumulated NC x NC transform to its NC rows of J^T.
 // Workgroups of a launch touch disjoint rows; launch boundaries are the only synchronisation between rounds.
+// The launches of kJacobiSweeps sweeps are all enqueued up front (no value is read back by the host); a sequence is
+// finished early on the device: every sweep counts, per sequence, the rotations whose two columns had a cosine above
+// kJacobiSettled, and the workgroups of the sweeps after one with a count of zero return at once.  Convergence is
+// quadratic by then: what a sweep without such a rotation leaves behind is of the order of the square of that bound.
 // ------------------------------------------------------------------------------------------------
 
 // (4z) Wn[c][i] = Vt[i][c]: the basis in the layout the orthonormalisation reads, for its second pass.
@@ -765,10 +769,14 @@ __global__ __launch_bounds__(256) void ritz_matrix_kernel(const float *__restric
         if (i0 + ty + 8 * u < r && j0 + tx < r) M[(size_t)(i0 + ty + 8 * u) * r + j0 + tx] = acc[u];
 }
 
-// (5b) Gt = (M + M^T) / 2 (row c = column c of the symmetric matrix), Jt = identity.
+constexpr int kJacobiSweeps = 10;        // most sweeps of the block Jacobi eigen-solver (each: every pair of column blocks once)
+constexpr double kJacobiSettled = 1e-7;  // a sweep whose rotations all stayed below this cosine was the last one needed
+
+// (5b) Gt = (M + M^T) / 2 (row c = column c of the symmetric matrix), Jt = identity, rotation counts zero.
 __global__ __launch_bounds__(256) void jacobi_init_kernel(const double *__restrict__ M, double *__restrict__ Gt,
-                                                          double *__restrict__ Jt, int r)
+                                                          double *__restrict__ Jt, int *__restrict__ rotations, int r)
 {
+    if (blockIdx.x == 0 && threadIdx.x < kJacobiSweeps) rotations[blockIdx.z * kJacobiSweeps + threadIdx.x] = 0;
     M += (size_t)blockIdx.z * r * r;
     Gt += (size_t)blockIdx.z * r * r;
     Jt += (size_t)blockIdx.z * r * r;
@@ -798,9 +806,15 @@ __device__ __forceinline__ double fz_wave_sum_f64(double v)
 
 // (5c) one tournament round between column blocks.  NC local columns (two blocks of NC / 2), NC / 2 wavefronts.
 template <int NC>
-__global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__restrict__ Gt, double *__restrict__ Jt, int r,
-                                                                  int n_blocks, int round)
+__global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__restrict__ Gt, double *__restrict__ Jt,
+                                                                  int *rotations, int r, int n_blocks,
+                                                                  int sweep, int round)
 {
+    // rotations[sequence][sweep]: written by the launches of that sweep only, read by those of the next
+    rotations += blockIdx.z * kJacobiSweeps;
+    if (sweep > 0 && rotations[sweep - 1] == 0) return;  // same value for the whole workgroup
+    __shared__ int big_rotations;
+    if (threadIdx.x == 0) big_rotations = 0;
     extern __shared__ double fz_sm[];
     double *cols = fz_sm;                // [NC][r]
     double *T = fz_sm + (size_t)NC * r;  // [NC][NC]: row c = coefficients of local column c in terms of the old ones
@@ -859,7 +873,9 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
             beta = fz_wave_sum_f64(beta);
             gamma = fz_wave_sum_f64(gamma);
             // rotate unless the two columns are already orthogonal to working accuracy (or one of them is zero)
-            if (fabs(alpha) > 1e-15 * sqrt(beta * gamma) && beta > 0.0 && gamma > 0.0) {
+            const double unit = sqrt(beta * gamma);
+            if (fabs(alpha) > 1e-15 * unit && beta > 0.0 && gamma > 0.0) {
+                if (lane == 0 && fabs(alpha) > kJacobiSettled * unit) atomicAdd(&big_rotations, 1);
                 const double zeta = (gamma - beta) / (2.0 * alpha);
                 const double tn = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
                 const double cs = 1.0 / sqrt(1.0 + tn * tn), sn = cs * tn;
@@ -881,6 +897,7 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
         const int c = idx / r, i = idx % r, gc = gcol(c);
         if (gc < r) Gt[(size_t)gc * r + i] = cols[idx];
     }
+    if (tid == 0 && big_rotations > 0) atomicAdd(&rotations[sweep], big_rotations);
     __syncthreads();
     // the same transform on this workgroup's rows of J^T: load them where the columns were, combine, store
     for (int idx = tid; idx < NC * r; idx += THREADS) {
@@ -972,7 +989,7 @@ constexpr int kFzChunk = 16;
 struct FzLayout {
     int n, Lp, bc, gram_tiles, gram_splits, w_splits, g_splits, chol_pb;
     size_t esz, xt_seq, part_seq, off_xt, off_part, off_c, off_vt, off_wn, off_g, off_lt, off_planes, off_diag, off_minv,
-        total;
+        off_rot, total;
 };
 
 FzLayout fz_layout(const xkv_shape &s, int r)
@@ -1011,6 +1028,7 @@ FzLayout fz_layout(const xkv_shape &s, int r)
     f.off_planes = o; o += align256(bc * f.g_splits * r * r * 8);
     f.off_diag = o;   o += align256(bc * r * 8);
     f.off_minv = o;   o += align256(bc * ((r + 15) / 16) * 256 * 8);
+    f.off_rot = o;    o += align256(bc * 16 * 4);
     f.total = o;
     return f;
 }
@@ -1028,8 +1046,6 @@ template <typename T> hipError_t launch_gemm(const GemmArgs &a, int tiles, int n
 
 inline unsigned blocks256(long long count) { return (unsigned)((count + 255) / 256); }
 
-constexpr int kJacobiSweeps = 8;  // sweeps of the block Jacobi eigen-solver (each: every pair of column blocks once)
-
 template <typename T>
 hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X, int r, int r_out, int iters, uint32_t seed,
                            void *A_out, void *B_out, float *sigma_out, unsigned char *ws, hipStream_t st)
@@ -1042,6 +1058,8 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
     double *Gm = reinterpret_cast<double *>(ws + f.off_g), *Lt = reinterpret_cast<double *>(ws + f.off_lt);
     double *planes = reinterpret_cast<double *>(ws + f.off_planes), *diag0 = reinterpret_cast<double *>(ws + f.off_diag);
     double *Minv = reinterpret_cast<double *>(ws + f.off_minv);
+    int *rotations = reinterpret_cast<int *>(ws + f.off_rot);
+    static_assert(kJacobiSweeps <= 16, "the rotation counters have 16 slots per sequence");
     static DynamicLdsOnce attr;
     if (hipError_t e0 = attr.ensure((const void *)chol_panel_kernel, 160 * 1024 - 256); e0 != hipSuccess) return e0;
     hipError_t e = hipSuccess;
@@ -1123,7 +1141,7 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
         int *order = reinterpret_cast<int *>(Minv);
         const int rb = (r + 31) / 32;
         hipLaunchKernelGGL(ritz_matrix_kernel, dim3(rb, rb, nb), dim3(256), 0, st, Vt, Wn, Mr, n, r);
-        hipLaunchKernelGGL(jacobi_init_kernel, dim3(blocks256((long long)r * r), 1, nb), dim3(256), 0, st, Mr, Gt, Jt, r);
+        hipLaunchKernelGGL(jacobi_init_kernel, dim3(blocks256((long long)r * r), 1, nb), dim3(256), 0, st, Mr, Gt, Jt, rotations, r);
         {
             const int nc = r <= 512 ? 32 : 16, bs = nc / 2;
             const int n_blocks = std::max(2, ((r + bs - 1) / bs + 1) / 2 * 2);  // an even number of column blocks
@@ -1136,10 +1154,10 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
                 for (int round = 0; round < n_blocks - 1; ++round) {
                     if (nc == 32)
                         hipLaunchKernelGGL(jacobi_round_kernel<32>, dim3(n_blocks / 2, 1, nb), dim3(16 * 64), lds, st, Gt, Jt,
-                                           r, n_blocks, round);
+                                           rotations, r, n_blocks, sweep, round);
                     else
-                        hipLaunchKernelGGL(jacobi_round_kernel<16>, dim3(n_blocks / 2, 1, nb), dim3(8 * 64), lds, st, Gt, Jt, r,
-                                           n_blocks, round);
+                        hipLaunchKernelGGL(jacobi_round_kernel<16>, dim3(n_blocks / 2, 1, nb), dim3(8 * 64), lds, st, Gt, Jt,
+                                           rotations, r, n_blocks, sweep, round);
                 }
         }
         hipLaunchKernelGGL(ritz_order_kernel, dim3(nb), dim3(1024), 0, st, Gt, order,
