@@ -267,9 +267,11 @@ def main():
                                                                      groups[s]["B_k"], groups[s]["B_v"], qs[s][l],
                                                                      idx, out, ws)),
     }
-    # algorithmic bytes of the kernels alone (the projection / packing pre-passes read B, not these kernels)
+    # algorithmic bytes of the kernels alone: the score kernel reads the projected queries, not B^K_l (the projection
+    # pre-pass does), so the r_K d term of the score stage is left out; the gather-reconstruct kernel reads B^K_l and
+    # B^V_l itself (in fragment order), so its figure is the stage's: selected rows plus B once
     kern_bytes = {"score": w.batch * (e * w.L * w.r_k + 4 * w.H_kv * w.L),
-                  "gather_attend": w.batch * e * w.H_kv * w.k * (w.r_k + w.r_v)}
+                  "gather_attend": bytes_gather}
     for kname in kern_ms:
         stages[kname]["kernel_ms"] = round(kern_ms[kname], 5)
         stages[kname]["kernel_GBps"] = round(kern_bytes[kname] / (kern_ms[kname] * 1e-3) / 1e9, 1)

@@ -258,7 +258,7 @@ def test_llama_group_full_size():
 
 def _full_size_sampled(w, seqs, seed, scale=None, whole_rows=True):
     """One layer of a benchmark configuration at full size, in the launch configuration bench.py times (fused
-    xkv_sr_decode on device-generated factors), checked on the sampled sequences: every pooled score of the sequence
+    xkv_sr_decode_packed on device-generated factors, and xkv_sr_decode beside it), checked on the sampled sequences: every pooled score of the sequence
     (whole_rows; else token ranges at the start, in the middle and at the end), the complete selection (against the
     oracle's selection on the GPU's own scores), and the attention outputs."""
     torch = torch_mod()
@@ -269,9 +269,25 @@ def _full_size_sampled(w, seqs, seed, scale=None, whole_rows=True):
     S = torch.empty((w.batch, w.H_kv, w.L), dtype=torch.float32, device="cuda")
     idx = torch.empty((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda")
     out = torch.empty((w.batch, w.H_q, w.d_h), dtype=synth.torch_dtype(w.dtype), device="cuda")
+    # the call the benchmark times: B_l re-ordered once for the group, then the packed step (where the shape has one)
+    if w.dtype == "bf16" and w.d_h == 128 and w.r_k % 16 == 0 and w.r_v % 16 == 0:
+        packed = torch.empty(xb.xkv_packed_b_bytes(shape), dtype=torch.uint8, device="cuda")
+        xb.xkv_pack_b(shape, dev["B_k"], dev["B_v"], packed)
+        xb.xkv_sr_decode_packed(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], packed, dev["q"][layer].contiguous(),
+                                out, idx, S, ws)
+        torch.cuda.synchronize()
+        packed_result = (out.clone(), idx.clone(), S.clone())
+        del packed
+        out.zero_(), idx.zero_(), S.zero_()
+    else:
+        packed_result = None
     xb.xkv_sr_decode(shape, layer, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], dev["q"][layer].contiguous(), out,
                      idx, S, ws)
     torch.cuda.synchronize()
+    if packed_result is not None:    # same kernels on the same operands: the two calls agree bit for bit
+        for a, b_ in zip(packed_result, (out, idx, S)):
+            assert torch.equal(a, b_)
+        del packed_result
     scale = oracle.default_scale(w.d_h) if scale is None else scale
     mid = w.L // 2
     ranges = [(0, w.L)] if whole_rows else [(0, 256), (mid - 128, mid + 128), (w.L - 256, w.L)]

@@ -681,3 +681,22 @@ def test_three_bit_quantiser_on_a_group_worked_by_hand():
     assert lo[0, 0] == 0.0 and step[0, 0] == np.float32(1.109375)
     np.testing.assert_array_equal(codes[0], np.clip(np.rint(x[0] / 1.109375), 0, 7))
     assert codes[0, 0] == 0 and codes[0, -1] == 7 and codes[0, 2] == 0 and codes[0, 3] == 1
+
+
+@pytest.mark.parametrize("bits", [4, 3])
+def test_quantiser_codes_against_the_plain_definition_in_double_precision(bits):
+    """The codes come from fp32 operations ((x - lo) times the rounded reciprocal of the step).  Against the plain
+    definition rint((x - lo) / step) evaluated in float64 they may differ only where the exact quotient is a tie
+    (fractional part exactly one half): there both neighbours are nearest, everywhere else the code is the same."""
+    rng = np.random.default_rng(5)
+    X = oracle._bf16_rne((rng.standard_normal((4000, 256)) / 16.0).astype(np.float32))
+    codes, step, lo = oracle.quantize_rows(X, bits)
+    g = X.reshape(4000, 8, 32).astype(np.float64)
+    t = ((g - lo.astype(np.float64)[:, :, None]) / step.astype(np.float64)[:, :, None]).reshape(4000, 256)
+    plain = np.clip(np.rint(t), 0, (1 << bits) - 1).astype(np.uint8)
+    differ = plain != codes
+    assert differ.mean() < 1e-3
+    assert differ.any()          # the sample is large enough to contain ties, or the check below is empty
+    frac = t[differ] - np.floor(t[differ])
+    np.testing.assert_array_equal(frac, 0.5)
+    assert np.abs(codes[differ].astype(np.int64) - plain[differ].astype(np.int64)).max() == 1
