@@ -709,8 +709,10 @@ __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict
 // of M^2, which are those of M, and the column norms are the eigenvalues.  Both M J and J are stored transposed (row c
 // = column vector c), so a rotation touches two contiguous rows.  The r columns are cut into blocks of NC / 2; a launch
 // is one round of a round-robin tournament between blocks, workgroup = one pair of blocks: it loads its NC column
-// vectors into LDS, runs a complete inner tournament over them (wavefront = one column pair per inner round: three dot
-// products, one rotation), writes them back, and applies the accumulated NC x NC transform to its NC rows of J^T.
+// vectors into LDS, runs an inner tournament over them (wavefront = one column pair per inner round: three dot
+// products, one rotation; all pairs in a sweep's first round, only the pairs between the two blocks afterwards, so that
+// every pair of columns meets exactly once per sweep), writes them back, and applies the accumulated NC x NC transform
+// to its NC rows of J^T.
 // Workgroups of a launch touch disjoint rows; launch boundaries are the only synchronisation between rounds.
 // The launches of kJacobiSweeps sweeps are all enqueued up front (no value is read back by the host); a sequence is
 // finished early on the device: every sweep counts, per sequence, the rotations whose two columns had a cosine above
@@ -844,10 +846,15 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
     }
     for (int idx = tid; idx < NC * NC; idx += THREADS) T[idx] = (idx / NC == idx % NC) ? 1.0 : 0.0;
     __syncthreads();
-    for (int t = 0; t < NC - 1; ++t) {
+    // In the sweep's first round the inner tournament is complete (every pair of the NC columns: that is where the
+    // pairs inside a block meet, once per sweep, every block being in exactly one workgroup of the round); in the
+    // other rounds only the BS x BS pairs between the two blocks are left to visit.
+    const bool complete = round == 0;
+    const int inner_rounds = complete ? NC - 1 : BS;
+    for (int t = 0; t < inner_rounds; ++t) {
         // wavefront w plays the w-th pair of the inner round
         int a = -1, b = -1;
-        {
+        if (complete) {
             int seen = 0;
             for (int x = 0; x < NC && a < 0; ++x) {
                 const int y = fz_opponent(x, t, NC);
@@ -859,6 +866,9 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
                     ++seen;
                 }
             }
+        } else {
+            a = w;
+            b = BS + (w + t) % BS;
         }
         if (gcol(a) < r && gcol(b) < r) {
             double *ga = cols + (size_t)a * r, *gb = cols + (size_t)b * r;
