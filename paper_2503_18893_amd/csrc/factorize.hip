@@ -712,7 +712,7 @@ __global__ __launch_bounds__(256) void orth_solve_kernel(const float *__restrict
 // vectors into LDS, runs an inner tournament over them (wavefront = one column pair per inner round: three dot
 // products, one rotation; all pairs in a sweep's first round, only the pairs between the two blocks afterwards, so that
 // every pair of columns meets exactly once per sweep), writes them back, and applies the accumulated NC x NC transform
-// to its NC rows of J^T.
+// to its NC rows of J^T (a 32 x 32 by 32 x r product on the fp64 matrix cores).
 // Workgroups of a launch touch disjoint rows; launch boundaries are the only synchronisation between rounds.
 // The launches of kJacobiSweeps sweeps are all enqueued up front (no value is read back by the host); a sequence is
 // finished early on the device: every sweep counts, per sequence, the rotations whose two columns had a cosine above
@@ -806,6 +806,32 @@ __device__ __forceinline__ double fz_wave_sum_f64(double v)
     return v;
 }
 
+// The same sum for code where every lane of the wavefront is active, through the data-parallel lane permutations of
+// the vector ALU instead of LDS round trips: four steps leave the sum of each row of 16 lanes in all of its lanes
+// (neighbour, other pair of the quad, other quad of the half row, other half row), the four row sums are then read
+// out as scalars.  CTRL: quad_perm(1,0,3,2) = 0xB1, quad_perm(2,3,0,1) = 0x4E, row_half_mirror = 0x141, row_mirror =
+// 0x140.
+template <int CTRL> __device__ __forceinline__ double fz_dpp_f64(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double fz_wave_sum_all_lanes_f64(double v)
+{
+    v += fz_dpp_f64<0xB1>(v);
+    v += fz_dpp_f64<0x4E>(v);
+    v += fz_dpp_f64<0x141>(v);
+    v += fz_dpp_f64<0x140>(v);
+    double sum = 0.0;
+#pragma unroll
+    for (int row = 0; row < kWave; row += 16)
+        sum += __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), row),
+                                __builtin_amdgcn_readlane(__double2loint(v), row));
+    return sum;
+}
+
 // (5c) one tournament round between column blocks.  NC local columns (two blocks of NC / 2), NC / 2 wavefronts.
 template <int NC>
 __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__restrict__ Gt, double *__restrict__ Jt,
@@ -818,8 +844,11 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
     __shared__ int big_rotations;
     if (threadIdx.x == 0) big_rotations = 0;
     extern __shared__ double fz_sm[];
-    double *cols = fz_sm;                // [NC][r]
-    double *T = fz_sm + (size_t)NC * r;  // [NC][NC]: row c = coefficients of local column c in terms of the old ones
+    // r <= 64 kMaxIt (512 for NC = 32, 1024 for NC = 16); the local columns are kept at that pitch and zero beyond r,
+    // so that the loops over a column need no per-element bounds (zeros rotate into zeros)
+    constexpr int kMaxIt = NC == 32 ? 8 : 16, RP = kMaxIt * kWave;
+    double *cols = fz_sm;                 // [NC][RP]
+    double *T = fz_sm + (size_t)NC * RP;  // [NC][NC]: row c = coefficients of local column c in terms of the old ones
     Gt += (size_t)blockIdx.z * r * r;
     Jt += (size_t)blockIdx.z * r * r;
     constexpr int BS = NC / 2, THREADS = NC / 2 * 64;
@@ -840,10 +869,25 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
         }
     }
     auto gcol = [&](int c) { return c < BS ? P * BS + c : Q * BS + (c - BS); };  // columns >= r do not exist
-    for (int idx = tid; idx < NC * r; idx += THREADS) {
-        const int c = idx / r, i = idx % r, gc = gcol(c);
-        cols[idx] = gc < r ? Gt[(size_t)gc * r + i] : 0.0;
-    }
+    // Rows move between memory and LDS a wavefront at a time: local column w and w + NC / 2, 64 consecutive elements
+    // per request, all requests of a wavefront issued before the first is awaited.
+    auto rows_to_lds = [&](const double *__restrict__ src) __attribute__((always_inline)) {
+        double v[2][kMaxIt];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int gc = gcol(w + BS * u);
+#pragma unroll
+            for (int it = 0; it < kMaxIt; ++it) {
+                const int i = lane + kWave * it;
+                v[u][it] = (gc < r && i < r) ? src[(size_t)gc * r + i] : 0.0;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int it = 0; it < kMaxIt; ++it) cols[(w + BS * u) * RP + lane + kWave * it] = v[u][it];
+    };
+    rows_to_lds(Gt);
     for (int idx = tid; idx < NC * NC; idx += THREADS) T[idx] = (idx / NC == idx % NC) ? 1.0 : 0.0;
     __syncthreads();
     // In the sweep's first round the inner tournament is complete (every pair of the NC columns: that is where the
@@ -853,46 +897,52 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
     const int inner_rounds = complete ? NC - 1 : BS;
     for (int t = 0; t < inner_rounds; ++t) {
         // wavefront w plays the w-th pair of the inner round
-        int a = -1, b = -1;
+        int a, b;
         if (complete) {
-            int seen = 0;
-            for (int x = 0; x < NC && a < 0; ++x) {
-                const int y = fz_opponent(x, t, NC);
-                if (x < y) {
-                    if (seen == w) {
-                        a = x;
-                        b = y;
-                    }
-                    ++seen;
-                }
-            }
+            // the pairs of round t of the tournament (fz_opponent): the last player meets t, and player t + j meets
+            // player t - j (modulo NC - 1) for j = 1 .. NC / 2 - 1; wavefront w takes pair number w of that list
+            constexpr int q = NC - 1;
+            const int x = w == 0 ? t % q : (t + w) % q, y = w == 0 ? q : (t - w + q) % q;
+            a = x < y ? x : y;
+            b = x < y ? y : x;
         } else {
             a = w;
             b = BS + (w + t) % BS;
         }
         if (gcol(a) < r && gcol(b) < r) {
-            double *ga = cols + (size_t)a * r, *gb = cols + (size_t)b * r;
-            double alpha = 0.0, beta = 0.0, gamma = 0.0;
-            for (int i = lane; i < r; i += kWave) {
-                const double x = ga[i], y = gb[i];
-                alpha = fma(x, y, alpha);
-                beta = fma(x, x, beta);
-                gamma = fma(y, y, gamma);
+            double *ga = cols + a * RP + lane, *gb = cols + b * RP + lane;
+            // the lane's elements of both columns stay in registers from the dot products to the rotation
+            // (all LDS reads are requested before the first wait)
+            double x[kMaxIt], y[kMaxIt];
+#pragma unroll
+            for (int it = 0; it < kMaxIt; ++it) {
+                x[it] = ga[kWave * it];
+                y[it] = gb[kWave * it];
             }
-            alpha = fz_wave_sum_f64(alpha);
-            beta = fz_wave_sum_f64(beta);
-            gamma = fz_wave_sum_f64(gamma);
+            double alpha = 0.0, beta = 0.0, gamma = 0.0;
+#pragma unroll
+            for (int it = 0; it < kMaxIt; ++it) {
+                alpha = fma(x[it], y[it], alpha);
+                beta = fma(x[it], x[it], beta);
+                gamma = fma(y[it], y[it], gamma);
+            }
+            alpha = fz_wave_sum_all_lanes_f64(alpha);
+            beta = fz_wave_sum_all_lanes_f64(beta);
+            gamma = fz_wave_sum_all_lanes_f64(gamma);
             // rotate unless the two columns are already orthogonal to working accuracy (or one of them is zero)
-            const double unit = sqrt(beta * gamma);
-            if (fabs(alpha) > 1e-15 * unit && beta > 0.0 && gamma > 0.0) {
-                if (lane == 0 && fabs(alpha) > kJacobiSettled * unit) atomicAdd(&big_rotations, 1);
-                const double zeta = (gamma - beta) / (2.0 * alpha);
-                const double tn = (zeta >= 0.0 ? 1.0 : -1.0) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-                const double cs = 1.0 / sqrt(1.0 + tn * tn), sn = cs * tn;
-                for (int i = lane; i < r; i += kWave) {
-                    const double x = ga[i], y = gb[i];
-                    ga[i] = cs * x - sn * y;
-                    gb[i] = sn * x + cs * y;
+            // (cosine of the two columns)^2 = alpha^2 / (beta gamma).  The rotation angle: tan(2 theta) = 2 alpha /
+            // (gamma - beta), the smaller root of the tangent written with one square root and one division.
+            const double a_sq = alpha * alpha, bg = beta * gamma;
+            if (a_sq > 1e-30 * bg && beta > 0.0 && gamma > 0.0) {
+                if (lane == 0 && a_sq > kJacobiSettled * kJacobiSettled * bg) atomicAdd(&big_rotations, 1);
+                const double dif = gamma - beta, a2 = 2.0 * alpha;
+                const double hyp = sqrt(dif * dif + a2 * a2);
+                const double tn = (dif >= 0.0 ? a2 : -a2) / (fabs(dif) + hyp);
+                const double cs = rsqrt(1.0 + tn * tn), sn = cs * tn;
+#pragma unroll
+                for (int it = 0; it < kMaxIt; ++it) {
+                    ga[kWave * it] = cs * x[it] - sn * y[it];
+                    gb[kWave * it] = sn * x[it] + cs * y[it];
                 }
                 if (lane < NC) {
                     const double x = T[a * NC + lane], y = T[b * NC + lane];
@@ -903,25 +953,49 @@ __global__ __launch_bounds__(NC / 2 * 64) void jacobi_round_kernel(double *__res
         }
         __syncthreads();
     }
-    for (int idx = tid; idx < NC * r; idx += THREADS) {
-        const int c = idx / r, i = idx % r, gc = gcol(c);
-        if (gc < r) Gt[(size_t)gc * r + i] = cols[idx];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int gc = gcol(w + BS * u);
+#pragma unroll
+        for (int it = 0; it < kMaxIt; ++it) {
+            const int i = lane + kWave * it;
+            if (gc < r && i < r) Gt[(size_t)gc * r + i] = cols[(w + BS * u) * RP + i];
+        }
     }
     if (tid == 0 && big_rotations > 0) atomicAdd(&rotations[sweep], big_rotations);
     __syncthreads();
     // the same transform on this workgroup's rows of J^T: load them where the columns were, combine, store
-    for (int idx = tid; idx < NC * r; idx += THREADS) {
-        const int c = idx / r, i = idx % r, gc = gcol(c);
-        cols[idx] = gc < r ? Jt[(size_t)gc * r + i] : 0.0;
-    }
+    rows_to_lds(Jt);
     __syncthreads();
-    for (int idx = tid; idx < NC * r; idx += THREADS) {
-        const int c = idx / r, i = idx % r, gc = gcol(c);
-        if (gc >= r) continue;
-        double v = 0.0;
-#pragma unroll 8
-        for (int c2 = 0; c2 < NC; ++c2) v = fma(T[c * NC + c2], cols[(size_t)c2 * r + i], v);
-        Jt[(size_t)gc * r + i] = v;
+    // J^T_new = T J^T_old on the fp64 matrix cores: result tiles of 16 local rows x 16 positions, NC / 4 steps each.
+    // A wavefront keeps its A operands (the NC x NC transform) in registers and walks the position tiles; its B
+    // operands are the old rows in LDS, so writing the new rows to memory in place disturbs nothing.
+    {
+        constexpr int MT = NC / 16, KS = NC / 4;
+        const int lr = lane & 15, lk = lane >> 4;
+        double ta[MT][KS];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) ta[mt][ks] = T[(16 * mt + lr) * NC + 4 * ks + lk];
+        const int n_tiles = (r + 15) / 16;
+        for (int nt = w; nt < n_tiles; nt += NC / 2) {
+            const int i = 16 * nt + lr;
+            double tb[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) tb[ks] = cols[(4 * ks + lk) * RP + i];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                fz_f64x4_t acc = fz_f64x4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(ta[mt][ks], tb[ks], acc, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int gc = gcol(16 * mt + lk + 4 * v);
+                    if (gc < r && i < r) Jt[(size_t)gc * r + i] = acc[v];
+                }
+            }
+        }
     }
 }
 
@@ -1155,7 +1229,7 @@ hipError_t factorize_typed(const xkv_shape &s, const FzLayout &f, const void *X,
         {
             const int nc = r <= 512 ? 32 : 16, bs = nc / 2;
             const int n_blocks = std::max(2, ((r + bs - 1) / bs + 1) / 2 * 2);  // an even number of column blocks
-            const size_t lds = ((size_t)nc * r + (size_t)nc * nc) * 8;
+            const size_t lds = ((size_t)nc * (nc == 32 ? 512 : 1024) + (size_t)nc * nc) * 8;  // columns at their full pitch
             static DynamicLdsOnce attr32, attr16;
             e = nc == 32 ? attr32.ensure((const void *)jacobi_round_kernel<32>, 160 * 1024 - 256)
                          : attr16.ensure((const void *)jacobi_round_kernel<16>, 160 * 1024 - 256);
