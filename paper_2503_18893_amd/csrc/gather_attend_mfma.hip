@@ -169,12 +169,18 @@ template <bool IS_K, int QB>
 __device__ __forceinline__ void q_steps(f32x16_t (&acc)[4], const u32x4_t *bcur, const unsigned char *crow, int gsel, int hf)
 {
     u32x4_t piece = u32x4_t{0u, 0u, 0u, 0u};
+    // 4-bit rows: the group's four (step, lo) words are one 16-byte piece; the codes are read a piece (two steps of
+    // both half-wavefronts) at a time as well -- one-word reads of rows 176 bytes apart would collide pairwise
+    u32x4_t pars = u32x4_t{0u, 0u, 0u, 0u};
+    if constexpr (QB == 4) pars = *reinterpret_cast<const u32x4_t *>(crow + 128 + 16 * gsel);
 #pragma unroll
     for (int fl = 0; fl < kGroup; ++fl) {
         uint32_t codes, param;
         if constexpr (QB == 4) {
-            codes = *reinterpret_cast<const uint32_t *>(crow + 4 * (16 * gsel + 2 * fl + hf));
-            param = *reinterpret_cast<const uint32_t *>(crow + 128 + 4 * (4 * gsel + fl / 2));
+            // word 16 gsel + 2 fl + hf of the row = word 2 (fl % 2) + hf of piece 4 gsel + fl / 2
+            if (fl % 2 == 0) piece = *reinterpret_cast<const u32x4_t *>(crow + 16 * (4 * gsel + fl / 2));
+            codes = fl % 2 == 0 ? (hf ? piece[1] : piece[0]) : (hf ? piece[3] : piece[2]);
+            param = pars[fl / 2];
         } else {
             // the group's 16-byte piece: 96 bits of codes (four units of 24, unit 2 (fl % 2) + hf is this lane's), then (step, lo)
             if (fl % 2 == 0) piece = *reinterpret_cast<const u32x4_t *>(crow + 16 * (4 * gsel + fl / 2));
