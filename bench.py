@@ -382,13 +382,21 @@ def main():
         del Kscr
         lstate = {"i": 0}
 
+        def landmark_call(i, s_i, l_i, theta):   # on B_l re-ordered once per prompt where the shape has that form
+            g = groups[s_i]
+            if packs is not None:
+                xb.xkv_sr_decode_landmark_packed(shape, l_i, g["A_k"], g["A_v"], 0, g["B_k"], packs[s_i], qs[s_i][l_i],
+                                                 lms[i], outls[i], c_lm, o_lm, out, None, None, None, lm_ws,
+                                                 rope_theta=theta)
+            else:
+                xb.xkv_sr_decode_landmark(shape, l_i, g["A_k"], g["A_v"], g["B_k"], g["B_v"], qs[s_i][l_i], lms[i],
+                                          outls[i], c_lm, o_lm, out, None, None, None, lm_ws, rope_theta=theta)
+
         def landmark_step():
             for _ in range(w.n_layers):
                 i = lstate["i"]
                 s_i, l_i = divmod(i, w.G)
-                g = groups[s_i]
-                xb.xkv_sr_decode_landmark(shape, l_i, g["A_k"], g["A_v"], g["B_k"], g["B_v"], qs[s_i][l_i], lms[i],
-                                          outls[i], c_lm, o_lm, out, None, None, None, lm_ws)
+                landmark_call(i, s_i, l_i, 0.0)
                 lstate["i"] = (i + 1) % n_lm_layers
 
         landmark_step()
@@ -399,9 +407,7 @@ def main():
             for _ in range(w.n_layers):
                 i = lstate["i"]
                 s_i, l_i = divmod(i, w.G)
-                g = groups[s_i]
-                xb.xkv_sr_decode_landmark(shape, l_i, g["A_k"], g["A_v"], g["B_k"], g["B_v"], qs[s_i][l_i], lms[i],
-                                          outls[i], c_lm, o_lm, out, None, None, None, lm_ws, rope_theta=rope_theta)
+                landmark_call(i, s_i, l_i, rope_theta)
                 lstate["i"] = (i + 1) % n_lm_layers
 
         ms_lm_rope = None
@@ -416,6 +422,7 @@ def main():
                     "with_rope": None if ms_lm_rope is None else {
                         "ms_per_step": round(ms_lm_rope, 4), "tokens_per_s": round(w.batch / (ms_lm_rope * 1e-3), 2),
                         "rope_theta": rope_theta},
+                    "entry_point": "xkv_sr_decode_landmark_packed" if packs is not None else "xkv_sr_decode_landmark",
                     "note": "SR decode with landmark-guided chunk selection instead of scoring every token from the "
                             "factors; same reconstruction and attention kernels"}
         del lms, outls, lm_ws

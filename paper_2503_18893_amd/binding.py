@@ -25,6 +25,7 @@ ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_static", 
                 "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
                 "xkv_quantized_row_bytes", "xkv_quantize_rows", "xkv_attend_absorbed_q4", "xkv_head_scores_q4",
                 "xkv_sr_decode_absorbed_q4", "xkv_gather_attend_q", "xkv_sr_decode_landmark_q", "xkv_sr_decode_q4",
+                "xkv_sr_decode_landmark_packed",
                 "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
@@ -113,6 +114,7 @@ def load() -> ctypes.CDLL:
         lib.xkv_sr_decode_landmark_q.argtypes = [sp, i32, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, ctypes.c_float, vp, vp,
                                                  i32, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_sr_decode_q4.argtypes = [sp, i32, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.xkv_sr_decode_landmark_packed.argtypes = lib.xkv_sr_decode_landmark_q.argtypes
         lib.xkv_profile_kernel.argtypes = [i32, vp, vp]
         lib.xkv_status_string.argtypes = [ctypes.c_int]
         lib.xkv_status_string.restype = ctypes.c_char_p
@@ -361,6 +363,17 @@ def xkv_sr_decode_landmark_q(shape, layer_in_group, Aq_k, Aq_v, bits, B_k, B_v, 
                                            _ptr(count_out), _ptr(score_out), _ptr(workspace),
                                            workspace.numel() * workspace.element_size(), _stream(stream)),
            "xkv_sr_decode_landmark_q")
+
+
+def xkv_sr_decode_landmark_packed(shape, layer_in_group, A_k, A_v, bits, B_k, B_packed, q, landmarks, outliers, c, o, out,
+                                  rows_out, count_out, score_out, workspace, stream=None, rope_theta=0.0, K_tail=None,
+                                  V_tail=None, T=0):
+    _check(load().xkv_sr_decode_landmark_packed(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), int(bits),
+                                                _ptr(B_k), _ptr(B_packed), _ptr(q), _ptr(landmarks), _ptr(outliers), c,
+                                                o, float(rope_theta), _ptr(K_tail), _ptr(V_tail), T, _ptr(out),
+                                                _ptr(rows_out), _ptr(count_out), _ptr(score_out), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream(stream)),
+           "xkv_sr_decode_landmark_packed")
 
 
 def xkv_sr_decode_q4(shape, layer_in_group, Aq_k, Aq_v, B_k, B_v, q, out, idx_out, score_out, workspace, stream=None,

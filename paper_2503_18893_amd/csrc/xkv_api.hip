@@ -487,8 +487,9 @@ xkv_status xkv_landmarks(const xkv_shape *shape, const void *K_rope, int32_t c, 
 }
 
 // qbits: 0 = A_k, A_v in shape->dtype; 4 or 3 = rows of 4-bit / 3-bit codes
+// B_packed (nullable): the group's B_l in fragment order from xkv_pack_b; B_v may then be NULL.
 static xkv_status sr_decode_landmark_impl(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
-                                          int qbits, const void *B_k, const void *B_v, const void *q,
+                                          int qbits, const void *B_k, const void *B_v, const void *B_packed, const void *q,
                                           const void *landmarks, const int32_t *outliers, int32_t c, int32_t o,
                                           float rope_theta, const void *K_tail, const void *V_tail, int32_t T, void *out,
                                           int32_t *rows_out, int32_t *count_out, float *score_out, void *workspace,
@@ -498,9 +499,10 @@ static xkv_status sr_decode_landmark_impl(const xkv_shape *shape, int32_t layer,
     if (st != XKV_OK) return st;
     LandmarkPlan lp;
     if ((st = make_landmark_plan(*shape, c, o, lp)) != XKV_OK) return st;
-    if (!A_k || !A_v || !B_k || !B_v || !q || !landmarks || !out || (o > 0 && !outliers) || layer < 0 ||
+    if (!A_k || !A_v || !B_k || (!B_v && !B_packed) || !q || !landmarks || !out || (o > 0 && !outliers) || layer < 0 ||
         layer >= shape->G)
         return XKV_ERR_INVALID_ARG;
+    if (B_packed) B_v = B_k;  // never read: the gather-reconstruct kernel takes both products' B from the packed copy
     if (!(rope_theta >= 0.0f) || !std::isfinite(rope_theta)) return XKV_ERR_INVALID_ARG;
     if (T < 0 || (T > 0 && (!K_tail || !V_tail))) return XKV_ERR_INVALID_ARG;
     if (rope_theta > 0.0f && !rope_shape_ok(*shape)) return XKV_ERR_UNSUPPORTED;
@@ -509,6 +511,10 @@ static xkv_status sr_decode_landmark_impl(const xkv_shape *shape, int32_t layer,
     if (qbits != 0 && !gather_attend_quant_ok(lp.attend_shape, lp.attend_plan, A_k, A_v, B_k, B_v,
                                               at<void>(workspace, lp.attend_plan.off_bpack), qbits))
         return XKV_ERR_UNSUPPORTED;
+    if (B_packed && (((uintptr_t)B_packed & 15u) ||
+                     !gather_attend_uses_mfma(lp.attend_plan, A_k, A_v, B_k, B_v,
+                                              at<void>(workspace, lp.attend_plan.off_bpack))))
+        return XKV_ERR_UNSUPPORTED;  // only the matrix-core kernel reads the packed layout
     if (shape->batch == 0) return XKV_OK;
     hipStream_t stream = (hipStream_t)hip_stream;
     const Plan &ps = lp.score_plan, &pa = lp.attend_plan;
@@ -534,8 +540,8 @@ static xkv_status sr_decode_landmark_impl(const xkv_shape *shape, int32_t layer,
     void *pack_ws = at<void>(workspace, pa.off_bpack);
     const bool mfma = gather_attend_uses_mfma(pa, A_k, A_v, B_k, B_v, pack_ws);
     if (e == hipSuccess)
-        e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, nullptr, false, part_o, part_ml,
-                                 stream, counts, rope_theta, qbits);
+        e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, B_packed, false, part_o,
+                                 part_ml, stream, counts, rope_theta, qbits);
     // the uncompressed tail, as in xkv_sr_decode_tail: a dense pass over its T tokens into a second set of partials
     int n_tail = 0;
     float *tail_o = at<float>(workspace, pa.off_tail_o), *tail_ml = at<float>(workspace, pa.off_tail_ml);
@@ -552,8 +558,9 @@ xkv_status xkv_sr_decode_landmark(const xkv_shape *shape, int32_t layer, const v
                                   const void *V_tail, int32_t T, void *out, int32_t *rows_out, int32_t *count_out,
                                   float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    return sr_decode_landmark_impl(shape, layer, A_k, A_v, 0, B_k, B_v, q, landmarks, outliers, c, o, rope_theta, K_tail,
-                                   V_tail, T, out, rows_out, count_out, score_out, workspace, workspace_bytes, hip_stream);
+    return sr_decode_landmark_impl(shape, layer, A_k, A_v, 0, B_k, B_v, nullptr, q, landmarks, outliers, c, o, rope_theta,
+                                   K_tail, V_tail, T, out, rows_out, count_out, score_out, workspace, workspace_bytes,
+                                   hip_stream);
 }
 
 xkv_status xkv_sr_decode_landmark_q(const xkv_shape *shape, int32_t layer, const void *Aq_k, const void *Aq_v,
@@ -563,9 +570,25 @@ xkv_status xkv_sr_decode_landmark_q(const xkv_shape *shape, int32_t layer, const
                                     float *score_out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (bits != 4 && bits != 3) return XKV_ERR_UNSUPPORTED;
-    return sr_decode_landmark_impl(shape, layer, Aq_k, Aq_v, bits, B_k, B_v, q, landmarks, outliers, c, o, rope_theta,
-                                   K_tail, V_tail, T, out, rows_out, count_out, score_out, workspace, workspace_bytes,
-                                   hip_stream);
+    return sr_decode_landmark_impl(shape, layer, Aq_k, Aq_v, bits, B_k, B_v, nullptr, q, landmarks, outliers, c, o,
+                                   rope_theta, K_tail, V_tail, T, out, rows_out, count_out, score_out, workspace,
+                                   workspace_bytes, hip_stream);
+}
+
+// The landmark-guided step on B_l re-ordered once per prompt (xkv_pack_b); bits 0 = rows of A in shape->dtype, 4 or 3 =
+// quantised rows.
+xkv_status xkv_sr_decode_landmark_packed(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                         int32_t bits, const void *B_k, const void *B_packed, const void *q,
+                                         const void *landmarks, const int32_t *outliers, int32_t c, int32_t o,
+                                         float rope_theta, const void *K_tail, const void *V_tail, int32_t T, void *out,
+                                         int32_t *rows_out, int32_t *count_out, float *score_out, void *workspace,
+                                         size_t workspace_bytes, void *hip_stream)
+{
+    if (bits != 0 && bits != 4 && bits != 3) return XKV_ERR_UNSUPPORTED;
+    if (!B_packed) return XKV_ERR_INVALID_ARG;
+    return sr_decode_landmark_impl(shape, layer, A_k, A_v, bits, B_k, nullptr, B_packed, q, landmarks, outliers, c, o,
+                                   rope_theta, K_tail, V_tail, T, out, rows_out, count_out, score_out, workspace,
+                                   workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

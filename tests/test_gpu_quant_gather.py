@@ -173,6 +173,19 @@ def test_landmark_step_on_a_quantised_cache(bits):
         res[which] = (synth.storage_to_f64(synth.to_host(out)), rows.cpu().numpy(), cnt.cpu().numpy())
     np.testing.assert_array_equal(res["quantised"][1], res["plain"][1])
     np.testing.assert_array_equal(res["quantised"][2], res["plain"][2])
+    # the same two calls on B_l re-ordered once for the group (xkv_pack_b): bit for bit the same results
+    packed = torch.full((xb.xkv_packed_b_bytes(shape),), 0xAB, dtype=torch.uint8, device="cuda")
+    xb.xkv_pack_b(shape, dev["B_k"], dev["B_v"], packed)
+    for which, qb, Ak, Av in (("plain", 0, dev["A_k"], dev["A_v"]), ("quantised", bits, Aq_k, Aq_v)):
+        out = torch.full((w.batch, w.H_q, w.d_h), float("nan"), dtype=torch.bfloat16, device="cuda")
+        rows = torch.zeros((w.batch, w.H_kv, cap), dtype=torch.int32, device="cuda")
+        cnt = torch.zeros((w.batch, w.H_kv), dtype=torch.int32, device="cuda")
+        xb.xkv_sr_decode_landmark_packed(shape, 0, Ak, Av, qb, dev["B_k"], packed, q, Lm, outl, c, o, out, rows, cnt, None,
+                                         ws, rope_theta=theta, K_tail=extra["Kt"], V_tail=extra["Vt"], T=T)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(synth.storage_to_f64(synth.to_host(out)), res[which][0])
+        np.testing.assert_array_equal(rows.cpu().numpy(), res[which][1])
+        np.testing.assert_array_equal(cnt.cpu().numpy(), res[which][2])
     got, rows_h, cnt_h = res["quantised"]
     for b in range(w.batch):
         row_lists = [rows_h[b, g, :cnt_h[b, g]] for g in range(w.H_kv)]
