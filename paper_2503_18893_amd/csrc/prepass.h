@@ -39,16 +39,26 @@ __device__ __forceinline__ void project_q_frag_block(const ProjArgs &a, int blk_
     pp_f32x16_t acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    // B_k == NULL: B_l is the identity (the landmark scoring problem, where the "factors" are the landmarks themselves);
+    // its rows are generated in registers instead of being read
+    const bool ident = B_k == nullptr;
     if (g < H_kv) {
         const int i = i0 + n < r_k ? i0 + n : r_k - 1;
-        const pack_u32x4_t *brow = reinterpret_cast<const pack_u32x4_t *>(B_k + (((size_t)b * G + layer) * r_k + i) * d +
-                                                                 (size_t)g * d_h) + hf;
+        const pack_u32x4_t *brow = ident ? nullptr
+                                         : reinterpret_cast<const pack_u32x4_t *>(
+                                               B_k + (((size_t)b * G + layer) * r_k + i) * d + (size_t)g * d_h) + hf;
         const pack_u32x4_t *qrow = reinterpret_cast<const pack_u32x4_t *>(q + ((size_t)b * H_q + (size_t)g * n_rep +
                                                                      (n < n_rep ? n : 0)) * d_h) + hf;
         for (int f = 0; f < d_h / 16; ++f) {
             pack_u32x4_t qa = qrow[2 * f];
             if (n >= n_rep) qa = pack_u32x4_t{0u, 0u, 0u, 0u};
-            pack_u32x4_t ba = brow[2 * f];
+            pack_u32x4_t ba = pack_u32x4_t{0u, 0u, 0u, 0u};
+            if (ident) {  // columns 16 f + 8 hf .. + 7 of row i: a one (bf16 0x3F80) where the column is i
+                const int e = i - (16 * f + 8 * hf);
+                if (e >= 0 && e < 8) ba[e >> 1] = 0x3F80u << (16 * (e & 1));
+            } else {
+                ba = brow[2 * f];
+            }
             if (i0 + n >= r_k) ba = pack_u32x4_t{0u, 0u, 0u, 0u};
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pp_bf16x8_t, qa),
                                                           __builtin_bit_cast(pp_bf16x8_t, ba), acc, 0, 0, 0);

@@ -1132,6 +1132,13 @@ static hipError_t launch_score_mfma_t(const xkv_shape &s, const Plan &p, const b
     return hipGetLastError();
 }
 
+bool score_stage_uses_mfma(const xkv_shape &s, const void *A_k, const void *B_k, const void *q, const void *P_ws,
+                           const float *S_heads)
+{
+    return score_mfma_ok(s, A_k) && ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) == 0 &&
+           (!S_heads || (((uintptr_t)S_heads) & 15u) == 0);
+}
+
 hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, const void *A_k, const void *B_k,
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
                               bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st,
@@ -1140,8 +1147,8 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
     if (hist_done) *hist_done = false;
     if (packed_done) *packed_done = false;
     // per-head scores come from either matrix-core kernel, or from the general one
-    const bool mfma = score_mfma_ok(s, A_k) && ((((uintptr_t)B_k | (uintptr_t)q | (uintptr_t)P_ws)) & 15u) == 0 &&
-                      (!S_heads || (((uintptr_t)S_heads) & 15u) == 0);
+    const bool mfma = score_stage_uses_mfma(s, A_k, B_k, q, P_ws, S_heads);
+    if (!mfma && !B_k) return hipErrorInvalidValue;  // only the matrix-core projection generates an identity B_l
     if (!mfma) return launch_score_generic(s, p, layer, A_k, B_k, q, (float *)P_ws, S, S_heads, st);
     const int n_rep = s.H_q / s.H_kv;
     const int F8 = (s.r_k / 16 + 7) / 8 * 8;

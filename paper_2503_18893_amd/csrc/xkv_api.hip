@@ -525,11 +525,21 @@ static xkv_status sr_decode_landmark_impl(const xkv_shape *shape, int32_t layer,
     int32_t *chunks = at<int32_t>(ws_s, ps.off_idx);
     uint32_t *hist = at<uint32_t>(ws_s, ps.off_hist), *state = at<uint32_t>(ws_s, ps.off_state);
     bool level0_done = false;
-    hipError_t e = launch_identity(*shape, ident, lp.score_shape.batch, stream);
+    // The identity in the place of B^K is written out only for the general score kernels; the matrix-core projection
+    // generates it.  That launch also carries the operand packing of the gather-reconstruct kernel below (the Q
+    // fragments, and B_l unless the caller brought the packed copy), as in xkv_sr_decode.
+    void *pack_ws = at<void>(workspace, pa.off_bpack);
+    const bool mfma = gather_attend_uses_mfma(pa, A_k, A_v, B_k, B_v, pack_ws);
+    const bool gen_ident = score_stage_uses_mfma(lp.score_shape, landmarks, nullptr, q, at<void>(ws_s, ps.off_p), nullptr);
+    PackArgs pk{};
+    if (mfma) pk = gather_attend_pack_args(lp.attend_shape, layer, B_k, B_v, q, pack_ws, B_packed == nullptr);
+    const bool fuse = gen_ident && mfma;
+    bool packed = false;
+    hipError_t e = gen_ident ? hipSuccess : launch_identity(*shape, ident, lp.score_shape.batch, stream);
     if (e == hipSuccess)
-        e = launch_score_stage(lp.score_shape, ps, 0, landmarks, ident, q, at<void>(ws_s, ps.off_p), S,
+        e = launch_score_stage(lp.score_shape, ps, 0, landmarks, gen_ident ? nullptr : ident, q, at<void>(ws_s, ps.off_p), S,
                                ps.score_hist ? topk_row_hist(ps, state) : nullptr,
-                               ps.score_hist ? hist : nullptr, &level0_done, nullptr, nullptr, stream);
+                               ps.score_hist ? hist : nullptr, &level0_done, fuse ? &pk : nullptr, &packed, stream);
     // top ceil(k / c) chunks per KV head, union with the outliers, expansion to rows
     if (e == hipSuccess) e = launch_topk(lp.score_shape, ps, S, chunks, hist, state, level0_done, stream);
     int32_t *rows = rows_out ? rows_out : at<int32_t>(workspace, pa.off_idx);
@@ -537,10 +547,8 @@ static xkv_status sr_decode_landmark_impl(const xkv_shape *shape, int32_t layer,
     if (e == hipSuccess) e = launch_expand_chunks(*shape, chunks, lp.k_ch, outliers, o, c, rows, counts, stream);
     // Eq. 3 and attention over the rows that are real
     float *part_o = at<float>(workspace, pa.off_part_o), *part_ml = at<float>(workspace, pa.off_part_ml);
-    void *pack_ws = at<void>(workspace, pa.off_bpack);
-    const bool mfma = gather_attend_uses_mfma(pa, A_k, A_v, B_k, B_v, pack_ws);
     if (e == hipSuccess)
-        e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, B_packed, false, part_o,
+        e = launch_gather_attend(lp.attend_shape, pa, layer, A_k, A_v, B_k, B_v, q, rows, pack_ws, B_packed, packed, part_o,
                                  part_ml, stream, counts, rope_theta, qbits);
     // the uncompressed tail, as in xkv_sr_decode_tail: a dense pass over its T tokens into a second set of partials
     int n_tail = 0;

@@ -154,6 +154,10 @@ hipError_t launch_score_stage(const xkv_shape &s, const Plan &p, int layer, cons
                               const void *q, void *P_ws, float *S, uint32_t *row_hist, uint32_t *chunk_hist,
                               bool *hist_done, const PackArgs *fuse_pack, bool *packed_done, hipStream_t st,
                               float *S_heads = nullptr);
+// Whether that stage runs on the matrix-core kernels for these operands.  Only then may B_k be NULL, which stands for
+// an identity B_l (landmark scoring): the projection generates its rows instead of reading them.
+bool score_stage_uses_mfma(const xkv_shape &s, const void *A_k, const void *B_k, const void *q, const void *P_ws,
+                           const float *S_heads);
 // S_heads (nullable): also store every query head's score, [batch][H_kv][L][head_pitch(H_q / H_kv)] fp32 with the
 // padding zero; S is then the maximum of exactly the stored values.
 inline int head_pitch_of(int n_rep) { return n_rep <= 1 ? 1 : n_rep <= 2 ? 2 : n_rep <= 4 ? 4 : n_rep <= 8 ? 8 : 16; }
