@@ -112,6 +112,7 @@ XKV_API xkv_status xkv_sr_decode_tail(const xkv_shape *shape, int32_t layer_in_g
  *     [batch][G][H_kv] blocks of 16-rank operand fragments, keys then values, zero beyond the rank).
  *   xkv_sr_decode_packed: xkv_sr_decode with B_v replaced by the packed copy; B_k is still read in its plain layout
  *     by the query projection.  Same kernels otherwise, bit for bit the same results as xkv_sr_decode.
+ *   xkv_sr_decode_tail_packed: xkv_sr_decode_tail (K_tail, V_tail, T as there) with B_v replaced by the packed copy.
  *   xkv_sr_decode_landmark_packed: the landmark-guided step (xkv_sr_decode_landmark below, all its arguments) with B_v
  *     replaced by the packed copy; bits = 0 for rows of A in shape->dtype, 4 or 3 for quantised rows
  *     (xkv_sr_decode_landmark_q).  Same results as those calls, bit for bit.
@@ -125,6 +126,11 @@ XKV_API xkv_status xkv_sr_decode_packed(const xkv_shape *shape, int32_t layer_in
                                         const void *A_v, const void *B_k, const void *B_packed, const void *q,
                                         void *out, int32_t *idx_out, float *score_out, void *workspace,
                                         size_t workspace_bytes, void *hip_stream);
+XKV_API xkv_status xkv_sr_decode_tail_packed(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
+                                             const void *A_v, const void *B_k, const void *B_packed, const void *q,
+                                             const void *K_tail, const void *V_tail, int32_t T, void *out,
+                                             int32_t *idx_out, float *score_out, void *workspace,
+                                             size_t workspace_bytes, void *hip_stream);
 XKV_API xkv_status xkv_sr_decode_landmark_packed(const xkv_shape *shape, int32_t layer_in_group, const void *A_k,
                                                  const void *A_v, int32_t bits, const void *B_k, const void *B_packed,
                                                  const void *q, const void *landmarks, const int32_t *outliers,

@@ -25,7 +25,7 @@ ENTRY_POINTS = ("xkv_workspace_bytes", "xkv_sr_decode", "xkv_sr_decode_static", 
                 "xkv_absorbed_workspace_bytes", "xkv_head_scores", "xkv_attend_absorbed", "xkv_sr_decode_absorbed",
                 "xkv_quantized_row_bytes", "xkv_quantize_rows", "xkv_attend_absorbed_q4", "xkv_head_scores_q4",
                 "xkv_sr_decode_absorbed_q4", "xkv_gather_attend_q", "xkv_sr_decode_landmark_q", "xkv_sr_decode_q4",
-                "xkv_sr_decode_landmark_packed",
+                "xkv_sr_decode_landmark_packed", "xkv_sr_decode_tail_packed",
                 "xkv_profile_kernel", "xkv_status_string", "xkv_version")
 
 
@@ -88,6 +88,7 @@ def load() -> ctypes.CDLL:
         lib.xkv_sr_decode_packed.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_sr_decode_static.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.xkv_sr_decode_tail.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        lib.xkv_sr_decode_tail_packed.argtypes = lib.xkv_sr_decode_tail.argtypes
         lib.xkv_dense_decode.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_score.argtypes = [sp, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.xkv_topk.argtypes = [sp, vp, vp, vp, sz, vp]
@@ -187,6 +188,14 @@ def xkv_sr_decode_packed(shape, layer_in_group, A_k, A_v, B_k, B_packed, q, out,
 
 
 STATIC_SCRATCH_BYTES = 40 << 20
+
+
+def xkv_sr_decode_tail_packed(shape, layer_in_group, A_k, A_v, B_k, B_packed, q, K_tail, V_tail, T, out, idx_out, score_out,
+                              workspace, stream=None):
+    _check(load().xkv_sr_decode_tail_packed(ctypes.byref(shape.c()), layer_in_group, _ptr(A_k), _ptr(A_v), _ptr(B_k),
+                                            _ptr(B_packed), _ptr(q), _ptr(K_tail), _ptr(V_tail), int(T), _ptr(out),
+                                            _ptr(idx_out), _ptr(score_out), _ptr(workspace), workspace.numel(),
+                                            _stream(stream)), "xkv_sr_decode_tail_packed")
 
 
 def xkv_sr_decode_static(shape, layer_in_group, A_k, A_v, B_k, B_v, q, out, idx_out, score_out, stream=None):

@@ -340,6 +340,18 @@ xkv_status xkv_sr_decode_tail(const xkv_shape *shape, int32_t layer, const void 
                           workspace_bytes, hip_stream);
 }
 
+// xkv_sr_decode_tail on B_l re-ordered once per prompt: what a serving loop calls once tokens have been generated.
+xkv_status xkv_sr_decode_tail_packed(const xkv_shape *shape, int32_t layer, const void *A_k, const void *A_v,
+                                     const void *B_k, const void *B_packed, const void *q, const void *K_tail,
+                                     const void *V_tail, int32_t T, void *out, int32_t *idx_out, float *score_out,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!B_packed) return XKV_ERR_INVALID_ARG;
+    if (T < 0 || (T > 0 && (!K_tail || !V_tail))) return XKV_ERR_INVALID_ARG;
+    return sr_decode_impl(shape, layer, A_k, A_v, B_k, nullptr, q, K_tail, V_tail, T, out, idx_out, score_out, workspace,
+                          workspace_bytes, hip_stream, B_packed);
+}
+
 
 xkv_status xkv_dense_decode(const xkv_shape *shape, const void *K, const void *V, const void *q, void *out,
                             void *workspace, size_t workspace_bytes, void *hip_stream)

@@ -467,6 +467,15 @@ def test_sr_decode_with_uncompressed_tail(name, w, T):
     torch.cuda.synchronize()
     np.testing.assert_array_equal(synth.to_host(out0), synth.to_host(out_plain))
     np.testing.assert_array_equal(idx.cpu().numpy(), idx_plain.cpu().numpy())
+    if w.dtype == "bf16" and w.d_h == 128 and w.r_k % 16 == 0 and w.r_v % 16 == 0:
+        # the same step on B_l re-ordered once for the group: bit for bit the same
+        packed = torch.full((xb.xkv_packed_b_bytes(shape),), 0xAB, dtype=torch.uint8, device="cuda")
+        xb.xkv_pack_b(shape, dev["B_k"], dev["B_v"], packed)
+        out_p, idx_p, S_p = torch.empty_like(out), torch.empty_like(idx), torch.empty_like(S)
+        xb.xkv_sr_decode_tail_packed(shape, 0, dev["A_k"], dev["A_v"], dev["B_k"], packed, q, tail["K"], tail["V"], T,
+                                     out_p, idx_p, S_p, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out_p, out) and torch.equal(idx_p, idx) and torch.equal(S_p, S)
     outh, idxh, Sh = synth.storage_to_f64(synth.to_host(out)), idx.cpu().numpy(), S.cpu().numpy()
     for b in range(w.batch):
         for g in range(w.H_kv):
