@@ -321,6 +321,8 @@ xkv_status xkv_sr_decode_static(const xkv_shape *shape, int32_t layer, const voi
     Plan p;
     make_plan(*shape, p);
     if (p.total > (size_t)XKV_STATIC_SCRATCH_BYTES) return XKV_ERR_WORKSPACE;  // shape too large for the built-in scratch
+    // (argument errors are reported before the device is touched, as in the other calls)
+    if (!A_k || !A_v || !B_k || !B_v || !q || !out || layer < 0 || layer >= shape->G) return XKV_ERR_INVALID_ARG;
     void *ws = nullptr;
     if ((st = static_scratch(&ws)) != XKV_OK) return st;
     // Every array the step keeps in the scratch is written by the step's own kernels before it is read (the row

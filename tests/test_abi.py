@@ -179,3 +179,48 @@ def test_binding_has_no_cpu_fallback(monkeypatch):
     monkeypatch.setattr(xb, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))
     with pytest.raises(RuntimeError):
         xb.load()
+
+
+def test_packed_and_static_calls_validate_on_the_host():
+    """The calls on B_l re-ordered once per prompt, and the call on the library's own scratch: rejected on the host,
+    before any launch, for missing operands, shapes the matrix-core kernel does not take, and plans beyond the
+    static scratch."""
+    lib = xb.load()
+    good = xb.Shape.of(synth.LLAMA_GROUP)
+    c, null, one, al = good.c(), ctypes.c_void_p(0), ctypes.c_void_p(256), ctypes.c_void_p(4096)
+    n = ctypes.c_size_t(0)
+    big = 1 << 40
+    # size of the packed copy: about B_k and B_v themselves (ranks padded to whole pairs of 128-rank groups)
+    plain = 2 * good.batch * good.G * good.r_k * good.H_kv * good.d_h * 2
+    assert plain <= xb.xkv_packed_b_bytes(good) <= 2 * plain
+    assert lib.xkv_packed_b_bytes(ctypes.byref(c), None) == xb.XKV_ERR_INVALID_ARG
+    f32 = xb.Shape.of(synth.TINY).c()                                            # fp32: no matrix-core kernel
+    assert lib.xkv_packed_b_bytes(ctypes.byref(f32), ctypes.byref(n)) == xb.XKV_ERR_UNSUPPORTED
+    assert lib.xkv_pack_b(ctypes.byref(c), null, al, al, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_pack_b(ctypes.byref(c), al, al, null, null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_pack_b(ctypes.byref(f32), al, al, al, null) == xb.XKV_ERR_UNSUPPORTED
+    # the packed steps: no packed copy, no workspace, a workspace too small
+    assert lib.xkv_sr_decode_packed(ctypes.byref(c), 0, al, al, al, null, al, al, null, null, al, big,
+                                    null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_sr_decode_packed(ctypes.byref(c), 0, al, al, al, al, al, al, null, null, al, 16,
+                                    null) == xb.XKV_ERR_WORKSPACE
+    assert lib.xkv_sr_decode_packed(ctypes.byref(c), 0, al, al, al, ctypes.c_void_p(4100), al, al, null, null, al, big,
+                                    null) == xb.XKV_ERR_UNSUPPORTED             # misaligned packed copy
+    assert lib.xkv_sr_decode_tail_packed(ctypes.byref(c), 0, al, al, al, null, al, null, null, 0, al, null, null, al, big,
+                                         null) == xb.XKV_ERR_INVALID_ARG
+    assert lib.xkv_sr_decode_tail_packed(ctypes.byref(c), 0, al, al, al, al, al, null, al, 7, al, null, null, al, big,
+                                         null) == xb.XKV_ERR_INVALID_ARG         # tail tokens without their keys
+    args = [ctypes.byref(c), 0, al, al, 0, al, null, al, al, null, 8, 0, ctypes.c_float(0.0), null, null, 0, al, null,
+            null, null, al]
+    assert lib.xkv_sr_decode_landmark_packed(*args, big, null) == xb.XKV_ERR_INVALID_ARG     # no packed copy
+    args[6], args[4] = al, 5
+    assert lib.xkv_sr_decode_landmark_packed(*args, big, null) == xb.XKV_ERR_UNSUPPORTED     # 5-bit rows
+    args[4] = 0
+    assert lib.xkv_sr_decode_landmark_packed(*args, 16, null) == xb.XKV_ERR_WORKSPACE
+    # the static scratch: configuration 3's plan is larger than the array
+    full = xb.Shape.of(synth.LLAMA_FULL)
+    assert xb.xkv_workspace_bytes(full) > xb.STATIC_SCRATCH_BYTES >= xb.xkv_workspace_bytes(good)
+    assert lib.xkv_sr_decode_static(ctypes.byref(full.c()), 0, al, al, al, al, al, al, null, null,
+                                    null) == xb.XKV_ERR_WORKSPACE
+    assert lib.xkv_sr_decode_static(ctypes.byref(c), 0, al, al, al, al, null, al, null, null,
+                                    null) == xb.XKV_ERR_INVALID_ARG
