@@ -82,3 +82,42 @@ def test_static_scratch_rejects_shapes_beyond_its_size():
     with pytest.raises(xb.XkvError) as err:
         xb.xkv_sr_decode_static(shape, 0, t, t, t, t, t, t, None, None)
     assert err.value.status == xb.XKV_ERR_WORKSPACE
+
+
+def test_static_scratch_step_can_be_recorded_into_a_graph():
+    """The callers the entry point is for: a step recorded once (after one eager call, which looks the scratch
+    array's address up) and replayed, every replay compared with the eager result, eager calls in between."""
+    torch = torch_mod()
+    w = synth.LLAMA_GROUP.with_(L=4096, k=512, batch=2)
+    case = synth.make_case(w, seed=17)
+    shape = xb.Shape.of(w)
+    dev = synth.to_device(case, w.dtype)
+    qs = [dev["q"][l].contiguous() for l in range(w.G)]
+    outs = [torch.zeros((w.batch, w.H_q, w.d_h), dtype=torch.bfloat16, device="cuda") for _ in range(w.G)]
+    idxs = [torch.zeros((w.batch, w.H_kv, w.k), dtype=torch.int32, device="cuda") for _ in range(w.G)]
+
+    def step():
+        for l in range(w.G):
+            xb.xkv_sr_decode_static(shape, l, dev["A_k"], dev["A_v"], dev["B_k"], dev["B_v"], qs[l], outs[l], idxs[l], None)
+
+    step()
+    torch.cuda.synchronize()
+    want_out = [o.clone() for o in outs]
+    want_idx = [i.clone() for i in idxs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for o, i in zip(outs, idxs):
+            o.zero_()
+            i.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(w.G):
+            assert torch.equal(outs[l], want_out[l]) and torch.equal(idxs[l], want_idx[l]), (rep, l)
+        step()                       # eager work between the replays
+        torch.cuda.synchronize()
